@@ -1,0 +1,304 @@
+// daf_oracle.cpp -- TEST INFRASTRUCTURE, NOT THE PRODUCT.
+//
+// Plain, slow, single-threaded CPU statement of what the DAF activation
+// quantize/pack path and its inverse compute.  It exists so that the HIP
+// library can be compared against it bit for bit.  It shares no code, header,
+// table or helper with the HIP path and must never be called from it: only the
+// test-suite, the smoke check and the benchmark's cpu_baseline leg use it.
+//
+// Build: g++ -std=c++17 -O2 -ffp-contract=off -fno-fast-math -shared -fPIC
+// All floating point below is IEEE binary32, round-to-nearest-even, one
+// rounding per written operation, subnormals kept.
+//
+// What follows the paper and what is this build's reading of it
+//   * Quantization formula: Sec. 2.2 "Quantization Calculation", Eq. 1
+//     (scale = (max-min)/(2^b-1), Q = round((X-min)/scale)).
+//   * Stored activations are dequantized to the original precision before the
+//     backward pass: Sec. 2.2 (text after Eq. 1) and Sec. 3.1.
+//   * Packing several b-bit codes into one 32-bit word: Sec. 3.3 "Bit Layout
+//     Conversion" (eight 4-bit values per word); order of the codes inside a
+//     word: Algorithm 2 (value j of a word is (w << 4j) >> 28, i.e. the first
+//     value sits in the most significant bits).
+//   * Readings where the paper is silent (each is listed in the design notes):
+//     statistics per contiguous group instead of per tensor; stochastic
+//     rounding driven by Philox4x32-10 instead of `round`; multiplication by a
+//     per-group reciprocal instead of a per-element division; bit widths
+//     {1,2,4,8}; groups start on a word boundary and are located by an
+//     exclusive scan of their word counts; no lane interleave across words.
+//
+// Pins (tests/test_oracle_*.py): Eq. 1 closed forms and grid points, the
+// Algorithm 2 extraction rule, the Eq. 5 bit-trick identity, published Philox
+// known answers plus an independent big-integer Philox, a text bit-string
+// packer, double-precision recomputation of every code, the |x - xhat| <= scale
+// bound, and the 4096-seed mean.  Nothing here is "parity unpinned" except the
+// conventions named above, for which the paper publishes no outputs.
+
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+
+#ifndef DAF_ORACLE_RAND_BITS
+#define DAF_ORACLE_RAND_BITS 8
+#endif
+
+namespace {
+
+constexpr int kRandBits = DAF_ORACLE_RAND_BITS;        // k: random bits spent per element
+constexpr int kElemsPerBlock = 128 / kRandBits;        // E: elements served by one Philox call
+static_assert(kRandBits == 8 || kRandBits == 16, "k must be 8 or 16");
+
+enum { F32 = 0, F16 = 1, BF16 = 2 };
+
+// ---- exact widening of the 16-bit formats (step "widen") --------------------
+float bits_to_float(uint32_t u) { float f; std::memcpy(&f, &u, 4); return f; }
+uint32_t float_to_bits(float f) { uint32_t u; std::memcpy(&u, &f, 4); return u; }
+
+float widen_bf16(uint16_t h) { return bits_to_float(static_cast<uint32_t>(h) << 16); }
+
+float widen_f16(uint16_t h) {
+  const uint32_t sign = static_cast<uint32_t>(h & 0x8000u) << 16;
+  const uint32_t exp = (h >> 10) & 0x1Fu;
+  const uint32_t man = h & 0x3FFu;
+  if (exp == 0x1Fu) return bits_to_float(sign | 0x7F800000u | (man << 13));  // inf / nan
+  if (exp != 0) return bits_to_float(sign | ((exp + 112u) << 23) | (man << 13));
+  // zero or subnormal: value = man * 2^-24, exactly representable in binary32
+  const float mag = static_cast<float>(man) * 5.9604644775390625e-08f;
+  return (sign != 0) ? -mag : mag;
+}
+
+// ---- narrowing with round-to-nearest-even (step "dequantize") ----------------
+uint16_t narrow_bf16(float f) {
+  uint32_t u = float_to_bits(f);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return static_cast<uint16_t>((u >> 16) | 0x0040u);  // nan
+  const uint32_t round_bias = 0x7FFFu + ((u >> 16) & 1u);
+  return static_cast<uint16_t>((u + round_bias) >> 16);
+}
+
+uint16_t narrow_f16(float f) {
+  const uint32_t u = float_to_bits(f);
+  const uint16_t sign = static_cast<uint16_t>((u >> 16) & 0x8000u);
+  const uint32_t mag = u & 0x7FFFFFFFu;
+  if (mag > 0x7F800000u) return static_cast<uint16_t>(sign | 0x7E00u);     // nan
+  if (mag >= 0x477FF000u) return static_cast<uint16_t>(sign | 0x7C00u);    // >= 65520 rounds to inf
+  if (mag < 0x33000001u) return sign;                                      // <= 2^-25 rounds to zero
+  const int e = static_cast<int>(mag >> 23) - 127;                         // unbiased exponent
+  uint32_t man = (mag & 0x7FFFFFu) | 0x800000u;                            // 24-bit significand
+  int shift;                                                               // bits dropped from it
+  uint32_t base;
+  if (e >= -14) { shift = 13; base = static_cast<uint32_t>(e + 15) << 10; man &= 0x7FFFFFu; }
+  else          { shift = 13 + (-14 - e); base = 0; }                      // subnormal result
+  const uint32_t kept = man >> shift;
+  const uint32_t rest = man & ((1u << shift) - 1u);
+  const uint32_t half = 1u << (shift - 1);
+  uint32_t h = base + kept;                                                // carry may bump the exponent: correct
+  if (rest > half || (rest == half && (kept & 1u))) h += 1;
+  return static_cast<uint16_t>(sign | h);
+}
+
+float load_elem(const void* x, int dtype, int64_t i) {
+  if (dtype == F32) return static_cast<const float*>(x)[i];
+  const uint16_t h = static_cast<const uint16_t*>(x)[i];
+  return dtype == F16 ? widen_f16(h) : widen_bf16(h);
+}
+
+void store_elem(void* x, int dtype, int64_t i, float v) {
+  if (dtype == F32) { static_cast<float*>(x)[i] = v; return; }
+  static_cast<uint16_t*>(x)[i] = (dtype == F16) ? narrow_f16(v) : narrow_bf16(v);
+}
+
+// ---- Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11) ----------------------
+// Ten rounds.  One round maps the counter (c0,c1,c2,c3) under key (k0,k1) to
+// (hi(M1*c2)^c1^k0, lo(M1*c2), hi(M0*c0)^c3^k1, lo(M0*c0)); the key is bumped
+// by the two Weyl constants between rounds.
+void philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+  const uint64_t M0 = 0xD2511F53ull, M1 = 0xCD9E8D57ull;
+  uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+  uint32_t k0 = key[0], k1 = key[1];
+  for (int round = 0; round < 10; ++round) {
+    if (round > 0) { k0 += 0x9E3779B9u; k1 += 0xBB67AE85u; }
+    const uint64_t p0 = M0 * c0;
+    const uint64_t p1 = M1 * c2;
+    const uint32_t n0 = static_cast<uint32_t>(p1 >> 32) ^ c1 ^ k0;
+    const uint32_t n1 = static_cast<uint32_t>(p1);
+    const uint32_t n2 = static_cast<uint32_t>(p0 >> 32) ^ c3 ^ k1;
+    const uint32_t n3 = static_cast<uint32_t>(p0);
+    c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// k random bits for flat element index i: block i/E is the Philox counter, the
+// 64-bit seed is the key, and slot i%E selects k bits, low bits first.
+uint32_t rand_k(uint64_t seed, uint64_t i) {
+  const uint64_t blk = i / kElemsPerBlock;
+  const uint32_t slot = static_cast<uint32_t>(i % kElemsPerBlock);
+  const uint32_t ctr[4] = {static_cast<uint32_t>(blk), static_cast<uint32_t>(blk >> 32), 0u, 0u};
+  const uint32_t key[2] = {static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32)};
+  uint32_t o[4];
+  philox4x32_10(ctr, key, o);
+  const uint32_t bit = slot * kRandBits;
+  return (o[bit / 32] >> (bit % 32)) & ((1u << kRandBits) - 1u);
+}
+
+bool valid_bits(uint8_t b) { return b == 1 || b == 2 || b == 4 || b == 8; }
+
+int64_t num_groups(int64_t n, int32_t gs) { return (n + gs - 1) / gs; }
+int64_t group_len(int64_t n, int32_t gs, int64_t g) {
+  const int64_t lo = g * gs;
+  const int64_t hi = (lo + gs < n) ? lo + gs : n;
+  return hi - lo;
+}
+uint8_t group_bits(const uint8_t* bits, int64_t n_bits, int64_t g) { return n_bits == 1 ? bits[0] : bits[g]; }
+
+}  // namespace
+
+extern "C" {
+
+int daf_oracle_rand_bits(void) { return kRandBits; }
+
+void daf_oracle_philox4x32_10(const uint32_t* ctr, const uint32_t* key, uint32_t* out) {
+  philox4x32_10(ctr, key, out);
+}
+
+uint32_t daf_oracle_rand(uint64_t seed, uint64_t i) { return rand_k(seed, i); }
+
+void daf_oracle_widen(const void* x, int dtype, int64_t n, float* out) {
+  for (int64_t i = 0; i < n; ++i) out[i] = load_elem(x, dtype, i);
+}
+
+void daf_oracle_narrow(const float* x, int dtype, int64_t n, void* out) {
+  for (int64_t i = 0; i < n; ++i) store_elem(out, dtype, i, x[i]);
+}
+
+// Plan: words per group w_g = ceil(n_g * b_g / 32) and their exclusive scan.
+// off may be null.  Returns the total word count, or -1 for bad arguments.
+// (The paper only says packed values are concatenated, Sec. 3.3; locating a
+// group by a scan of word counts is this build's reading.)
+int64_t daf_oracle_plan(int64_t n, int32_t gs, const uint8_t* bits, int64_t n_bits, uint32_t* off) {
+  if (n <= 0 || gs < 32 || gs % 32 != 0 || bits == nullptr) return -1;
+  const int64_t G = num_groups(n, gs);
+  if (n_bits != 1 && n_bits != G) return -1;
+  int64_t total = 0;
+  for (int64_t g = 0; g < G; ++g) {
+    const uint8_t b = group_bits(bits, n_bits, g);
+    if (!valid_bits(b)) return -1;
+    if (off) off[g] = static_cast<uint32_t>(total);
+    total += (group_len(n, gs, g) * b + 31) / 32;
+  }
+  return total;
+}
+
+// Quantize + pack groups [g_begin, g_end).  off[] comes from daf_oracle_plan.
+// codes (optional, one byte per element) receives the b-bit codes unpacked.
+int daf_oracle_quantize_pack_range(const void* x, int dtype, int64_t n, int32_t gs,
+                                   const uint8_t* bits, int64_t n_bits, const uint32_t* off,
+                                   uint64_t seed, int64_t g_begin, int64_t g_end,
+                                   uint32_t* words, float* out_min, float* out_scale,
+                                   uint8_t* codes) {
+  const float two_k = static_cast<float>(1u << kRandBits);
+  for (int64_t g = g_begin; g < g_end; ++g) {
+    const int64_t lo = g * gs;
+    const int64_t len = group_len(n, gs, g);
+    const uint32_t b = group_bits(bits, n_bits, g);
+    const uint32_t levels = (1u << b) - 1u;                     // 2^b - 1
+
+    // per-group statistics (Eq. 1: min and max; here per group)
+    float mn = load_elem(x, dtype, lo), mx = mn;
+    for (int64_t j = 1; j < len; ++j) {
+      const float v = load_elem(x, dtype, lo + j);
+      if (v < mn) mn = v;
+      if (v > mx) mx = v;
+    }
+    mn = mn + 0.0f;                                             // a stored zero is never -0
+    mx = mx + 0.0f;
+
+    // Eq. 1, left: scale; plus the reciprocal used instead of dividing per element
+    const float L = static_cast<float>(levels);
+    const float range = mx - mn;
+    const float scale = range / L;
+    float inv = 0.0f;
+    if (range > 0.0f) {
+      inv = L / range;
+      if (!std::isfinite(inv)) inv = 0.0f;
+    }
+    out_min[g] = mn;
+    out_scale[g] = scale;
+
+    // Eq. 1, right, with stochastic rounding in place of `round`; then pack
+    const int64_t nwords = (len * b + 31) / 32;
+    uint32_t* w = words + off[g];
+    for (int64_t t = 0; t < nwords; ++t) w[t] = 0u;
+    for (int64_t j = 0; j < len; ++j) {
+      const int64_t i = lo + j;
+      const float d = load_elem(x, dtype, i) - mn;
+      const float v = d * inv;
+      const float q0 = std::floor(v);
+      const float f = v - q0;                                   // exact, in [0,1)
+      const uint32_t r = rand_k(seed, static_cast<uint64_t>(i));
+      const bool up = (static_cast<float>(r) + 0.5f) < f * two_k;   // both sides exact
+      uint32_t code = static_cast<uint32_t>(q0) + (up ? 1u : 0u);
+      if (code > levels) code = levels;
+      if (codes) codes[i] = static_cast<uint8_t>(code);
+      const int64_t bitpos = j * b;                             // within the group's bit string
+      const uint32_t shift = 32u - b - static_cast<uint32_t>(bitpos % 32);  // first code -> top bits
+      w[bitpos / 32] |= code << shift;
+    }
+  }
+  return 0;
+}
+
+// Whole-tensor quantize + pack.  words must hold daf_oracle_plan(...) entries.
+int daf_oracle_quantize_pack(const void* x, int dtype, int64_t n, int32_t gs,
+                             const uint8_t* bits, int64_t n_bits, uint64_t seed,
+                             uint32_t* words, float* out_min, float* out_scale, uint8_t* codes) {
+  const int64_t G = num_groups(n, gs);
+  uint32_t* off = new uint32_t[G];
+  const int64_t total = daf_oracle_plan(n, gs, bits, n_bits, off);
+  int rc = -1;
+  if (total >= 0 && dtype >= F32 && dtype <= BF16)
+    rc = daf_oracle_quantize_pack_range(x, dtype, n, gs, bits, n_bits, off, seed, 0, G,
+                                        words, out_min, out_scale, codes);
+  delete[] off;
+  return rc;
+}
+
+// Unpack (Algorithm 2's extraction rule, generalised from 4 bits to b) and
+// dequantize (inverse of Eq. 1) groups [g_begin, g_end).
+int daf_oracle_unpack_dequantize_range(const uint32_t* words, const float* mn, const float* scale,
+                                       const uint8_t* bits, int64_t n_bits, const uint32_t* off,
+                                       int64_t n, int32_t gs, int64_t g_begin, int64_t g_end,
+                                       void* out_x, int dtype, uint8_t* codes) {
+  for (int64_t g = g_begin; g < g_end; ++g) {
+    const int64_t lo = g * gs;
+    const int64_t len = group_len(n, gs, g);
+    const uint32_t b = group_bits(bits, n_bits, g);
+    const uint32_t levels = (1u << b) - 1u;
+    const uint32_t* w = words + off[g];
+    for (int64_t j = 0; j < len; ++j) {
+      const int64_t bitpos = j * b;
+      const uint32_t word = w[bitpos / 32];
+      // same as (word << (bitpos%32)) >> (32-b): shift left to the top, then right
+      const uint32_t code = (word >> (32u - b - static_cast<uint32_t>(bitpos % 32))) & levels;
+      if (codes) codes[lo + j] = static_cast<uint8_t>(code);
+      const float xh = std::fmaf(static_cast<float>(code), scale[g], mn[g]);
+      store_elem(out_x, dtype, lo + j, xh);
+    }
+  }
+  return 0;
+}
+
+int daf_oracle_unpack_dequantize(const uint32_t* words, const float* mn, const float* scale,
+                                 const uint8_t* bits, int64_t n_bits, int64_t n, int32_t gs,
+                                 void* out_x, int dtype, uint8_t* codes) {
+  const int64_t G = num_groups(n, gs);
+  uint32_t* off = new uint32_t[G];
+  const int64_t total = daf_oracle_plan(n, gs, bits, n_bits, off);
+  int rc = -1;
+  if (total >= 0 && dtype >= F32 && dtype <= BF16)
+    rc = daf_oracle_unpack_dequantize_range(words, mn, scale, bits, n_bits, off, n, gs, 0, G,
+                                            out_x, dtype, codes);
+  delete[] off;
+  return rc;
+}
+
+}  // extern "C"

@@ -1,0 +1,152 @@
+"""ctypes + numpy face of the C++ oracle (oracle/daf_oracle.cpp).
+
+TEST INFRASTRUCTURE.  Arrays in, arrays out; every function is a thin call into the C++
+code, which is where the method is written down.  16-bit inputs travel as uint16 bit
+patterns (numpy has no bfloat16).
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+F32, F16, BF16 = 0, 1, 2
+_NP = {F32: np.float32, F16: np.uint16, BF16: np.uint16}
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.build(force=False)
+        L = ctypes.CDLL(path)
+        c = ctypes
+        vp, i64, i32, u64 = c.c_void_p, c.c_int64, c.c_int32, c.c_uint64
+        L.daf_oracle_rand_bits.restype = c.c_int
+        L.daf_oracle_philox4x32_10.argtypes = [vp, vp, vp]
+        L.daf_oracle_rand.argtypes = [u64, u64]
+        L.daf_oracle_rand.restype = c.c_uint32
+        L.daf_oracle_widen.argtypes = [vp, c.c_int, i64, vp]
+        L.daf_oracle_narrow.argtypes = [vp, c.c_int, i64, vp]
+        L.daf_oracle_plan.argtypes = [i64, i32, vp, i64, vp]
+        L.daf_oracle_plan.restype = i64
+        L.daf_oracle_quantize_pack.argtypes = [vp, c.c_int, i64, i32, vp, i64, u64, vp, vp, vp, vp]
+        L.daf_oracle_quantize_pack.restype = c.c_int
+        L.daf_oracle_quantize_pack_range.argtypes = [vp, c.c_int, i64, i32, vp, i64, vp, u64, i64, i64,
+                                                     vp, vp, vp, vp]
+        L.daf_oracle_quantize_pack_range.restype = c.c_int
+        L.daf_oracle_unpack_dequantize.argtypes = [vp, vp, vp, vp, i64, i64, i32, vp, c.c_int, vp]
+        L.daf_oracle_unpack_dequantize.restype = c.c_int
+        L.daf_oracle_unpack_dequantize_range.argtypes = [vp, vp, vp, vp, i64, vp, i64, i32, i64, i64,
+                                                         vp, c.c_int, vp]
+        L.daf_oracle_unpack_dequantize_range.restype = c.c_int
+        _lib = L
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _bits_arr(bits, G):
+    b = np.ascontiguousarray(np.atleast_1d(np.asarray(bits)).astype(np.uint8))
+    if b.size not in (1, G):
+        raise ValueError("bits must have 1 or G entries")
+    return b
+
+
+def rand_bits() -> int:
+    return int(lib().daf_oracle_rand_bits())
+
+
+def philox4x32_10(ctr, key):
+    c = np.asarray(ctr, dtype=np.uint32)
+    k = np.asarray(key, dtype=np.uint32)
+    o = np.zeros(4, dtype=np.uint32)
+    lib().daf_oracle_philox4x32_10(_p(c), _p(k), _p(o))
+    return o
+
+
+def rand(seed: int, i: int) -> int:
+    return int(lib().daf_oracle_rand(seed, i))
+
+
+def widen(x: np.ndarray, dtype: int) -> np.ndarray:
+    x = np.ascontiguousarray(x.reshape(-1), dtype=_NP[dtype])
+    out = np.empty(x.size, dtype=np.float32)
+    lib().daf_oracle_widen(_p(x), dtype, x.size, _p(out))
+    return out
+
+
+def narrow(x: np.ndarray, dtype: int) -> np.ndarray:
+    x = np.ascontiguousarray(x.reshape(-1), dtype=np.float32)
+    out = np.empty(x.size, dtype=_NP[dtype])
+    lib().daf_oracle_narrow(_p(x), dtype, x.size, _p(out))
+    return out
+
+
+def num_groups(n: int, gs: int) -> int:
+    return (n + gs - 1) // gs
+
+
+def plan(n: int, gs: int, bits):
+    """Returns (off[G] uint32, total_words)."""
+    G = num_groups(n, gs)
+    b = _bits_arr(bits, G)
+    off = np.empty(G, dtype=np.uint32)
+    total = lib().daf_oracle_plan(n, gs, _p(b), b.size, _p(off))
+    if total < 0:
+        raise ValueError("daf_oracle_plan rejected the arguments")
+    return off, int(total)
+
+
+def quantize_pack(x: np.ndarray, dtype: int, gs: int, bits, seed: int, want_codes: bool = False):
+    """x: flat float32 array, or uint16 bit patterns for F16/BF16.
+    Returns (words uint32[total], min float32[G], scale float32[G], codes uint8[N] or None)."""
+    x = np.ascontiguousarray(x.reshape(-1), dtype=_NP[dtype])
+    n = x.size
+    G = num_groups(n, gs)
+    b = _bits_arr(bits, G)
+    _, total = plan(n, gs, b)
+    words = np.empty(total, dtype=np.uint32)
+    mn = np.empty(G, dtype=np.float32)
+    sc = np.empty(G, dtype=np.float32)
+    codes = np.empty(n, dtype=np.uint8) if want_codes else None
+    rc = lib().daf_oracle_quantize_pack(_p(x), dtype, n, gs, _p(b), b.size, seed,
+                                        _p(words), _p(mn), _p(sc), _p(codes))
+    if rc != 0:
+        raise ValueError("daf_oracle_quantize_pack failed")
+    return words, mn, sc, codes
+
+
+def quantize_pack_range(x, dtype, gs, bits, off, seed, g_begin, g_end, words, mn, sc):
+    """Groups [g_begin, g_end) only, into caller-provided arrays (used to time the oracle
+    from several threads over disjoint ranges; ctypes drops the GIL during the call)."""
+    n = x.size
+    b = _bits_arr(bits, num_groups(n, gs))
+    return lib().daf_oracle_quantize_pack_range(_p(x), dtype, n, gs, _p(b), b.size, _p(off), seed,
+                                                g_begin, g_end, _p(words), _p(mn), _p(sc), None)
+
+
+def unpack_dequantize(words, mn, sc, bits, n: int, gs: int, dtype: int, want_codes: bool = False):
+    """Returns (xhat as float32 or uint16 bit patterns, codes or None)."""
+    G = num_groups(n, gs)
+    b = _bits_arr(bits, G)
+    words = np.ascontiguousarray(words, dtype=np.uint32)
+    mn = np.ascontiguousarray(mn, dtype=np.float32)
+    sc = np.ascontiguousarray(sc, dtype=np.float32)
+    out = np.empty(n, dtype=_NP[dtype])
+    codes = np.empty(n, dtype=np.uint8) if want_codes else None
+    rc = lib().daf_oracle_unpack_dequantize(_p(words), _p(mn), _p(sc), _p(b), b.size, n, gs,
+                                            _p(out), dtype, _p(codes))
+    if rc != 0:
+        raise ValueError("daf_oracle_unpack_dequantize failed")
+    return out, codes
+
+
+def unpack_dequantize_range(words, mn, sc, bits, off, n, gs, g_begin, g_end, out, dtype):
+    b = _bits_arr(bits, num_groups(n, gs))
+    return lib().daf_oracle_unpack_dequantize_range(_p(words), _p(mn), _p(sc), _p(b), b.size, _p(off),
+                                                    n, gs, g_begin, g_end, _p(out), dtype, None)

@@ -1,0 +1,50 @@
+"""Pins for the oracle's 16-bit conversions against numpy float16 and torch bfloat16."""
+import numpy as np
+import torch
+
+from oracle import daf_oracle as orc
+
+
+def test_widen_f16_all_patterns():
+    h = np.arange(65536, dtype=np.uint16)
+    got = orc.widen(h, orc.F16)
+    want = h.view(np.float16).astype(np.float32)
+    assert np.array_equal(got.view(np.uint32)[~np.isnan(want)], want.view(np.uint32)[~np.isnan(want)])
+    assert np.all(np.isnan(got[np.isnan(want)]))
+
+
+def test_widen_bf16_all_patterns():
+    h = np.arange(65536, dtype=np.uint16)
+    got = orc.widen(h, orc.BF16)
+    want = torch.from_numpy(h.view(np.int16)).view(torch.bfloat16).float().numpy()
+    ok = ~np.isnan(want)
+    assert np.array_equal(got.view(np.uint32)[ok], want.view(np.uint32)[ok])
+
+
+def _samples():
+    rng = np.random.default_rng(0)
+    a = rng.standard_normal(200_000).astype(np.float32) * (10.0 ** rng.uniform(-9, 5, 200_000)).astype(np.float32)
+    # every float32 that sits exactly between two 16-bit neighbours, plus neighbours of those
+    h = np.arange(0, 0x7C00, dtype=np.uint16)
+    mid16 = (h.view(np.float16).astype(np.float64) + (h + 1).astype(np.uint16).view(np.float16).astype(np.float64)) / 2
+    mid16 = mid16[np.isfinite(mid16)].astype(np.float32)
+    bf = (np.arange(0x0001, 0x7F7F, dtype=np.uint32) << 16).view(np.float32).astype(np.float64)
+    midbf = ((bf[:-1] + bf[1:]) / 2).astype(np.float32)
+    edge = np.array([0.0, -0.0, 65504.0, 65519.99, 65520.0, 70000.0, 2.0 ** -24, 2.0 ** -25,
+                     2.0 ** -25 * 1.0000001, 6.1e-5, 5.96e-8, 3.3e38, -3.3e38, 1e-45], dtype=np.float32)
+    allv = np.concatenate([a, mid16, np.nextafter(mid16, np.float32(0)), np.nextafter(mid16, np.float32(np.inf)),
+                           midbf, np.nextafter(midbf, np.float32(0)), edge])
+    return np.concatenate([allv, -allv])
+
+
+def test_narrow_f16_matches_numpy():
+    x = _samples()
+    with np.errstate(over="ignore"):
+        want = x.astype(np.float16).view(np.uint16)
+    assert np.array_equal(orc.narrow(x, orc.F16), want)
+
+
+def test_narrow_bf16_matches_torch():
+    x = _samples()
+    want = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(orc.narrow(x, orc.BF16), want)
