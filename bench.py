@@ -1,0 +1,174 @@
+#!/usr/bin/env python3
+"""Benchmark of the DAF activation quantize/pack hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--no-cpu-baseline]
+
+A step is one pass of the whole hot path over one activation batch: daf_quantize_pack
+(min/max, scale, stochastic-rounding quantize, pack) followed by daf_unpack_dequantize, with
+all inputs resident in HBM.  The default workload is the ResNet-50-like conv activation
+(fp32 64x256x56x56, groups of 256, 2 bits, seed 1).  Steps rotate over several buffer sets
+whose total exceeds the 256 MB last-level cache, so loads come from HBM.
+
+Prints ONE JSON line.  `value` is GB/s of activation bytes through the path: each step moves
+the activation tensor once through quantize+pack and once through unpack+dequantize, so
+value = 2 * N * sizeof(dtype) / step time.  Per-direction rates and the roofline of the
+dominant kernel (algorithmic bytes / HIP-event kernel time, against 8 TB/s) ride along, as
+does the CPU oracle timed on this host (a reported baseline, not a target).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+ROTATE_BYTES = 768 << 20          # buffer sets rotate over at least this much input
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def algorithmic_bytes(w, total_words):
+    """Bytes the method must move for one direction of one tensor: the activation once, the
+    packed words once, min and scale once, plus (per-group widths only) one width byte per
+    group and one 4-byte offset per group."""
+    n, G = w.numel, w.num_groups
+    esz = w.x.element_size()
+    meta = 0 if w.bits.size == 1 else G * (1 + 4)
+    return n * esz + 4 * total_words + 8 * G + meta
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2507_07149_amd as daf
+    from daf_inputs import CONFIG_NAMES, make_config, to_numpy_bits
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    daf.load_library()                      # fails loudly if libdaf.so is missing
+    dev = torch.device("cuda:0")
+
+    workloads = make_config(args.config)
+    in_bytes = sum(w.numel * w.x.element_size() for w in workloads)
+    n_sets = max(1, -(-ROTATE_BYTES // in_bytes))
+    if in_bytes >= ROTATE_BYTES:
+        n_sets = 1
+
+    # device state: per tensor a plan, and per (set, tensor) its buffers
+    plans, dbits = [], []
+    for w in workloads:
+        if w.bits.size == 1:
+            dbits.append(None)
+            plans.append(daf.daf_plan(tuple(w.x.shape), w.group_size, int(w.bits[0])))
+        else:
+            dbits.append(torch.from_numpy(w.bits).to(dev))
+            plans.append(daf.daf_plan(tuple(w.x.shape), w.group_size, dbits[-1]))
+    sets = []
+    for s in range(n_sets):
+        bufs = []
+        for w, p in zip(workloads, plans):
+            x = w.x.reshape(-1).to(dev)
+            bufs.append(dict(x=x, words=torch.empty(p.packed_words, dtype=torch.int32, device=dev),
+                             mn=torch.empty(p.num_groups, dtype=torch.float32, device=dev),
+                             sc=torch.empty(p.num_groups, dtype=torch.float32, device=dev),
+                             xh=torch.empty_like(x)))
+        sets.append(bufs)
+    torch.cuda.synchronize()
+
+    def step(i, ev=None):
+        bufs = sets[i % n_sets]
+        # forward order, then reverse order (a training step saves, then restores backwards)
+        if ev is not None:
+            ev[0].record()
+        for w, p, b in zip(workloads, plans, bufs):
+            daf.daf_quantize_pack(p, b["x"], w.seed, b["words"], b["mn"], b["sc"])
+        if ev is not None:
+            ev[1].record()
+        for w, p, b in reversed(list(zip(workloads, plans, bufs))):
+            daf.daf_unpack_dequantize(p, b["words"], b["mn"], b["sc"], b["xh"])
+        if ev is not None:
+            ev[2].record()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i, events[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    q_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
+    d_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
+    alg = sum(algorithmic_bytes(w, p.packed_words) for w, p in zip(workloads, plans))
+    value = 2 * in_bytes / (ms_per_step * 1e-3) / 1e9
+
+    def roof(ms):
+        ach = alg / (ms * 1e-3) / 1e9
+        return {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None}
+
+    out = {
+        "metric": "quantize+pack and unpack+dequantize GB/s of activations",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": {0: "f32", 1: "f16", 2: "bf16"}[workloads[0].dtype],
+        "data": "synthetic", "config": {"workload": CONFIG_NAMES[args.config], "tensors": len(workloads),
+                                        "elements": sum(w.numel for w in workloads),
+                                        "group_size": workloads[0].group_size, "buffer_sets": n_sets},
+        "quantize_pack": {"ms": round(q_ms, 4), "input_GBps": round(in_bytes / q_ms / 1e6, 1),
+                          "algorithmic_bytes": alg},
+        "unpack_dequantize": {"ms": round(d_ms, 4), "output_GBps": round(in_bytes / d_ms / 1e6, 1),
+                              "algorithmic_bytes": alg},
+        "roofline": dict(roof(q_ms), kernel="k_quantize_pack_tile"),
+        "roofline_unpack_dequantize": dict(roof(d_ms), kernel="k_unpack_dequantize_chunk"),
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import daf_oracle as orc
+        # the oracle as it stands, one thread, on the first tensor(s) of the same workload,
+        # bounded to ~256 MB of input; best of 3
+        budget, sample, done = 256 << 20, [], 0
+        for w in workloads:
+            if done >= budget:
+                break
+            sample.append(w)
+            done += w.numel * w.x.element_size()
+        best = float("inf")
+        for _ in range(3):
+            t = time.perf_counter()
+            for w in sample:
+                xb = to_numpy_bits(w.x)
+                ow, omn, osc, _ = orc.quantize_pack(xb, w.dtype, w.group_size, w.bits, w.seed)
+                orc.unpack_dequantize(ow, omn, osc, w.bits, w.numel, w.group_size, w.dtype)
+            best = min(best, time.perf_counter() - t)
+        out["cpu_baseline"] = {"value": round(2 * done / best / 1e9, 4), "unit": "GB/s", "cores": 1,
+                               "kind": "oracle", "seconds": round(best, 2),
+                               "sample": f"{len(sample)} of {len(workloads)} tensors, {done} input bytes, "
+                                         "quantize+pack then unpack+dequantize, best of 3"}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

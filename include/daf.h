@@ -1,0 +1,144 @@
+/* daf.h -- C ABI of the MI355X (gfx950) DAF activation quantize/pack library.
+ *
+ * The library implements, on one GPU, the storage half of dynamic activation
+ * quantization for training: an activation tensor computed by the forward pass is
+ * quantized group by group to a per-group bit width, the codes are packed tightly
+ * into 32-bit words, and before the backward pass the words are unpacked and
+ * dequantized to the original precision (paper Sec. 2.2 "Quantization Calculation",
+ * Eq. 1, and the paragraph after it; Sec. 3.1 overview; Sec. 3.3 "Bit Layout
+ * Conversion"; Algorithm 2 for the order of codes inside a word).
+ *
+ * Conventions common to all calls
+ *   - Pointers marked DEVICE are addresses in the current HIP device's memory; pointers
+ *     marked HOST are ordinary process memory.  The library never takes ownership of a
+ *     caller buffer and never writes to an input.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - The tensor is row-major contiguous; it is treated as a flat array of
+ *     N = prod(shape) elements.  Group g covers flat indices
+ *     [g*group_size, min((g+1)*group_size, N)); the last group may be short.
+ *   - Every call returns a daf_status_t (0 = success, negative = error).  No exceptions,
+ *     no logging, no abort.  Argument checks that do not need the GPU happen before any
+ *     HIP call.
+ *   - Packed layout (part of the ABI): group g owns words
+ *     [off[g], off[g] + ceil(n_g*bits[g]/32)) of the packed buffer, where off is the
+ *     exclusive prefix sum of those word counts.  Inside a group, code j occupies bits
+ *     bits[g] wide at bit position j*bits[g] of the group's bit string, and the bit string
+ *     fills each 32-bit word from its most significant bit downwards (Algorithm 2:
+ *     value j of a word is (w << 4j) >> 28 for 4-bit codes).  Unused low bits of a short
+ *     last group's final word are zero.
+ *   - Random numbers: element i draws 8 bits from Philox4x32-10 with counter
+ *     (lo32(i/16), hi32(i/16), 0, 0) and key (lo32(seed), hi32(seed)): byte i%16 of the
+ *     128-bit output taken low word first, low byte first.  The draw depends on
+ *     (seed, i) only, not on shape, grouping or launch configuration.
+ */
+#ifndef DAF_H_
+#define DAF_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct daf_plan_s daf_plan_t;         /* opaque; created by daf_plan, freed by daf_plan_destroy */
+
+typedef enum { DAF_F32 = 0, DAF_F16 = 1, DAF_BF16 = 2 } daf_dtype_t;
+
+typedef enum {
+  DAF_OK = 0,
+  DAF_EINVAL = -1,        /* null pointer, bad shape, bad bits value, misaligned pointer, wrong count */
+  DAF_EUNSUPPORTED = -2,  /* group_size not a multiple of 32, unknown dtype, packed size >= 2^32 words */
+  DAF_ENOMEM = -3,        /* host or device allocation for the plan failed */
+  DAF_EDEVICE = -4        /* a HIP call or kernel launch failed */
+} daf_status_t;
+
+/* Number of random bits spent per element by stochastic rounding (8). */
+int daf_rand_bits(void);
+
+/* Human-readable name of a status code; never NULL; static storage. */
+const char* daf_status_string(int status);
+
+/* daf_plan -- size and locate the packed representation of one activation tensor.
+ *
+ * Computes, per group, the number of 32-bit words ceil(n_g * bits[g] / 32) its codes
+ * occupy (Sec. 3.3 packs eight 4-bit values per 32-bit word; generalised here to
+ * 32/b codes per word) and the exclusive prefix sum of those counts, i.e. each group's
+ * word offset in the packed buffer, with a device scan.
+ *
+ *   shape, ndim   HOST.  ndim >= 1, every dimension >= 1.  N = prod(shape).
+ *   group_size    elements per group; a multiple of 32, >= 32.
+ *   bits, n_bits  bit width of every group, each in {1,2,4,8}.
+ *                 n_bits == 1: `bits` is a HOST pointer to the one width shared by all groups.
+ *                 n_bits == G = ceil(N/group_size): `bits` is a DEVICE pointer to G bytes;
+ *                 the plan keeps its own device copy.
+ *   stream        stream the scan runs on; the call synchronizes it once before returning
+ *                 (to read back the total and the validity flag).
+ *   out_plan      HOST.  Receives the plan on success, NULL otherwise.
+ *
+ * Errors: DAF_EINVAL (null pointer, ndim < 1, dimension < 1, n_bits not in {1, G}, a width
+ * outside {1,2,4,8}), DAF_EUNSUPPORTED (group_size % 32 != 0 or < 32, total >= 2^32 words),
+ * DAF_ENOMEM, DAF_EDEVICE.
+ */
+int daf_plan(const int64_t* shape, int ndim, int32_t group_size,
+             const uint8_t* bits, int64_t n_bits, void* stream, daf_plan_t** out_plan);
+
+/* Plan queries (plain host reads, no HIP call). */
+int64_t daf_plan_num_elements(const daf_plan_t* plan);   /* N */
+int64_t daf_plan_num_groups(const daf_plan_t* plan);     /* G */
+int64_t daf_plan_packed_words(const daf_plan_t* plan);   /* words the caller must allocate for out_words */
+int32_t daf_plan_group_size(const daf_plan_t* plan);
+int32_t daf_plan_uniform_bits(const daf_plan_t* plan);   /* the shared width, or 0 for per-group widths */
+
+/* Copies the G group word offsets to HOST memory (synchronous; for inspection and tests).
+ * Works for uniform plans too (offsets are then computed, not stored). */
+int daf_plan_copy_offsets(const daf_plan_t* plan, uint32_t* out_off);
+
+/* Frees the plan and the device memory it owns.  NULL is allowed. */
+void daf_plan_destroy(daf_plan_t* plan);
+
+/* daf_quantize_pack -- forward-pass side: per-group min/max, scale, stochastic-rounding
+ * quantization and bit packing, fused in one pass over x.
+ *
+ * For every group: min and max over the group (Eq. 1's min and max, taken per group), with
+ * a zero result stored as +0; scale = (max-min)/(2^b-1) (Eq. 1, left); each element is
+ * mapped to v = (x-min) * ((2^b-1)/(max-min)) and rounded to floor(v) or floor(v)+1, up
+ * with probability equal to its fractional part quantised to 8 bits (Eq. 1, right, with
+ * stochastic rounding in place of `round`; r + 1/2 < frac(v)*256 for the element's random
+ * byte r), clamped to 2^b-1; the codes are packed as described at the top of this file.
+ * A group whose max equals its min (or whose reciprocal range overflows) gets all-zero
+ * codes and scale = range/(2^b-1).
+ *
+ *   plan       from daf_plan, for this tensor's shape, group size and widths.
+ *   x          DEVICE, N elements of `dtype`, 16-byte aligned.  Finite values only.
+ *   dtype      element type of x.  16-bit inputs are widened exactly to binary32 first.
+ *   seed       key of the random stream.
+ *   out_words  DEVICE, daf_plan_packed_words(plan) uint32, 4-byte aligned; fully overwritten.
+ *   out_min    DEVICE, G floats; out_scale: DEVICE, G floats.  Always binary32.
+ *   stream     the call only enqueues work on this stream; it does not synchronize.
+ *
+ * Errors: DAF_EINVAL (null or misaligned pointer), DAF_EUNSUPPORTED (dtype), DAF_EDEVICE.
+ */
+int daf_quantize_pack(const daf_plan_t* plan, const void* x, daf_dtype_t dtype, uint64_t seed,
+                      uint32_t* out_words, float* out_min, float* out_scale, void* stream);
+
+/* daf_unpack_dequantize -- backward-pass side: extract every code (Algorithm 2's rule,
+ * for the group's width) and restore xhat = fma(code, scale, min) in binary32, then round
+ * to `dtype` (nearest even): the stored activation returns to its original precision
+ * before gradients are computed (Sec. 2.2).
+ *
+ *   words, min, scale   DEVICE, as produced by daf_quantize_pack for the same plan.
+ *   bits                DEVICE pointer to G widths, or NULL to use the plan's own copy
+ *                       (must be NULL for a uniform plan).
+ *   out_x               DEVICE, N elements of `dtype`, 16-byte aligned; fully overwritten.
+ *   stream              enqueue only; no synchronization.
+ *
+ * Errors: DAF_EINVAL, DAF_EUNSUPPORTED (dtype), DAF_EDEVICE.
+ */
+int daf_unpack_dequantize(const daf_plan_t* plan, const uint32_t* words,
+                          const float* min, const float* scale, const uint8_t* bits,
+                          void* out_x, daf_dtype_t dtype, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DAF_H_ */

@@ -1,0 +1,147 @@
+"""ctypes binding of libdaf.so: same names as the C ABI, argument marshalling only."""
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import torch
+
+F32, F16, BF16 = 0, 1, 2
+_DTYPE_ID = {torch.float32: F32, torch.float16: F16, torch.bfloat16: BF16}
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libdaf.so")
+_lib = None
+
+
+class DafError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = load_library().daf_status_string(status).decode()
+        super().__init__(f"{where}: {msg} ({status})")
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads libdaf.so.  Fails loudly if it has not been built (python -m paper_2507_07149_amd.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2507_07149_amd.build`; "
+                          "there is no fallback path")
+    L = ctypes.CDLL(_LIB_PATH)
+    c = ctypes
+    vp, i64, i32, u64 = c.c_void_p, c.c_int64, c.c_int32, c.c_uint64
+    L.daf_rand_bits.restype = c.c_int
+    L.daf_status_string.argtypes = [c.c_int]
+    L.daf_status_string.restype = c.c_char_p
+    L.daf_plan.argtypes = [c.POINTER(i64), c.c_int, i32, vp, i64, vp, c.POINTER(vp)]
+    L.daf_plan.restype = c.c_int
+    for name, res in (("daf_plan_num_elements", i64), ("daf_plan_num_groups", i64),
+                      ("daf_plan_packed_words", i64), ("daf_plan_group_size", i32),
+                      ("daf_plan_uniform_bits", i32)):
+        getattr(L, name).argtypes = [vp]
+        getattr(L, name).restype = res
+    L.daf_plan_copy_offsets.argtypes = [vp, vp]
+    L.daf_plan_copy_offsets.restype = c.c_int
+    L.daf_plan_destroy.argtypes = [vp]
+    L.daf_plan_destroy.restype = None
+    L.daf_quantize_pack.argtypes = [vp, vp, c.c_int, u64, vp, vp, vp, vp]
+    L.daf_quantize_pack.restype = c.c_int
+    L.daf_unpack_dequantize.argtypes = [vp, vp, vp, vp, vp, vp, c.c_int, vp]
+    L.daf_unpack_dequantize.restype = c.c_int
+    _lib = L
+    return L
+
+
+def rand_bits() -> int:
+    return int(load_library().daf_rand_bits())
+
+
+def dtype_id(dtype: torch.dtype) -> int:
+    return _DTYPE_ID[dtype]
+
+
+def _stream_handle(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+class Plan:
+    """Owns a daf_plan_t*.  `bits` (a device uint8 tensor for per-group widths) is kept alive."""
+
+    def __init__(self, handle: int, bits_keepalive=None):
+        self._h = handle
+        self._keep = bits_keepalive
+
+    @property
+    def handle(self) -> int:
+        if not self._h:
+            raise ValueError("plan already destroyed")
+        return self._h
+
+    num_elements = property(lambda s: int(load_library().daf_plan_num_elements(s.handle)))
+    num_groups = property(lambda s: int(load_library().daf_plan_num_groups(s.handle)))
+    packed_words = property(lambda s: int(load_library().daf_plan_packed_words(s.handle)))
+    group_size = property(lambda s: int(load_library().daf_plan_group_size(s.handle)))
+    uniform_bits = property(lambda s: int(load_library().daf_plan_uniform_bits(s.handle)))
+
+    def offsets(self) -> torch.Tensor:
+        out = torch.empty(self.num_groups, dtype=torch.int32)
+        rc = load_library().daf_plan_copy_offsets(self.handle, out.data_ptr())
+        if rc != 0:
+            raise DafError(rc, "daf_plan_copy_offsets")
+        return out
+
+    def destroy(self):
+        if self._h:
+            load_library().daf_plan_destroy(self._h)
+            self._h = 0
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def daf_plan(shape: Sequence[int], group_size: int, bits, stream=None) -> Plan:
+    """bits: an int (one width for all groups) or a device uint8 tensor with one width per group."""
+    L = load_library()
+    shp = (ctypes.c_int64 * len(shape))(*[int(s) for s in shape])
+    out = ctypes.c_void_p()
+    if isinstance(bits, int):
+        b = (ctypes.c_uint8 * 1)(bits)
+        rc = L.daf_plan(shp, len(shape), group_size, ctypes.cast(b, ctypes.c_void_p), 1, None, ctypes.byref(out))
+        keep = None
+    else:
+        if bits.dtype != torch.uint8 or not bits.is_cuda or not bits.is_contiguous():
+            raise TypeError("per-group bits must be a contiguous uint8 device tensor")
+        rc = L.daf_plan(shp, len(shape), group_size, bits.data_ptr(), bits.numel(), _stream_handle(stream),
+                        ctypes.byref(out))
+        keep = bits
+    if rc != 0:
+        raise DafError(rc, "daf_plan")
+    return Plan(out.value, keep)
+
+
+def daf_quantize_pack(plan: Plan, x: torch.Tensor, seed: int, out_words: torch.Tensor, out_min: torch.Tensor,
+                      out_scale: torch.Tensor, stream=None) -> None:
+    rc = load_library().daf_quantize_pack(plan.handle, x.data_ptr(), _DTYPE_ID[x.dtype], seed,
+                                          out_words.data_ptr(), out_min.data_ptr(), out_scale.data_ptr(),
+                                          _stream_handle(stream))
+    if rc != 0:
+        raise DafError(rc, "daf_quantize_pack")
+
+
+def daf_unpack_dequantize(plan: Plan, words: torch.Tensor, mn: torch.Tensor, scale: torch.Tensor,
+                          out_x: torch.Tensor, bits: Optional[torch.Tensor] = None, stream=None) -> None:
+    rc = load_library().daf_unpack_dequantize(plan.handle, words.data_ptr(), mn.data_ptr(), scale.data_ptr(),
+                                              bits.data_ptr() if bits is not None else None,
+                                              out_x.data_ptr(), _DTYPE_ID[out_x.dtype], _stream_handle(stream))
+    if rc != 0:
+        raise DafError(rc, "daf_unpack_dequantize")

@@ -1,0 +1,165 @@
+// C ABI of libdaf: argument checks, plan construction, dispatch to the kernel launchers.
+// Every check that does not need the GPU comes before the first HIP call.
+#include <new>
+
+#include "daf_internal.h"
+
+namespace {
+
+bool valid_width(int b) { return b == 1 || b == 2 || b == 4 || b == 8; }
+bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+struct DeviceGuard {      // make the plan's device current for the duration of a call
+  int prev = -1;
+  bool switched = false;
+  hipError_t enter(int dev) {
+    hipError_t e = hipGetDevice(&prev);
+    if (e != hipSuccess) return e;
+    if (prev != dev) {
+      e = hipSetDevice(dev);
+      switched = (e == hipSuccess);
+    }
+    return e;
+  }
+  ~DeviceGuard() {
+    if (switched) (void)hipSetDevice(prev);
+  }
+};
+
+}  // namespace
+
+extern "C" {
+
+int daf_rand_bits(void) { return 8; }
+
+const char* daf_status_string(int status) {
+  switch (status) {
+    case DAF_OK: return "DAF_OK";
+    case DAF_EINVAL: return "DAF_EINVAL: invalid argument";
+    case DAF_EUNSUPPORTED: return "DAF_EUNSUPPORTED: unsupported group size, dtype or packed size";
+    case DAF_ENOMEM: return "DAF_ENOMEM: allocation failed";
+    case DAF_EDEVICE: return "DAF_EDEVICE: HIP call or kernel launch failed";
+    default: return "unknown daf status";
+  }
+}
+
+int daf_plan(const int64_t* shape, int ndim, int32_t group_size, const uint8_t* bits, int64_t n_bits,
+             void* stream, daf_plan_t** out_plan) {
+  if (out_plan == nullptr) return DAF_EINVAL;
+  *out_plan = nullptr;
+  if (shape == nullptr || bits == nullptr || ndim < 1) return DAF_EINVAL;
+  int64_t n = 1;
+  for (int d = 0; d < ndim; ++d) {
+    if (shape[d] < 1) return DAF_EINVAL;
+    if (n > INT64_MAX / shape[d]) return DAF_EUNSUPPORTED;
+    n *= shape[d];
+  }
+  if (group_size < 32 || group_size % 32 != 0) return DAF_EUNSUPPORTED;
+  const int64_t G = (n + group_size - 1) / group_size;
+  if (n_bits != 1 && n_bits != G) return DAF_EINVAL;
+
+  daf_plan_t* p = new (std::nothrow) daf_plan_t();
+  if (p == nullptr) return DAF_ENOMEM;
+  p->n = n;
+  p->num_groups = G;
+  p->group_size = group_size;
+  p->d_bits = nullptr;
+  p->d_off = nullptr;
+  p->device = -1;
+
+  if (n_bits == 1) {                     // uniform width: `bits` is a host pointer, no device work
+    const int b = bits[0];
+    if (!valid_width(b)) { delete p; return DAF_EINVAL; }
+    const int64_t full = n / group_size, tail = n - full * group_size;
+    const int64_t total = full * ((int64_t)group_size * b / 32) + (tail * b + 31) / 32;
+    if (total >= (int64_t)1 << 32) { delete p; return DAF_EUNSUPPORTED; }
+    p->uniform_bits = b;
+    p->total_words = total;
+    (void)hipGetDevice(&p->device);      // remembered when a device exists; harmless otherwise
+    *out_plan = p;
+    return DAF_OK;
+  }
+
+  // per-group widths: device copy + device scan
+  p->uniform_bits = 0;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  int rc = DAF_OK;
+  unsigned long long* d_sums = nullptr;   // block sums + [n_blocks] total + bad flag
+  const int64_t n_blocks = daf_plan_scan_blocks(G);
+  struct { unsigned long long total; int bad; int pad; } h = {0, 0, 0};
+  do {
+    if (hipGetDevice(&p->device) != hipSuccess) { rc = DAF_EDEVICE; break; }
+    if (hipMalloc(&p->d_bits, (size_t)G) != hipSuccess) { rc = DAF_ENOMEM; break; }
+    if (hipMalloc(&p->d_off, (size_t)G * sizeof(uint32_t)) != hipSuccess) { rc = DAF_ENOMEM; break; }
+    if (hipMalloc(&d_sums, (size_t)(n_blocks + 2) * sizeof(unsigned long long)) != hipSuccess) { rc = DAF_ENOMEM; break; }
+    unsigned long long* d_total = d_sums + n_blocks;
+    int* d_bad = reinterpret_cast<int*>(d_sums + n_blocks + 1);
+    if (hipMemcpyAsync(p->d_bits, bits, (size_t)G, hipMemcpyDeviceToDevice, st) != hipSuccess) { rc = DAF_EDEVICE; break; }
+    if (hipMemsetAsync(d_total, 0, 2 * sizeof(unsigned long long), st) != hipSuccess) { rc = DAF_EDEVICE; break; }
+    if (daf_launch_plan_scan(p->d_bits, G, n, group_size, p->d_off, d_sums, n_blocks, d_total, d_bad, st) != hipSuccess) { rc = DAF_EDEVICE; break; }
+    if (hipMemcpyAsync(&h, d_total, sizeof(h), hipMemcpyDeviceToHost, st) != hipSuccess) { rc = DAF_EDEVICE; break; }
+    if (hipStreamSynchronize(st) != hipSuccess) { rc = DAF_EDEVICE; break; }
+    if (h.bad) { rc = DAF_EINVAL; break; }
+    if (h.total >= 1ull << 32) { rc = DAF_EUNSUPPORTED; break; }
+    p->total_words = (int64_t)h.total;
+  } while (false);
+  if (d_sums) (void)hipFree(d_sums);
+  if (rc != DAF_OK) {
+    daf_plan_destroy(p);
+    return rc;
+  }
+  *out_plan = p;
+  return DAF_OK;
+}
+
+int64_t daf_plan_num_elements(const daf_plan_t* plan) { return plan ? plan->n : -1; }
+int64_t daf_plan_num_groups(const daf_plan_t* plan) { return plan ? plan->num_groups : -1; }
+int64_t daf_plan_packed_words(const daf_plan_t* plan) { return plan ? plan->total_words : -1; }
+int32_t daf_plan_group_size(const daf_plan_t* plan) { return plan ? plan->group_size : -1; }
+int32_t daf_plan_uniform_bits(const daf_plan_t* plan) { return plan ? plan->uniform_bits : -1; }
+
+int daf_plan_copy_offsets(const daf_plan_t* plan, uint32_t* out_off) {
+  if (plan == nullptr || out_off == nullptr) return DAF_EINVAL;
+  if (plan->uniform_bits) {
+    const uint32_t wpg = (uint32_t)((int64_t)plan->group_size * plan->uniform_bits / 32);
+    for (int64_t g = 0; g < plan->num_groups; ++g) out_off[g] = (uint32_t)g * wpg;
+    return DAF_OK;
+  }
+  DeviceGuard guard;
+  if (guard.enter(plan->device) != hipSuccess) return DAF_EDEVICE;
+  if (hipMemcpy(out_off, plan->d_off, (size_t)plan->num_groups * sizeof(uint32_t), hipMemcpyDeviceToHost) != hipSuccess)
+    return DAF_EDEVICE;
+  return DAF_OK;
+}
+
+void daf_plan_destroy(daf_plan_t* plan) {
+  if (plan == nullptr) return;
+  if (plan->d_bits) (void)hipFree(plan->d_bits);
+  if (plan->d_off) (void)hipFree(plan->d_off);
+  delete plan;
+}
+
+int daf_quantize_pack(const daf_plan_t* plan, const void* x, daf_dtype_t dtype, uint64_t seed,
+                      uint32_t* out_words, float* out_min, float* out_scale, void* stream) {
+  if (plan == nullptr || x == nullptr || out_words == nullptr || out_min == nullptr || out_scale == nullptr)
+    return DAF_EINVAL;
+  if (!aligned(x, 16) || !aligned(out_words, 4) || !aligned(out_min, 4) || !aligned(out_scale, 4)) return DAF_EINVAL;
+  if (dtype != DAF_F32 && dtype != DAF_F16 && dtype != DAF_BF16) return DAF_EUNSUPPORTED;
+  const hipError_t e = daf_launch_quantize_pack(plan, x, (int)dtype, seed, out_words, out_min, out_scale,
+                                                static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? DAF_OK : DAF_EDEVICE;
+}
+
+int daf_unpack_dequantize(const daf_plan_t* plan, const uint32_t* words, const float* min, const float* scale,
+                          const uint8_t* bits, void* out_x, daf_dtype_t dtype, void* stream) {
+  if (plan == nullptr || words == nullptr || min == nullptr || scale == nullptr || out_x == nullptr) return DAF_EINVAL;
+  if (!aligned(out_x, 16) || !aligned(words, 4) || !aligned(min, 4) || !aligned(scale, 4)) return DAF_EINVAL;
+  if (plan->uniform_bits && bits != nullptr) return DAF_EINVAL;
+  if (dtype != DAF_F32 && dtype != DAF_F16 && dtype != DAF_BF16) return DAF_EUNSUPPORTED;
+  const uint8_t* d_bits = bits ? bits : plan->d_bits;
+  const hipError_t e = daf_launch_unpack_dequantize(plan, words, min, scale, d_bits, out_x, (int)dtype,
+                                                    static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? DAF_OK : DAF_EDEVICE;
+}
+
+}  // extern "C"

@@ -1,0 +1,31 @@
+// Internal declarations shared by the translation units of libdaf (host side).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "daf.h"
+
+struct daf_plan_s {
+  int64_t n;             // elements
+  int64_t num_groups;    // G = ceil(n / group_size)
+  int64_t total_words;   // packed size
+  int32_t group_size;
+  int32_t uniform_bits;  // shared width, or 0 when widths are per group
+  int device;            // HIP device the plan's memory lives on
+  uint8_t* d_bits;       // G widths (device), mixed plans only
+  uint32_t* d_off;       // G word offsets (device), mixed plans only
+};
+
+// Launchers.  Each returns hipSuccess or the first HIP error.
+hipError_t daf_launch_plan_scan(const uint8_t* d_bits, int64_t num_groups, int64_t n, int32_t group_size,
+                                uint32_t* d_off, unsigned long long* d_block_sums, int64_t n_blocks,
+                                unsigned long long* d_total, int* d_bad, hipStream_t stream);
+int64_t daf_plan_scan_blocks(int64_t num_groups);
+
+hipError_t daf_launch_quantize_pack(const daf_plan_t* plan, const void* x, int dtype, uint64_t seed,
+                                    uint32_t* out_words, float* out_min, float* out_scale,
+                                    hipStream_t stream);
+
+hipError_t daf_launch_unpack_dequantize(const daf_plan_t* plan, const uint32_t* words, const float* mn,
+                                        const float* scale, const uint8_t* d_bits, void* out_x, int dtype,
+                                        hipStream_t stream);

@@ -1,0 +1,429 @@
+// Forward-pass side: per-group min/max -> scale -> stochastic-rounding quantization ->
+// bit packing, in one pass over the activation (paper Sec. 2.2, Eq. 1; Sec. 3.3; order of
+// codes in a word from Algorithm 2).  Two kernels:
+//
+//   k_quantize_pack_tile   the fast path.  One wave owns a tile of 2048 or 4096 consecutive
+//                          elements (a whole number of groups).  x is read from HBM once with
+//                          16-byte loads and stays in registers between the reduction and the
+//                          quantization; random bytes, group statistics and the packed words
+//                          are staged in wave-private LDS; the words leave as contiguous runs.
+//   k_quantize_pack_group  the general path, one wave per group: any group size that is a
+//                          multiple of 32, the groups after the last full tile, and the short
+//                          last group.
+//
+// Rounding arithmetic.  With mn, L = 2^b-1 and inv = L/range of the group, an element maps to
+// v = (x-mn)*inv and is rounded up iff r + 1/2 < frac(v)*256 for its random byte r.  The
+// kernels evaluate the equivalent integer form
+//     code = -floor_shift9( floor((mn-x) * (inv*512)) + 2r + 1 )
+// (floor_shift9 = arithmetic shift right by 9).  (mn-x)*(inv*512) is v*512 negated, exactly,
+// as long as inv*512 does not overflow; groups where it would are handled with two
+// multiplications.  No clamp to L is needed: v <= L*(1+2^-22), so ceil(v*512) <= 512*L + 1.
+#include "daf_device.h"
+#include "daf_internal.h"
+
+namespace {
+
+using namespace daf;
+
+constexpr int kWavesPerBlock = 4;
+constexpr int kThreads = kWave * kWavesPerBlock;
+constexpr float kTwo9 = 512.0f;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct GroupScale {
+  float mn, scale, inv;
+};
+
+// Eq. 1 (left) per group, plus the reciprocal used for the per-element map.
+__device__ __forceinline__ GroupScale group_scale(float mn, float mx, uint32_t b) {
+  GroupScale s;
+  s.mn = mn + 0.0f;                               // a zero minimum is stored as +0
+  const float mxc = mx + 0.0f;
+  const float L = (float)((1u << b) - 1u);
+  const float range = mxc - s.mn;
+  s.scale = range / L;
+  float inv = 0.0f;
+  if (range > 0.0f) {
+    inv = L / range;
+    if (!(inv <= 3.402823466e+38f)) inv = 0.0f;   // reciprocal overflowed
+  }
+  s.inv = inv;
+  return s;
+}
+
+// Negated code of one element.  EXACT2 = false: invs = inv*512 (finite).  EXACT2 = true:
+// invs = inv, and the factor 512 is applied to the rounded product.
+template <bool EXACT2>
+__device__ __forceinline__ int neg_code(float x, float mn, float invs, uint32_t two_r_plus_1) {
+  float w = (mn - x) * invs;
+  if (EXACT2) w = w * kTwo9;
+  return (floor_to_int(w) + (int)two_r_plus_1) >> 9;
+}
+
+// ------------------------------------------------------------------------------------------
+// General path: one wave per group.
+// ------------------------------------------------------------------------------------------
+template <int DT>
+__device__ __forceinline__ float load_elem(const void* x, int64_t i) {
+  if (DT == kF32) return static_cast<const float*>(x)[i];
+  return widen16<DT == kF32 ? kF16 : DT>(static_cast<const uint16_t*>(x)[i]);
+}
+
+template <int DT>
+__global__ __launch_bounds__(kThreads) void k_quantize_pack_group(
+    const void* __restrict__ x, int64_t n, int32_t gs, int64_t g_begin, int64_t g_end,
+    const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, int32_t uniform_bits,
+    uint32_t seed_lo, uint32_t seed_hi, uint32_t* __restrict__ words, float* __restrict__ out_min,
+    float* __restrict__ out_scale) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+  const int64_t n_waves = (int64_t)gridDim.x * kWavesPerBlock;
+  for (int64_t g = g_begin + wave; g < g_end; g += n_waves) {
+    const int64_t lo = g * (int64_t)gs;
+    const int32_t len = (int32_t)((lo + gs <= n) ? gs : (n - lo));
+    const uint32_t b = uniform_bits ? (uint32_t)uniform_bits : (uint32_t)bits[g];
+    const uint32_t woff = uniform_bits ? (uint32_t)(g * (int64_t)((gs * uniform_bits) >> 5)) : off[g];
+
+    float mn = load_elem<DT>(x, lo), mx = mn;              // element 0 exists in every group
+    for (int32_t j = lane; j < len; j += kWave) {
+      const float v = load_elem<DT>(x, lo + j);
+      mn = fminf(mn, v);
+      mx = fmaxf(mx, v);
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+      mn = fminf(mn, __shfl_xor(mn, o));
+      mx = fmaxf(mx, __shfl_xor(mx, o));
+    }
+    const GroupScale s = group_scale(mn, mx, b);
+    if (lane == 0) {
+      out_min[g] = s.mn;
+      out_scale[g] = s.scale;
+    }
+    const uint32_t cpw = 32u / b;                          // codes per word
+    const int32_t n_words = (int32_t)(((int64_t)len * b + 31) >> 5);
+    for (int32_t t = lane; t < n_words; t += kWave) {
+      uint32_t word = 0;
+      uint64_t cur_blk = ~0ull;
+      uint4 rnd = make_uint4(0, 0, 0, 0);
+      for (uint32_t c = 0; c < cpw; ++c) {
+        const int32_t j = (int32_t)(t * cpw + c);
+        if (j >= len) break;
+        const uint64_t i = (uint64_t)(lo + j);
+        const uint64_t blk = i / kElemsPerPhilox;
+        if (blk != cur_blk) {
+          rnd = philox_block(blk, seed_lo, seed_hi);
+          cur_blk = blk;
+        }
+        const uint32_t slot = (uint32_t)(i % kElemsPerPhilox);
+        const uint32_t rw = (slot < 4) ? rnd.x : (slot < 8) ? rnd.y : (slot < 12) ? rnd.z : rnd.w;
+        const uint32_t r = (rw >> (8u * (slot & 3u))) & 0xFFu;
+        const int nc = neg_code<true>(load_elem<DT>(x, lo + j), s.mn, s.inv, 2u * r + 1u);
+        word |= (uint32_t)(-nc) << (32u - b - c * b);
+      }
+      words[woff + t] = word;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Fast path: one wave per tile.
+// ------------------------------------------------------------------------------------------
+// Lane l of load u holds the 16-byte chunk u*64 + l of the tile.  A group spans
+// LPG = 2^LPG_LOG2 neighbouring lanes of one load.
+template <int DT, int LPG_LOG2>
+struct TileShape {
+  static constexpr int kEpl = ElemTraits<DT>::kPerLoad;            // elements per lane per load
+  static constexpr int kLpg = 1 << LPG_LOG2;                       // lanes per group
+  static constexpr int kGpl = kWave / kLpg;                        // groups per load
+  static constexpr int kMaxLoads = 4096 / (kWave * kEpl);          // 16 (fp32) or 8 (16-bit)
+  static constexpr int kLoads = (kMaxLoads * kGpl <= kWave) ? kMaxLoads : kWave / kGpl;
+  static constexpr int kGroups = kLoads * kGpl;                    // groups per tile, <= 64
+  static constexpr int kElems = kLoads * kWave * kEpl;             // 2048 or 4096
+  static constexpr int kGroupSize = kLpg * kEpl;
+  static constexpr int kPhilox = kElems / kElemsPerPhilox / kWave; // Philox calls per lane
+  static_assert(kGroups <= kWave && kPhilox >= 1, "tile shape");
+};
+
+struct alignas(16) GroupInfo {   // what every lane of a group needs for the element map
+  float mn;
+  float invs;                    // inv*512, or inv on the two-multiplication path
+  uint32_t b;
+  uint32_t woff;                 // word offset of the group inside the tile's packed run
+};
+
+template <int DT, int LPG_LOG2>
+struct alignas(16) WaveLds {
+  using S = TileShape<DT, LPG_LOG2>;
+  uint8_t rand_bytes[S::kElems];        // byte e = random byte of tile element e
+  uint32_t stage[S::kElems / 4];        // packed words of the tile (8 bits/element at most)
+  GroupInfo info[kWave];
+  float2 stat[kWave];                   // (min, max) per group, written by the group's last lane
+};
+
+// Codes of one 16-byte chunk, accumulated most significant first: acc0 = elements 0..3,
+// acc1 = elements 4..7 (16-bit inputs only).
+template <int DT, bool EXACT2>
+__device__ __forceinline__ void quantize_chunk(const float (&xf)[ElemTraits<DT>::kPerLoad], float mn,
+                                               float invs, uint32_t b, const uint32_t* rnd,
+                                               uint32_t& acc0, uint32_t& acc1) {
+  constexpr int kEpl = ElemTraits<DT>::kPerLoad;
+  uint32_t nacc[2] = {0u, 0u};
+#pragma unroll
+  for (int q = 0; q < kEpl / 4; ++q) {
+    // 2r+1 for the four random bytes of one dword, as 16-bit fields of two registers
+    const uint32_t rw = rnd[q];
+    const uint32_t even = ((rw & 0x00FF00FFu) << 1) | 0x00010001u;          // bytes 0, 2
+    const uint32_t odd = (((rw >> 8) & 0x00FF00FFu) << 1) | 0x00010001u;    // bytes 1, 3
+    const uint32_t t[4] = {even & 0xFFFFu, odd & 0xFFFFu, even >> 16, odd >> 16};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int nc = neg_code<EXACT2>(xf[q * 4 + e], mn, invs, t[e]);
+      nacc[q] = (nacc[q] << b) + (uint32_t)nc;
+    }
+  }
+  acc0 = 0u - nacc[0];
+  acc1 = (kEpl == 8) ? 0u - nacc[1] : 0u;
+}
+
+// B = 1, 2, 4, 8: every group has that width (offsets are computed).  B = 0: per-group widths
+// from `bits`, offsets from `off`.
+template <int DT, int LPG_LOG2, int B>
+__global__ __launch_bounds__(kThreads) void k_quantize_pack_tile(
+    const u32x4* __restrict__ x, int64_t n_tiles, const uint8_t* __restrict__ bits,
+    const uint32_t* __restrict__ off, uint32_t seed_lo, uint32_t seed_hi,
+    uint32_t* __restrict__ words, float* __restrict__ out_min, float* __restrict__ out_scale) {
+  using S = TileShape<DT, LPG_LOG2>;
+  constexpr int kEpl = S::kEpl;
+  constexpr bool kMixed = (B == 0);
+  constexpr uint32_t kGroupWords32 = S::kGroupSize / 32;      // words per group and bit of width
+  __shared__ WaveLds<DT, LPG_LOG2> lds_all[kWavesPerBlock];
+
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t tile = (int64_t)blockIdx.x * kWavesPerBlock + wave_in_block;
+  if (tile >= n_tiles) return;
+  WaveLds<DT, LPG_LOG2>& lds = lds_all[wave_in_block];
+
+  const int64_t g0 = tile * S::kGroups;                       // first group of the tile
+  const int64_t chunk0 = tile * (S::kLoads * kWave);          // first 16-byte chunk of the tile
+
+  // 1. all global loads of the tile, issued up front
+  uint4 raw[S::kLoads];
+#pragma unroll
+  for (int u = 0; u < S::kLoads; ++u) {
+    const u32x4 v = __builtin_nontemporal_load(&x[chunk0 + u * kWave + lane]);
+    raw[u] = make_uint4(v.x, v.y, v.z, v.w);
+  }
+  uint32_t my_b = (uint32_t)B;
+  uint32_t tile_base;
+  if (kMixed) {
+    my_b = (lane < S::kGroups) ? (uint32_t)bits[g0 + lane] : 1u;
+    tile_base = off[g0];
+  } else {
+    tile_base = (uint32_t)tile * (uint32_t)(S::kGroups * kGroupWords32 * B);
+  }
+
+  // 2. random bytes of the tile (independent of the data; overlaps the loads' latency)
+  {
+    const uint64_t blk0 = (uint64_t)tile * (S::kElems / kElemsPerPhilox);
+    uint4* dst = reinterpret_cast<uint4*>(lds.rand_bytes);
+#pragma unroll
+    for (int m = 0; m < S::kPhilox; ++m)
+      dst[m * kWave + lane] = philox_block(blk0 + (uint64_t)(m * kWave + lane), seed_lo, seed_hi);
+  }
+
+  // 3. per-group min/max: in-lane over the chunk, then across the group's lanes (two loads at
+  //    a time so that four independent DPP chains interleave)
+  float xf[S::kLoads][kEpl];
+  static_assert(S::kLoads % 2 == 0, "loads are reduced in pairs");
+#pragma unroll
+  for (int u = 0; u < S::kLoads; u += 2) {
+    float mn[2], mx[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+#pragma unroll
+      for (int e = 0; e < kEpl; ++e) xf[u + h][e] = chunk_elem<DT>(raw[u + h], e);
+      const float(&v)[kEpl] = xf[u + h];
+      if (kEpl == 4) {
+        mn[h] = vmin(vmin3(v[0], v[1], v[2]), v[3]);
+        mx[h] = vmax(vmax3(v[0], v[1], v[2]), v[3]);
+      } else {
+        mn[h] = vmin(vmin3(vmin3(vmin3(v[0], v[1], v[2]), v[3], v[4 % kEpl]), v[5 % kEpl], v[6 % kEpl]), v[7 % kEpl]);
+        mx[h] = vmax(vmax3(vmax3(vmax3(v[0], v[1], v[2]), v[3], v[4 % kEpl]), v[5 % kEpl], v[6 % kEpl]), v[7 % kEpl]);
+      }
+    }
+    seg_minmax_x2<LPG_LOG2>(mn[0], mx[0], mn[1], mx[1]);
+    if ((lane & (S::kLpg - 1)) == S::kLpg - 1) {
+      lds.stat[u * S::kGpl + (lane >> LPG_LOG2)] = make_float2(mn[0], mx[0]);
+      lds.stat[(u + 1) * S::kGpl + (lane >> LPG_LOG2)] = make_float2(mn[1], mx[1]);
+    }
+  }
+  wave_lds_sync();
+
+  // 4. lane g of the wave finishes group g of the tile: scale, reciprocal, word offset
+  bool need_exact2;
+  uint32_t tile_words;
+  {
+    const float2 st = lds.stat[lane & (S::kGroups - 1)];
+    const GroupScale s = group_scale(st.x, st.y, my_b);
+    const float invs = s.inv * kTwo9;
+    need_exact2 = __builtin_amdgcn_ballot_w64(!(invs <= 3.402823466e+38f) && lane < S::kGroups) != 0ull;
+    uint32_t woff;
+    if (kMixed) {
+      const uint32_t w = (lane < S::kGroups) ? kGroupWords32 * my_b : 0u;
+      const uint32_t incl = wave_inclusive_sum(w);
+      tile_words = (uint32_t)__builtin_amdgcn_readlane((int)incl, kWave - 1);
+      woff = incl - w;
+    } else {
+      tile_words = S::kGroups * kGroupWords32 * B;
+      woff = (uint32_t)lane * (kGroupWords32 * B);
+    }
+    if (lane < S::kGroups) {
+      out_min[g0 + lane] = s.mn;
+      out_scale[g0 + lane] = s.scale;
+      GroupInfo gi;
+      gi.mn = s.mn;
+      gi.invs = need_exact2 ? s.inv : invs;
+      gi.b = my_b;
+      gi.woff = woff;
+      lds.info[lane] = gi;
+    }
+  }
+  wave_lds_sync();
+
+  // 5. quantize every chunk and drop its bits at their place in the staged word run.
+  //    The staged run is a big-endian bit string per word: byte k of the string lives at
+  //    byte address k^3, halfword k at byte address 2k^2.
+  const int lig = lane & (S::kLpg - 1);
+  uint8_t* stage8 = reinterpret_cast<uint8_t*>(lds.stage);
+#pragma unroll
+  for (int u = 0; u < S::kLoads; ++u) {
+    const int grp = u * S::kGpl + (lane >> LPG_LOG2);
+    float g_mn, g_invs;
+    uint32_t b, woff;
+    if (kMixed) {
+      const GroupInfo gi = lds.info[grp];
+      g_mn = gi.mn; g_invs = gi.invs; b = gi.b; woff = gi.woff;
+    } else {
+      const float2 mi = *reinterpret_cast<const float2*>(&lds.info[grp]);
+      g_mn = mi.x; g_invs = mi.y; b = B; woff = (uint32_t)grp * (kGroupWords32 * B);
+    }
+    uint32_t rnd[kEpl / 4];
+    if (kEpl == 4) {
+      rnd[0] = reinterpret_cast<const uint32_t*>(lds.rand_bytes)[u * kWave + lane];
+    } else {
+      const uint2 r2 = reinterpret_cast<const uint2*>(lds.rand_bytes)[u * kWave + lane];
+      rnd[0] = r2.x;
+      rnd[kEpl / 4 - 1] = r2.y;
+    }
+    uint32_t acc0, acc1;
+    if (need_exact2) quantize_chunk<DT, true>(xf[u], g_mn, g_invs, b, rnd, acc0, acc1);
+    else             quantize_chunk<DT, false>(xf[u], g_mn, g_invs, b, rnd, acc0, acc1);
+
+    const uint32_t pbits = (uint32_t)kEpl * b;                    // bits this lane contributes
+    const uint32_t bitpos = (uint32_t)lig * pbits;                // inside the group's bit string
+    const uint32_t byte_pos = woff * 4u + (bitpos >> 3);          // logical byte of the staged run
+    if (kEpl == 4) {
+      if (b == 1u) {           // 4 bits per lane: the even lane takes its odd neighbour's nibble
+        const uint32_t nb = dpp<kDppXor1>(acc0, acc0);
+        if ((lane & 1) == 0) stage8[byte_pos ^ 3u] = (uint8_t)((acc0 << 4) | nb);
+      } else if (b == 2u) {
+        stage8[byte_pos ^ 3u] = (uint8_t)acc0;
+      } else if (b == 4u) {
+        *reinterpret_cast<uint16_t*>(stage8 + (byte_pos ^ 2u)) = (uint16_t)acc0;
+      } else {
+        *reinterpret_cast<uint32_t*>(stage8 + byte_pos) = acc0;
+      }
+    } else {
+      const uint32_t both = (acc0 << ((4u * b) & 31u)) | acc1;    // valid for b <= 4
+      if (b == 1u) {
+        stage8[byte_pos ^ 3u] = (uint8_t)both;
+      } else if (b == 2u) {
+        *reinterpret_cast<uint16_t*>(stage8 + (byte_pos ^ 2u)) = (uint16_t)both;
+      } else if (b == 4u) {
+        *reinterpret_cast<uint32_t*>(stage8 + byte_pos) = both;
+      } else {
+        *reinterpret_cast<uint2*>(stage8 + byte_pos) = make_uint2(acc0, acc1);
+      }
+    }
+  }
+  wave_lds_sync();
+
+  // 6. the tile's words are one contiguous run in the packed buffer
+  uint32_t* dst = words + tile_base;
+  for (uint32_t i = lane; i < tile_words; i += kWave) dst[i] = lds.stage[i];
+}
+
+template <int DT, int LPG_LOG2>
+hipError_t launch_tile(const daf_plan_t* p, const void* x, int64_t n_tiles, uint32_t seed_lo, uint32_t seed_hi,
+                       uint32_t* out_words, float* out_min, float* out_scale, hipStream_t stream) {
+  const unsigned blocks = (unsigned)((n_tiles + kWavesPerBlock - 1) / kWavesPerBlock);
+#define DAF_LAUNCH(BITS)                                                                                  \
+  hipLaunchKernelGGL((k_quantize_pack_tile<DT, LPG_LOG2, BITS>), dim3(blocks), dim3(kThreads), 0, stream, \
+                     static_cast<const u32x4*>(x), n_tiles, p->d_bits, p->d_off, seed_lo, seed_hi,        \
+                     out_words, out_min, out_scale)
+  switch (p->uniform_bits) {
+    case 0: DAF_LAUNCH(0); break;
+    case 1: DAF_LAUNCH(1); break;
+    case 2: DAF_LAUNCH(2); break;
+    case 4: DAF_LAUNCH(4); break;
+    case 8: DAF_LAUNCH(8); break;
+    default: return hipErrorInvalidValue;
+  }
+#undef DAF_LAUNCH
+  return hipGetLastError();
+}
+
+template <int DT>
+hipError_t launch_dtype(const daf_plan_t* p, const void* x, uint64_t seed, uint32_t* out_words, float* out_min,
+                        float* out_scale, hipStream_t stream) {
+  const uint32_t seed_lo = (uint32_t)seed, seed_hi = (uint32_t)(seed >> 32);
+  constexpr int kEpl = ElemTraits<DT>::kPerLoad;
+  const int64_t full_groups = p->n / p->group_size;
+  int64_t fast_groups = 0;
+
+  // fast path: groups of 4..64 lanes (a power of two), whole tiles only
+  const int32_t lpg = p->group_size / kEpl;
+  if (p->group_size % kEpl == 0 && lpg >= 4 && lpg <= 64 && (lpg & (lpg - 1)) == 0) {
+    int64_t n_tiles = 0;
+    hipError_t e = hipSuccess;
+#define DAF_CASE(LOG2)                                                                                   \
+  case (1 << LOG2):                                                                                      \
+    n_tiles = full_groups / TileShape<DT, LOG2>::kGroups;                                                \
+    fast_groups = n_tiles * TileShape<DT, LOG2>::kGroups;                                                \
+    if (n_tiles > 0) e = launch_tile<DT, LOG2>(p, x, n_tiles, seed_lo, seed_hi, out_words, out_min,      \
+                                               out_scale, stream);                                       \
+    break;
+    switch (lpg) {
+      DAF_CASE(2) DAF_CASE(3) DAF_CASE(4) DAF_CASE(5) DAF_CASE(6)
+      default: break;
+    }
+#undef DAF_CASE
+    if (e != hipSuccess) return e;
+  }
+
+  // general path for everything the tiles did not cover
+  const int64_t rest = p->num_groups - fast_groups;
+  if (rest > 0) {
+    int64_t blocks = (rest + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL((k_quantize_pack_group<DT>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, x, p->n,
+                       p->group_size, fast_groups, p->num_groups, p->d_bits, p->d_off, p->uniform_bits,
+                       seed_lo, seed_hi, out_words, out_min, out_scale);
+    return hipGetLastError();
+  }
+  return hipSuccess;
+}
+
+}  // namespace
+
+hipError_t daf_launch_quantize_pack(const daf_plan_t* plan, const void* x, int dtype, uint64_t seed,
+                                    uint32_t* out_words, float* out_min, float* out_scale,
+                                    hipStream_t stream) {
+  switch (dtype) {
+    case daf::kF32:  return launch_dtype<daf::kF32>(plan, x, seed, out_words, out_min, out_scale, stream);
+    case daf::kF16:  return launch_dtype<daf::kF16>(plan, x, seed, out_words, out_min, out_scale, stream);
+    case daf::kBF16: return launch_dtype<daf::kBF16>(plan, x, seed, out_words, out_min, out_scale, stream);
+    default: return hipErrorInvalidValue;
+  }
+}

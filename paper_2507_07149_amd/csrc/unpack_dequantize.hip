@@ -1,0 +1,152 @@
+// Backward-pass side: unpack the codes (the extraction rule of Algorithm 2, for the group's
+// own width) and dequantize them to the original precision, xhat = fma(code, scale, min)
+// (inverse of Eq. 1; paper Sec. 2.2).  Two kernels:
+//
+//   k_unpack_dequantize_chunk  the fast path.  A thread produces 16 bytes of output at a time
+//                              (4 fp32 or 8 16-bit elements).  Such a chunk never straddles a
+//                              group and its bits never straddle a word pair, so it needs one
+//                              (or, at 8 bits and 16-bit output, two) packed words.  Covers all
+//                              full groups of any group size.
+//   k_unpack_dequantize_group  one wave per group, element by element: the short last group.
+#include "daf_device.h"
+#include "daf_internal.h"
+
+namespace {
+
+using namespace daf;
+
+constexpr int kThreads = 256;
+constexpr int kChunksPerThread = 4;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <int DT>
+__device__ __forceinline__ void store_elem(void* out, int64_t i, float v) {
+  if (DT == kF32) static_cast<float*>(out)[i] = v;
+  else static_cast<uint16_t*>(out)[i] = (uint16_t)narrow16<DT == kF32 ? kF16 : DT>(v);
+}
+
+template <int DT>
+__global__ __launch_bounds__(kThreads) void k_unpack_dequantize_group(
+    const uint32_t* __restrict__ words, const float* __restrict__ mn, const float* __restrict__ scale,
+    const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, int32_t uniform_bits, int64_t n,
+    int32_t gs, int64_t g_begin, int64_t g_end, void* __restrict__ out) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t wave = (int64_t)blockIdx.x * (kThreads / kWave) + (threadIdx.x >> 6);
+  const int64_t n_waves = (int64_t)gridDim.x * (kThreads / kWave);
+  for (int64_t g = g_begin + wave; g < g_end; g += n_waves) {
+    const int64_t lo = g * (int64_t)gs;
+    const int32_t len = (int32_t)((lo + gs <= n) ? gs : (n - lo));
+    const uint32_t b = uniform_bits ? (uint32_t)uniform_bits : (uint32_t)bits[g];
+    const uint32_t woff = uniform_bits ? (uint32_t)(g * (int64_t)((gs * uniform_bits) >> 5)) : off[g];
+    const float m = mn[g], s = scale[g];
+    const uint32_t levels = (1u << b) - 1u;
+    for (int32_t j = lane; j < len; j += kWave) {
+      const uint32_t bitpos = (uint32_t)j * b;
+      const uint32_t w = words[woff + (bitpos >> 5)];
+      const uint32_t code = (w >> (32u - b - (bitpos & 31u))) & levels;
+      store_elem<DT>(out, lo + j, __builtin_fmaf((float)code, s, m));
+    }
+  }
+}
+
+template <int DT, bool MIXED>
+__global__ __launch_bounds__(kThreads) void k_unpack_dequantize_chunk(
+    const uint32_t* __restrict__ words, const float* __restrict__ mn, const float* __restrict__ scale,
+    const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, int32_t uniform_bits,
+    int64_t n_chunks, int32_t gs, int32_t gs_shift, u32x4* __restrict__ out) {
+  constexpr int kEpl = ElemTraits<DT>::kPerLoad;
+  const int64_t base = (int64_t)blockIdx.x * (kThreads * kChunksPerThread) + threadIdx.x;
+#pragma unroll
+  for (int k = 0; k < kChunksPerThread; ++k) {
+    const int64_t c = base + (int64_t)k * kThreads;
+    if (c >= n_chunks) break;
+    const int64_t e0 = c * kEpl;                                   // first element of the chunk
+    const int64_t g = (gs_shift >= 0) ? (e0 >> gs_shift) : (e0 / gs);
+    const uint32_t j0 = (uint32_t)(e0 - g * (int64_t)gs);          // position inside the group
+    uint32_t b, woff;
+    if (MIXED) {
+      b = bits[g];
+      woff = off[g];
+    } else {
+      b = (uint32_t)uniform_bits;
+      woff = (uint32_t)g * ((uint32_t)(gs >> 5) * b);
+    }
+    const float m = mn[g], s = scale[g];
+    const uint32_t bitpos = j0 * b;
+    const uint32_t* wp = words + woff + (bitpos >> 5);
+    const uint32_t levels = (1u << b) - 1u;
+    float v[kEpl];
+    if (kEpl == 8 && b == 8u) {
+      const uint32_t w0 = wp[0], w1 = wp[1];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        v[e] = __builtin_fmaf((float)((w0 >> (24 - 8 * e)) & 0xFFu), s, m);
+        v[kEpl - 4 + e] = __builtin_fmaf((float)((w1 >> (24 - 8 * e)) & 0xFFu), s, m);
+      }
+    } else {
+      const uint32_t pbits = (uint32_t)kEpl * b;                   // <= 32 here
+      const uint32_t field = wp[0] >> (32u - pbits - (bitpos & 31u));
+#pragma unroll
+      for (int e = 0; e < kEpl; ++e) {
+        const uint32_t code = (field >> ((uint32_t)(kEpl - 1 - e) * b)) & levels;
+        v[e] = __builtin_fmaf((float)code, s, m);
+      }
+    }
+    u32x4 o;
+    if (DT == kF32) {
+      o = (u32x4){f2u(v[0]), f2u(v[1]), f2u(v[2]), f2u(v[3])};
+    } else {
+      constexpr int D = (DT == kF32) ? kF16 : DT;
+      uint32_t h[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        h[q] = narrow16<D>(v[(2 * q) % kEpl]) | (narrow16<D>(v[(2 * q + 1) % kEpl]) << 16);
+      o = (u32x4){h[0], h[1], h[2], h[3]};
+    }
+    __builtin_nontemporal_store(o, &out[c]);
+  }
+}
+
+template <int DT>
+hipError_t launch_dtype(const daf_plan_t* p, const uint32_t* words, const float* mn, const float* scale,
+                        const uint8_t* d_bits, void* out_x, hipStream_t stream) {
+  constexpr int kEpl = ElemTraits<DT>::kPerLoad;
+  const int64_t full_groups = p->n / p->group_size;
+  const int64_t n_chunks = full_groups * (p->group_size / kEpl);
+  int32_t gs_shift = -1;
+  if ((p->group_size & (p->group_size - 1)) == 0) gs_shift = __builtin_ctz((unsigned)p->group_size);
+  if (n_chunks > 0) {
+    const int64_t per_block = (int64_t)kThreads * kChunksPerThread;
+    const unsigned blocks = (unsigned)((n_chunks + per_block - 1) / per_block);
+    if (p->uniform_bits)
+      hipLaunchKernelGGL((k_unpack_dequantize_chunk<DT, false>), dim3(blocks), dim3(kThreads), 0, stream, words,
+                         mn, scale, nullptr, nullptr, p->uniform_bits, n_chunks, p->group_size, gs_shift,
+                         static_cast<u32x4*>(out_x));
+    else
+      hipLaunchKernelGGL((k_unpack_dequantize_chunk<DT, true>), dim3(blocks), dim3(kThreads), 0, stream, words,
+                         mn, scale, d_bits, p->d_off, 0, n_chunks, p->group_size, gs_shift,
+                         static_cast<u32x4*>(out_x));
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  if (full_groups < p->num_groups) {
+    hipLaunchKernelGGL((k_unpack_dequantize_group<DT>), dim3(1), dim3(kThreads), 0, stream, words, mn, scale,
+                       d_bits, p->d_off, p->uniform_bits, p->n, p->group_size, full_groups, p->num_groups,
+                       out_x);
+    return hipGetLastError();
+  }
+  return hipSuccess;
+}
+
+}  // namespace
+
+hipError_t daf_launch_unpack_dequantize(const daf_plan_t* plan, const uint32_t* words, const float* mn,
+                                        const float* scale, const uint8_t* d_bits, void* out_x, int dtype,
+                                        hipStream_t stream) {
+  switch (dtype) {
+    case daf::kF32:  return launch_dtype<daf::kF32>(plan, words, mn, scale, d_bits, out_x, stream);
+    case daf::kF16:  return launch_dtype<daf::kF16>(plan, words, mn, scale, d_bits, out_x, stream);
+    case daf::kBF16: return launch_dtype<daf::kBF16>(plan, words, mn, scale, d_bits, out_x, stream);
+    default: return hipErrorInvalidValue;
+  }
+}

@@ -1,0 +1,128 @@
+"""Helpers for the GPU parity tests: run a workload through libdaf (C ABI via the ctypes
+binding) and through the CPU oracle, and compare."""
+import numpy as np
+import torch
+
+import paper_2507_07149_amd as daf
+from daf_inputs import Workload, to_numpy_bits
+from oracle import daf_oracle as orc
+
+
+def u32(t: torch.Tensor) -> np.ndarray:
+    return t.cpu().numpy().view(np.uint32)
+
+
+class HipResult:
+    def __init__(self, plan, words, mn, scale, xhat, d_bits):
+        self.plan, self.words, self.mn, self.scale, self.xhat, self.d_bits = plan, words, mn, scale, xhat, d_bits
+
+
+def run_hip(w: Workload, dequantize: bool = True) -> HipResult:
+    dev = torch.device("cuda:0")
+    x = w.x.contiguous().reshape(-1).to(dev)
+    if w.bits.size == 1:
+        plan = daf.daf_plan(tuple(w.x.shape), w.group_size, int(w.bits[0]))
+        d_bits = None
+    else:
+        d_bits = torch.from_numpy(w.bits).to(dev)
+        plan = daf.daf_plan(tuple(w.x.shape), w.group_size, d_bits)
+    G = plan.num_groups
+    words = torch.full((max(plan.packed_words, 1),), -1, dtype=torch.int32, device=dev)[: plan.packed_words]
+    mn = torch.full((G,), float("nan"), dtype=torch.float32, device=dev)
+    sc = torch.full((G,), float("nan"), dtype=torch.float32, device=dev)
+    daf.daf_quantize_pack(plan, x, w.seed, words, mn, sc)
+    xhat = None
+    if dequantize:
+        xhat = torch.empty_like(x)
+        xhat.view(torch.int16 if x.element_size() == 2 else torch.int32).fill_(-1 if x.element_size() == 4 else 0x7FFF)
+        daf.daf_unpack_dequantize(plan, words, mn, sc, xhat)
+    torch.cuda.synchronize()
+    return HipResult(plan, words, mn, sc, xhat, d_bits)
+
+
+def first_diff(a: np.ndarray, b: np.ndarray):
+    d = np.nonzero(a != b)[0]
+    return None if d.size == 0 else int(d[0])
+
+
+def assert_full_parity(w: Workload, res: HipResult):
+    """Element-by-element comparison against the oracle on the whole tensor."""
+    xb = to_numpy_bits(w.x)
+    n, gs = w.numel, w.group_size
+    ow, omn, osc, ocodes = orc.quantize_pack(xb, w.dtype, gs, w.bits, w.seed, want_codes=True)
+    off, total = orc.plan(n, gs, w.bits)
+    assert res.plan.packed_words == total
+    assert res.plan.num_groups == off.size
+    assert np.array_equal(res.plan.offsets().numpy().view(np.uint32), off)
+    gmn, gsc, gw = u32(res.mn), u32(res.scale), u32(res.words)
+    d = first_diff(gmn, omn.view(np.uint32))
+    assert d is None, f"min differs first at group {d}: hip {res.mn[d].item()!r} oracle {omn[d]!r}"
+    d = first_diff(gsc, osc.view(np.uint32))
+    assert d is None, f"scale differs first at group {d}: hip {res.scale[d].item()!r} oracle {osc[d]!r}"
+    d = first_diff(gw, ow)
+    if d is not None:
+        g = int(np.searchsorted(off, d, side="right") - 1)
+        raise AssertionError(f"packed word {d} differs (group {g}, bits "
+                             f"{int(w.bits[0] if w.bits.size == 1 else w.bits[g])}): hip {gw[d]:08x} oracle {ow[d]:08x}")
+    if res.xhat is not None:
+        oxh, codes_back = orc.unpack_dequantize(ow, omn, osc, w.bits, n, gs, w.dtype, want_codes=True)
+        assert np.array_equal(codes_back, ocodes)
+        gx = to_numpy_bits(res.xhat.cpu())
+        # bar: 1e-6 of the group range for fp32, one output ulp for 16-bit; bit-equality expected
+        if w.dtype == orc.F32:
+            rng = np.repeat(osc.astype(np.float64) * ((1 << np.broadcast_to(w.bits, off.shape).astype(np.int64)) - 1), gs)[:n]
+            assert np.all(np.abs(gx.astype(np.float64) - oxh.astype(np.float64)) <= 1e-6 * rng)
+        else:
+            assert np.all(np.abs(gx.astype(np.int32) - oxh.astype(np.int32)) <= 1)
+        d = first_diff(gx.view(np.uint32 if w.dtype == orc.F32 else np.uint16),
+                       oxh.view(np.uint32 if w.dtype == orc.F32 else np.uint16))
+        assert d is None, f"dequantized element {d} not bit-identical: hip {gx[d]!r} oracle {oxh[d]!r}"
+
+
+def assert_sampled_parity(w: Workload, res: HipResult, n_samples: int = 1500, seed: int = 0):
+    """Full-size workloads: compare sampled groups (plus the first and last ones) with the
+    oracle computed group by group, and check global properties on the GPU."""
+    xb = to_numpy_bits(w.x)
+    n, gs = w.numel, w.group_size
+    off, total = orc.plan(n, gs, w.bits)
+    G = off.size
+    assert res.plan.packed_words == total and res.plan.num_groups == G
+    assert np.array_equal(res.plan.offsets().numpy().view(np.uint32), off)
+    rng = np.random.default_rng(seed)
+    picks = np.unique(np.concatenate([np.arange(min(G, 130)), np.arange(max(0, G - 130), G),
+                                      rng.integers(0, G, n_samples)]))
+    gw, gmn, gsc = u32(res.words), res.mn.cpu().numpy(), res.scale.cpu().numpy()
+    gx = to_numpy_bits(res.xhat.cpu()) if res.xhat is not None else None
+    ow = np.zeros(total, dtype=np.uint32)
+    omn = np.zeros(G, dtype=np.float32)
+    osc = np.zeros(G, dtype=np.float32)
+    oxh = np.zeros(n, dtype=xb.dtype)
+    bits_full = w.bits
+    for g in picks:
+        g = int(g)
+        orc.quantize_pack_range(xb, w.dtype, gs, bits_full, off, w.seed, g, g + 1, ow, omn, osc)
+        b = int(bits_full[0] if bits_full.size == 1 else bits_full[g])
+        lo, hi = g * gs, min((g + 1) * gs, n)
+        nw = ((hi - lo) * b + 31) // 32
+        sl = slice(int(off[g]), int(off[g]) + nw)
+        assert gmn.view(np.uint32)[g] == omn.view(np.uint32)[g], f"min of group {g}"
+        assert gsc.view(np.uint32)[g] == osc.view(np.uint32)[g], f"scale of group {g}"
+        assert np.array_equal(gw[sl], ow[sl]), f"words of group {g} (bits {b})"
+        if gx is not None:
+            orc.unpack_dequantize_range(ow, omn, osc, bits_full, off, n, gs, g, g + 1, oxh, w.dtype)
+            assert np.array_equal(gx[lo:hi], oxh[lo:hi]), f"dequantized values of group {g}"
+    # properties that hold at any size, evaluated on the device over every element
+    if res.xhat is not None:
+        full = (n // gs) * gs
+        xs = w.x.reshape(-1)[:full].to("cuda:0").float().reshape(-1, gs)
+        xh = res.xhat[:full].float().reshape(-1, gs)
+        sc = res.scale[: full // gs, None]
+        mnv = res.mn[: full // gs, None]
+        assert torch.equal(mnv[:, 0], xs.amin(dim=1) + 0.0)
+        # |x - xhat| <= scale, plus binary32 slack, plus the rounding of xhat to a 16-bit dtype
+        # (relative 2^-9 for bf16 / 2^-11 for fp16 of |xhat| <= |x| + scale; fp16 subnormal step 2^-24)
+        ulp16 = {orc.F32: 0.0, orc.BF16: 2.0 ** -8, orc.F16: 2.0 ** -10}[w.dtype]
+        abs16 = 2.0 ** -24 if w.dtype == orc.F16 else 0.0
+        bound = (sc * (1 + 2.0 ** -20) + (xs.amax(dim=1, keepdim=True) - mnv) * 2.0 ** -22
+                 + (xs.abs() + sc) * ulp16 + abs16)
+        assert bool(((xs - xh).abs() <= bound).all())

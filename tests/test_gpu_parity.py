@@ -1,0 +1,196 @@
+"""GPU parity: libdaf (through the C ABI) against the CPU oracle, bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+from daf_inputs import BF16, F16, F32, Workload, make_config, torch_dtype
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def H():
+    from tests import hip_harness
+    assert torch.cuda.is_available(), "GPU tests need cuda:0"
+    return hip_harness
+
+
+def _workload(dtype, n, gs, bits, seed, scale=1.0, rng_seed=0):
+    g = torch.Generator().manual_seed(rng_seed)
+    x = (torch.randn(n, generator=g) * scale).to(torch_dtype(dtype))
+    G = (n + gs - 1) // gs
+    if bits == "mixed":
+        b = np.random.default_rng(rng_seed).choice([1, 2, 4, 8], G).astype(np.uint8)
+    else:
+        b = np.array([bits], dtype=np.uint8)
+    return Workload(f"dt{dtype}_n{n}_g{gs}_b{bits}", x, dtype, gs, b, seed)
+
+
+# reduced instances of the five configurations: several tiles plus a tail that the tile
+# kernel does not cover; the oracle finishes each in seconds
+@pytest.mark.parametrize("cfg,scale", [(1, 1.0), (2, 3 / 64), (3, 3 / 32), (4, 1 / 64), (5, 1 / 16)])
+def test_reduced_configs_full_parity(H, cfg, scale):
+    for w in make_config(cfg, scale):
+        print("case", w.name, tuple(w.x.shape), flush=True)
+        H.assert_full_parity(w, H.run_hip(w))
+
+
+@pytest.mark.parametrize("dtype", [F32, F16, BF16])
+@pytest.mark.parametrize("gs", [32, 64, 96, 128, 256, 512, 1024])
+@pytest.mark.parametrize("bits", [1, 2, 4, 8, "mixed"])
+def test_group_size_matrix(H, dtype, gs, bits):
+    # ~2.5 tiles worth of groups plus a ragged tail
+    n = 4096 * 2 + gs * 3 + 17
+    w = _workload(dtype, n, gs, bits, seed=0xABCDEF0123456789 % (1 << 64), rng_seed=gs + 7 * dtype)
+    print("case", w.name, flush=True)
+    H.assert_full_parity(w, H.run_hip(w))
+
+
+@pytest.mark.parametrize("dtype", [F32, F16, BF16])
+@pytest.mark.parametrize("n", [1, 5, 31, 32, 33, 255, 256, 4095, 4096, 4097, 12288])
+def test_small_and_ragged_sizes(H, dtype, n):
+    for gs, bits in ((32, 4), (128, 2), (256, "mixed")):
+        w = _workload(dtype, n, gs, bits, seed=n, rng_seed=n)
+        print("case", w.name, flush=True)
+        H.assert_full_parity(w, H.run_hip(w))
+
+
+@pytest.mark.parametrize("dtype", [F32, F16, BF16])
+def test_degenerate_groups(H, dtype):
+    """Constant groups, all-zero groups with mixed signs of zero, subnormal ranges, ranges so
+    small that the reciprocal overflows, huge magnitudes."""
+    gs = 128 if dtype == F32 else 64
+    n = 4096 * 3
+    g = torch.Generator().manual_seed(5)
+    x = torch.randn(n, generator=g)
+    x[0:gs] = 1.75
+    x[gs:2 * gs] = 0.0
+    x[gs:2 * gs:2] = -0.0
+    x[2 * gs:3 * gs] = -3.0
+    x[3 * gs] = 1e-30
+    x[3 * gs + 1:4 * gs] = 0.0
+    if dtype == F32:
+        x[4 * gs:5 * gs] = torch.arange(gs) * 1.4e-45             # subnormal grid
+        x[5 * gs:6 * gs] = torch.randn(gs, generator=g) * 1e-37   # reciprocal of range*512 overflows
+        x[6 * gs:7 * gs] = torch.randn(gs, generator=g) * 1e37
+        x[4096:4096 + gs] = torch.randn(gs, generator=g) * 3e-38  # a second tile with a tiny group
+    elif dtype == F16:
+        x[4 * gs:5 * gs] = torch.arange(gs) * 5.96e-8             # fp16 subnormals
+        x[5 * gs:6 * gs] = torch.randn(gs, generator=g) * 1e4
+    else:
+        x[4 * gs:5 * gs] = torch.randn(gs, generator=g) * 1e-38
+        x[5 * gs:6 * gs] = torch.randn(gs, generator=g) * 1e37   # max - min must stay finite
+    x = x.to(torch_dtype(dtype))
+    for bits in (1, 2, 8, "mixed"):
+        G = n // gs
+        b = (np.random.default_rng(1).choice([1, 2, 4, 8], G).astype(np.uint8) if bits == "mixed"
+             else np.array([bits], np.uint8))
+        w = Workload(f"degenerate_dt{dtype}_b{bits}", x, dtype, gs, b, 11)
+        print("case", w.name, flush=True)
+        H.assert_full_parity(w, H.run_hip(w))
+
+
+# full-size configurations, in the launch configuration bench.py times: sampled groups against
+# the oracle (which computes them one by one), plus properties evaluated over every element
+@pytest.mark.timeout(400)
+@pytest.mark.parametrize("cfg", [2, 3, 5])
+def test_full_size_configs_sampled(H, cfg):
+    (w,) = make_config(cfg)
+    print("case", w.name, tuple(w.x.shape), flush=True)
+    res = H.run_hip(w)
+    print("ran; checking", flush=True)
+    H.assert_sampled_parity(w, res, n_samples=1200, seed=cfg)
+
+
+@pytest.mark.timeout(400)
+def test_full_size_resnet18_step_sampled(H):
+    """All 17 saved activations of the batch-256 step: quantize in forward order, dequantize in
+    reverse order with every packed result alive, then sampled comparison per tensor."""
+    import paper_2507_07149_amd as daf
+    ws = make_config(4)
+    assert len(ws) == 17 and sum(w.numel for w in ws) == 590_872_576
+    dev = "cuda:0"
+    state = []
+    for w in ws:
+        x = w.x.reshape(-1).to(dev)
+        plan = daf.daf_plan(tuple(w.x.shape), w.group_size, int(w.bits[0]))
+        words = torch.empty(plan.packed_words, dtype=torch.int32, device=dev)
+        mn = torch.empty(plan.num_groups, device=dev)
+        sc = torch.empty(plan.num_groups, device=dev)
+        daf.daf_quantize_pack(plan, x, w.seed, words, mn, sc)
+        state.append((plan, x, words, mn, sc))
+    for t in reversed(range(17)):
+        plan, x, words, mn, sc = state[t]
+        xh = torch.empty_like(x)
+        daf.daf_unpack_dequantize(plan, words, mn, sc, xh)
+        torch.cuda.synchronize()
+        print("tensor", t, flush=True)
+        H.assert_sampled_parity(ws[t], H.HipResult(plan, words, mn, sc, xh, None), n_samples=150, seed=t)
+        state[t] = None
+        del x, xh
+
+
+def test_seed_changes_codes_and_is_reproducible(H):
+    w = _workload(F32, 4096 * 4, 256, 2, seed=1)
+    a = H.u32(H.run_hip(w).words)
+    b = H.u32(H.run_hip(w).words)
+    w2 = Workload(w.name, w.x, w.dtype, w.group_size, w.bits, seed=2)
+    c = H.u32(H.run_hip(w2).words)
+    assert np.array_equal(a, b) and not np.array_equal(a, c)
+    # high seed word is part of the key
+    w3 = Workload(w.name, w.x, w.dtype, w.group_size, w.bits, seed=1 + (1 << 32))
+    assert not np.array_equal(a, H.u32(H.run_hip(w3).words))
+    H.assert_full_parity(w3, H.run_hip(w3))
+
+
+def test_plan_scan_large_mixed(H):
+    """Offsets of 5.6 M groups (the size of the LLM configuration) against the oracle's scan."""
+    import paper_2507_07149_amd as daf
+    from oracle import daf_oracle as orc
+    G, gs = 5_636_096, 64
+    bits = np.random.default_rng(3).choice([2, 4, 8], G).astype(np.uint8)
+    n = G * gs - 13                                             # short last group
+    plan = daf.daf_plan((n,), gs, torch.from_numpy(bits).cuda())
+    off, total = orc.plan(n, gs, bits)
+    assert plan.packed_words == total
+    assert np.array_equal(plan.offsets().numpy().view(np.uint32), off)
+
+
+def test_abi_errors_on_device(H):
+    import paper_2507_07149_amd as daf
+    dev = "cuda:0"
+    bad_bits = torch.tensor([2, 4, 3, 8], dtype=torch.uint8, device=dev)
+    with pytest.raises(daf.DafError) as e:
+        daf.daf_plan((4 * 64,), 64, bad_bits)
+    assert e.value.status == -1
+    plan = daf.daf_plan((1024,), 64, 2)
+    x = torch.zeros(1024 + 4, device=dev)
+    words = torch.zeros(plan.packed_words, dtype=torch.int32, device=dev)
+    mn = torch.zeros(plan.num_groups, device=dev)
+    sc = torch.zeros(plan.num_groups, device=dev)
+    with pytest.raises(daf.DafError) as e:                      # x not 16-byte aligned
+        daf.daf_quantize_pack(plan, x[1:1025], 0, words, mn, sc)
+    assert e.value.status == -1
+    with pytest.raises(daf.DafError):                           # bits given for a uniform plan
+        daf.daf_unpack_dequantize(plan, words, mn, sc, x[:1024], bits=bad_bits)
+    daf.daf_quantize_pack(plan, x[:1024], 0, words, mn, sc)     # and the good call still works
+    torch.cuda.synchronize()
+    assert int(words.abs().sum()) == 0
+
+
+def test_runs_on_a_side_stream(H):
+    import paper_2507_07149_amd as daf
+    w = _workload(F16, 4096 * 6 + 64, 128, "mixed", seed=9)
+    ref = H.run_hip(w)
+    s = torch.cuda.Stream()
+    x = w.x.cuda()
+    words = torch.empty_like(ref.words)
+    mn = torch.empty_like(ref.mn)
+    sc = torch.empty_like(ref.scale)
+    xh = torch.empty_like(x)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        daf.daf_quantize_pack(ref.plan, x, w.seed, words, mn, sc, stream=s)
+        daf.daf_unpack_dequantize(ref.plan, words, mn, sc, xh, stream=s)
+    s.synchronize()
+    assert torch.equal(words, ref.words) and torch.equal(mn, ref.mn) and torch.equal(xh, ref.xhat)
