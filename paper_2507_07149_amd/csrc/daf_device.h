@@ -105,6 +105,106 @@ __device__ __forceinline__ void seg_minmax_x2(float& a, float& b, float& c, floa
 #undef DAF_MM4_ASM
 #undef DAF_MM4
 
+// ---- transposed reduction --------------------------------------------------------------
+// Reducing 16 registers (one per load) over the lanes of a wave one register at a time costs
+// one DPP instruction per register and level.  Reducing them together is cheaper: at a level
+// that pairs lane L with lane L^k, two registers A and B are merged into one whose lanes with
+// bit k clear hold A reduced over {L, L^k} and whose lanes with bit k set hold B reduced the
+// same way, so every level halves the number of live registers.
+//
+// Levels 4 and 8 (inside a row of 16 lanes): two DPP instructions with complementary bank
+// masks write the two lane sets of the merged register.
+#define DAF_BANK_PAIR(OP, O, A, B, CTRL_LO, MASK_LO, CTRL_HI, MASK_HI)                          \
+  OP " " O ", " A ", " A " " CTRL_LO " row_mask:0xf bank_mask:" MASK_LO "\n"                   \
+  OP " " O ", " B ", " B " " CTRL_HI " row_mask:0xf bank_mask:" MASK_HI "\n"
+// lanes with bit 2 clear (banks 0, 2) take A from lane+4; lanes with bit 2 set take B from lane-4
+#define DAF_X4(OP, O, A, B) DAF_BANK_PAIR(OP, O, A, B, "row_shl:4", "0x5", "row_shr:4", "0xa")
+// lanes 0..7 of a row (banks 0, 1) take A from lane+8; lanes 8..15 take B from lane-8
+#define DAF_X8(OP, O, A, B) DAF_BANK_PAIR(OP, O, A, B, "row_ror:8", "0x3", "row_ror:8", "0xc")
+
+// in[16] -> out[8] at level 4, or in[8] -> out[4] at level 8 (OP = v_min_f32_dpp / v_max_f32_dpp).
+// Instructions of one block are independent of each other (distinct outputs, inputs are
+// read-only), so only the block's first DPP read needs the wait states after a VALU write.
+#define DAF_DEFINE_BANK_LEVEL(NAME, OP, X)                                                       \
+  __device__ __forceinline__ void NAME##_16(const float (&i)[16], float (&o)[8]) {               \
+    asm("s_nop 4\n" X(OP, "%0", "%8", "%9") X(OP, "%1", "%10", "%11") X(OP, "%2", "%12", "%13")  \
+        X(OP, "%3", "%14", "%15") X(OP, "%4", "%16", "%17") X(OP, "%5", "%18", "%19")            \
+        X(OP, "%6", "%20", "%21") X(OP, "%7", "%22", "%23") "s_nop 1\n"                          \
+        : "=&v"(o[0]), "=&v"(o[1]), "=&v"(o[2]), "=&v"(o[3]), "=&v"(o[4]), "=&v"(o[5]),          \
+          "=&v"(o[6]), "=&v"(o[7])                                                               \
+        : "v"(i[0]), "v"(i[1]), "v"(i[2]), "v"(i[3]), "v"(i[4]), "v"(i[5]), "v"(i[6]),           \
+          "v"(i[7]), "v"(i[8]), "v"(i[9]), "v"(i[10]), "v"(i[11]), "v"(i[12]), "v"(i[13]),       \
+          "v"(i[14]), "v"(i[15]));                                                               \
+  }                                                                                              \
+  __device__ __forceinline__ void NAME##_8(const float (&i)[8], float (&o)[4]) {                 \
+    asm("s_nop 4\n" X(OP, "%0", "%4", "%5") X(OP, "%1", "%6", "%7") X(OP, "%2", "%8", "%9")      \
+        X(OP, "%3", "%10", "%11") "s_nop 1\n"                                                    \
+        : "=&v"(o[0]), "=&v"(o[1]), "=&v"(o[2]), "=&v"(o[3])                                     \
+        : "v"(i[0]), "v"(i[1]), "v"(i[2]), "v"(i[3]), "v"(i[4]), "v"(i[5]), "v"(i[6]),           \
+          "v"(i[7]));                                                                            \
+  }
+DAF_DEFINE_BANK_LEVEL(min_x4, "v_min_f32_dpp", DAF_X4)
+DAF_DEFINE_BANK_LEVEL(max_x4, "v_max_f32_dpp", DAF_X4)
+DAF_DEFINE_BANK_LEVEL(min_x8, "v_min_f32_dpp", DAF_X8)
+DAF_DEFINE_BANK_LEVEL(max_x8, "v_max_f32_dpp", DAF_X8)
+#undef DAF_DEFINE_BANK_LEVEL
+#undef DAF_X8
+#undef DAF_X4
+#undef DAF_BANK_PAIR
+
+// Levels 16 and 32 (across rows): the row-swap instructions exchange the odd rows of A with
+// the even rows of B (16), or the upper half of A with the lower half of B (32); one min/max
+// of the two results then holds A reduced in the lanes with the level's bit clear and B
+// reduced in the others.
+template <int LEVEL, bool IS_MIN>
+__device__ __forceinline__ float merge_rows(float a, float b) {
+  typedef unsigned u2 __attribute__((ext_vector_type(2)));
+  const u2 r = (LEVEL == 16) ? __builtin_amdgcn_permlane16_swap(f2u(a), f2u(b), false, false)
+                             : __builtin_amdgcn_permlane32_swap(f2u(a), f2u(b), false, false);
+  return IS_MIN ? vmin(u2f(r.x), u2f(r.y)) : vmax(u2f(r.x), u2f(r.y));
+}
+
+// Levels 1 and 2 (inside a quad), one register: afterwards all four lanes of a quad agree.
+__device__ __forceinline__ void quad_minmax(float& mn, float& mx) {
+  asm("s_nop 4\n"
+      "v_min_f32_dpp %0, %0, %0 " DAF_DPP_X1 "\n"
+      "v_max_f32_dpp %1, %1, %1 " DAF_DPP_X1 "\n"
+      "s_nop 0\n"
+      "v_min_f32_dpp %0, %0, %0 " DAF_DPP_X2 "\n"
+      "v_max_f32_dpp %1, %1, %1 " DAF_DPP_X2 "\n"
+      "s_nop 1\n"
+      : "+v"(mn), "+v"(mx));
+}
+
+// min/max of 16 per-load values over runs of 32 (LPG_LOG2 = 5) or 64 (6) lanes.
+//   LPG_LOG2 = 6: afterwards lane L holds in mn[0]/mx[0] the result of load (L >> 2) & 15.
+//   LPG_LOG2 = 5: afterwards lane L holds in mn[r]/mx[r], r = 0, 1, the result of load
+//                 8r + ((L >> 2) & 7) for the run L >> 5.
+template <int LPG_LOG2>
+__device__ __forceinline__ void transposed_minmax16(const float (&mn_in)[16], const float (&mx_in)[16],
+                                                    float (&mn)[2], float (&mx)[2]) {
+  static_assert(LPG_LOG2 == 5 || LPG_LOG2 == 6, "runs of 32 or 64 lanes");
+  float a8[8], b8[8], a4[4], b4[4];
+  min_x4_16(mn_in, a8);
+  max_x4_16(mx_in, b8);
+  min_x8_8(a8, a4);
+  max_x8_8(b8, b4);
+  float a2[2] = {merge_rows<16, true>(a4[0], a4[1]), merge_rows<16, true>(a4[2], a4[3])};
+  float b2[2] = {merge_rows<16, false>(b4[0], b4[1]), merge_rows<16, false>(b4[2], b4[3])};
+  if (LPG_LOG2 == 6) {
+    mn[0] = merge_rows<32, true>(a2[0], a2[1]);
+    mx[0] = merge_rows<32, false>(b2[0], b2[1]);
+    quad_minmax(mn[0], mx[0]);
+    mn[1] = mn[0];
+    mx[1] = mx[0];
+  } else {
+    mn[0] = a2[0]; mn[1] = a2[1];
+    mx[0] = b2[0]; mx[1] = b2[1];
+    quad_minmax(mn[0], mx[0]);
+    quad_minmax(mn[1], mx[1]);
+  }
+}
+
 // Inclusive prefix sum over the 64 lanes of a wave.
 __device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v) {
 #define DAF_SCAN(CTRL, MASK) v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, MASK, 0xF, false)
@@ -149,10 +249,10 @@ __device__ __forceinline__ uint4 philox_block(uint64_t blk, uint32_t seed_lo, ui
   return philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), 0u, 0u, seed_lo, seed_hi);
 }
 
-// floor(x) as a signed integer in one instruction.
-__device__ __forceinline__ int floor_to_int(float x) {
+// floor(x + 1/2) as a signed integer in one instruction (round to nearest, ties upward).
+__device__ __forceinline__ int round_half_up_to_int(float x) {
   int r;
-  asm("v_cvt_flr_i32_f32 %0, %1" : "=v"(r) : "v"(x));
+  asm("v_cvt_rpi_i32_f32 %0, %1" : "=v"(r) : "v"(x));
   return r;
 }
 

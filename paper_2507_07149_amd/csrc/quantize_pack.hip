@@ -12,12 +12,14 @@
 //                          last group.
 //
 // Rounding arithmetic.  With mn, L = 2^b-1 and inv = L/range of the group, an element maps to
-// v = (x-mn)*inv and is rounded up iff r + 1/2 < frac(v)*256 for its random byte r.  The
-// kernels evaluate the equivalent integer form
-//     code = -floor_shift9( floor((mn-x) * (inv*512)) + 2r + 1 )
-// (floor_shift9 = arithmetic shift right by 9).  (mn-x)*(inv*512) is v*512 negated, exactly,
-// as long as inv*512 does not overflow; groups where it would are handled with two
-// multiplications.  No clamp to L is needed: v <= L*(1+2^-22), so ceil(v*512) <= 512*L + 1.
+// v = (x-mn)*inv and is rounded up iff r + 1/2 < frac(v)*256 for its random byte r, i.e. iff
+// r < T where T = ceil(256*frac(v) - 1/2) counts the bytes that round up.  With the integer
+// part folded in, code = floor((ceil(256*v - 1/2) + 255 - r) / 256).  The kernels evaluate the
+// negated form, which needs one conversion instruction and one add per element:
+//     code = -( (floor((mn-x)*(inv*256) + 1/2) + r) >> 8 )        (arithmetic shift)
+// (mn-x)*(inv*256) is -256*v exactly as long as inv*256 does not overflow; groups where it
+// would are handled with two multiplications.  floor(w + 1/2) is exact for |w| < 2^16.
+// No clamp to L is needed: v <= L*(1+2^-22), so ceil(256*v - 1/2) <= 256*L.
 #include "daf_device.h"
 #include "daf_internal.h"
 
@@ -27,7 +29,7 @@ using namespace daf;
 
 constexpr int kWavesPerBlock = 4;
 constexpr int kThreads = kWave * kWavesPerBlock;
-constexpr float kTwo9 = 512.0f;
+constexpr float kScale = 256.0f;            // 2^kRandBits
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 struct GroupScale {
@@ -51,13 +53,13 @@ __device__ __forceinline__ GroupScale group_scale(float mn, float mx, uint32_t b
   return s;
 }
 
-// Negated code of one element.  EXACT2 = false: invs = inv*512 (finite).  EXACT2 = true:
-// invs = inv, and the factor 512 is applied to the rounded product.
+// Negated code of one element.  EXACT2 = false: invs = inv*256 (finite).  EXACT2 = true:
+// invs = inv, and the factor 256 is applied to the rounded product.
 template <bool EXACT2>
-__device__ __forceinline__ int neg_code(float x, float mn, float invs, uint32_t two_r_plus_1) {
+__device__ __forceinline__ int neg_code(float x, float mn, float invs, uint32_t r) {
   float w = (mn - x) * invs;
-  if (EXACT2) w = w * kTwo9;
-  return (floor_to_int(w) + (int)two_r_plus_1) >> 9;
+  if (EXACT2) w = w * kScale;
+  return (round_half_up_to_int(w) + (int)r) >> 8;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -117,7 +119,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_group(
         const uint32_t slot = (uint32_t)(i % kElemsPerPhilox);
         const uint32_t rw = (slot < 4) ? rnd.x : (slot < 8) ? rnd.y : (slot < 12) ? rnd.z : rnd.w;
         const uint32_t r = (rw >> (8u * (slot & 3u))) & 0xFFu;
-        const int nc = neg_code<true>(load_elem<DT>(x, lo + j), s.mn, s.inv, 2u * r + 1u);
+        const int nc = neg_code<true>(load_elem<DT>(x, lo + j), s.mn, s.inv, r);
         word |= (uint32_t)(-nc) << (32u - b - c * b);
       }
       words[woff + t] = word;
@@ -146,47 +148,52 @@ struct TileShape {
 
 struct alignas(16) GroupInfo {   // what every lane of a group needs for the element map
   float mn;
-  float invs;                    // inv*512, or inv on the two-multiplication path
-  uint32_t b;
-  uint32_t woff;                 // word offset of the group inside the tile's packed run
+  float invs;                    // inv*256, or inv on the two-multiplication path
+  uint32_t b;                    // width; bits 8..9: byte-address swizzle of the staged run (3, 2 or 0)
+  uint32_t byte_off;             // byte offset of the group inside the tile's packed run
 };
 
 template <int DT, int LPG_LOG2>
 struct alignas(16) WaveLds {
   using S = TileShape<DT, LPG_LOG2>;
-  uint8_t rand_bytes[S::kElems];        // byte e = random byte of tile element e
-  uint32_t stage[S::kElems / 4];        // packed words of the tile (8 bits/element at most)
+  // First the random bytes of the tile (byte e serves tile element e); once every lane has
+  // taken its bytes into registers the same memory stages the tile's packed words (at most
+  // 8 bits per element, so the run always fits).
+  union {
+    uint8_t rand_bytes[S::kElems];
+    uint32_t stage[S::kElems / 4];
+  };
   GroupInfo info[kWave];
   float2 stat[kWave];                   // (min, max) per group, written by the group's last lane
 };
 
-// Codes of one 16-byte chunk, accumulated most significant first: acc0 = elements 0..3,
-// acc1 = elements 4..7 (16-bit inputs only).
+// Codes of one 16-byte chunk, accumulated most significant first and NEGATED (the element map
+// yields -code): nacc0 = -(elements 0..3), nacc1 = -(elements 4..7) (16-bit inputs only).
 template <int DT, bool EXACT2>
 __device__ __forceinline__ void quantize_chunk(const float (&xf)[ElemTraits<DT>::kPerLoad], float mn,
                                                float invs, uint32_t b, const uint32_t* rnd,
-                                               uint32_t& acc0, uint32_t& acc1) {
+                                               uint32_t& nacc0, uint32_t& nacc1) {
   constexpr int kEpl = ElemTraits<DT>::kPerLoad;
   uint32_t nacc[2] = {0u, 0u};
 #pragma unroll
   for (int q = 0; q < kEpl / 4; ++q) {
-    // 2r+1 for the four random bytes of one dword, as 16-bit fields of two registers
-    const uint32_t rw = rnd[q];
-    const uint32_t even = ((rw & 0x00FF00FFu) << 1) | 0x00010001u;          // bytes 0, 2
-    const uint32_t odd = (((rw >> 8) & 0x00FF00FFu) << 1) | 0x00010001u;    // bytes 1, 3
-    const uint32_t t[4] = {even & 0xFFFFu, odd & 0xFFFFu, even >> 16, odd >> 16};
+    const uint32_t rw = rnd[q];                 // the random bytes of four consecutive elements
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const int nc = neg_code<EXACT2>(xf[q * 4 + e], mn, invs, t[e]);
+      const int nc = neg_code<EXACT2>(xf[q * 4 + e], mn, invs, (rw >> (8 * e)) & 0xFFu);
       nacc[q] = (nacc[q] << b) + (uint32_t)nc;
     }
   }
-  acc0 = 0u - nacc[0];
-  acc1 = (kEpl == 8) ? 0u - nacc[1] : 0u;
+  nacc0 = nacc[0];
+  nacc1 = nacc[1];
 }
 
 // B = 1, 2, 4, 8: every group has that width (offsets are computed).  B = 0: per-group widths
 // from `bits`, offsets from `off`.
+// One tile per wave; the hardware schedules the waves.  (A looping variant in which a wave
+// prefetched its next tile while quantizing the current one was slower: it needs more
+// registers, and on this architecture loads and stores share one in-order counter, so waiting
+// for a prefetched load also waits for the stores issued after it.)
 template <int DT, int LPG_LOG2, int B>
 __global__ __launch_bounds__(kThreads) void k_quantize_pack_tile(
     const u32x4* __restrict__ x, int64_t n_tiles, const uint8_t* __restrict__ bits,
@@ -203,165 +210,206 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_tile(
   const int64_t tile = (int64_t)blockIdx.x * kWavesPerBlock + wave_in_block;
   if (tile >= n_tiles) return;
   WaveLds<DT, LPG_LOG2>& lds = lds_all[wave_in_block];
-
-  const int64_t g0 = tile * S::kGroups;                       // first group of the tile
-  const int64_t chunk0 = tile * (S::kLoads * kWave);          // first 16-byte chunk of the tile
+  const uint32_t lig = (uint32_t)(lane & (S::kLpg - 1));
+  uint8_t* stage8 = reinterpret_cast<uint8_t*>(lds.stage);
 
   // 1. all global loads of the tile, issued up front
   uint4 raw[S::kLoads];
 #pragma unroll
   for (int u = 0; u < S::kLoads; ++u) {
-    const u32x4 v = __builtin_nontemporal_load(&x[chunk0 + u * kWave + lane]);
+    const u32x4 v = __builtin_nontemporal_load(&x[tile * (S::kLoads * kWave) + u * kWave + lane]);
     raw[u] = make_uint4(v.x, v.y, v.z, v.w);
   }
-  uint32_t my_b = (uint32_t)B;
-  uint32_t tile_base;
-  if (kMixed) {
-    my_b = (lane < S::kGroups) ? (uint32_t)bits[g0 + lane] : 1u;
-    tile_base = off[g0];
-  } else {
-    tile_base = (uint32_t)tile * (uint32_t)(S::kGroups * kGroupWords32 * B);
-  }
 
-  // 2. random bytes of the tile (independent of the data; overlaps the loads' latency)
   {
-    const uint64_t blk0 = (uint64_t)tile * (S::kElems / kElemsPerPhilox);
-    uint4* dst = reinterpret_cast<uint4*>(lds.rand_bytes);
-#pragma unroll
-    for (int m = 0; m < S::kPhilox; ++m)
-      dst[m * kWave + lane] = philox_block(blk0 + (uint64_t)(m * kWave + lane), seed_lo, seed_hi);
-  }
+    const int64_t g0 = tile * S::kGroups;                     // first group of the tile
 
-  // 3. per-group min/max: in-lane over the chunk, then across the group's lanes (two loads at
-  //    a time so that four independent DPP chains interleave)
-  float xf[S::kLoads][kEpl];
-  static_assert(S::kLoads % 2 == 0, "loads are reduced in pairs");
+    uint32_t my_b = (uint32_t)B;
+    uint32_t tile_base;
+    if (kMixed) {
+      my_b = (lane < S::kGroups) ? (uint32_t)bits[g0 + lane] : 1u;
+      tile_base = off[g0];
+    } else {
+      tile_base = (uint32_t)tile * (uint32_t)(S::kGroups * kGroupWords32 * B);
+    }
+
+    // 2. random bytes of the tile (independent of the data; overlaps the loads' latency)
+    {
+      const uint64_t blk0 = (uint64_t)tile * (S::kElems / kElemsPerPhilox);
+      uint4* dst = reinterpret_cast<uint4*>(lds.rand_bytes);
 #pragma unroll
-  for (int u = 0; u < S::kLoads; u += 2) {
-    float mn[2], mx[2];
+      for (int m = 0; m < S::kPhilox; ++m)
+        dst[m * kWave + lane] = philox_block(blk0 + (uint64_t)(m * kWave + lane), seed_lo, seed_hi);
+    }
+
+    // 3. per-group min/max: in-lane over the chunk, then across the group's lanes
+    float xf[S::kLoads][kEpl];
+    static_assert(S::kLoads % 2 == 0, "loads are reduced in pairs");
+    if constexpr (DT == kF32 && LPG_LOG2 >= 5) {
+      // groups of 32 or 64 lanes: all 16 loads are reduced together (transposed reduction)
+      static_assert(S::kLoads == 16, "transposed reduction takes 16 values");
+      float lmn[16], lmx[16];
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
+      for (int u = 0; u < 16; ++u) {
 #pragma unroll
-      for (int e = 0; e < kEpl; ++e) xf[u + h][e] = chunk_elem<DT>(raw[u + h], e);
-      const float(&v)[kEpl] = xf[u + h];
+        for (int e = 0; e < kEpl; ++e) xf[u][e] = chunk_elem<DT>(raw[u], e);
+        lmn[u] = vmin(vmin3(xf[u][0], xf[u][1], xf[u][2]), xf[u][3]);
+        lmx[u] = vmax(vmax3(xf[u][0], xf[u][1], xf[u][2]), xf[u][3]);
+      }
+      float mn[2], mx[2];
+      transposed_minmax16<LPG_LOG2>(lmn, lmx, mn, mx);
+      if ((lane & 3) == 0) {
+        if (LPG_LOG2 == 6) {
+          lds.stat[(lane >> 2) & 15] = make_float2(mn[0], mx[0]);
+        } else {
+          const int u = (lane >> 2) & 7, seg = lane >> 5;
+          lds.stat[u * 2 + seg] = make_float2(mn[0], mx[0]);
+          lds.stat[(u + 8) * 2 + seg] = make_float2(mn[1], mx[1]);
+        }
+      }
+    } else {
+      // two loads at a time so that four independent DPP chains interleave
+#pragma unroll
+      for (int u = 0; u < S::kLoads; u += 2) {
+        float mn[2], mx[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+#pragma unroll
+          for (int e = 0; e < kEpl; ++e) xf[u + h][e] = chunk_elem<DT>(raw[u + h], e);
+          const float(&v)[kEpl] = xf[u + h];
+          if (kEpl == 4) {
+            mn[h] = vmin(vmin3(v[0], v[1], v[2]), v[3]);
+            mx[h] = vmax(vmax3(v[0], v[1], v[2]), v[3]);
+          } else {
+            mn[h] = vmin(vmin3(vmin3(vmin3(v[0], v[1], v[2]), v[3], v[4 % kEpl]), v[5 % kEpl], v[6 % kEpl]), v[7 % kEpl]);
+            mx[h] = vmax(vmax3(vmax3(vmax3(v[0], v[1], v[2]), v[3], v[4 % kEpl]), v[5 % kEpl], v[6 % kEpl]), v[7 % kEpl]);
+          }
+        }
+        seg_minmax_x2<LPG_LOG2>(mn[0], mx[0], mn[1], mx[1]);
+        if (lig == (uint32_t)S::kLpg - 1u) {
+          lds.stat[u * S::kGpl + (lane >> LPG_LOG2)] = make_float2(mn[0], mx[0]);
+          lds.stat[(u + 1) * S::kGpl + (lane >> LPG_LOG2)] = make_float2(mn[1], mx[1]);
+        }
+      }
+    }
+    wave_lds_sync();
+
+    // 4. lane g of the wave finishes group g of the tile: scale, reciprocal, place in the run
+    bool need_exact2;
+    uint32_t tile_words;
+    {
+      const float2 st = lds.stat[lane & (S::kGroups - 1)];
+      const GroupScale s = group_scale(st.x, st.y, my_b);
+      const float invs = s.inv * kScale;
+      need_exact2 = __builtin_amdgcn_ballot_w64(!(invs <= 3.402823466e+38f) && lane < S::kGroups) != 0ull;
+      uint32_t woff;
+      if (kMixed) {
+        const uint32_t w = (lane < S::kGroups) ? kGroupWords32 * my_b : 0u;
+        const uint32_t incl = wave_inclusive_sum(w);
+        tile_words = (uint32_t)__builtin_amdgcn_readlane((int)incl, kWave - 1);
+        woff = incl - w;
+      } else {
+        tile_words = S::kGroups * kGroupWords32 * B;
+        woff = (uint32_t)lane * (kGroupWords32 * B);
+      }
+      if (lane < S::kGroups) {
+        out_min[g0 + lane] = s.mn;
+        out_scale[g0 + lane] = s.scale;
+        GroupInfo gi;
+        gi.mn = s.mn;
+        gi.invs = need_exact2 ? s.inv : invs;
+        // A lane's bits are written as a byte (swizzle 3), a halfword (2) or whole words (0).
+        const uint32_t lane_bits = (uint32_t)kEpl * my_b;
+        const uint32_t swz = (lane_bits <= 8u) ? 3u : (lane_bits == 16u) ? 2u : 0u;
+        gi.b = my_b | (swz << 8);
+        gi.byte_off = woff * 4u;
+        lds.info[lane] = gi;
+      }
+    }
+
+    // the lane's random bytes, one dword per four elements, out of LDS before it is reused
+    uint32_t rnd[S::kLoads][kEpl / 4];
+#pragma unroll
+    for (int u = 0; u < S::kLoads; ++u) {
       if (kEpl == 4) {
-        mn[h] = vmin(vmin3(v[0], v[1], v[2]), v[3]);
-        mx[h] = vmax(vmax3(v[0], v[1], v[2]), v[3]);
+        rnd[u][0] = reinterpret_cast<const uint32_t*>(lds.rand_bytes)[u * kWave + lane];
       } else {
-        mn[h] = vmin(vmin3(vmin3(vmin3(v[0], v[1], v[2]), v[3], v[4 % kEpl]), v[5 % kEpl], v[6 % kEpl]), v[7 % kEpl]);
-        mx[h] = vmax(vmax3(vmax3(vmax3(v[0], v[1], v[2]), v[3], v[4 % kEpl]), v[5 % kEpl], v[6 % kEpl]), v[7 % kEpl]);
+        const uint2 r2 = reinterpret_cast<const uint2*>(lds.rand_bytes)[u * kWave + lane];
+        rnd[u][0] = r2.x;
+        rnd[u][kEpl / 4 - 1] = r2.y;
       }
     }
-    seg_minmax_x2<LPG_LOG2>(mn[0], mx[0], mn[1], mx[1]);
-    if ((lane & (S::kLpg - 1)) == S::kLpg - 1) {
-      lds.stat[u * S::kGpl + (lane >> LPG_LOG2)] = make_float2(mn[0], mx[0]);
-      lds.stat[(u + 1) * S::kGpl + (lane >> LPG_LOG2)] = make_float2(mn[1], mx[1]);
-    }
-  }
-  wave_lds_sync();
+    wave_lds_sync();
 
-  // 4. lane g of the wave finishes group g of the tile: scale, reciprocal, word offset
-  bool need_exact2;
-  uint32_t tile_words;
-  {
-    const float2 st = lds.stat[lane & (S::kGroups - 1)];
-    const GroupScale s = group_scale(st.x, st.y, my_b);
-    const float invs = s.inv * kTwo9;
-    need_exact2 = __builtin_amdgcn_ballot_w64(!(invs <= 3.402823466e+38f) && lane < S::kGroups) != 0ull;
-    uint32_t woff;
-    if (kMixed) {
-      const uint32_t w = (lane < S::kGroups) ? kGroupWords32 * my_b : 0u;
-      const uint32_t incl = wave_inclusive_sum(w);
-      tile_words = (uint32_t)__builtin_amdgcn_readlane((int)incl, kWave - 1);
-      woff = incl - w;
-    } else {
-      tile_words = S::kGroups * kGroupWords32 * B;
-      woff = (uint32_t)lane * (kGroupWords32 * B);
-    }
-    if (lane < S::kGroups) {
-      out_min[g0 + lane] = s.mn;
-      out_scale[g0 + lane] = s.scale;
-      GroupInfo gi;
-      gi.mn = s.mn;
-      gi.invs = need_exact2 ? s.inv : invs;
-      gi.b = my_b;
-      gi.woff = woff;
-      lds.info[lane] = gi;
-    }
-  }
-  wave_lds_sync();
-
-  // 5. quantize every chunk and drop its bits at their place in the staged word run.
-  //    The staged run is a big-endian bit string per word: byte k of the string lives at
-  //    byte address k^3, halfword k at byte address 2k^2.
-  const int lig = lane & (S::kLpg - 1);
-  uint8_t* stage8 = reinterpret_cast<uint8_t*>(lds.stage);
+    // 5. quantize every chunk and drop its bits at their place in the staged word run.
+    //    The staged run is a big-endian bit string per word: byte k of the string lives at
+    //    byte address k^3, halfword k at byte address 2k^2.
 #pragma unroll
-  for (int u = 0; u < S::kLoads; ++u) {
-    const int grp = u * S::kGpl + (lane >> LPG_LOG2);
-    float g_mn, g_invs;
-    uint32_t b, woff;
-    if (kMixed) {
-      const GroupInfo gi = lds.info[grp];
-      g_mn = gi.mn; g_invs = gi.invs; b = gi.b; woff = gi.woff;
-    } else {
-      const float2 mi = *reinterpret_cast<const float2*>(&lds.info[grp]);
-      g_mn = mi.x; g_invs = mi.y; b = B; woff = (uint32_t)grp * (kGroupWords32 * B);
-    }
-    uint32_t rnd[kEpl / 4];
-    if (kEpl == 4) {
-      rnd[0] = reinterpret_cast<const uint32_t*>(lds.rand_bytes)[u * kWave + lane];
-    } else {
-      const uint2 r2 = reinterpret_cast<const uint2*>(lds.rand_bytes)[u * kWave + lane];
-      rnd[0] = r2.x;
-      rnd[kEpl / 4 - 1] = r2.y;
-    }
-    uint32_t acc0, acc1;
-    if (need_exact2) quantize_chunk<DT, true>(xf[u], g_mn, g_invs, b, rnd, acc0, acc1);
-    else             quantize_chunk<DT, false>(xf[u], g_mn, g_invs, b, rnd, acc0, acc1);
+    for (int u = 0; u < S::kLoads; ++u) {
+      const int grp = u * S::kGpl + (lane >> LPG_LOG2);
+      float g_mn, g_invs;
+      uint32_t b, addr;
+      if (kMixed) {
+        const GroupInfo gi = lds.info[grp];
+        g_mn = gi.mn; g_invs = gi.invs; b = gi.b & 0xFFu;
+        // byte address of this lane's bits: lig * (kEpl*b) bits = lig*b*kEpl/8 bytes
+        addr = (gi.byte_off + ((lig * b * (uint32_t)kEpl) >> 3)) ^ (gi.b >> 8);
+      } else {
+        const float2 mi = *reinterpret_cast<const float2*>(&lds.info[grp]);
+        g_mn = mi.x; g_invs = mi.y; b = B;
+        constexpr uint32_t kLaneBits = (uint32_t)kEpl * B;
+        constexpr uint32_t kSwz = (kLaneBits <= 8u) ? 3u : (kLaneBits == 16u) ? 2u : 0u;
+        addr = ((uint32_t)grp * (kGroupWords32 * B * 4u) + ((lig * kLaneBits) >> 3)) ^ kSwz;
+      }
+      uint32_t n0, n1;
+      if (need_exact2) quantize_chunk<DT, true>(xf[u], g_mn, g_invs, b, rnd[u], n0, n1);
+      else             quantize_chunk<DT, false>(xf[u], g_mn, g_invs, b, rnd[u], n0, n1);
 
-    const uint32_t pbits = (uint32_t)kEpl * b;                    // bits this lane contributes
-    const uint32_t bitpos = (uint32_t)lig * pbits;                // inside the group's bit string
-    const uint32_t byte_pos = woff * 4u + (bitpos >> 3);          // logical byte of the staged run
-    if (kEpl == 4) {
-      if (b == 1u) {           // 4 bits per lane: the even lane takes its odd neighbour's nibble
-        const uint32_t nb = dpp<kDppXor1>(acc0, acc0);
-        if ((lane & 1) == 0) stage8[byte_pos ^ 3u] = (uint8_t)((acc0 << 4) | nb);
-      } else if (b == 2u) {
-        stage8[byte_pos ^ 3u] = (uint8_t)acc0;
-      } else if (b == 4u) {
-        *reinterpret_cast<uint16_t*>(stage8 + (byte_pos ^ 2u)) = (uint16_t)acc0;
+      if (kEpl == 4) {
+        const uint32_t acc = 0u - n0;
+        if (b == 1u) {           // 4 bits per lane: the even lane takes its odd neighbour's nibble
+          const uint32_t nb = dpp<kDppXor1>(acc, acc);
+          if ((lane & 1) == 0) stage8[addr] = (uint8_t)((acc << 4) | nb);
+        } else if (b == 2u) {
+          stage8[addr] = (uint8_t)acc;
+        } else if (b == 4u) {
+          *reinterpret_cast<uint16_t*>(stage8 + addr) = (uint16_t)acc;
+        } else {
+          *reinterpret_cast<uint32_t*>(stage8 + addr) = acc;
+        }
       } else {
-        *reinterpret_cast<uint32_t*>(stage8 + byte_pos) = acc0;
-      }
-    } else {
-      const uint32_t both = (acc0 << ((4u * b) & 31u)) | acc1;    // valid for b <= 4
-      if (b == 1u) {
-        stage8[byte_pos ^ 3u] = (uint8_t)both;
-      } else if (b == 2u) {
-        *reinterpret_cast<uint16_t*>(stage8 + (byte_pos ^ 2u)) = (uint16_t)both;
-      } else if (b == 4u) {
-        *reinterpret_cast<uint32_t*>(stage8 + byte_pos) = both;
-      } else {
-        *reinterpret_cast<uint2*>(stage8 + byte_pos) = make_uint2(acc0, acc1);
+        if (b == 8u) {
+          *reinterpret_cast<uint2*>(stage8 + addr) = make_uint2(0u - n0, 0u - n1);
+        } else {
+          const uint32_t both = 0u - ((n0 << (4u * b)) + n1);
+          if (b == 4u) {
+            *reinterpret_cast<uint32_t*>(stage8 + addr) = both;
+          } else if (b == 2u) {
+            *reinterpret_cast<uint16_t*>(stage8 + addr) = (uint16_t)both;
+          } else {
+            stage8[addr] = (uint8_t)both;
+          }
+        }
       }
     }
+    wave_lds_sync();
+
+    // 6. the tile's words are one contiguous run in the packed buffer
+    uint32_t* dst = words + tile_base;
+    for (uint32_t i = lane; i < tile_words; i += kWave) dst[i] = lds.stage[i];
   }
-  wave_lds_sync();
-
-  // 6. the tile's words are one contiguous run in the packed buffer
-  uint32_t* dst = words + tile_base;
-  for (uint32_t i = lane; i < tile_words; i += kWave) dst[i] = lds.stage[i];
 }
 
 template <int DT, int LPG_LOG2>
 hipError_t launch_tile(const daf_plan_t* p, const void* x, int64_t n_tiles, uint32_t seed_lo, uint32_t seed_hi,
                        uint32_t* out_words, float* out_min, float* out_scale, hipStream_t stream) {
-  const unsigned blocks = (unsigned)((n_tiles + kWavesPerBlock - 1) / kWavesPerBlock);
-#define DAF_LAUNCH(BITS)                                                                                  \
-  hipLaunchKernelGGL((k_quantize_pack_tile<DT, LPG_LOG2, BITS>), dim3(blocks), dim3(kThreads), 0, stream, \
-                     static_cast<const u32x4*>(x), n_tiles, p->d_bits, p->d_off, seed_lo, seed_hi,        \
-                     out_words, out_min, out_scale)
+#define DAF_LAUNCH(BITS)                                                                                   \
+  do {                                                                                                     \
+    auto kernel = k_quantize_pack_tile<DT, LPG_LOG2, BITS>;                                                \
+    const unsigned blocks = (unsigned)((n_tiles + kWavesPerBlock - 1) / kWavesPerBlock);                   \
+    hipLaunchKernelGGL(kernel, dim3(blocks), dim3(kThreads), 0, stream, static_cast<const u32x4*>(x),      \
+                       n_tiles, p->d_bits, p->d_off, seed_lo, seed_hi, out_words, out_min, out_scale);     \
+  } while (0)
   switch (p->uniform_bits) {
     case 0: DAF_LAUNCH(0); break;
     case 1: DAF_LAUNCH(1); break;

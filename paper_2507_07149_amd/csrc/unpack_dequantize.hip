@@ -16,7 +16,7 @@ namespace {
 using namespace daf;
 
 constexpr int kThreads = 256;
-constexpr int kChunksPerThread = 4;
+constexpr int kChunksPerThread = 8;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 template <int DT>
@@ -49,47 +49,65 @@ __global__ __launch_bounds__(kThreads) void k_unpack_dequantize_group(
   }
 }
 
+// The loop over a thread's chunks is split into phases (metadata loads, word loads,
+// arithmetic + stores) so that all loads of one phase are in flight together: with per-group
+// widths the word address depends on two earlier loads, and a chunk-by-chunk loop would pay
+// that latency once per chunk.
 template <int DT, bool MIXED>
 __global__ __launch_bounds__(kThreads) void k_unpack_dequantize_chunk(
     const uint32_t* __restrict__ words, const float* __restrict__ mn, const float* __restrict__ scale,
     const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, int32_t uniform_bits,
     int64_t n_chunks, int32_t gs, int32_t gs_shift, u32x4* __restrict__ out) {
   constexpr int kEpl = ElemTraits<DT>::kPerLoad;
-  const int64_t base = (int64_t)blockIdx.x * (kThreads * kChunksPerThread) + threadIdx.x;
+  constexpr int K = kChunksPerThread;
+  const int64_t base = (int64_t)blockIdx.x * (kThreads * K) + threadIdx.x;
+
+  int64_t g[K];
+  uint32_t b[K], woff[K], bitpos[K];
+  float m[K], s[K];
 #pragma unroll
-  for (int k = 0; k < kChunksPerThread; ++k) {
-    const int64_t c = base + (int64_t)k * kThreads;
-    if (c >= n_chunks) break;
+  for (int k = 0; k < K; ++k) {
+    int64_t c = base + (int64_t)k * kThreads;
+    c = (c < n_chunks) ? c : n_chunks - 1;                         // clamp: loads stay in bounds
     const int64_t e0 = c * kEpl;                                   // first element of the chunk
-    const int64_t g = (gs_shift >= 0) ? (e0 >> gs_shift) : (e0 / gs);
-    const uint32_t j0 = (uint32_t)(e0 - g * (int64_t)gs);          // position inside the group
-    uint32_t b, woff;
+    g[k] = (gs_shift >= 0) ? (e0 >> gs_shift) : (e0 / gs);
+    bitpos[k] = (uint32_t)(e0 - g[k] * (int64_t)gs);               // element position in the group
     if (MIXED) {
-      b = bits[g];
-      woff = off[g];
+      b[k] = bits[g[k]];
+      woff[k] = off[g[k]];
     } else {
-      b = (uint32_t)uniform_bits;
-      woff = (uint32_t)g * ((uint32_t)(gs >> 5) * b);
+      b[k] = (uint32_t)uniform_bits;
+      woff[k] = (uint32_t)g[k] * ((uint32_t)(gs >> 5) * b[k]);
     }
-    const float m = mn[g], s = scale[g];
-    const uint32_t bitpos = j0 * b;
-    const uint32_t* wp = words + woff + (bitpos >> 5);
-    const uint32_t levels = (1u << b) - 1u;
+    m[k] = mn[g[k]];
+    s[k] = scale[g[k]];
+  }
+  uint32_t w0[K], w1[K];
+#pragma unroll
+  for (int k = 0; k < K; ++k) {
+    bitpos[k] *= b[k];                                             // bit position in the group
+    const uint32_t* wp = words + woff[k] + (bitpos[k] >> 5);
+    w0[k] = wp[0];
+    w1[k] = (kEpl == 8 && b[k] == 8u) ? wp[1] : 0u;                // 64 bits only for 8 x 8-bit codes
+  }
+#pragma unroll
+  for (int k = 0; k < K; ++k) {
+    const int64_t c = base + (int64_t)k * kThreads;
+    const uint32_t levels = (1u << b[k]) - 1u;
     float v[kEpl];
-    if (kEpl == 8 && b == 8u) {
-      const uint32_t w0 = wp[0], w1 = wp[1];
+    if (kEpl == 8 && b[k] == 8u) {
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        v[e] = __builtin_fmaf((float)((w0 >> (24 - 8 * e)) & 0xFFu), s, m);
-        v[kEpl - 4 + e] = __builtin_fmaf((float)((w1 >> (24 - 8 * e)) & 0xFFu), s, m);
+        v[e] = __builtin_fmaf((float)((w0[k] >> (24 - 8 * e)) & 0xFFu), s[k], m[k]);
+        v[kEpl - 4 + e] = __builtin_fmaf((float)((w1[k] >> (24 - 8 * e)) & 0xFFu), s[k], m[k]);
       }
     } else {
-      const uint32_t pbits = (uint32_t)kEpl * b;                   // <= 32 here
-      const uint32_t field = wp[0] >> (32u - pbits - (bitpos & 31u));
+      const uint32_t pbits = (uint32_t)kEpl * b[k];                // <= 32 here
+      const uint32_t field = w0[k] >> (32u - pbits - (bitpos[k] & 31u));
 #pragma unroll
       for (int e = 0; e < kEpl; ++e) {
-        const uint32_t code = (field >> ((uint32_t)(kEpl - 1 - e) * b)) & levels;
-        v[e] = __builtin_fmaf((float)code, s, m);
+        const uint32_t code = (field >> ((uint32_t)(kEpl - 1 - e) * b[k])) & levels;
+        v[e] = __builtin_fmaf((float)code, s[k], m[k]);
       }
     }
     u32x4 o;
@@ -103,7 +121,7 @@ __global__ __launch_bounds__(kThreads) void k_unpack_dequantize_chunk(
         h[q] = narrow16<D>(v[(2 * q) % kEpl]) | (narrow16<D>(v[(2 * q + 1) % kEpl]) << 16);
       o = (u32x4){h[0], h[1], h[2], h[3]};
     }
-    __builtin_nontemporal_store(o, &out[c]);
+    if (c < n_chunks) __builtin_nontemporal_store(o, &out[c]);
   }
 }
 

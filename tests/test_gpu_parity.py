@@ -130,6 +130,18 @@ def test_full_size_resnet18_step_sampled(H):
         del x, xh
 
 
+@pytest.mark.timeout(400)
+@pytest.mark.parametrize("dtype,gs,bits,n_tiles", [(BF16, 64, "mixed", 20000), (F32, 256, 2, 26000),
+                                                   (F16, 128, "mixed", 19000)])
+def test_many_tiles_full_parity(H, dtype, gs, bits, n_tiles):
+    """Several times more tiles than the GPU holds waves at once, so that workgroups are
+    dispatched in many rounds: whole-tensor comparison (77-107 M elements)."""
+    n = n_tiles * 4096 + 5 * gs + 3
+    w = _workload(dtype, n, gs, bits, seed=77, rng_seed=n_tiles)
+    print("case", w.name, flush=True)
+    H.assert_full_parity(w, H.run_hip(w))
+
+
 def test_seed_changes_codes_and_is_reproducible(H):
     w = _workload(F32, 4096 * 4, 256, 2, seed=1)
     a = H.u32(H.run_hip(w).words)
