@@ -43,6 +43,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--streams", type=int, default=1,
+                    help="launch the tensors of a batch round-robin on this many HIP streams (default "
+                         "priority), so that the tail of one kernel overlaps the start of the next")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a device copy of 1 GiB (a kernel of known traffic) so that the HBM "
                          "byte counters of a rocprofv3 --pmc run can be scaled against it")
@@ -115,13 +118,42 @@ def main():
         sets.append(bufs)
     torch.cuda.synchronize()
 
+    # Tensor t always uses stream t % n_streams in both directions, so its dequantize is
+    # ordered after its quantize without any cross-stream event.
+    main = torch.cuda.current_stream()
+    streams = [main] + [torch.cuda.Stream() for _ in range(max(0, args.streams - 1))]
+    order = list(enumerate(zip(workloads, plans)))
+
+    def fork():
+        if len(streams) > 1:
+            ev = torch.cuda.Event()
+            ev.record(main)
+            for s in streams[1:]:
+                s.wait_event(ev)
+
+    def join():
+        for s in streams[1:]:
+            ev = torch.cuda.Event()
+            ev.record(s)
+            main.wait_event(ev)
+
+    def quantize_all(bufs):
+        for t, (w, p) in order:
+            b = bufs[t]
+            daf.daf_quantize_pack(p, b["x"], w.seed, b["words"], b["mn"], b["sc"], stream=streams[t % len(streams)])
+
+    def dequantize_all(bufs):
+        for t, (w, p) in reversed(order):
+            b = bufs[t]
+            daf.daf_unpack_dequantize(p, b["words"], b["mn"], b["sc"], b["xh"], stream=streams[t % len(streams)])
+
     def step(i):
         bufs = sets[i % n_sets]
         # forward order, then reverse order (a training step saves, then restores backwards)
-        for w, p, b in zip(workloads, plans, bufs):
-            daf.daf_quantize_pack(p, b["x"], w.seed, b["words"], b["mn"], b["sc"])
-        for w, p, b in reversed(list(zip(workloads, plans, bufs))):
-            daf.daf_unpack_dequantize(p, b["words"], b["mn"], b["sc"], b["xh"])
+        fork()
+        quantize_all(bufs)
+        dequantize_all(bufs)
+        join()
 
     for i in range(args.warmup):
         step(i)
@@ -139,13 +171,13 @@ def main():
     def kernel_pass(direction, reps):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
+        fork()
         for r in range(reps):
-            bufs = sets[r % n_sets]
-            for w, p, b in zip(workloads, plans, bufs):
-                if direction == "q":
-                    daf.daf_quantize_pack(p, b["x"], w.seed, b["words"], b["mn"], b["sc"])
-                else:
-                    daf.daf_unpack_dequantize(p, b["words"], b["mn"], b["sc"], b["xh"])
+            if direction == "q":
+                quantize_all(sets[r % n_sets])
+            else:
+                dequantize_all(sets[r % n_sets])
+        join()
         e1.record()
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / reps
@@ -172,7 +204,8 @@ def main():
         "vs_baseline": None, "dtype": {0: "f32", 1: "f16", 2: "bf16"}[workloads[0].dtype],
         "data": "synthetic", "config": {"workload": CONFIG_NAMES[args.config], "tensors": len(workloads),
                                         "elements": sum(w.numel for w in workloads),
-                                        "group_size": workloads[0].group_size, "buffer_sets": n_sets},
+                                        "group_size": workloads[0].group_size, "buffer_sets": n_sets,
+                                        "streams": len(streams)},
         "quantize_pack": {"kernel_ms": round(qk_ms, 4),
                           "input_GBps": round(in_bytes / qk_ms / 1e6, 1), "algorithmic_bytes": alg,
                           "launches": len(workloads)},

@@ -170,6 +170,19 @@ void daf_oracle_narrow(const float* x, int dtype, int64_t n, void* out) {
   for (int64_t i = 0; i < n; ++i) store_elem(out, dtype, i, x[i]);
 }
 
+// Whole-tensor minimum and maximum (the collective reduction of Sec. 3.2, whose result Eq. 1
+// consumes when the statistics are taken per tensor).  A zero result is returned as +0.
+void daf_oracle_minmax(const void* x, int dtype, int64_t n, float* out_minmax) {
+  float mn = load_elem(x, dtype, 0), mx = mn;
+  for (int64_t i = 1; i < n; ++i) {
+    const float v = load_elem(x, dtype, i);
+    if (v < mn) mn = v;
+    if (v > mx) mx = v;
+  }
+  out_minmax[0] = mn + 0.0f;
+  out_minmax[1] = mx + 0.0f;
+}
+
 // Plan: words per group w_g = ceil(n_g * b_g / 32) and their exclusive scan.
 // off may be null.  Returns the total word count, or -1 for bad arguments.
 // (The paper only says packed values are concatenated, Sec. 3.3; locating a

@@ -30,6 +30,7 @@ def lib():
         L.daf_oracle_rand.restype = c.c_uint32
         L.daf_oracle_widen.argtypes = [vp, c.c_int, i64, vp]
         L.daf_oracle_narrow.argtypes = [vp, c.c_int, i64, vp]
+        L.daf_oracle_minmax.argtypes = [vp, c.c_int, i64, vp]
         L.daf_oracle_plan.argtypes = [i64, i32, vp, i64, vp]
         L.daf_oracle_plan.restype = i64
         L.daf_oracle_quantize_pack.argtypes = [vp, c.c_int, i64, i32, vp, i64, u64, vp, vp, vp, vp]
@@ -84,6 +85,14 @@ def narrow(x: np.ndarray, dtype: int) -> np.ndarray:
     x = np.ascontiguousarray(x.reshape(-1), dtype=np.float32)
     out = np.empty(x.size, dtype=_NP[dtype])
     lib().daf_oracle_narrow(_p(x), dtype, x.size, _p(out))
+    return out
+
+
+def minmax(x: np.ndarray, dtype: int) -> np.ndarray:
+    """Whole-tensor (min, max) as float32[2]."""
+    x = np.ascontiguousarray(x.reshape(-1), dtype=_NP[dtype])
+    out = np.empty(2, dtype=np.float32)
+    lib().daf_oracle_minmax(_p(x), dtype, x.size, _p(out))
     return out
 
 

@@ -131,19 +131,24 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_group(
 // Fast path: one wave per tile.
 // ------------------------------------------------------------------------------------------
 // Lane l of load u holds the 16-byte chunk u*64 + l of the tile.  A group spans
-// LPG = 2^LPG_LOG2 neighbouring lanes of one load.
+// 2^LPG_LOG2 consecutive chunks: up to 64 neighbouring lanes of one load (LPG_LOG2 <= 6), or
+// the whole wave over 2, 4, 8 or 16 consecutive loads (LPG_LOG2 = 7..10).
 template <int DT, int LPG_LOG2>
 struct TileShape {
   static constexpr int kEpl = ElemTraits<DT>::kPerLoad;            // elements per lane per load
-  static constexpr int kLpg = 1 << LPG_LOG2;                       // lanes per group
-  static constexpr int kGpl = kWave / kLpg;                        // groups per load
+  static constexpr int kLaneLog2 = LPG_LOG2 < 6 ? LPG_LOG2 : 6;    // log2 lanes of a group in one load
+  static constexpr int kLpg = 1 << kLaneLog2;                      // lanes per group (in one load)
+  static constexpr int kGpl = kWave / kLpg;                        // group segments per load
+  static constexpr int kLoadsPerGroup = 1 << (LPG_LOG2 - kLaneLog2);
   static constexpr int kMaxLoads = 4096 / (kWave * kEpl);          // 16 (fp32) or 8 (16-bit)
   static constexpr int kLoads = (kMaxLoads * kGpl <= kWave) ? kMaxLoads : kWave / kGpl;
-  static constexpr int kGroups = kLoads * kGpl;                    // groups per tile, <= 64
+  static constexpr int kSegments = kLoads * kGpl;                  // (load, lane run) pairs, <= 64
+  static constexpr int kGroups = kSegments / kLoadsPerGroup;       // groups per tile
   static constexpr int kElems = kLoads * kWave * kEpl;             // 2048 or 4096
-  static constexpr int kGroupSize = kLpg * kEpl;
+  static constexpr int kGroupSize = (1 << LPG_LOG2) * kEpl;
   static constexpr int kPhilox = kElems / kElemsPerPhilox / kWave; // Philox calls per lane
-  static_assert(kGroups <= kWave && kPhilox >= 1, "tile shape");
+  static constexpr bool kValid = kLoadsPerGroup <= kLoads;
+  static_assert(kSegments <= kWave && kPhilox >= 1, "tile shape");
 };
 
 struct alignas(16) GroupInfo {   // what every lane of a group needs for the element map
@@ -210,7 +215,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_tile(
   const int64_t tile = (int64_t)blockIdx.x * kWavesPerBlock + wave_in_block;
   if (tile >= n_tiles) return;
   WaveLds<DT, LPG_LOG2>& lds = lds_all[wave_in_block];
-  const uint32_t lig = (uint32_t)(lane & (S::kLpg - 1));
+  const uint32_t lane_in_run = (uint32_t)(lane & (S::kLpg - 1));
   uint8_t* stage8 = reinterpret_cast<uint8_t*>(lds.stage);
 
   // 1. all global loads of the tile, issued up front
@@ -257,9 +262,9 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_tile(
         lmx[u] = vmax(vmax3(xf[u][0], xf[u][1], xf[u][2]), xf[u][3]);
       }
       float mn[2], mx[2];
-      transposed_minmax16<LPG_LOG2>(lmn, lmx, mn, mx);
+      transposed_minmax16<S::kLaneLog2>(lmn, lmx, mn, mx);
       if ((lane & 3) == 0) {
-        if (LPG_LOG2 == 6) {
+        if (LPG_LOG2 >= 6) {
           lds.stat[(lane >> 2) & 15] = make_float2(mn[0], mx[0]);
         } else {
           const int u = (lane >> 2) & 7, seg = lane >> 5;
@@ -285,10 +290,10 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_tile(
             mx[h] = vmax(vmax3(vmax3(vmax3(v[0], v[1], v[2]), v[3], v[4 % kEpl]), v[5 % kEpl], v[6 % kEpl]), v[7 % kEpl]);
           }
         }
-        seg_minmax_x2<LPG_LOG2>(mn[0], mx[0], mn[1], mx[1]);
-        if (lig == (uint32_t)S::kLpg - 1u) {
-          lds.stat[u * S::kGpl + (lane >> LPG_LOG2)] = make_float2(mn[0], mx[0]);
-          lds.stat[(u + 1) * S::kGpl + (lane >> LPG_LOG2)] = make_float2(mn[1], mx[1]);
+        seg_minmax_x2<S::kLaneLog2>(mn[0], mx[0], mn[1], mx[1]);
+        if ((lane & (S::kLpg - 1)) == S::kLpg - 1) {
+          lds.stat[u * S::kGpl + (lane >> S::kLaneLog2)] = make_float2(mn[0], mx[0]);
+          lds.stat[(u + 1) * S::kGpl + (lane >> S::kLaneLog2)] = make_float2(mn[1], mx[1]);
         }
       }
     }
@@ -298,7 +303,14 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_tile(
     bool need_exact2;
     uint32_t tile_words;
     {
-      const float2 st = lds.stat[lane & (S::kGroups - 1)];
+      // the group's (load, lane run) segments are consecutive entries of stat
+      float2 st = lds.stat[(lane & (S::kGroups - 1)) * S::kLoadsPerGroup];
+#pragma unroll
+      for (int j = 1; j < S::kLoadsPerGroup; ++j) {
+        const float2 t = lds.stat[(lane & (S::kGroups - 1)) * S::kLoadsPerGroup + j];
+        st.x = vmin(st.x, t.x);
+        st.y = vmax(st.y, t.y);
+      }
       const GroupScale s = group_scale(st.x, st.y, my_b);
       const float invs = s.inv * kScale;
       need_exact2 = __builtin_amdgcn_ballot_w64(!(invs <= 3.402823466e+38f) && lane < S::kGroups) != 0ull;
@@ -346,7 +358,9 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_tile(
     //    byte address k^3, halfword k at byte address 2k^2.
 #pragma unroll
     for (int u = 0; u < S::kLoads; ++u) {
-      const int grp = u * S::kGpl + (lane >> LPG_LOG2);
+      const int grp = (u * S::kGpl + (lane >> S::kLaneLog2)) / S::kLoadsPerGroup;
+      // position of this lane's chunk among the chunks of its group
+      const uint32_t lig = lane_in_run + (uint32_t)(u % S::kLoadsPerGroup) * kWave;
       float g_mn, g_invs;
       uint32_t b, addr;
       if (kMixed) {
@@ -430,20 +444,23 @@ hipError_t launch_dtype(const daf_plan_t* p, const void* x, uint64_t seed, uint3
   const int64_t full_groups = p->n / p->group_size;
   int64_t fast_groups = 0;
 
-  // fast path: groups of 4..64 lanes (a power of two), whole tiles only
+  // fast path: groups of 4 .. 1024 chunks (a power of two, at most one tile), whole tiles only
   const int32_t lpg = p->group_size / kEpl;
-  if (p->group_size % kEpl == 0 && lpg >= 4 && lpg <= 64 && (lpg & (lpg - 1)) == 0) {
+  if (p->group_size % kEpl == 0 && lpg >= 4 && (lpg & (lpg - 1)) == 0) {
     int64_t n_tiles = 0;
     hipError_t e = hipSuccess;
 #define DAF_CASE(LOG2)                                                                                   \
   case (1 << LOG2):                                                                                      \
-    n_tiles = full_groups / TileShape<DT, LOG2>::kGroups;                                                \
-    fast_groups = n_tiles * TileShape<DT, LOG2>::kGroups;                                                \
-    if (n_tiles > 0) e = launch_tile<DT, LOG2>(p, x, n_tiles, seed_lo, seed_hi, out_words, out_min,      \
-                                               out_scale, stream);                                       \
+    if constexpr (TileShape<DT, LOG2>::kValid) {                                                         \
+      n_tiles = full_groups / TileShape<DT, LOG2>::kGroups;                                              \
+      fast_groups = n_tiles * TileShape<DT, LOG2>::kGroups;                                              \
+      if (n_tiles > 0) e = launch_tile<DT, LOG2>(p, x, n_tiles, seed_lo, seed_hi, out_words, out_min,    \
+                                                 out_scale, stream);                                     \
+    }                                                                                                    \
     break;
     switch (lpg) {
       DAF_CASE(2) DAF_CASE(3) DAF_CASE(4) DAF_CASE(5) DAF_CASE(6)
+      DAF_CASE(7) DAF_CASE(8) DAF_CASE(9) DAF_CASE(10)
       default: break;
     }
 #undef DAF_CASE

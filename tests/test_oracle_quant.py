@@ -212,3 +212,48 @@ def test_dequantize_endpoints_and_double_recomputation(dtype):
         assert np.array_equal(xw[::gs], mn)             # code 0 gives min exactly
     else:
         assert np.array_equal(xh, orc.narrow(f32, dtype))
+
+
+@pytest.mark.parametrize("dtype", [orc.F32, orc.F16, orc.BF16])
+def test_whole_tensor_minmax_against_numpy(dtype):
+    """Pins for the per-tensor reduction: numpy's min/max on the widened values, the position
+    of the extremes anywhere in the array, single elements, and +0 for a zero result."""
+    rng = np.random.default_rng(31 + dtype)
+    for n in (1, 2, 63, 64, 65, 1000, 50_176, 393_216):
+        xf = (rng.standard_normal(n) * 10 ** rng.uniform(-3, 3)).astype(np.float32)
+        x = xf if dtype == orc.F32 else orc.narrow(xf, dtype)
+        w = orc.widen(x, dtype)
+        got = orc.minmax(x, dtype)
+        assert got[0] == w.min() and got[1] == w.max()
+        for pos in (0, n - 1, n // 2):                       # extremes at the ends and in the middle
+            y = w.copy()
+            y[pos] = w.max() * 2 + 1
+            y[(pos + 1) % n if n > 1 else 0] = min(w.min() * 2 - 1, y[(pos + 1) % n if n > 1 else 0]) if n > 1 else y[0]
+            yy = y if dtype == orc.F32 else orc.narrow(y, dtype)
+            yw = orc.widen(yy, dtype)
+            g = orc.minmax(yy, dtype)
+            assert g[0] == yw.min() and g[1] == yw.max()
+    z = np.zeros(8, dtype=np.float32)
+    z[::2] = -0.0
+    zz = z if dtype == orc.F32 else orc.narrow(z, dtype)
+    g = orc.minmax(zz, dtype)
+    assert g.view(np.uint32)[0] == 0 and g.view(np.uint32)[1] == 0
+    neg = -np.abs(rng.standard_normal(100)).astype(np.float32) - 1
+    nn = neg if dtype == orc.F32 else orc.narrow(neg, dtype)
+    g = orc.minmax(nn, dtype)
+    assert g[1] == orc.widen(nn, dtype).max() < 0
+
+
+def test_one_group_is_per_tensor_quantization():
+    """group_size >= N gives the paper's own granularity (Eq. 1 with tensor-wide min and max):
+    min and scale must be those of the whole-tensor reduction."""
+    rng = np.random.default_rng(77)
+    n = 5000
+    x = rng.standard_normal(n).astype(np.float32)
+    gs = 5024                                                 # multiple of 32, >= n
+    for b in (2, 4):
+        _, mn, sc, codes = orc.quantize_pack(x, orc.F32, gs, [b], 5, want_codes=True)
+        mm = orc.minmax(x, orc.F32)
+        assert mn.size == 1 and mn[0] == mm[0]
+        assert sc[0] == (mm[1] - mm[0]) / np.float32((1 << b) - 1)
+        assert codes[np.argmin(x)] == 0 and codes[np.argmax(x)] == (1 << b) - 1
