@@ -43,6 +43,12 @@ def parse():
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--minmax", action="store_true",
+                    help="time daf_minmax (whole-tensor reduction, both methods) on the paper's two shapes "
+                         "and on the default activation instead of the quantize/dequantize step")
+    ap.add_argument("--group-size", type=int, default=None,
+                    help="override the group size of a uniform-width configuration; 0 = one group per "
+                         "tensor (the paper's per-tensor statistics)")
     ap.add_argument("--streams", type=int, default=1,
                     help="launch the tensors of a batch round-robin on this many HIP streams (default "
                          "priority), so that the tail of one kernel overlaps the start of the next")
@@ -81,6 +87,7 @@ def main():
     daf.load_library()                      # fails loudly if libdaf.so is missing
     dev = torch.device("cuda:0")
 
+    import numpy as np
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB
         dst = torch.empty_like(src)
@@ -91,7 +98,43 @@ def main():
                                                "launches": args.steps}}))
         return
 
+    if args.minmax:
+        ws = daf.daf_minmax_workspace()
+        out = torch.empty(2, device=dev)
+        res = []
+        shapes = [("conv2d_in_1x256x14x14", (1, 256, 14, 14)), ("attention_in_1x512x768", (1, 512, 768)),
+                  ("resnet50_conv_64x256x56x56", (64, 256, 56, 56))]
+        for name, shape in shapes:
+            n = int(np.prod(shape))
+            n_sets = max(1, min(64, -(-ROTATE_BYTES // (4 * n))))
+            xs = [torch.randn(n, device=dev) for _ in range(n_sets)]
+            row = {"shape": name, "elements": n, "dtype": "f32", "buffer_sets": n_sets}
+            for label, method in (("two_pass", daf.REDUCE_TWO_PASS), ("atomic", daf.REDUCE_ATOMIC)):
+                for i in range(args.warmup):
+                    daf.daf_minmax(xs[i % n_sets], method, ws, out)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                reps = max(args.steps, 2 * n_sets)
+                torch.cuda.synchronize()
+                e0.record()
+                for i in range(reps):
+                    daf.daf_minmax(xs[i % n_sets], method, ws, out)
+                e1.record()
+                torch.cuda.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / reps
+                row[label + "_us"] = round(us, 2)
+                row[label + "_GBps"] = round(4 * n / us / 1e3, 1)
+            res.append(row)
+        print(json.dumps({"metric": "whole-tensor min/max reduction time per call", "unit": "us", "n_gpus": 1,
+                          "data": "synthetic", "results": res}))
+        return
+
     workloads = make_config(args.config)
+    if args.group_size is not None:
+        for w in workloads:
+            if w.bits.size != 1:
+                print("bench.py: --group-size needs a uniform-width configuration", file=sys.stderr)
+                sys.exit(2)
+            w.group_size = args.group_size if args.group_size > 0 else ((w.numel + 31) // 32) * 32
     in_bytes = sum(w.numel * w.x.element_size() for w in workloads)
     n_sets = max(1, -(-ROTATE_BYTES // in_bytes))
     if in_bytes >= ROTATE_BYTES:
@@ -188,12 +231,15 @@ def main():
     kernel_pass("d", n_sets)
     dk_ms = kernel_pass("d", reps)
     alg = sum(algorithmic_bytes(w, p.packed_words) for w, p in zip(workloads, plans))
+    # groups longer than a 4096-element tile need their statistics before any element can be
+    # quantized: the quantize direction then reads the activation twice
+    alg_q = alg + sum(w.numel * w.x.element_size() for w in workloads if w.group_size > 4096)
     value = 2 * in_bytes / (ms_per_step * 1e-3) / 1e9
 
-    traffic = MEASURED_TRAFFIC.get(args.config, (None, None))
+    traffic = MEASURED_TRAFFIC.get(args.config, (None, None)) if args.group_size is None else (None, None)
 
-    def roof(ms, measured):
-        ach = alg / (ms * 1e-3) / 1e9
+    def roof(ms, measured, nbytes):
+        ach = nbytes / (ms * 1e-3) / 1e9
         return {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": measured}
 
@@ -207,13 +253,13 @@ def main():
                                         "group_size": workloads[0].group_size, "buffer_sets": n_sets,
                                         "streams": len(streams)},
         "quantize_pack": {"kernel_ms": round(qk_ms, 4),
-                          "input_GBps": round(in_bytes / qk_ms / 1e6, 1), "algorithmic_bytes": alg,
+                          "input_GBps": round(in_bytes / qk_ms / 1e6, 1), "algorithmic_bytes": alg_q,
                           "launches": len(workloads)},
         "unpack_dequantize": {"kernel_ms": round(dk_ms, 4),
                               "output_GBps": round(in_bytes / dk_ms / 1e6, 1), "algorithmic_bytes": alg,
                               "launches": len(workloads)},
-        "roofline": dict(roof(qk_ms, traffic[0]), kernel="k_quantize_pack_tile"),
-        "roofline_unpack_dequantize": dict(roof(dk_ms, traffic[1]), kernel="k_unpack_dequantize_chunk"),
+        "roofline": dict(roof(qk_ms, traffic[0], alg_q), kernel="k_quantize_pack_tile"),
+        "roofline_unpack_dequantize": dict(roof(dk_ms, traffic[1], alg), kernel="k_unpack_dequantize_chunk"),
     }
 
     if not args.no_cpu_baseline:

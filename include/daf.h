@@ -138,6 +138,39 @@ int daf_unpack_dequantize(const daf_plan_t* plan, const uint32_t* words,
                           const float* min, const float* scale, const uint8_t* bits,
                           void* out_x, daf_dtype_t dtype, void* stream);
 
+/* ---- whole-tensor reduction -------------------------------------------------------------
+ *
+ * daf_minmax -- minimum and maximum over all N elements of a tensor: the collective reduction
+ * that Sec. 3.2 identifies as the expensive part of dynamic quantization control, in the two
+ * forms the section describes.
+ *
+ *   DAF_REDUCE_TWO_PASS  tree reduction inside each workgroup, one (min, max) pair per
+ *                        workgroup written to memory, a second launch reduces the pairs
+ *                        (Sec. 3.2.1, "parallel reduction").
+ *   DAF_REDUCE_ATOMIC    tree reduction inside each workgroup, then the pair is merged into
+ *                        one shared result with a float atomic minimum/maximum built from
+ *                        integer compare-and-swap (Algorithm 1; Sec. 3.2.2, the hybrid of
+ *                        tree and atomic reduction).  One launch.
+ *
+ *   x, dtype, n     DEVICE, n >= 1 elements, 16-byte aligned, finite values.
+ *   method          one of the two above.
+ *   workspace       DEVICE, daf_minmax_workspace_bytes() bytes, 16-byte aligned, prepared once
+ *                   with daf_minmax_workspace_init (on the same stream or synchronized before
+ *                   first use).  Calls that share a workspace must not overlap in time; the
+ *                   workspace is left ready for the next call.
+ *   out_minmax      DEVICE, 2 floats: min then max, as binary32; a zero result is +0.
+ *   stream          enqueue only; no synchronization.
+ *
+ * Errors: DAF_EINVAL (null or misaligned pointer, n < 1, unknown method), DAF_EUNSUPPORTED
+ * (dtype), DAF_EDEVICE.
+ */
+typedef enum { DAF_REDUCE_TWO_PASS = 0, DAF_REDUCE_ATOMIC = 1 } daf_reduce_method_t;
+
+int64_t daf_minmax_workspace_bytes(void);
+int daf_minmax_workspace_init(void* workspace, void* stream);
+int daf_minmax(const void* x, daf_dtype_t dtype, int64_t n, int method, void* workspace,
+               float* out_minmax, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -53,6 +53,11 @@ def load_library():
     L.daf_quantize_pack.restype = c.c_int
     L.daf_unpack_dequantize.argtypes = [vp, vp, vp, vp, vp, vp, c.c_int, vp]
     L.daf_unpack_dequantize.restype = c.c_int
+    L.daf_minmax_workspace_bytes.restype = i64
+    L.daf_minmax_workspace_init.argtypes = [vp, vp]
+    L.daf_minmax_workspace_init.restype = c.c_int
+    L.daf_minmax.argtypes = [vp, c.c_int, i64, c.c_int, vp, vp, vp]
+    L.daf_minmax.restype = c.c_int
     _lib = L
     return L
 
@@ -145,3 +150,23 @@ def daf_unpack_dequantize(plan: Plan, words: torch.Tensor, mn: torch.Tensor, sca
                                               out_x.data_ptr(), _DTYPE_ID[out_x.dtype], _stream_handle(stream))
     if rc != 0:
         raise DafError(rc, "daf_unpack_dequantize")
+
+
+REDUCE_TWO_PASS, REDUCE_ATOMIC = 0, 1
+
+
+def daf_minmax_workspace(device="cuda:0", stream=None) -> torch.Tensor:
+    """Allocates and prepares a workspace for daf_minmax (reusable across calls that do not overlap)."""
+    L = load_library()
+    ws = torch.empty(int(L.daf_minmax_workspace_bytes()), dtype=torch.uint8, device=device)
+    rc = L.daf_minmax_workspace_init(ws.data_ptr(), _stream_handle(stream))
+    if rc != 0:
+        raise DafError(rc, "daf_minmax_workspace_init")
+    return ws
+
+
+def daf_minmax(x: torch.Tensor, method: int, workspace: torch.Tensor, out_minmax: torch.Tensor, stream=None) -> None:
+    rc = load_library().daf_minmax(x.data_ptr(), _DTYPE_ID[x.dtype], x.numel(), method, workspace.data_ptr(),
+                                   out_minmax.data_ptr(), _stream_handle(stream))
+    if rc != 0:
+        raise DafError(rc, "daf_minmax")

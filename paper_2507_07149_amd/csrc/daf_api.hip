@@ -28,6 +28,15 @@ struct DeviceGuard {      // make the plan's device current for the duration of 
 
 }  // namespace
 
+bool daf_plan_needs_big_scratch(int64_t n, int32_t group_size, int64_t num_groups, int64_t* bytes) {
+  constexpr int64_t kTile = 4096;
+  if (group_size <= kTile) return false;
+  if (group_size % kTile != 0 && num_groups != 1) return false;   // handled group by group instead
+  const int64_t n_partials = (n + kTile - 1) / kTile;
+  *bytes = (n_partials + num_groups) * 8;
+  return true;
+}
+
 extern "C" {
 
 int daf_rand_bits(void) { return 8; }
@@ -65,7 +74,10 @@ int daf_plan(const int64_t* shape, int ndim, int32_t group_size, const uint8_t* 
   p->group_size = group_size;
   p->d_bits = nullptr;
   p->d_off = nullptr;
+  p->d_big_scratch = nullptr;
   p->device = -1;
+  int64_t big_bytes = 0;
+  const bool big = daf_plan_needs_big_scratch(n, group_size, G, &big_bytes);
 
   if (n_bits == 1) {                     // uniform width: `bits` is a host pointer, no device work
     const int b = bits[0];
@@ -76,6 +88,10 @@ int daf_plan(const int64_t* shape, int ndim, int32_t group_size, const uint8_t* 
     p->uniform_bits = b;
     p->total_words = total;
     (void)hipGetDevice(&p->device);      // remembered when a device exists; harmless otherwise
+    if (big && hipMalloc(&p->d_big_scratch, (size_t)big_bytes) != hipSuccess) {
+      delete p;
+      return DAF_ENOMEM;
+    }
     *out_plan = p;
     return DAF_OK;
   }
@@ -91,6 +107,7 @@ int daf_plan(const int64_t* shape, int ndim, int32_t group_size, const uint8_t* 
     if (hipGetDevice(&p->device) != hipSuccess) { rc = DAF_EDEVICE; break; }
     if (hipMalloc(&p->d_bits, (size_t)G) != hipSuccess) { rc = DAF_ENOMEM; break; }
     if (hipMalloc(&p->d_off, (size_t)G * sizeof(uint32_t)) != hipSuccess) { rc = DAF_ENOMEM; break; }
+    if (big && hipMalloc(&p->d_big_scratch, (size_t)big_bytes) != hipSuccess) { rc = DAF_ENOMEM; break; }
     if (hipMalloc(&d_sums, (size_t)(n_blocks + 2) * sizeof(unsigned long long)) != hipSuccess) { rc = DAF_ENOMEM; break; }
     unsigned long long* d_total = d_sums + n_blocks;
     int* d_bad = reinterpret_cast<int*>(d_sums + n_blocks + 1);
@@ -136,6 +153,7 @@ void daf_plan_destroy(daf_plan_t* plan) {
   if (plan == nullptr) return;
   if (plan->d_bits) (void)hipFree(plan->d_bits);
   if (plan->d_off) (void)hipFree(plan->d_off);
+  if (plan->d_big_scratch) (void)hipFree(plan->d_big_scratch);
   delete plan;
 }
 
@@ -159,6 +177,25 @@ int daf_unpack_dequantize(const daf_plan_t* plan, const uint32_t* words, const f
   const uint8_t* d_bits = bits ? bits : plan->d_bits;
   const hipError_t e = daf_launch_unpack_dequantize(plan, words, min, scale, d_bits, out_x, (int)dtype,
                                                     static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? DAF_OK : DAF_EDEVICE;
+}
+
+int64_t daf_minmax_workspace_bytes(void) { return daf_minmax_workspace_size(); }
+
+int daf_minmax_workspace_init(void* workspace, void* stream) {
+  if (workspace == nullptr || !aligned(workspace, 16)) return DAF_EINVAL;
+  return daf_launch_minmax_workspace_init(workspace, static_cast<hipStream_t>(stream)) == hipSuccess ? DAF_OK
+                                                                                                    : DAF_EDEVICE;
+}
+
+int daf_minmax(const void* x, daf_dtype_t dtype, int64_t n, int method, void* workspace, float* out_minmax,
+               void* stream) {
+  if (x == nullptr || workspace == nullptr || out_minmax == nullptr || n < 1) return DAF_EINVAL;
+  if (!aligned(x, 16) || !aligned(workspace, 16) || !aligned(out_minmax, 4)) return DAF_EINVAL;
+  if (method != DAF_REDUCE_TWO_PASS && method != DAF_REDUCE_ATOMIC) return DAF_EINVAL;
+  if (dtype != DAF_F32 && dtype != DAF_F16 && dtype != DAF_BF16) return DAF_EUNSUPPORTED;
+  const hipError_t e = daf_launch_minmax(x, (int)dtype, n, method, workspace, out_minmax,
+                                         static_cast<hipStream_t>(stream));
   return e == hipSuccess ? DAF_OK : DAF_EDEVICE;
 }
 

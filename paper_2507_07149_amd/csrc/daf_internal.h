@@ -14,7 +14,13 @@ struct daf_plan_s {
   int device;            // HIP device the plan's memory lives on
   uint8_t* d_bits;       // G widths (device), mixed plans only
   uint32_t* d_off;       // G word offsets (device), mixed plans only
+  void* d_big_scratch;   // groups longer than a 4096-element tile: one (min, max) pair per tile and
+                         // per group, written by the quantize call's first pass (else null)
 };
+
+// True when the plan's groups are longer than a tile and tile-aligned (or there is one group),
+// i.e. when daf_quantize_pack takes the two-pass route; bytes of scratch it then needs.
+bool daf_plan_needs_big_scratch(int64_t n, int32_t group_size, int64_t num_groups, int64_t* bytes);
 
 // Launchers.  Each returns hipSuccess or the first HIP error.
 hipError_t daf_launch_plan_scan(const uint8_t* d_bits, int64_t num_groups, int64_t n, int32_t group_size,
@@ -29,3 +35,8 @@ hipError_t daf_launch_quantize_pack(const daf_plan_t* plan, const void* x, int d
 hipError_t daf_launch_unpack_dequantize(const daf_plan_t* plan, const uint32_t* words, const float* mn,
                                         const float* scale, const uint8_t* d_bits, void* out_x, int dtype,
                                         hipStream_t stream);
+
+int64_t daf_minmax_workspace_size(void);
+hipError_t daf_launch_minmax_workspace_init(void* workspace, hipStream_t stream);
+hipError_t daf_launch_minmax(const void* x, int dtype, int64_t n, int method, void* workspace, float* out_minmax,
+                             hipStream_t stream);

@@ -5,9 +5,9 @@
 //   k_unpack_dequantize_chunk  the fast path.  A thread produces 16 bytes of output at a time
 //                              (4 fp32 or 8 16-bit elements).  Such a chunk never straddles a
 //                              group and its bits never straddle a word pair, so it needs one
-//                              (or, at 8 bits and 16-bit output, two) packed words.  Covers all
-//                              full groups of any group size.
-//   k_unpack_dequantize_group  one wave per group, element by element: the short last group.
+//                              (or, at 8 bits and 16-bit output, two) packed words.  Covers every
+//                              whole chunk of the tensor, for any group size.
+//   k_unpack_dequantize_tail   the fewer than 8 elements after the last whole chunk.
 #include "daf_device.h"
 #include "daf_internal.h"
 
@@ -25,28 +25,21 @@ __device__ __forceinline__ void store_elem(void* out, int64_t i, float v) {
   else static_cast<uint16_t*>(out)[i] = (uint16_t)narrow16<DT == kF32 ? kF16 : DT>(v);
 }
 
+// The last elements of the tensor, [e_begin, n) with n - e_begin < 8: all in the last group.
 template <int DT>
-__global__ __launch_bounds__(kThreads) void k_unpack_dequantize_group(
+__global__ __launch_bounds__(kWave) void k_unpack_dequantize_tail(
     const uint32_t* __restrict__ words, const float* __restrict__ mn, const float* __restrict__ scale,
-    const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, int32_t uniform_bits, int64_t n,
-    int32_t gs, int64_t g_begin, int64_t g_end, void* __restrict__ out) {
-  const int lane = threadIdx.x & (kWave - 1);
-  const int64_t wave = (int64_t)blockIdx.x * (kThreads / kWave) + (threadIdx.x >> 6);
-  const int64_t n_waves = (int64_t)gridDim.x * (kThreads / kWave);
-  for (int64_t g = g_begin + wave; g < g_end; g += n_waves) {
-    const int64_t lo = g * (int64_t)gs;
-    const int32_t len = (int32_t)((lo + gs <= n) ? gs : (n - lo));
-    const uint32_t b = uniform_bits ? (uint32_t)uniform_bits : (uint32_t)bits[g];
-    const uint32_t woff = uniform_bits ? (uint32_t)(g * (int64_t)((gs * uniform_bits) >> 5)) : off[g];
-    const float m = mn[g], s = scale[g];
-    const uint32_t levels = (1u << b) - 1u;
-    for (int32_t j = lane; j < len; j += kWave) {
-      const uint32_t bitpos = (uint32_t)j * b;
-      const uint32_t w = words[woff + (bitpos >> 5)];
-      const uint32_t code = (w >> (32u - b - (bitpos & 31u))) & levels;
-      store_elem<DT>(out, lo + j, __builtin_fmaf((float)code, s, m));
-    }
-  }
+    const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, int32_t uniform_bits, int64_t e_begin,
+    int64_t n, int32_t gs, void* __restrict__ out) {
+  const int64_t i = e_begin + threadIdx.x;
+  if (i >= n) return;
+  const int64_t g = i / gs;
+  const uint32_t b = uniform_bits ? (uint32_t)uniform_bits : (uint32_t)bits[g];
+  const uint32_t woff = uniform_bits ? (uint32_t)(g * (((int64_t)gs * uniform_bits) >> 5)) : off[g];
+  const uint64_t bitpos = (uint64_t)(i - g * (int64_t)gs) * b;
+  const uint32_t w = words[woff + (bitpos >> 5)];
+  const uint32_t code = (w >> (32u - b - (uint32_t)(bitpos & 31u))) & ((1u << b) - 1u);
+  store_elem<DT>(out, i, __builtin_fmaf((float)code, scale[g], mn[g]));
 }
 
 // The loop over a thread's chunks is split into phases (metadata loads, word loads,
@@ -85,8 +78,9 @@ __global__ __launch_bounds__(kThreads) void k_unpack_dequantize_chunk(
   uint32_t w0[K], w1[K];
 #pragma unroll
   for (int k = 0; k < K; ++k) {
-    bitpos[k] *= b[k];                                             // bit position in the group
-    const uint32_t* wp = words + woff[k] + (bitpos[k] >> 5);
+    const uint64_t bit64 = (uint64_t)bitpos[k] * b[k];             // bit position in the group
+    bitpos[k] = (uint32_t)bit64 & 31u;                             // ... and in its word
+    const uint32_t* wp = words + woff[k] + (uint32_t)(bit64 >> 5);
     w0[k] = wp[0];
     w1[k] = (kEpl == 8 && b[k] == 8u) ? wp[1] : 0u;                // 64 bits only for 8 x 8-bit codes
   }
@@ -103,7 +97,7 @@ __global__ __launch_bounds__(kThreads) void k_unpack_dequantize_chunk(
       }
     } else {
       const uint32_t pbits = (uint32_t)kEpl * b[k];                // <= 32 here
-      const uint32_t field = w0[k] >> (32u - pbits - (bitpos[k] & 31u));
+      const uint32_t field = w0[k] >> (32u - pbits - bitpos[k]);
 #pragma unroll
       for (int e = 0; e < kEpl; ++e) {
         const uint32_t code = (field >> ((uint32_t)(kEpl - 1 - e) * b[k])) & levels;
@@ -129,8 +123,7 @@ template <int DT>
 hipError_t launch_dtype(const daf_plan_t* p, const uint32_t* words, const float* mn, const float* scale,
                         const uint8_t* d_bits, void* out_x, hipStream_t stream) {
   constexpr int kEpl = ElemTraits<DT>::kPerLoad;
-  const int64_t full_groups = p->n / p->group_size;
-  const int64_t n_chunks = full_groups * (p->group_size / kEpl);
+  const int64_t n_chunks = p->n / kEpl;                 // a chunk never straddles a group (32 | group size)
   int32_t gs_shift = -1;
   if ((p->group_size & (p->group_size - 1)) == 0) gs_shift = __builtin_ctz((unsigned)p->group_size);
   if (n_chunks > 0) {
@@ -147,10 +140,9 @@ hipError_t launch_dtype(const daf_plan_t* p, const uint32_t* words, const float*
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  if (full_groups < p->num_groups) {
-    hipLaunchKernelGGL((k_unpack_dequantize_group<DT>), dim3(1), dim3(kThreads), 0, stream, words, mn, scale,
-                       d_bits, p->d_off, p->uniform_bits, p->n, p->group_size, full_groups, p->num_groups,
-                       out_x);
+  if (n_chunks * kEpl < p->n) {
+    hipLaunchKernelGGL((k_unpack_dequantize_tail<DT>), dim3(1), dim3(kWave), 0, stream, words, mn, scale, d_bits,
+                       p->d_off, p->uniform_bits, n_chunks * kEpl, p->n, p->group_size, out_x);
     return hipGetLastError();
   }
   return hipSuccess;

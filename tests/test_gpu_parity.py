@@ -36,11 +36,11 @@ def test_reduced_configs_full_parity(H, cfg, scale):
 
 
 @pytest.mark.parametrize("dtype", [F32, F16, BF16])
-@pytest.mark.parametrize("gs", [32, 64, 96, 128, 256, 512, 1024])
+@pytest.mark.parametrize("gs", [32, 64, 96, 128, 256, 512, 1024, 2048, 4096, 8192])
 @pytest.mark.parametrize("bits", [1, 2, 4, 8, "mixed"])
 def test_group_size_matrix(H, dtype, gs, bits):
-    # ~2.5 tiles worth of groups plus a ragged tail
-    n = 4096 * 2 + gs * 3 + 17
+    # a few tiles worth of groups plus a ragged tail
+    n = 4096 * 2 + gs * 3 + 17 + (4096 * 6 if gs >= 2048 else 0)
     w = _workload(dtype, n, gs, bits, seed=0xABCDEF0123456789 % (1 << 64), rng_seed=gs + 7 * dtype)
     print("case", w.name, flush=True)
     H.assert_full_parity(w, H.run_hip(w))
@@ -140,6 +140,32 @@ def test_many_tiles_full_parity(H, dtype, gs, bits, n_tiles):
     w = _workload(dtype, n, gs, bits, seed=77, rng_seed=n_tiles)
     print("case", w.name, flush=True)
     H.assert_full_parity(w, H.run_hip(w))
+
+
+@pytest.mark.parametrize("dtype", [F32, F16, BF16])
+@pytest.mark.parametrize("bits", [1, 2, 8, "mixed"])
+@pytest.mark.parametrize("n,gs", [(4096 * 9 + 77, 8192), (4096 * 12, 4096 * 4), (4096 * 7 + 4095, 4096 * 3),
+                                  (50_176, 50_176), (393_216, 393_216), (100_003, 100_032), (5000, 5024),
+                                  (4096 * 5 + 1, 4096 * 5 + 32)])
+def test_groups_longer_than_a_tile(H, dtype, bits, n, gs):
+    """Group sizes above 4096 elements take the two-pass route (tile min/max, per-group reduce,
+    quantize with the group's statistics), up to one group for the whole tensor (the paper's
+    per-tensor statistics; 50,176 and 393,216 are the shapes of its reduction experiment)."""
+    w = _workload(dtype, n, gs, bits, seed=gs, rng_seed=n % 1000)
+    print("case", w.name, flush=True)
+    H.assert_full_parity(w, H.run_hip(w))
+
+
+@pytest.mark.timeout(300)
+def test_per_tensor_quantization_of_the_resnet50_activation(H):
+    (w0,) = make_config(2)
+    n = w0.numel
+    w = Workload("resnet50_per_tensor", w0.x, F32, n, np.array([2], np.uint8), 1)
+    res = H.run_hip(w)
+    H.assert_sampled_parity(w, res, n_samples=10)       # one group: this compares everything
+    from oracle import daf_oracle as orc
+    mm = orc.minmax(w0.x.reshape(-1).numpy(), F32)
+    assert res.mn.cpu().numpy()[0] == mm[0]
 
 
 def test_seed_changes_codes_and_is_reproducible(H):
