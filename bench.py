@@ -49,9 +49,10 @@ def parse():
     ap.add_argument("--group-size", type=int, default=None,
                     help="override the group size of a uniform-width configuration; 0 = one group per "
                          "tensor (the paper's per-tensor statistics)")
-    ap.add_argument("--streams", type=int, default=1,
-                    help="launch the tensors of a batch round-robin on this many HIP streams (default "
-                         "priority), so that the tail of one kernel overlaps the start of the next")
+    ap.add_argument("--streams", type=int, default=2,
+                    help="the timed steps launch independent tensors / independent batches round-robin on "
+                         "this many HIP streams (default priority), so that the tail of one kernel overlaps "
+                         "the start of the next; the per-kernel roofline timing always uses one stream")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a device copy of 1 GiB (a kernel of known traffic) so that the HBM "
                          "byte counters of a rocprofv3 --pmc run can be scaled against it")
@@ -161,8 +162,10 @@ def main():
         sets.append(bufs)
     torch.cuda.synchronize()
 
-    # Tensor t always uses stream t % n_streams in both directions, so its dequantize is
-    # ordered after its quantize without any cross-stream event.
+    # Tensor t of buffer set k always uses stream (k + t) % n_streams, in both directions and in
+    # every step, so its dequantize is ordered after its quantize, and each reuse of a buffer
+    # after the previous one, without any cross-stream event.  Independent tensors and
+    # independent batches may overlap (the tail of one kernel with the start of the next).
     main = torch.cuda.current_stream()
     streams = [main] + [torch.cuda.Stream() for _ in range(max(0, args.streams - 1))]
     order = list(enumerate(zip(workloads, plans)))
@@ -180,47 +183,49 @@ def main():
             ev.record(s)
             main.wait_event(ev)
 
-    def quantize_all(bufs):
+    def quantize_all(k, single=False):
         for t, (w, p) in order:
-            b = bufs[t]
-            daf.daf_quantize_pack(p, b["x"], w.seed, b["words"], b["mn"], b["sc"], stream=streams[t % len(streams)])
+            b = sets[k][t]
+            daf.daf_quantize_pack(p, b["x"], w.seed, b["words"], b["mn"], b["sc"],
+                                  stream=main if single else streams[(k + t) % len(streams)])
 
-    def dequantize_all(bufs):
+    def dequantize_all(k, single=False):
         for t, (w, p) in reversed(order):
-            b = bufs[t]
-            daf.daf_unpack_dequantize(p, b["words"], b["mn"], b["sc"], b["xh"], stream=streams[t % len(streams)])
+            b = sets[k][t]
+            daf.daf_unpack_dequantize(p, b["words"], b["mn"], b["sc"], b["xh"],
+                                      stream=main if single else streams[(k + t) % len(streams)])
 
     def step(i):
-        bufs = sets[i % n_sets]
         # forward order, then reverse order (a training step saves, then restores backwards)
-        fork()
-        quantize_all(bufs)
-        dequantize_all(bufs)
-        join()
+        quantize_all(i % n_sets)
+        dequantize_all(i % n_sets)
 
+    fork()
     for i in range(args.warmup):
         step(i)
+    join()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    fork()
     for i in range(args.steps):
         step(args.warmup + i)
+    join()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
-    # Kernel time per direction, for the roofline: the launches of one direction back to back
-    # (rotating over the buffer sets), bracketed by ONE pair of HIP events on the launch
-    # stream, so that the few microseconds an event pair costs are not charged to every launch.
+    # Kernel time per direction, for the roofline: the launches of one direction back to back on
+    # ONE stream (rotating over the buffer sets, no overlap between kernels), bracketed by one
+    # pair of HIP events on that stream, so that the few microseconds an event pair costs are
+    # not charged to every launch.
     def kernel_pass(direction, reps):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        fork()
         for r in range(reps):
             if direction == "q":
-                quantize_all(sets[r % n_sets])
+                quantize_all(r % n_sets, single=True)
             else:
-                dequantize_all(sets[r % n_sets])
-        join()
+                dequantize_all(r % n_sets, single=True)
         e1.record()
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / reps
