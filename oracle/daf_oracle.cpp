@@ -183,6 +183,60 @@ void daf_oracle_minmax(const void* x, int dtype, int64_t n, float* out_minmax) {
   out_minmax[1] = mx + 0.0f;
 }
 
+// Per-group minimum and maximum (the statistics of Eq. 1, taken per group), each with a zero
+// stored as +0.  This is what a bit-width controller reads before it chooses the widths
+// (Sec. 3.2: scale and importance metrics are reductions over the activation).
+void daf_oracle_group_minmax(const void* x, int dtype, int64_t n, int32_t gs, float* out_min, float* out_max) {
+  const int64_t G = num_groups(n, gs);
+  for (int64_t g = 0; g < G; ++g) {
+    const int64_t lo = g * gs, len = group_len(n, gs, g);
+    float mn = load_elem(x, dtype, lo), mx = mn;
+    for (int64_t j = 1; j < len; ++j) {
+      const float v = load_elem(x, dtype, lo + j);
+      if (v < mn) mn = v;
+      if (v > mx) mx = v;
+    }
+    out_min[g] = mn + 0.0f;
+    out_max[g] = mx + 0.0f;
+  }
+}
+
+// Stand-in width policy of the benchmark configurations: rank the groups by (range, index)
+// ascending, range = max - min in binary32, and give rank r the class floor(r*C/G); class c
+// gets classes[c] bits, so the groups with the smallest range get classes[0].  (The paper's own
+// controller, Sec. 3.4.1, ranks activations by an importance score; the rule here only fixes
+// which groups get which width in the synthetic workloads.)  Insertion into a sorted order is
+// done with a plain stable merge sort on (range, index).
+static void merge_sort_by_range(const float* range, int64_t* idx, int64_t* tmp, int64_t lo, int64_t hi) {
+  if (hi - lo < 2) return;
+  const int64_t mid = lo + (hi - lo) / 2;
+  merge_sort_by_range(range, idx, tmp, lo, mid);
+  merge_sort_by_range(range, idx, tmp, mid, hi);
+  int64_t a = lo, b = mid, o = lo;
+  while (a < mid && b < hi) tmp[o++] = (range[idx[b]] < range[idx[a]]) ? idx[b++] : idx[a++];   // ties: left (lower index) first
+  while (a < mid) tmp[o++] = idx[a++];
+  while (b < hi) tmp[o++] = idx[b++];
+  for (int64_t i = lo; i < hi; ++i) idx[i] = tmp[i];
+}
+
+int daf_oracle_select_bits(const float* gmin, const float* gmax, int64_t G, const uint8_t* classes,
+                           int32_t n_classes, uint8_t* out_bits) {
+  if (G < 1 || n_classes < 1 || n_classes > 4) return -1;
+  float* range = new float[G];
+  int64_t* idx = new int64_t[G];
+  int64_t* tmp = new int64_t[G];
+  for (int64_t g = 0; g < G; ++g) {
+    range[g] = gmax[g] - gmin[g];
+    idx[g] = g;
+  }
+  merge_sort_by_range(range, idx, tmp, 0, G);
+  for (int64_t r = 0; r < G; ++r) out_bits[idx[r]] = classes[(r * n_classes) / G];
+  delete[] range;
+  delete[] idx;
+  delete[] tmp;
+  return 0;
+}
+
 // Plan: words per group w_g = ceil(n_g * b_g / 32) and their exclusive scan.
 // off may be null.  Returns the total word count, or -1 for bad arguments.
 // (The paper only says packed values are concatenated, Sec. 3.3; locating a

@@ -31,6 +31,9 @@ def lib():
         L.daf_oracle_widen.argtypes = [vp, c.c_int, i64, vp]
         L.daf_oracle_narrow.argtypes = [vp, c.c_int, i64, vp]
         L.daf_oracle_minmax.argtypes = [vp, c.c_int, i64, vp]
+        L.daf_oracle_group_minmax.argtypes = [vp, c.c_int, i64, i32, vp, vp]
+        L.daf_oracle_select_bits.argtypes = [vp, vp, i64, vp, i32, vp]
+        L.daf_oracle_select_bits.restype = c.c_int
         L.daf_oracle_plan.argtypes = [i64, i32, vp, i64, vp]
         L.daf_oracle_plan.restype = i64
         L.daf_oracle_quantize_pack.argtypes = [vp, c.c_int, i64, i32, vp, i64, u64, vp, vp, vp, vp]
@@ -93,6 +96,27 @@ def minmax(x: np.ndarray, dtype: int) -> np.ndarray:
     x = np.ascontiguousarray(x.reshape(-1), dtype=_NP[dtype])
     out = np.empty(2, dtype=np.float32)
     lib().daf_oracle_minmax(_p(x), dtype, x.size, _p(out))
+    return out
+
+
+def group_minmax(x: np.ndarray, dtype: int, gs: int):
+    """Per-group (min[G], max[G]) as float32."""
+    x = np.ascontiguousarray(x.reshape(-1), dtype=_NP[dtype])
+    G = (x.size + gs - 1) // gs
+    mn = np.empty(G, dtype=np.float32)
+    mx = np.empty(G, dtype=np.float32)
+    lib().daf_oracle_group_minmax(_p(x), dtype, x.size, gs, _p(mn), _p(mx))
+    return mn, mx
+
+
+def select_bits(gmin: np.ndarray, gmax: np.ndarray, classes) -> np.ndarray:
+    """Width per group by rank quantiles of the range (smallest range -> classes[0])."""
+    gmin = np.ascontiguousarray(gmin, dtype=np.float32)
+    gmax = np.ascontiguousarray(gmax, dtype=np.float32)
+    cl = np.ascontiguousarray(classes, dtype=np.uint8)
+    out = np.empty(gmin.size, dtype=np.uint8)
+    if lib().daf_oracle_select_bits(_p(gmin), _p(gmax), gmin.size, _p(cl), cl.size, _p(out)) != 0:
+        raise ValueError("daf_oracle_select_bits rejected the arguments")
     return out
 
 

@@ -1,0 +1,77 @@
+"""Pins for the oracle's per-group statistics and the rank-quantile width rule."""
+import numpy as np
+import pytest
+
+from daf_inputs import bits_by_range_quantiles, make_config, to_numpy_bits
+from oracle import daf_oracle as orc
+
+
+@pytest.mark.parametrize("dtype", [orc.F32, orc.F16, orc.BF16])
+@pytest.mark.parametrize("n,gs", [(64, 32), (1000, 96), (4096 + 5, 128), (777, 1024)])
+def test_group_minmax_against_numpy(dtype, n, gs):
+    rng = np.random.default_rng(n + gs)
+    xf = (rng.standard_normal(n) * 3).astype(np.float32)
+    x = xf if dtype == orc.F32 else orc.narrow(xf, dtype)
+    w = orc.widen(x, dtype)
+    mn, mx = orc.group_minmax(x, dtype, gs)
+    G = (n + gs - 1) // gs
+    assert mn.size == G
+    for g in range(G):
+        seg = w[g * gs:min((g + 1) * gs, n)]
+        assert mn[g] == seg.min() and mx[g] == seg.max()
+    # the quantizer's stored min is the same statistic
+    _, qmn, qsc, _ = orc.quantize_pack(x, dtype, gs, [8], 0)
+    assert np.array_equal(qmn.view(np.uint32), mn.view(np.uint32))
+
+
+def test_group_minmax_zero_is_positive():
+    x = np.zeros(64, dtype=np.float32)
+    x[::3] = -0.0
+    mn, mx = orc.group_minmax(x, orc.F32, 32)
+    assert not mn.view(np.uint32).any() and not mx.view(np.uint32).any()
+
+
+def lexsort_rule(gmin, gmax, classes):
+    """The rule written with numpy's lexsort (an independent library sort)."""
+    rng = gmax.astype(np.float32) - gmin.astype(np.float32)
+    G = rng.size
+    order = np.lexsort((np.arange(G), rng))
+    rank = np.empty(G, dtype=np.int64)
+    rank[order] = np.arange(G)
+    return np.asarray(classes, np.uint8)[(rank * len(classes)) // G]
+
+
+@pytest.mark.parametrize("G", [1, 2, 3, 4, 5, 7, 64, 1000, 4097, 100_003])
+@pytest.mark.parametrize("classes", [(1, 2, 4, 8), (2, 4, 8), (4, 8), (2,)])
+def test_select_bits_against_lexsort(G, classes):
+    rng = np.random.default_rng(G)
+    gmin = rng.standard_normal(G).astype(np.float32)
+    gmax = gmin + np.abs(rng.standard_normal(G)).astype(np.float32)
+    assert np.array_equal(orc.select_bits(gmin, gmax, classes), lexsort_rule(gmin, gmax, classes))
+
+
+@pytest.mark.parametrize("classes", [(1, 2, 4, 8), (2, 4, 8)])
+def test_select_bits_with_many_ties(classes):
+    """Equal ranges are ordered by group index; constant (range 0) groups are the common case."""
+    rng = np.random.default_rng(9)
+    G = 10_007
+    gmin = np.zeros(G, dtype=np.float32)
+    gmax = rng.choice([0.0, 0.0, 0.0, 0.5, 1.0, 1.0, 2.0], G).astype(np.float32)
+    got = orc.select_bits(gmin, gmax, classes)
+    assert np.array_equal(got, lexsort_rule(gmin, gmax, classes))
+    # class sizes are the equal-count split whatever the ties
+    C = len(classes)
+    want_counts = np.bincount((np.arange(G) * C) // G, minlength=C)
+    assert np.array_equal(np.array([(got == c).sum() for c in classes]), want_counts)
+    # all-equal keys: classes follow the group index
+    same = orc.select_bits(np.zeros(G, np.float32), np.ones(G, np.float32), classes)
+    assert np.array_equal(same, np.asarray(classes, np.uint8)[(np.arange(G) * C) // G])
+
+
+def test_select_bits_reproduces_the_benchmark_workloads():
+    """The generators' own width assignment (numpy) equals the oracle's rule on the oracle's
+    per-group statistics."""
+    for cfg, scale, classes in ((3, 1 / 16, (1, 2, 4, 8)), (5, 1 / 16, (2, 4, 8))):
+        (w,) = make_config(cfg, scale)
+        mn, mx = orc.group_minmax(to_numpy_bits(w.x), w.dtype, w.group_size)
+        assert np.array_equal(orc.select_bits(mn, mx, classes), w.bits)
