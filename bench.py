@@ -46,6 +46,9 @@ def parse():
     ap.add_argument("--minmax", action="store_true",
                     help="time daf_minmax (whole-tensor reduction, both methods) on the paper's two shapes "
                          "and on the default activation instead of the quantize/dequantize step")
+    ap.add_argument("--device-widths", action="store_true",
+                    help="for a per-group-width configuration (3 or 5): time the device-side sequence "
+                         "daf_group_minmax -> daf_select_bits -> daf_plan that produces the widths and offsets")
     ap.add_argument("--group-size", type=int, default=None,
                     help="override the group size of a uniform-width configuration; 0 = one group per "
                          "tensor (the paper's per-tensor statistics)")
@@ -127,6 +130,46 @@ def main():
             res.append(row)
         print(json.dumps({"metric": "whole-tensor min/max reduction time per call", "unit": "us", "n_gpus": 1,
                           "data": "synthetic", "results": res}))
+        return
+
+    if args.device_widths:
+        (w,) = make_config(args.config)
+        classes = {3: (1, 2, 4, 8), 5: (2, 4, 8)}[args.config]
+        x = w.x.reshape(-1).to(dev)
+        stats_plan = daf.daf_plan(tuple(w.x.shape), w.group_size, 8)
+        G = stats_plan.num_groups
+        mn, mx = torch.empty(G, device=dev), torch.empty(G, device=dev)
+        bits = torch.empty(G, dtype=torch.uint8, device=dev)
+        ws = daf.daf_select_bits_workspace(G)
+
+        def timed(fn, reps):
+            for _ in range(args.warmup):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) * 1e3 / reps
+
+        t_stats = timed(lambda: daf.daf_group_minmax(stats_plan, x, mn, mx), args.steps)
+        t_select = timed(lambda: daf.daf_select_bits(mn, mx, classes, bits, ws), args.steps)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(10):
+            daf.daf_plan(tuple(w.x.shape), w.group_size, bits).destroy()
+        t_plan = (time.perf_counter() - t) * 1e6 / 10
+        ok = bool((bits.cpu().numpy() == w.bits).all())
+        stats_bytes = w.numel * w.x.element_size() + 8 * G
+        print(json.dumps({"metric": "device-side width selection", "unit": "us", "n_gpus": 1, "data": "synthetic",
+                          "config": {"workload": CONFIG_NAMES[args.config], "groups": G},
+                          "group_minmax_us": round(t_stats, 2),
+                          "group_minmax_GBps": round(stats_bytes / t_stats / 1e3, 1),
+                          "group_minmax_frac_of_8TBps": round(stats_bytes / t_stats / 1e3 / HBM_PEAK_GBPS, 4),
+                          "select_bits_us": round(t_select, 2), "plan_us_with_sync": round(t_plan, 1),
+                          "widths_match_generator": ok}))
         return
 
     workloads = make_config(args.config)

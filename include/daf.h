@@ -171,6 +171,38 @@ int daf_minmax_workspace_init(void* workspace, void* stream);
 int daf_minmax(const void* x, daf_dtype_t dtype, int64_t n, int method, void* workspace,
                float* out_minmax, void* stream);
 
+/* ---- statistics for a width controller, and a width rule on the device -------------------
+ *
+ * daf_group_minmax -- per-group minimum and maximum of x (the statistics of Eq. 1, per
+ * group; the reductions a controller needs before it can choose widths, Sec. 3.2), each with
+ * a zero stored as +0.  Same grouping, dtypes and alignment rules as daf_quantize_pack; the
+ * plan supplies shape and group size (its widths are not used).
+ *
+ *   out_min, out_max   DEVICE, G floats each.
+ *
+ * daf_select_bits -- widths by rank quantiles of the range: groups are ranked by
+ * (max - min in binary32, group index) ascending and rank r receives
+ * classes[floor(r * n_classes / G)], so the smallest ranges get classes[0].  This is the rule
+ * the benchmark workloads use in place of the paper's importance-driven controller
+ * (Sec. 3.4.1); the result can be passed to daf_plan as its DEVICE bits array.
+ *
+ *   group_min, group_max   DEVICE, G floats each (e.g. from daf_group_minmax).
+ *   classes, n_classes     HOST, 1..4 widths, each in {1,2,4,8}.
+ *   out_bits               DEVICE, G bytes.
+ *   workspace              DEVICE, daf_select_bits_workspace_bytes(G) bytes, 16-byte aligned;
+ *                          contents need no preparation and are garbage afterwards.
+ *
+ * Both calls only enqueue work on `stream`.
+ * Errors: DAF_EINVAL (null/misaligned pointer, G < 1, bad class count or width),
+ * DAF_EUNSUPPORTED (dtype; G >= 2^32), DAF_EDEVICE.
+ */
+int daf_group_minmax(const daf_plan_t* plan, const void* x, daf_dtype_t dtype,
+                     float* out_min, float* out_max, void* stream);
+int64_t daf_select_bits_workspace_bytes(int64_t num_groups);
+int daf_select_bits(const float* group_min, const float* group_max, int64_t num_groups,
+                    const uint8_t* classes, int32_t n_classes, uint8_t* out_bits,
+                    void* workspace, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

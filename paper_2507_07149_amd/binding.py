@@ -53,6 +53,12 @@ def load_library():
     L.daf_quantize_pack.restype = c.c_int
     L.daf_unpack_dequantize.argtypes = [vp, vp, vp, vp, vp, vp, c.c_int, vp]
     L.daf_unpack_dequantize.restype = c.c_int
+    L.daf_group_minmax.argtypes = [vp, vp, c.c_int, vp, vp, vp]
+    L.daf_group_minmax.restype = c.c_int
+    L.daf_select_bits_workspace_bytes.argtypes = [i64]
+    L.daf_select_bits_workspace_bytes.restype = i64
+    L.daf_select_bits.argtypes = [vp, vp, i64, vp, i32, vp, vp, vp]
+    L.daf_select_bits.restype = c.c_int
     L.daf_minmax_workspace_bytes.restype = i64
     L.daf_minmax_workspace_init.argtypes = [vp, vp]
     L.daf_minmax_workspace_init.restype = c.c_int
@@ -170,3 +176,25 @@ def daf_minmax(x: torch.Tensor, method: int, workspace: torch.Tensor, out_minmax
                                    out_minmax.data_ptr(), _stream_handle(stream))
     if rc != 0:
         raise DafError(rc, "daf_minmax")
+
+
+def daf_group_minmax(plan: Plan, x: torch.Tensor, out_min: torch.Tensor, out_max: torch.Tensor, stream=None) -> None:
+    rc = load_library().daf_group_minmax(plan.handle, x.data_ptr(), _DTYPE_ID[x.dtype], out_min.data_ptr(),
+                                         out_max.data_ptr(), _stream_handle(stream))
+    if rc != 0:
+        raise DafError(rc, "daf_group_minmax")
+
+
+def daf_select_bits_workspace(num_groups: int, device="cuda:0") -> torch.Tensor:
+    nbytes = int(load_library().daf_select_bits_workspace_bytes(num_groups))
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def daf_select_bits(group_min: torch.Tensor, group_max: torch.Tensor, classes: Sequence[int], out_bits: torch.Tensor,
+                    workspace: torch.Tensor, stream=None) -> None:
+    cl = (ctypes.c_uint8 * len(classes))(*[int(c) for c in classes])
+    rc = load_library().daf_select_bits(group_min.data_ptr(), group_max.data_ptr(), group_min.numel(),
+                                        ctypes.cast(cl, ctypes.c_void_p), len(classes), out_bits.data_ptr(),
+                                        workspace.data_ptr(), _stream_handle(stream))
+    if rc != 0:
+        raise DafError(rc, "daf_select_bits")

@@ -199,4 +199,31 @@ int daf_minmax(const void* x, daf_dtype_t dtype, int64_t n, int method, void* wo
   return e == hipSuccess ? DAF_OK : DAF_EDEVICE;
 }
 
+int daf_group_minmax(const daf_plan_t* plan, const void* x, daf_dtype_t dtype, float* out_min, float* out_max,
+                     void* stream) {
+  if (plan == nullptr || x == nullptr || out_min == nullptr || out_max == nullptr) return DAF_EINVAL;
+  if (!aligned(x, 16) || !aligned(out_min, 4) || !aligned(out_max, 4)) return DAF_EINVAL;
+  if (dtype != DAF_F32 && dtype != DAF_F16 && dtype != DAF_BF16) return DAF_EUNSUPPORTED;
+  const hipError_t e = daf_launch_group_minmax(plan, x, (int)dtype, out_min, out_max, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? DAF_OK : DAF_EDEVICE;
+}
+
+int64_t daf_select_bits_workspace_bytes(int64_t num_groups) {
+  return num_groups < 1 ? -1 : daf_select_bits_workspace_size(num_groups);
+}
+
+int daf_select_bits(const float* group_min, const float* group_max, int64_t num_groups, const uint8_t* classes,
+                    int32_t n_classes, uint8_t* out_bits, void* workspace, void* stream) {
+  if (group_min == nullptr || group_max == nullptr || classes == nullptr || out_bits == nullptr ||
+      workspace == nullptr || num_groups < 1 || n_classes < 1 || n_classes > 4)
+    return DAF_EINVAL;
+  if (!aligned(group_min, 4) || !aligned(group_max, 4) || !aligned(workspace, 16)) return DAF_EINVAL;
+  for (int c = 0; c < n_classes; ++c)
+    if (!valid_width(classes[c])) return DAF_EINVAL;
+  if (num_groups >= (int64_t)1 << 32) return DAF_EUNSUPPORTED;
+  const hipError_t e = daf_launch_select_bits(group_min, group_max, num_groups, classes, n_classes, out_bits,
+                                              workspace, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? DAF_OK : DAF_EDEVICE;
+}
+
 }  // extern "C"

@@ -40,3 +40,9 @@ int64_t daf_minmax_workspace_size(void);
 hipError_t daf_launch_minmax_workspace_init(void* workspace, hipStream_t stream);
 hipError_t daf_launch_minmax(const void* x, int dtype, int64_t n, int method, void* workspace, float* out_minmax,
                              hipStream_t stream);
+
+hipError_t daf_launch_group_minmax(const daf_plan_t* plan, const void* x, int dtype, float* out_min, float* out_max,
+                                   hipStream_t stream);
+int64_t daf_select_bits_workspace_size(int64_t num_groups);
+hipError_t daf_launch_select_bits(const float* gmin, const float* gmax, int64_t num_groups, const uint8_t* classes,
+                                  int n_classes, uint8_t* out_bits, void* workspace, hipStream_t stream);

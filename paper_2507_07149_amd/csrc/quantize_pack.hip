@@ -193,6 +193,64 @@ __device__ __forceinline__ void quantize_chunk(const float (&xf)[ElemTraits<DT>:
   nacc1 = nacc[1];
 }
 
+// Widens the tile's chunks into xf and leaves one (min, max) pair per (load, lane run) segment
+// in stat[load * runs_per_load + run]; a group's segments are consecutive entries.
+template <int DT, int LPG_LOG2>
+__device__ __forceinline__ void tile_minmax(const uint4 (&raw)[TileShape<DT, LPG_LOG2>::kLoads],
+                                            float (&xf)[TileShape<DT, LPG_LOG2>::kLoads][ElemTraits<DT>::kPerLoad],
+                                            float2* stat, int lane) {
+  using S = TileShape<DT, LPG_LOG2>;
+  constexpr int kEpl = S::kEpl;
+  static_assert(S::kLoads % 2 == 0, "loads are reduced in pairs");
+  if constexpr (DT == kF32 && LPG_LOG2 >= 5) {
+    // groups of 32 or 64 lanes: all 16 loads are reduced together (transposed reduction)
+    static_assert(S::kLoads == 16, "transposed reduction takes 16 values");
+    float lmn[16], lmx[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+#pragma unroll
+      for (int e = 0; e < kEpl; ++e) xf[u][e] = chunk_elem<DT>(raw[u], e);
+      lmn[u] = vmin(vmin3(xf[u][0], xf[u][1], xf[u][2]), xf[u][3]);
+      lmx[u] = vmax(vmax3(xf[u][0], xf[u][1], xf[u][2]), xf[u][3]);
+    }
+    float mn[2], mx[2];
+    transposed_minmax16<S::kLaneLog2>(lmn, lmx, mn, mx);
+    if ((lane & 3) == 0) {
+      if (LPG_LOG2 >= 6) {
+        stat[(lane >> 2) & 15] = make_float2(mn[0], mx[0]);
+      } else {
+        const int u = (lane >> 2) & 7, seg = lane >> 5;
+        stat[u * 2 + seg] = make_float2(mn[0], mx[0]);
+        stat[(u + 8) * 2 + seg] = make_float2(mn[1], mx[1]);
+      }
+    }
+  } else {
+    // two loads at a time so that four independent DPP chains interleave
+#pragma unroll
+    for (int u = 0; u < S::kLoads; u += 2) {
+      float mn[2], mx[2];
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+#pragma unroll
+        for (int e = 0; e < kEpl; ++e) xf[u + h][e] = chunk_elem<DT>(raw[u + h], e);
+        const float(&v)[kEpl] = xf[u + h];
+        if (kEpl == 4) {
+          mn[h] = vmin(vmin3(v[0], v[1], v[2]), v[3]);
+          mx[h] = vmax(vmax3(v[0], v[1], v[2]), v[3]);
+        } else {
+          mn[h] = vmin(vmin3(vmin3(vmin3(v[0], v[1], v[2]), v[3], v[4 % kEpl]), v[5 % kEpl], v[6 % kEpl]), v[7 % kEpl]);
+          mx[h] = vmax(vmax3(vmax3(vmax3(v[0], v[1], v[2]), v[3], v[4 % kEpl]), v[5 % kEpl], v[6 % kEpl]), v[7 % kEpl]);
+        }
+      }
+      seg_minmax_x2<S::kLaneLog2>(mn[0], mx[0], mn[1], mx[1]);
+      if ((lane & (S::kLpg - 1)) == S::kLpg - 1) {
+        stat[u * S::kGpl + (lane >> S::kLaneLog2)] = make_float2(mn[0], mx[0]);
+        stat[(u + 1) * S::kGpl + (lane >> S::kLaneLog2)] = make_float2(mn[1], mx[1]);
+      }
+    }
+  }
+}
+
 // B = 1, 2, 4, 8: every group has that width (offsets are computed).  B = 0: per-group widths
 // from `bits`, offsets from `off`.
 // One tile per wave; the hardware schedules the waves.  (A looping variant in which a wave
@@ -258,59 +316,14 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_tile(
 
     // 3. per-group min/max: in-lane over the chunk, then across the group's lanes
     float xf[S::kLoads][kEpl];
-    static_assert(S::kLoads % 2 == 0, "loads are reduced in pairs");
     if constexpr (EXT) {
 #pragma unroll
       for (int u = 0; u < S::kLoads; ++u) {
 #pragma unroll
         for (int e = 0; e < kEpl; ++e) xf[u][e] = chunk_elem<DT>(raw[u], e);
       }
-    } else if constexpr (DT == kF32 && LPG_LOG2 >= 5) {
-      // groups of 32 or 64 lanes: all 16 loads are reduced together (transposed reduction)
-      static_assert(S::kLoads == 16, "transposed reduction takes 16 values");
-      float lmn[16], lmx[16];
-#pragma unroll
-      for (int u = 0; u < 16; ++u) {
-#pragma unroll
-        for (int e = 0; e < kEpl; ++e) xf[u][e] = chunk_elem<DT>(raw[u], e);
-        lmn[u] = vmin(vmin3(xf[u][0], xf[u][1], xf[u][2]), xf[u][3]);
-        lmx[u] = vmax(vmax3(xf[u][0], xf[u][1], xf[u][2]), xf[u][3]);
-      }
-      float mn[2], mx[2];
-      transposed_minmax16<S::kLaneLog2>(lmn, lmx, mn, mx);
-      if ((lane & 3) == 0) {
-        if (LPG_LOG2 >= 6) {
-          lds.stat[(lane >> 2) & 15] = make_float2(mn[0], mx[0]);
-        } else {
-          const int u = (lane >> 2) & 7, seg = lane >> 5;
-          lds.stat[u * 2 + seg] = make_float2(mn[0], mx[0]);
-          lds.stat[(u + 8) * 2 + seg] = make_float2(mn[1], mx[1]);
-        }
-      }
     } else {
-      // two loads at a time so that four independent DPP chains interleave
-#pragma unroll
-      for (int u = 0; u < S::kLoads; u += 2) {
-        float mn[2], mx[2];
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-#pragma unroll
-          for (int e = 0; e < kEpl; ++e) xf[u + h][e] = chunk_elem<DT>(raw[u + h], e);
-          const float(&v)[kEpl] = xf[u + h];
-          if (kEpl == 4) {
-            mn[h] = vmin(vmin3(v[0], v[1], v[2]), v[3]);
-            mx[h] = vmax(vmax3(v[0], v[1], v[2]), v[3]);
-          } else {
-            mn[h] = vmin(vmin3(vmin3(vmin3(v[0], v[1], v[2]), v[3], v[4 % kEpl]), v[5 % kEpl], v[6 % kEpl]), v[7 % kEpl]);
-            mx[h] = vmax(vmax3(vmax3(vmax3(v[0], v[1], v[2]), v[3], v[4 % kEpl]), v[5 % kEpl], v[6 % kEpl]), v[7 % kEpl]);
-          }
-        }
-        seg_minmax_x2<S::kLaneLog2>(mn[0], mx[0], mn[1], mx[1]);
-        if ((lane & (S::kLpg - 1)) == S::kLpg - 1) {
-          lds.stat[u * S::kGpl + (lane >> S::kLaneLog2)] = make_float2(mn[0], mx[0]);
-          lds.stat[(u + 1) * S::kGpl + (lane >> S::kLaneLog2)] = make_float2(mn[1], mx[1]);
-        }
-      }
+      tile_minmax<DT, LPG_LOG2>(raw, xf, lds.stat, lane);
     }
     wave_lds_sync();
 
@@ -643,6 +656,129 @@ hipError_t launch_big(const daf_plan_t* p, const void* x, uint32_t seed_lo, uint
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------
+// Statistics only: per-group min and max, for a controller that chooses the widths.
+// ------------------------------------------------------------------------------------------
+template <int DT, int LPG_LOG2>
+__global__ __launch_bounds__(kThreads) void k_group_minmax_tile(const u32x4* __restrict__ x, int64_t n_tiles,
+                                                                float* __restrict__ out_min,
+                                                                float* __restrict__ out_max) {
+  using S = TileShape<DT, LPG_LOG2>;
+  __shared__ float2 stat_all[kWavesPerBlock][kWave];
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t tile = (int64_t)blockIdx.x * kWavesPerBlock + wave_in_block;
+  if (tile >= n_tiles) return;
+  float2* stat = stat_all[wave_in_block];
+  uint4 raw[S::kLoads];
+#pragma unroll
+  for (int u = 0; u < S::kLoads; ++u) {
+    const u32x4 v = __builtin_nontemporal_load(&x[tile * (S::kLoads * kWave) + u * kWave + lane]);
+    raw[u] = make_uint4(v.x, v.y, v.z, v.w);
+  }
+  float xf[S::kLoads][S::kEpl];
+  tile_minmax<DT, LPG_LOG2>(raw, xf, stat, lane);
+  wave_lds_sync();
+  if (lane < S::kGroups) {
+    float2 st = stat[lane * S::kLoadsPerGroup];
+#pragma unroll
+    for (int j = 1; j < S::kLoadsPerGroup; ++j) {
+      const float2 t = stat[lane * S::kLoadsPerGroup + j];
+      st.x = vmin(st.x, t.x);
+      st.y = vmax(st.y, t.y);
+    }
+    out_min[tile * S::kGroups + lane] = st.x + 0.0f;
+    out_max[tile * S::kGroups + lane] = st.y + 0.0f;
+  }
+}
+
+template <int DT>
+__global__ __launch_bounds__(kThreads) void k_group_minmax_group(const void* __restrict__ x, int64_t n, int32_t gs,
+                                                                 int64_t g_begin, int64_t g_end,
+                                                                 float* __restrict__ out_min,
+                                                                 float* __restrict__ out_max) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+  const int64_t n_waves = (int64_t)gridDim.x * kWavesPerBlock;
+  for (int64_t g = g_begin + wave; g < g_end; g += n_waves) {
+    const int64_t lo = g * (int64_t)gs;
+    const int64_t len = (lo + gs <= n) ? gs : (n - lo);
+    float mn = load_elem<DT>(x, lo), mx = mn;
+    for (int64_t j = lane; j < len; j += kWave) {
+      const float v = load_elem<DT>(x, lo + j);
+      mn = vmin(mn, v);
+      mx = vmax(mx, v);
+    }
+    float mn2 = mn, mx2 = mx;
+    seg_minmax_x2<6>(mn, mx, mn2, mx2);
+    if (lane == kWave - 1) {
+      out_min[g] = mn + 0.0f;
+      out_max[g] = mx + 0.0f;
+    }
+  }
+}
+
+__global__ void k_stat_to_outputs(const float2* __restrict__ stat, int64_t num_groups, float* __restrict__ out_min,
+                                  float* __restrict__ out_max) {
+  const int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (g < num_groups) {
+    out_min[g] = stat[g].x + 0.0f;
+    out_max[g] = stat[g].y + 0.0f;
+  }
+}
+
+template <int DT>
+hipError_t launch_group_minmax(const daf_plan_t* p, const void* x, float* out_min, float* out_max,
+                               hipStream_t stream) {
+  constexpr int kEpl = ElemTraits<DT>::kPerLoad;
+  if (p->d_big_scratch != nullptr) {          // groups longer than a tile: tile pairs, then per-group reduce
+    const int64_t n_full_tiles = p->n / kBigTile;
+    const int64_t n_partials = n_full_tiles + ((n_full_tiles * kBigTile < p->n) ? 1 : 0);
+    const int64_t tpg = (p->num_groups == 1) ? n_partials : p->group_size / kBigTile;
+    float2* partial = reinterpret_cast<float2*>(p->d_big_scratch);
+    float2* stat = partial + n_partials;
+    hipLaunchKernelGGL((k_tile_minmax<DT>), dim3((unsigned)((n_partials + kWavesPerBlock - 1) / kWavesPerBlock)),
+                       dim3(kThreads), 0, stream, x, n_full_tiles, p->n, partial);
+    hipLaunchKernelGGL(k_group_reduce, dim3((unsigned)p->num_groups), dim3(kReduceThreads), 0, stream, partial,
+                       n_partials, tpg, stat);
+    hipLaunchKernelGGL(k_stat_to_outputs, dim3((unsigned)((p->num_groups + 255) / 256)), dim3(256), 0, stream, stat,
+                       p->num_groups, out_min, out_max);
+    return hipGetLastError();
+  }
+  const int64_t full_groups = p->n / p->group_size;
+  int64_t fast_groups = 0;
+  const int32_t lpg = p->group_size / kEpl;
+  if (p->group_size % kEpl == 0 && lpg >= 4 && (lpg & (lpg - 1)) == 0) {
+#define DAF_CASE(LOG2)                                                                                          \
+  case (1 << LOG2):                                                                                             \
+    if constexpr (TileShape<DT, LOG2>::kValid) {                                                                \
+      const int64_t n_tiles = full_groups / TileShape<DT, LOG2>::kGroups;                                       \
+      fast_groups = n_tiles * TileShape<DT, LOG2>::kGroups;                                                     \
+      if (n_tiles > 0)                                                                                          \
+        hipLaunchKernelGGL((k_group_minmax_tile<DT, LOG2>), dim3((unsigned)((n_tiles + kWavesPerBlock - 1) /    \
+                           kWavesPerBlock)), dim3(kThreads), 0, stream, static_cast<const u32x4*>(x), n_tiles,  \
+                           out_min, out_max);                                                                   \
+    }                                                                                                           \
+    break;
+    switch (lpg) {
+      DAF_CASE(2) DAF_CASE(3) DAF_CASE(4) DAF_CASE(5) DAF_CASE(6)
+      DAF_CASE(7) DAF_CASE(8) DAF_CASE(9) DAF_CASE(10)
+      default: break;
+    }
+#undef DAF_CASE
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  const int64_t rest = p->num_groups - fast_groups;
+  if (rest > 0) {
+    int64_t blocks = (rest + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL((k_group_minmax_group<DT>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, x, p->n,
+                       p->group_size, fast_groups, p->num_groups, out_min, out_max);
+  }
+  return hipGetLastError();
+}
+
 template <int DT>
 hipError_t launch_dtype(const daf_plan_t* p, const void* x, uint64_t seed, uint32_t* out_words, float* out_min,
                         float* out_scale, hipStream_t stream) {
@@ -690,6 +826,16 @@ hipError_t launch_dtype(const daf_plan_t* p, const void* x, uint64_t seed, uint3
 }
 
 }  // namespace
+
+hipError_t daf_launch_group_minmax(const daf_plan_t* plan, const void* x, int dtype, float* out_min, float* out_max,
+                                   hipStream_t stream) {
+  switch (dtype) {
+    case daf::kF32:  return launch_group_minmax<daf::kF32>(plan, x, out_min, out_max, stream);
+    case daf::kF16:  return launch_group_minmax<daf::kF16>(plan, x, out_min, out_max, stream);
+    case daf::kBF16: return launch_group_minmax<daf::kBF16>(plan, x, out_min, out_max, stream);
+    default: return hipErrorInvalidValue;
+  }
+}
 
 hipError_t daf_launch_quantize_pack(const daf_plan_t* plan, const void* x, int dtype, uint64_t seed,
                                     uint32_t* out_words, float* out_min, float* out_scale,

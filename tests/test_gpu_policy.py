@@ -1,0 +1,121 @@
+"""GPU parity of the controller-side calls: per-group min/max and the rank-quantile width rule,
+and the whole device-side sequence statistics -> widths -> plan -> quantize."""
+import numpy as np
+import pytest
+import torch
+
+from daf_inputs import BF16, F16, F32, make_config, to_numpy_bits, torch_dtype
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import paper_2507_07149_amd as daf
+    from oracle import daf_oracle as orc
+    assert torch.cuda.is_available()
+    return daf, orc
+
+
+def _group_minmax(daf, x, gs):
+    plan = daf.daf_plan(tuple(x.shape), gs, 8)
+    G = plan.num_groups
+    mn = torch.full((G,), float("nan"), device="cuda:0")
+    mx = torch.full((G,), float("nan"), device="cuda:0")
+    daf.daf_group_minmax(plan, x.cuda(), mn, mx)
+    torch.cuda.synchronize()
+    return mn, mx
+
+
+@pytest.mark.parametrize("dtype", [F32, F16, BF16])
+@pytest.mark.parametrize("gs", [32, 64, 96, 128, 256, 1024, 4096, 8192, 12320, 1 << 20])
+def test_group_minmax_matrix(env, dtype, gs):
+    daf, orc = env
+    n = 4096 * 11 + 3 * gs + 29 if gs < (1 << 20) else 4096 * 40 + 77
+    g = torch.Generator().manual_seed(gs)
+    x = (torch.randn(n, generator=g) * 2).to(torch_dtype(dtype))
+    x[5] = 0.0
+    print("case", dtype, gs, n, flush=True)
+    mn, mx = _group_minmax(daf, x, gs)
+    omn, omx = orc.group_minmax(to_numpy_bits(x), dtype, gs)
+    assert np.array_equal(mn.cpu().numpy().view(np.uint32), omn.view(np.uint32))
+    assert np.array_equal(mx.cpu().numpy().view(np.uint32), omx.view(np.uint32))
+
+
+def _select(daf, gmin, gmax, classes):
+    G = gmin.numel()
+    out = torch.full((G,), 255, dtype=torch.uint8, device="cuda:0")
+    ws = daf.daf_select_bits_workspace(G)
+    daf.daf_select_bits(gmin, gmax, classes, out, ws)
+    torch.cuda.synchronize()
+    return out
+
+
+@pytest.mark.parametrize("G", [1, 2, 3, 4, 5, 7, 255, 256, 2048, 2049, 100_003, 1_500_000])
+@pytest.mark.parametrize("classes", [(1, 2, 4, 8), (2, 4, 8), (4, 8), (2,)])
+def test_select_bits_random(env, G, classes):
+    daf, orc = env
+    rng = np.random.default_rng(G)
+    gmin = rng.standard_normal(G).astype(np.float32)
+    gmax = gmin + np.abs(rng.standard_normal(G)).astype(np.float32) * 10 ** rng.uniform(-3, 3, G).astype(np.float32)
+    got = _select(daf, torch.from_numpy(gmin).cuda(), torch.from_numpy(gmax).cuda(), classes)
+    assert np.array_equal(got.cpu().numpy(), orc.select_bits(gmin, gmax, classes)), (G, classes)
+
+
+@pytest.mark.parametrize("classes", [(1, 2, 4, 8), (2, 4, 8)])
+def test_select_bits_ties(env, classes):
+    daf, orc = env
+    rng = np.random.default_rng(4)
+    for G, choices in ((10_007, [0.0, 0.0, 0.0, 0.5, 1.0, 1.0, 2.0]), (70_001, [1.0]), (5000, [0.0, 3.0]),
+                       (300_000, [0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 1.0])):
+        gmin = np.zeros(G, dtype=np.float32)
+        gmax = rng.choice(choices, G).astype(np.float32)
+        got = _select(daf, torch.from_numpy(gmin).cuda(), torch.from_numpy(gmax).cuda(), classes)
+        assert np.array_equal(got.cpu().numpy(), orc.select_bits(gmin, gmax, classes)), (G, choices)
+
+
+@pytest.mark.timeout(400)
+@pytest.mark.parametrize("cfg,scale,classes", [(3, 1 / 8, (1, 2, 4, 8)), (5, 1 / 16, (2, 4, 8)),
+                                               (3, 1.0, (1, 2, 4, 8)), (5, 1.0, (2, 4, 8))])
+def test_device_side_width_selection_reproduces_the_workloads(env, cfg, scale, classes):
+    """statistics -> widths on the device give the generator's widths; planning and quantizing
+    with them gives the oracle's packed output (sampled at full size)."""
+    daf, orc = env
+    from tests import hip_harness as H
+    (w,) = make_config(cfg, scale)
+    print("case", w.name, tuple(w.x.shape), flush=True)
+    x = w.x.reshape(-1).cuda()
+    stats_plan = daf.daf_plan(tuple(w.x.shape), w.group_size, 8)
+    G = stats_plan.num_groups
+    mn = torch.empty(G, device="cuda:0")
+    mx = torch.empty(G, device="cuda:0")
+    bits = torch.empty(G, dtype=torch.uint8, device="cuda:0")
+    ws = daf.daf_select_bits_workspace(G)
+    daf.daf_group_minmax(stats_plan, x, mn, mx)
+    daf.daf_select_bits(mn, mx, classes, bits, ws)
+    plan = daf.daf_plan(tuple(w.x.shape), w.group_size, bits)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits.cpu().numpy(), w.bits)
+    words = torch.empty(plan.packed_words, dtype=torch.int32, device="cuda:0")
+    sc = torch.empty(G, device="cuda:0")
+    mn2 = torch.empty(G, device="cuda:0")
+    xh = torch.empty_like(x)
+    daf.daf_quantize_pack(plan, x, w.seed, words, mn2, sc)
+    daf.daf_unpack_dequantize(plan, words, mn2, sc, xh)
+    torch.cuda.synchronize()
+    assert torch.equal(mn, mn2)
+    res = H.HipResult(plan, words, mn2, sc, xh, bits)
+    if scale < 1.0:
+        H.assert_full_parity(w, res)
+    else:
+        H.assert_sampled_parity(w, res, n_samples=400, seed=cfg)
+
+
+def test_argument_errors(env):
+    daf, _ = env
+    mn = torch.zeros(64, device="cuda:0")
+    out = torch.zeros(64, dtype=torch.uint8, device="cuda:0")
+    ws = daf.daf_select_bits_workspace(64)
+    for bad in ((3,), (1, 2, 4, 8, 8), ()):
+        with pytest.raises(daf.DafError):
+            daf.daf_select_bits(mn, mn, bad, out, ws)
