@@ -232,3 +232,36 @@ def test_runs_on_a_side_stream(H):
         daf.daf_unpack_dequantize(ref.plan, words, mn, sc, xh, stream=s)
     s.synchronize()
     assert torch.equal(words, ref.words) and torch.equal(mn, ref.mn) and torch.equal(xh, ref.xhat)
+
+
+def test_calls_can_be_captured_in_a_hip_graph(H):
+    """daf_quantize_pack / daf_unpack_dequantize only enqueue kernels (no allocation, memset or
+    synchronization), so a caller may capture them; every replay must equal the eager result,
+    also after the input changed between replays."""
+    import paper_2507_07149_amd as daf
+    ws = [_workload(F32, 4096 * 40 + 300, 256, 2, seed=3), _workload(BF16, 4096 * 33 + 64, 64, "mixed", seed=4),
+          _workload(F32, 4096 * 24, 4096 * 8, 4, seed=5)]
+    state = []
+    for w in ws:
+        r = H.run_hip(w)                      # eager reference; also builds the plan
+        x = w.x.reshape(-1).cuda()
+        state.append((w, r, x, torch.empty_like(r.words), torch.empty_like(r.mn), torch.empty_like(r.scale),
+                      torch.empty_like(x)))
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for w, r, x, words, mn, sc, xh in state:
+            daf.daf_quantize_pack(r.plan, x, w.seed, words, mn, sc)
+            daf.daf_unpack_dequantize(r.plan, words, mn, sc, xh)
+    for replay in range(3):
+        if replay == 1:                        # new input values, same buffers
+            for w, r, x, *_ in state:
+                x.mul_(-1.5)
+        graph.replay()
+        torch.cuda.synchronize()
+        for w, r, x, words, mn, sc, xh in state:
+            if replay == 0:
+                assert torch.equal(words, r.words) and torch.equal(mn, r.mn) and torch.equal(xh, r.xhat)
+            else:
+                w2 = Workload(w.name, x.cpu().reshape(w.x.shape), w.dtype, w.group_size, w.bits, w.seed)
+                H.assert_full_parity(w2, H.HipResult(r.plan, words, mn, sc, xh, None))
