@@ -329,6 +329,30 @@ int daf_oracle_quantize_pack(const void* x, int dtype, int64_t n, int32_t gs,
   return rc;
 }
 
+// Importance metrics of a quantized activation, per group, in double precision (Sec. 3.2 names
+// quantization error and tensor magnitude among the reductions a controller needs):
+//   metrics[2g]   = sum over the group of (x - xhat)^2, xhat = fma(code, scale, min) in binary32
+//                   (the dequantized value before it is narrowed to a 16-bit dtype)
+//   metrics[2g+1] = sum over the group of x^2
+// codes, min and scale are the outputs of the quantizer.
+void daf_oracle_group_metrics(const void* x, int dtype, int64_t n, int32_t gs, const uint8_t* codes,
+                              const float* mn, const float* scale, double* metrics) {
+  const int64_t G = num_groups(n, gs);
+  for (int64_t g = 0; g < G; ++g) {
+    const int64_t lo = g * gs, len = group_len(n, gs, g);
+    double err = 0.0, mag = 0.0;
+    for (int64_t j = 0; j < len; ++j) {
+      const float xv = load_elem(x, dtype, lo + j);
+      const float xh = std::fmaf(static_cast<float>(codes[lo + j]), scale[g], mn[g]);
+      const double d = static_cast<double>(xv) - static_cast<double>(xh);
+      err += d * d;
+      mag += static_cast<double>(xv) * static_cast<double>(xv);
+    }
+    metrics[2 * g] = err;
+    metrics[2 * g + 1] = mag;
+  }
+}
+
 // Unpack (Algorithm 2's extraction rule, generalised from 4 bits to b) and
 // dequantize (inverse of Eq. 1) groups [g_begin, g_end).
 int daf_oracle_unpack_dequantize_range(const uint32_t* words, const float* mn, const float* scale,

@@ -31,6 +31,7 @@ def lib():
         L.daf_oracle_widen.argtypes = [vp, c.c_int, i64, vp]
         L.daf_oracle_narrow.argtypes = [vp, c.c_int, i64, vp]
         L.daf_oracle_minmax.argtypes = [vp, c.c_int, i64, vp]
+        L.daf_oracle_group_metrics.argtypes = [vp, c.c_int, i64, i32, vp, vp, vp, vp]
         L.daf_oracle_group_minmax.argtypes = [vp, c.c_int, i64, i32, vp, vp]
         L.daf_oracle_select_bits.argtypes = [vp, vp, i64, vp, i32, vp]
         L.daf_oracle_select_bits.restype = c.c_int
@@ -96,6 +97,18 @@ def minmax(x: np.ndarray, dtype: int) -> np.ndarray:
     x = np.ascontiguousarray(x.reshape(-1), dtype=_NP[dtype])
     out = np.empty(2, dtype=np.float32)
     lib().daf_oracle_minmax(_p(x), dtype, x.size, _p(out))
+    return out
+
+
+def group_metrics(x: np.ndarray, dtype: int, gs: int, codes, mn, sc) -> np.ndarray:
+    """float64[G, 2]: per group, sum (x - xhat)^2 and sum x^2."""
+    x = np.ascontiguousarray(x.reshape(-1), dtype=_NP[dtype])
+    G = (x.size + gs - 1) // gs
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    mn = np.ascontiguousarray(mn, dtype=np.float32)
+    sc = np.ascontiguousarray(sc, dtype=np.float32)
+    out = np.empty((G, 2), dtype=np.float64)
+    lib().daf_oracle_group_metrics(_p(x), dtype, x.size, gs, _p(codes), _p(mn), _p(sc), _p(out))
     return out
 
 

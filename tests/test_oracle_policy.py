@@ -75,3 +75,29 @@ def test_select_bits_reproduces_the_benchmark_workloads():
         (w,) = make_config(cfg, scale)
         mn, mx = orc.group_minmax(to_numpy_bits(w.x), w.dtype, w.group_size)
         assert np.array_equal(orc.select_bits(mn, mx, classes), w.bits)
+
+
+@pytest.mark.parametrize("dtype", [orc.F32, orc.F16, orc.BF16])
+def test_group_metrics_against_numpy(dtype):
+    """Quantization error and magnitude per group, recomputed with numpy from the quantizer's
+    codes: xhat is the single rounding to binary32 of code*scale+min evaluated exactly."""
+    rng = np.random.default_rng(40 + dtype)
+    n, gs = 128 * 9 + 50, 128
+    G = (n + gs - 1) // gs
+    bits = rng.choice([1, 2, 4, 8], G).astype(np.uint8)
+    xf = (rng.standard_normal(n) * 2).astype(np.float32)
+    x = xf if dtype == orc.F32 else orc.narrow(xf, dtype)
+    w = orc.widen(x, dtype).astype(np.float64)
+    words, mn, sc, codes = orc.quantize_pack(x, dtype, gs, bits, 6, want_codes=True)
+    got = orc.group_metrics(x, dtype, gs, codes, mn, sc)
+    g = np.arange(n) // gs
+    xhat = (codes.astype(np.float64) * sc.astype(np.float64)[g] + mn.astype(np.float64)[g]).astype(np.float32)
+    err = np.bincount(g, weights=(w - xhat.astype(np.float64)) ** 2, minlength=G)
+    mag = np.bincount(g, weights=w ** 2, minlength=G)
+    assert np.allclose(got[:, 0], err, rtol=1e-12, atol=0) and np.allclose(got[:, 1], mag, rtol=1e-12, atol=0)
+    if dtype == orc.F32:        # for binary32 tensors xhat is exactly what dequantize returns
+        xh, _ = orc.unpack_dequantize(words, mn, sc, bits, n, gs, orc.F32)
+        assert np.array_equal(xh, xhat)
+    # more bits, less error; error bounded by n_g * scale^2
+    lens = np.minimum(gs, n - gs * np.arange(G))
+    assert np.all(got[:, 0] <= lens * sc.astype(np.float64) ** 2 * (1 + 1e-6) + 1e-30)
