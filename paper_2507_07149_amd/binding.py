@@ -53,6 +53,8 @@ def load_library():
     L.daf_quantize_pack.restype = c.c_int
     L.daf_unpack_dequantize.argtypes = [vp, vp, vp, vp, vp, vp, c.c_int, vp]
     L.daf_unpack_dequantize.restype = c.c_int
+    L.daf_quantize_pack_metrics.argtypes = [vp, vp, c.c_int, u64, vp, vp, vp, vp, vp]
+    L.daf_quantize_pack_metrics.restype = c.c_int
     L.daf_group_minmax.argtypes = [vp, vp, c.c_int, vp, vp, vp]
     L.daf_group_minmax.restype = c.c_int
     L.daf_select_bits_workspace_bytes.argtypes = [i64]
@@ -198,3 +200,12 @@ def daf_select_bits(group_min: torch.Tensor, group_max: torch.Tensor, classes: S
                                         workspace.data_ptr(), _stream_handle(stream))
     if rc != 0:
         raise DafError(rc, "daf_select_bits")
+
+
+def daf_quantize_pack_metrics(plan: Plan, x: torch.Tensor, seed: int, out_words: torch.Tensor, out_min: torch.Tensor,
+                              out_scale: torch.Tensor, out_metrics: torch.Tensor, stream=None) -> None:
+    rc = load_library().daf_quantize_pack_metrics(plan.handle, x.data_ptr(), _DTYPE_ID[x.dtype], seed,
+                                                  out_words.data_ptr(), out_min.data_ptr(), out_scale.data_ptr(),
+                                                  out_metrics.data_ptr(), _stream_handle(stream))
+    if rc != 0:
+        raise DafError(rc, "daf_quantize_pack_metrics")

@@ -163,8 +163,24 @@ int daf_quantize_pack(const daf_plan_t* plan, const void* x, daf_dtype_t dtype, 
     return DAF_EINVAL;
   if (!aligned(x, 16) || !aligned(out_words, 4) || !aligned(out_min, 4) || !aligned(out_scale, 4)) return DAF_EINVAL;
   if (dtype != DAF_F32 && dtype != DAF_F16 && dtype != DAF_BF16) return DAF_EUNSUPPORTED;
-  const hipError_t e = daf_launch_quantize_pack(plan, x, (int)dtype, seed, out_words, out_min, out_scale,
+  const hipError_t e = daf_launch_quantize_pack(plan, x, (int)dtype, seed, out_words, out_min, out_scale, nullptr,
                                                 static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? DAF_OK : DAF_EDEVICE;
+}
+
+int daf_quantize_pack_metrics(const daf_plan_t* plan, const void* x, daf_dtype_t dtype, uint64_t seed,
+                              uint32_t* out_words, float* out_min, float* out_scale, float* out_metrics,
+                              void* stream) {
+  if (plan == nullptr || x == nullptr || out_words == nullptr || out_min == nullptr || out_scale == nullptr ||
+      out_metrics == nullptr)
+    return DAF_EINVAL;
+  if (!aligned(x, 16) || !aligned(out_words, 4) || !aligned(out_min, 4) || !aligned(out_scale, 4) ||
+      !aligned(out_metrics, 8))
+    return DAF_EINVAL;
+  if (dtype != DAF_F32 && dtype != DAF_F16 && dtype != DAF_BF16) return DAF_EUNSUPPORTED;
+  if (plan->d_big_scratch != nullptr) return DAF_EUNSUPPORTED;     // groups longer than 4096 elements
+  const hipError_t e = daf_launch_quantize_pack(plan, x, (int)dtype, seed, out_words, out_min, out_scale,
+                                                out_metrics, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? DAF_OK : DAF_EDEVICE;
 }
 

@@ -205,6 +205,33 @@ __device__ __forceinline__ void transposed_minmax16(const float (&mn_in)[16], co
   }
 }
 
+// Sums of two values over aligned runs of 2^LPG_LOG2 lanes (complete in the LAST lane of each
+// run).  Two chains: an instruction reads the register written two instructions earlier, so one
+// s_nop between steps completes the two wait states a DPP read needs.
+#define DAF_SUM2(CTRL)                         \
+  "v_add_f32_dpp %0, %0, %0 " CTRL "\n"        \
+  "v_add_f32_dpp %1, %1, %1 " CTRL "\n"        \
+  "s_nop 0\n"
+template <int LPG_LOG2>
+__device__ __forceinline__ void seg_sum2(float& a, float& b) {
+  static_assert(LPG_LOG2 >= 2 && LPG_LOG2 <= 6, "run length 4..64 lanes");
+  if constexpr (LPG_LOG2 == 2) {
+    asm("s_nop 4\n" DAF_SUM2(DAF_DPP_X1) DAF_SUM2(DAF_DPP_X2) "s_nop 1\n" : "+v"(a), "+v"(b));
+  } else if constexpr (LPG_LOG2 == 3) {
+    asm("s_nop 4\n" DAF_SUM2(DAF_DPP_X1) DAF_SUM2(DAF_DPP_X2) DAF_SUM2(DAF_DPP_HM) "s_nop 1\n" : "+v"(a), "+v"(b));
+  } else if constexpr (LPG_LOG2 == 4) {
+    asm("s_nop 4\n" DAF_SUM2(DAF_DPP_X1) DAF_SUM2(DAF_DPP_X2) DAF_SUM2(DAF_DPP_HM) DAF_SUM2(DAF_DPP_M) "s_nop 1\n"
+        : "+v"(a), "+v"(b));
+  } else if constexpr (LPG_LOG2 == 5) {
+    asm("s_nop 4\n" DAF_SUM2(DAF_DPP_X1) DAF_SUM2(DAF_DPP_X2) DAF_SUM2(DAF_DPP_HM) DAF_SUM2(DAF_DPP_M)
+        DAF_SUM2(DAF_DPP_B15) "s_nop 1\n" : "+v"(a), "+v"(b));
+  } else {
+    asm("s_nop 4\n" DAF_SUM2(DAF_DPP_X1) DAF_SUM2(DAF_DPP_X2) DAF_SUM2(DAF_DPP_HM) DAF_SUM2(DAF_DPP_M)
+        DAF_SUM2(DAF_DPP_B15) DAF_SUM2(DAF_DPP_B31) "s_nop 1\n" : "+v"(a), "+v"(b));
+  }
+}
+#undef DAF_SUM2
+
 // Inclusive prefix sum over the 64 lanes of a wave.
 __device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v) {
 #define DAF_SCAN(CTRL, MASK) v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, MASK, 0xF, false)

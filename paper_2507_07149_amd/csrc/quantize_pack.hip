@@ -71,12 +71,12 @@ __device__ __forceinline__ float load_elem(const void* x, int64_t i) {
   return widen16<DT == kF32 ? kF16 : DT>(static_cast<const uint16_t*>(x)[i]);
 }
 
-template <int DT>
+template <int DT, bool METRICS = false>
 __global__ __launch_bounds__(kThreads) void k_quantize_pack_group(
     const void* __restrict__ x, int64_t n, int32_t gs, int64_t g_begin, int64_t g_end,
     const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, int32_t uniform_bits,
     uint32_t seed_lo, uint32_t seed_hi, uint32_t* __restrict__ words, float* __restrict__ out_min,
-    float* __restrict__ out_scale) {
+    float* __restrict__ out_scale, float2* __restrict__ out_metrics) {
   const int lane = threadIdx.x & (kWave - 1);
   const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
   const int64_t n_waves = (int64_t)gridDim.x * kWavesPerBlock;
@@ -103,6 +103,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_group(
     }
     const uint32_t cpw = 32u / b;                          // codes per word
     const int32_t n_words = (int32_t)(((int64_t)len * b + 31) >> 5);
+    float err = 0.0f, mag = 0.0f;
     for (int32_t t = lane; t < n_words; t += kWave) {
       uint32_t word = 0;
       uint64_t cur_blk = ~0ull;
@@ -119,10 +120,20 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_group(
         const uint32_t slot = (uint32_t)(i % kElemsPerPhilox);
         const uint32_t rw = (slot < 4) ? rnd.x : (slot < 8) ? rnd.y : (slot < 12) ? rnd.z : rnd.w;
         const uint32_t r = (rw >> (8u * (slot & 3u))) & 0xFFu;
-        const int nc = neg_code<true>(load_elem<DT>(x, lo + j), s.mn, s.inv, r);
+        const float xv = load_elem<DT>(x, lo + j);
+        const int nc = neg_code<true>(xv, s.mn, s.inv, r);
         word |= (uint32_t)(-nc) << (32u - b - c * b);
+        if (METRICS) {
+          const float d = xv - __builtin_fmaf((float)(-nc), s.scale, s.mn);
+          err = __builtin_fmaf(d, d, err);
+          mag = __builtin_fmaf(xv, xv, mag);
+        }
       }
       words[woff + t] = word;
+    }
+    if (METRICS) {
+      seg_sum2<6>(err, mag);
+      if (lane == kWave - 1) out_metrics[g] = make_float2(err, mag);
     }
   }
 }
@@ -169,28 +180,46 @@ struct alignas(16) WaveLds {
     uint32_t stage[S::kElems / 4];
   };
   GroupInfo info[kWave];
-  float2 stat[kWave];                   // (min, max) per group, written by the group's last lane
+  float2 stat[kWave];                   // (min, max) per group, written by the group's last lane;
+                                        // later (metrics variant) the group's (error, magnitude) sums
+  float gscale[kWave];                  // scale per group (metrics variant)
 };
 
 // Codes of one 16-byte chunk, accumulated most significant first and NEGATED (the element map
 // yields -code): nacc0 = -(elements 0..3), nacc1 = -(elements 4..7) (16-bit inputs only).
-template <int DT, bool EXACT2>
+//
+// METRICS: also returns this lane's share of the group's importance sums (Sec. 3.2 names
+// quantization error and tensor magnitude): err += (x - xhat)^2 with xhat = fma(code, scale, mn)
+// as the dequantizer computes it, mag += x^2, both in binary32.
+template <int DT, bool EXACT2, bool METRICS = false>
 __device__ __forceinline__ void quantize_chunk(const float (&xf)[ElemTraits<DT>::kPerLoad], float mn,
                                                float invs, uint32_t b, const uint32_t* rnd,
-                                               uint32_t& nacc0, uint32_t& nacc1) {
+                                               uint32_t& nacc0, uint32_t& nacc1, float scale = 0.0f,
+                                               float* err = nullptr, float* mag = nullptr) {
   constexpr int kEpl = ElemTraits<DT>::kPerLoad;
   uint32_t nacc[2] = {0u, 0u};
+  float e2 = 0.0f, m2 = 0.0f;
 #pragma unroll
   for (int q = 0; q < kEpl / 4; ++q) {
     const uint32_t rw = rnd[q];                 // the random bytes of four consecutive elements
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const int nc = neg_code<EXACT2>(xf[q * 4 + e], mn, invs, (rw >> (8 * e)) & 0xFFu);
+      const float xv = xf[q * 4 + e];
+      const int nc = neg_code<EXACT2>(xv, mn, invs, (rw >> (8 * e)) & 0xFFu);
       nacc[q] = (nacc[q] << b) + (uint32_t)nc;
+      if (METRICS) {
+        const float d = xv - __builtin_fmaf((float)(-nc), scale, mn);
+        e2 = __builtin_fmaf(d, d, e2);
+        m2 = __builtin_fmaf(xv, xv, m2);
+      }
     }
   }
   nacc0 = nacc[0];
   nacc1 = nacc[1];
+  if (METRICS) {
+    *err = e2;
+    *mag = m2;
+  }
 }
 
 // Widens the tile's chunks into xf and leaves one (min, max) pair per (load, lane run) segment
@@ -261,14 +290,18 @@ __device__ __forceinline__ void tile_minmax(const uint4 (&raw)[TileShape<DT, LPG
 // EXT = true (only with the one-group-per-tile shape): the group is `tiles_per_group` tiles
 // long and its (min, max) comes from `ext_stat`, computed by an earlier pass; the tile skips
 // the reduction, and the group's first tile stores min and scale.
-template <int DT, int LPG_LOG2, int B, bool EXT = false>
+//
+// METRICS = true: additionally writes, per group, the sums (x - xhat)^2 and x^2 over the group
+// (binary32, accumulated per lane, then across the group's lanes, then across its loads).
+template <int DT, int LPG_LOG2, int B, bool EXT = false, bool METRICS = false>
 __global__ __launch_bounds__(kThreads) void k_quantize_pack_tile(
     const u32x4* __restrict__ x, int64_t n_tiles, const uint8_t* __restrict__ bits,
     const uint32_t* __restrict__ off, uint32_t seed_lo, uint32_t seed_hi,
     uint32_t* __restrict__ words, float* __restrict__ out_min, float* __restrict__ out_scale,
-    const float2* __restrict__ ext_stat, int64_t tiles_per_group) {
+    const float2* __restrict__ ext_stat, int64_t tiles_per_group, float2* __restrict__ out_metrics) {
   using S = TileShape<DT, LPG_LOG2>;
   static_assert(!EXT || S::kGroups == 1, "external statistics: the tile is part of one group");
+  static_assert(!(EXT && METRICS), "metrics are not computed for groups longer than a tile");
   constexpr int kEpl = S::kEpl;
   constexpr bool kMixed = (B == 0);
   constexpr uint32_t kGroupWords32 = S::kGroupSize / 32;      // words per group and bit of width
@@ -371,6 +404,11 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_tile(
         gi.b = my_b | (swz << 8);
         gi.byte_off = woff * 4u;
         lds.info[lane] = gi;
+        if (METRICS) lds.gscale[lane] = s.scale;
+      }
+      if (METRICS) {
+        wave_lds_sync();                       // every lane has read its (min, max) pairs
+        lds.stat[lane] = make_float2(0.0f, 0.0f);
       }
     }
 
@@ -411,8 +449,20 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_tile(
         addr = ((uint32_t)grp * (kGroupWords32 * B * 4u) + ((lig * kLaneBits) >> 3)) ^ kSwz;
       }
       uint32_t n0, n1;
-      if (need_exact2) quantize_chunk<DT, true>(xf[u], g_mn, g_invs, b, rnd[u], n0, n1);
-      else             quantize_chunk<DT, false>(xf[u], g_mn, g_invs, b, rnd[u], n0, n1);
+      if constexpr (METRICS) {
+        const float g_scale = lds.gscale[grp];
+        float err, mag;
+        if (need_exact2) quantize_chunk<DT, true, true>(xf[u], g_mn, g_invs, b, rnd[u], n0, n1, g_scale, &err, &mag);
+        else             quantize_chunk<DT, false, true>(xf[u], g_mn, g_invs, b, rnd[u], n0, n1, g_scale, &err, &mag);
+        seg_sum2<S::kLaneLog2>(err, mag);      // over the group's lanes of this load
+        if (lane_in_run == (uint32_t)S::kLpg - 1u) {
+          const float2 acc = lds.stat[grp];    // the group's earlier loads (same lane, in order)
+          lds.stat[grp] = make_float2(acc.x + err, acc.y + mag);
+        }
+      } else {
+        if (need_exact2) quantize_chunk<DT, true>(xf[u], g_mn, g_invs, b, rnd[u], n0, n1);
+        else             quantize_chunk<DT, false>(xf[u], g_mn, g_invs, b, rnd[u], n0, n1);
+      }
 
       if (kEpl == 4) {
         const uint32_t acc = 0u - n0;
@@ -446,19 +496,21 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_tile(
     // 6. the tile's words are one contiguous run in the packed buffer
     uint32_t* dst = words + tile_base;
     for (uint32_t i = lane; i < tile_words; i += kWave) dst[i] = lds.stage[i];
+    if (METRICS && lane < S::kGroups) out_metrics[g0 + lane] = lds.stat[lane];
   }
 }
 
-template <int DT, int LPG_LOG2>
+template <int DT, int LPG_LOG2, bool METRICS>
 hipError_t launch_tile(const daf_plan_t* p, const void* x, int64_t n_tiles, uint32_t seed_lo, uint32_t seed_hi,
-                       uint32_t* out_words, float* out_min, float* out_scale, hipStream_t stream) {
+                       uint32_t* out_words, float* out_min, float* out_scale, float2* out_metrics,
+                       hipStream_t stream) {
 #define DAF_LAUNCH(BITS)                                                                                   \
   do {                                                                                                     \
-    auto kernel = k_quantize_pack_tile<DT, LPG_LOG2, BITS>;                                                \
+    auto kernel = k_quantize_pack_tile<DT, LPG_LOG2, BITS, false, METRICS>;                                \
     const unsigned blocks = (unsigned)((n_tiles + kWavesPerBlock - 1) / kWavesPerBlock);                   \
     hipLaunchKernelGGL(kernel, dim3(blocks), dim3(kThreads), 0, stream, static_cast<const u32x4*>(x),      \
                        n_tiles, p->d_bits, p->d_off, seed_lo, seed_hi, out_words, out_min, out_scale,      \
-                       nullptr, (int64_t)1);                                                               \
+                       nullptr, (int64_t)1, out_metrics);                                                  \
   } while (0)
   switch (p->uniform_bits) {
     case 0: DAF_LAUNCH(0); break;
@@ -636,7 +688,7 @@ hipError_t launch_big(const daf_plan_t* p, const void* x, uint32_t seed_lo, uint
 #define DAF_LAUNCH(BITS)                                                                                      \
   hipLaunchKernelGGL((k_quantize_pack_tile<DT, kMaxLog2, BITS, true>), dim3(blocks), dim3(kThreads), 0, stream, \
                      static_cast<const u32x4*>(x), n_full_tiles, p->d_bits, p->d_off, seed_lo, seed_hi,       \
-                     out_words, out_min, out_scale, stat, tpg)
+                     out_words, out_min, out_scale, stat, tpg, nullptr)
     switch (p->uniform_bits) {
       case 0: DAF_LAUNCH(0); break;
       case 1: DAF_LAUNCH(1); break;
@@ -779,15 +831,17 @@ hipError_t launch_group_minmax(const daf_plan_t* p, const void* x, float* out_mi
   return hipGetLastError();
 }
 
-template <int DT>
+template <int DT, bool METRICS>
 hipError_t launch_dtype(const daf_plan_t* p, const void* x, uint64_t seed, uint32_t* out_words, float* out_min,
-                        float* out_scale, hipStream_t stream) {
+                        float* out_scale, float2* out_metrics, hipStream_t stream) {
   const uint32_t seed_lo = (uint32_t)seed, seed_hi = (uint32_t)(seed >> 32);
   constexpr int kEpl = ElemTraits<DT>::kPerLoad;
   const int64_t full_groups = p->n / p->group_size;
   int64_t fast_groups = 0;
-  if (p->d_big_scratch != nullptr)      // groups longer than a tile (set up by daf_plan)
+  if (p->d_big_scratch != nullptr) {    // groups longer than a tile (set up by daf_plan)
+    if (METRICS) return hipErrorNotSupported;
     return launch_big<DT>(p, x, seed_lo, seed_hi, out_words, out_min, out_scale, stream);
+  }
 
   // fast path: groups of 4 .. 1024 chunks (a power of two, at most one tile), whole tiles only
   const int32_t lpg = p->group_size / kEpl;
@@ -799,8 +853,8 @@ hipError_t launch_dtype(const daf_plan_t* p, const void* x, uint64_t seed, uint3
     if constexpr (TileShape<DT, LOG2>::kValid) {                                                         \
       n_tiles = full_groups / TileShape<DT, LOG2>::kGroups;                                              \
       fast_groups = n_tiles * TileShape<DT, LOG2>::kGroups;                                              \
-      if (n_tiles > 0) e = launch_tile<DT, LOG2>(p, x, n_tiles, seed_lo, seed_hi, out_words, out_min,    \
-                                                 out_scale, stream);                                     \
+      if (n_tiles > 0) e = launch_tile<DT, LOG2, METRICS>(p, x, n_tiles, seed_lo, seed_hi, out_words,    \
+                                                          out_min, out_scale, out_metrics, stream);      \
     }                                                                                                    \
     break;
     switch (lpg) {
@@ -817,9 +871,9 @@ hipError_t launch_dtype(const daf_plan_t* p, const void* x, uint64_t seed, uint3
   if (rest > 0) {
     int64_t blocks = (rest + kWavesPerBlock - 1) / kWavesPerBlock;
     if (blocks > 65536) blocks = 65536;
-    hipLaunchKernelGGL((k_quantize_pack_group<DT>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, x, p->n,
-                       p->group_size, fast_groups, p->num_groups, p->d_bits, p->d_off, p->uniform_bits,
-                       seed_lo, seed_hi, out_words, out_min, out_scale);
+    hipLaunchKernelGGL((k_quantize_pack_group<DT, METRICS>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, x,
+                       p->n, p->group_size, fast_groups, p->num_groups, p->d_bits, p->d_off, p->uniform_bits,
+                       seed_lo, seed_hi, out_words, out_min, out_scale, out_metrics);
     return hipGetLastError();
   }
   return hipSuccess;
@@ -838,12 +892,17 @@ hipError_t daf_launch_group_minmax(const daf_plan_t* plan, const void* x, int dt
 }
 
 hipError_t daf_launch_quantize_pack(const daf_plan_t* plan, const void* x, int dtype, uint64_t seed,
-                                    uint32_t* out_words, float* out_min, float* out_scale,
+                                    uint32_t* out_words, float* out_min, float* out_scale, float* out_metrics,
                                     hipStream_t stream) {
+  float2* m = reinterpret_cast<float2*>(out_metrics);
+#define DAF_DT(D)                                                                                         \
+  return m ? launch_dtype<D, true>(plan, x, seed, out_words, out_min, out_scale, m, stream)               \
+           : launch_dtype<D, false>(plan, x, seed, out_words, out_min, out_scale, nullptr, stream)
   switch (dtype) {
-    case daf::kF32:  return launch_dtype<daf::kF32>(plan, x, seed, out_words, out_min, out_scale, stream);
-    case daf::kF16:  return launch_dtype<daf::kF16>(plan, x, seed, out_words, out_min, out_scale, stream);
-    case daf::kBF16: return launch_dtype<daf::kBF16>(plan, x, seed, out_words, out_min, out_scale, stream);
+    case daf::kF32:  DAF_DT(daf::kF32);
+    case daf::kF16:  DAF_DT(daf::kF16);
+    case daf::kBF16: DAF_DT(daf::kBF16);
     default: return hipErrorInvalidValue;
   }
+#undef DAF_DT
 }

@@ -119,3 +119,51 @@ def test_argument_errors(env):
     for bad in ((3,), (1, 2, 4, 8, 8), ()):
         with pytest.raises(daf.DafError):
             daf.daf_select_bits(mn, mn, bad, out, ws)
+
+
+@pytest.mark.parametrize("dtype", [F32, F16, BF16])
+@pytest.mark.parametrize("gs", [32, 64, 96, 128, 256, 1024, 4096])
+@pytest.mark.parametrize("bits", [2, 8, "mixed"])
+def test_fused_metrics(env, dtype, gs, bits):
+    """daf_quantize_pack_metrics: words/min/scale identical to daf_quantize_pack (bit-exact
+    against the oracle), and the per-group error and magnitude sums within the binary32
+    accumulation bound of the oracle's double-precision values."""
+    daf, orc = env
+    n = 4096 * 5 + 3 * gs + 21
+    G = (n + gs - 1) // gs
+    g = torch.Generator().manual_seed(gs + dtype)
+    x = (torch.randn(n, generator=g) * 1.7).to(torch_dtype(dtype))
+    b = (np.random.default_rng(gs).choice([1, 2, 4, 8], G).astype(np.uint8) if bits == "mixed"
+         else np.array([bits], np.uint8))
+    print("case", dtype, gs, bits, flush=True)
+    xd = x.cuda()
+    dbits = torch.from_numpy(b).cuda() if b.size > 1 else int(b[0])
+    plan = daf.daf_plan((n,), gs, dbits)
+    words = torch.empty(plan.packed_words, dtype=torch.int32, device="cuda:0")
+    mn = torch.empty(G, device="cuda:0")
+    sc = torch.empty(G, device="cuda:0")
+    met = torch.full((G, 2), float("nan"), device="cuda:0")
+    daf.daf_quantize_pack_metrics(plan, xd, 9, words, mn, sc, met)
+    torch.cuda.synchronize()
+    xb = to_numpy_bits(x)
+    ow, omn, osc, codes = orc.quantize_pack(xb, dtype, gs, b, 9, want_codes=True)
+    assert np.array_equal(words.cpu().numpy().view(np.uint32), ow)
+    assert np.array_equal(mn.cpu().numpy().view(np.uint32), omn.view(np.uint32))
+    assert np.array_equal(sc.cpu().numpy().view(np.uint32), osc.view(np.uint32))
+    want = orc.group_metrics(xb, dtype, gs, codes, omn, osc)
+    got = met.cpu().numpy().astype(np.float64)
+    # every one of the <= gs products and additions rounds with relative error <= 2^-24 and all
+    # terms are non-negative, so the sum is within (gs + 2) * 2^-24 of the exact one
+    rtol = (gs + 2) * 2.0 ** -24
+    assert np.all(np.abs(got - want) <= rtol * want + 1e-38), np.abs(got - want).max()
+
+
+def test_fused_metrics_rejects_long_groups(env):
+    daf, _ = env
+    x = torch.zeros(4096 * 4, device="cuda:0")
+    plan = daf.daf_plan((x.numel(),), 8192, 2)
+    words = torch.empty(plan.packed_words, dtype=torch.int32, device="cuda:0")
+    mn = torch.empty(2, device="cuda:0")
+    with pytest.raises(daf.DafError) as e:
+        daf.daf_quantize_pack_metrics(plan, x, 0, words, mn, mn.clone(), torch.empty(2, 2, device="cuda:0"))
+    assert e.value.status == -2
