@@ -29,9 +29,9 @@ HBM_PEAK_GBPS = 8000.0
 # same counter reads for a 1 GiB device copy (factors 2.000 and 1.000); see profiles/*.md.
 # (quantize+pack, unpack+dequantize) per configuration; None where it was not measured.
 MEASURED_TRAFFIC = {
-    2: (220115202, 220295705),
-    3: (64895873, 65092922),
-    5: (994360536, 1007781984),
+    2: (220116407, 220276367),
+    3: (64895828, 65096579),
+    5: (994368003, 1007779370),
 }
 ROTATE_BYTES = 768 << 20          # buffer sets rotate over at least this much input
 
