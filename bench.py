@@ -39,8 +39,8 @@ ROTATE_BYTES = 768 << 20          # buffer sets rotate over at least this much i
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=40)
-    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--minmax", action="store_true",
@@ -261,23 +261,31 @@ def main():
     # ONE stream (rotating over the buffer sets, no overlap between kernels), bracketed by one
     # pair of HIP events on that stream, so that the few microseconds an event pair costs are
     # not charged to every launch.
-    def kernel_pass(direction, reps):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for r in range(reps):
-            if direction == "q":
-                quantize_all(r % n_sets, single=True)
-            else:
-                dequantize_all(r % n_sets, single=True)
-        e1.record()
+    def kernel_pass(direction, batch, n_batches):
+        # every batch = `batch` launches bracketed by one event pair; all events are recorded
+        # first and read after one synchronization
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(n_batches + 1)]
+        evs[0].record()
+        r = 0
+        for b in range(n_batches):
+            for _ in range(batch):
+                if direction == "q":
+                    quantize_all(r % n_sets, single=True)
+                else:
+                    dequantize_all(r % n_sets, single=True)
+                r += 1
+            evs[b + 1].record()
         torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / reps
+        per = sorted(evs[b].elapsed_time(evs[b + 1]) / batch for b in range(n_batches))
+        return {"median": per[len(per) // 2], "min": per[0], "mean": sum(per) / len(per)}
 
-    reps = max(args.steps, 4 * n_sets)
-    kernel_pass("q", n_sets)
-    qk_ms = kernel_pass("q", reps)
-    kernel_pass("d", n_sets)
-    dk_ms = kernel_pass("d", reps)
+    batch = max(10, n_sets) if len(workloads) == 1 else 1
+    n_batches = max(5, -(-args.steps // batch))
+    kernel_pass("q", n_sets, 1)
+    qk = kernel_pass("q", batch, n_batches)
+    kernel_pass("d", n_sets, 1)
+    dk = kernel_pass("d", batch, n_batches)
+    qk_ms, dk_ms = qk["median"], dk["median"]
     alg = sum(algorithmic_bytes(w, p.packed_words) for w, p in zip(workloads, plans))
     # groups longer than a 4096-element tile need their statistics before any element can be
     # quantized: the quantize direction then reads the activation twice
@@ -300,10 +308,12 @@ def main():
                                         "elements": sum(w.numel for w in workloads),
                                         "group_size": workloads[0].group_size, "buffer_sets": n_sets,
                                         "streams": len(streams)},
-        "quantize_pack": {"kernel_ms": round(qk_ms, 4),
+        "quantize_pack": {"kernel_ms": round(qk_ms, 4), "kernel_ms_min": round(qk["min"], 4),
+                          "kernel_ms_mean": round(qk["mean"], 4),
                           "input_GBps": round(in_bytes / qk_ms / 1e6, 1), "algorithmic_bytes": alg_q,
                           "launches": len(workloads)},
-        "unpack_dequantize": {"kernel_ms": round(dk_ms, 4),
+        "unpack_dequantize": {"kernel_ms": round(dk_ms, 4), "kernel_ms_min": round(dk["min"], 4),
+                              "kernel_ms_mean": round(dk["mean"], 4),
                               "output_GBps": round(in_bytes / dk_ms / 1e6, 1), "algorithmic_bytes": alg,
                               "launches": len(workloads)},
         "roofline": dict(roof(qk_ms, traffic[0], alg_q), kernel="k_quantize_pack_tile"),
@@ -332,6 +342,37 @@ def main():
                                "kind": "oracle", "seconds": round(best, 2),
                                "sample": f"{len(sample)} of {len(workloads)} tensors, {done} input bytes, "
                                          "quantize+pack then unpack+dequantize, best of 3"}
+        # the same oracle functions over disjoint group ranges (groups are independent once
+        # the offsets are known), one range per host thread: a second reported baseline
+        import concurrent.futures as cf
+        n_thr = max(1, min(len(os.sched_getaffinity(0)), 16))
+        prepared = []
+        for w in sample:
+            xb = to_numpy_bits(w.x).reshape(-1)
+            off, total = orc.plan(w.numel, w.group_size, w.bits)
+            G = orc.num_groups(w.numel, w.group_size)
+            prepared.append((w, xb, off, G, np.empty(total, np.uint32), np.empty(G, np.float32),
+                             np.empty(G, np.float32), np.empty(w.numel, xb.dtype)))
+
+        def one_range(args_):
+            (w, xb, off, G, ow, omn, osc, oxh), g0, g1 = args_
+            orc.quantize_pack_range(xb, w.dtype, w.group_size, w.bits, off, w.seed, g0, g1, ow, omn, osc)
+            orc.unpack_dequantize_range(ow, omn, osc, w.bits, off, w.numel, w.group_size, g0, g1, oxh, w.dtype)
+
+        jobs = []
+        for p_ in prepared:
+            G = p_[3]
+            cuts = [G * i // n_thr for i in range(n_thr + 1)]
+            jobs += [(p_, cuts[i], cuts[i + 1]) for i in range(n_thr) if cuts[i + 1] > cuts[i]]
+        best_mt = float("inf")
+        with cf.ThreadPoolExecutor(max_workers=n_thr) as ex:
+            for _ in range(3):
+                t = time.perf_counter()
+                list(ex.map(one_range, jobs))
+                best_mt = min(best_mt, time.perf_counter() - t)
+        out["cpu_baseline_all_cores"] = {"value": round(2 * done / best_mt / 1e9, 4), "unit": "GB/s",
+                                         "cores": n_thr, "kind": "oracle", "seconds": round(best_mt, 2),
+                                         "sample": "same sample, groups split into one range per thread"}
     print(json.dumps(out))
 
 
