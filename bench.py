@@ -56,6 +56,9 @@ def parse():
                     help="the timed steps launch independent tensors / independent batches round-robin on "
                          "this many HIP streams (default priority), so that the tail of one kernel overlaps "
                          "the start of the next; the per-kernel roofline timing always uses one stream")
+    ap.add_argument("--page-store", action="store_true",
+                    help="time the host-side paged activation store (red-black trees against re-sorting, and the "
+                         "plain model) on synthetic iterations; uses no GPU")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a device copy of 1 GiB (a kernel of known traffic) so that the HBM "
                          "byte counters of a rocprofv3 --pmc run can be scaled against it")
@@ -72,6 +75,54 @@ def algorithmic_bytes(w, total_words):
     return n * esz + 4 * total_words + 8 * G + meta
 
 
+def bench_page_store(args, np):
+    """One iteration = reset, pre-iteration estimation of all activations, then all of them
+    arriving in the forward pass with importances that differ from the moving averages
+    (Algorithm 3).  Budget = 35 % of the bytes at the widest width, so the reduction loop runs
+    for most arrivals.  Reported: microseconds per iteration for the red-black-tree indices,
+    for re-sorting at every selection, and for the plain Python model."""
+    from oracle.page_store_oracle import PageStoreOracle
+    from paper_2507_07149_amd import store
+    page, widths = 64 << 10, [8, 4, 2, 1]
+    rows = []
+    for n in (64, 512, 4096):
+        rng = np.random.default_rng(100 + n)
+        numel = (rng.integers(1, 64, n) * 65536).astype(np.int64)               # elements per activation
+        by = np.stack([numel * w // 8 + 8 * (numel // 256) for w in widths], 1)    # words + min/scale, group 256
+        tm = np.stack([numel // 4000 + 2000 for _ in widths], 1).astype(np.int64)  # ~4 elements per ns + launch
+        ma = rng.uniform(0.1, 10.0, n)
+        imp = ma * rng.uniform(0.3, 3.0, n)
+        ids = np.arange(n, dtype=np.int64)
+        budget = int(by[:, 0].sum() * 0.35)
+        res = {}
+        for name, kind in (("rbtree", store.INDEX_RBTREE), ("sort", store.INDEX_SORT)):
+            st = store.Store(page, budget, None, 100 << 20, index_kind=kind)
+            reps = max(3, min(args.steps, 200000 // n))
+            best = float("inf")
+            for _ in range(reps):
+                t = time.perf_counter()
+                st.reset()
+                st.add_many(ids, widths, by, tm, ma)
+                bits, _, _ = st.receive_many(ids, imp)
+                best = min(best, time.perf_counter() - t)
+            res[name] = {"us_per_iteration": round(best * 1e6, 1), "selections": st.num_selections() // reps,
+                         "stored": int((bits > 0).sum())}
+            st.destroy()
+        if n <= 512:
+            o = PageStoreOracle(page, budget, None, 100 << 20)
+            t = time.perf_counter()
+            for i in range(n):
+                o.add(int(ids[i]), widths, by[i].tolist(), tm[i].tolist(), float(ma[i]))
+            ob = [o.receive(int(ids[i]), float(imp[i]))[0] for i in range(n)]
+            res["python_model_us"] = round((time.perf_counter() - t) * 1e6, 1)
+            assert ob == bits.tolist(), "the store and the model disagree"
+        res["speedup_rbtree_over_sort"] = round(res["sort"]["us_per_iteration"] / res["rbtree"]["us_per_iteration"], 2)
+        rows.append({"activations": n, **res})
+    print(json.dumps({"metric": "paged activation store, microseconds per iteration of Algorithm 3",
+                      "unit": "us", "higher_is_better": False, "data": "synthetic", "n_gpus": 0,
+                      "config": {"workload": "page_store_budget35pct_page64KiB"}, "results": rows}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -84,6 +135,10 @@ def main():
 
     import paper_2507_07149_amd as daf
     from daf_inputs import CONFIG_NAMES, make_config, to_numpy_bits
+
+    if args.page_store:
+        bench_page_store(args, np)
+        return
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)

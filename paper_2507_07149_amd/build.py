@@ -18,16 +18,18 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libdaf.so")
 SOURCES = ["daf_api.hip", "plan_scan.hip", "quantize_pack.hip", "unpack_dequantize.hip", "minmax.hip",
-           "select_bits.hip"]
+           "select_bits.hip", "page_store.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-ffp-contract=off", "-fno-strict-aliasing",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
+HOST_FLAGS = ["-O2", "-std=c++17", "-fPIC", "-Wall", "-Wextra", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
 
 
 def _compile(src: str) -> str:
-    obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-    r = subprocess.run([HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj],
+    obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
+    flags = HOST_FLAGS if src.endswith(".cpp") else FLAGS        # .cpp = host-only code
+    r = subprocess.run([HIPCC, *flags, "-c", os.path.join(CSRC, src), "-o", obj],
                        stderr=subprocess.PIPE, text=True)
     # the host pass warns that it does not know the packed-fp32 target feature: harmless
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
@@ -40,7 +42,7 @@ def _compile(src: str) -> str:
 
 def build() -> str:
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=6) as ex:
+    with ThreadPoolExecutor(max_workers=7) as ex:
         objs = list(ex.map(_compile, SOURCES))
     subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], check=True)
     return LIB

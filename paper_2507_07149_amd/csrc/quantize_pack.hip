@@ -392,8 +392,16 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_tile(
       }
       if (lane < S::kGroups) {
         if (!EXT || tile_in_group == 0u) {
-          out_min[g0 + lane] = s.mn;
-          out_scale[g0 + lane] = s.scale;
+          if (kMixed) {
+            // Streaming stores: with many packed words per tile (wide codes) plain stores
+            // of these two small runs slowed the whole kernel down measurably; with the
+            // few words of uniform narrow codes they made no difference.
+            __builtin_nontemporal_store(s.mn, &out_min[g0 + lane]);
+            __builtin_nontemporal_store(s.scale, &out_scale[g0 + lane]);
+          } else {
+            out_min[g0 + lane] = s.mn;
+            out_scale[g0 + lane] = s.scale;
+          }
         }
         GroupInfo gi;
         gi.mn = s.mn;
