@@ -218,6 +218,26 @@ int daf_group_minmax(const daf_plan_t* plan, const void* x, daf_dtype_t dtype,
 int daf_quantize_pack_metrics(const daf_plan_t* plan, const void* x, daf_dtype_t dtype, uint64_t seed,
                               uint32_t* out_words, float* out_min, float* out_scale,
                               float* out_metrics, void* stream);
+
+/* ---- producer fusion: the activation function and the quantization in one pass -------------
+ *
+ * daf_relu_quantize_pack -- for a layer whose saved activation is y = max(z, 0): reads the
+ * pre-activation z once, writes y (the forward pass needs it) and the quantized, packed y
+ * exactly as daf_quantize_pack(plan, y, ...) would produce them (the element-wise fusion of
+ * Sec. 3.2.3 applied to the producing operator; without it y is written by one kernel and
+ * read back by the next).  Per element: y = z if z > 0, else +0 (so -0 becomes +0).
+ *
+ *   z        DEVICE, N elements of dtype, 16-byte aligned, finite.
+ *   out_y    DEVICE, N elements of dtype, 16-byte aligned.  May be z itself (in place);
+ *            otherwise must not overlap z.
+ *   others   as daf_quantize_pack.
+ *
+ * Errors: as daf_quantize_pack; DAF_EINVAL also for out_y partially overlapping z;
+ * DAF_EUNSUPPORTED also for plans whose groups are longer than 4096 elements.
+ */
+int daf_relu_quantize_pack(const daf_plan_t* plan, const void* z, daf_dtype_t dtype, uint64_t seed, void* out_y,
+                           uint32_t* out_words, float* out_min, float* out_scale, void* stream);
+
 int64_t daf_select_bits_workspace_bytes(int64_t num_groups);
 int daf_select_bits(const float* group_min, const float* group_max, int64_t num_groups,
                     const uint8_t* classes, int32_t n_classes, uint8_t* out_bits,

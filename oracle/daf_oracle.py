@@ -92,6 +92,15 @@ def narrow(x: np.ndarray, dtype: int) -> np.ndarray:
     return out
 
 
+def relu(x: np.ndarray, dtype: int) -> np.ndarray:
+    """y = x if x > 0 else +0, element by element, in the element format (x: float32 values, or
+    uint16 bit patterns for F16/BF16; same representation returned).  The activation function
+    whose output the fused producer call stores and quantizes (Sec. 3.2.3)."""
+    x = np.ascontiguousarray(x.reshape(-1), dtype=_NP[dtype])
+    v = widen(x, dtype)                     # exact
+    return np.where(v > 0, x, np.zeros_like(x))
+
+
 def minmax(x: np.ndarray, dtype: int) -> np.ndarray:
     """Whole-tensor (min, max) as float32[2]."""
     x = np.ascontiguousarray(x.reshape(-1), dtype=_NP[dtype])

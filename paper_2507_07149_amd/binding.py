@@ -55,6 +55,8 @@ def load_library():
     L.daf_unpack_dequantize.restype = c.c_int
     L.daf_quantize_pack_metrics.argtypes = [vp, vp, c.c_int, u64, vp, vp, vp, vp, vp]
     L.daf_quantize_pack_metrics.restype = c.c_int
+    L.daf_relu_quantize_pack.argtypes = [vp, vp, c.c_int, u64, vp, vp, vp, vp, vp]
+    L.daf_relu_quantize_pack.restype = c.c_int
     L.daf_group_minmax.argtypes = [vp, vp, c.c_int, vp, vp, vp]
     L.daf_group_minmax.restype = c.c_int
     L.daf_select_bits_workspace_bytes.argtypes = [i64]
@@ -200,6 +202,17 @@ def daf_select_bits(group_min: torch.Tensor, group_max: torch.Tensor, classes: S
                                         workspace.data_ptr(), _stream_handle(stream))
     if rc != 0:
         raise DafError(rc, "daf_select_bits")
+
+
+def daf_relu_quantize_pack(plan: Plan, z: torch.Tensor, seed: int, out_y: torch.Tensor, out_words: torch.Tensor,
+                           out_min: torch.Tensor, out_scale: torch.Tensor, stream=None) -> None:
+    if out_y.dtype != z.dtype or out_y.numel() != z.numel():
+        raise ValueError("out_y must have the dtype and the number of elements of z")
+    rc = load_library().daf_relu_quantize_pack(plan.handle, z.data_ptr(), _DTYPE_ID[z.dtype], seed, out_y.data_ptr(),
+                                               out_words.data_ptr(), out_min.data_ptr(), out_scale.data_ptr(),
+                                               _stream_handle(stream))
+    if rc != 0:
+        raise DafError(rc, "daf_relu_quantize_pack")
 
 
 def daf_quantize_pack_metrics(plan: Plan, x: torch.Tensor, seed: int, out_words: torch.Tensor, out_min: torch.Tensor,

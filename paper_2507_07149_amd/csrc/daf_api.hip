@@ -164,7 +164,28 @@ int daf_quantize_pack(const daf_plan_t* plan, const void* x, daf_dtype_t dtype, 
   if (!aligned(x, 16) || !aligned(out_words, 4) || !aligned(out_min, 4) || !aligned(out_scale, 4)) return DAF_EINVAL;
   if (dtype != DAF_F32 && dtype != DAF_F16 && dtype != DAF_BF16) return DAF_EUNSUPPORTED;
   const hipError_t e = daf_launch_quantize_pack(plan, x, (int)dtype, seed, out_words, out_min, out_scale, nullptr,
-                                                static_cast<hipStream_t>(stream));
+                                                nullptr, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? DAF_OK : DAF_EDEVICE;
+}
+
+int daf_relu_quantize_pack(const daf_plan_t* plan, const void* z, daf_dtype_t dtype, uint64_t seed, void* out_y,
+                           uint32_t* out_words, float* out_min, float* out_scale, void* stream) {
+  if (plan == nullptr || z == nullptr || out_y == nullptr || out_words == nullptr || out_min == nullptr ||
+      out_scale == nullptr)
+    return DAF_EINVAL;
+  if (!aligned(z, 16) || !aligned(out_y, 16) || !aligned(out_words, 4) || !aligned(out_min, 4) ||
+      !aligned(out_scale, 4))
+    return DAF_EINVAL;
+  if (dtype != DAF_F32 && dtype != DAF_F16 && dtype != DAF_BF16) return DAF_EUNSUPPORTED;
+  if (plan->d_big_scratch != nullptr) return DAF_EUNSUPPORTED;     // groups longer than 4096 elements
+  if (out_y != z) {                                                // in place, or not overlapping at all
+    const int64_t bytes = plan->n * (dtype == DAF_F32 ? 4 : 2);
+    const char* a = static_cast<const char*>(z);
+    const char* b = static_cast<const char*>(out_y);
+    if (a < b + bytes && b < a + bytes) return DAF_EINVAL;
+  }
+  const hipError_t e = daf_launch_quantize_pack(plan, z, (int)dtype, seed, out_words, out_min, out_scale, nullptr,
+                                                out_y, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? DAF_OK : DAF_EDEVICE;
 }
 
@@ -180,7 +201,7 @@ int daf_quantize_pack_metrics(const daf_plan_t* plan, const void* x, daf_dtype_t
   if (dtype != DAF_F32 && dtype != DAF_F16 && dtype != DAF_BF16) return DAF_EUNSUPPORTED;
   if (plan->d_big_scratch != nullptr) return DAF_EUNSUPPORTED;     // groups longer than 4096 elements
   const hipError_t e = daf_launch_quantize_pack(plan, x, (int)dtype, seed, out_words, out_min, out_scale,
-                                                out_metrics, static_cast<hipStream_t>(stream));
+                                                out_metrics, nullptr, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? DAF_OK : DAF_EDEVICE;
 }
 

@@ -20,6 +20,8 @@
 // (mn-x)*(inv*256) is -256*v exactly as long as inv*256 does not overflow; groups where it
 // would are handled with two multiplications.  floor(w + 1/2) is exact for |w| < 2^16.
 // No clamp to L is needed: v <= L*(1+2^-22), so ceil(256*v - 1/2) <= 256*L.
+#include <type_traits>
+
 #include "daf_device.h"
 #include "daf_internal.h"
 
@@ -62,21 +64,46 @@ __device__ __forceinline__ int neg_code(float x, float mn, float invs, uint32_t 
   return (round_half_up_to_int(w) + (int)r) >> 8;
 }
 
+// max(x, +0) on the raw bits of one 32-bit word (one binary32 value or two 16-bit values):
+// a value whose sign bit is set (negative, or -0) is a negative integer and becomes +0, any
+// other value is kept; for finite inputs that is x > 0 ? x : +0 exactly.
+template <int DT>
+__device__ __forceinline__ uint32_t relu_bits(uint32_t w) {
+  if (DT == kF32) {
+    const int32_t v = (int32_t)w;
+    return (uint32_t)(v > 0 ? v : 0);
+  }
+  typedef short short2v __attribute__((ext_vector_type(2)));
+  const short2v v = __builtin_bit_cast(short2v, w);
+  const short2v zero = {0, 0};
+  return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(v, zero));
+}
+
 // ------------------------------------------------------------------------------------------
 // General path: one wave per group.
 // ------------------------------------------------------------------------------------------
-template <int DT>
+template <int DT, bool RELU = false>
 __device__ __forceinline__ float load_elem(const void* x, int64_t i) {
-  if (DT == kF32) return static_cast<const float*>(x)[i];
-  return widen16<DT == kF32 ? kF16 : DT>(static_cast<const uint16_t*>(x)[i]);
+  float v;
+  if (DT == kF32) v = static_cast<const float*>(x)[i];
+  else v = widen16<DT == kF32 ? kF16 : DT>(static_cast<const uint16_t*>(x)[i]);
+  if (RELU) v = v > 0.0f ? v : 0.0f;
+  return v;
+}
+template <int DT>
+__device__ __forceinline__ void store_elem(void* y, int64_t i, float v) {   // v is a value of the format
+  if (DT == kF32) static_cast<float*>(y)[i] = v;
+  else static_cast<uint16_t*>(y)[i] = (uint16_t)(DT == kBF16 ? f2u(v) >> 16 : narrow16<DT == kF32 ? kF16 : DT>(v));
 }
 
-template <int DT, bool METRICS = false>
+// RELU = true: the input is z, every element is replaced by max(z, +0) before anything else, and
+// the result is also written to out_y (which may be the input buffer itself).
+template <int DT, bool METRICS = false, bool RELU = false>
 __global__ __launch_bounds__(kThreads) void k_quantize_pack_group(
-    const void* __restrict__ x, int64_t n, int32_t gs, int64_t g_begin, int64_t g_end,
+    const void* x, int64_t n, int32_t gs, int64_t g_begin, int64_t g_end,
     const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, int32_t uniform_bits,
     uint32_t seed_lo, uint32_t seed_hi, uint32_t* __restrict__ words, float* __restrict__ out_min,
-    float* __restrict__ out_scale, float2* __restrict__ out_metrics) {
+    float* __restrict__ out_scale, float2* __restrict__ out_metrics, void* out_y) {
   const int lane = threadIdx.x & (kWave - 1);
   const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
   const int64_t n_waves = (int64_t)gridDim.x * kWavesPerBlock;
@@ -86,9 +113,10 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_group(
     const uint32_t b = uniform_bits ? (uint32_t)uniform_bits : (uint32_t)bits[g];
     const uint32_t woff = uniform_bits ? (uint32_t)(g * (((int64_t)gs * uniform_bits) >> 5)) : off[g];
 
-    float mn = load_elem<DT>(x, lo), mx = mn;              // element 0 exists in every group
+    float mn = load_elem<DT, RELU>(x, lo), mx = mn;        // element 0 exists in every group
     for (int32_t j = lane; j < len; j += kWave) {
-      const float v = load_elem<DT>(x, lo + j);
+      const float v = load_elem<DT, RELU>(x, lo + j);
+      if (RELU) store_elem<DT>(out_y, lo + j, v);          // every element passes here exactly once
       mn = fminf(mn, v);
       mx = fmaxf(mx, v);
     }
@@ -120,7 +148,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_group(
         const uint32_t slot = (uint32_t)(i % kElemsPerPhilox);
         const uint32_t rw = (slot < 4) ? rnd.x : (slot < 8) ? rnd.y : (slot < 12) ? rnd.z : rnd.w;
         const uint32_t r = (rw >> (8u * (slot & 3u))) & 0xFFu;
-        const float xv = load_elem<DT>(x, lo + j);
+        const float xv = load_elem<DT, RELU>(x, lo + j);     // z or y: max(., +0) gives y either way
         const int nc = neg_code<true>(xv, s.mn, s.inv, r);
         word |= (uint32_t)(-nc) << (32u - b - c * b);
         if (METRICS) {
@@ -293,15 +321,21 @@ __device__ __forceinline__ void tile_minmax(const uint4 (&raw)[TileShape<DT, LPG
 //
 // METRICS = true: additionally writes, per group, the sums (x - xhat)^2 and x^2 over the group
 // (binary32, accumulated per lane, then across the group's lanes, then across its loads).
-template <int DT, int LPG_LOG2, int B, bool EXT = false, bool METRICS = false>
+//
+// RELU = true: x holds z; every element becomes max(z, +0) right after the load, the result is
+// written to out_y in the same layout (out_y may be x itself: a lane only overwrites chunks it
+// has already loaded), and everything else sees y.
+template <int DT, int LPG_LOG2, int B, bool EXT = false, bool METRICS = false, bool RELU = false>
 __global__ __launch_bounds__(kThreads) void k_quantize_pack_tile(
-    const u32x4* __restrict__ x, int64_t n_tiles, const uint8_t* __restrict__ bits,
-    const uint32_t* __restrict__ off, uint32_t seed_lo, uint32_t seed_hi,
+    typename std::conditional<RELU, const u32x4*, const u32x4* __restrict__>::type x, int64_t n_tiles,
+    const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, uint32_t seed_lo, uint32_t seed_hi,
     uint32_t* __restrict__ words, float* __restrict__ out_min, float* __restrict__ out_scale,
-    const float2* __restrict__ ext_stat, int64_t tiles_per_group, float2* __restrict__ out_metrics) {
+    const float2* __restrict__ ext_stat, int64_t tiles_per_group, float2* __restrict__ out_metrics,
+    u32x4* out_y) {
   using S = TileShape<DT, LPG_LOG2>;
   static_assert(!EXT || S::kGroups == 1, "external statistics: the tile is part of one group");
   static_assert(!(EXT && METRICS), "metrics are not computed for groups longer than a tile");
+  static_assert(!(RELU && (EXT || METRICS)), "the fused max(z, 0) exists for the plain tile kernel only");
   constexpr int kEpl = S::kEpl;
   constexpr bool kMixed = (B == 0);
   constexpr uint32_t kGroupWords32 = S::kGroupSize / 32;      // words per group and bit of width
@@ -321,6 +355,15 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_tile(
   for (int u = 0; u < S::kLoads; ++u) {
     const u32x4 v = __builtin_nontemporal_load(&x[tile * (S::kLoads * kWave) + u * kWave + lane]);
     raw[u] = make_uint4(v.x, v.y, v.z, v.w);
+  }
+  if constexpr (RELU) {
+#pragma unroll
+    for (int u = 0; u < S::kLoads; ++u) {
+      raw[u] = make_uint4(relu_bits<DT>(raw[u].x), relu_bits<DT>(raw[u].y), relu_bits<DT>(raw[u].z),
+                          relu_bits<DT>(raw[u].w));
+      const u32x4 y = {raw[u].x, raw[u].y, raw[u].z, raw[u].w};
+      out_y[tile * (S::kLoads * kWave) + u * kWave + lane] = y;    // the next layer reads it soon: cached store
+    }
   }
 
   {
@@ -508,17 +551,17 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_tile(
   }
 }
 
-template <int DT, int LPG_LOG2, bool METRICS>
+template <int DT, int LPG_LOG2, bool METRICS, bool RELU>
 hipError_t launch_tile(const daf_plan_t* p, const void* x, int64_t n_tiles, uint32_t seed_lo, uint32_t seed_hi,
-                       uint32_t* out_words, float* out_min, float* out_scale, float2* out_metrics,
+                       uint32_t* out_words, float* out_min, float* out_scale, float2* out_metrics, void* out_y,
                        hipStream_t stream) {
 #define DAF_LAUNCH(BITS)                                                                                   \
   do {                                                                                                     \
-    auto kernel = k_quantize_pack_tile<DT, LPG_LOG2, BITS, false, METRICS>;                                \
+    auto kernel = k_quantize_pack_tile<DT, LPG_LOG2, BITS, false, METRICS, RELU>;                          \
     const unsigned blocks = (unsigned)((n_tiles + kWavesPerBlock - 1) / kWavesPerBlock);                   \
     hipLaunchKernelGGL(kernel, dim3(blocks), dim3(kThreads), 0, stream, static_cast<const u32x4*>(x),      \
                        n_tiles, p->d_bits, p->d_off, seed_lo, seed_hi, out_words, out_min, out_scale,      \
-                       nullptr, (int64_t)1, out_metrics);                                                  \
+                       nullptr, (int64_t)1, out_metrics, static_cast<u32x4*>(out_y));                      \
   } while (0)
   switch (p->uniform_bits) {
     case 0: DAF_LAUNCH(0); break;
@@ -696,7 +739,7 @@ hipError_t launch_big(const daf_plan_t* p, const void* x, uint32_t seed_lo, uint
 #define DAF_LAUNCH(BITS)                                                                                      \
   hipLaunchKernelGGL((k_quantize_pack_tile<DT, kMaxLog2, BITS, true>), dim3(blocks), dim3(kThreads), 0, stream, \
                      static_cast<const u32x4*>(x), n_full_tiles, p->d_bits, p->d_off, seed_lo, seed_hi,       \
-                     out_words, out_min, out_scale, stat, tpg, nullptr)
+                     out_words, out_min, out_scale, stat, tpg, nullptr, nullptr)
     switch (p->uniform_bits) {
       case 0: DAF_LAUNCH(0); break;
       case 1: DAF_LAUNCH(1); break;
@@ -839,15 +882,15 @@ hipError_t launch_group_minmax(const daf_plan_t* p, const void* x, float* out_mi
   return hipGetLastError();
 }
 
-template <int DT, bool METRICS>
+template <int DT, bool METRICS, bool RELU = false>
 hipError_t launch_dtype(const daf_plan_t* p, const void* x, uint64_t seed, uint32_t* out_words, float* out_min,
-                        float* out_scale, float2* out_metrics, hipStream_t stream) {
+                        float* out_scale, float2* out_metrics, void* out_y, hipStream_t stream) {
   const uint32_t seed_lo = (uint32_t)seed, seed_hi = (uint32_t)(seed >> 32);
   constexpr int kEpl = ElemTraits<DT>::kPerLoad;
   const int64_t full_groups = p->n / p->group_size;
   int64_t fast_groups = 0;
   if (p->d_big_scratch != nullptr) {    // groups longer than a tile (set up by daf_plan)
-    if (METRICS) return hipErrorNotSupported;
+    if (METRICS || RELU) return hipErrorNotSupported;
     return launch_big<DT>(p, x, seed_lo, seed_hi, out_words, out_min, out_scale, stream);
   }
 
@@ -861,8 +904,9 @@ hipError_t launch_dtype(const daf_plan_t* p, const void* x, uint64_t seed, uint3
     if constexpr (TileShape<DT, LOG2>::kValid) {                                                         \
       n_tiles = full_groups / TileShape<DT, LOG2>::kGroups;                                              \
       fast_groups = n_tiles * TileShape<DT, LOG2>::kGroups;                                              \
-      if (n_tiles > 0) e = launch_tile<DT, LOG2, METRICS>(p, x, n_tiles, seed_lo, seed_hi, out_words,    \
-                                                          out_min, out_scale, out_metrics, stream);      \
+      if (n_tiles > 0) e = launch_tile<DT, LOG2, METRICS, RELU>(p, x, n_tiles, seed_lo, seed_hi, out_words, \
+                                                                out_min, out_scale, out_metrics, out_y,  \
+                                                                stream);                                 \
     }                                                                                                    \
     break;
     switch (lpg) {
@@ -879,9 +923,9 @@ hipError_t launch_dtype(const daf_plan_t* p, const void* x, uint64_t seed, uint3
   if (rest > 0) {
     int64_t blocks = (rest + kWavesPerBlock - 1) / kWavesPerBlock;
     if (blocks > 65536) blocks = 65536;
-    hipLaunchKernelGGL((k_quantize_pack_group<DT, METRICS>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, x,
-                       p->n, p->group_size, fast_groups, p->num_groups, p->d_bits, p->d_off, p->uniform_bits,
-                       seed_lo, seed_hi, out_words, out_min, out_scale, out_metrics);
+    hipLaunchKernelGGL((k_quantize_pack_group<DT, METRICS, RELU>), dim3((unsigned)blocks), dim3(kThreads), 0, stream,
+                       x, p->n, p->group_size, fast_groups, p->num_groups, p->d_bits, p->d_off, p->uniform_bits,
+                       seed_lo, seed_hi, out_words, out_min, out_scale, out_metrics, out_y);
     return hipGetLastError();
   }
   return hipSuccess;
@@ -901,11 +945,14 @@ hipError_t daf_launch_group_minmax(const daf_plan_t* plan, const void* x, int dt
 
 hipError_t daf_launch_quantize_pack(const daf_plan_t* plan, const void* x, int dtype, uint64_t seed,
                                     uint32_t* out_words, float* out_min, float* out_scale, float* out_metrics,
-                                    hipStream_t stream) {
+                                    void* out_relu_y, hipStream_t stream) {
   float2* m = reinterpret_cast<float2*>(out_metrics);
+  if (m && out_relu_y) return hipErrorNotSupported;
 #define DAF_DT(D)                                                                                         \
-  return m ? launch_dtype<D, true>(plan, x, seed, out_words, out_min, out_scale, m, stream)               \
-           : launch_dtype<D, false>(plan, x, seed, out_words, out_min, out_scale, nullptr, stream)
+  if (out_relu_y)                                                                                         \
+    return launch_dtype<D, false, true>(plan, x, seed, out_words, out_min, out_scale, nullptr, out_relu_y, stream); \
+  return m ? launch_dtype<D, true>(plan, x, seed, out_words, out_min, out_scale, m, nullptr, stream)      \
+           : launch_dtype<D, false>(plan, x, seed, out_words, out_min, out_scale, nullptr, nullptr, stream)
   switch (dtype) {
     case daf::kF32:  DAF_DT(daf::kF32);
     case daf::kF16:  DAF_DT(daf::kF16);

@@ -48,3 +48,23 @@ def test_narrow_bf16_matches_torch():
     x = _samples()
     want = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
     assert np.array_equal(orc.narrow(x, orc.BF16), want)
+
+
+def test_relu_matches_torch_on_every_16_bit_pattern_and_on_floats():
+    # pinned against torch.relu on the CPU (an independent implementation), every finite pattern
+    import torch
+    pats = np.arange(65536, dtype=np.uint16)
+    for dt, tdt in ((orc.F16, torch.float16), (orc.BF16, torch.bfloat16)):
+        t = torch.from_numpy(pats.view(np.int16).copy()).view(tdt)
+        finite = torch.isfinite(t.float()).numpy()
+        want = torch.relu(t.float()).to(tdt).view(torch.int16).numpy().view(np.uint16)
+        got = orc.relu(pats, dt)
+        finite[0x8000] = False                                    # torch keeps -0; here -0 becomes +0
+        assert np.array_equal(got[finite], want[finite])
+        assert got[0x8000] == 0
+    rng = np.random.default_rng(5)
+    x = np.concatenate([rng.standard_normal(10000).astype(np.float32),
+                        np.array([0.0, -0.0, 1e-45, -1e-45, 3e38, -3e38], np.float32)])
+    want = torch.relu(torch.from_numpy(x)).numpy() + np.float32(0.0)      # -0 + 0 = +0
+    got = orc.relu(x, orc.F32)
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
