@@ -56,6 +56,9 @@ def parse():
                     help="the timed steps launch independent tensors / independent batches round-robin on "
                          "this many HIP streams (default priority), so that the tail of one kernel overlaps "
                          "the start of the next; the per-kernel roofline timing always uses one stream")
+    ap.add_argument("--fused-relu", action="store_true",
+                    help="time daf_relu_quantize_pack (activation function fused into the quantize pass) "
+                         "against a separate relu kernel followed by daf_quantize_pack")
     ap.add_argument("--page-store", action="store_true",
                     help="time the host-side paged activation store (red-black trees against re-sorting, and the "
                          "plain model) on synthetic iterations; uses no GPU")
@@ -225,6 +228,63 @@ def main():
                           "group_minmax_frac_of_8TBps": round(stats_bytes / t_stats / 1e3 / HBM_PEAK_GBPS, 4),
                           "select_bits_us": round(t_select, 2), "plan_us_with_sync": round(t_plan, 1),
                           "widths_match_generator": ok}))
+        return
+
+    if args.fused_relu:
+        # pre-activations z = the workload's values with random signs; buffers rotate over > 768 MB
+        workloads = make_config(args.config)
+        in_bytes = sum(w.numel * w.x.element_size() for w in workloads)
+        n_sets = 1 if in_bytes >= ROTATE_BYTES else -(-ROTATE_BYTES // in_bytes)
+        gen = torch.Generator().manual_seed(17)
+        plans, sets = [], []
+        for w in workloads:
+            plans.append(daf.daf_plan(tuple(w.x.shape), w.group_size,
+                                      int(w.bits[0]) if w.bits.size == 1 else torch.from_numpy(w.bits).to(dev)))
+        for _ in range(n_sets):
+            bufs = []
+            for w, p in zip(workloads, plans):
+                sign = torch.randint(0, 2, (w.numel,), generator=gen, dtype=torch.int8).to(w.x.dtype).mul_(2).sub_(1)
+                z = (w.x.reshape(-1) * sign).to(dev)
+                bufs.append(dict(z=z, y=torch.empty_like(z),
+                                 words=torch.empty(p.packed_words, dtype=torch.int32, device=dev),
+                                 mn=torch.empty(p.num_groups, device=dev), sc=torch.empty(p.num_groups, device=dev)))
+            sets.append(bufs)
+
+        def fused(k):
+            for (w, p, b) in zip(workloads, plans, sets[k]):
+                daf.daf_relu_quantize_pack(p, b["z"], w.seed, b["y"], b["words"], b["mn"], b["sc"])
+
+        def separate(k):
+            for (w, p, b) in zip(workloads, plans, sets[k]):
+                torch.clamp_min(b["z"], 0, out=b["y"])
+                daf.daf_quantize_pack(p, b["y"], w.seed, b["words"], b["mn"], b["sc"])
+
+        def timed(fn):
+            for i in range(args.warmup):
+                fn(i % n_sets)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for i in range(args.steps):
+                fn(i % n_sets)
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / args.steps
+
+        t_sep, t_fused = timed(separate), timed(fused)
+        alg = sum(algorithmic_bytes(w, p.packed_words) + w.numel * w.x.element_size()
+                  for w, p in zip(workloads, plans))            # z read, y written, words, min, scale
+        ach = alg / (t_fused * 1e-3) / 1e9
+        print(json.dumps({"metric": "relu + quantize+pack GB/s of activations", "value": round(in_bytes / t_fused / 1e6, 1),
+                          "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "data": "synthetic",
+                          "higher_is_better": True, "dtype": {0: "f32", 1: "f16", 2: "bf16"}[workloads[0].dtype],
+                          "config": {"workload": CONFIG_NAMES[args.config] + "_fused_relu", "tensors": len(workloads),
+                                     "buffer_sets": n_sets},
+                          "fused_ms": round(t_fused, 4), "separate_relu_then_quantize_ms": round(t_sep, 4),
+                          "speedup": round(t_sep / t_fused, 3),
+                          "roofline": {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                                       "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None,
+                                       "kernel": "k_quantize_pack_tile<..., RELU>", "algorithmic_bytes": alg}}))
         return
 
     workloads = make_config(args.config)
