@@ -271,10 +271,21 @@ def main():
             torch.cuda.synchronize()
             return e0.elapsed_time(e1) / args.steps
 
+        def fused_bwd(k):
+            for (w, p, b) in zip(workloads, plans, sets[k]):
+                daf.daf_unpack_relu_backward(p, b["words"], b["mn"], b["sc"], b["z"], b["y"])   # z plays grad_y
+
+        def separate_bwd(k):
+            for (w, p, b) in zip(workloads, plans, sets[k]):
+                daf.daf_unpack_dequantize(p, b["words"], b["mn"], b["sc"], b["y"])
+                torch.ops.aten.threshold_backward.grad_input(b["z"], b["y"], 0, grad_input=b["y"])
+
         t_sep, t_fused = timed(separate), timed(fused)
+        t_bsep, t_bfused = timed(separate_bwd), timed(fused_bwd)
         alg = sum(algorithmic_bytes(w, p.packed_words) + w.numel * w.x.element_size()
                   for w, p in zip(workloads, plans))            # z read, y written, words, min, scale
         ach = alg / (t_fused * 1e-3) / 1e9
+        ach_b = alg / (t_bfused * 1e-3) / 1e9
         print(json.dumps({"metric": "relu + quantize+pack GB/s of activations", "value": round(in_bytes / t_fused / 1e6, 1),
                           "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "data": "synthetic",
                           "higher_is_better": True, "dtype": {0: "f32", 1: "f16", 2: "bf16"}[workloads[0].dtype],
@@ -282,6 +293,13 @@ def main():
                                      "buffer_sets": n_sets},
                           "fused_ms": round(t_fused, 4), "separate_relu_then_quantize_ms": round(t_sep, 4),
                           "speedup": round(t_sep / t_fused, 3),
+                          "backward_fused_ms": round(t_bfused, 4),
+                          "backward_separate_dequantize_then_threshold_ms": round(t_bsep, 4),
+                          "backward_speedup": round(t_bsep / t_bfused, 3),
+                          "roofline_backward": {"bound": "hbm", "achieved": round(ach_b, 1), "peak": HBM_PEAK_GBPS,
+                                                "unit": "GB/s", "frac": round(ach_b / HBM_PEAK_GBPS, 4),
+                                                "kernel": "k_unpack_dequantize_chunk<..., RELU_BWD>",
+                                                "algorithmic_bytes": alg},
                           "roofline": {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                                        "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None,
                                        "kernel": "k_quantize_pack_tile<..., RELU>", "algorithmic_bytes": alg}}))

@@ -238,6 +238,25 @@ int daf_quantize_pack_metrics(const daf_plan_t* plan, const void* x, daf_dtype_t
 int daf_relu_quantize_pack(const daf_plan_t* plan, const void* z, daf_dtype_t dtype, uint64_t seed, void* out_y,
                            uint32_t* out_words, float* out_min, float* out_scale, void* stream);
 
+/* ---- consumer fusion for an element-wise consumer -------------------------------------------
+ *
+ * daf_unpack_relu_backward -- backward of y = max(z, 0) when y is the saved, quantized
+ * activation: grad_z[i] = grad_y[i] if xhat[i] > 0, else +0, where xhat[i] is exactly the value
+ * daf_unpack_dequantize would write (fma(code, scale, min) rounded to dtype).  The words are
+ * unpacked and dequantized in registers and only the sign test leaves them; xhat is never
+ * written to memory (the point of unpacking next to the consumer, Sec. 3.3 and Sec. 4.3.1).
+ *
+ *   words, min, scale, bits   as daf_unpack_dequantize.
+ *   grad_y       DEVICE, N elements of dtype, 16-byte aligned.
+ *   out_grad_z   DEVICE, N elements of dtype, 16-byte aligned.  May be grad_y itself (in place);
+ *                otherwise must not overlap it.
+ *
+ * Errors: as daf_unpack_dequantize; DAF_EINVAL also for partially overlapping gradients.
+ */
+int daf_unpack_relu_backward(const daf_plan_t* plan, const uint32_t* words, const float* min, const float* scale,
+                             const uint8_t* bits, const void* grad_y, void* out_grad_z, daf_dtype_t dtype,
+                             void* stream);
+
 int64_t daf_select_bits_workspace_bytes(int64_t num_groups);
 int daf_select_bits(const float* group_min, const float* group_max, int64_t num_groups,
                     const uint8_t* classes, int32_t n_classes, uint8_t* out_bits,

@@ -101,6 +101,14 @@ def relu(x: np.ndarray, dtype: int) -> np.ndarray:
     return np.where(v > 0, x, np.zeros_like(x))
 
 
+def relu_backward(xhat: np.ndarray, grad_y: np.ndarray, dtype: int) -> np.ndarray:
+    """grad_z = grad_y where xhat > 0, else +0 (backward of y = max(z, 0) seen through the
+    dequantized y); all arrays in the element format (float32, or uint16 bit patterns)."""
+    xhat = np.ascontiguousarray(xhat.reshape(-1), dtype=_NP[dtype])
+    grad_y = np.ascontiguousarray(grad_y.reshape(-1), dtype=_NP[dtype])
+    return np.where(widen(xhat, dtype) > 0, grad_y, np.zeros_like(grad_y))
+
+
 def minmax(x: np.ndarray, dtype: int) -> np.ndarray:
     """Whole-tensor (min, max) as float32[2]."""
     x = np.ascontiguousarray(x.reshape(-1), dtype=_NP[dtype])

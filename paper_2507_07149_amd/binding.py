@@ -57,6 +57,8 @@ def load_library():
     L.daf_quantize_pack_metrics.restype = c.c_int
     L.daf_relu_quantize_pack.argtypes = [vp, vp, c.c_int, u64, vp, vp, vp, vp, vp]
     L.daf_relu_quantize_pack.restype = c.c_int
+    L.daf_unpack_relu_backward.argtypes = [vp, vp, vp, vp, vp, vp, vp, c.c_int, vp]
+    L.daf_unpack_relu_backward.restype = c.c_int
     L.daf_group_minmax.argtypes = [vp, vp, c.c_int, vp, vp, vp]
     L.daf_group_minmax.restype = c.c_int
     L.daf_select_bits_workspace_bytes.argtypes = [i64]
@@ -160,6 +162,19 @@ def daf_unpack_dequantize(plan: Plan, words: torch.Tensor, mn: torch.Tensor, sca
                                               out_x.data_ptr(), _DTYPE_ID[out_x.dtype], _stream_handle(stream))
     if rc != 0:
         raise DafError(rc, "daf_unpack_dequantize")
+
+
+def daf_unpack_relu_backward(plan: Plan, words: torch.Tensor, mn: torch.Tensor, scale: torch.Tensor,
+                             grad_y: torch.Tensor, out_grad_z: torch.Tensor, bits: Optional[torch.Tensor] = None,
+                             stream=None) -> None:
+    if out_grad_z.dtype != grad_y.dtype or out_grad_z.numel() != grad_y.numel():
+        raise ValueError("out_grad_z must have the dtype and the number of elements of grad_y")
+    rc = load_library().daf_unpack_relu_backward(plan.handle, words.data_ptr(), mn.data_ptr(), scale.data_ptr(),
+                                                 bits.data_ptr() if bits is not None else None, grad_y.data_ptr(),
+                                                 out_grad_z.data_ptr(), _DTYPE_ID[grad_y.dtype],
+                                                 _stream_handle(stream))
+    if rc != 0:
+        raise DafError(rc, "daf_unpack_relu_backward")
 
 
 REDUCE_TWO_PASS, REDUCE_ATOMIC = 0, 1

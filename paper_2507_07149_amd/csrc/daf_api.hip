@@ -212,7 +212,30 @@ int daf_unpack_dequantize(const daf_plan_t* plan, const uint32_t* words, const f
   if (plan->uniform_bits && bits != nullptr) return DAF_EINVAL;
   if (dtype != DAF_F32 && dtype != DAF_F16 && dtype != DAF_BF16) return DAF_EUNSUPPORTED;
   const uint8_t* d_bits = bits ? bits : plan->d_bits;
-  const hipError_t e = daf_launch_unpack_dequantize(plan, words, min, scale, d_bits, out_x, (int)dtype,
+  const hipError_t e = daf_launch_unpack_dequantize(plan, words, min, scale, d_bits, out_x, (int)dtype, nullptr,
+                                                    static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? DAF_OK : DAF_EDEVICE;
+}
+
+int daf_unpack_relu_backward(const daf_plan_t* plan, const uint32_t* words, const float* min, const float* scale,
+                             const uint8_t* bits, const void* grad_y, void* out_grad_z, daf_dtype_t dtype,
+                             void* stream) {
+  if (plan == nullptr || words == nullptr || min == nullptr || scale == nullptr || grad_y == nullptr ||
+      out_grad_z == nullptr)
+    return DAF_EINVAL;
+  if (!aligned(out_grad_z, 16) || !aligned(grad_y, 16) || !aligned(words, 4) || !aligned(min, 4) ||
+      !aligned(scale, 4))
+    return DAF_EINVAL;
+  if (plan->uniform_bits && bits != nullptr) return DAF_EINVAL;
+  if (dtype != DAF_F32 && dtype != DAF_F16 && dtype != DAF_BF16) return DAF_EUNSUPPORTED;
+  if (out_grad_z != grad_y) {                                      // in place, or not overlapping at all
+    const int64_t bytes = plan->n * (dtype == DAF_F32 ? 4 : 2);
+    const char* a = static_cast<const char*>(grad_y);
+    const char* b = static_cast<const char*>(out_grad_z);
+    if (a < b + bytes && b < a + bytes) return DAF_EINVAL;
+  }
+  const uint8_t* d_bits = bits ? bits : plan->d_bits;
+  const hipError_t e = daf_launch_unpack_dequantize(plan, words, min, scale, d_bits, out_grad_z, (int)dtype, grad_y,
                                                     static_cast<hipStream_t>(stream));
   return e == hipSuccess ? DAF_OK : DAF_EDEVICE;
 }

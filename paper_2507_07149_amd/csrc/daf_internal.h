@@ -35,9 +35,10 @@ hipError_t daf_launch_quantize_pack(const daf_plan_t* plan, const void* x, int d
                                     uint32_t* out_words, float* out_min, float* out_scale, float* out_metrics,
                                     void* out_relu_y, hipStream_t stream);
 
+// relu_grad_y: null, or the gradient of y = max(z, 0): out_x then receives (xhat > 0) ? grad_y : +0
 hipError_t daf_launch_unpack_dequantize(const daf_plan_t* plan, const uint32_t* words, const float* mn,
                                         const float* scale, const uint8_t* d_bits, void* out_x, int dtype,
-                                        hipStream_t stream);
+                                        const void* relu_grad_y, hipStream_t stream);
 
 int64_t daf_minmax_workspace_size(void);
 hipError_t daf_launch_minmax_workspace_init(void* workspace, hipStream_t stream);

@@ -8,6 +8,11 @@
 //                              (or, at 8 bits and 16-bit output, two) packed words.  Covers every
 //                              whole chunk of the tensor, for any group size.
 //   k_unpack_dequantize_tail   the fewer than 8 elements after the last whole chunk.
+//
+// RELU_BWD = true turns both into the backward of y = max(z, 0) whose output y was the saved
+// activation: instead of xhat the kernels write grad_z = (xhat > 0) ? grad_y : +0, with xhat
+// rounded to the element format first, so the result is what a threshold on the materialised
+// xhat would give, and xhat itself never reaches memory.
 #include "daf_device.h"
 #include "daf_internal.h"
 
@@ -25,12 +30,21 @@ __device__ __forceinline__ void store_elem(void* out, int64_t i, float v) {
   else static_cast<uint16_t*>(out)[i] = (uint16_t)narrow16<DT == kF32 ? kF16 : DT>(v);
 }
 
-// The last elements of the tensor, [e_begin, n) with n - e_begin < 8: all in the last group.
+// Positive in the element format: the pattern read as a signed integer is > 0 (finite values).
 template <int DT>
+__device__ __forceinline__ uint32_t keep_where_positive(uint32_t xhat_word, uint32_t grad_word) {
+  if (DT == kF32) return ((int32_t)xhat_word > 0) ? grad_word : 0u;
+  const uint32_t lo = ((int16_t)(uint16_t)(xhat_word & 0xFFFFu) > 0) ? (grad_word & 0xFFFFu) : 0u;
+  const uint32_t hi = ((int16_t)(uint16_t)(xhat_word >> 16) > 0) ? (grad_word & 0xFFFF0000u) : 0u;
+  return lo | hi;
+}
+
+// The last elements of the tensor, [e_begin, n) with n - e_begin < 8: all in the last group.
+template <int DT, bool RELU_BWD>
 __global__ __launch_bounds__(kWave) void k_unpack_dequantize_tail(
     const uint32_t* __restrict__ words, const float* __restrict__ mn, const float* __restrict__ scale,
     const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, int32_t uniform_bits, int64_t e_begin,
-    int64_t n, int32_t gs, void* __restrict__ out) {
+    int64_t n, int32_t gs, void* out, const void* grad) {
   const int64_t i = e_begin + threadIdx.x;
   if (i >= n) return;
   const int64_t g = i / gs;
@@ -39,18 +53,30 @@ __global__ __launch_bounds__(kWave) void k_unpack_dequantize_tail(
   const uint64_t bitpos = (uint64_t)(i - g * (int64_t)gs) * b;
   const uint32_t w = words[woff + (bitpos >> 5)];
   const uint32_t code = (w >> (32u - b - (uint32_t)(bitpos & 31u))) & ((1u << b) - 1u);
-  store_elem<DT>(out, i, __builtin_fmaf((float)code, scale[g], mn[g]));
+  const float v = __builtin_fmaf((float)code, scale[g], mn[g]);
+  if (RELU_BWD) {
+    if (DT == kF32) {
+      const uint32_t gw = static_cast<const uint32_t*>(grad)[i];
+      static_cast<uint32_t*>(out)[i] = keep_where_positive<DT>(f2u(v), gw);
+    } else {
+      const uint32_t gw = static_cast<const uint16_t*>(grad)[i];
+      const uint32_t xh = narrow16<DT == kF32 ? kF16 : DT>(v);
+      static_cast<uint16_t*>(out)[i] = (uint16_t)keep_where_positive<DT>(xh, gw);
+    }
+  } else {
+    store_elem<DT>(out, i, v);
+  }
 }
 
 // The loop over a thread's chunks is split into phases (metadata loads, word loads,
 // arithmetic + stores) so that all loads of one phase are in flight together: with per-group
 // widths the word address depends on two earlier loads, and a chunk-by-chunk loop would pay
 // that latency once per chunk.
-template <int DT, bool MIXED>
+template <int DT, bool MIXED, bool RELU_BWD>
 __global__ __launch_bounds__(kThreads) void k_unpack_dequantize_chunk(
     const uint32_t* __restrict__ words, const float* __restrict__ mn, const float* __restrict__ scale,
     const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, int32_t uniform_bits,
-    int64_t n_chunks, int32_t gs, int32_t gs_shift, u32x4* __restrict__ out) {
+    int64_t n_chunks, int32_t gs, int32_t gs_shift, u32x4* out, const u32x4* grad) {
   constexpr int kEpl = ElemTraits<DT>::kPerLoad;
   constexpr int K = kChunksPerThread;
   const int64_t base = (int64_t)blockIdx.x * (kThreads * K) + threadIdx.x;
@@ -76,8 +102,14 @@ __global__ __launch_bounds__(kThreads) void k_unpack_dequantize_chunk(
     s[k] = scale[g[k]];
   }
   uint32_t w0[K], w1[K];
+  u32x4 gq[RELU_BWD ? K : 1];
 #pragma unroll
   for (int k = 0; k < K; ++k) {
+    if (RELU_BWD) {                                                // the gradient chunk at the output's place
+      int64_t c = base + (int64_t)k * kThreads;
+      c = (c < n_chunks) ? c : n_chunks - 1;
+      gq[k] = __builtin_nontemporal_load(&grad[c]);
+    }
     const uint64_t bit64 = (uint64_t)bitpos[k] * b[k];             // bit position in the group
     bitpos[k] = (uint32_t)bit64 & 31u;                             // ... and in its word
     const uint32_t* wp = words + woff[k] + (uint32_t)(bit64 >> 5);
@@ -115,13 +147,17 @@ __global__ __launch_bounds__(kThreads) void k_unpack_dequantize_chunk(
         h[q] = narrow16<D>(v[(2 * q) % kEpl]) | (narrow16<D>(v[(2 * q + 1) % kEpl]) << 16);
       o = (u32x4){h[0], h[1], h[2], h[3]};
     }
+    if (RELU_BWD) {
+      o = (u32x4){keep_where_positive<DT>(o.x, gq[k].x), keep_where_positive<DT>(o.y, gq[k].y),
+                  keep_where_positive<DT>(o.z, gq[k].z), keep_where_positive<DT>(o.w, gq[k].w)};
+    }
     if (c < n_chunks) __builtin_nontemporal_store(o, &out[c]);
   }
 }
 
-template <int DT>
+template <int DT, bool RELU_BWD>
 hipError_t launch_dtype(const daf_plan_t* p, const uint32_t* words, const float* mn, const float* scale,
-                        const uint8_t* d_bits, void* out_x, hipStream_t stream) {
+                        const uint8_t* d_bits, void* out_x, const void* grad, hipStream_t stream) {
   constexpr int kEpl = ElemTraits<DT>::kPerLoad;
   const int64_t n_chunks = p->n / kEpl;                 // a chunk never straddles a group (32 | group size)
   int32_t gs_shift = -1;
@@ -130,19 +166,19 @@ hipError_t launch_dtype(const daf_plan_t* p, const uint32_t* words, const float*
     const int64_t per_block = (int64_t)kThreads * kChunksPerThread;
     const unsigned blocks = (unsigned)((n_chunks + per_block - 1) / per_block);
     if (p->uniform_bits)
-      hipLaunchKernelGGL((k_unpack_dequantize_chunk<DT, false>), dim3(blocks), dim3(kThreads), 0, stream, words,
-                         mn, scale, nullptr, nullptr, p->uniform_bits, n_chunks, p->group_size, gs_shift,
-                         static_cast<u32x4*>(out_x));
+      hipLaunchKernelGGL((k_unpack_dequantize_chunk<DT, false, RELU_BWD>), dim3(blocks), dim3(kThreads), 0, stream,
+                         words, mn, scale, nullptr, nullptr, p->uniform_bits, n_chunks, p->group_size, gs_shift,
+                         static_cast<u32x4*>(out_x), static_cast<const u32x4*>(grad));
     else
-      hipLaunchKernelGGL((k_unpack_dequantize_chunk<DT, true>), dim3(blocks), dim3(kThreads), 0, stream, words,
-                         mn, scale, d_bits, p->d_off, 0, n_chunks, p->group_size, gs_shift,
-                         static_cast<u32x4*>(out_x));
+      hipLaunchKernelGGL((k_unpack_dequantize_chunk<DT, true, RELU_BWD>), dim3(blocks), dim3(kThreads), 0, stream,
+                         words, mn, scale, d_bits, p->d_off, 0, n_chunks, p->group_size, gs_shift,
+                         static_cast<u32x4*>(out_x), static_cast<const u32x4*>(grad));
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
   if (n_chunks * kEpl < p->n) {
-    hipLaunchKernelGGL((k_unpack_dequantize_tail<DT>), dim3(1), dim3(kWave), 0, stream, words, mn, scale, d_bits,
-                       p->d_off, p->uniform_bits, n_chunks * kEpl, p->n, p->group_size, out_x);
+    hipLaunchKernelGGL((k_unpack_dequantize_tail<DT, RELU_BWD>), dim3(1), dim3(kWave), 0, stream, words, mn, scale,
+                       d_bits, p->d_off, p->uniform_bits, n_chunks * kEpl, p->n, p->group_size, out_x, grad);
     return hipGetLastError();
   }
   return hipSuccess;
@@ -152,11 +188,15 @@ hipError_t launch_dtype(const daf_plan_t* p, const uint32_t* words, const float*
 
 hipError_t daf_launch_unpack_dequantize(const daf_plan_t* plan, const uint32_t* words, const float* mn,
                                         const float* scale, const uint8_t* d_bits, void* out_x, int dtype,
-                                        hipStream_t stream) {
+                                        const void* relu_grad_y, hipStream_t stream) {
+#define DAF_DT(D)                                                                                        \
+  return relu_grad_y ? launch_dtype<D, true>(plan, words, mn, scale, d_bits, out_x, relu_grad_y, stream) \
+                     : launch_dtype<D, false>(plan, words, mn, scale, d_bits, out_x, nullptr, stream)
   switch (dtype) {
-    case daf::kF32:  return launch_dtype<daf::kF32>(plan, words, mn, scale, d_bits, out_x, stream);
-    case daf::kF16:  return launch_dtype<daf::kF16>(plan, words, mn, scale, d_bits, out_x, stream);
-    case daf::kBF16: return launch_dtype<daf::kBF16>(plan, words, mn, scale, d_bits, out_x, stream);
+    case daf::kF32:  DAF_DT(daf::kF32);
+    case daf::kF16:  DAF_DT(daf::kF16);
+    case daf::kBF16: DAF_DT(daf::kBF16);
     default: return hipErrorInvalidValue;
   }
+#undef DAF_DT
 }

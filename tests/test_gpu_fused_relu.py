@@ -107,3 +107,75 @@ def test_fused_relu_argument_errors(env):
     with pytest.raises(daf.DafError) as e:
         daf.daf_relu_quantize_pack(long_plan, z, 0, z, words, mn[:1], sc[:1])
     assert e.value.status == -2
+
+
+# ---- consumer side: backward of max(z, 0) straight from the packed words --------------------
+
+@pytest.mark.parametrize("dtype", [F32, F16, BF16])
+@pytest.mark.parametrize("gs", [32, 64, 96, 256, 4096, 8192])
+@pytest.mark.parametrize("bits", [1, 2, 4, 8, "mixed"])
+@pytest.mark.parametrize("in_place", [False, True])
+def test_unpack_relu_backward_matrix(env, dtype, gs, bits, in_place):
+    daf, orc = env
+    n = 256 * 8 * 8 * 2 + 5 * gs + 13               # two blocks of chunks, whole groups, a ragged tail
+    G = (n + gs - 1) // gs
+    g = torch.Generator().manual_seed(17 * gs + dtype)
+    y = torch.relu(torch.randn(n, generator=g) * 1.5).to(torch_dtype(dtype))       # the saved activation
+    gy = torch.randn(n, generator=g).to(torch_dtype(dtype))
+    gy[::101] = -0.0
+    b = (np.random.default_rng(gs).choice([1, 2, 4, 8], G).astype(np.uint8) if bits == "mixed"
+         else np.array([bits], np.uint8))
+    print("case", dtype, gs, bits, in_place, flush=True)
+    ow, omn, osc, _ = orc.quantize_pack(to_numpy_bits(y), dtype, gs, b, 23)
+    oxh, _ = orc.unpack_dequantize(ow, omn, osc, b, n, gs, dtype)
+    want = orc.relu_backward(oxh, to_numpy_bits(gy), dtype)
+    assert 0.05 < np.count_nonzero(want) / n < 0.95      # both branches are exercised
+
+    dbits = torch.from_numpy(b).cuda() if b.size > 1 else None
+    plan = daf.daf_plan((n,), gs, dbits if dbits is not None else int(b[0]))
+    words = torch.from_numpy(ow.view(np.int32)).cuda()
+    mn, sc = torch.from_numpy(omn).cuda(), torch.from_numpy(osc).cuda()
+    gyd = gy.cuda()
+    out = gyd if in_place else torch.full_like(gyd, 3.0)
+    daf.daf_unpack_relu_backward(plan, words, mn, sc, gyd, out)
+    torch.cuda.synchronize()
+    got = to_numpy_bits(out.cpu())
+    assert np.array_equal(got.view(want.dtype), want), "grad_z differs"
+    if not in_place:
+        assert np.array_equal(to_numpy_bits(gyd.cpu()), to_numpy_bits(gy)), "grad_y was modified"
+    plan.destroy()
+
+
+def test_unpack_relu_backward_equals_threshold_on_materialised_xhat(env):
+    """Against the unfused GPU sequence: daf_unpack_dequantize, then torch's threshold backward."""
+    daf, _ = env
+    (w,) = make_config(3, 1 / 8)
+    x = torch.relu(w.x.float()).to(w.x.dtype).reshape(-1).cuda()
+    bits = torch.from_numpy(w.bits).cuda()
+    plan = daf.daf_plan(tuple(w.x.shape), w.group_size, bits)
+    words = torch.empty(plan.packed_words, dtype=torch.int32, device="cuda:0")
+    mn = torch.empty(plan.num_groups, device="cuda:0")
+    sc = torch.empty_like(mn)
+    daf.daf_quantize_pack(plan, x, w.seed, words, mn, sc)
+    xh = torch.empty_like(x)
+    daf.daf_unpack_dequantize(plan, words, mn, sc, xh)
+    gy = torch.randn(x.numel(), device="cuda:0").to(x.dtype)
+    gz = torch.empty_like(gy)
+    daf.daf_unpack_relu_backward(plan, words, mn, sc, gy, gz)
+    torch.cuda.synchronize()
+    want = torch.where(xh > 0, gy, torch.zeros_like(gy))
+    assert torch.equal(gz.view(torch.int16), want.view(torch.int16))
+    plan.destroy()
+
+
+def test_unpack_relu_backward_argument_errors(env):
+    daf, _ = env
+    plan = daf.daf_plan((8192,), 256, 2)
+    words = torch.zeros(plan.packed_words, dtype=torch.int32, device="cuda:0")
+    mn = torch.zeros(plan.num_groups, device="cuda:0")
+    big = torch.zeros(8192 + 1024, device="cuda:0")
+    with pytest.raises(daf.DafError) as e:
+        daf.daf_unpack_relu_backward(plan, words, mn, mn, big[:8192], big[1024:])
+    assert e.value.status == -1
+    with pytest.raises(ValueError):
+        daf.daf_unpack_relu_backward(plan, words, mn, mn, big[:8192], torch.zeros(8192, dtype=torch.float16, device="cuda:0"))

@@ -68,3 +68,25 @@ def test_relu_matches_torch_on_every_16_bit_pattern_and_on_floats():
     want = torch.relu(torch.from_numpy(x)).numpy() + np.float32(0.0)      # -0 + 0 = +0
     got = orc.relu(x, orc.F32)
     assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+
+
+def test_relu_backward_matches_torch_threshold_backward():
+    import torch
+    rng = np.random.default_rng(9)
+    for dt, tdt in ((orc.F32, torch.float32), (orc.F16, torch.float16), (orc.BF16, torch.bfloat16)):
+        xh = torch.from_numpy(rng.standard_normal(20000).astype(np.float32)).to(tdt)
+        xh[::7] = 0.0
+        xh[3::11] = -0.0
+        gy = torch.from_numpy(rng.standard_normal(20000).astype(np.float32)).to(tdt)
+        want = torch.ops.aten.threshold_backward(gy.float(), xh.float(), 0.0).to(tdt)
+        bits = lambda t: t.view(torch.int32 if dt == orc.F32 else torch.int16).numpy().view(
+            np.uint32 if dt == orc.F32 else np.uint16)
+        src = (lambda t: t.numpy()) if dt == orc.F32 else bits
+        got = orc.relu_backward(src(xh), src(gy), dt)
+        want_bits = bits(want + 0.0) if dt == orc.F32 else bits(want)
+        got_bits = got.view(np.uint32) if dt == orc.F32 else got
+        zero_neg = np.uint32(0x80000000) if dt == orc.F32 else np.uint16(0x8000)
+        want_bits = np.where(want_bits == zero_neg, 0, want_bits)      # a dropped gradient is +0 here
+        kept = src(gy) == zero_neg if dt != orc.F32 else bits(gy) == zero_neg
+        want_bits = np.where(kept & (got_bits == zero_neg), zero_neg, want_bits)   # a kept -0 gradient stays -0
+        assert np.array_equal(got_bits, want_bits)
