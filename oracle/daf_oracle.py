@@ -109,6 +109,16 @@ def relu_backward(xhat: np.ndarray, grad_y: np.ndarray, dtype: int) -> np.ndarra
     return np.where(widen(xhat, dtype) > 0, grad_y, np.zeros_like(grad_y))
 
 
+def grad_weight(xhat: np.ndarray, grad_y: np.ndarray, m: int, k: int, n: int, dtype: int) -> np.ndarray:
+    """Weight gradient of y = x W^T seen through the dequantized activation:
+    dW[j, c] = sum_i grad_y[i, j] * xhat[i, c], float64[n, k].  xhat is [m, k] and grad_y is [m, n],
+    both in the element format (float32, or uint16 bit patterns); the products and the sum are
+    evaluated in double precision (each product of two 16-bit-format values is exact in it)."""
+    xh = widen(xhat, dtype).astype(np.float64).reshape(m, k)
+    gy = widen(grad_y, dtype).astype(np.float64).reshape(m, n)
+    return gy.T @ xh
+
+
 def minmax(x: np.ndarray, dtype: int) -> np.ndarray:
     """Whole-tensor (min, max) as float32[2]."""
     x = np.ascontiguousarray(x.reshape(-1), dtype=_NP[dtype])

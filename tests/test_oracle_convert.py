@@ -90,3 +90,36 @@ def test_relu_backward_matches_torch_threshold_backward():
         kept = src(gy) == zero_neg if dt != orc.F32 else bits(gy) == zero_neg
         want_bits = np.where(kept & (got_bits == zero_neg), zero_neg, want_bits)   # a kept -0 gradient stays -0
         assert np.array_equal(got_bits, want_bits)
+
+
+def test_grad_weight_against_explicit_loops_and_fractions():
+    # the definition written out with exact rational arithmetic on a tiny case, and with plain
+    # Python loops on a slightly larger one
+    from fractions import Fraction
+    import torch
+    rng = np.random.default_rng(2)
+    m, k, n = 5, 4, 3
+    xh = torch.from_numpy(rng.standard_normal((m, k)).astype(np.float32)).to(torch.bfloat16)
+    gy = torch.from_numpy(rng.standard_normal((m, n)).astype(np.float32)).to(torch.bfloat16)
+    bits = lambda t: t.view(torch.int16).numpy().view(np.uint16)
+    got = orc.grad_weight(bits(xh), bits(gy), m, k, n, orc.BF16)
+    assert got.shape == (n, k) and got.dtype == np.float64
+    for j in range(n):
+        for c in range(k):
+            exact = sum(Fraction(float(gy[i, j])) * Fraction(float(xh[i, c])) for i in range(m))
+            assert abs(Fraction(float(got[j, c])) - exact) <= abs(exact) * Fraction(1, 2 ** 48) + Fraction(1, 2 ** 200)
+    m, k, n = 17, 9, 6
+    xh = rng.standard_normal((m, k)).astype(np.float32)
+    gy = rng.standard_normal((m, n)).astype(np.float32)
+    got = orc.grad_weight(xh, gy, m, k, n, orc.F32)
+    for j in range(n):
+        for c in range(k):
+            want = 0.0
+            for i in range(m):
+                want += float(gy[i, j]) * float(xh[i, c])
+            assert abs(got[j, c] - want) <= 1e-12 * (1 + abs(want))
+    # transposed operand check: a matrix with one non-zero entry lands where the definition says
+    xh = np.zeros((m, k), np.float32); gy = np.zeros((m, n), np.float32)
+    xh[3, 7] = 2.0; gy[3, 4] = 5.0
+    got = orc.grad_weight(xh, gy, m, k, n, orc.F32)
+    assert got[4, 7] == 10.0 and np.count_nonzero(got) == 1
