@@ -257,6 +257,33 @@ int daf_unpack_relu_backward(const daf_plan_t* plan, const uint32_t* words, cons
                              const uint8_t* bits, const void* grad_y, void* out_grad_z, daf_dtype_t dtype,
                              void* stream);
 
+/* ---- consumer fusion for a contraction ---------------------------------------------------------
+ *
+ * daf_unpack_matmul_grad_weight -- weight gradient of a linear layer y = x W^T whose input x
+ * is the saved, quantized activation: with the plan's tensor read as x[M, K] (M = N_elements / K,
+ * row-major, groups inside a row) and grad_y[M, N],
+ *     out_grad_w[n, k] = sum_m grad_y[m, n] * xhat[m, k]        (binary32, [N, K] row-major)
+ * where xhat[m, k] is exactly the value daf_unpack_dequantize would write in `dtype`.  The words
+ * are unpacked and dequantized tile by tile inside the product (matrix cores, binary32
+ * accumulation) and xhat is never written to memory (Sec. 3.3 / Sec. 4.3.1: unpack next to the
+ * consumer).  The order of the additions differs from a plain loop, so the result agrees with a
+ * double-precision evaluation to about M * 2^-24 relative to sum_m |grad_y| * |xhat|.
+ *
+ *   grad_y       DEVICE, M*N elements of dtype (DAF_F16 or DAF_BF16), 16-byte aligned.
+ *   N, K         columns of grad_y; columns of x (must divide the plan's element count).
+ *   out_grad_w   DEVICE, N*K floats, 16-byte aligned.
+ *   workspace    DEVICE, daf_unpack_matmul_workspace_bytes(plan, N, K) bytes, 16-byte aligned
+ *                (partial sums when m is split over several work-groups; may be NULL if 0).
+ *
+ * Errors: DAF_EINVAL (null or misaligned pointer, K not dividing the element count, missing
+ * workspace); DAF_EUNSUPPORTED (binary32 tensors; M % 64, N % 256, K % 128 or K % group_size
+ * non-zero); DAF_EDEVICE.  daf_unpack_matmul_workspace_bytes returns -1 for such shapes.
+ */
+int64_t daf_unpack_matmul_workspace_bytes(const daf_plan_t* plan, int64_t N, int64_t K);
+int daf_unpack_matmul_grad_weight(const daf_plan_t* plan, const uint32_t* words, const float* min, const float* scale,
+                                  const uint8_t* bits, const void* grad_y, int64_t N, int64_t K, daf_dtype_t dtype,
+                                  float* out_grad_w, void* workspace, void* stream);
+
 int64_t daf_select_bits_workspace_bytes(int64_t num_groups);
 int daf_select_bits(const float* group_min, const float* group_max, int64_t num_groups,
                     const uint8_t* classes, int32_t n_classes, uint8_t* out_bits,

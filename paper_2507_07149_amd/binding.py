@@ -59,6 +59,10 @@ def load_library():
     L.daf_relu_quantize_pack.restype = c.c_int
     L.daf_unpack_relu_backward.argtypes = [vp, vp, vp, vp, vp, vp, vp, c.c_int, vp]
     L.daf_unpack_relu_backward.restype = c.c_int
+    L.daf_unpack_matmul_workspace_bytes.argtypes = [vp, i64, i64]
+    L.daf_unpack_matmul_workspace_bytes.restype = i64
+    L.daf_unpack_matmul_grad_weight.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, c.c_int, vp, vp, vp]
+    L.daf_unpack_matmul_grad_weight.restype = c.c_int
     L.daf_group_minmax.argtypes = [vp, vp, c.c_int, vp, vp, vp]
     L.daf_group_minmax.restype = c.c_int
     L.daf_select_bits_workspace_bytes.argtypes = [i64]
@@ -175,6 +179,26 @@ def daf_unpack_relu_backward(plan: Plan, words: torch.Tensor, mn: torch.Tensor, 
                                                  _stream_handle(stream))
     if rc != 0:
         raise DafError(rc, "daf_unpack_relu_backward")
+
+
+def daf_unpack_matmul_workspace_bytes(plan: Plan, N: int, K: int) -> int:
+    return int(load_library().daf_unpack_matmul_workspace_bytes(plan.handle, N, K))
+
+
+def daf_unpack_matmul_grad_weight(plan: Plan, words: torch.Tensor, mn: torch.Tensor, scale: torch.Tensor,
+                                  grad_y: torch.Tensor, out_grad_w: torch.Tensor,
+                                  workspace: Optional[torch.Tensor] = None, bits: Optional[torch.Tensor] = None,
+                                  stream=None) -> None:
+    """grad_y is [M, N]; out_grad_w is float32 [N, K]; the plan's tensor is read as [M, K]."""
+    N, K = out_grad_w.shape
+    if out_grad_w.dtype != torch.float32 or grad_y.shape[-1] != N:
+        raise ValueError("out_grad_w must be float32 [N, K] with N = grad_y.shape[-1]")
+    rc = load_library().daf_unpack_matmul_grad_weight(
+        plan.handle, words.data_ptr(), mn.data_ptr(), scale.data_ptr(), bits.data_ptr() if bits is not None else None,
+        grad_y.data_ptr(), N, K, _DTYPE_ID[grad_y.dtype], out_grad_w.data_ptr(),
+        workspace.data_ptr() if workspace is not None else None, _stream_handle(stream))
+    if rc != 0:
+        raise DafError(rc, "daf_unpack_matmul_grad_weight")
 
 
 REDUCE_TWO_PASS, REDUCE_ATOMIC = 0, 1

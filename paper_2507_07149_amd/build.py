@@ -18,7 +18,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libdaf.so")
 SOURCES = ["daf_api.hip", "plan_scan.hip", "quantize_pack.hip", "unpack_dequantize.hip", "minmax.hip",
-           "select_bits.hip", "page_store.cpp"]
+           "select_bits.hip", "unpack_matmul.hip", "page_store.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-ffp-contract=off", "-fno-strict-aliasing",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall",
@@ -42,7 +42,7 @@ def _compile(src: str) -> str:
 
 def build() -> str:
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=7) as ex:
+    with ThreadPoolExecutor(max_workers=8) as ex:
         objs = list(ex.map(_compile, SOURCES))
     subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], check=True)
     return LIB

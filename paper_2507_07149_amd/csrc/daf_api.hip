@@ -240,6 +240,35 @@ int daf_unpack_relu_backward(const daf_plan_t* plan, const uint32_t* words, cons
   return e == hipSuccess ? DAF_OK : DAF_EDEVICE;
 }
 
+int64_t daf_unpack_matmul_workspace_bytes(const daf_plan_t* plan, int64_t N, int64_t K) {
+  if (plan == nullptr || N <= 0 || K <= 0 || plan->n % K != 0) return -1;
+  const int64_t M = plan->n / K;
+  if (!daf_unpack_matmul_shape_ok(M, N, K, plan->group_size)) return -1;
+  const int32_t splits = daf_unpack_matmul_splits(M, N, K);
+  return splits > 1 ? (int64_t)splits * N * K * 4 : 0;
+}
+
+int daf_unpack_matmul_grad_weight(const daf_plan_t* plan, const uint32_t* words, const float* min, const float* scale,
+                                  const uint8_t* bits, const void* grad_y, int64_t N, int64_t K, daf_dtype_t dtype,
+                                  float* out_grad_w, void* workspace, void* stream) {
+  if (plan == nullptr || words == nullptr || min == nullptr || scale == nullptr || grad_y == nullptr ||
+      out_grad_w == nullptr)
+    return DAF_EINVAL;
+  if (N <= 0 || K <= 0 || plan->n % K != 0) return DAF_EINVAL;
+  if (!aligned(grad_y, 16) || !aligned(out_grad_w, 16) || !aligned(words, 4) || !aligned(min, 4) ||
+      !aligned(scale, 4) || !aligned(workspace, 16))
+    return DAF_EINVAL;
+  if (plan->uniform_bits && bits != nullptr) return DAF_EINVAL;
+  if (dtype != DAF_F16 && dtype != DAF_BF16) return DAF_EUNSUPPORTED;
+  const int64_t M = plan->n / K;
+  if (!daf_unpack_matmul_shape_ok(M, N, K, plan->group_size)) return DAF_EUNSUPPORTED;
+  if (daf_unpack_matmul_splits(M, N, K) > 1 && workspace == nullptr) return DAF_EINVAL;
+  const uint8_t* d_bits = bits ? bits : plan->d_bits;
+  const hipError_t e = daf_launch_unpack_matmul(plan, words, min, scale, d_bits, grad_y, N, K, (int)dtype, out_grad_w,
+                                                static_cast<float*>(workspace), static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? DAF_OK : DAF_EDEVICE;
+}
+
 int64_t daf_minmax_workspace_bytes(void) { return daf_minmax_workspace_size(); }
 
 int daf_minmax_workspace_init(void* workspace, void* stream) {

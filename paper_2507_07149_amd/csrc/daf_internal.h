@@ -35,6 +35,14 @@ hipError_t daf_launch_quantize_pack(const daf_plan_t* plan, const void* x, int d
                                     uint32_t* out_words, float* out_min, float* out_scale, float* out_metrics,
                                     void* out_relu_y, hipStream_t stream);
 
+// Weight gradient straight from the packed activation (unpack_matmul.hip).  The plan's tensor is
+// read as [n / K, K]; out is [N, K] binary32; workspace holds splits * N * K floats when splits > 1.
+int32_t daf_unpack_matmul_splits(int64_t M, int64_t N, int64_t K);
+bool daf_unpack_matmul_shape_ok(int64_t M, int64_t N, int64_t K, int32_t gs);
+hipError_t daf_launch_unpack_matmul(const daf_plan_t* p, const uint32_t* words, const float* mn, const float* scale,
+                                    const uint8_t* d_bits, const void* grad_y, int64_t N, int64_t K, int dtype,
+                                    float* out, float* workspace, hipStream_t stream);
+
 // relu_grad_y: null, or the gradient of y = max(z, 0): out_x then receives (xhat > 0) ? grad_y : +0
 hipError_t daf_launch_unpack_dequantize(const daf_plan_t* plan, const uint32_t* words, const float* mn,
                                         const float* scale, const uint8_t* d_bits, void* out_x, int dtype,

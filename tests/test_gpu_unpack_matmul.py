@@ -1,0 +1,96 @@
+"""GPU parity of the fused weight gradient: daf_unpack_matmul_grad_weight (unpack + dequantize
+inside the matrix product) against the oracle's dequantized activation multiplied out in double
+precision.  The additions happen in binary32 in an unspecified order, so the bar is the
+accumulation bound M * 2^-24 * sum_m |grad_y| |xhat| (with a factor 2 of slack)."""
+import numpy as np
+import pytest
+import torch
+
+from daf_inputs import BF16, F16, F32, to_numpy_bits, torch_dtype
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import paper_2507_07149_amd as daf
+    from oracle import daf_oracle as orc
+    assert torch.cuda.is_available()
+    return daf, orc
+
+
+def _case(daf, orc, M, N, K, gs, bits, dtype, seed):
+    g = torch.Generator().manual_seed(seed)
+    x = (torch.randn(M, K, generator=g) * (1 + torch.rand(M, 1, generator=g))).to(torch_dtype(dtype))
+    gy = (torch.randn(M, N, generator=g) * 0.5).to(torch_dtype(dtype))
+    G = M * K // gs
+    b = (np.random.default_rng(seed).choice([1, 2, 4, 8], G).astype(np.uint8) if bits == "mixed"
+         else np.array([bits], np.uint8))
+    ow, omn, osc, _ = orc.quantize_pack(to_numpy_bits(x), dtype, gs, b, seed)
+    oxh, _ = orc.unpack_dequantize(ow, omn, osc, b, M * K, gs, dtype)
+    want = orc.grad_weight(oxh, to_numpy_bits(gy), M, K, N, dtype)
+    mag = orc.grad_weight(np.abs(orc.widen(oxh, dtype)), np.abs(orc.widen(to_numpy_bits(gy), dtype)), M, K, N, F32)
+
+    dbits = torch.from_numpy(b).cuda() if b.size > 1 else None
+    plan = daf.daf_plan((M, K), gs, dbits if dbits is not None else int(b[0]))
+    ws_bytes = daf.daf_unpack_matmul_workspace_bytes(plan, N, K)
+    assert ws_bytes >= 0
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda:0")
+    out = torch.full((N, K), float("nan"), device="cuda:0")
+    daf.daf_unpack_matmul_grad_weight(plan, torch.from_numpy(ow.view(np.int32)).cuda(), torch.from_numpy(omn).cuda(),
+                                      torch.from_numpy(osc).cuda(), gy.cuda(), out, ws)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    bound = 2.0 * M * 2.0 ** -24 * mag + 1e-30
+    err = np.abs(got - want)
+    assert np.all(err <= bound), (f"worst {err.max():.3e} at {np.unravel_index(err.argmax(), err.shape)}, "
+                                  f"bound there {bound.flat[err.argmax()]:.3e}, share outside {np.mean(err > bound):.4f}")
+    plan.destroy()
+    return ws_bytes
+
+
+@pytest.mark.parametrize("dtype", [BF16, F16])
+@pytest.mark.parametrize("bits", [1, 2, 4, 8, "mixed"])
+@pytest.mark.parametrize("gs", [32, 128])
+def test_grad_weight_small(env, dtype, bits, gs):
+    daf, orc = env
+    print("case small", dtype, bits, gs, flush=True)
+    _case(daf, orc, 128, 256, 256, gs, bits, dtype, 7)                 # two k-tiles, m split in two
+
+
+@pytest.mark.parametrize("shape", [(64, 256, 128), (192, 512, 384), (1024, 256, 128), (2048, 512, 1024)])
+@pytest.mark.parametrize("bits", [2, "mixed"])
+def test_grad_weight_shapes(env, shape, bits):
+    daf, orc = env
+    M, N, K = shape
+    print("case shape", shape, bits, flush=True)
+    _case(daf, orc, M, N, K, 64, bits, BF16, 11)
+
+
+def test_grad_weight_without_split_needs_no_workspace(env):
+    daf, orc = env
+    print("case no split", flush=True)
+    ws = _case(daf, orc, 64, 4096, 4096, 256, 4, BF16, 3)              # 512 tiles: one slice of m
+    assert ws == 0
+
+
+def test_grad_weight_argument_errors(env):
+    daf, _ = env
+    plan = daf.daf_plan((128, 256), 64, 2)
+    words = torch.zeros(plan.packed_words, dtype=torch.int32, device="cuda:0")
+    mn = torch.zeros(plan.num_groups, device="cuda:0")
+    gy = torch.zeros(128, 256, dtype=torch.bfloat16, device="cuda:0")
+    out = torch.zeros(256, 256, device="cuda:0")
+    assert daf.daf_unpack_matmul_workspace_bytes(plan, 256, 256) > 0
+    assert daf.daf_unpack_matmul_workspace_bytes(plan, 100, 256) == -1       # N not a multiple of 256
+    assert daf.daf_unpack_matmul_workspace_bytes(plan, 256, 96) == -1        # K does not divide the tensor
+    with pytest.raises(daf.DafError) as e:                                    # split, but no workspace
+        daf.daf_unpack_matmul_grad_weight(plan, words, mn, mn, gy, out, None)
+    assert e.value.status == -1
+    with pytest.raises(daf.DafError) as e:                                    # binary32 is not offered
+        daf.daf_unpack_matmul_grad_weight(plan, words, mn, mn, gy.float(), out, torch.empty(1 << 22, dtype=torch.uint8, device="cuda:0"))
+    assert e.value.status == -2
+    plan2 = daf.daf_plan((96, 256), 64, 2)                                    # M not a multiple of 64
+    with pytest.raises(daf.DafError) as e:
+        daf.daf_unpack_matmul_grad_weight(plan2, words, mn, mn, gy[:96], out, torch.empty(1 << 22, dtype=torch.uint8, device="cuda:0"))
+    assert e.value.status == -2
