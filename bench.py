@@ -56,6 +56,10 @@ def parse():
                     help="the timed steps launch independent tensors / independent batches round-robin on "
                          "this many HIP streams (default priority), so that the tail of one kernel overlaps "
                          "the start of the next; the per-kernel roofline timing always uses one stream")
+    ap.add_argument("--fused-matmul", action="store_true",
+                    help="time daf_unpack_matmul_grad_weight (unpack+dequantize inside the weight-gradient "
+                         "product) against daf_unpack_dequantize followed by the library matrix product; "
+                         "--config 5 (LLM MLP, bf16) or 3 (ViT MLP, fp16)")
     ap.add_argument("--fused-relu", action="store_true",
                     help="time daf_relu_quantize_pack (activation function fused into the quantize pass) "
                          "against a separate relu kernel followed by daf_quantize_pack")
@@ -228,6 +232,64 @@ def main():
                           "group_minmax_frac_of_8TBps": round(stats_bytes / t_stats / 1e3 / HBM_PEAK_GBPS, 4),
                           "select_bits_us": round(t_select, 2), "plan_us_with_sync": round(t_plan, 1),
                           "widths_match_generator": ok}))
+        return
+
+    if args.fused_matmul:
+        (w,) = make_config(args.config)
+        K = w.x.shape[-1]
+        M = w.numel // K
+        N = {5: 4096, 3: 3072}.get(args.config, 1024)
+        x = w.x.reshape(-1).to(dev)
+        bits = int(w.bits[0]) if w.bits.size == 1 else torch.from_numpy(w.bits).to(dev)
+        plan = daf.daf_plan((M, K), w.group_size, bits)
+        words = torch.empty(plan.packed_words, dtype=torch.int32, device=dev)
+        mn, sc = torch.empty(plan.num_groups, device=dev), torch.empty(plan.num_groups, device=dev)
+        daf.daf_quantize_pack(plan, x, w.seed, words, mn, sc)
+        gy = (torch.randn(M, N, device=dev) * 0.1).to(w.x.dtype)
+        out = torch.empty(N, K, device=dev)
+        ws_bytes = daf.daf_unpack_matmul_workspace_bytes(plan, N, K)
+        if ws_bytes < 0:
+            print("bench.py: shape not supported by the fused product", file=sys.stderr)
+            sys.exit(2)
+        ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+        xh = torch.empty(M, K, dtype=w.x.dtype, device=dev)
+        out_lib = torch.empty(N, K, dtype=w.x.dtype, device=dev)
+
+        def timed(fn, reps):
+            for _ in range(max(2, args.warmup // 4)):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps
+
+        def unfused():
+            daf.daf_unpack_dequantize(plan, words, mn, sc, xh.view(-1))
+            torch.mm(gy.t(), xh, out=out_lib)
+
+        reps = max(3, min(args.steps, 20))
+        t_fused = timed(lambda: daf.daf_unpack_matmul_grad_weight(plan, words, mn, sc, gy, out, ws), reps)
+        t_unfused = timed(unfused, reps)
+        t_mm = timed(lambda: torch.mm(gy.t(), xh, out=out_lib), reps)
+        rel = ((out - out_lib.float()).abs().max() / out.abs().max()).item()
+        flops = 2.0 * M * N * K
+        ach = flops / (t_fused * 1e-3) / 1e12
+        print(json.dumps({"metric": "weight gradient from the packed activation, TFLOP/s", "value": round(ach, 1),
+                          "unit": "TFLOP/s", "n_gpus": 1, "steps": reps, "data": "synthetic", "higher_is_better": True,
+                          "dtype": {1: "f16", 2: "bf16"}[w.dtype],
+                          "config": {"workload": CONFIG_NAMES[args.config] + f"_grad_weight_N{N}", "M": M, "N": N, "K": K,
+                                     "splits_workspace_bytes": ws_bytes},
+                          "fused_ms": round(t_fused, 4), "unfused_dequantize_plus_library_mm_ms": round(t_unfused, 4),
+                          "library_mm_alone_ms": round(t_mm, 4),
+                          "library_mm_TFLOPs": round(flops / (t_mm * 1e-3) / 1e12, 1),
+                          "xhat_bytes_never_written": M * K * w.x.element_size(),
+                          "max_rel_diff_vs_library_bf16_output": round(rel, 5),
+                          "roofline": {"bound": "mfma", "achieved": round(ach, 1), "peak": 2500.0, "unit": "TFLOP/s",
+                                       "frac": round(ach / 2500.0, 4), "traffic": None, "kernel": "k_unpack_matmul"}}))
         return
 
     if args.fused_relu:

@@ -45,60 +45,49 @@ __device__ __forceinline__ uint32_t lds_unit(uint32_t col, uint32_t oct) {
   return col * (uint32_t)kOct + (oct ^ ((col & 7u) ^ ((col >> 3) & 7u)));
 }
 
-// What one thread fetches for one step: 4 rows x 8 columns of each of the two 128-column halves
-// of the grad_y tile, and the packed words and group constants of 4 rows x 8 columns of xhat.
-struct Fetch {
+// With per-group widths the address of a row's words depends on off[] and bits[] of its group:
+// those are fetched one step before the words are requested.
+struct Addr {
+  uint32_t b[4], off[4];
+};
+// Everything a thread needs to build its share of one step's LDS tiles: 4 rows x 8 columns of
+// each 128-column panel of grad_y, and the words, width, min and scale of 4 rows x 8 columns of x.
+struct Stage {
   uint4 gy[2][4];
-  uint32_t w0[4], w1[4], shift[4], b[4];
+  uint32_t w0[4], w1[4], b[4];
   float mn[4], sc[4];
 };
+constexpr int kStages = 3;                          // loads are requested kStages-1 steps ahead
 
-template <int DT, bool MIXED>
-__device__ __forceinline__ void fetch_step(Fetch& f, const u32x4* __restrict__ grad_y, int64_t N8, int64_t m_base,
-                                           int64_t n0_8, uint32_t co, const uint32_t* __restrict__ words,
-                                           const float* __restrict__ mn, const float* __restrict__ scale,
-                                           const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off,
-                                           uint32_t uniform_bits, int64_t groups_per_row, int32_t gs,
-                                           uint32_t words_per_group_bit, int64_t k_col) {
-#pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const int64_t m = m_base + r;
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const u32x4 v = grad_y[m * N8 + n0_8 + 16 * h + co];
-      f.gy[h][r] = make_uint4(v.x, v.y, v.z, v.w);
-    }
-    // the 8 codes of row m, columns k_col .. k_col+7: one group, one or two words
-    const int64_t gk = k_col / gs;
-    const int64_t g = m * groups_per_row + gk;
-    const uint32_t in_group = (uint32_t)(k_col - gk * gs);
-    uint32_t b, woff;
-    if (MIXED) {
-      b = bits[g];
-      woff = off[g];
-    } else {
-      b = uniform_bits;
-      woff = (uint32_t)g * (words_per_group_bit * b);
-    }
-    const uint32_t bit = in_group * b;
-    const uint32_t* wp = words + woff + (bit >> 5);
-    f.w0[r] = wp[0];
-    f.w1[r] = (b == 8u) ? wp[1] : 0u;
-    f.shift[r] = 32u - 8u * b - (bit & 31u);        // used for b < 8 only
-    f.b[r] = b;
-    f.mn[r] = mn[g];
-    f.sc[r] = scale[g];
+template <int I> struct Index { static constexpr int value = I; };
+template <int N, int I = 0, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(Index<I>{});
+    static_for<N, I + 1>(f);
   }
 }
 
-// 16-bit pattern of xhat for code c (exactly what the plain dequantize kernel stores).
+// Two binary32 values rounded to nearest-even in the 16-bit format, lo in bits 0..15 (the same
+// patterns the plain dequantize kernel stores; the compiler's conversions are the hardware's
+// round-to-nearest-even ones, one instruction per pair for bf16).
 template <int DT>
-__device__ __forceinline__ uint32_t xhat16(uint32_t code, float sc, float mn) {
-  return narrow16<DT>(__builtin_fmaf((float)code, sc, mn));
+__device__ __forceinline__ uint32_t narrow16_pair(float lo, float hi) {
+  if constexpr (DT == kBF16) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+  } else {
+    asm("" : "+v"(lo), "+v"(hi));                   // the binary32 values exist before they are rounded again
+    typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+    const f16x2 v = {(_Float16)lo, (_Float16)hi};
+    return __builtin_bit_cast(uint32_t, v);
+  }
 }
 
 template <int DT, bool MIXED>
-__global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
+__global__ __launch_bounds__(kThreads) void k_unpack_matmul(
     const uint32_t* __restrict__ words, const float* __restrict__ mn, const float* __restrict__ scale,
     const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, uint32_t uniform_bits, int32_t gs,
     const u32x4* __restrict__ grad_y, int64_t M, int64_t N, int64_t K, int32_t tiles_n, int32_t tiles_k,
@@ -108,30 +97,78 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
 
   const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
   // Consecutive block ids go to different XCDs (each with its own L2).  Give every XCD a
-  // contiguous range of tiles, n fastest, so that the tiles resident on one XCD share their
-  // xhat panel and a few grad_y panels.
+  // contiguous range of the tile sequence, and order the sequence in bands of 4 tiles of n, k
+  // running inside a band: the ~32 tiles resident on an XCD then form a 4 x 8 patch that reads
+  // 4 panels of grad_y and 8 (small) panels of packed words per step instead of all 16 of grad_y.
   const uint32_t n_tiles = (uint32_t)tiles_n * (uint32_t)tiles_k;
-  const uint32_t per_split = n_tiles;
   const uint32_t bid = blockIdx.x;
-  const uint32_t split = bid / per_split;
-  uint32_t tile = bid - split * per_split;
+  const uint32_t split = bid / n_tiles;
+  uint32_t tile = bid - split * n_tiles;
   {
     const uint32_t xcd = tile & 7u, idx = tile >> 3;
     const uint32_t base = n_tiles / 8u, rem = n_tiles & 7u;       // XCD x owns base (+1 if x < rem) tiles
     tile = xcd * base + (xcd < rem ? xcd : rem) + idx;
   }
-  const uint32_t tn = tile % (uint32_t)tiles_n, tk = tile / (uint32_t)tiles_n;
+  constexpr uint32_t kBand = 4;
+  const uint32_t band = tile / (kBand * (uint32_t)tiles_k);
+  const uint32_t in_band = tile - band * (kBand * (uint32_t)tiles_k);
+  const uint32_t band_h = ((uint32_t)tiles_n - band * kBand) < kBand ? ((uint32_t)tiles_n - band * kBand) : kBand;
+  const uint32_t tn = band * kBand + in_band % band_h, tk = in_band / band_h;
   const int64_t n0 = (int64_t)tn * kBN, k0 = (int64_t)tk * kBK;
   const int64_t m_per_split = M / splits;
   const int64_t m_begin = (int64_t)split * m_per_split;
   const int steps = (int)(m_per_split / kBM);
 
-  const uint32_t co = t & 15u, rq = t >> 4;         // column octet and row quad of the loader role
+  // Loader role: thread (co, rq) owns rows 4*rq .. 4*rq+3 of the step and 8 columns of each
+  // 128-column panel.  Addresses are a block-uniform 64-bit base that advances by a constant per
+  // step, plus 32-bit per-thread offsets.
+  const uint32_t co = t & 15u, rq = t >> 4;
   const uint32_t oct = rq >> 1, half = rq & 1u;
-  const int64_t N8 = N / 8;
-  const int64_t groups_per_row = K / gs;
-  const uint32_t wpgb = (uint32_t)gs >> 5;
-  const int64_t k_col = k0 + 8 * (int64_t)co;
+  const uint32_t row_chunks = (uint32_t)(N / 8);                        // 16-byte chunks per grad_y row
+  const uint32_t gpr = (uint32_t)(K / gs);                              // groups per row of x
+  const uint32_t k_col = (uint32_t)k0 + 8u * co;
+  const uint32_t gk = k_col / (uint32_t)gs;
+  const uint32_t in_group = k_col - gk * (uint32_t)gs;                  // multiple of 8
+  const uint32_t wpgb = (uint32_t)gs >> 5;                              // words per group and bit of width
+  const u32x4* gy_step = grad_y + m_begin * (int64_t)row_chunks + n0 / 8;   // uniform; + 64 rows per step
+  const uint32_t gy_off = (4u * rq) * row_chunks + co;
+  const int64_t g_step0 = m_begin * (int64_t)gpr;                        // uniform; + 64*gpr per step
+  const uint32_t g_off = (4u * rq) * gpr + gk;
+
+  auto fetch_addr = [&](Addr& ad, int step) __attribute__((always_inline)) {
+    const int64_t gb = g_step0 + (int64_t)step * (kBM * (int64_t)gpr);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int64_t g = gb + (g_off + (uint32_t)r * gpr);
+      if (MIXED) {
+        ad.b[r] = bits[g];
+        ad.off[r] = off[g];
+      } else {
+        ad.b[r] = uniform_bits;
+        ad.off[r] = (uint32_t)g * (wpgb * uniform_bits);
+      }
+    }
+  };
+  auto fetch_stage = [&](Stage& f, const Addr& ad, int step) __attribute__((always_inline)) {
+    const u32x4* gp = gy_step + (int64_t)step * (kBM * (int64_t)row_chunks);
+    const int64_t gb = g_step0 + (int64_t)step * (kBM * (int64_t)gpr);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const u32x4 v = gp[gy_off + (uint32_t)r * row_chunks + 16u * (uint32_t)h];
+        f.gy[h][r] = make_uint4(v.x, v.y, v.z, v.w);
+      }
+      const uint32_t bit = in_group * ad.b[r];
+      const uint32_t* wp = words + ad.off[r] + (bit >> 5);
+      f.w0[r] = wp[0];
+      f.w1[r] = wp[ad.b[r] == 8u ? 1 : 0];          // a second word only for 8 x 8-bit codes
+      f.b[r] = ad.b[r];
+      const int64_t g = gb + (g_off + (uint32_t)r * gpr);
+      f.mn[r] = mn[g];
+      f.sc[r] = scale[g];
+    }
+  };
 
   f32x16 acc[4][2];
 #pragma unroll
@@ -141,23 +178,21 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-  Fetch f;
-  fetch_step<DT, MIXED>(f, grad_y, N8, m_begin + 4 * (int64_t)rq, n0 / 8, co, words, mn, scale, bits, off,
-                        uniform_bits, groups_per_row, gs, wpgb, k_col);
-
   const uint32_t wn = wave >> 1, wk = wave & 1u;
   const uint32_t li = lane & 31u, lg = lane >> 5;
 
-  for (int step = 0; step < steps; ++step) {
+  // One step: build the LDS tiles from stage `cur`, request the loads of the step kStages-1
+  // ahead into `fill` (the stage consumed one step ago), then run the products.
+  auto do_step = [&](const Stage& cur, Stage& fill, Addr& ad_use, Addr& ad_fill, int step) __attribute__((always_inline)) {
     __syncthreads();                                // the previous step's operand reads are done
 
     // ---- grad_y: pair rows, one 8-byte store per column ----
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      const uint32_t r0[4] = {f.gy[h][0].x, f.gy[h][0].y, f.gy[h][0].z, f.gy[h][0].w};
-      const uint32_t r1[4] = {f.gy[h][1].x, f.gy[h][1].y, f.gy[h][1].z, f.gy[h][1].w};
-      const uint32_t r2[4] = {f.gy[h][2].x, f.gy[h][2].y, f.gy[h][2].z, f.gy[h][2].w};
-      const uint32_t r3[4] = {f.gy[h][3].x, f.gy[h][3].y, f.gy[h][3].z, f.gy[h][3].w};
+      const uint32_t r0[4] = {cur.gy[h][0].x, cur.gy[h][0].y, cur.gy[h][0].z, cur.gy[h][0].w};
+      const uint32_t r1[4] = {cur.gy[h][1].x, cur.gy[h][1].y, cur.gy[h][1].z, cur.gy[h][1].w};
+      const uint32_t r2[4] = {cur.gy[h][2].x, cur.gy[h][2].y, cur.gy[h][2].z, cur.gy[h][2].w};
+      const uint32_t r3[4] = {cur.gy[h][3].x, cur.gy[h][3].y, cur.gy[h][3].z, cur.gy[h][3].w};
 #pragma unroll
       for (int c = 0; c < 8; ++c) {
         const int j = c >> 1;
@@ -174,39 +209,38 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
       }
     }
     // ---- xhat: unpack, dequantize, round to the element format, same transposed store ----
+    // One code path for every width: code e of the row sits in w0 (e < 4) or w1 (e >= 4; for
+    // widths below 8 w1 is a copy of w0) at shift (s0 + (7-e)*b) mod 32, where s0 places the
+    // 8 codes inside their word (0 for 8-bit codes).
     {
-      uint32_t xh[4][8];
+      uint32_t sh0[4], lv[4];
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const uint32_t b = f.b[r];
-        if (b == 8u) {
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            xh[r][e] = xhat16<DT>((f.w0[r] >> (24 - 8 * e)) & 0xFFu, f.sc[r], f.mn[r]);
-            xh[r][4 + e] = xhat16<DT>((f.w1[r] >> (24 - 8 * e)) & 0xFFu, f.sc[r], f.mn[r]);
-          }
-        } else {
-          const uint32_t field = f.w0[r] >> f.shift[r];
-          const uint32_t levels = (1u << b) - 1u;
-#pragma unroll
-          for (int e = 0; e < 8; ++e)
-            xh[r][e] = xhat16<DT>((field >> ((uint32_t)(7 - e) * b)) & levels, f.sc[r], f.mn[r]);
-        }
+        const uint32_t b = cur.b[r];
+        sh0[r] = (b == 8u) ? 0u : 32u - 8u * b - ((in_group * b) & 31u);
+        lv[r] = (1u << b) - 1u;
       }
 #pragma unroll
       for (int c = 0; c < 8; ++c) {
-        uint2 v;
-        v.x = xh[0][c] | (xh[1][c] << 16);
-        v.y = xh[2][c] | (xh[3][c] << 16);
+        float v[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const uint32_t w = (c < 4) ? cur.w0[r] : cur.w1[r];
+          const uint32_t code = (w >> ((sh0[r] + (uint32_t)(7 - c) * cur.b[r]) & 31u)) & lv[r];
+          v[r] = __builtin_fmaf((float)code, cur.sc[r], cur.mn[r]);
+        }
         const uint32_t col = 8u * co + (uint32_t)c;
-        reinterpret_cast<uint2*>(b_lds)[lds_unit(col, oct) * 2u + half] = v;
+        reinterpret_cast<uint2*>(b_lds)[lds_unit(col, oct) * 2u + half] =
+            make_uint2(narrow16_pair<DT>(v[0], v[1]), narrow16_pair<DT>(v[2], v[3]));
       }
     }
     __syncthreads();
 
-    if (step + 1 < steps)                           // next step's loads fly during the products
-      fetch_step<DT, MIXED>(f, grad_y, N8, m_begin + (int64_t)(step + 1) * kBM + 4 * (int64_t)rq, n0 / 8, co, words,
-                            mn, scale, bits, off, uniform_bits, groups_per_row, gs, wpgb, k_col);
+    // Loads for later steps fly during the products.  They are requested unconditionally (past
+    // the end the last step is requested again and never used), so that the number of loads in
+    // flight is the same in every iteration and the waits can leave the newest ones outstanding.
+    fetch_stage(fill, ad_use, min(step + (kStages - 1), steps - 1));
+    fetch_addr(ad_fill, min(step + kStages, steps - 1));
 
 #pragma unroll
     for (int ss = 0; ss < kBM / 16; ++ss) {
@@ -221,7 +255,32 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
 #pragma unroll
         for (int j = 0; j < 2; ++j) acc[i][j] = mfma_32x32x16<DT>(a[i], b[j], acc[i][j]);
     }
+  };
+
+  // Step q lives in stage q % kStages, and so do its group addresses (requested one step
+  // before its words).  The prologue requests steps 0 .. kStages-2 and the addresses of step
+  // kStages-1.
+  Stage st[kStages];
+  Addr ad[kStages];
+  static_for<kStages - 1>([&](auto I) __attribute__((always_inline)) {
+    constexpr int q = decltype(I)::value;
+    fetch_addr(ad[q], min(q, steps - 1));
+    fetch_stage(st[q], ad[q], min(q, steps - 1));
+  });
+  fetch_addr(ad[kStages - 1], min(kStages - 1, steps - 1));
+
+  int base = 0;
+  for (; base + kStages <= steps; base += kStages) {
+    static_for<kStages>([&](auto I) __attribute__((always_inline)) {
+      constexpr int q = decltype(I)::value;         // step base + q: stage q, fills stage (q + kStages-1) % kStages
+      do_step(st[q], st[(q + kStages - 1) % kStages], ad[(q + kStages - 1) % kStages], ad[q], base + q);
+    });
   }
+  static_for<kStages - 1>([&](auto I) __attribute__((always_inline)) {      // the last steps % kStages steps
+    constexpr int q = decltype(I)::value;
+    if (base + q < steps)
+      do_step(st[q], st[(q + kStages - 1) % kStages], ad[(q + kStages - 1) % kStages], ad[q], base + q);
+  });
 
   // ---- epilogue: register r of a 32 x 32 block is row 8*(r/4) + 4*(lane/32) + r%4, column lane%32 ----
   float* dst = out + (int64_t)split * N * K;

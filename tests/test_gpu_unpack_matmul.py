@@ -94,3 +94,38 @@ def test_grad_weight_argument_errors(env):
     with pytest.raises(daf.DafError) as e:
         daf.daf_unpack_matmul_grad_weight(plan2, words, mn, mn, gy[:96], out, torch.empty(1 << 22, dtype=torch.uint8, device="cuda:0"))
     assert e.value.status == -2
+
+
+@pytest.mark.parametrize("dtype", [BF16, F16])
+@pytest.mark.parametrize("bits", [1, 2, 4, 8, "mixed"])
+def test_identity_gradient_returns_xhat_bit_for_bit(env, dtype, bits):
+    """With grad_y = identity every output is a sum with exactly one non-zero term, so
+    out[n, k] must equal xhat[n, k] exactly: the dequantization inside the product produces the
+    same 16-bit patterns as the oracle's unpack_dequantize (tiny and huge scales included)."""
+    daf, orc = env
+    M = N = 256
+    K, gs = 384, 32
+    print("case identity", dtype, bits, flush=True)
+    g = torch.Generator().manual_seed(5)
+    mag = torch.exp(torch.randn(M, K // gs, 1, generator=g) * 6.0)              # group scales over many octaves
+    x = (torch.randn(M, K // gs, gs, generator=g) * mag).reshape(M, K).to(torch_dtype(dtype))
+    x[torch.isinf(x.float())] = 0
+    G = M * K // gs
+    b = (np.random.default_rng(1).choice([1, 2, 4, 8], G).astype(np.uint8) if bits == "mixed"
+         else np.array([bits], np.uint8))
+    ow, omn, osc, _ = orc.quantize_pack(to_numpy_bits(x), dtype, gs, b, 2)
+    oxh, _ = orc.unpack_dequantize(ow, omn, osc, b, M * K, gs, dtype)
+    finite = np.isfinite(orc.widen(oxh, dtype))
+    dbits = torch.from_numpy(b).cuda() if b.size > 1 else None
+    plan = daf.daf_plan((M, K), gs, dbits if dbits is not None else int(b[0]))
+    ws = torch.empty(max(daf.daf_unpack_matmul_workspace_bytes(plan, N, K), 16), dtype=torch.uint8, device="cuda:0")
+    out = torch.empty(N, K, device="cuda:0")
+    gy = torch.eye(M, dtype=torch_dtype(dtype), device="cuda:0")
+    daf.daf_unpack_matmul_grad_weight(plan, torch.from_numpy(ow.view(np.int32)).cuda(), torch.from_numpy(omn).cuda(),
+                                      torch.from_numpy(osc).cuda(), gy, out, ws)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().reshape(-1)
+    want = orc.widen(oxh, dtype)
+    assert finite.all()
+    assert np.array_equal((got + np.float32(0)).view(np.uint32), (want + np.float32(0)).view(np.uint32))
+    plan.destroy()
