@@ -57,7 +57,6 @@ struct Stage {
   uint32_t w0[4], w1[4], b[4];
   float mn[4], sc[4];
 };
-constexpr int kStages = 3;                          // loads are requested kStages-1 steps ahead
 
 template <int I> struct Index { static constexpr int value = I; };
 template <int N, int I = 0, class F>
@@ -92,8 +91,9 @@ __global__ __launch_bounds__(kThreads) void k_unpack_matmul(
     const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, uint32_t uniform_bits, int32_t gs,
     const u32x4* __restrict__ grad_y, int64_t M, int64_t N, int64_t K, int32_t tiles_n, int32_t tiles_k,
     int32_t splits, float* __restrict__ out) {
-  __shared__ uint4 a_lds[kBN * kOct];               // grad_y^T: (n, 8 consecutive m)
-  __shared__ uint4 b_lds[kBK * kOct];               // xhat^T:   (k, 8 consecutive m)
+  // Two copies of: grad_y^T as (n, 8 consecutive m) units, then xhat^T as (k, 8 consecutive m).
+  // While the products read one copy, the next step's tiles are written into the other.
+  __shared__ uint4 lds[2][(kBN + kBK) * kOct];
 
   const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
   // Consecutive block ids go to different XCDs (each with its own L2).  Give every XCD a
@@ -181,67 +181,48 @@ __global__ __launch_bounds__(kThreads) void k_unpack_matmul(
   const uint32_t wn = wave >> 1, wk = wave & 1u;
   const uint32_t li = lane & 31u, lg = lane >> 5;
 
-  // One step: build the LDS tiles from stage `cur`, request the loads of the step kStages-1
-  // ahead into `fill` (the stage consumed one step ago), then run the products.
-  auto do_step = [&](const Stage& cur, Stage& fill, Addr& ad_use, Addr& ad_fill, int step) __attribute__((always_inline)) {
-    __syncthreads();                                // the previous step's operand reads are done
-
+  // A quarter (two columns of each 8-column run) of the work of turning a stage into LDS tiles.
+  auto build_quarter = [&](const Stage& cur, uint4* buf, int qtr) __attribute__((always_inline)) {
+    uint2* a_half = reinterpret_cast<uint2*>(buf);
+    uint2* b_half = reinterpret_cast<uint2*>(buf + kBN * kOct);
     // ---- grad_y: pair rows, one 8-byte store per column ----
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      const uint32_t r0[4] = {cur.gy[h][0].x, cur.gy[h][0].y, cur.gy[h][0].z, cur.gy[h][0].w};
-      const uint32_t r1[4] = {cur.gy[h][1].x, cur.gy[h][1].y, cur.gy[h][1].z, cur.gy[h][1].w};
-      const uint32_t r2[4] = {cur.gy[h][2].x, cur.gy[h][2].y, cur.gy[h][2].z, cur.gy[h][2].w};
-      const uint32_t r3[4] = {cur.gy[h][3].x, cur.gy[h][3].y, cur.gy[h][3].z, cur.gy[h][3].w};
-#pragma unroll
-      for (int c = 0; c < 8; ++c) {
-        const int j = c >> 1;
-        uint2 v;
-        if (c & 1) {
-          v.x = (r0[j] >> 16) | (r1[j] & 0xFFFF0000u);
-          v.y = (r2[j] >> 16) | (r3[j] & 0xFFFF0000u);
-        } else {
-          v.x = (r0[j] & 0xFFFFu) | (r1[j] << 16);
-          v.y = (r2[j] & 0xFFFFu) | (r3[j] << 16);
-        }
-        const uint32_t col = 128u * (uint32_t)h + 8u * co + (uint32_t)c;
-        reinterpret_cast<uint2*>(a_lds)[lds_unit(col, oct) * 2u + half] = v;
-      }
+      const uint32_t r0 = (&cur.gy[h][0].x)[qtr], r1 = (&cur.gy[h][1].x)[qtr];
+      const uint32_t r2 = (&cur.gy[h][2].x)[qtr], r3 = (&cur.gy[h][3].x)[qtr];
+      const uint32_t col = 128u * (uint32_t)h + 8u * co + 2u * (uint32_t)qtr;
+      a_half[lds_unit(col, oct) * 2u + half] = make_uint2((r0 & 0xFFFFu) | (r1 << 16), (r2 & 0xFFFFu) | (r3 << 16));
+      a_half[lds_unit(col + 1u, oct) * 2u + half] =
+          make_uint2((r0 >> 16) | (r1 & 0xFFFF0000u), (r2 >> 16) | (r3 & 0xFFFF0000u));
     }
     // ---- xhat: unpack, dequantize, round to the element format, same transposed store ----
     // One code path for every width: code e of the row sits in w0 (e < 4) or w1 (e >= 4; for
-    // widths below 8 w1 is a copy of w0) at shift (s0 + (7-e)*b) mod 32, where s0 places the
-    // 8 codes inside their word (0 for 8-bit codes).
-    {
-      uint32_t sh0[4], lv[4];
+    // widths below 8 w1 is a copy of w0) at bit (s0 + (7-e)*b) mod 32, where s0 places the 8
+    // codes inside their word (0 for 8-bit codes).
+#pragma unroll
+    for (int cc = 0; cc < 2; ++cc) {
+      const int c = 2 * qtr + cc;
+      float v[4];
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const uint32_t b = cur.b[r];
-        sh0[r] = (b == 8u) ? 0u : 32u - 8u * b - ((in_group * b) & 31u);
-        lv[r] = (1u << b) - 1u;
+        const uint32_t s0 = (b == 8u) ? 0u : 32u - 8u * b - ((in_group * b) & 31u);
+        const uint32_t w = (c < 4) ? cur.w0[r] : cur.w1[r];
+        const uint32_t code = __builtin_amdgcn_ubfe(w, (s0 + (uint32_t)(7 - c) * b) & 31u, b);
+        v[r] = __builtin_fmaf((float)code, cur.sc[r], cur.mn[r]);
       }
-#pragma unroll
-      for (int c = 0; c < 8; ++c) {
-        float v[4];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const uint32_t w = (c < 4) ? cur.w0[r] : cur.w1[r];
-          const uint32_t code = (w >> ((sh0[r] + (uint32_t)(7 - c) * cur.b[r]) & 31u)) & lv[r];
-          v[r] = __builtin_fmaf((float)code, cur.sc[r], cur.mn[r]);
-        }
-        const uint32_t col = 8u * co + (uint32_t)c;
-        reinterpret_cast<uint2*>(b_lds)[lds_unit(col, oct) * 2u + half] =
-            make_uint2(narrow16_pair<DT>(v[0], v[1]), narrow16_pair<DT>(v[2], v[3]));
-      }
+      b_half[lds_unit(8u * co + (uint32_t)c, oct) * 2u + half] =
+          make_uint2(narrow16_pair<DT>(v[0], v[1]), narrow16_pair<DT>(v[2], v[3]));
     }
-    __syncthreads();
+  };
 
-    // Loads for later steps fly during the products.  They are requested unconditionally (past
-    // the end the last step is requested again and never used), so that the number of loads in
-    // flight is the same in every iteration and the waits can leave the newest ones outstanding.
-    fetch_stage(fill, ad_use, min(step + (kStages - 1), steps - 1));
-    fetch_addr(ad_fill, min(step + kStages, steps - 1));
-
+  // One step: request the loads of the step two ahead into `fill`, then run the products on
+  // copy BUF of the tiles while building the next step's tiles (from `next`) in the other copy.
+  auto do_step = [&](auto BUF, const Stage& next, Stage& fill, Addr& ad_use, Addr& ad_fill, int step)
+                     __attribute__((always_inline)) {
+    constexpr int buf = decltype(BUF)::value;
+    const uint4* a_lds = lds[buf];
+    const uint4* b_lds = lds[buf] + kBN * kOct;
 #pragma unroll
     for (int ss = 0; ss < kBM / 16; ++ss) {
       const uint32_t o = 2u * (uint32_t)ss + lg;
@@ -254,33 +235,41 @@ __global__ __launch_bounds__(kThreads) void k_unpack_matmul(
       for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) acc[i][j] = mfma_32x32x16<DT>(a[i], b[j], acc[i][j]);
+      build_quarter(next, lds[buf ^ 1], ss);
     }
+    // `next` has been consumed: its registers take the loads of the step after it.  Requested
+    // unconditionally (past the end the last step is requested again and never used), so that
+    // the number of loads in flight is the same in every iteration.
+    fetch_stage(fill, ad_use, min(step + 3, steps - 1));
+    fetch_addr(ad_fill, min(step + 4, steps - 1));
+    __syncthreads();                                // the other copy is complete, this one is free
   };
 
-  // Step q lives in stage q % kStages, and so do its group addresses (requested one step
-  // before its words).  The prologue requests steps 0 .. kStages-2 and the addresses of step
-  // kStages-1.
-  Stage st[kStages];
-  Addr ad[kStages];
-  static_for<kStages - 1>([&](auto I) __attribute__((always_inline)) {
-    constexpr int q = decltype(I)::value;
-    fetch_addr(ad[q], min(q, steps - 1));
-    fetch_stage(st[q], ad[q], min(q, steps - 1));
-  });
-  fetch_addr(ad[kStages - 1], min(kStages - 1, steps - 1));
+  // Step q lives in stage q % 2 and LDS copy q % 2, its group addresses in ad[q % 2] (requested
+  // one step before its words).  Prologue: steps 0..2 requested (step 0 is consumed at once,
+  // step 2 takes its registers), addresses of step 3 requested, tiles of step 0 built.
+  Stage st[2];
+  Addr ad[2];
+  fetch_addr(ad[0], 0);
+  fetch_stage(st[0], ad[0], 0);
+  fetch_addr(ad[1], min(1, steps - 1));
+  fetch_stage(st[1], ad[1], min(1, steps - 1));
+#pragma unroll
+  for (int qtr = 0; qtr < 4; ++qtr) build_quarter(st[0], lds[0], qtr);
+  fetch_addr(ad[0], min(2, steps - 1));
+  fetch_stage(st[0], ad[0], min(2, steps - 1));
+  fetch_addr(ad[1], min(3, steps - 1));
+  __syncthreads();
 
+  // In iteration s: products on copy s % 2; tiles of step s+1 (stage (s+1) % 2) into the other
+  // copy; then loads of step s+3 into that same stage, with the addresses in ad[(s+1) % 2]
+  // (requested in iteration s-1); addresses of step s+4 into ad[s % 2].
   int base = 0;
-  for (; base + kStages <= steps; base += kStages) {
-    static_for<kStages>([&](auto I) __attribute__((always_inline)) {
-      constexpr int q = decltype(I)::value;         // step base + q: stage q, fills stage (q + kStages-1) % kStages
-      do_step(st[q], st[(q + kStages - 1) % kStages], ad[(q + kStages - 1) % kStages], ad[q], base + q);
-    });
+  for (; base + 2 <= steps; base += 2) {
+    do_step(Index<0>{}, st[1], st[1], ad[1], ad[0], base);
+    do_step(Index<1>{}, st[0], st[0], ad[0], ad[1], base + 1);
   }
-  static_for<kStages - 1>([&](auto I) __attribute__((always_inline)) {      // the last steps % kStages steps
-    constexpr int q = decltype(I)::value;
-    if (base + q < steps)
-      do_step(st[q], st[(q + kStages - 1) % kStages], ad[(q + kStages - 1) % kStages], ad[q], base + q);
-  });
+  if (base < steps) do_step(Index<0>{}, st[1], st[1], ad[1], ad[0], base);
 
   // ---- epilogue: register r of a 32 x 32 block is row 8*(r/4) + 4*(lane/32) + r%4, column lane%32 ----
   float* dst = out + (int64_t)split * N * K;
