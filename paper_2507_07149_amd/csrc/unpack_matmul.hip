@@ -8,14 +8,16 @@
 //
 // Both operands have the reduction index m as their slow dimension in memory, while an MFMA
 // lane needs 8 consecutive m for one row (of grad_y^T) or one column (of xhat).  The tiles are
-// therefore transposed on their way into LDS: a thread holds 4 rows x 8 columns, pairs rows in
-// registers, and writes, per column, 8 bytes = 4 consecutive m.  LDS holds 16-byte units
-// (column, 8 consecutive m); unit (c, o) lives at index c*8 + (o ^ s(c)) with
-// s(c) = (c & 7) ^ ((c >> 3) & 7), which makes both the transposing writes and the operand
-// reads conflict-free.
+// therefore transposed on their way into LDS: a thread holds a few rows x 8 columns, pairs rows
+// in registers, and writes, per column, 8 bytes (4 consecutive m of grad_y) or 4 bytes (2
+// consecutive m of xhat).  LDS holds 16-byte units (column, 8 consecutive m); unit (c, o) lives
+// at index ((c >> 4) * 4 + o) * 16 + ((c & 15) ^ ((c >> 4) & 15)): the writers (lanes 8 columns
+// apart) and the operand reads (lanes on consecutive columns) both spread over all banks.
 //
-// Work-group tile: 256 (n) x 128 (k) outputs, 64 values of m per step, 4 waves in a 2 x 2
+// Work-group tile: 256 (n) x 128 (k) outputs, 32 values of m per step, 4 waves in a 2 x 2
 // arrangement of 128 x 64 each (4 x 2 MFMA blocks of 32 x 32, 128 accumulator registers).
+// Two copies of the LDS tiles: while the products read one, the next step's tiles are built
+// in the other, interleaved with the MFMA instructions; two work-groups share a CU.
 #include "daf_device.h"
 #include "daf_internal.h"
 
@@ -23,7 +25,7 @@ namespace {
 
 using namespace daf;
 
-constexpr int kBN = 256, kBK = 128, kBM = 64, kThreads = 256;
+constexpr int kBN = 256, kBK = 128, kBM = 32, kThreads = 256;
 constexpr int kOct = kBM / 8;                       // 16-byte units per column
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -42,20 +44,20 @@ __device__ __forceinline__ f32x16 mfma_32x32x16(const uint4& a, const uint4& b, 
 }
 
 __device__ __forceinline__ uint32_t lds_unit(uint32_t col, uint32_t oct) {
-  return col * (uint32_t)kOct + (oct ^ ((col & 7u) ^ ((col >> 3) & 7u)));
+  return (((col >> 4) * (uint32_t)kOct + oct) << 4) + ((col & 15u) ^ ((col >> 4) & 15u));
 }
 
 // With per-group widths the address of a row's words depends on off[] and bits[] of its group:
 // those are fetched one step before the words are requested.
 struct Addr {
-  uint32_t b[4], off[4];
+  uint32_t b[2], off[2];
 };
 // Everything a thread needs to build its share of one step's LDS tiles: 4 rows x 8 columns of
-// each 128-column panel of grad_y, and the words, width, min and scale of 4 rows x 8 columns of x.
+// grad_y, and the words, width, min and scale of 2 rows x 8 columns of x.
 struct Stage {
-  uint4 gy[2][4];
-  uint32_t w0[4], w1[4], b[4];
-  float mn[4], sc[4];
+  uint4 gy[4];
+  uint32_t w0[2], w1[2], b[2];
+  float mn[2], sc[2];
 };
 
 template <int I> struct Index { static constexpr int value = I; };
@@ -86,7 +88,7 @@ __device__ __forceinline__ uint32_t narrow16_pair(float lo, float hi) {
 }
 
 template <int DT, bool MIXED>
-__global__ __launch_bounds__(kThreads) void k_unpack_matmul(
+__global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
     const uint32_t* __restrict__ words, const float* __restrict__ mn, const float* __restrict__ scale,
     const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, uint32_t uniform_bits, int32_t gs,
     const u32x4* __restrict__ grad_y, int64_t M, int64_t N, int64_t K, int32_t tiles_n, int32_t tiles_k,
@@ -119,26 +121,29 @@ __global__ __launch_bounds__(kThreads) void k_unpack_matmul(
   const int64_t m_begin = (int64_t)split * m_per_split;
   const int steps = (int)(m_per_split / kBM);
 
-  // Loader role: thread (co, rq) owns rows 4*rq .. 4*rq+3 of the step and 8 columns of each
-  // 128-column panel.  Addresses are a block-uniform 64-bit base that advances by a constant per
-  // step, plus 32-bit per-thread offsets.
-  const uint32_t co = t & 15u, rq = t >> 4;
-  const uint32_t oct = rq >> 1, half = rq & 1u;
+  // Loader roles.  grad_y: thread (cg, rq) owns rows 4*rq .. 4*rq+3 of the step and columns
+  // 8*cg .. 8*cg+7 of the 256.  x: thread (co, rp) owns rows 2*rp, 2*rp+1 and columns
+  // 8*co .. 8*co+7 of the 128.  Addresses are a block-uniform 64-bit base that advances by a
+  // constant per step, plus 32-bit per-thread offsets.
+  const uint32_t cg = t & 31u, rq = t >> 5;
+  const uint32_t gy_oct = rq >> 1, gy_half = rq & 1u;
+  const uint32_t co = t & 15u, rp = t >> 4;
+  const uint32_t x_oct = rp >> 2, x_quarter = rp & 3u;
   const uint32_t row_chunks = (uint32_t)(N / 8);                        // 16-byte chunks per grad_y row
   const uint32_t gpr = (uint32_t)(K / gs);                              // groups per row of x
   const uint32_t k_col = (uint32_t)k0 + 8u * co;
   const uint32_t gk = k_col / (uint32_t)gs;
   const uint32_t in_group = k_col - gk * (uint32_t)gs;                  // multiple of 8
   const uint32_t wpgb = (uint32_t)gs >> 5;                              // words per group and bit of width
-  const u32x4* gy_step = grad_y + m_begin * (int64_t)row_chunks + n0 / 8;   // uniform; + 64 rows per step
-  const uint32_t gy_off = (4u * rq) * row_chunks + co;
-  const int64_t g_step0 = m_begin * (int64_t)gpr;                        // uniform; + 64*gpr per step
-  const uint32_t g_off = (4u * rq) * gpr + gk;
+  const u32x4* gy_step = grad_y + m_begin * (int64_t)row_chunks + n0 / 8;   // uniform; + 32 rows per step
+  const uint32_t gy_off = (4u * rq) * row_chunks + cg;
+  const int64_t g_step0 = m_begin * (int64_t)gpr;                        // uniform; + 32*gpr per step
+  const uint32_t g_off = (2u * rp) * gpr + gk;
 
   auto fetch_addr = [&](Addr& ad, int step) __attribute__((always_inline)) {
     const int64_t gb = g_step0 + (int64_t)step * (kBM * (int64_t)gpr);
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
+    for (int r = 0; r < 2; ++r) {
       const int64_t g = gb + (g_off + (uint32_t)r * gpr);
       if (MIXED) {
         ad.b[r] = bits[g];
@@ -154,11 +159,11 @@ __global__ __launch_bounds__(kThreads) void k_unpack_matmul(
     const int64_t gb = g_step0 + (int64_t)step * (kBM * (int64_t)gpr);
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
+      const u32x4 v = gp[gy_off + (uint32_t)r * row_chunks];
+      f.gy[r] = make_uint4(v.x, v.y, v.z, v.w);
+    }
 #pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const u32x4 v = gp[gy_off + (uint32_t)r * row_chunks + 16u * (uint32_t)h];
-        f.gy[h][r] = make_uint4(v.x, v.y, v.z, v.w);
-      }
+    for (int r = 0; r < 2; ++r) {
       const uint32_t bit = in_group * ad.b[r];
       const uint32_t* wp = words + ad.off[r] + (bit >> 5);
       f.w0[r] = wp[0];
@@ -181,66 +186,66 @@ __global__ __launch_bounds__(kThreads) void k_unpack_matmul(
   const uint32_t wn = wave >> 1, wk = wave & 1u;
   const uint32_t li = lane & 31u, lg = lane >> 5;
 
-  // A quarter (two columns of each 8-column run) of the work of turning a stage into LDS tiles.
-  auto build_quarter = [&](const Stage& cur, uint4* buf, int qtr) __attribute__((always_inline)) {
+  // Half (four of each run of eight columns) of the work of turning a stage into LDS tiles.
+  auto build_half = [&](const Stage& cur, uint4* buf, int hs) __attribute__((always_inline)) {
     uint2* a_half = reinterpret_cast<uint2*>(buf);
-    uint2* b_half = reinterpret_cast<uint2*>(buf + kBN * kOct);
-    // ---- grad_y: pair rows, one 8-byte store per column ----
+    uint32_t* b_quarter = reinterpret_cast<uint32_t*>(buf + kBN * kOct);
+    // ---- grad_y: pair rows, one 8-byte store (4 consecutive m) per column ----
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const uint32_t r0 = (&cur.gy[h][0].x)[qtr], r1 = (&cur.gy[h][1].x)[qtr];
-      const uint32_t r2 = (&cur.gy[h][2].x)[qtr], r3 = (&cur.gy[h][3].x)[qtr];
-      const uint32_t col = 128u * (uint32_t)h + 8u * co + 2u * (uint32_t)qtr;
-      a_half[lds_unit(col, oct) * 2u + half] = make_uint2((r0 & 0xFFFFu) | (r1 << 16), (r2 & 0xFFFFu) | (r3 << 16));
-      a_half[lds_unit(col + 1u, oct) * 2u + half] =
+    for (int jj = 0; jj < 2; ++jj) {
+      const int j = 2 * hs + jj;
+      const uint32_t r0 = (&cur.gy[0].x)[j], r1 = (&cur.gy[1].x)[j];
+      const uint32_t r2 = (&cur.gy[2].x)[j], r3 = (&cur.gy[3].x)[j];
+      const uint32_t col = 8u * cg + 2u * (uint32_t)j;
+      a_half[lds_unit(col, gy_oct) * 2u + gy_half] =
+          make_uint2((r0 & 0xFFFFu) | (r1 << 16), (r2 & 0xFFFFu) | (r3 << 16));
+      a_half[lds_unit(col + 1u, gy_oct) * 2u + gy_half] =
           make_uint2((r0 >> 16) | (r1 & 0xFFFF0000u), (r2 >> 16) | (r3 & 0xFFFF0000u));
     }
-    // ---- xhat: unpack, dequantize, round to the element format, same transposed store ----
-    // One code path for every width: code e of the row sits in w0 (e < 4) or w1 (e >= 4; for
-    // widths below 8 w1 is a copy of w0) at bit (s0 + (7-e)*b) mod 32, where s0 places the 8
-    // codes inside their word (0 for 8-bit codes).
+    // ---- xhat: unpack, dequantize, round to the element format; 4 bytes (2 consecutive m) per column ----
+    // One code path for every width: code c of the row sits in w0 (c < 4) or w1 (c >= 4; for
+    // widths below 8 w1 is a copy of w0) at bit s0 + (7-c)*b, where s0 places the 8 codes inside
+    // their word; for 8-bit codes (two words) the position is taken inside the word, mod 32.
 #pragma unroll
-    for (int cc = 0; cc < 2; ++cc) {
-      const int c = 2 * qtr + cc;
-      float v[4];
+    for (int cc = 0; cc < 4; ++cc) {
+      const int c = 4 * hs + cc;
+      float v[2];
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
+      for (int r = 0; r < 2; ++r) {
         const uint32_t b = cur.b[r];
         const uint32_t s0 = (b == 8u) ? 0u : 32u - 8u * b - ((in_group * b) & 31u);
         const uint32_t w = (c < 4) ? cur.w0[r] : cur.w1[r];
         const uint32_t code = __builtin_amdgcn_ubfe(w, (s0 + (uint32_t)(7 - c) * b) & 31u, b);
         v[r] = __builtin_fmaf((float)code, cur.sc[r], cur.mn[r]);
       }
-      b_half[lds_unit(8u * co + (uint32_t)c, oct) * 2u + half] =
-          make_uint2(narrow16_pair<DT>(v[0], v[1]), narrow16_pair<DT>(v[2], v[3]));
+      b_quarter[lds_unit(8u * co + (uint32_t)c, x_oct) * 4u + x_quarter] = narrow16_pair<DT>(v[0], v[1]);
     }
   };
 
-  // One step: request the loads of the step two ahead into `fill`, then run the products on
-  // copy BUF of the tiles while building the next step's tiles (from `next`) in the other copy.
-  auto do_step = [&](auto BUF, const Stage& next, Stage& fill, Addr& ad_use, Addr& ad_fill, int step)
-                     __attribute__((always_inline)) {
+  // One step: run the products on copy BUF of the tiles while building the next step's tiles
+  // (from `next`) in the other copy, then request the loads of the step after that into the
+  // registers just consumed.
+  auto do_step = [&](auto BUF, Stage& next, Addr& ad_use, Addr& ad_fill, int step) __attribute__((always_inline)) {
     constexpr int buf = decltype(BUF)::value;
     const uint4* a_lds = lds[buf];
     const uint4* b_lds = lds[buf] + kBN * kOct;
 #pragma unroll
     for (int ss = 0; ss < kBM / 16; ++ss) {
       const uint32_t o = 2u * (uint32_t)ss + lg;
-      uint4 a[4], b[2];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) a[i] = a_lds[lds_unit(128u * wn + 32u * (uint32_t)i + li, o)];
+      uint4 b[2];
 #pragma unroll
       for (int j = 0; j < 2; ++j) b[j] = b_lds[lds_unit(64u * wk + 32u * (uint32_t)j + li, o)];
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+      for (int i = 0; i < 4; ++i) {                 // one grad_y operand at a time: fewer live registers
+        const uint4 a = a_lds[lds_unit(128u * wn + 32u * (uint32_t)i + li, o)];
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = mfma_32x32x16<DT>(a[i], b[j], acc[i][j]);
-      build_quarter(next, lds[buf ^ 1], ss);
+        for (int j = 0; j < 2; ++j) acc[i][j] = mfma_32x32x16<DT>(a, b[j], acc[i][j]);
+      }
+      build_half(next, lds[buf ^ 1], ss);
     }
-    // `next` has been consumed: its registers take the loads of the step after it.  Requested
-    // unconditionally (past the end the last step is requested again and never used), so that
-    // the number of loads in flight is the same in every iteration.
-    fetch_stage(fill, ad_use, min(step + 3, steps - 1));
+    // Requested unconditionally (past the end the last step is requested again and never
+    // used), so that the number of loads in flight is the same in every iteration.
+    fetch_stage(next, ad_use, min(step + 3, steps - 1));
     fetch_addr(ad_fill, min(step + 4, steps - 1));
     __syncthreads();                                // the other copy is complete, this one is free
   };
@@ -254,8 +259,8 @@ __global__ __launch_bounds__(kThreads) void k_unpack_matmul(
   fetch_stage(st[0], ad[0], 0);
   fetch_addr(ad[1], min(1, steps - 1));
   fetch_stage(st[1], ad[1], min(1, steps - 1));
-#pragma unroll
-  for (int qtr = 0; qtr < 4; ++qtr) build_quarter(st[0], lds[0], qtr);
+  build_half(st[0], lds[0], 0);
+  build_half(st[0], lds[0], 1);
   fetch_addr(ad[0], min(2, steps - 1));
   fetch_stage(st[0], ad[0], min(2, steps - 1));
   fetch_addr(ad[1], min(3, steps - 1));
@@ -266,10 +271,10 @@ __global__ __launch_bounds__(kThreads) void k_unpack_matmul(
   // (requested in iteration s-1); addresses of step s+4 into ad[s % 2].
   int base = 0;
   for (; base + 2 <= steps; base += 2) {
-    do_step(Index<0>{}, st[1], st[1], ad[1], ad[0], base);
-    do_step(Index<1>{}, st[0], st[0], ad[0], ad[1], base + 1);
+    do_step(Index<0>{}, st[1], ad[1], ad[0], base);
+    do_step(Index<1>{}, st[0], ad[0], ad[1], base + 1);
   }
-  if (base < steps) do_step(Index<0>{}, st[1], st[1], ad[1], ad[0], base);
+  if (base < steps) do_step(Index<0>{}, st[1], ad[1], ad[0], base);
 
   // ---- epilogue: register r of a 32 x 32 block is row 8*(r/4) + 4*(lane/32) + r%4, column lane%32 ----
   float* dst = out + (int64_t)split * N * K;

@@ -58,7 +58,8 @@ def test_grad_weight_small(env, dtype, bits, gs):
     _case(daf, orc, 128, 256, 256, gs, bits, dtype, 7)                 # two k-tiles, m split in two
 
 
-@pytest.mark.parametrize("shape", [(64, 256, 128), (192, 512, 384), (1024, 256, 128), (2048, 512, 1024)])
+@pytest.mark.parametrize("shape", [(32, 256, 128), (64, 256, 128), (96, 256, 256), (192, 512, 384), (1024, 256, 128),
+                                   (2048, 512, 1024)])
 @pytest.mark.parametrize("bits", [2, "mixed"])
 def test_grad_weight_shapes(env, shape, bits):
     daf, orc = env
@@ -90,9 +91,9 @@ def test_grad_weight_argument_errors(env):
     with pytest.raises(daf.DafError) as e:                                    # binary32 is not offered
         daf.daf_unpack_matmul_grad_weight(plan, words, mn, mn, gy.float(), out, torch.empty(1 << 22, dtype=torch.uint8, device="cuda:0"))
     assert e.value.status == -2
-    plan2 = daf.daf_plan((96, 256), 64, 2)                                    # M not a multiple of 64
+    plan2 = daf.daf_plan((80, 256), 64, 2)                                    # M not a multiple of 32
     with pytest.raises(daf.DafError) as e:
-        daf.daf_unpack_matmul_grad_weight(plan2, words, mn, mn, gy[:96], out, torch.empty(1 << 22, dtype=torch.uint8, device="cuda:0"))
+        daf.daf_unpack_matmul_grad_weight(plan2, words, mn, mn, gy[:80], out, torch.empty(1 << 22, dtype=torch.uint8, device="cuda:0"))
     assert e.value.status == -2
 
 
