@@ -14,10 +14,12 @@
 // at index ((c >> 4) * 4 + o) * 16 + ((c & 15) ^ ((c >> 4) & 15)): the writers (lanes 8 columns
 // apart) and the operand reads (lanes on consecutive columns) both spread over all banks.
 //
-// Work-group tile: 256 (n) x 128 (k) outputs, 32 values of m per step, 4 waves in a 2 x 2
-// arrangement of 128 x 64 each (4 x 2 MFMA blocks of 32 x 32, 128 accumulator registers).
-// Two copies of the LDS tiles: while the products read one, the next step's tiles are built
-// in the other, interleaved with the MFMA instructions; two work-groups share a CU.
+// Work-group tile: 256 (n) x 64 (k) outputs, 32 values of m per step, 4 waves of 64 x 64
+// each (2 x 2 MFMA blocks of 32 x 32, 64 accumulator registers).  The wide n keeps the number
+// of times a value of x is dequantized (once per tile of n) low; the small wave tile keeps the
+// register count low enough for several work-groups per CU, which is what hides the latencies
+// of one wave behind the work of another.  Two copies of the LDS tiles: while the products
+// read one, the next step's tiles are built in the other, between the MFMA instructions.
 #include "daf_device.h"
 #include "daf_internal.h"
 
@@ -25,7 +27,7 @@ namespace {
 
 using namespace daf;
 
-constexpr int kBN = 256, kBK = 128, kBM = 32, kThreads = 256;
+constexpr int kBN = 256, kBK = 64, kBM = 32, kThreads = 256;
 constexpr int kOct = kBM / 8;                       // 16-byte units per column
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -53,10 +55,10 @@ struct Addr {
   uint32_t b[2], off[2];
 };
 // Everything a thread needs to build its share of one step's LDS tiles: 4 rows x 8 columns of
-// grad_y, and the words, width, min and scale of 2 rows x 8 columns of x.
+// grad_y, and the word, width, min and scale of 2 rows x 4 columns of x.
 struct Stage {
   uint4 gy[4];
-  uint32_t w0[2], w1[2], b[2];
+  uint32_t w[2], b[2];
   float mn[2], sc[2];
 };
 
@@ -123,7 +125,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
 
   // Loader roles.  grad_y: thread (cg, rq) owns rows 4*rq .. 4*rq+3 of the step and columns
   // 8*cg .. 8*cg+7 of the 256.  x: thread (co, rp) owns rows 2*rp, 2*rp+1 and columns
-  // 8*co .. 8*co+7 of the 128.  Addresses are a block-uniform 64-bit base that advances by a
+  // 4*co .. 4*co+3 of the 64 (their codes lie in one word, whatever the width).  Addresses are a block-uniform 64-bit base that advances by a
   // constant per step, plus 32-bit per-thread offsets.
   const uint32_t cg = t & 31u, rq = t >> 5;
   const uint32_t gy_oct = rq >> 1, gy_half = rq & 1u;
@@ -131,9 +133,9 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
   const uint32_t x_oct = rp >> 2, x_quarter = rp & 3u;
   const uint32_t row_chunks = (uint32_t)(N / 8);                        // 16-byte chunks per grad_y row
   const uint32_t gpr = (uint32_t)(K / gs);                              // groups per row of x
-  const uint32_t k_col = (uint32_t)k0 + 8u * co;
+  const uint32_t k_col = (uint32_t)k0 + 4u * co;
   const uint32_t gk = k_col / (uint32_t)gs;
-  const uint32_t in_group = k_col - gk * (uint32_t)gs;                  // multiple of 8
+  const uint32_t in_group = k_col - gk * (uint32_t)gs;                  // multiple of 4
   const uint32_t wpgb = (uint32_t)gs >> 5;                              // words per group and bit of width
   const u32x4* gy_step = grad_y + m_begin * (int64_t)row_chunks + n0 / 8;   // uniform; + 32 rows per step
   const uint32_t gy_off = (4u * rq) * row_chunks + cg;
@@ -164,10 +166,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
     }
 #pragma unroll
     for (int r = 0; r < 2; ++r) {
-      const uint32_t bit = in_group * ad.b[r];
-      const uint32_t* wp = words + ad.off[r] + (bit >> 5);
-      f.w0[r] = wp[0];
-      f.w1[r] = wp[ad.b[r] == 8u ? 1 : 0];          // a second word only for 8 x 8-bit codes
+      f.w[r] = words[ad.off[r] + ((in_group * ad.b[r]) >> 5)];
       f.b[r] = ad.b[r];
       const int64_t g = gb + (g_off + (uint32_t)r * gpr);
       f.mn[r] = mn[g];
@@ -175,15 +174,15 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
     }
   };
 
-  f32x16 acc[4][2];
+  f32x16 acc[2][2];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < 2; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-  const uint32_t wn = wave >> 1, wk = wave & 1u;
+  const uint32_t wn = wave;
   const uint32_t li = lane & 31u, lg = lane >> 5;
 
   // Half (four of each run of eight columns) of the work of turning a stage into LDS tiles.
@@ -203,22 +202,19 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
           make_uint2((r0 >> 16) | (r1 & 0xFFFF0000u), (r2 >> 16) | (r3 & 0xFFFF0000u));
     }
     // ---- xhat: unpack, dequantize, round to the element format; 4 bytes (2 consecutive m) per column ----
-    // One code path for every width: code c of the row sits in w0 (c < 4) or w1 (c >= 4; for
-    // widths below 8 w1 is a copy of w0) at bit s0 + (7-c)*b, where s0 places the 8 codes inside
-    // their word; for 8-bit codes (two words) the position is taken inside the word, mod 32.
+    // Code c of the thread's four sits at bit s0 + (3-c)*b of the word, s0 = 32 - 4b - (first bit mod 32).
 #pragma unroll
-    for (int cc = 0; cc < 4; ++cc) {
-      const int c = 4 * hs + cc;
+    for (int cc = 0; cc < 2; ++cc) {
+      const int c = 2 * hs + cc;
       float v[2];
 #pragma unroll
       for (int r = 0; r < 2; ++r) {
         const uint32_t b = cur.b[r];
-        const uint32_t s0 = (b == 8u) ? 0u : 32u - 8u * b - ((in_group * b) & 31u);
-        const uint32_t w = (c < 4) ? cur.w0[r] : cur.w1[r];
-        const uint32_t code = __builtin_amdgcn_ubfe(w, (s0 + (uint32_t)(7 - c) * b) & 31u, b);
+        const uint32_t s0 = 32u - 4u * b - ((in_group * b) & 31u);
+        const uint32_t code = __builtin_amdgcn_ubfe(cur.w[r], s0 + (uint32_t)(3 - c) * b, b);
         v[r] = __builtin_fmaf((float)code, cur.sc[r], cur.mn[r]);
       }
-      b_quarter[lds_unit(8u * co + (uint32_t)c, x_oct) * 4u + x_quarter] = narrow16_pair<DT>(v[0], v[1]);
+      b_quarter[lds_unit(4u * co + (uint32_t)c, x_oct) * 4u + x_quarter] = narrow16_pair<DT>(v[0], v[1]);
     }
   };
 
@@ -232,15 +228,15 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
 #pragma unroll
     for (int ss = 0; ss < kBM / 16; ++ss) {
       const uint32_t o = 2u * (uint32_t)ss + lg;
-      uint4 b[2];
+      uint4 a[2], b[2];
 #pragma unroll
-      for (int j = 0; j < 2; ++j) b[j] = b_lds[lds_unit(64u * wk + 32u * (uint32_t)j + li, o)];
+      for (int i = 0; i < 2; ++i) a[i] = a_lds[lds_unit(64u * wn + 32u * (uint32_t)i + li, o)];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {                 // one grad_y operand at a time: fewer live registers
-        const uint4 a = a_lds[lds_unit(128u * wn + 32u * (uint32_t)i + li, o)];
+      for (int j = 0; j < 2; ++j) b[j] = b_lds[lds_unit(32u * (uint32_t)j + li, o)];
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = mfma_32x32x16<DT>(a, b[j], acc[i][j]);
-      }
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = mfma_32x32x16<DT>(a[i], b[j], acc[i][j]);
       build_half(next, lds[buf ^ 1], ss);
     }
     // Requested unconditionally (past the end the last step is requested again and never
@@ -279,13 +275,13 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
   // ---- epilogue: register r of a 32 x 32 block is row 8*(r/4) + 4*(lane/32) + r%4, column lane%32 ----
   float* dst = out + (int64_t)split * N * K;
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < 2; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int64_t n = n0 + 128 * wn + 32 * i + 8 * (r >> 2) + 4 * lg + (r & 3);
-        const int64_t k = k0 + 64 * wk + 32 * j + li;
+        const int64_t n = n0 + 64 * wn + 32 * i + 8 * (r >> 2) + 4 * lg + (r & 3);
+        const int64_t k = k0 + 32 * j + li;
         dst[n * K + k] = acc[i][j][r];
       }
 }
