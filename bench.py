@@ -60,6 +60,8 @@ def parse():
                     help="time daf_unpack_matmul_grad_weight (unpack+dequantize inside the weight-gradient "
                          "product) against daf_unpack_dequantize followed by the library matrix product; "
                          "--config 5 (LLM MLP, bf16) or 3 (ViT MLP, fp16)")
+    ap.add_argument("--uniform-bits", type=int, default=None, choices=[1, 2, 4, 8],
+                    help="with --fused-matmul: one width for every group instead of the configuration's per-group widths")
     ap.add_argument("--fused-relu", action="store_true",
                     help="time daf_relu_quantize_pack (activation function fused into the quantize pass) "
                          "against a separate relu kernel followed by daf_quantize_pack")
@@ -241,6 +243,8 @@ def main():
         N = {5: 4096, 3: 3072}.get(args.config, 1024)
         x = w.x.reshape(-1).to(dev)
         bits = int(w.bits[0]) if w.bits.size == 1 else torch.from_numpy(w.bits).to(dev)
+        if args.uniform_bits:
+            bits = args.uniform_bits
         plan = daf.daf_plan((M, K), w.group_size, bits)
         words = torch.empty(plan.packed_words, dtype=torch.int32, device=dev)
         mn, sc = torch.empty(plan.num_groups, device=dev), torch.empty(plan.num_groups, device=dev)

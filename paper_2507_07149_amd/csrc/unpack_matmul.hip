@@ -7,12 +7,13 @@
 // so it runs on MFMA (v_mfma_f32_32x32x16 for bf16 / f16, binary32 accumulation).
 //
 // Both operands have the reduction index m as their slow dimension in memory, while an MFMA
-// lane needs 8 consecutive m for one row (of grad_y^T) or one column (of xhat).  The tiles are
-// therefore transposed on their way into LDS: a thread holds a few rows x 8 columns, pairs rows
-// in registers, and writes, per column, 8 bytes (4 consecutive m of grad_y) or 4 bytes (2
-// consecutive m of xhat).  LDS holds 16-byte units (column, 8 consecutive m); unit (c, o) lives
-// at index ((c >> 4) * 4 + o) * 16 + ((c & 15) ^ ((c >> 4) & 15)): the writers (lanes 8 columns
-// apart) and the operand reads (lanes on consecutive columns) both spread over all banks.
+// lane needs 8 consecutive m for one row (of grad_y^T) or one column (of xhat).  The tiles go
+// into LDS as they are (row = one m, columns contiguous) and are transposed by the operand
+// reads: gfx950's ds_read_b64_tr_b16 hands lane L of each group of 16 lanes the L-th 16-bit
+// element of each of the four 32-byte runs addressed by lanes 0-3, 4-7, 8-11 and 12-15.  With
+// those four runs on four consecutive rows, a lane receives 4 consecutive m of its column; two
+// such loads make one 8-element MFMA operand.  Rows are padded (stride = 64 bytes mod 256) so
+// that the four rows of a load fall on different banks.
 //
 // Work-group tile: 256 (n) x 64 (k) outputs, 32 values of m per step, 4 waves of 64 x 64
 // each (2 x 2 MFMA blocks of 32 x 32, 64 accumulator registers).  The wide n keeps the number
@@ -28,7 +29,9 @@ namespace {
 using namespace daf;
 
 constexpr int kBN = 256, kBK = 64, kBM = 32, kThreads = 256;
-constexpr int kOct = kBM / 8;                       // 16-byte units per column
+constexpr int kRowA = kBN * 2 + 64;                 // bytes per row of the grad_y tile in LDS (padded)
+constexpr int kRowB = kBK * 2 + 64;                 // bytes per row of the xhat tile in LDS (padded)
+constexpr int kBufBytes = kBM * (kRowA + kRowB);    // one copy of both tiles
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -45,8 +48,16 @@ __device__ __forceinline__ f32x16 mfma_32x32x16(const uint4& a, const uint4& b, 
   }
 }
 
-__device__ __forceinline__ uint32_t lds_unit(uint32_t col, uint32_t oct) {
-  return (((col >> 4) * (uint32_t)kOct + oct) << 4) + ((col & 15u) ^ ((col >> 4) & 15u));
+typedef short i16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
+
+// One MFMA operand: 8 consecutive m of the lane's column, from rows `p` (m .. m+3 across the
+// lane groups) and `p + 4 rows`.
+__device__ __forceinline__ uint4 operand_tr(const char* p, int row_bytes) {
+  const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(p));
+  const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(p + 4 * row_bytes));
+  const uint2 l2 = __builtin_bit_cast(uint2, lo), h2 = __builtin_bit_cast(uint2, hi);
+  return make_uint4(l2.x, l2.y, h2.x, h2.y);
 }
 
 // With per-group widths the address of a row's words depends on off[] and bits[] of its group:
@@ -95,9 +106,9 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
     const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, uint32_t uniform_bits, int32_t gs,
     const u32x4* __restrict__ grad_y, int64_t M, int64_t N, int64_t K, int32_t tiles_n, int32_t tiles_k,
     int32_t splits, float* __restrict__ out) {
-  // Two copies of: grad_y^T as (n, 8 consecutive m) units, then xhat^T as (k, 8 consecutive m).
-  // While the products read one copy, the next step's tiles are written into the other.
-  __shared__ uint4 lds[2][(kBN + kBK) * kOct];
+  // Two copies of: the grad_y tile (kBM rows of kRowA bytes), then the xhat tile (kBM rows of
+  // kRowB bytes).  While the products read one copy, the next step's tiles are written into the other.
+  __shared__ __attribute__((aligned(16))) char lds[2][kBufBytes];
 
   const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
   // Consecutive block ids go to different XCDs (each with its own L2).  Give every XCD a
@@ -128,9 +139,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
   // 4*co .. 4*co+3 of the 64 (their codes lie in one word, whatever the width).  Addresses are a block-uniform 64-bit base that advances by a
   // constant per step, plus 32-bit per-thread offsets.
   const uint32_t cg = t & 31u, rq = t >> 5;
-  const uint32_t gy_oct = rq >> 1, gy_half = rq & 1u;
   const uint32_t co = t & 15u, rp = t >> 4;
-  const uint32_t x_oct = rp >> 2, x_quarter = rp & 3u;
   const uint32_t row_chunks = (uint32_t)(N / 8);                        // 16-byte chunks per grad_y row
   const uint32_t gpr = (uint32_t)(K / gs);                              // groups per row of x
   const uint32_t k_col = (uint32_t)k0 + 4u * co;
@@ -184,37 +193,37 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
 
   const uint32_t wn = wave;
   const uint32_t li = lane & 31u, lg = lane >> 5;
+  // Operand reads: lane l of 16-lane group G = l / 16 addresses row 8*(l/32) + (l%16)/4 (plus 16 per
+  // sub-step, plus 4 for the second half of the operand) and the 4 columns 16*(G%2) + 4*(l%4) ..
+  // of its 32-column block; it receives column 16*(G%2) + l%16 = l%32 of the block.
+  const uint32_t tr_row = 8u * lg + ((lane & 15u) >> 2), tr_col = 16u * ((lane >> 4) & 1u) + 4u * (lane & 3u);
+  const uint32_t a_read = tr_row * (uint32_t)kRowA + (64u * wn + tr_col) * 2u;
+  const uint32_t b_read = (uint32_t)(kBM * kRowA) + tr_row * (uint32_t)kRowB + tr_col * 2u;
 
-  // Half (four of each run of eight columns) of the work of turning a stage into LDS tiles.
-  auto build_half = [&](const Stage& cur, uint4* buf, int hs) __attribute__((always_inline)) {
-    uint2* a_half = reinterpret_cast<uint2*>(buf);
-    uint32_t* b_quarter = reinterpret_cast<uint32_t*>(buf + kBN * kOct);
-    // ---- grad_y: pair rows, one 8-byte store (4 consecutive m) per column ----
+  // Half of the work of turning a stage into LDS tiles: two of the thread's four grad_y rows
+  // (copied as loaded) and one of its two rows of x.
+  const uint32_t a_store = (4u * rq) * (uint32_t)kRowA + 16u * cg;
+  const uint32_t b_store = (uint32_t)(kBM * kRowA) + (2u * rp) * (uint32_t)kRowB + 8u * co;
+  auto build_half = [&](const Stage& cur, char* buf, int hs) __attribute__((always_inline)) {
 #pragma unroll
-    for (int jj = 0; jj < 2; ++jj) {
-      const int j = 2 * hs + jj;
-      const uint32_t r0 = (&cur.gy[0].x)[j], r1 = (&cur.gy[1].x)[j];
-      const uint32_t r2 = (&cur.gy[2].x)[j], r3 = (&cur.gy[3].x)[j];
-      const uint32_t col = 8u * cg + 2u * (uint32_t)j;
-      a_half[lds_unit(col, gy_oct) * 2u + gy_half] =
-          make_uint2((r0 & 0xFFFFu) | (r1 << 16), (r2 & 0xFFFFu) | (r3 << 16));
-      a_half[lds_unit(col + 1u, gy_oct) * 2u + gy_half] =
-          make_uint2((r0 >> 16) | (r1 & 0xFFFF0000u), (r2 >> 16) | (r3 & 0xFFFF0000u));
+    for (int rr = 0; rr < 2; ++rr) {
+      const int r = 2 * hs + rr;
+      *reinterpret_cast<uint4*>(buf + a_store + (uint32_t)r * kRowA) = cur.gy[r];
     }
-    // ---- xhat: unpack, dequantize, round to the element format; 4 bytes (2 consecutive m) per column ----
+    // ---- xhat: unpack, dequantize, round to the element format; 4 columns = 8 bytes of one row ----
     // Code c of the thread's four sits at bit s0 + (3-c)*b of the word, s0 = 32 - 4b - (first bit mod 32).
+    {
+      const int r = hs;
+      const uint32_t b = cur.b[r];
+      const uint32_t s0 = 32u - 4u * b - ((in_group * b) & 31u);
+      float v[4];
 #pragma unroll
-    for (int cc = 0; cc < 2; ++cc) {
-      const int c = 2 * hs + cc;
-      float v[2];
-#pragma unroll
-      for (int r = 0; r < 2; ++r) {
-        const uint32_t b = cur.b[r];
-        const uint32_t s0 = 32u - 4u * b - ((in_group * b) & 31u);
+      for (int c = 0; c < 4; ++c) {
         const uint32_t code = __builtin_amdgcn_ubfe(cur.w[r], s0 + (uint32_t)(3 - c) * b, b);
-        v[r] = __builtin_fmaf((float)code, cur.sc[r], cur.mn[r]);
+        v[c] = __builtin_fmaf((float)code, cur.sc[r], cur.mn[r]);
       }
-      b_quarter[lds_unit(4u * co + (uint32_t)c, x_oct) * 4u + x_quarter] = narrow16_pair<DT>(v[0], v[1]);
+      *reinterpret_cast<uint2*>(buf + b_store + (uint32_t)r * kRowB) =
+          make_uint2(narrow16_pair<DT>(v[0], v[1]), narrow16_pair<DT>(v[2], v[3]));
     }
   };
 
@@ -223,16 +232,15 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
   // registers just consumed.
   auto do_step = [&](auto BUF, Stage& next, Addr& ad_use, Addr& ad_fill, int step) __attribute__((always_inline)) {
     constexpr int buf = decltype(BUF)::value;
-    const uint4* a_lds = lds[buf];
-    const uint4* b_lds = lds[buf] + kBN * kOct;
+    const char* a_lds = lds[buf] + a_read;
+    const char* b_lds = lds[buf] + b_read;
 #pragma unroll
     for (int ss = 0; ss < kBM / 16; ++ss) {
-      const uint32_t o = 2u * (uint32_t)ss + lg;
       uint4 a[2], b[2];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) a[i] = a_lds[lds_unit(64u * wn + 32u * (uint32_t)i + li, o)];
+      for (int i = 0; i < 2; ++i) a[i] = operand_tr(a_lds + ss * 16 * kRowA + i * 64, kRowA);
 #pragma unroll
-      for (int j = 0; j < 2; ++j) b[j] = b_lds[lds_unit(32u * (uint32_t)j + li, o)];
+      for (int j = 0; j < 2; ++j) b[j] = operand_tr(b_lds + ss * 16 * kRowB + j * 64, kRowB);
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
