@@ -63,14 +63,14 @@ __device__ __forceinline__ uint4 operand_tr(const char* p, int row_bytes) {
 // With per-group widths the address of a row's words depends on off[] and bits[] of its group:
 // those are fetched one step before the words are requested.
 struct Addr {
-  uint32_t b[2], off[2];
+  uint32_t b, off;
 };
 // Everything a thread needs to build its share of one step's LDS tiles: 4 rows x 8 columns of
-// grad_y, and the word, width, min and scale of 2 rows x 4 columns of x.
+// grad_y, and the words, width, min and scale of 8 columns of one row of x.
 struct Stage {
   uint4 gy[4];
-  uint32_t w[2], b[2];
-  float mn[2], sc[2];
+  uint32_t w0, w1, b;                               // code c < 4 is in w0, c >= 4 in w1 (the same word below 8 bits)
+  float mn, sc;
 };
 
 template <int I> struct Index { static constexpr int value = I; };
@@ -105,7 +105,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
     const uint32_t* __restrict__ words, const float* __restrict__ mn, const float* __restrict__ scale,
     const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, uint32_t uniform_bits, int32_t gs,
     const u32x4* __restrict__ grad_y, int64_t M, int64_t N, int64_t K, int32_t tiles_n, int32_t tiles_k,
-    int32_t splits, float* __restrict__ out) {
+    int32_t splits, uint32_t total_words, float* __restrict__ out) {
   // Two copies of: the grad_y tile (kBM rows of kRowA bytes), then the xhat tile (kBM rows of
   // kRowB bytes).  While the products read one copy, the next step's tiles are written into the other.
   __shared__ __attribute__((aligned(16))) char lds[2][kBufBytes];
@@ -135,52 +135,54 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
   const int steps = (int)(m_per_split / kBM);
 
   // Loader roles.  grad_y: thread (cg, rq) owns rows 4*rq .. 4*rq+3 of the step and columns
-  // 8*cg .. 8*cg+7 of the 256.  x: thread (co, rp) owns rows 2*rp, 2*rp+1 and columns
-  // 4*co .. 4*co+3 of the 64 (their codes lie in one word, whatever the width).  Addresses are a block-uniform 64-bit base that advances by a
+  // 8*cg .. 8*cg+7 of the 256.  x: thread (co, xr) owns row xr and columns 8*co .. 8*co+7 of the
+  // 64: one load instruction each for its words, min, scale (and width, offset) per step.  Addresses are a block-uniform 64-bit base that advances by a
   // constant per step, plus 32-bit per-thread offsets.
   const uint32_t cg = t & 31u, rq = t >> 5;
-  const uint32_t co = t & 15u, rp = t >> 4;
+  const uint32_t co = t & 7u, xr = t >> 3;
   const uint32_t row_chunks = (uint32_t)(N / 8);                        // 16-byte chunks per grad_y row
   const uint32_t gpr = (uint32_t)(K / gs);                              // groups per row of x
-  const uint32_t k_col = (uint32_t)k0 + 4u * co;
+  const uint32_t k_col = (uint32_t)k0 + 8u * co;
   const uint32_t gk = k_col / (uint32_t)gs;
-  const uint32_t in_group = k_col - gk * (uint32_t)gs;                  // multiple of 4
+  const uint32_t in_group = k_col - gk * (uint32_t)gs;                  // multiple of 8
   const uint32_t wpgb = (uint32_t)gs >> 5;                              // words per group and bit of width
   const u32x4* gy_step = grad_y + m_begin * (int64_t)row_chunks + n0 / 8;   // uniform; + 32 rows per step
   const uint32_t gy_off = (4u * rq) * row_chunks + cg;
   const int64_t g_step0 = m_begin * (int64_t)gpr;                        // uniform; + 32*gpr per step
-  const uint32_t g_off = (2u * rp) * gpr + gk;
+  const uint32_t g_off = xr * gpr + gk;
 
   auto fetch_addr = [&](Addr& ad, int step) __attribute__((always_inline)) {
-    const int64_t gb = g_step0 + (int64_t)step * (kBM * (int64_t)gpr);
-#pragma unroll
-    for (int r = 0; r < 2; ++r) {
-      const int64_t g = gb + (g_off + (uint32_t)r * gpr);
-      if (MIXED) {
-        ad.b[r] = bits[g];
-        ad.off[r] = off[g];
-      } else {
-        ad.b[r] = uniform_bits;
-        ad.off[r] = (uint32_t)g * (wpgb * uniform_bits);
-      }
+    const int64_t g = g_step0 + (int64_t)step * (kBM * (int64_t)gpr) + g_off;
+    if (MIXED) {
+      ad.b = bits[g];
+      ad.off = off[g];
+    } else {
+      ad.b = uniform_bits;
+      ad.off = (uint32_t)g * (wpgb * uniform_bits);
     }
   };
   auto fetch_stage = [&](Stage& f, const Addr& ad, int step) __attribute__((always_inline)) {
     const u32x4* gp = gy_step + (int64_t)step * (kBM * (int64_t)row_chunks);
-    const int64_t gb = g_step0 + (int64_t)step * (kBM * (int64_t)gpr);
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const u32x4 v = gp[gy_off + (uint32_t)r * row_chunks];
       f.gy[r] = make_uint4(v.x, v.y, v.z, v.w);
     }
-#pragma unroll
-    for (int r = 0; r < 2; ++r) {
-      f.w[r] = words[ad.off[r] + ((in_group * ad.b[r]) >> 5)];
-      f.b[r] = ad.b[r];
-      const int64_t g = gb + (g_off + (uint32_t)r * gpr);
-      f.mn[r] = mn[g];
-      f.sc[r] = scale[g];
-    }
+    // The 8 codes lie in two words (8 bits) or in one: one 8-byte load either way.  For a single
+    // word the load is the aligned pair that contains it (or, for the last word of a buffer with
+    // an odd number of words, the word before it and it).
+    const uint32_t wi = ad.off + ((in_group * ad.b) >> 5);
+    const bool two = ad.b == 8u;
+    const uint32_t ps = two ? wi : (((wi | 1u) < total_words) ? (wi & ~1u) : wi - 1u);
+    uint2 pair;
+    __builtin_memcpy(&pair, words + ps, 8);
+    const uint32_t one = (wi != ps) ? pair.y : pair.x;
+    f.w0 = two ? pair.x : one;
+    f.w1 = two ? pair.y : one;
+    f.b = ad.b;
+    const int64_t g = g_step0 + (int64_t)step * (kBM * (int64_t)gpr) + g_off;
+    f.mn = mn[g];
+    f.sc = scale[g];
   };
 
   f32x16 acc[2][2];
@@ -203,26 +205,28 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
   // Half of the work of turning a stage into LDS tiles: two of the thread's four grad_y rows
   // (copied as loaded) and one of its two rows of x.
   const uint32_t a_store = (4u * rq) * (uint32_t)kRowA + 16u * cg;
-  const uint32_t b_store = (uint32_t)(kBM * kRowA) + (2u * rp) * (uint32_t)kRowB + 8u * co;
+  const uint32_t b_store = (uint32_t)(kBM * kRowA) + xr * (uint32_t)kRowB + 16u * co;
   auto build_half = [&](const Stage& cur, char* buf, int hs) __attribute__((always_inline)) {
 #pragma unroll
     for (int rr = 0; rr < 2; ++rr) {
       const int r = 2 * hs + rr;
       *reinterpret_cast<uint4*>(buf + a_store + (uint32_t)r * kRowA) = cur.gy[r];
     }
-    // ---- xhat: unpack, dequantize, round to the element format; 4 columns = 8 bytes of one row ----
-    // Code c of the thread's four sits at bit s0 + (3-c)*b of the word, s0 = 32 - 4b - (first bit mod 32).
+    // ---- xhat: unpack, dequantize, round to the element format; 4 columns = 8 bytes of the row ----
+    // Code c sits at bit s0 + (7-c)*b, s0 placing the 8 codes inside their word; for 8-bit codes
+    // (two words) the position is taken inside the word, mod 32.
     {
-      const int r = hs;
-      const uint32_t b = cur.b[r];
-      const uint32_t s0 = 32u - 4u * b - ((in_group * b) & 31u);
+      const uint32_t b = cur.b;
+      const uint32_t s0 = (b == 8u) ? 0u : 32u - 8u * b - ((in_group * b) & 31u);
+      const uint32_t w = hs ? cur.w1 : cur.w0;
       float v[4];
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const uint32_t code = __builtin_amdgcn_ubfe(cur.w[r], s0 + (uint32_t)(3 - c) * b, b);
-        v[c] = __builtin_fmaf((float)code, cur.sc[r], cur.mn[r]);
+      for (int cc = 0; cc < 4; ++cc) {
+        const int c = 4 * hs + cc;
+        const uint32_t code = __builtin_amdgcn_ubfe(w, (s0 + (uint32_t)(7 - c) * b) & 31u, b);
+        v[cc] = __builtin_fmaf((float)code, cur.sc, cur.mn);
       }
-      *reinterpret_cast<uint2*>(buf + b_store + (uint32_t)r * kRowB) =
+      *reinterpret_cast<uint2*>(buf + b_store + 8u * (uint32_t)hs) =
           make_uint2(narrow16_pair<DT>(v[0], v[1]), narrow16_pair<DT>(v[2], v[3]));
     }
   };
@@ -335,7 +339,7 @@ hipError_t daf_launch_unpack_matmul(const daf_plan_t* p, const uint32_t* words, 
 #define DAF_LAUNCH(DT, MIXED)                                                                                     \
   hipLaunchKernelGGL((k_unpack_matmul<DT, MIXED>), dim3(blocks), dim3(kThreads), 0, stream, words, mn, scale,     \
                      d_bits, p->d_off, (uint32_t)p->uniform_bits, p->group_size, gy, M, N, K, tiles_n, tiles_k,   \
-                     splits, target)
+                     splits, (uint32_t)p->total_words, target)
   if (dtype == daf::kBF16) {
     if (p->uniform_bits) DAF_LAUNCH(daf::kBF16, false); else DAF_LAUNCH(daf::kBF16, true);
   } else if (dtype == daf::kF16) {
