@@ -124,7 +124,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
     const uint32_t base = n_tiles / 8u, rem = n_tiles & 7u;       // XCD x owns base (+1 if x < rem) tiles
     tile = xcd * base + (xcd < rem ? xcd : rem) + idx;
   }
-  constexpr uint32_t kBand = 4;
+  constexpr uint32_t kBand = 1;
   const uint32_t band = tile / (kBand * (uint32_t)tiles_k);
   const uint32_t in_band = tile - band * (kBand * (uint32_t)tiles_k);
   const uint32_t band_h = ((uint32_t)tiles_n - band * kBand) < kBand ? ((uint32_t)tiles_n - band * kBand) : kBand;
