@@ -236,6 +236,9 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
   // registers just consumed.
   auto do_step = [&](auto BUF, Stage& next, Addr& ad_use, Addr& ad_fill, int step) __attribute__((always_inline)) {
     constexpr int buf = decltype(BUF)::value;
+    // The group addresses of the step after the one requested below go first: when they are
+    // needed (one step from now) all of this step's other loads are younger and may stay in flight.
+    fetch_addr(ad_fill, min(step + 4, steps - 1));
     const char* a_lds = lds[buf] + a_read;
     const char* b_lds = lds[buf] + b_read;
 #pragma unroll
@@ -254,7 +257,6 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
     // Requested unconditionally (past the end the last step is requested again and never
     // used), so that the number of loads in flight is the same in every iteration.
     fetch_stage(next, ad_use, min(step + 3, steps - 1));
-    fetch_addr(ad_fill, min(step + 4, steps - 1));
     __syncthreads();                                // the other copy is complete, this one is free
   };
 
