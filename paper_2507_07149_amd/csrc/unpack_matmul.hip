@@ -279,7 +279,18 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
   // In iteration s: products on copy s % 2; tiles of step s+1 (stage (s+1) % 2) into the other
   // copy; then loads of step s+3 into that same stage, with the addresses in ad[(s+1) % 2]
   // (requested in iteration s-1); addresses of step s+4 into ad[s % 2].
+  // Several steps per trip of the main loop: at a loop header the compiler waits for every load
+  // in flight (it does not carry the order of the previous trip's loads across the back edge),
+  // so the fewer headers, the fewer full drains of the prefetch.
+  constexpr int kTrip = MIXED ? 2 : 8;              // (more would cost the mixed-width kernel a work-group per CU in registers)
   int base = 0;
+  for (; base + kTrip <= steps; base += kTrip) {
+#pragma unroll
+    for (int u = 0; u < kTrip; u += 2) {
+      do_step(Index<0>{}, st[1], ad[1], ad[0], base + u);
+      do_step(Index<1>{}, st[0], ad[0], ad[1], base + u + 1);
+    }
+  }
   for (; base + 2 <= steps; base += 2) {
     do_step(Index<0>{}, st[1], ad[1], ad[0], base);
     do_step(Index<1>{}, st[0], ad[0], ad[1], base + 1);
