@@ -353,6 +353,47 @@ void daf_oracle_group_metrics(const void* x, int dtype, int64_t n, int32_t gs, c
   }
 }
 
+// Quantization variance per group (the third metric Sec. 3.2 names), in double precision: the
+// variance of xhat under the stochastic rounding, sum over the group of scale^2 * p * (1 - p),
+// where p is the share of the 2^k random values for which the element rounds up, counted one
+// random value at a time with the quantizer's own comparison.  Group statistics, scale and
+// reciprocal exactly as the quantizer computes them.
+void daf_oracle_group_variance(const void* x, int dtype, int64_t n, int32_t gs, const uint8_t* bits,
+                               int64_t n_bits, double* variance) {
+  const float two_k = static_cast<float>(1u << kRandBits);
+  const int64_t G = num_groups(n, gs);
+  for (int64_t g = 0; g < G; ++g) {
+    const int64_t lo = g * gs, len = group_len(n, gs, g);
+    const float L = static_cast<float>((1u << group_bits(bits, n_bits, g)) - 1u);
+    float mn = load_elem(x, dtype, lo), mx = mn;
+    for (int64_t j = 1; j < len; ++j) {
+      const float v = load_elem(x, dtype, lo + j);
+      if (v < mn) mn = v;
+      if (v > mx) mx = v;
+    }
+    mn = mn + 0.0f;
+    mx = mx + 0.0f;
+    const float range = mx - mn;
+    const float scale = range / L;
+    float inv = 0.0f;
+    if (range > 0.0f) {
+      inv = L / range;
+      if (!std::isfinite(inv)) inv = 0.0f;
+    }
+    double sum = 0.0;
+    for (int64_t j = 0; j < len; ++j) {
+      const float v = (load_elem(x, dtype, lo + j) - mn) * inv;
+      const float f = v - std::floor(v);
+      uint32_t ups = 0;
+      for (uint32_t r = 0; r < (1u << kRandBits); ++r)
+        if ((static_cast<float>(r) + 0.5f) < f * two_k) ++ups;
+      const double p = static_cast<double>(ups) / static_cast<double>(1u << kRandBits);
+      sum += p * (1.0 - p);
+    }
+    variance[g] = sum * static_cast<double>(scale) * static_cast<double>(scale);
+  }
+}
+
 // Unpack (Algorithm 2's extraction rule, generalised from 4 bits to b) and
 // dequantize (inverse of Eq. 1) groups [g_begin, g_end).
 int daf_oracle_unpack_dequantize_range(const uint32_t* words, const float* mn, const float* scale,

@@ -32,6 +32,8 @@ def lib():
         L.daf_oracle_narrow.argtypes = [vp, c.c_int, i64, vp]
         L.daf_oracle_minmax.argtypes = [vp, c.c_int, i64, vp]
         L.daf_oracle_group_metrics.argtypes = [vp, c.c_int, i64, i32, vp, vp, vp, vp]
+        L.daf_oracle_group_variance.argtypes = [vp, c.c_int, i64, i32, vp, i64, vp]
+        L.daf_oracle_group_variance.restype = None
         L.daf_oracle_group_minmax.argtypes = [vp, c.c_int, i64, i32, vp, vp]
         L.daf_oracle_select_bits.argtypes = [vp, vp, i64, vp, i32, vp]
         L.daf_oracle_select_bits.restype = c.c_int
@@ -136,6 +138,16 @@ def group_metrics(x: np.ndarray, dtype: int, gs: int, codes, mn, sc) -> np.ndarr
     sc = np.ascontiguousarray(sc, dtype=np.float32)
     out = np.empty((G, 2), dtype=np.float64)
     lib().daf_oracle_group_metrics(_p(x), dtype, x.size, gs, _p(codes), _p(mn), _p(sc), _p(out))
+    return out
+
+
+def group_variance(x: np.ndarray, dtype: int, gs: int, bits) -> np.ndarray:
+    """float64[G]: per group, the variance of xhat under the stochastic rounding."""
+    x = np.ascontiguousarray(x.reshape(-1), dtype=_NP[dtype])
+    G = (x.size + gs - 1) // gs
+    b = _bits_arr(bits, G)
+    out = np.empty(G, dtype=np.float64)
+    lib().daf_oracle_group_variance(_p(x), dtype, x.size, gs, _p(b), b.size, _p(out))
     return out
 
 

@@ -101,3 +101,40 @@ def test_group_metrics_against_numpy(dtype):
     # more bits, less error; error bounded by n_g * scale^2
     lens = np.minimum(gs, n - gs * np.arange(G))
     assert np.all(got[:, 0] <= lens * sc.astype(np.float64) ** 2 * (1 + 1e-6) + 1e-30)
+
+
+def test_group_variance_closed_form_and_sampling():
+    """Quantization variance per group: (1) against the closed form in numpy (the number of
+    random bytes that round an element up is ceil(256 f - 1/2) clipped to [0, 256], f the
+    fractional part of the binary32 product), (2) against the sample variance of the dequantized
+    values over many seeds of the oracle's own quantizer."""
+    rng = np.random.default_rng(77)
+    n, gs = 64 * 6, 64
+    G = n // gs
+    bits = np.array([1, 2, 4, 8, 2, 4], np.uint8)
+    x = (rng.standard_normal(n) * 3).astype(np.float32)
+    got = orc.group_variance(x, orc.F32, gs, bits)
+    g = np.arange(n) // gs
+    mn, mx = orc.group_minmax(x, orc.F32, gs)
+    L = (2.0 ** bits.astype(np.float64) - 1).astype(np.float32)
+    rng_ = (mx - mn).astype(np.float32)
+    scale = (rng_ / L).astype(np.float32)
+    inv = (L / rng_).astype(np.float32)
+    v = ((x - mn[g]).astype(np.float32) * inv[g]).astype(np.float32)
+    f = (v - np.floor(v)).astype(np.float64)
+    T = np.clip(np.ceil(256.0 * f - 0.5), 0, 256)
+    p = T / 256.0
+    want = np.bincount(g, weights=p * (1 - p), minlength=G) * scale.astype(np.float64) ** 2
+    assert np.allclose(got, want, rtol=1e-12, atol=0)
+    # sampling: the variance of xhat over seeds, summed per group
+    seeds = 3000
+    acc = np.zeros((seeds, n), np.float64)
+    for s in range(seeds):
+        _, omn, osc, codes = orc.quantize_pack(x, orc.F32, gs, bits, 1000 + s, want_codes=True)
+        acc[s] = codes.astype(np.float64) * osc.astype(np.float64)[g] + omn.astype(np.float64)[g]
+    sample = np.bincount(g, weights=acc.var(axis=0), minlength=G)
+    assert np.all(np.abs(sample - got) <= 0.08 * got + 1e-12), (sample, got)
+    # a constant group has no variance; neither has a group whose values sit on the levels
+    assert orc.group_variance(np.full(64, 2.5, np.float32), orc.F32, 64, 4)[0] == 0.0
+    lv = np.tile(np.arange(4, dtype=np.float32), 16)
+    assert orc.group_variance(lv, orc.F32, 64, 2)[0] == 0.0
