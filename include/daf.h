@@ -199,18 +199,23 @@ int daf_minmax(const void* x, daf_dtype_t dtype, int64_t n, int method, void* wo
 int daf_group_minmax(const daf_plan_t* plan, const void* x, daf_dtype_t dtype,
                      float* out_min, float* out_max, void* stream);
 
-/* daf_quantize_pack_metrics -- daf_quantize_pack that also returns, per group, two of the
- * importance metrics Sec. 3.2 lists as reductions over the activation, computed in the same
- * pass (the reduction-fusion idea of Sec. 3.2.3 applied to this pass):
- *   out_metrics[2g]   = sum over group g of (x - xhat)^2   (quantization error), where
+/* daf_quantize_pack_metrics -- daf_quantize_pack that also returns, per group, the three
+ * importance metrics Sec. 3.2 lists as reductions over the activation (quantization error,
+ * quantization variance, magnitude), computed in the same pass (the reduction-fusion idea of
+ * Sec. 3.2.3 applied to this pass):
+ *   out_metrics[3g]   = sum over group g of (x - xhat)^2   (quantization error), where
  *                       xhat = fma(code, scale, min) in binary32, i.e. the dequantized value
  *                       before any narrowing to a 16-bit dtype;
- *   out_metrics[2g+1] = sum over group g of x^2            (magnitude).
- * Sums are accumulated in binary32 (per lane, then across lanes, then across loads), so they
- * agree with a double-precision evaluation to a relative error of about n_g * 2^-24.
- * words, min and scale are identical to daf_quantize_pack's.
+ *   out_metrics[3g+1] = sum over group g of x^2            (magnitude);
+ *   out_metrics[3g+2] = scale^2 * sum over group g of p (1 - p)   (quantization variance: the
+ *                       variance of xhat under the stochastic rounding), p = the share of the
+ *                       256 random bytes for which the element rounds up.
+ * Sums are accumulated in binary32 (per lane, then across lanes, then across loads; the
+ * variance as an exact integer per lane), so they agree with a double-precision evaluation to
+ * a relative error of about n_g * 2^-24.  words, min and scale are identical to
+ * daf_quantize_pack's.
  *
- *   out_metrics   DEVICE, 2*G floats, 8-byte aligned.
+ *   out_metrics   DEVICE, 3*G floats, 4-byte aligned.
  *
  * Errors: as daf_quantize_pack; DAF_EUNSUPPORTED also for plans whose groups are longer than
  * 4096 elements.

@@ -196,7 +196,7 @@ int daf_quantize_pack_metrics(const daf_plan_t* plan, const void* x, daf_dtype_t
       out_metrics == nullptr)
     return DAF_EINVAL;
   if (!aligned(x, 16) || !aligned(out_words, 4) || !aligned(out_min, 4) || !aligned(out_scale, 4) ||
-      !aligned(out_metrics, 8))
+      !aligned(out_metrics, 4))
     return DAF_EINVAL;
   if (dtype != DAF_F32 && dtype != DAF_F16 && dtype != DAF_BF16) return DAF_EUNSUPPORTED;
   if (plan->d_big_scratch != nullptr) return DAF_EUNSUPPORTED;     // groups longer than 4096 elements

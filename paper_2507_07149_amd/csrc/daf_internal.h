@@ -28,7 +28,7 @@ hipError_t daf_launch_plan_scan(const uint8_t* d_bits, int64_t num_groups, int64
                                 unsigned long long* d_total, int* d_bad, hipStream_t stream);
 int64_t daf_plan_scan_blocks(int64_t num_groups);
 
-// out_metrics: null, or 2 floats per group (sum (x-xhat)^2, sum x^2); not with groups longer than a tile.
+// out_metrics: null, or 3 floats per group (sum (x-xhat)^2, sum x^2, rounding variance); not with groups longer than a tile.
 // out_relu_y: null, or the buffer that receives max(x, +0), which is then what gets quantized (may be x
 // itself); not together with out_metrics, not with groups longer than a tile.
 hipError_t daf_launch_quantize_pack(const daf_plan_t* plan, const void* x, int dtype, uint64_t seed,

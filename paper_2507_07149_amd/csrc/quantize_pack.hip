@@ -58,10 +58,19 @@ __device__ __forceinline__ GroupScale group_scale(float mn, float mx, uint32_t b
 // Negated code of one element.  EXACT2 = false: invs = inv*256 (finite).  EXACT2 = true:
 // invs = inv, and the factor 256 is applied to the rounded product.
 template <bool EXACT2>
-__device__ __forceinline__ int neg_code(float x, float mn, float invs, uint32_t r) {
+__device__ __forceinline__ int neg_code(float x, float mn, float invs, uint32_t r, int* t_out = nullptr) {
   float w = (mn - x) * invs;
   if (EXACT2) w = w * kScale;
-  return (round_half_up_to_int(w) + (int)r) >> 8;
+  const int t = round_half_up_to_int(w);            // -(256*floor(v) + T), T = byte values that round up
+  if (t_out) *t_out = t;
+  return (t + (int)r) >> 8;
+}
+
+// T * (256 - T) for the element whose rounded product is t: 65536 * p * (1 - p) with p = T / 256
+// the probability of rounding up (T = 256, always up, reads as 0 here: the same product).
+__device__ __forceinline__ uint32_t sr_variance_term(int t) {
+  const uint32_t T = (uint32_t)(-t) & 255u;
+  return T * (256u - T);
 }
 
 // max(x, +0) on the raw bits of one 32-bit word (one binary32 value or two 16-bit values):
@@ -103,7 +112,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_group(
     const void* x, int64_t n, int32_t gs, int64_t g_begin, int64_t g_end,
     const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, int32_t uniform_bits,
     uint32_t seed_lo, uint32_t seed_hi, uint32_t* __restrict__ words, float* __restrict__ out_min,
-    float* __restrict__ out_scale, float2* __restrict__ out_metrics, void* out_y) {
+    float* __restrict__ out_scale, float* __restrict__ out_metrics, void* out_y) {
   const int lane = threadIdx.x & (kWave - 1);
   const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
   const int64_t n_waves = (int64_t)gridDim.x * kWavesPerBlock;
@@ -132,6 +141,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_group(
     const uint32_t cpw = 32u / b;                          // codes per word
     const int32_t n_words = (int32_t)(((int64_t)len * b + 31) >> 5);
     float err = 0.0f, mag = 0.0f;
+    uint32_t var_i = 0u;
     for (int32_t t = lane; t < n_words; t += kWave) {
       uint32_t word = 0;
       uint64_t cur_blk = ~0ull;
@@ -149,19 +159,27 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_group(
         const uint32_t rw = (slot < 4) ? rnd.x : (slot < 8) ? rnd.y : (slot < 12) ? rnd.z : rnd.w;
         const uint32_t r = (rw >> (8u * (slot & 3u))) & 0xFFu;
         const float xv = load_elem<DT, RELU>(x, lo + j);     // z or y: max(., +0) gives y either way
-        const int nc = neg_code<true>(xv, s.mn, s.inv, r);
+        int rt;
+        const int nc = neg_code<true>(xv, s.mn, s.inv, r, &rt);
         word |= (uint32_t)(-nc) << (32u - b - c * b);
         if (METRICS) {
           const float d = xv - __builtin_fmaf((float)(-nc), s.scale, s.mn);
           err = __builtin_fmaf(d, d, err);
           mag = __builtin_fmaf(xv, xv, mag);
+          var_i += sr_variance_term(rt);
         }
       }
       words[woff + t] = word;
     }
     if (METRICS) {
+      float var = (float)var_i, unused = 0.0f;
       seg_sum2<6>(err, mag);
-      if (lane == kWave - 1) out_metrics[g] = make_float2(err, mag);
+      seg_sum2<6>(var, unused);
+      if (lane == kWave - 1) {
+        out_metrics[3 * g] = err;
+        out_metrics[3 * g + 1] = mag;
+        out_metrics[3 * g + 2] = (var * 1.52587890625e-05f) * (s.scale * s.scale);
+      }
     }
   }
 }
@@ -211,6 +229,7 @@ struct alignas(16) WaveLds {
   float2 stat[kWave];                   // (min, max) per group, written by the group's last lane;
                                         // later (metrics variant) the group's (error, magnitude) sums
   float gscale[kWave];                  // scale per group (metrics variant)
+  float gvar[kWave];                    // sum of T*(256-T) per group (metrics variant)
 };
 
 // Codes of one 16-byte chunk, accumulated most significant first and NEGATED (the element map
@@ -218,27 +237,31 @@ struct alignas(16) WaveLds {
 //
 // METRICS: also returns this lane's share of the group's importance sums (Sec. 3.2 names
 // quantization error and tensor magnitude): err += (x - xhat)^2 with xhat = fma(code, scale, mn)
-// as the dequantizer computes it, mag += x^2, both in binary32.
+// as the dequantizer computes it, mag += x^2, both in binary32; var = sum of T*(256-T), the
+// variance of the stochastic rounding in units of scale^2 / 65536 (exact integer).
 template <int DT, bool EXACT2, bool METRICS = false>
 __device__ __forceinline__ void quantize_chunk(const float (&xf)[ElemTraits<DT>::kPerLoad], float mn,
                                                float invs, uint32_t b, const uint32_t* rnd,
                                                uint32_t& nacc0, uint32_t& nacc1, float scale = 0.0f,
-                                               float* err = nullptr, float* mag = nullptr) {
+                                               float* err = nullptr, float* mag = nullptr, float* var = nullptr) {
   constexpr int kEpl = ElemTraits<DT>::kPerLoad;
   uint32_t nacc[2] = {0u, 0u};
   float e2 = 0.0f, m2 = 0.0f;
+  uint32_t v2 = 0u;
 #pragma unroll
   for (int q = 0; q < kEpl / 4; ++q) {
     const uint32_t rw = rnd[q];                 // the random bytes of four consecutive elements
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const float xv = xf[q * 4 + e];
-      const int nc = neg_code<EXACT2>(xv, mn, invs, (rw >> (8 * e)) & 0xFFu);
+      int rt;
+      const int nc = neg_code<EXACT2>(xv, mn, invs, (rw >> (8 * e)) & 0xFFu, METRICS ? &rt : nullptr);
       nacc[q] = (nacc[q] << b) + (uint32_t)nc;
       if (METRICS) {
         const float d = xv - __builtin_fmaf((float)(-nc), scale, mn);
         e2 = __builtin_fmaf(d, d, e2);
         m2 = __builtin_fmaf(xv, xv, m2);
+        v2 += sr_variance_term(rt);
       }
     }
   }
@@ -247,6 +270,7 @@ __device__ __forceinline__ void quantize_chunk(const float (&xf)[ElemTraits<DT>:
   if (METRICS) {
     *err = e2;
     *mag = m2;
+    *var = (float)v2;
   }
 }
 
@@ -320,7 +344,8 @@ __device__ __forceinline__ void tile_minmax(const uint4 (&raw)[TileShape<DT, LPG
 // the reduction, and the group's first tile stores min and scale.
 //
 // METRICS = true: additionally writes, per group, the sums (x - xhat)^2 and x^2 over the group
-// (binary32, accumulated per lane, then across the group's lanes, then across its loads).
+// (binary32, accumulated per lane, then across the group's lanes, then across its loads) and the
+// variance of the stochastic rounding, scale^2 * sum p (1 - p).
 //
 // RELU = true: x holds z; every element becomes max(z, +0) right after the load, the result is
 // written to out_y in the same layout (out_y may be x itself: a lane only overwrites chunks it
@@ -330,7 +355,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_tile(
     typename std::conditional<RELU, const u32x4*, const u32x4* __restrict__>::type x, int64_t n_tiles,
     const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, uint32_t seed_lo, uint32_t seed_hi,
     uint32_t* __restrict__ words, float* __restrict__ out_min, float* __restrict__ out_scale,
-    const float2* __restrict__ ext_stat, int64_t tiles_per_group, float2* __restrict__ out_metrics,
+    const float2* __restrict__ ext_stat, int64_t tiles_per_group, float* __restrict__ out_metrics,
     u32x4* out_y) {
   using S = TileShape<DT, LPG_LOG2>;
   static_assert(!EXT || S::kGroups == 1, "external statistics: the tile is part of one group");
@@ -460,6 +485,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_tile(
       if (METRICS) {
         wave_lds_sync();                       // every lane has read its (min, max) pairs
         lds.stat[lane] = make_float2(0.0f, 0.0f);
+        lds.gvar[lane] = 0.0f;
       }
     }
 
@@ -502,13 +528,17 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_tile(
       uint32_t n0, n1;
       if constexpr (METRICS) {
         const float g_scale = lds.gscale[grp];
-        float err, mag;
-        if (need_exact2) quantize_chunk<DT, true, true>(xf[u], g_mn, g_invs, b, rnd[u], n0, n1, g_scale, &err, &mag);
-        else             quantize_chunk<DT, false, true>(xf[u], g_mn, g_invs, b, rnd[u], n0, n1, g_scale, &err, &mag);
+        float err, mag, var, unused = 0.0f;
+        if (need_exact2)
+          quantize_chunk<DT, true, true>(xf[u], g_mn, g_invs, b, rnd[u], n0, n1, g_scale, &err, &mag, &var);
+        else
+          quantize_chunk<DT, false, true>(xf[u], g_mn, g_invs, b, rnd[u], n0, n1, g_scale, &err, &mag, &var);
         seg_sum2<S::kLaneLog2>(err, mag);      // over the group's lanes of this load
+        seg_sum2<S::kLaneLog2>(var, unused);
         if (lane_in_run == (uint32_t)S::kLpg - 1u) {
           const float2 acc = lds.stat[grp];    // the group's earlier loads (same lane, in order)
           lds.stat[grp] = make_float2(acc.x + err, acc.y + mag);
+          lds.gvar[grp] += var;
         }
       } else {
         if (need_exact2) quantize_chunk<DT, true>(xf[u], g_mn, g_invs, b, rnd[u], n0, n1);
@@ -547,13 +577,19 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_tile(
     // 6. the tile's words are one contiguous run in the packed buffer
     uint32_t* dst = words + tile_base;
     for (uint32_t i = lane; i < tile_words; i += kWave) dst[i] = lds.stage[i];
-    if (METRICS && lane < S::kGroups) out_metrics[g0 + lane] = lds.stat[lane];
+    if (METRICS && lane < S::kGroups) {
+      const float sc = lds.gscale[lane];
+      float* m = out_metrics + 3 * (g0 + lane);
+      m[0] = lds.stat[lane].x;
+      m[1] = lds.stat[lane].y;
+      m[2] = (lds.gvar[lane] * 1.52587890625e-05f) * (sc * sc);
+    }
   }
 }
 
 template <int DT, int LPG_LOG2, bool METRICS, bool RELU>
 hipError_t launch_tile(const daf_plan_t* p, const void* x, int64_t n_tiles, uint32_t seed_lo, uint32_t seed_hi,
-                       uint32_t* out_words, float* out_min, float* out_scale, float2* out_metrics, void* out_y,
+                       uint32_t* out_words, float* out_min, float* out_scale, float* out_metrics, void* out_y,
                        hipStream_t stream) {
 #define DAF_LAUNCH(BITS)                                                                                   \
   do {                                                                                                     \
@@ -884,7 +920,7 @@ hipError_t launch_group_minmax(const daf_plan_t* p, const void* x, float* out_mi
 
 template <int DT, bool METRICS, bool RELU = false>
 hipError_t launch_dtype(const daf_plan_t* p, const void* x, uint64_t seed, uint32_t* out_words, float* out_min,
-                        float* out_scale, float2* out_metrics, void* out_y, hipStream_t stream) {
+                        float* out_scale, float* out_metrics, void* out_y, hipStream_t stream) {
   const uint32_t seed_lo = (uint32_t)seed, seed_hi = (uint32_t)(seed >> 32);
   constexpr int kEpl = ElemTraits<DT>::kPerLoad;
   const int64_t full_groups = p->n / p->group_size;
@@ -946,7 +982,7 @@ hipError_t daf_launch_group_minmax(const daf_plan_t* plan, const void* x, int dt
 hipError_t daf_launch_quantize_pack(const daf_plan_t* plan, const void* x, int dtype, uint64_t seed,
                                     uint32_t* out_words, float* out_min, float* out_scale, float* out_metrics,
                                     void* out_relu_y, hipStream_t stream) {
-  float2* m = reinterpret_cast<float2*>(out_metrics);
+  float* m = out_metrics;
   if (m && out_relu_y) return hipErrorNotSupported;
 #define DAF_DT(D)                                                                                         \
   if (out_relu_y)                                                                                         \

@@ -142,7 +142,7 @@ def test_fused_metrics(env, dtype, gs, bits):
     words = torch.empty(plan.packed_words, dtype=torch.int32, device="cuda:0")
     mn = torch.empty(G, device="cuda:0")
     sc = torch.empty(G, device="cuda:0")
-    met = torch.full((G, 2), float("nan"), device="cuda:0")
+    met = torch.full((G, 3), float("nan"), device="cuda:0")
     daf.daf_quantize_pack_metrics(plan, xd, 9, words, mn, sc, met)
     torch.cuda.synchronize()
     xb = to_numpy_bits(x)
@@ -150,12 +150,15 @@ def test_fused_metrics(env, dtype, gs, bits):
     assert np.array_equal(words.cpu().numpy().view(np.uint32), ow)
     assert np.array_equal(mn.cpu().numpy().view(np.uint32), omn.view(np.uint32))
     assert np.array_equal(sc.cpu().numpy().view(np.uint32), osc.view(np.uint32))
-    want = orc.group_metrics(xb, dtype, gs, codes, omn, osc)
+    want = np.concatenate([orc.group_metrics(xb, dtype, gs, codes, omn, osc),
+                           orc.group_variance(xb, dtype, gs, b)[:, None]], axis=1)
     got = met.cpu().numpy().astype(np.float64)
     # every one of the <= gs products and additions rounds with relative error <= 2^-24 and all
     # terms are non-negative, so the sum is within (gs + 2) * 2^-24 of the exact one
-    rtol = (gs + 2) * 2.0 ** -24
+    # (the variance: an exact integer per lane, then at most gs additions and three multiplications)
+    rtol = (gs + 4) * 2.0 ** -24
     assert np.all(np.abs(got - want) <= rtol * want + 1e-38), np.abs(got - want).max()
+    assert want[:, 2].max() > 0
 
 
 def test_fused_metrics_rejects_long_groups(env):
@@ -165,5 +168,5 @@ def test_fused_metrics_rejects_long_groups(env):
     words = torch.empty(plan.packed_words, dtype=torch.int32, device="cuda:0")
     mn = torch.empty(2, device="cuda:0")
     with pytest.raises(daf.DafError) as e:
-        daf.daf_quantize_pack_metrics(plan, x, 0, words, mn, mn.clone(), torch.empty(2, 2, device="cuda:0"))
+        daf.daf_quantize_pack_metrics(plan, x, 0, words, mn, mn.clone(), torch.empty(2, 3, device="cuda:0"))
     assert e.value.status == -2
