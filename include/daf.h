@@ -224,6 +224,43 @@ int daf_quantize_pack_metrics(const daf_plan_t* plan, const void* x, daf_dtype_t
                               uint32_t* out_words, float* out_min, float* out_scale,
                               float* out_metrics, void* stream);
 
+/* ---- several tensors per call ----------------------------------------------------------------
+ *
+ * A training step saves many activations (Sec. 3.1; e.g. 17 per ResNet-18 step).  These two
+ * calls take a list of tensors of one dtype and produce exactly what one daf_quantize_pack /
+ * daf_unpack_dequantize per item would, but merge the items into as few kernel launches as
+ * their plans allow (consecutive items with the same group size and the same kind of width
+ * share a launch, at most 32 per launch), so that the start-up and drain of a launch are paid
+ * once per list instead of once per tensor.
+ *
+ *   items     HOST array; the pointers inside are DEVICE pointers with the alignment rules of
+ *             the single-tensor calls; `bits` in a dequantize item may be NULL (the plan's).
+ *
+ * Errors: DAF_EINVAL (null array or pointer, n_items < 1, misaligned pointer),
+ * DAF_EUNSUPPORTED (dtype), DAF_EDEVICE.  Argument checks cover the whole list before any
+ * launch.
+ */
+typedef struct {
+  const daf_plan_t* plan;
+  const void* x;
+  uint64_t seed;
+  uint32_t* out_words;
+  float* out_min;
+  float* out_scale;
+} daf_quantize_item_t;
+
+typedef struct {
+  const daf_plan_t* plan;
+  const uint32_t* words;
+  const float* min;
+  const float* scale;
+  const uint8_t* bits;
+  void* out_x;
+} daf_dequantize_item_t;
+
+int daf_quantize_pack_batch(const daf_quantize_item_t* items, int32_t n_items, daf_dtype_t dtype, void* stream);
+int daf_unpack_dequantize_batch(const daf_dequantize_item_t* items, int32_t n_items, daf_dtype_t dtype, void* stream);
+
 /* ---- producer fusion: the activation function and the quantization in one pass -------------
  *
  * daf_relu_quantize_pack -- for a layer whose saved activation is y = max(z, 0): reads the

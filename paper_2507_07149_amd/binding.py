@@ -55,6 +55,10 @@ def load_library():
     L.daf_unpack_dequantize.restype = c.c_int
     L.daf_quantize_pack_metrics.argtypes = [vp, vp, c.c_int, u64, vp, vp, vp, vp, vp]
     L.daf_quantize_pack_metrics.restype = c.c_int
+    L.daf_quantize_pack_batch.argtypes = [vp, i32, c.c_int, vp]
+    L.daf_quantize_pack_batch.restype = c.c_int
+    L.daf_unpack_dequantize_batch.argtypes = [vp, i32, c.c_int, vp]
+    L.daf_unpack_dequantize_batch.restype = c.c_int
     L.daf_relu_quantize_pack.argtypes = [vp, vp, c.c_int, u64, vp, vp, vp, vp, vp]
     L.daf_relu_quantize_pack.restype = c.c_int
     L.daf_unpack_relu_backward.argtypes = [vp, vp, vp, vp, vp, vp, vp, c.c_int, vp]
@@ -166,6 +170,56 @@ def daf_unpack_dequantize(plan: Plan, words: torch.Tensor, mn: torch.Tensor, sca
                                               out_x.data_ptr(), _DTYPE_ID[out_x.dtype], _stream_handle(stream))
     if rc != 0:
         raise DafError(rc, "daf_unpack_dequantize")
+
+
+class _QuantizeItem(ctypes.Structure):
+    _fields_ = [("plan", ctypes.c_void_p), ("x", ctypes.c_void_p), ("seed", ctypes.c_uint64),
+                ("out_words", ctypes.c_void_p), ("out_min", ctypes.c_void_p), ("out_scale", ctypes.c_void_p)]
+
+
+class _DequantizeItem(ctypes.Structure):
+    _fields_ = [("plan", ctypes.c_void_p), ("words", ctypes.c_void_p), ("min", ctypes.c_void_p),
+                ("scale", ctypes.c_void_p), ("bits", ctypes.c_void_p), ("out_x", ctypes.c_void_p)]
+
+
+def quantize_items(items):
+    """Marshals [(plan, x, seed, out_words, out_min, out_scale), ...] once; the result can be passed to
+    daf_quantize_pack_batch any number of times while the tensors stay alive."""
+    arr = (_QuantizeItem * len(items))()
+    for a, (plan, x, seed, words, mn, sc) in zip(arr, items):
+        a.plan, a.x, a.seed = plan.handle, x.data_ptr(), seed
+        a.out_words, a.out_min, a.out_scale = words.data_ptr(), mn.data_ptr(), sc.data_ptr()
+    arr.dtype_id = _DTYPE_ID[items[0][1].dtype]
+    return arr
+
+
+def dequantize_items(items):
+    """Marshals [(plan, words, min, scale, out_x, bits or None), ...] for daf_unpack_dequantize_batch."""
+    arr = (_DequantizeItem * len(items))()
+    for a, (plan, words, mn, sc, out_x, bits) in zip(arr, items):
+        a.plan, a.words, a.min, a.scale = plan.handle, words.data_ptr(), mn.data_ptr(), sc.data_ptr()
+        a.bits = bits.data_ptr() if bits is not None else None
+        a.out_x = out_x.data_ptr()
+    arr.dtype_id = _DTYPE_ID[items[0][4].dtype]
+    return arr
+
+
+def daf_quantize_pack_batch(items, stream=None) -> None:
+    """items: a list of (plan, x, seed, out_words, out_min, out_scale), or the result of quantize_items."""
+    arr = items if isinstance(items, ctypes.Array) else quantize_items(items)
+    rc = load_library().daf_quantize_pack_batch(ctypes.cast(arr, ctypes.c_void_p), len(arr), arr.dtype_id,
+                                                _stream_handle(stream))
+    if rc != 0:
+        raise DafError(rc, "daf_quantize_pack_batch")
+
+
+def daf_unpack_dequantize_batch(items, stream=None) -> None:
+    """items: a list of (plan, words, min, scale, out_x, bits or None), or the result of dequantize_items."""
+    arr = items if isinstance(items, ctypes.Array) else dequantize_items(items)
+    rc = load_library().daf_unpack_dequantize_batch(ctypes.cast(arr, ctypes.c_void_p), len(arr), arr.dtype_id,
+                                                    _stream_handle(stream))
+    if rc != 0:
+        raise DafError(rc, "daf_unpack_dequantize_batch")
 
 
 def daf_unpack_relu_backward(plan: Plan, words: torch.Tensor, mn: torch.Tensor, scale: torch.Tensor,

@@ -168,6 +168,36 @@ int daf_quantize_pack(const daf_plan_t* plan, const void* x, daf_dtype_t dtype, 
   return e == hipSuccess ? DAF_OK : DAF_EDEVICE;
 }
 
+int daf_quantize_pack_batch(const daf_quantize_item_t* items, int32_t n_items, daf_dtype_t dtype, void* stream) {
+  if (items == nullptr || n_items < 1) return DAF_EINVAL;
+  if (dtype != DAF_F32 && dtype != DAF_F16 && dtype != DAF_BF16) return DAF_EUNSUPPORTED;
+  for (int32_t i = 0; i < n_items; ++i) {
+    const daf_quantize_item_t& it = items[i];
+    if (it.plan == nullptr || it.x == nullptr || it.out_words == nullptr || it.out_min == nullptr ||
+        it.out_scale == nullptr)
+      return DAF_EINVAL;
+    if (!aligned(it.x, 16) || !aligned(it.out_words, 4) || !aligned(it.out_min, 4) || !aligned(it.out_scale, 4))
+      return DAF_EINVAL;
+  }
+  const hipError_t e = daf_launch_quantize_pack_batch(items, n_items, (int)dtype, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? DAF_OK : DAF_EDEVICE;
+}
+
+int daf_unpack_dequantize_batch(const daf_dequantize_item_t* items, int32_t n_items, daf_dtype_t dtype, void* stream) {
+  if (items == nullptr || n_items < 1) return DAF_EINVAL;
+  if (dtype != DAF_F32 && dtype != DAF_F16 && dtype != DAF_BF16) return DAF_EUNSUPPORTED;
+  for (int32_t i = 0; i < n_items; ++i) {
+    const daf_dequantize_item_t& it = items[i];
+    if (it.plan == nullptr || it.words == nullptr || it.min == nullptr || it.scale == nullptr || it.out_x == nullptr)
+      return DAF_EINVAL;
+    if (!aligned(it.out_x, 16) || !aligned(it.words, 4) || !aligned(it.min, 4) || !aligned(it.scale, 4))
+      return DAF_EINVAL;
+    if (it.plan->uniform_bits && it.bits != nullptr) return DAF_EINVAL;
+  }
+  const hipError_t e = daf_launch_unpack_dequantize_batch(items, n_items, (int)dtype, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? DAF_OK : DAF_EDEVICE;
+}
+
 int daf_relu_quantize_pack(const daf_plan_t* plan, const void* z, daf_dtype_t dtype, uint64_t seed, void* out_y,
                            uint32_t* out_words, float* out_min, float* out_scale, void* stream) {
   if (plan == nullptr || z == nullptr || out_y == nullptr || out_words == nullptr || out_min == nullptr ||

@@ -43,6 +43,12 @@ hipError_t daf_launch_unpack_matmul(const daf_plan_t* p, const uint32_t* words, 
                                     const uint8_t* d_bits, const void* grad_y, int64_t N, int64_t K, int dtype,
                                     float* out, float* workspace, hipStream_t stream);
 
+// One call for several tensors of one dtype (daf_quantize_item_t / daf_dequantize_item_t: daf.h).
+hipError_t daf_launch_quantize_pack_batch(const daf_quantize_item_t* items, int32_t n_items, int dtype,
+                                          hipStream_t stream);
+hipError_t daf_launch_unpack_dequantize_batch(const daf_dequantize_item_t* items, int32_t n_items, int dtype,
+                                              hipStream_t stream);
+
 // relu_grad_y: null, or the gradient of y = max(z, 0): out_x then receives (xhat > 0) ? grad_y : +0
 hipError_t daf_launch_unpack_dequantize(const daf_plan_t* plan, const uint32_t* words, const float* mn,
                                         const float* scale, const uint8_t* d_bits, void* out_x, int dtype,

@@ -351,8 +351,8 @@ __device__ __forceinline__ void tile_minmax(const uint4 (&raw)[TileShape<DT, LPG
 // written to out_y in the same layout (out_y may be x itself: a lane only overwrites chunks it
 // has already loaded), and everything else sees y.
 template <int DT, int LPG_LOG2, int B, bool EXT = false, bool METRICS = false, bool RELU = false>
-__global__ __launch_bounds__(kThreads) void k_quantize_pack_tile(
-    typename std::conditional<RELU, const u32x4*, const u32x4* __restrict__>::type x, int64_t n_tiles,
+__device__ __forceinline__ void quantize_pack_tile_body(
+    typename std::conditional<RELU, const u32x4*, const u32x4* __restrict__>::type x, int64_t tile, int wave_in_block,
     const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, uint32_t seed_lo, uint32_t seed_hi,
     uint32_t* __restrict__ words, float* __restrict__ out_min, float* __restrict__ out_scale,
     const float2* __restrict__ ext_stat, int64_t tiles_per_group, float* __restrict__ out_metrics,
@@ -367,9 +367,6 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_tile(
   __shared__ WaveLds<DT, LPG_LOG2> lds_all[kWavesPerBlock];
 
   const int lane = threadIdx.x & (kWave - 1);
-  const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int64_t tile = (int64_t)blockIdx.x * kWavesPerBlock + wave_in_block;
-  if (tile >= n_tiles) return;
   WaveLds<DT, LPG_LOG2>& lds = lds_all[wave_in_block];
   const uint32_t lane_in_run = (uint32_t)(lane & (S::kLpg - 1));
   uint8_t* stage8 = reinterpret_cast<uint8_t*>(lds.stage);
@@ -585,6 +582,54 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_tile(
       m[2] = (lds.gvar[lane] * 1.52587890625e-05f) * (sc * sc);
     }
   }
+}
+
+template <int DT, int LPG_LOG2, int B, bool EXT = false, bool METRICS = false, bool RELU = false>
+__global__ __launch_bounds__(kThreads) void k_quantize_pack_tile(
+    typename std::conditional<RELU, const u32x4*, const u32x4* __restrict__>::type x, int64_t n_tiles,
+    const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, uint32_t seed_lo, uint32_t seed_hi,
+    uint32_t* __restrict__ words, float* __restrict__ out_min, float* __restrict__ out_scale,
+    const float2* __restrict__ ext_stat, int64_t tiles_per_group, float* __restrict__ out_metrics,
+    u32x4* out_y) {
+  const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t tile = (int64_t)blockIdx.x * kWavesPerBlock + wave_in_block;
+  if (tile >= n_tiles) return;
+  quantize_pack_tile_body<DT, LPG_LOG2, B, EXT, METRICS, RELU>(x, tile, wave_in_block, bits, off, seed_lo, seed_hi, words,
+                                                               out_min, out_scale, ext_stat, tiles_per_group,
+                                                               out_metrics, out_y);
+}
+
+// Several tensors in one launch (the activations a training step saves, Sec. 3.1): the tiles
+// of all of them form one sequence, and a wave finds its tensor by walking the cumulative tile
+// counts.  One launch has one ramp at its start and one tail at its end instead of one per
+// tensor.  The descriptors travel as kernel arguments.
+constexpr int kMaxBatch = 32;
+struct BatchEntry {
+  const void* x;
+  const uint8_t* bits;
+  const uint32_t* off;
+  uint32_t* words;
+  float* mn;
+  float* sc;
+  int64_t tile_end;                                 // tiles of this and all earlier entries
+  uint32_t seed_lo, seed_hi;
+};
+struct Batch {
+  BatchEntry e[kMaxBatch];
+  int32_t n;
+};
+
+template <int DT, int LPG_LOG2, int B>
+__global__ __launch_bounds__(kThreads) void k_quantize_pack_tile_batch(const Batch batch) {
+  const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t gtile = (int64_t)blockIdx.x * kWavesPerBlock + wave_in_block;
+  if (gtile >= batch.e[batch.n - 1].tile_end) return;
+  int t = 0;
+  while (gtile >= batch.e[t].tile_end) ++t;         // uniform over the wave; t < batch.n by the check above
+  const BatchEntry& e = batch.e[t];
+  const int64_t tile = gtile - (t ? batch.e[t - 1].tile_end : 0);
+  quantize_pack_tile_body<DT, LPG_LOG2, B>(static_cast<const u32x4*>(e.x), tile, wave_in_block, e.bits, e.off, e.seed_lo,
+                                           e.seed_hi, e.words, e.mn, e.sc, nullptr, (int64_t)1, nullptr, nullptr);
 }
 
 template <int DT, int LPG_LOG2, bool METRICS, bool RELU>
@@ -967,7 +1012,133 @@ hipError_t launch_dtype(const daf_plan_t* p, const void* x, uint64_t seed, uint3
   return hipSuccess;
 }
 
+// Tiles per tensor on the fast path (0 if the plan is not eligible) and the groups they cover.
+template <int DT>
+bool tile_geometry(const daf_plan_t* p, int* lpg_log2, int64_t* n_tiles, int64_t* fast_groups) {
+  constexpr int kEpl = ElemTraits<DT>::kPerLoad;
+  *n_tiles = 0;
+  *fast_groups = 0;
+  if (p->d_big_scratch != nullptr) return false;
+  const int32_t lpg = p->group_size / kEpl;
+  if (p->group_size % kEpl != 0 || lpg < 4 || (lpg & (lpg - 1)) != 0) return false;
+  const int64_t full_groups = p->n / p->group_size;
+  bool ok = false;
+#define DAF_CASE(LOG2)                                                   \
+  case (1 << LOG2):                                                      \
+    if constexpr (TileShape<DT, LOG2>::kValid) {                         \
+      *lpg_log2 = LOG2;                                                  \
+      *n_tiles = full_groups / TileShape<DT, LOG2>::kGroups;             \
+      *fast_groups = *n_tiles * TileShape<DT, LOG2>::kGroups;            \
+      ok = *n_tiles > 0;                                                 \
+    }                                                                    \
+    break;
+  switch (lpg) {
+    DAF_CASE(2) DAF_CASE(3) DAF_CASE(4) DAF_CASE(5) DAF_CASE(6)
+    DAF_CASE(7) DAF_CASE(8) DAF_CASE(9) DAF_CASE(10)
+    default: break;
+  }
+#undef DAF_CASE
+  return ok;
+}
+
+template <int DT, int LPG_LOG2>
+hipError_t launch_batch_bits(const Batch& batch, int32_t uniform_bits, hipStream_t stream) {
+  const int64_t tiles = batch.e[batch.n - 1].tile_end;
+  const unsigned blocks = (unsigned)((tiles + kWavesPerBlock - 1) / kWavesPerBlock);
+#define DAF_LAUNCH(BITS) \
+  hipLaunchKernelGGL((k_quantize_pack_tile_batch<DT, LPG_LOG2, BITS>), dim3(blocks), dim3(kThreads), 0, stream, batch)
+  switch (uniform_bits) {
+    case 0: DAF_LAUNCH(0); break;
+    case 1: DAF_LAUNCH(1); break;
+    case 2: DAF_LAUNCH(2); break;
+    case 4: DAF_LAUNCH(4); break;
+    case 8: DAF_LAUNCH(8); break;
+    default: return hipErrorInvalidValue;
+  }
+#undef DAF_LAUNCH
+  return hipGetLastError();
+}
+
+template <int DT>
+hipError_t launch_batch(const Batch& batch, int lpg_log2, int32_t uniform_bits, hipStream_t stream) {
+  switch (lpg_log2) {
+#define DAF_CASE(LOG2)                                                                      \
+  case LOG2:                                                                                \
+    if constexpr (TileShape<DT, LOG2>::kValid) return launch_batch_bits<DT, LOG2>(batch, uniform_bits, stream); \
+    break;
+    DAF_CASE(2) DAF_CASE(3) DAF_CASE(4) DAF_CASE(5) DAF_CASE(6)
+    DAF_CASE(7) DAF_CASE(8) DAF_CASE(9) DAF_CASE(10)
+#undef DAF_CASE
+    default: break;
+  }
+  return hipErrorInvalidValue;
+}
+
+// Same results as one daf_launch_quantize_pack per item.  Consecutive items whose plans share
+// group size and width kind go into one launch for their whole tiles (at most kMaxBatch per
+// launch); the groups after an item's last whole tile, and items the fast path does not cover,
+// are launched as before.
+template <int DT>
+hipError_t launch_items(const daf_quantize_item_t* items, int32_t n_items, hipStream_t stream) {
+  Batch batch;
+  batch.n = 0;
+  int cur_log2 = -1, cur_gs = -1, cur_bits = -1;
+  hipError_t err = hipSuccess;
+  auto flush = [&]() {
+    if (batch.n > 0 && err == hipSuccess) err = launch_batch<DT>(batch, cur_log2, cur_bits, stream);
+    batch.n = 0;
+  };
+  for (int32_t i = 0; i < n_items && err == hipSuccess; ++i) {
+    const daf_quantize_item_t& it = items[i];
+    const daf_plan_t* p = it.plan;
+    int log2 = 0;
+    int64_t n_tiles = 0, fast_groups = 0;
+    if (!tile_geometry<DT>(p, &log2, &n_tiles, &fast_groups)) {
+      flush();
+      if (err == hipSuccess)
+        err = launch_dtype<DT, false>(p, it.x, it.seed, it.out_words, it.out_min, it.out_scale, nullptr, nullptr, stream);
+      continue;
+    }
+    if (batch.n == kMaxBatch || (batch.n > 0 && (p->group_size != cur_gs || p->uniform_bits != cur_bits))) flush();
+    cur_log2 = log2;
+    cur_gs = p->group_size;
+    cur_bits = p->uniform_bits;
+    BatchEntry& e = batch.e[batch.n];
+    e.x = it.x;
+    e.bits = p->d_bits;
+    e.off = p->d_off;
+    e.words = it.out_words;
+    e.mn = it.out_min;
+    e.sc = it.out_scale;
+    e.tile_end = (batch.n ? batch.e[batch.n - 1].tile_end : 0) + n_tiles;
+    e.seed_lo = (uint32_t)it.seed;
+    e.seed_hi = (uint32_t)(it.seed >> 32);
+    ++batch.n;
+    const int64_t rest = p->num_groups - fast_groups;
+    if (rest > 0 && err == hipSuccess) {
+      int64_t blocks = (rest + kWavesPerBlock - 1) / kWavesPerBlock;
+      if (blocks > 65536) blocks = 65536;
+      hipLaunchKernelGGL((k_quantize_pack_group<DT, false, false>), dim3((unsigned)blocks), dim3(kThreads), 0, stream,
+                         it.x, p->n, p->group_size, fast_groups, p->num_groups, p->d_bits, p->d_off, p->uniform_bits,
+                         e.seed_lo, e.seed_hi, it.out_words, it.out_min, it.out_scale, nullptr, nullptr);
+      err = hipGetLastError();
+    }
+  }
+  flush();
+  return err;
+}
+
 }  // namespace
+
+hipError_t daf_launch_quantize_pack_batch(const daf_quantize_item_t* items, int32_t n_items, int dtype,
+                                          hipStream_t stream) {
+  switch (dtype) {
+    case daf::kF32:  return launch_items<daf::kF32>(items, n_items, stream);
+    case daf::kF16:  return launch_items<daf::kF16>(items, n_items, stream);
+    case daf::kBF16: return launch_items<daf::kBF16>(items, n_items, stream);
+    default: return hipErrorInvalidValue;
+  }
+}
 
 hipError_t daf_launch_group_minmax(const daf_plan_t* plan, const void* x, int dtype, float* out_min, float* out_max,
                                    hipStream_t stream) {

@@ -73,13 +73,13 @@ __global__ __launch_bounds__(kWave) void k_unpack_dequantize_tail(
 // widths the word address depends on two earlier loads, and a chunk-by-chunk loop would pay
 // that latency once per chunk.
 template <int DT, bool MIXED, bool RELU_BWD>
-__global__ __launch_bounds__(kThreads) void k_unpack_dequantize_chunk(
-    const uint32_t* __restrict__ words, const float* __restrict__ mn, const float* __restrict__ scale,
+__device__ __forceinline__ void unpack_dequantize_block(
+    int64_t block, const uint32_t* __restrict__ words, const float* __restrict__ mn, const float* __restrict__ scale,
     const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, int32_t uniform_bits,
     int64_t n_chunks, int32_t gs, int32_t gs_shift, u32x4* out, const u32x4* grad) {
   constexpr int kEpl = ElemTraits<DT>::kPerLoad;
   constexpr int K = kChunksPerThread;
-  const int64_t base = (int64_t)blockIdx.x * (kThreads * K) + threadIdx.x;
+  const int64_t base = block * (kThreads * K) + threadIdx.x;
 
   int64_t g[K];
   uint32_t b[K], woff[K], bitpos[K];
@@ -155,6 +155,44 @@ __global__ __launch_bounds__(kThreads) void k_unpack_dequantize_chunk(
   }
 }
 
+template <int DT, bool MIXED, bool RELU_BWD>
+__global__ __launch_bounds__(kThreads) void k_unpack_dequantize_chunk(
+    const uint32_t* __restrict__ words, const float* __restrict__ mn, const float* __restrict__ scale,
+    const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, int32_t uniform_bits,
+    int64_t n_chunks, int32_t gs, int32_t gs_shift, u32x4* out, const u32x4* grad) {
+  unpack_dequantize_block<DT, MIXED, RELU_BWD>((int64_t)blockIdx.x, words, mn, scale, bits, off, uniform_bits, n_chunks,
+                                               gs, gs_shift, out, grad);
+}
+
+// Several tensors in one launch: the blocks of all of them form one sequence and a block finds
+// its tensor by walking the cumulative block counts (descriptors travel as kernel arguments).
+constexpr int kMaxBatch = 32;
+struct BatchEntry {
+  const uint32_t* words;
+  const float* mn;
+  const float* scale;
+  const uint8_t* bits;
+  const uint32_t* off;
+  u32x4* out;
+  int64_t n_chunks;
+  int64_t block_end;                                // blocks of this and all earlier entries
+  int32_t uniform_bits, gs, gs_shift;
+};
+struct Batch {
+  BatchEntry e[kMaxBatch];
+  int32_t n;
+};
+
+template <int DT, bool MIXED>
+__global__ __launch_bounds__(kThreads) void k_unpack_dequantize_chunk_batch(const Batch batch) {
+  const int64_t gblock = blockIdx.x;
+  int t = 0;
+  while (t + 1 < batch.n && gblock >= batch.e[t].block_end) ++t;
+  const BatchEntry& e = batch.e[t];
+  unpack_dequantize_block<DT, MIXED, false>(gblock - (t ? batch.e[t - 1].block_end : 0), e.words, e.mn, e.scale, e.bits,
+                                            e.off, e.uniform_bits, e.n_chunks, e.gs, e.gs_shift, e.out, nullptr);
+}
+
 template <int DT, bool RELU_BWD>
 hipError_t launch_dtype(const daf_plan_t* p, const uint32_t* words, const float* mn, const float* scale,
                         const uint8_t* d_bits, void* out_x, const void* grad, hipStream_t stream) {
@@ -184,7 +222,77 @@ hipError_t launch_dtype(const daf_plan_t* p, const uint32_t* words, const float*
   return hipSuccess;
 }
 
+// Same results as one daf_launch_unpack_dequantize per item.  Consecutive items of the same
+// width kind (one width for all groups, or per-group widths) share a launch for their whole
+// chunks (at most kMaxBatch per launch); the few elements after an item's last whole chunk are
+// launched as before.
+template <int DT>
+hipError_t launch_items(const daf_dequantize_item_t* items, int32_t n_items, hipStream_t stream) {
+  constexpr int kEpl = ElemTraits<DT>::kPerLoad;
+  const int64_t per_block = (int64_t)kThreads * kChunksPerThread;
+  Batch batch;
+  batch.n = 0;
+  bool cur_mixed = false;
+  hipError_t err = hipSuccess;
+  auto flush = [&]() {
+    if (batch.n > 0 && err == hipSuccess) {
+      const unsigned blocks = (unsigned)batch.e[batch.n - 1].block_end;
+      if (cur_mixed)
+        hipLaunchKernelGGL((k_unpack_dequantize_chunk_batch<DT, true>), dim3(blocks), dim3(kThreads), 0, stream, batch);
+      else
+        hipLaunchKernelGGL((k_unpack_dequantize_chunk_batch<DT, false>), dim3(blocks), dim3(kThreads), 0, stream, batch);
+      err = hipGetLastError();
+    }
+    batch.n = 0;
+  };
+  for (int32_t i = 0; i < n_items && err == hipSuccess; ++i) {
+    const daf_dequantize_item_t& it = items[i];
+    const daf_plan_t* p = it.plan;
+    const uint8_t* d_bits = it.bits ? it.bits : p->d_bits;
+    const int64_t n_chunks = p->n / kEpl;
+    const bool mixed = p->uniform_bits == 0;
+    if (n_chunks > 0) {
+      const int64_t blocks = (n_chunks + per_block - 1) / per_block;
+      if (batch.n == kMaxBatch || (batch.n > 0 && mixed != cur_mixed) ||
+          (batch.n > 0 && batch.e[batch.n - 1].block_end + blocks > 0x7fffffff))
+        flush();
+      cur_mixed = mixed;
+      BatchEntry& e = batch.e[batch.n];
+      e.words = it.words;
+      e.mn = it.min;
+      e.scale = it.scale;
+      e.bits = mixed ? d_bits : nullptr;
+      e.off = mixed ? p->d_off : nullptr;
+      e.out = static_cast<u32x4*>(it.out_x);
+      e.n_chunks = n_chunks;
+      e.block_end = (batch.n ? batch.e[batch.n - 1].block_end : 0) + blocks;
+      e.uniform_bits = p->uniform_bits;
+      e.gs = p->group_size;
+      e.gs_shift = ((p->group_size & (p->group_size - 1)) == 0) ? __builtin_ctz((unsigned)p->group_size) : -1;
+      ++batch.n;
+    }
+    if (n_chunks * kEpl < p->n && err == hipSuccess) {
+      hipLaunchKernelGGL((k_unpack_dequantize_tail<DT, false>), dim3(1), dim3(kWave), 0, stream, it.words, it.min,
+                         it.scale, d_bits, p->d_off, p->uniform_bits, n_chunks * kEpl, p->n, p->group_size, it.out_x,
+                         nullptr);
+      err = hipGetLastError();
+    }
+  }
+  flush();
+  return err;
+}
+
 }  // namespace
+
+hipError_t daf_launch_unpack_dequantize_batch(const daf_dequantize_item_t* items, int32_t n_items, int dtype,
+                                              hipStream_t stream) {
+  switch (dtype) {
+    case daf::kF32:  return launch_items<daf::kF32>(items, n_items, stream);
+    case daf::kF16:  return launch_items<daf::kF16>(items, n_items, stream);
+    case daf::kBF16: return launch_items<daf::kBF16>(items, n_items, stream);
+    default: return hipErrorInvalidValue;
+  }
+}
 
 hipError_t daf_launch_unpack_dequantize(const daf_plan_t* plan, const uint32_t* words, const float* mn,
                                         const float* scale, const uint8_t* d_bits, void* out_x, int dtype,
