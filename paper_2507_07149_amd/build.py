@@ -17,8 +17,14 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libdaf.so")
-SOURCES = ["daf_api.hip", "plan_scan.hip", "quantize_pack.hip", "unpack_dequantize.hip", "minmax.hip",
-           "select_bits.hip", "unpack_matmul.hip", "page_store.cpp"]
+# (source, object name, extra flags): quantize_pack.hip is built once per element format
+SOURCES = [("quantize_pack.hip", "quantize_pack_f32", ["-DDAF_DT=0"]),
+           ("quantize_pack.hip", "quantize_pack_f16", ["-DDAF_DT=1"]),
+           ("quantize_pack.hip", "quantize_pack_bf16", ["-DDAF_DT=2"]),
+           ("daf_api.hip", "daf_api", []), ("quantize_dispatch.hip", "quantize_dispatch", []),
+           ("plan_scan.hip", "plan_scan", []), ("unpack_dequantize.hip", "unpack_dequantize", []),
+           ("minmax.hip", "minmax", []), ("select_bits.hip", "select_bits", []),
+           ("unpack_matmul.hip", "unpack_matmul", []), ("page_store.cpp", "page_store", [])]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-ffp-contract=off", "-fno-strict-aliasing",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall",
@@ -26,10 +32,11 @@ FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-ffp-contract=o
 HOST_FLAGS = ["-O2", "-std=c++17", "-fPIC", "-Wall", "-Wextra", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
 
 
-def _compile(src: str) -> str:
-    obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
+def _compile(item) -> str:
+    src, name, extra = item
+    obj = os.path.join(OBJ, name + ".o")
     flags = HOST_FLAGS if src.endswith(".cpp") else FLAGS        # .cpp = host-only code
-    r = subprocess.run([HIPCC, *flags, "-c", os.path.join(CSRC, src), "-o", obj],
+    r = subprocess.run([HIPCC, *flags, *extra, "-c", os.path.join(CSRC, src), "-o", obj],
                        stderr=subprocess.PIPE, text=True)
     # the host pass warns that it does not know the packed-fp32 target feature: harmless
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)

@@ -1130,41 +1130,31 @@ hipError_t launch_items(const daf_quantize_item_t* items, int32_t n_items, hipSt
 
 }  // namespace
 
-hipError_t daf_launch_quantize_pack_batch(const daf_quantize_item_t* items, int32_t n_items, int dtype,
-                                          hipStream_t stream) {
-  switch (dtype) {
-    case daf::kF32:  return launch_items<daf::kF32>(items, n_items, stream);
-    case daf::kF16:  return launch_items<daf::kF16>(items, n_items, stream);
-    case daf::kBF16: return launch_items<daf::kBF16>(items, n_items, stream);
-    default: return hipErrorInvalidValue;
-  }
+// This file is compiled once per element format (-DDAF_DT=0, 1, 2: the three builds run in
+// parallel and each holds a third of the kernel instantiations); quantize_dispatch.hip picks
+// the build by dtype.
+#ifndef DAF_DT
+#error "compile with -DDAF_DT=0 (binary32), 1 (binary16) or 2 (bfloat16)"
+#endif
+#define DAF_DT_NAME_(name, dt) name##_dt##dt
+#define DAF_DT_NAME(name, dt) DAF_DT_NAME_(name, dt)
+
+hipError_t DAF_DT_NAME(daf_launch_quantize_pack_batch, DAF_DT)(const daf_quantize_item_t* items, int32_t n_items,
+                                                               hipStream_t stream) {
+  return launch_items<DAF_DT>(items, n_items, stream);
 }
 
-hipError_t daf_launch_group_minmax(const daf_plan_t* plan, const void* x, int dtype, float* out_min, float* out_max,
-                                   hipStream_t stream) {
-  switch (dtype) {
-    case daf::kF32:  return launch_group_minmax<daf::kF32>(plan, x, out_min, out_max, stream);
-    case daf::kF16:  return launch_group_minmax<daf::kF16>(plan, x, out_min, out_max, stream);
-    case daf::kBF16: return launch_group_minmax<daf::kBF16>(plan, x, out_min, out_max, stream);
-    default: return hipErrorInvalidValue;
-  }
+hipError_t DAF_DT_NAME(daf_launch_group_minmax, DAF_DT)(const daf_plan_t* plan, const void* x, float* out_min,
+                                                        float* out_max, hipStream_t stream) {
+  return launch_group_minmax<DAF_DT>(plan, x, out_min, out_max, stream);
 }
 
-hipError_t daf_launch_quantize_pack(const daf_plan_t* plan, const void* x, int dtype, uint64_t seed,
-                                    uint32_t* out_words, float* out_min, float* out_scale, float* out_metrics,
-                                    void* out_relu_y, hipStream_t stream) {
-  float* m = out_metrics;
-  if (m && out_relu_y) return hipErrorNotSupported;
-#define DAF_DT(D)                                                                                         \
-  if (out_relu_y)                                                                                         \
-    return launch_dtype<D, false, true>(plan, x, seed, out_words, out_min, out_scale, nullptr, out_relu_y, stream); \
-  return m ? launch_dtype<D, true>(plan, x, seed, out_words, out_min, out_scale, m, nullptr, stream)      \
-           : launch_dtype<D, false>(plan, x, seed, out_words, out_min, out_scale, nullptr, nullptr, stream)
-  switch (dtype) {
-    case daf::kF32:  DAF_DT(daf::kF32);
-    case daf::kF16:  DAF_DT(daf::kF16);
-    case daf::kBF16: DAF_DT(daf::kBF16);
-    default: return hipErrorInvalidValue;
-  }
-#undef DAF_DT
+hipError_t DAF_DT_NAME(daf_launch_quantize_pack, DAF_DT)(const daf_plan_t* plan, const void* x, uint64_t seed,
+                                                         uint32_t* out_words, float* out_min, float* out_scale,
+                                                         float* out_metrics, void* out_relu_y, hipStream_t stream) {
+  if (out_metrics && out_relu_y) return hipErrorNotSupported;
+  if (out_relu_y)
+    return launch_dtype<DAF_DT, false, true>(plan, x, seed, out_words, out_min, out_scale, nullptr, out_relu_y, stream);
+  return out_metrics ? launch_dtype<DAF_DT, true>(plan, x, seed, out_words, out_min, out_scale, out_metrics, nullptr, stream)
+                     : launch_dtype<DAF_DT, false>(plan, x, seed, out_words, out_min, out_scale, nullptr, nullptr, stream);
 }
