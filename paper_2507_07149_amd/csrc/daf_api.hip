@@ -292,6 +292,7 @@ int daf_unpack_matmul_grad_weight(const daf_plan_t* plan, const uint32_t* words,
   if (dtype != DAF_F16 && dtype != DAF_BF16) return DAF_EUNSUPPORTED;
   const int64_t M = plan->n / K;
   if (!daf_unpack_matmul_shape_ok(M, N, K, plan->group_size)) return DAF_EUNSUPPORTED;
+  if (plan->total_words >= (int64_t)1 << 30) return DAF_EUNSUPPORTED;   // 32-bit byte offsets into the words
   if (daf_unpack_matmul_splits(M, N, K) > 1 && workspace == nullptr) return DAF_EINVAL;
   const uint8_t* d_bits = bits ? bits : plan->d_bits;
   const hipError_t e = daf_launch_unpack_matmul(plan, words, min, scale, d_bits, grad_y, N, K, (int)dtype, out_grad_w,

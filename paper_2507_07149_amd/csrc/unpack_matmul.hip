@@ -28,10 +28,23 @@ namespace {
 
 using namespace daf;
 
-constexpr int kBN = 256, kBK = 64, kBM = 32, kThreads = 256;
+constexpr int kBN = 256, kBM = 32, kThreads = 256;
 constexpr int kRowA = kBN * 2 + 64;                 // bytes per row of the grad_y tile in LDS (padded)
-constexpr int kRowB = kBK * 2 + 64;                 // bytes per row of the xhat tile in LDS (padded)
-constexpr int kBufBytes = kBM * (kRowA + kRowB);    // one copy of both tiles
+// The tile is BK = 64 or 128 columns of k wide (a template parameter of the kernel).
+template <int BK>
+struct TileB {
+  static constexpr int kRow = BK * 2 + 64;          // bytes per row of the xhat tile in LDS (padded)
+  static constexpr int kBufBytes = kBM * (kRowA + kRow);   // one copy of both tiles
+  static constexpr int kSegs = BK / 8;              // 8-column segments per row
+  static constexpr int kRowsPerPass = kThreads / kSegs;    // rows of x the threads cover at once
+  static constexpr int kPasses = kBM / kRowsPerPass;       // 1 (BK = 64) or 2 (BK = 128)
+  static constexpr int kJ = BK / 32;                // MFMA blocks along k per wave
+  // Per-group constants of a step (min, scale, width, word offset: 16 bytes per group) go
+  // through a ring in LDS: at most BK / 32 groups per row of the tile (groups have >= 32 elements).
+  static constexpr int kGroupsPerRow = BK / 32;
+  static constexpr int kMetaEntries = kBM * kGroupsPerRow;          // per step
+  static constexpr int kMetaRing = BK > 64 ? 8 : 5;                 // steps in the ring (5 is the minimum)
+};
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -60,18 +73,28 @@ __device__ __forceinline__ uint4 operand_tr(const char* p, int row_bytes) {
   return make_uint4(l2.x, l2.y, h2.x, h2.y);
 }
 
-// With per-group widths the address of a row's words depends on off[] and bits[] of its group:
-// those are fetched one step before the words are requested.
+// The width and word offset of the group of a thread's segment, read from the ring one step
+// before the words are requested.
+template <int P>
 struct Addr {
-  uint32_t b, off;
+  uint32_t b[P], off[P];
 };
 // Everything a thread needs to build its share of one step's LDS tiles: 4 rows x 8 columns of
-// grad_y, and the words, width, min and scale of 8 columns of one row of x.
+// grad_y, and the words and width of 8 columns of P rows of x.  Nothing here is computed from
+// loaded values when it is requested (that would make the requesting step wait for its own loads).
+template <int P>
 struct Stage {
   uint4 gy[4];
-  uint32_t w0, w1, b;                               // code c < 4 is in w0, c >= 4 in w1 (the same word below 8 bits)
-  float mn, sc;
+  uint32_t wa[P], wb[P], b[P];                      // the word of codes 0..3, the word of codes 4..7, the width
 };
+
+// A load from a block-uniform base plus a 32-bit per-thread byte offset: one address register
+// per load instead of a 64-bit pair and the 64-bit arithmetic that makes it.
+template <class T>
+__device__ __forceinline__ T load_at(const void* uniform_base, uint32_t byte_off) {
+  const char* base = static_cast<const char*>(uniform_base);
+  return *reinterpret_cast<const T*>(base + byte_off);
+}
 
 template <int I> struct Index { static constexpr int value = I; };
 template <int N, int I = 0, class F>
@@ -100,21 +123,25 @@ __device__ __forceinline__ uint32_t narrow16_pair(float lo, float hi) {
   }
 }
 
-template <int DT, bool MIXED>
+template <int DT, bool MIXED, int BK>
 __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
     const uint32_t* __restrict__ words, const float* __restrict__ mn, const float* __restrict__ scale,
     const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, uint32_t uniform_bits, int32_t gs,
-    const u32x4* __restrict__ grad_y, int64_t M, int64_t N, int64_t K, int32_t tiles_n, int32_t tiles_k,
-    int32_t splits, uint32_t total_words, float* __restrict__ out) {
+    const void* __restrict__ grad_y, int64_t M, int64_t N, int64_t K, int32_t tiles_n, int32_t tiles_k,
+    int32_t splits, float* __restrict__ out) {
+  using TB = TileB<BK>;
+  constexpr int kRowB = TB::kRow, kBufBytes = TB::kBufBytes, kP = TB::kPasses, kJ = TB::kJ;
   // Two copies of: the grad_y tile (kBM rows of kRowA bytes), then the xhat tile (kBM rows of
   // kRowB bytes).  While the products read one copy, the next step's tiles are written into the other.
   __shared__ __attribute__((aligned(16))) char lds[2][kBufBytes];
+  // Ring of per-group constants: slot (q mod kMetaRing) holds {min, scale, width, word offset}
+  // of the groups of step q, entry = row * kGroupsPerRow + (group - first group of the tile).
+  __shared__ uint4 meta[TB::kMetaRing][TB::kMetaEntries];
 
   const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
   // Consecutive block ids go to different XCDs (each with its own L2).  Give every XCD a
-  // contiguous range of the tile sequence, and order the sequence in bands of 4 tiles of n, k
-  // running inside a band: the ~32 tiles resident on an XCD then form a 4 x 8 patch that reads
-  // 4 panels of grad_y and 8 (small) panels of packed words per step instead of all 16 of grad_y.
+  // contiguous range of the tile sequence, k running fastest: the tiles resident on an XCD at
+  // one time then share one or two panels of grad_y (the large operand) in its L2.
   const uint32_t n_tiles = (uint32_t)tiles_n * (uint32_t)tiles_k;
   const uint32_t bid = blockIdx.x;
   const uint32_t split = bid / n_tiles;
@@ -124,72 +151,96 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
     const uint32_t base = n_tiles / 8u, rem = n_tiles & 7u;       // XCD x owns base (+1 if x < rem) tiles
     tile = xcd * base + (xcd < rem ? xcd : rem) + idx;
   }
-  constexpr uint32_t kBand = 1;
-  const uint32_t band = tile / (kBand * (uint32_t)tiles_k);
-  const uint32_t in_band = tile - band * (kBand * (uint32_t)tiles_k);
-  const uint32_t band_h = ((uint32_t)tiles_n - band * kBand) < kBand ? ((uint32_t)tiles_n - band * kBand) : kBand;
-  const uint32_t tn = band * kBand + in_band % band_h, tk = in_band / band_h;
-  const int64_t n0 = (int64_t)tn * kBN, k0 = (int64_t)tk * kBK;
+  const uint32_t tn = tile / (uint32_t)tiles_k, tk = tile - tn * (uint32_t)tiles_k;
+  const int64_t n0 = (int64_t)tn * kBN, k0 = (int64_t)tk * BK;
   const int64_t m_per_split = M / splits;
   const int64_t m_begin = (int64_t)split * m_per_split;
   const int steps = (int)(m_per_split / kBM);
 
   // Loader roles.  grad_y: thread (cg, rq) owns rows 4*rq .. 4*rq+3 of the step and columns
-  // 8*cg .. 8*cg+7 of the 256.  x: thread (co, xr) owns row xr and columns 8*co .. 8*co+7 of the
-  // 64: one load instruction each for its words, min, scale (and width, offset) per step.  Addresses are a block-uniform 64-bit base that advances by a
-  // constant per step, plus 32-bit per-thread offsets.
+  // 8*cg .. 8*cg+7 of the 256.  x: thread (co, xr) owns columns 8*co .. 8*co+7 of the BK in row
+  // xr (and, for BK = 128, row xr + 16).  Addresses are a block-uniform 64-bit base that
+  // advances by a constant per step, plus 32-bit per-thread byte offsets.
   const uint32_t cg = t & 31u, rq = t >> 5;
-  const uint32_t co = t & 7u, xr = t >> 3;
-  const uint32_t row_chunks = (uint32_t)(N / 8);                        // 16-byte chunks per grad_y row
+  const uint32_t co = t % (uint32_t)TB::kSegs, xr = t / (uint32_t)TB::kSegs;
+  const uint32_t row_bytes = (uint32_t)N * 2u;                          // bytes per grad_y row
   const uint32_t gpr = (uint32_t)(K / gs);                              // groups per row of x
   const uint32_t k_col = (uint32_t)k0 + 8u * co;
   const uint32_t gk = k_col / (uint32_t)gs;
   const uint32_t in_group = k_col - gk * (uint32_t)gs;                  // multiple of 8
   const uint32_t wpgb = (uint32_t)gs >> 5;                              // words per group and bit of width
-  const u32x4* gy_step = grad_y + m_begin * (int64_t)row_chunks + n0 / 8;   // uniform; + 32 rows per step
-  const uint32_t gy_off = (4u * rq) * row_chunks + cg;
+  const char* gy_base = reinterpret_cast<const char*>(grad_y) + (m_begin * (int64_t)row_bytes + n0 * 2);
+  const uint32_t gy_voff = (4u * rq) * row_bytes + 16u * cg;
   const int64_t g_step0 = m_begin * (int64_t)gpr;                        // uniform; + 32*gpr per step
-  const uint32_t g_off = xr * gpr + gk;
 
-  auto fetch_addr = [&](Addr& ad, int step) __attribute__((always_inline)) {
-    const int64_t g = g_step0 + (int64_t)step * (kBM * (int64_t)gpr) + g_off;
-    if (MIXED) {
-      ad.b = bits[g];
-      ad.off = off[g];
-    } else {
-      ad.b = uniform_bits;
-      ad.off = (uint32_t)g * (wpgb * uniform_bits);
+  // The per-group constants are fetched once per work-group and step, one group per thread
+  // (threads 0 .. 32 * kGroupsPerRow - 1: whole waves), six steps ahead, and handed to the
+  // threads that need them through the ring: four small loads per thread and step of its own
+  // would keep the memory pipeline busier than the tiles of grad_y do.
+  const uint32_t g_first = (uint32_t)k0 / (uint32_t)gs;
+  const uint32_t n_groups = ((uint32_t)k0 + (uint32_t)BK - 1u) / (uint32_t)gs - g_first + 1u;   // <= kGroupsPerRow
+  const bool meta_wave = t < (uint32_t)TB::kMetaEntries;
+  const uint32_t m_row = t / (uint32_t)TB::kGroupsPerRow, m_j = t % (uint32_t)TB::kGroupsPerRow;
+  const bool meta_lane = meta_wave && m_j < n_groups;
+  const uint32_t m_goff = m_row * gpr + g_first + m_j;                  // the loader's group, relative to the step's first
+  const uint32_t my_entry = xr * (uint32_t)TB::kGroupsPerRow + (gk - g_first);   // the consumer's entry (pass 0)
+
+  auto meta_load = [&](uint4& mv, int step) __attribute__((always_inline)) {
+    if (meta_lane) {
+      const int64_t gu = g_step0 + (int64_t)step * (kBM * (int64_t)gpr);
+      mv.x = __builtin_bit_cast(uint32_t, load_at<float>(mn + gu, 4u * m_goff));
+      mv.y = __builtin_bit_cast(uint32_t, load_at<float>(scale + gu, 4u * m_goff));
+      if (MIXED) {
+        mv.z = load_at<uint8_t>(bits + gu, m_goff);
+        mv.w = load_at<uint32_t>(off + gu, 4u * m_goff);
+      } else {
+        mv.z = uniform_bits;
+        mv.w = ((uint32_t)gu + m_goff) * (wpgb * uniform_bits);
+      }
     }
   };
-  auto fetch_stage = [&](Stage& f, const Addr& ad, int step) __attribute__((always_inline)) {
-    const u32x4* gp = gy_step + (int64_t)step * (kBM * (int64_t)row_chunks);
+  auto meta_store = [&](const uint4& mv, uint32_t slot) __attribute__((always_inline)) {
+    if (meta_lane) meta[slot][t] = mv;
+  };
+  const uint32_t g_voff = xr * gpr + gk;                                 // the thread's group, relative to the step's first
+  auto fetch_addr = [&](Addr<kP>& ad, uint32_t slot, int step) __attribute__((always_inline)) {
+#pragma unroll
+    for (int p = 0; p < kP; ++p) {
+      if (MIXED) {
+        const uint4* e = &meta[slot][my_entry + (uint32_t)(p * TB::kRowsPerPass * TB::kGroupsPerRow)];
+        const uint2 v = *reinterpret_cast<const uint2*>(reinterpret_cast<const char*>(e) + 8);
+        ad.b[p] = v.x;
+        ad.off[p] = v.y;
+      } else {                                      // one width: the offset follows from the group's index
+        const uint32_t g = (uint32_t)(g_step0 + (int64_t)step * (kBM * (int64_t)gpr)) + g_voff +
+                           (uint32_t)(p * TB::kRowsPerPass) * gpr;
+        ad.b[p] = uniform_bits;
+        ad.off[p] = g * (wpgb * uniform_bits);
+      }
+    }
+  };
+  auto fetch_stage = [&](Stage<kP>& f, const Addr<kP>& ad, int step) __attribute__((always_inline)) {
+    const char* gp = gy_base + (int64_t)step * (kBM * (int64_t)row_bytes);
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const u32x4 v = gp[gy_off + (uint32_t)r * row_chunks];
+      const u32x4 v = load_at<u32x4>(gp + (int64_t)r * row_bytes, gy_voff);
       f.gy[r] = make_uint4(v.x, v.y, v.z, v.w);
     }
-    // The 8 codes lie in two words (8 bits) or in one: one 8-byte load either way.  For a single
-    // word the load is the aligned pair that contains it (or, for the last word of a buffer with
-    // an odd number of words, the word before it and it).
-    const uint32_t wi = ad.off + ((in_group * ad.b) >> 5);
-    const bool two = ad.b == 8u;
-    const uint32_t ps = two ? wi : (((wi | 1u) < total_words) ? (wi & ~1u) : wi - 1u);
-    uint2 pair;
-    __builtin_memcpy(&pair, words + ps, 8);
-    const uint32_t one = (wi != ps) ? pair.y : pair.x;
-    f.w0 = two ? pair.x : one;
-    f.w1 = two ? pair.y : one;
-    f.b = ad.b;
-    const int64_t g = g_step0 + (int64_t)step * (kBM * (int64_t)gpr) + g_off;
-    f.mn = mn[g];
-    f.sc = scale[g];
+#pragma unroll
+    for (int p = 0; p < kP; ++p) {
+      // The 8 codes lie in one word, or (8 bits) in two: codes 0..3 in the first, 4..7 in the next.
+      const uint32_t wi = ad.off[p] + (__umul24(in_group, ad.b[p]) >> 5);   // (both factors are small)
+      f.wa[p] = load_at<uint32_t>(words, 4u * wi);
+      f.wb[p] = load_at<uint32_t>(words, 4u * (wi + (ad.b[p] >> 3)));
+      f.b[p] = ad.b[p];
+    }
   };
 
-  f32x16 acc[2][2];
+  f32x16 acc[2][kJ];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < kJ; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
@@ -200,109 +251,136 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
   // of its 32-column block; it receives column 16*(G%2) + l%16 = l%32 of the block.
   const uint32_t tr_row = 8u * lg + ((lane & 15u) >> 2), tr_col = 16u * ((lane >> 4) & 1u) + 4u * (lane & 3u);
   const uint32_t a_read = tr_row * (uint32_t)kRowA + (64u * wn + tr_col) * 2u;
-  const uint32_t b_read = (uint32_t)(kBM * kRowA) + tr_row * (uint32_t)kRowB + tr_col * 2u;
+  // In odd rows of the xhat tile the two 8-byte halves of every 16 bytes are exchanged: the
+  // writes of two neighbouring rows (one instruction) then fall on different banks.
+  const uint32_t b_read = (uint32_t)(kBM * kRowA) + tr_row * (uint32_t)kRowB + ((tr_col * 2u) ^ (8u * (tr_row & 1u)));
 
   // Half of the work of turning a stage into LDS tiles: two of the thread's four grad_y rows
-  // (copied as loaded) and one of its two rows of x.
+  // (copied as loaded) and half of each of its rows of x.
   const uint32_t a_store = (4u * rq) * (uint32_t)kRowA + 16u * cg;
-  const uint32_t b_store = (uint32_t)(kBM * kRowA) + xr * (uint32_t)kRowB + 16u * co;
-  auto build_half = [&](const Stage& cur, char* buf, int hs) __attribute__((always_inline)) {
+  const uint32_t b_store = (uint32_t)(kBM * kRowA) + xr * (uint32_t)kRowB + 16u * co + 8u * (xr & 1u);
+  auto build_half = [&](const Stage<kP>& cur, char* buf, int hs, uint32_t slot) __attribute__((always_inline)) {
 #pragma unroll
     for (int rr = 0; rr < 2; ++rr) {
       const int r = 2 * hs + rr;
       *reinterpret_cast<uint4*>(buf + a_store + (uint32_t)r * kRowA) = cur.gy[r];
     }
     // ---- xhat: unpack, dequantize, round to the element format; 4 columns = 8 bytes of the row ----
-    // Code c sits at bit s0 + (7-c)*b, s0 placing the 8 codes inside their word; for 8-bit codes
-    // (two words) the position is taken inside the word, mod 32.
-    {
-      const uint32_t b = cur.b;
-      const uint32_t s0 = (b == 8u) ? 0u : 32u - 8u * b - ((in_group * b) & 31u);
-      const uint32_t w = hs ? cur.w1 : cur.w0;
+    // Element j of a group has its lowest bit at bit -(j + 1) * b (mod 32) of its word; the
+    // bit-field extract takes its offset mod 32, which also covers the second word of 8-bit codes.
+#pragma unroll
+    for (int p = 0; p < kP; ++p) {
+      const uint32_t b = cur.b[p];
+      uint32_t w = hs ? cur.wb[p] : cur.wa[p];
+      // The word is taken here, after the barrier that ended the step before: moved up into
+      // that step, its unpacking would wait for the loads requested last.
+      asm volatile("" : "+v"(w));
+      const float2 ms = *reinterpret_cast<const float2*>(
+          &meta[slot][my_entry + (uint32_t)(p * TB::kRowsPerPass * TB::kGroupsPerRow)]);   // {min, scale}
+      uint32_t sh = 0u - __umul24(b, in_group + 4u * (uint32_t)hs + 1u);
       float v[4];
 #pragma unroll
       for (int cc = 0; cc < 4; ++cc) {
-        const int c = 4 * hs + cc;
-        const uint32_t code = __builtin_amdgcn_ubfe(w, (s0 + (uint32_t)(7 - c) * b) & 31u, b);
-        v[cc] = __builtin_fmaf((float)code, cur.sc, cur.mn);
+        const uint32_t code = __builtin_amdgcn_ubfe(w, sh, b);
+        sh -= b;
+        v[cc] = __builtin_fmaf((float)code, ms.y, ms.x);
       }
-      *reinterpret_cast<uint2*>(buf + b_store + 8u * (uint32_t)hs) =
+      *reinterpret_cast<uint2*>(buf + ((b_store + (uint32_t)(p * TB::kRowsPerPass * kRowB)) ^ (8u * (uint32_t)hs))) =
           make_uint2(narrow16_pair<DT>(v[0], v[1]), narrow16_pair<DT>(v[2], v[3]));
     }
   };
 
+  // Position in the ring of the step c steps after the one whose position is `at`.
+  constexpr uint32_t kRing = (uint32_t)TB::kMetaRing;
+  auto ring = [&](uint32_t at, uint32_t c) __attribute__((always_inline)) {
+    const uint32_t v = at + c;                      // at < kRing, c <= kRing
+    return v >= kRing ? v - kRing : v;
+  };
+
   // One step: run the products on copy BUF of the tiles while building the next step's tiles
   // (from `next`) in the other copy, then request the loads of the step after that into the
-  // registers just consumed.
-  auto do_step = [&](auto BUF, Stage& next, Addr& ad_use, Addr& ad_fill, int step) __attribute__((always_inline)) {
+  // registers just consumed.  `at` is the step's position in the ring of group constants.
+  uint4 mv;                                         // group constants on their way into the ring
+  auto do_step = [&](auto BUF, Stage<kP>& next, Addr<kP>& ad_use, Addr<kP>& ad_fill, int step, uint32_t& at)
+                     __attribute__((always_inline)) {
     constexpr int buf = decltype(BUF)::value;
-    // The group addresses of the step after the one requested below go first: when they are
-    // needed (one step from now) all of this step's other loads are younger and may stay in flight.
-    fetch_addr(ad_fill, min(step + 4, steps - 1));
+    // Group constants: those requested one step ago (of step + 5) go into the ring, those of
+    // step + 6 are requested; width and offset of step + 4 (stored one step ago) are read.
+    if (meta_wave) {
+      meta_store(mv, ring(at, 5));
+      meta_load(mv, min(step + 6, steps - 1));
+    }
+    fetch_addr(ad_fill, ring(at, 4), min(step + 4, steps - 1));
     const char* a_lds = lds[buf] + a_read;
     const char* b_lds = lds[buf] + b_read;
 #pragma unroll
     for (int ss = 0; ss < kBM / 16; ++ss) {
-      uint4 a[2], b[2];
+      uint4 a[2], b[kJ];
 #pragma unroll
       for (int i = 0; i < 2; ++i) a[i] = operand_tr(a_lds + ss * 16 * kRowA + i * 64, kRowA);
 #pragma unroll
-      for (int j = 0; j < 2; ++j) b[j] = operand_tr(b_lds + ss * 16 * kRowB + j * 64, kRowB);
+      for (int j = 0; j < kJ; ++j) b[j] = operand_tr(b_lds + ss * 16 * kRowB + j * 64, kRowB);
+      build_half(next, lds[buf ^ 1], ss, ring(at, 1));
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = mfma_32x32x16<DT>(a[i], b[j], acc[i][j]);
-      build_half(next, lds[buf ^ 1], ss);
+        for (int j = 0; j < kJ; ++j) acc[i][j] = mfma_32x32x16<DT>(a[i], b[j], acc[i][j]);
     }
     // Requested unconditionally (past the end the last step is requested again and never
     // used), so that the number of loads in flight is the same in every iteration.
     fetch_stage(next, ad_use, min(step + 3, steps - 1));
-    __syncthreads();                                // the other copy is complete, this one is free
+    __syncthreads();                                // the other copies are complete, this one is free
+    at = ring(at, 1);
   };
 
-  // Step q lives in stage q % 2 and LDS copy q % 2, its group addresses in ad[q % 2] (requested
-  // one step before its words).  Prologue: steps 0..2 requested (step 0 is consumed at once,
-  // step 2 takes its registers), addresses of step 3 requested, tiles of step 0 built.
-  Stage st[2];
-  Addr ad[2];
-  fetch_addr(ad[0], 0);
-  fetch_stage(st[0], ad[0], 0);
-  fetch_addr(ad[1], min(1, steps - 1));
-  fetch_stage(st[1], ad[1], min(1, steps - 1));
-  build_half(st[0], lds[0], 0);
-  build_half(st[0], lds[0], 1);
-  fetch_addr(ad[0], min(2, steps - 1));
-  fetch_stage(st[0], ad[0], min(2, steps - 1));
-  fetch_addr(ad[1], min(3, steps - 1));
+  // Step q lives in stage q % 2 and LDS copy q % 2, its width and offset in ad[q % 2] (read
+  // one step before its words are requested), its group constants in ring position q mod kRing.
+  // Prologue: group constants of steps 0..4 in the ring, those of step 5 requested; tiles of
+  // step 0 built; loads of steps 1 and 2 requested.
+  Stage<kP> st[2];
+  Addr<kP> ad[2];
+  if (meta_wave) {
+#pragma unroll
+    for (int q = 0; q < 5; ++q) {
+      uint4 m0 = make_uint4(0u, 0u, 0u, 0u);
+      meta_load(m0, min(q, steps - 1));
+      meta_store(m0, (uint32_t)q);
+    }
+    meta_load(mv, min(5, steps - 1));
+  }
   __syncthreads();
+  fetch_addr(ad[0], 0u, 0);
+  fetch_addr(ad[1], 1u, min(1, steps - 1));
+  fetch_stage(st[0], ad[0], 0);
+  fetch_addr(ad[0], 2u, min(2, steps - 1));
+  fetch_stage(st[1], ad[1], min(1, steps - 1));
+  build_half(st[0], lds[0], 0, 0u);
+  build_half(st[0], lds[0], 1, 0u);
+  fetch_addr(ad[1], 3u, min(3, steps - 1));
+  fetch_stage(st[0], ad[0], min(2, steps - 1));
+  // Every load has arrived before the loop is entered (once per work-group): the waits at the
+  // top of the loop must hold on this path too, and are then the ones its own iterations need.
+  __builtin_amdgcn_s_waitcnt(0x0F70);               // vmcnt(0)
+  __syncthreads();
+  __builtin_amdgcn_sched_barrier(0);
 
   // In iteration s: products on copy s % 2; tiles of step s+1 (stage (s+1) % 2) into the other
-  // copy; then loads of step s+3 into that same stage, with the addresses in ad[(s+1) % 2]
-  // (requested in iteration s-1); addresses of step s+4 into ad[s % 2].
-  // Several steps per trip of the main loop: at a loop header the compiler waits for every load
-  // in flight (it does not carry the order of the previous trip's loads across the back edge),
-  // so the fewer headers, the fewer full drains of the prefetch.
-  constexpr int kTrip = MIXED ? 2 : 8;              // (more would cost the mixed-width kernel a work-group per CU in registers)
+  // copy; then loads of step s+3 into that same stage, with the width and offset in
+  // ad[(s+1) % 2] (read in iteration s-1); width and offset of step s+4 into ad[s % 2].
+  uint32_t at = 0u;
   int base = 0;
-  for (; base + kTrip <= steps; base += kTrip) {
-#pragma unroll
-    for (int u = 0; u < kTrip; u += 2) {
-      do_step(Index<0>{}, st[1], ad[1], ad[0], base + u);
-      do_step(Index<1>{}, st[0], ad[0], ad[1], base + u + 1);
-    }
-  }
   for (; base + 2 <= steps; base += 2) {
-    do_step(Index<0>{}, st[1], ad[1], ad[0], base);
-    do_step(Index<1>{}, st[0], ad[0], ad[1], base + 1);
+    do_step(Index<0>{}, st[1], ad[1], ad[0], base, at);
+    do_step(Index<1>{}, st[0], ad[0], ad[1], base + 1, at);
   }
-  if (base < steps) do_step(Index<0>{}, st[1], ad[1], ad[0], base);
+  if (base < steps) do_step(Index<0>{}, st[1], ad[1], ad[0], base, at);
 
   // ---- epilogue: register r of a 32 x 32 block is row 8*(r/4) + 4*(lane/32) + r%4, column lane%32 ----
   float* dst = out + (int64_t)split * N * K;
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < kJ; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int64_t n = n0 + 64 * wn + 32 * i + 8 * (r >> 2) + 4 * lg + (r & 3);
@@ -326,18 +404,23 @@ __global__ __launch_bounds__(256) void k_sum_slabs(const float4* __restrict__ pa
 
 }  // namespace
 
+// Width of the tile along k: 128 when K allows it (half the reads of grad_y and half the LDS
+// traffic per product of the 64-wide tile), else 64.
+static int tile_bk(int64_t K) { return K % 128 == 0 ? 128 : 64; }
+
 // Number of slices of m that run as separate work-groups: 1 when the output alone has enough
 // tiles to fill the chip, otherwise a power of two (at most 16) that divides M / 64.
 int32_t daf_unpack_matmul_splits(int64_t M, int64_t N, int64_t K) {
-  const int64_t tiles = (N / kBN) * (K / kBK);
+  const int64_t tiles = (N / kBN) * (K / tile_bk(K));
   int32_t s = 1;
   while (s < 16 && tiles * s < 512 && (M / kBM) % (2 * s) == 0) s *= 2;
   return s;
 }
 
 bool daf_unpack_matmul_shape_ok(int64_t M, int64_t N, int64_t K, int32_t gs) {
-  return M > 0 && N > 0 && K > 0 && M % kBM == 0 && N % kBN == 0 && K % kBK == 0 && K % gs == 0 &&
-         (N / kBN) * (K / kBK) * 16 < (int64_t)1 << 31;
+  // N and K below 2^24: the per-thread parts of the addresses are 32-bit byte offsets.
+  return M > 0 && N > 0 && K > 0 && M % kBM == 0 && N % kBN == 0 && K % 64 == 0 && K % gs == 0 &&
+         N < (1 << 24) && K < (1 << 24) && (N / kBN) * (K / 64) * 16 < (int64_t)1 << 31;
 }
 
 hipError_t daf_launch_unpack_matmul(const daf_plan_t* p, const uint32_t* words, const float* mn, const float* scale,
@@ -345,21 +428,27 @@ hipError_t daf_launch_unpack_matmul(const daf_plan_t* p, const uint32_t* words, 
                                     float* out, float* workspace, hipStream_t stream) {
   const int64_t M = p->n / K;
   const int32_t splits = daf_unpack_matmul_splits(M, N, K);
-  const int32_t tiles_n = (int32_t)(N / kBN), tiles_k = (int32_t)(K / kBK);
+  const int bk = tile_bk(K);
+  const int32_t tiles_n = (int32_t)(N / kBN), tiles_k = (int32_t)(K / bk);
   const unsigned blocks = (unsigned)((int64_t)tiles_n * tiles_k * splits);
   float* target = splits > 1 ? workspace : out;
-  const u32x4* gy = static_cast<const u32x4*>(grad_y);
-#define DAF_LAUNCH(DT, MIXED)                                                                                     \
-  hipLaunchKernelGGL((k_unpack_matmul<DT, MIXED>), dim3(blocks), dim3(kThreads), 0, stream, words, mn, scale,     \
+  const void* gy = grad_y;
+#define DAF_LAUNCH(DT, MIXED, BK)                                                                                 \
+  hipLaunchKernelGGL((k_unpack_matmul<DT, MIXED, BK>), dim3(blocks), dim3(kThreads), 0, stream, words, mn, scale, \
                      d_bits, p->d_off, (uint32_t)p->uniform_bits, p->group_size, gy, M, N, K, tiles_n, tiles_k,   \
-                     splits, (uint32_t)p->total_words, target)
+                     splits, target)
+#define DAF_LAUNCH_BK(DT, MIXED)                                                                                  \
+  do {                                                                                                            \
+    if (bk == 128) DAF_LAUNCH(DT, MIXED, 128); else DAF_LAUNCH(DT, MIXED, 64);                                    \
+  } while (0)
   if (dtype == daf::kBF16) {
-    if (p->uniform_bits) DAF_LAUNCH(daf::kBF16, false); else DAF_LAUNCH(daf::kBF16, true);
+    if (p->uniform_bits) DAF_LAUNCH_BK(daf::kBF16, false); else DAF_LAUNCH_BK(daf::kBF16, true);
   } else if (dtype == daf::kF16) {
-    if (p->uniform_bits) DAF_LAUNCH(daf::kF16, false); else DAF_LAUNCH(daf::kF16, true);
+    if (p->uniform_bits) DAF_LAUNCH_BK(daf::kF16, false); else DAF_LAUNCH_BK(daf::kF16, true);
   } else {
     return hipErrorInvalidValue;
   }
+#undef DAF_LAUNCH_BK
 #undef DAF_LAUNCH
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || splits == 1) return e;

@@ -58,8 +58,10 @@ def test_grad_weight_small(env, dtype, bits, gs):
     _case(daf, orc, 128, 256, 256, gs, bits, dtype, 7)                 # two k-tiles, m split in two
 
 
+# K a multiple of 128 runs the 128-column tile, any other multiple of 64 the 64-column one.
 @pytest.mark.parametrize("shape", [(32, 256, 128), (64, 256, 128), (96, 256, 256), (192, 512, 384), (1024, 256, 128),
-                                   (2048, 512, 1024)])
+                                   (2048, 512, 1024), (32, 256, 64), (96, 256, 192), (160, 512, 320),
+                                   (1024, 256, 448)])
 @pytest.mark.parametrize("bits", [2, "mixed"])
 def test_grad_weight_shapes(env, shape, bits):
     daf, orc = env
@@ -99,14 +101,15 @@ def test_grad_weight_argument_errors(env):
 
 @pytest.mark.parametrize("dtype", [BF16, F16])
 @pytest.mark.parametrize("bits", [1, 2, 4, 8, "mixed"])
-def test_identity_gradient_returns_xhat_bit_for_bit(env, dtype, bits):
+@pytest.mark.parametrize("K", [384, 192])                                      # 128- and 64-column tiles
+def test_identity_gradient_returns_xhat_bit_for_bit(env, dtype, bits, K):
     """With grad_y = identity every output is a sum with exactly one non-zero term, so
     out[n, k] must equal xhat[n, k] exactly: the dequantization inside the product produces the
     same 16-bit patterns as the oracle's unpack_dequantize (tiny and huge scales included)."""
     daf, orc = env
     M = N = 256
-    K, gs = 384, 32
-    print("case identity", dtype, bits, flush=True)
+    gs = 32
+    print("case identity", dtype, bits, K, flush=True)
     g = torch.Generator().manual_seed(5)
     mag = torch.exp(torch.randn(M, K // gs, 1, generator=g) * 6.0)              # group scales over many octaves
     x = (torch.randn(M, K // gs, gs, generator=g) * mag).reshape(M, K).to(torch_dtype(dtype))
