@@ -185,9 +185,11 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
   const uint32_t m_goff = m_row * gpr + g_first + m_j;                  // the loader's group, relative to the step's first
   const uint32_t my_entry = xr * (uint32_t)TB::kGroupsPerRow + (gk - g_first);   // the consumer's entry (pass 0)
 
-  auto meta_load = [&](uint4& mv, int step) __attribute__((always_inline)) {
+  const int64_t g_stride = kBM * (int64_t)gpr;                           // groups per step
+  const int64_t gy_stride = kBM * (int64_t)row_bytes;                    // bytes of grad_y per step
+  // gu: index of the step's first group (uniform)
+  auto meta_load = [&](uint4& mv, int64_t gu) __attribute__((always_inline)) {
     if (meta_lane) {
-      const int64_t gu = g_step0 + (int64_t)step * (kBM * (int64_t)gpr);
       mv.x = __builtin_bit_cast(uint32_t, load_at<float>(mn + gu, 4u * m_goff));
       mv.y = __builtin_bit_cast(uint32_t, load_at<float>(scale + gu, 4u * m_goff));
       if (MIXED) {
@@ -219,8 +221,8 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
       }
     }
   };
-  auto fetch_stage = [&](Stage<kP>& f, const Addr<kP>& ad, int step) __attribute__((always_inline)) {
-    const char* gp = gy_base + (int64_t)step * (kBM * (int64_t)row_bytes);
+  // gp: the step's rows of grad_y, at the tile's first column (uniform)
+  auto fetch_stage = [&](Stage<kP>& f, const Addr<kP>& ad, const char* gp) __attribute__((always_inline)) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const u32x4 v = load_at<u32x4>(gp + (int64_t)r * row_bytes, gy_voff);
@@ -301,6 +303,8 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
   // (from `next`) in the other copy, then request the loads of the step after that into the
   // registers just consumed.  `at` is the step's position in the ring of group constants.
   uint4 mv;                                         // group constants on their way into the ring
+  const char* gy_next;                              // rows of grad_y of the step requested next
+  int64_t gu_meta;                                  // first group of the step whose constants are requested next
   auto do_step = [&](auto BUF, Stage<kP>& next, Addr<kP>& ad_use, Addr<kP>& ad_fill, int step, uint32_t& at)
                      __attribute__((always_inline)) {
     constexpr int buf = decltype(BUF)::value;
@@ -308,8 +312,9 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
     // step + 6 are requested; width and offset of step + 4 (stored one step ago) are read.
     if (meta_wave) {
       meta_store(mv, ring(at, 5));
-      meta_load(mv, min(step + 6, steps - 1));
+      meta_load(mv, gu_meta);
     }
+    if (step + 6 < steps - 1) gu_meta += g_stride;  // (past the end the last step's are requested again)
     fetch_addr(ad_fill, ring(at, 4), min(step + 4, steps - 1));
     const char* a_lds = lds[buf] + a_read;
     const char* b_lds = lds[buf] + b_read;
@@ -328,7 +333,8 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
     }
     // Requested unconditionally (past the end the last step is requested again and never
     // used), so that the number of loads in flight is the same in every iteration.
-    fetch_stage(next, ad_use, min(step + 3, steps - 1));
+    fetch_stage(next, ad_use, gy_next);
+    if (step + 3 < steps - 1) gy_next += gy_stride;
     __syncthreads();                                // the other copies are complete, this one is free
     at = ring(at, 1);
   };
@@ -343,21 +349,23 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
 #pragma unroll
     for (int q = 0; q < 5; ++q) {
       uint4 m0 = make_uint4(0u, 0u, 0u, 0u);
-      meta_load(m0, min(q, steps - 1));
+      meta_load(m0, g_step0 + (int64_t)min(q, steps - 1) * g_stride);
       meta_store(m0, (uint32_t)q);
     }
-    meta_load(mv, min(5, steps - 1));
+    meta_load(mv, g_step0 + (int64_t)min(5, steps - 1) * g_stride);
   }
+  gu_meta = g_step0 + (int64_t)min(6, steps - 1) * g_stride;
   __syncthreads();
   fetch_addr(ad[0], 0u, 0);
   fetch_addr(ad[1], 1u, min(1, steps - 1));
-  fetch_stage(st[0], ad[0], 0);
+  fetch_stage(st[0], ad[0], gy_base);
   fetch_addr(ad[0], 2u, min(2, steps - 1));
-  fetch_stage(st[1], ad[1], min(1, steps - 1));
+  fetch_stage(st[1], ad[1], gy_base + min(1, steps - 1) * gy_stride);
   build_half(st[0], lds[0], 0, 0u);
   build_half(st[0], lds[0], 1, 0u);
   fetch_addr(ad[1], 3u, min(3, steps - 1));
-  fetch_stage(st[0], ad[0], min(2, steps - 1));
+  fetch_stage(st[0], ad[0], gy_base + min(2, steps - 1) * gy_stride);
+  gy_next = gy_base + min(3, steps - 1) * gy_stride;
   // Every load has arrived before the loop is entered (once per work-group): the waits at the
   // top of the loop must hold on this path too, and are then the ones its own iterations need.
   __builtin_amdgcn_s_waitcnt(0x0F70);               // vmcnt(0)
@@ -408,13 +416,28 @@ __global__ __launch_bounds__(256) void k_sum_slabs(const float4* __restrict__ pa
 // traffic per product of the 64-wide tile), else 64.
 static int tile_bk(int64_t K) { return K % 128 == 0 ? 128 : 64; }
 
-// Number of slices of m that run as separate work-groups: 1 when the output alone has enough
-// tiles to fill the chip, otherwise a power of two (at most 16) that divides M / 64.
+// Number of slices of m that run as separate work-groups (a power of two, at most 16, that
+// divides the number of steps).  The work-groups run in rounds of as many as fit on the chip
+// (2 per CU with the 128-column tile, 3 with the 64-column one, 256 CUs); with s slices a
+// round takes 1/s of the time, and the partial sums (s * N * K floats, kept below 256 MiB)
+// are written once and read once more at about 4 TB/s.  The cheapest s by that estimate.
 int32_t daf_unpack_matmul_splits(int64_t M, int64_t N, int64_t K) {
   const int64_t tiles = (N / kBN) * (K / tile_bk(K));
-  int32_t s = 1;
-  while (s < 16 && tiles * s < 512 && (M / kBM) % (2 * s) == 0) s *= 2;
-  return s;
+  const int64_t slots = 256 * (tile_bk(K) == 128 ? 2 : 3);
+  const int64_t steps = M / kBM;
+  const double t_all_m = (double)steps * 1.4e-6;     // one work-group over all of m (measured per step)
+  const double out_bytes = (double)N * (double)K * 4.0;
+  int32_t best = 1;
+  double best_cost = (double)((tiles + slots - 1) / slots) * t_all_m;
+  for (int32_t s = 2; s <= 16 && steps % s == 0; s *= 2) {
+    if ((double)s * out_bytes > 256.0 * 1048576.0) break;
+    const double cost = (double)((tiles * s + slots - 1) / slots) * t_all_m / s + (s + 1) * out_bytes / 4.0e12;
+    if (cost < best_cost * 0.98) {                   // (a clear gain only)
+      best_cost = cost;
+      best = s;
+    }
+  }
+  return best;
 }
 
 bool daf_unpack_matmul_shape_ok(int64_t M, int64_t N, int64_t K, int32_t gs) {

@@ -55,7 +55,7 @@ def _case(daf, orc, M, N, K, gs, bits, dtype, seed):
 def test_grad_weight_small(env, dtype, bits, gs):
     daf, orc = env
     print("case small", dtype, bits, gs, flush=True)
-    _case(daf, orc, 128, 256, 256, gs, bits, dtype, 7)                 # two k-tiles, m split in two
+    _case(daf, orc, 128, 256, 256, gs, bits, dtype, 7)                 # two k-tiles, m in several slices
 
 
 # K a multiple of 128 runs the 128-column tile, any other multiple of 64 the 64-column one.
