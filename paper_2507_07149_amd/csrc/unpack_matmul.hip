@@ -90,6 +90,13 @@ struct Stage {
 
 // A load from a block-uniform base plus a 32-bit per-thread byte offset: one address register
 // per load instead of a 64-bit pair and the 64-bit arithmetic that makes it.
+// A loop-invariant offset is passed through opaque() inside the loop: otherwise its widening to
+// 64 bits is moved out of the loop and the scalar-base form of the load can no longer be chosen.
+__device__ __forceinline__ uint32_t opaque(uint32_t v) {
+  asm volatile("" : "+v"(v));
+  return v;
+}
+
 template <class T>
 __device__ __forceinline__ T load_at(const void* uniform_base, uint32_t byte_off) {
   const char* base = static_cast<const char*>(uniform_base);
@@ -190,11 +197,12 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
   // gu: index of the step's first group (uniform)
   auto meta_load = [&](uint4& mv, int64_t gu) __attribute__((always_inline)) {
     if (meta_lane) {
-      mv.x = __builtin_bit_cast(uint32_t, load_at<float>(mn + gu, 4u * m_goff));
-      mv.y = __builtin_bit_cast(uint32_t, load_at<float>(scale + gu, 4u * m_goff));
+      const uint32_t mo = opaque(m_goff), mo4 = 4u * mo;
+      mv.x = __builtin_bit_cast(uint32_t, load_at<float>(mn + gu, mo4));
+      mv.y = __builtin_bit_cast(uint32_t, load_at<float>(scale + gu, mo4));
       if (MIXED) {
-        mv.z = load_at<uint8_t>(bits + gu, m_goff);
-        mv.w = load_at<uint32_t>(off + gu, 4u * m_goff);
+        mv.z = load_at<uint8_t>(bits + gu, mo);
+        mv.w = load_at<uint32_t>(off + gu, mo4);
       } else {
         mv.z = uniform_bits;
         mv.w = ((uint32_t)gu + m_goff) * (wpgb * uniform_bits);
@@ -225,7 +233,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
   auto fetch_stage = [&](Stage<kP>& f, const Addr<kP>& ad, const char* gp) __attribute__((always_inline)) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const u32x4 v = load_at<u32x4>(gp + (int64_t)r * row_bytes, gy_voff);
+      const u32x4 v = load_at<u32x4>(gp + (int64_t)r * row_bytes, opaque(gy_voff));   // (per load: else rows 1..3 get vector addresses)
       f.gy[r] = make_uint4(v.x, v.y, v.z, v.w);
     }
 #pragma unroll
@@ -279,7 +287,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
       asm volatile("" : "+v"(w));
       const float2 ms = *reinterpret_cast<const float2*>(
           &meta[slot][my_entry + (uint32_t)(p * TB::kRowsPerPass * TB::kGroupsPerRow)]);   // {min, scale}
-      uint32_t sh = 0u - __umul24(b, in_group + 4u * (uint32_t)hs + 1u);
+      uint32_t sh = (uint32_t)__mul24((int)b, -(int)(in_group + 4u * (uint32_t)hs + 1u));
       float v[4];
 #pragma unroll
       for (int cc = 0; cc < 4; ++cc) {
@@ -296,6 +304,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
   constexpr uint32_t kRing = (uint32_t)TB::kMetaRing;
   auto ring = [&](uint32_t at, uint32_t c) __attribute__((always_inline)) {
     const uint32_t v = at + c;                      // at < kRing, c <= kRing
+    if constexpr ((kRing & (kRing - 1u)) == 0u) return v & (kRing - 1u);
     return v >= kRing ? v - kRing : v;
   };
 
