@@ -28,17 +28,22 @@ namespace {
 
 using namespace daf;
 
-constexpr int kBN = 256, kBM = 32, kThreads = 256;
+constexpr int kBN = 256, kBM = 32;
 constexpr int kRowA = kBN * 2 + 64;                 // bytes per row of the grad_y tile in LDS (padded)
-// The tile is BK = 64 or 128 columns of k wide (a template parameter of the kernel).
+// The tile is BK = 64, 128 or 256 columns of k wide (a template parameter of the kernel).  Four
+// waves side by side along n, each with all the columns of k up to 128; the 256-column tile
+// has a second row of four waves for columns 128..255.
 template <int BK>
 struct TileB {
+  static constexpr int kThreads = BK > 128 ? 512 : 256;
+  static constexpr int kWaveK = BK > 128 ? 128 : BK;        // columns of k per wave
   static constexpr int kRow = BK * 2 + 64;          // bytes per row of the xhat tile in LDS (padded)
   static constexpr int kBufBytes = kBM * (kRowA + kRow);   // one copy of both tiles
+  static constexpr int kGyRows = kBM / (kThreads / 32);    // rows of the grad_y tile per thread: 4 or 2
   static constexpr int kSegs = BK / 8;              // 8-column segments per row
   static constexpr int kRowsPerPass = kThreads / kSegs;    // rows of x the threads cover at once
-  static constexpr int kPasses = kBM / kRowsPerPass;       // 1 (BK = 64) or 2 (BK = 128)
-  static constexpr int kJ = BK / 32;                // MFMA blocks along k per wave
+  static constexpr int kPasses = kBM / kRowsPerPass;       // 1 (BK = 64) or 2
+  static constexpr int kJ = kWaveK / 32;            // MFMA blocks along k per wave
   // Per-group constants of a step (min, scale, width, word offset: 16 bytes per group) go
   // through a ring in LDS: at most BK / 32 groups per row of the tile (groups have >= 32 elements).
   static constexpr int kGroupsPerRow = BK / 32;
@@ -82,9 +87,9 @@ struct Addr {
 // Everything a thread needs to build its share of one step's LDS tiles: 4 rows x 8 columns of
 // grad_y, and the words and width of 8 columns of P rows of x.  Nothing here is computed from
 // loaded values when it is requested (that would make the requesting step wait for its own loads).
-template <int P>
+template <int P, int R>
 struct Stage {
-  uint4 gy[4];
+  uint4 gy[R];
   uint32_t wa[P], wb[P], b[P];                      // the word of codes 0..3, the word of codes 4..7, the width
 };
 
@@ -131,13 +136,13 @@ __device__ __forceinline__ uint32_t narrow16_pair(float lo, float hi) {
 }
 
 template <int DT, bool MIXED, int BK>
-__global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
+__global__ __launch_bounds__(TileB<BK>::kThreads, BK > 128 ? 1 : 2) void k_unpack_matmul(
     const uint32_t* __restrict__ words, const float* __restrict__ mn, const float* __restrict__ scale,
     const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, uint32_t uniform_bits, int32_t gs,
     const void* __restrict__ grad_y, int64_t M, int64_t N, int64_t K, int32_t tiles_n, int32_t tiles_k,
     int32_t splits, float* __restrict__ out) {
   using TB = TileB<BK>;
-  constexpr int kRowB = TB::kRow, kBufBytes = TB::kBufBytes, kP = TB::kPasses, kJ = TB::kJ;
+  constexpr int kRowB = TB::kRow, kBufBytes = TB::kBufBytes, kP = TB::kPasses, kJ = TB::kJ, kR = TB::kGyRows;
   // Two copies of: the grad_y tile (kBM rows of kRowA bytes), then the xhat tile (kBM rows of
   // kRowB bytes).  While the products read one copy, the next step's tiles are written into the other.
   __shared__ __attribute__((aligned(16))) char lds[2][kBufBytes];
@@ -164,7 +169,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
   const int64_t m_begin = (int64_t)split * m_per_split;
   const int steps = (int)(m_per_split / kBM);
 
-  // Loader roles.  grad_y: thread (cg, rq) owns rows 4*rq .. 4*rq+3 of the step and columns
+  // Loader roles.  grad_y: thread (cg, rq) owns rows kR*rq .. kR*rq+kR-1 of the step and columns
   // 8*cg .. 8*cg+7 of the 256.  x: thread (co, xr) owns columns 8*co .. 8*co+7 of the BK in row
   // xr (and, for BK = 128, row xr + 16).  Addresses are a block-uniform 64-bit base that
   // advances by a constant per step, plus 32-bit per-thread byte offsets.
@@ -177,7 +182,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
   const uint32_t in_group = k_col - gk * (uint32_t)gs;                  // multiple of 8
   const uint32_t wpgb = (uint32_t)gs >> 5;                              // words per group and bit of width
   const char* gy_base = reinterpret_cast<const char*>(grad_y) + (m_begin * (int64_t)row_bytes + n0 * 2);
-  const uint32_t gy_voff = (4u * rq) * row_bytes + 16u * cg;
+  const uint32_t gy_voff = ((uint32_t)kR * rq) * row_bytes + 16u * cg;
   const int64_t g_step0 = m_begin * (int64_t)gpr;                        // uniform; + 32*gpr per step
 
   // The per-group constants are fetched once per work-group and step, one group per thread
@@ -230,9 +235,9 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
     }
   };
   // gp: the step's rows of grad_y, at the tile's first column (uniform)
-  auto fetch_stage = [&](Stage<kP>& f, const Addr<kP>& ad, const char* gp) __attribute__((always_inline)) {
+  auto fetch_stage = [&](Stage<kP, kR>& f, const Addr<kP>& ad, const char* gp) __attribute__((always_inline)) {
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
+    for (int r = 0; r < kR; ++r) {
       const u32x4 v = load_at<u32x4>(gp + (int64_t)r * row_bytes, opaque(gy_voff));   // (per load: else rows 1..3 get vector addresses)
       f.gy[r] = make_uint4(v.x, v.y, v.z, v.w);
     }
@@ -254,7 +259,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-  const uint32_t wn = wave;
+  const uint32_t wn = wave & 3u, wk = wave >> 2;    // (wk = 0 except for the 256-column tile)
   const uint32_t li = lane & 31u, lg = lane >> 5;
   // Operand reads: lane l of 16-lane group G = l / 16 addresses row 8*(l/32) + (l%16)/4 (plus 16 per
   // sub-step, plus 4 for the second half of the operand) and the 4 columns 16*(G%2) + 4*(l%4) ..
@@ -263,16 +268,17 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
   const uint32_t a_read = tr_row * (uint32_t)kRowA + (64u * wn + tr_col) * 2u;
   // In odd rows of the xhat tile the two 8-byte halves of every 16 bytes are exchanged: the
   // writes of two neighbouring rows (one instruction) then fall on different banks.
-  const uint32_t b_read = (uint32_t)(kBM * kRowA) + tr_row * (uint32_t)kRowB + ((tr_col * 2u) ^ (8u * (tr_row & 1u)));
+  const uint32_t b_read = (uint32_t)(kBM * kRowA) + tr_row * (uint32_t)kRowB + wk * (uint32_t)(TB::kWaveK * 2) +
+                          ((tr_col * 2u) ^ (8u * (tr_row & 1u)));
 
   // Half of the work of turning a stage into LDS tiles: two of the thread's four grad_y rows
   // (copied as loaded) and half of each of its rows of x.
-  const uint32_t a_store = (4u * rq) * (uint32_t)kRowA + 16u * cg;
+  const uint32_t a_store = ((uint32_t)kR * rq) * (uint32_t)kRowA + 16u * cg;
   const uint32_t b_store = (uint32_t)(kBM * kRowA) + xr * (uint32_t)kRowB + 16u * co + 8u * (xr & 1u);
-  auto build_half = [&](const Stage<kP>& cur, char* buf, int hs, uint32_t slot) __attribute__((always_inline)) {
+  auto build_half = [&](const Stage<kP, kR>& cur, char* buf, int hs, uint32_t slot) __attribute__((always_inline)) {
 #pragma unroll
-    for (int rr = 0; rr < 2; ++rr) {
-      const int r = 2 * hs + rr;
+    for (int rr = 0; rr < kR / 2; ++rr) {
+      const int r = (kR / 2) * hs + rr;
       *reinterpret_cast<uint4*>(buf + a_store + (uint32_t)r * kRowA) = cur.gy[r];
     }
     // ---- xhat: unpack, dequantize, round to the element format; 4 columns = 8 bytes of the row ----
@@ -314,7 +320,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
   uint4 mv;                                         // group constants on their way into the ring
   const char* gy_next;                              // rows of grad_y of the step requested next
   int64_t gu_meta;                                  // first group of the step whose constants are requested next
-  auto do_step = [&](auto BUF, Stage<kP>& next, Addr<kP>& ad_use, Addr<kP>& ad_fill, int step, uint32_t& at)
+  auto do_step = [&](auto BUF, Stage<kP, kR>& next, Addr<kP>& ad_use, Addr<kP>& ad_fill, int step, uint32_t& at)
                      __attribute__((always_inline)) {
     constexpr int buf = decltype(BUF)::value;
     // Group constants: those requested one step ago (of step + 5) go into the ring, those of
@@ -352,7 +358,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
   // one step before its words are requested), its group constants in ring position q mod kRing.
   // Prologue: group constants of steps 0..4 in the ring, those of step 5 requested; tiles of
   // step 0 built; loads of steps 1 and 2 requested.
-  Stage<kP> st[2];
+  Stage<kP, kR> st[2];
   Addr<kP> ad[2];
   if (meta_wave) {
 #pragma unroll
@@ -401,7 +407,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_unpack_matmul(
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int64_t n = n0 + 64 * wn + 32 * i + 8 * (r >> 2) + 4 * lg + (r & 3);
-        const int64_t k = k0 + 32 * j + li;
+        const int64_t k = k0 + TB::kWaveK * wk + 32 * j + li;
         dst[n * K + k] = acc[i][j][r];
       }
 }
@@ -421,18 +427,23 @@ __global__ __launch_bounds__(256) void k_sum_slabs(const float4* __restrict__ pa
 
 }  // namespace
 
-// Width of the tile along k: 128 when K allows it (half the reads of grad_y and half the LDS
-// traffic per product of the 64-wide tile), else 64.
-static int tile_bk(int64_t K) { return K % 128 == 0 ? 128 : 64; }
+// Width of the tile along k.  Each doubling halves the number of times a row of grad_y is
+// fetched; the 256-column tile (8 waves, one work-group per CU) is used when the output has
+// enough of them to fill the chip without slicing m, else the 128-column one (measured: LLM
+// shape 780 -> 860 TFLOP/s with 256 columns, ViT shape 0.30 against 0.29 ms).
+static int tile_bk(int64_t N, int64_t K) {
+  if (K % 256 == 0 && (N / kBN) * (K / 256) >= 256) return 256;
+  return K % 128 == 0 ? 128 : 64;
+}
 
 // Number of slices of m that run as separate work-groups (a power of two, at most 16, that
 // divides the number of steps).  The work-groups run in rounds of as many as fit on the chip
-// (2 per CU with the 128-column tile, 3 with the 64-column one, 256 CUs); with s slices a
+// (1 per CU with the 256-column tile, 2 with the 128-column one, 3 with the 64-column one, 256 CUs); with s slices a
 // round takes 1/s of the time, and the partial sums (s * N * K floats, kept below 256 MiB)
 // are written once and read once more at about 4 TB/s.  The cheapest s by that estimate.
 int32_t daf_unpack_matmul_splits(int64_t M, int64_t N, int64_t K) {
-  const int64_t tiles = (N / kBN) * (K / tile_bk(K));
-  const int64_t slots = 256 * (tile_bk(K) == 128 ? 2 : 3);
+  const int64_t tiles = (N / kBN) * (K / tile_bk(N, K));
+  const int64_t slots = 256 * (tile_bk(N, K) == 256 ? 1 : tile_bk(N, K) == 128 ? 2 : 3);
   const int64_t steps = M / kBM;
   const double t_all_m = (double)steps * 1.4e-6;     // one work-group over all of m (measured per step)
   const double out_bytes = (double)N * (double)K * 4.0;
@@ -460,18 +471,21 @@ hipError_t daf_launch_unpack_matmul(const daf_plan_t* p, const uint32_t* words, 
                                     float* out, float* workspace, hipStream_t stream) {
   const int64_t M = p->n / K;
   const int32_t splits = daf_unpack_matmul_splits(M, N, K);
-  const int bk = tile_bk(K);
+  const int bk = tile_bk(N, K);
   const int32_t tiles_n = (int32_t)(N / kBN), tiles_k = (int32_t)(K / bk);
   const unsigned blocks = (unsigned)((int64_t)tiles_n * tiles_k * splits);
   float* target = splits > 1 ? workspace : out;
   const void* gy = grad_y;
 #define DAF_LAUNCH(DT, MIXED, BK)                                                                                 \
-  hipLaunchKernelGGL((k_unpack_matmul<DT, MIXED, BK>), dim3(blocks), dim3(kThreads), 0, stream, words, mn, scale, \
+  hipLaunchKernelGGL((k_unpack_matmul<DT, MIXED, BK>), dim3(blocks), dim3(TileB<BK>::kThreads), 0, stream, words,    \
+                     mn, scale,                                                                                   \
                      d_bits, p->d_off, (uint32_t)p->uniform_bits, p->group_size, gy, M, N, K, tiles_n, tiles_k,   \
                      splits, target)
 #define DAF_LAUNCH_BK(DT, MIXED)                                                                                  \
   do {                                                                                                            \
-    if (bk == 128) DAF_LAUNCH(DT, MIXED, 128); else DAF_LAUNCH(DT, MIXED, 64);                                    \
+    if (bk == 256) DAF_LAUNCH(DT, MIXED, 256);                                                                    \
+    else if (bk == 128) DAF_LAUNCH(DT, MIXED, 128);                                                               \
+    else DAF_LAUNCH(DT, MIXED, 64);                                                                               \
   } while (0)
   if (dtype == daf::kBF16) {
     if (p->uniform_bits) DAF_LAUNCH_BK(daf::kBF16, false); else DAF_LAUNCH_BK(daf::kBF16, true);

@@ -77,6 +77,18 @@ def test_grad_weight_without_split_needs_no_workspace(env):
     assert ws == 0
 
 
+# 256 or more 256 x 256 tiles: the 256-column tile (8 waves per work-group)
+@pytest.mark.parametrize("case", [(32, 4096, 4096, 64, "mixed", BF16), (96, 4096, 4096, 128, "mixed", F16),
+                                  (64, 8192, 2048, 32, "mixed", BF16), (64, 2048, 8192, 256, 8, F16),
+                                  (32, 4096, 4096, 64, 1, BF16)])
+def test_grad_weight_wide_tile(env, case):
+    daf, orc = env
+    M, N, K, gs, bits, dtype = case
+    print("case wide tile", case, flush=True)
+    ws = _case(daf, orc, M, N, K, gs, bits, dtype, 13)
+    assert ws == 0
+
+
 def test_grad_weight_argument_errors(env):
     daf, _ = env
     plan = daf.daf_plan((128, 256), 64, 2)
@@ -103,13 +115,22 @@ def test_grad_weight_argument_errors(env):
 @pytest.mark.parametrize("bits", [1, 2, 4, 8, "mixed"])
 @pytest.mark.parametrize("K", [384, 192])                                      # 128- and 64-column tiles
 def test_identity_gradient_returns_xhat_bit_for_bit(env, dtype, bits, K):
+    _identity_case(env, dtype, bits, 256, K)
+
+
+@pytest.mark.parametrize("dtype,bits", [(BF16, "mixed"), (F16, "mixed"), (BF16, 8), (F16, 2)])
+def test_identity_gradient_wide_tile(env, dtype, bits):
+    _identity_case(env, dtype, bits, 4096, 4096)                               # 256 tiles of 256 x 256
+
+
+def _identity_case(env, dtype, bits, M, K):
     """With grad_y = identity every output is a sum with exactly one non-zero term, so
     out[n, k] must equal xhat[n, k] exactly: the dequantization inside the product produces the
     same 16-bit patterns as the oracle's unpack_dequantize (tiny and huge scales included)."""
     daf, orc = env
-    M = N = 256
+    N = M
     gs = 32
-    print("case identity", dtype, bits, K, flush=True)
+    print("case identity", dtype, bits, M, K, flush=True)
     g = torch.Generator().manual_seed(5)
     mag = torch.exp(torch.randn(M, K // gs, 1, generator=g) * 6.0)              # group scales over many octaves
     x = (torch.randn(M, K // gs, gs, generator=g) * mag).reshape(M, K).to(torch_dtype(dtype))
