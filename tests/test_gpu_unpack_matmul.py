@@ -154,3 +154,81 @@ def _identity_case(env, dtype, bits, M, K):
     assert finite.all()
     assert np.array_equal((got + np.float32(0)).view(np.uint32), (want + np.float32(0)).view(np.uint32))
     plan.destroy()
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("cfg,N", [(5, 4096), (3, 3072)])
+def test_grad_weight_at_benchmark_size_sampled(env, cfg, N):
+    """The shapes bench.py --fused-matmul times (the LLM MLP activation with per-group widths
+    {2,4,8} on the 256-column tile; the ViT activation with {1,2,4,8}, m in slices): sampled
+    outputs against the oracle, which quantizes and dequantizes only the groups those outputs
+    read, one group at a time; and every output against the plain dequantize kernel's xhat
+    multiplied by the library in binary32 (a property that holds at any size)."""
+    from daf_inputs import make_config
+    daf, orc = env
+    (w,) = make_config(cfg)
+    K = w.x.shape[-1]
+    M = w.numel // K
+    gs, dtype = w.group_size, w.dtype
+    gpr = K // gs
+    print("case benchmark size", w.name, M, N, K, flush=True)
+    g = torch.Generator().manual_seed(100 + cfg)
+    gy = (torch.randn(M, N, generator=g) * 0.5).to(torch_dtype(dtype))
+
+    dev = "cuda:0"
+    x = w.x.reshape(-1).to(dev)
+    dbits = torch.from_numpy(w.bits).to(dev)
+    plan = daf.daf_plan((M, K), gs, dbits)
+    words = torch.empty(plan.packed_words, dtype=torch.int32, device=dev)
+    mn = torch.empty(plan.num_groups, device=dev)
+    sc = torch.empty(plan.num_groups, device=dev)
+    daf.daf_quantize_pack(plan, x, w.seed, words, mn, sc)
+    ws = torch.empty(max(daf.daf_unpack_matmul_workspace_bytes(plan, N, K), 16), dtype=torch.uint8, device=dev)
+    out = torch.full((N, K), float("nan"), device=dev)
+    gyd = gy.to(dev)
+    daf.daf_unpack_matmul_grad_weight(plan, words, mn, sc, gyd, out, ws)
+    torch.cuda.synchronize()
+    print("ran; oracle on sampled columns", flush=True)
+
+    # ---- sampled outputs: 6 group columns (first, last, 4 random), all their k, 8 values of n ----
+    rng = np.random.default_rng(cfg)
+    gcols = np.unique(np.concatenate([[0, gpr - 1], rng.integers(0, gpr, 4)]))
+    ns = np.unique(np.concatenate([[0, N - 1], rng.integers(0, N, 6)]))
+    xb = to_numpy_bits(w.x).reshape(-1)
+    off, total = orc.plan(w.numel, gs, w.bits)
+    ow = np.zeros(total, dtype=np.uint32)
+    omn = np.zeros(plan.num_groups, dtype=np.float32)
+    osc = np.zeros(plan.num_groups, dtype=np.float32)
+    oxh = np.zeros(w.numel, dtype=xb.dtype)
+    for gc in gcols:
+        for m in range(M):
+            gi = m * gpr + int(gc)
+            orc.quantize_pack_range(xb, dtype, gs, w.bits, off, w.seed, gi, gi + 1, ow, omn, osc)
+            orc.unpack_dequantize_range(ow, omn, osc, w.bits, off, w.numel, gs, gi, gi + 1, oxh, dtype)
+    gy64 = orc.widen(to_numpy_bits(gy), dtype).reshape(M, N)[:, ns].astype(np.float64)         # [M, ns]
+    got = out.cpu().numpy()
+    for gc in gcols:
+        ks = np.arange(int(gc) * gs, (int(gc) + 1) * gs)
+        xh64 = orc.widen(oxh, dtype).reshape(M, K)[:, ks].astype(np.float64)                     # [M, gs]
+        want = gy64.T @ xh64                                                                      # [ns, gs]
+        mag = np.abs(gy64).T @ np.abs(xh64)
+        err = np.abs(got[np.ix_(ns, ks)].astype(np.float64) - want)
+        bound = 2.0 * M * 2.0 ** -24 * mag + 1e-30
+        assert np.all(err <= bound), f"group column {gc}: worst {err.max():.3e}, bound there {bound.flat[err.argmax()]:.3e}"
+    print("sampled outputs agree; every output against dequantize + binary32 product", flush=True)
+
+    # ---- every output: the fused kernel against xhat from the plain kernel times grad_y ----
+    xh = torch.empty_like(x)
+    daf.daf_unpack_dequantize(plan, words, mn, sc, xh)
+    ref = torch.zeros(N, K, device=dev)
+    mag = torch.zeros(N, K, device=dev)
+    step = 4096
+    for m0 in range(0, M, step):                       # slabs of m keep the binary32 copies small
+        a = gyd[m0:m0 + step].float()
+        b = xh.view(M, K)[m0:m0 + step].float()
+        ref += a.t() @ b
+        mag += a.abs().t() @ b.abs()
+    torch.cuda.synchronize()
+    # both sides add M products in binary32 in their own order
+    assert bool(((out - ref).abs() <= 4.0 * M * 2.0 ** -24 * mag + 1e-30).all())
+    plan.destroy()
