@@ -274,8 +274,7 @@ int64_t daf_unpack_matmul_workspace_bytes(const daf_plan_t* plan, int64_t N, int
   if (plan == nullptr || N <= 0 || K <= 0 || plan->n % K != 0) return -1;
   const int64_t M = plan->n / K;
   if (!daf_unpack_matmul_shape_ok(M, N, K, plan->group_size)) return -1;
-  const int32_t splits = daf_unpack_matmul_splits(M, N, K);
-  return splits > 1 ? (int64_t)splits * N * K * 4 : 0;
+  return daf_unpack_matmul_workspace_size(M, N, K);
 }
 
 int daf_unpack_matmul_grad_weight(const daf_plan_t* plan, const uint32_t* words, const float* min, const float* scale,
@@ -293,7 +292,7 @@ int daf_unpack_matmul_grad_weight(const daf_plan_t* plan, const uint32_t* words,
   const int64_t M = plan->n / K;
   if (!daf_unpack_matmul_shape_ok(M, N, K, plan->group_size)) return DAF_EUNSUPPORTED;
   if (plan->total_words >= (int64_t)1 << 30) return DAF_EUNSUPPORTED;   // 32-bit byte offsets into the words
-  if (daf_unpack_matmul_splits(M, N, K) > 1 && workspace == nullptr) return DAF_EINVAL;
+  if (daf_unpack_matmul_workspace_size(M, N, K) > 0 && workspace == nullptr) return DAF_EINVAL;
   const uint8_t* d_bits = bits ? bits : plan->d_bits;
   const hipError_t e = daf_launch_unpack_matmul(plan, words, min, scale, d_bits, grad_y, N, K, (int)dtype, out_grad_w,
                                                 static_cast<float*>(workspace), static_cast<hipStream_t>(stream));

@@ -36,8 +36,8 @@ hipError_t daf_launch_quantize_pack(const daf_plan_t* plan, const void* x, int d
                                     void* out_relu_y, hipStream_t stream);
 
 // Weight gradient straight from the packed activation (unpack_matmul.hip).  The plan's tensor is
-// read as [n / K, K]; out is [N, K] binary32; workspace holds splits * N * K floats when splits > 1.
-int32_t daf_unpack_matmul_splits(int64_t M, int64_t N, int64_t K);
+// read as [n / K, K]; out is [N, K] binary32; workspace holds daf_unpack_matmul_workspace_size bytes.
+int64_t daf_unpack_matmul_workspace_size(int64_t M, int64_t N, int64_t K);   // bytes (0: none needed)
 bool daf_unpack_matmul_shape_ok(int64_t M, int64_t N, int64_t K, int32_t gs);
 hipError_t daf_launch_unpack_matmul(const daf_plan_t* p, const uint32_t* words, const float* mn, const float* scale,
                                     const uint8_t* d_bits, const void* grad_y, int64_t N, int64_t K, int dtype,

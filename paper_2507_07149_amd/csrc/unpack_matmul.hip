@@ -140,7 +140,7 @@ __global__ __launch_bounds__(TileB<BK>::kThreads, BK > 128 ? 1 : 2) void k_unpac
     const uint32_t* __restrict__ words, const float* __restrict__ mn, const float* __restrict__ scale,
     const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, uint32_t uniform_bits, int32_t gs,
     const void* __restrict__ grad_y, int64_t M, int64_t N, int64_t K, int32_t tiles_n, int32_t tiles_k,
-    int32_t splits, float* __restrict__ out) {
+    uint32_t whole, int32_t slices, float* __restrict__ out, float* __restrict__ partial) {
   using TB = TileB<BK>;
   constexpr int kRowB = TB::kRow, kBufBytes = TB::kBufBytes, kP = TB::kPasses, kJ = TB::kJ, kR = TB::kGyRows;
   // Two copies of: the grad_y tile (kBM rows of kRowA bytes), then the xhat tile (kBM rows of
@@ -151,23 +151,30 @@ __global__ __launch_bounds__(TileB<BK>::kThreads, BK > 128 ? 1 : 2) void k_unpac
   __shared__ uint4 meta[TB::kMetaRing][TB::kMetaEntries];
 
   const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
+  // The first `whole` work-groups take one tile each over all of m and write it to `out`; the
+  // tiles after those are each taken by `slices` work-groups, one slice of m each, which write
+  // their partial sums to `partial` as compact tiles [slice][tile - whole][256][BK].
   // Consecutive block ids go to different XCDs (each with its own L2).  Give every XCD a
   // contiguous range of the tile sequence, k running fastest: the tiles resident on an XCD at
   // one time then share one or two panels of grad_y (the large operand) in its L2.
   const uint32_t n_tiles = (uint32_t)tiles_n * (uint32_t)tiles_k;
   const uint32_t bid = blockIdx.x;
-  const uint32_t split = bid / n_tiles;
-  uint32_t tile = bid - split * n_tiles;
+  const bool sliced = bid >= whole;
+  const uint32_t count = sliced ? n_tiles - whole : whole;       // tiles of this kind
+  const uint32_t rel = sliced ? bid - whole : bid;
+  const uint32_t slice = sliced ? rel / count : 0u;
+  uint32_t ti = rel - slice * count;
   {
-    const uint32_t xcd = tile & 7u, idx = tile >> 3;
-    const uint32_t base = n_tiles / 8u, rem = n_tiles & 7u;       // XCD x owns base (+1 if x < rem) tiles
-    tile = xcd * base + (xcd < rem ? xcd : rem) + idx;
+    const uint32_t xcd = ti & 7u, idx = ti >> 3;
+    const uint32_t base = count / 8u, rem = count & 7u;          // XCD x owns base (+1 if x < rem) tiles
+    ti = xcd * base + (xcd < rem ? xcd : rem) + idx;
   }
+  const uint32_t tile = sliced ? whole + ti : ti;
   const uint32_t tn = tile / (uint32_t)tiles_k, tk = tile - tn * (uint32_t)tiles_k;
   const int64_t n0 = (int64_t)tn * kBN, k0 = (int64_t)tk * BK;
-  const int64_t m_per_split = M / splits;
-  const int64_t m_begin = (int64_t)split * m_per_split;
-  const int steps = (int)(m_per_split / kBM);
+  const int64_t m_per_slice = sliced ? M / slices : M;
+  const int64_t m_begin = (int64_t)slice * m_per_slice;
+  const int steps = (int)(m_per_slice / kBM);
 
   // Loader roles.  grad_y: thread (cg, rq) owns rows kR*rq .. kR*rq+kR-1 of the step and columns
   // 8*cg .. 8*cg+7 of the 256.  x: thread (co, xr) owns columns 8*co .. 8*co+7 of the BK in row
@@ -399,30 +406,39 @@ __global__ __launch_bounds__(TileB<BK>::kThreads, BK > 128 ? 1 : 2) void k_unpac
   if (base < steps) do_step(Index<0>{}, st[1], ad[1], ad[0], base, at);
 
   // ---- epilogue: register r of a 32 x 32 block is row 8*(r/4) + 4*(lane/32) + r%4, column lane%32 ----
-  float* dst = out + (int64_t)split * N * K;
+  float* dst = sliced ? partial + ((int64_t)slice * count + ti) * (int64_t)(kBN * BK) : out + n0 * K + k0;
+  const int64_t ld = sliced ? BK : K;
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
     for (int j = 0; j < kJ; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int64_t n = n0 + 64 * wn + 32 * i + 8 * (r >> 2) + 4 * lg + (r & 3);
-        const int64_t k = k0 + TB::kWaveK * wk + 32 * j + li;
-        dst[n * K + k] = acc[i][j][r];
+        const int64_t n = 64 * wn + 32 * i + 8 * (r >> 2) + 4 * lg + (r & 3);
+        const int64_t k = TB::kWaveK * wk + 32 * j + li;
+        dst[n * ld + k] = acc[i][j][r];
       }
 }
 
-// out[i] = sum over the slabs of part[s][i]
-__global__ __launch_bounds__(256) void k_sum_slabs(const float4* __restrict__ part, int64_t n4, int32_t splits,
-                                                   float4* __restrict__ out) {
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256) {
-    float4 s = part[i];
-    for (int32_t p = 1; p < splits; ++p) {
-      const float4 v = part[(int64_t)p * n4 + i];
-      s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
-    }
-    out[i] = s;
+// The sliced tiles: out[tile] = sum over the slices of partial[slice][tile - whole]; one
+// work-group per 256 x 16 strip (bk4 = BK / 4 float4 per row).
+__global__ __launch_bounds__(256) void k_sum_slices(const float4* __restrict__ partial, uint32_t whole, uint32_t count,
+                                                    int32_t slices, int32_t tiles_k, int32_t bk4, int64_t K,
+                                                    float* __restrict__ out) {
+  const uint32_t strips = (uint32_t)(kBN * bk4) / 256u;           // work-groups per tile
+  const uint32_t ti = blockIdx.x / strips;
+  const uint32_t e = (blockIdx.x - ti * strips) * 256u + threadIdx.x;   // float4 index inside the tile
+  const uint32_t tile = whole + ti;
+  const uint32_t tn = tile / (uint32_t)tiles_k, tk = tile - tn * (uint32_t)tiles_k;
+  const uint32_t row = e / (uint32_t)bk4, col4 = e - row * (uint32_t)bk4;
+  const int64_t tile4 = (int64_t)kBN * bk4;
+  float4 s = partial[(int64_t)ti * tile4 + e];
+  for (int32_t p = 1; p < slices; ++p) {
+    const float4 v = partial[((int64_t)p * count + ti) * tile4 + e];
+    s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
   }
+  float* dst = out + ((int64_t)tn * kBN + row) * K + (int64_t)tk * (bk4 * 4) + 4 * col4;
+  *reinterpret_cast<float4*>(dst) = s;
 }
 
 }  // namespace
@@ -436,28 +452,50 @@ static int tile_bk(int64_t N, int64_t K) {
   return K % 128 == 0 ? 128 : 64;
 }
 
-// Number of slices of m that run as separate work-groups (a power of two, at most 16, that
-// divides the number of steps).  The work-groups run in rounds of as many as fit on the chip
-// (1 per CU with the 256-column tile, 2 with the 128-column one, 3 with the 64-column one, 256 CUs); with s slices a
-// round takes 1/s of the time, and the partial sums (s * N * K floats, kept below 256 MiB)
-// are written once and read once more at about 4 TB/s.  The cheapest s by that estimate.
-int32_t daf_unpack_matmul_splits(int64_t M, int64_t N, int64_t K) {
-  const int64_t tiles = (N / kBN) * (K / tile_bk(N, K));
-  const int64_t slots = 256 * (tile_bk(N, K) == 256 ? 1 : tile_bk(N, K) == 128 ? 2 : 3);
+// How the tiles are run.  Work-groups run in rounds of as many as fit on the chip (slots: 1 per
+// CU with the 256-column tile, 2 with the 128-column one, 3 with the 64-column one; 256 CUs).
+// The tiles of the whole rounds run over all of m; the tiles of a last, partly filled round
+// (all tiles, when there is less than one round) may be cut into `slices` slices of m (a power
+// of two, at most 16, that divides the number of steps) that run as work-groups of their own
+// and leave partial sums: a round of those takes 1/slices of the time, and the partial sums
+// (kept below 256 MiB) are written once and read once more at about 4 TB/s.  The cheapest
+// choice by that estimate; the per-step times are measured ones.
+namespace {
+struct Schedule {
+  int bk;
+  int64_t tiles, whole;    // tiles in all; tiles that run over all of m
+  int32_t slices;          // of each other tile (1: there is none)
+};
+Schedule schedule(int64_t M, int64_t N, int64_t K) {
+  Schedule sc;
+  sc.bk = tile_bk(N, K);
+  sc.tiles = (N / kBN) * (K / sc.bk);
+  const int64_t slots = 256 * (sc.bk == 256 ? 1 : sc.bk == 128 ? 2 : 3);
   const int64_t steps = M / kBM;
-  const double t_all_m = (double)steps * 1.4e-6;     // one work-group over all of m (measured per step)
-  const double out_bytes = (double)N * (double)K * 4.0;
-  int32_t best = 1;
-  double best_cost = (double)((tiles + slots - 1) / slots) * t_all_m;
+  const double t_all_m = (double)steps * (sc.bk == 256 ? 1.1e-6 : 1.25e-6);   // one work-group over all of m
+  const double tile_bytes = (double)kBN * sc.bk * 4.0;
+  sc.whole = sc.tiles;
+  sc.slices = 1;
+  double best_cost = (double)((sc.tiles + slots - 1) / slots) * t_all_m;
+  const int64_t whole = sc.tiles / slots * slots, rest = sc.tiles - whole;
+  if (rest == 0) return sc;
   for (int32_t s = 2; s <= 16 && steps % s == 0; s *= 2) {
-    if ((double)s * out_bytes > 256.0 * 1048576.0) break;
-    const double cost = (double)((tiles * s + slots - 1) / slots) * t_all_m / s + (s + 1) * out_bytes / 4.0e12;
+    if ((double)s * rest * tile_bytes > 256.0 * 1048576.0) break;
+    const double cost = (double)(whole / slots) * t_all_m + (double)((rest * s + slots - 1) / slots) * t_all_m / s +
+                        (2 * s + 1) * rest * tile_bytes / 4.0e12;
     if (cost < best_cost * 0.98) {                   // (a clear gain only)
       best_cost = cost;
-      best = s;
+      sc.whole = whole;
+      sc.slices = s;
     }
   }
-  return best;
+  return sc;
+}
+}  // namespace
+
+int64_t daf_unpack_matmul_workspace_size(int64_t M, int64_t N, int64_t K) {
+  const Schedule sc = schedule(M, N, K);
+  return sc.slices > 1 ? (int64_t)sc.slices * (sc.tiles - sc.whole) * kBN * sc.bk * 4 : 0;
 }
 
 bool daf_unpack_matmul_shape_ok(int64_t M, int64_t N, int64_t K, int32_t gs) {
@@ -470,17 +508,19 @@ hipError_t daf_launch_unpack_matmul(const daf_plan_t* p, const uint32_t* words, 
                                     const uint8_t* d_bits, const void* grad_y, int64_t N, int64_t K, int dtype,
                                     float* out, float* workspace, hipStream_t stream) {
   const int64_t M = p->n / K;
-  const int32_t splits = daf_unpack_matmul_splits(M, N, K);
-  const int bk = tile_bk(N, K);
+  const Schedule sc = schedule(M, N, K);
+  const int bk = sc.bk;
   const int32_t tiles_n = (int32_t)(N / kBN), tiles_k = (int32_t)(K / bk);
-  const unsigned blocks = (unsigned)((int64_t)tiles_n * tiles_k * splits);
-  float* target = splits > 1 ? workspace : out;
+  const int64_t rest = sc.tiles - sc.whole;
+  const unsigned blocks = (unsigned)(sc.whole + rest * sc.slices);
+  const uint32_t whole = (uint32_t)sc.whole;
+  const int32_t slices = sc.slices;
   const void* gy = grad_y;
 #define DAF_LAUNCH(DT, MIXED, BK)                                                                                 \
   hipLaunchKernelGGL((k_unpack_matmul<DT, MIXED, BK>), dim3(blocks), dim3(TileB<BK>::kThreads), 0, stream, words,    \
                      mn, scale,                                                                                   \
                      d_bits, p->d_off, (uint32_t)p->uniform_bits, p->group_size, gy, M, N, K, tiles_n, tiles_k,   \
-                     splits, target)
+                     whole, slices, out, workspace)
 #define DAF_LAUNCH_BK(DT, MIXED)                                                                                  \
   do {                                                                                                            \
     if (bk == 256) DAF_LAUNCH(DT, MIXED, 256);                                                                    \
@@ -497,10 +537,10 @@ hipError_t daf_launch_unpack_matmul(const daf_plan_t* p, const uint32_t* words, 
 #undef DAF_LAUNCH_BK
 #undef DAF_LAUNCH
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess || splits == 1) return e;
-  const int64_t n4 = N * K / 4;
-  const unsigned rblocks = (unsigned)((n4 + 255) / 256 < 4096 ? (n4 + 255) / 256 : 4096);
-  hipLaunchKernelGGL(k_sum_slabs, dim3(rblocks), dim3(256), 0, stream, reinterpret_cast<const float4*>(workspace), n4,
-                     splits, reinterpret_cast<float4*>(out));
+  if (e != hipSuccess || rest == 0) return e;
+  const int32_t bk4 = bk / 4;
+  const unsigned rblocks = (unsigned)(rest * (kBN * bk4 / 256));
+  hipLaunchKernelGGL(k_sum_slices, dim3(rblocks), dim3(256), 0, stream, reinterpret_cast<const float4*>(workspace),
+                     whole, (uint32_t)rest, slices, tiles_k, bk4, K, out);
   return hipGetLastError();
 }

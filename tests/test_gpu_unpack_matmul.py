@@ -89,6 +89,19 @@ def test_grad_weight_wide_tile(env, case):
     assert ws == 0
 
 
+# One tile more than whole rounds of work-groups (256, 512 or 768 per round for the 256-, 128- and
+# 64-column tile): the tiles of the last round are cut into slices of m, the others are not.
+@pytest.mark.timeout(300)
+@pytest.mark.parametrize("K,bk,bits,dtype", [(4352, 256, "mixed", BF16), (4224, 128, "mixed", F16), (3136, 64, 4, BF16)])
+def test_grad_weight_sliced_last_round(env, K, bk, bits, dtype):
+    daf, orc = env
+    M, N = 4096, 4096
+    print("case sliced last round", K, bk, bits, dtype, flush=True)
+    ws = _case(daf, orc, M, N, K, 64, bits, dtype, 17)
+    tile_bytes = 256 * bk * 4
+    assert ws > 0 and ws % (16 * tile_bytes) == 0 and ws <= 16 * 16 * tile_bytes     # 16 tiles in 2..16 slices
+
+
 def test_grad_weight_argument_errors(env):
     daf, _ = env
     plan = daf.daf_plan((128, 256), 64, 2)
