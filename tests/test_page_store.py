@@ -360,3 +360,27 @@ def test_batched_calls_equal_the_single_ones(kind):
     assert want == list(zip(bits.tolist(), off.tolist(), size.tolist()))
     assert one.pop_evicted() == many.pop_evicted() and many.validate()
     assert one.num_selections() == many.num_selections() > 0
+
+
+def test_cpp_store_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """page_store.cpp is host-only code: build it with tests/page_store_churn.cpp under
+    -fsanitize=address,undefined and run random call sequences on a red-black-tree store and a
+    re-sorting store side by side (same decisions, daf_store_validate after every call)."""
+    import shutil
+    import subprocess
+    if shutil.which("g++") is None:
+        pytest.skip("no g++")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = str(tmp_path / "page_store_churn")
+    cmd = ["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+           "-I" + os.path.join(root, "include"), "-I" + os.path.join(root, "paper_2507_07149_amd", "csrc"),
+           os.path.join(root, "tests", "page_store_churn.cpp"),
+           os.path.join(root, "paper_2507_07149_amd", "csrc", "page_store.cpp"), "-o", exe]
+    build = subprocess.run(cmd, capture_output=True, text=True)
+    if build.returncode != 0 and "sanitize" in build.stderr and "cannot find" in build.stderr:
+        pytest.skip("sanitizer runtimes are not installed")
+    assert build.returncode == 0, build.stderr
+    env = dict(os.environ, ASAN_OPTIONS="verify_asan_link_order=0:detect_leaks=1")
+    run = subprocess.run([exe, "12", "2500"], capture_output=True, text=True, env=env, timeout=300)
+    assert run.returncode == 0, run.stdout + run.stderr
+    assert run.stdout.startswith("ok:")
