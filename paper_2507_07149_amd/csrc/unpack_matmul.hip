@@ -15,12 +15,15 @@
 // such loads make one 8-element MFMA operand.  Rows are padded (stride = 64 bytes mod 256) so
 // that the four rows of a load fall on different banks.
 //
-// Work-group tile: 256 (n) x 64 (k) outputs, 32 values of m per step, 4 waves of 64 x 64
-// each (2 x 2 MFMA blocks of 32 x 32, 64 accumulator registers).  The wide n keeps the number
-// of times a value of x is dequantized (once per tile of n) low; the small wave tile keeps the
-// register count low enough for several work-groups per CU, which is what hides the latencies
-// of one wave behind the work of another.  Two copies of the LDS tiles: while the products
-// read one, the next step's tiles are built in the other, between the MFMA instructions.
+// Work-group tile: 256 (n) x BK (k) outputs, BK = 256 on 8 waves, or 128 or 64 on 4 waves; 32
+// values of m per step.  A wave owns 64 (n) x 128 (k) (64 x 64 in the narrowest tile): 2 x 4
+// MFMA blocks of 32 x 32, 128 accumulator registers, two waves per SIMD.  The wide n keeps the
+// number of times a value of x is dequantized (once per tile of n) low; the wide k keeps the
+// number of times a row of grad_y is fetched low.  Two copies of the LDS tiles: while the
+// products read one, the next step's tiles are built in the other, next to the MFMA
+// instructions; one barrier per step.  Global loads run two steps ahead of their use; the
+// per-group constants are fetched once per work-group, six steps ahead, and passed through a
+// ring in LDS.
 #include "daf_device.h"
 #include "daf_internal.h"
 
