@@ -60,6 +60,8 @@ def parse():
                     help="time daf_unpack_matmul_grad_weight (unpack+dequantize inside the weight-gradient "
                          "product) against daf_unpack_dequantize followed by the library matrix product; "
                          "--config 5 (LLM MLP, bf16) or 3 (ViT MLP, fp16)")
+    ap.add_argument("--f32", action="store_true",
+                    help="with --fused-matmul: the same shape with binary32 tensors (32x32x2 MFMA, 157.3 TFLOP/s peak)")
     ap.add_argument("--uniform-bits", type=int, default=None, choices=[1, 2, 4, 8],
                     help="with --fused-matmul: one width for every group instead of the configuration's per-group widths")
     ap.add_argument("--fused-relu", action="store_true",
@@ -241,7 +243,8 @@ def main():
         K = w.x.shape[-1]
         M = w.numel // K
         N = {5: 4096, 3: 3072}.get(args.config, 1024)
-        x = w.x.reshape(-1).to(dev)
+        dt = torch.float32 if args.f32 else w.x.dtype
+        x = w.x.reshape(-1).to(dev).to(dt)
         bits = int(w.bits[0]) if w.bits.size == 1 else torch.from_numpy(w.bits).to(dev)
         if args.uniform_bits:
             bits = args.uniform_bits
@@ -249,15 +252,15 @@ def main():
         words = torch.empty(plan.packed_words, dtype=torch.int32, device=dev)
         mn, sc = torch.empty(plan.num_groups, device=dev), torch.empty(plan.num_groups, device=dev)
         daf.daf_quantize_pack(plan, x, w.seed, words, mn, sc)
-        gy = (torch.randn(M, N, device=dev) * 0.1).to(w.x.dtype)
+        gy = (torch.randn(M, N, device=dev) * 0.1).to(dt)
         out = torch.empty(N, K, device=dev)
         ws_bytes = daf.daf_unpack_matmul_workspace_bytes(plan, N, K)
         if ws_bytes < 0:
             print("bench.py: shape not supported by the fused product", file=sys.stderr)
             sys.exit(2)
         ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
-        xh = torch.empty(M, K, dtype=w.x.dtype, device=dev)
-        out_lib = torch.empty(N, K, dtype=w.x.dtype, device=dev)
+        xh = torch.empty(M, K, dtype=dt, device=dev)
+        out_lib = torch.empty(N, K, dtype=dt, device=dev)
 
         def timed(fn, reps):
             for _ in range(max(2, args.warmup // 4)):
@@ -281,19 +284,20 @@ def main():
         t_mm = timed(lambda: torch.mm(gy.t(), xh, out=out_lib), reps)
         rel = ((out - out_lib.float()).abs().max() / out.abs().max()).item()
         flops = 2.0 * M * N * K
+        peak = 157.3 if args.f32 else 2500.0           # dense MFMA, binary32 / 16-bit formats
         ach = flops / (t_fused * 1e-3) / 1e12
         print(json.dumps({"metric": "weight gradient from the packed activation, TFLOP/s", "value": round(ach, 1),
                           "unit": "TFLOP/s", "n_gpus": 1, "steps": reps, "data": "synthetic", "higher_is_better": True,
-                          "dtype": {1: "f16", 2: "bf16"}[w.dtype],
+                          "dtype": "f32" if args.f32 else {1: "f16", 2: "bf16"}[w.dtype],
                           "config": {"workload": CONFIG_NAMES[args.config] + f"_grad_weight_N{N}", "M": M, "N": N, "K": K,
                                      "splits_workspace_bytes": ws_bytes},
                           "fused_ms": round(t_fused, 4), "unfused_dequantize_plus_library_mm_ms": round(t_unfused, 4),
                           "library_mm_alone_ms": round(t_mm, 4),
                           "library_mm_TFLOPs": round(flops / (t_mm * 1e-3) / 1e12, 1),
-                          "xhat_bytes_never_written": M * K * w.x.element_size(),
-                          "max_rel_diff_vs_library_bf16_output": round(rel, 5),
-                          "roofline": {"bound": "mfma", "achieved": round(ach, 1), "peak": 2500.0, "unit": "TFLOP/s",
-                                       "frac": round(ach / 2500.0, 4), "traffic": None, "kernel": "k_unpack_matmul"}}))
+                          "xhat_bytes_never_written": M * K * x.element_size(),
+                          "max_rel_diff_vs_library_output": round(rel, 5),
+                          "roofline": {"bound": "mfma", "achieved": round(ach, 1), "peak": peak, "unit": "TFLOP/s",
+                                       "frac": round(ach / peak, 4), "traffic": None, "kernel": "k_unpack_matmul"}}))
         return
 
     if args.fused_relu:

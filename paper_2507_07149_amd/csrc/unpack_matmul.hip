@@ -31,27 +31,35 @@ namespace {
 
 using namespace daf;
 
-constexpr int kBN = 256, kBM = 32;
-constexpr int kRowA = kBN * 2 + 64;                 // bytes per row of the grad_y tile in LDS (padded)
+constexpr int kBN = 256;
 // The tile is BK = 64, 128 or 256 columns of k wide (a template parameter of the kernel).  Four
 // waves side by side along n, each with all the columns of k up to 128; the 256-column tile
-// has a second row of four waves for columns 128..255.
-template <int BK>
+// has a second row of four waves for columns 128..255.  ES = bytes per element of grad_y and
+// xhat: 2 (bf16, f16; 32 values of m per step) or 4 (binary32; 16 values of m per step, so
+// that the LDS tiles have the same size).
+template <int BK, int ES>
 struct TileB {
+  static constexpr int kBM = ES == 2 ? 32 : 16;     // values of m per step
   static constexpr int kThreads = BK > 128 ? 512 : 256;
   static constexpr int kWaveK = BK > 128 ? 128 : BK;        // columns of k per wave
-  static constexpr int kRow = BK * 2 + 64;          // bytes per row of the xhat tile in LDS (padded)
+  // Row strides in LDS: 64 bytes mod 256 for the transposing 16-bit reads (four rows of a load on
+  // different banks), 128 bytes mod 256 for the plain 32-bit reads (the two rows of a load).
+  static constexpr int kPad = ES == 2 ? 64 : 128;
+  static constexpr int kRowA = kBN * ES + kPad;     // bytes per row of the grad_y tile in LDS
+  static constexpr int kRow = BK * ES + kPad;       // bytes per row of the xhat tile in LDS
   static constexpr int kBufBytes = kBM * (kRowA + kRow);   // one copy of both tiles
-  static constexpr int kGyRows = kBM / (kThreads / 32);    // rows of the grad_y tile per thread: 4 or 2
+  static constexpr int kGyChunks = kBN * ES / 16;   // 16-byte chunks per row of the grad_y tile
+  static constexpr int kGyRows = kBM / (kThreads / kGyChunks);   // rows of the grad_y tile per thread: 4 or 2
   static constexpr int kSegs = BK / 8;              // 8-column segments per row
   static constexpr int kRowsPerPass = kThreads / kSegs;    // rows of x the threads cover at once
-  static constexpr int kPasses = kBM / kRowsPerPass;       // 1 (BK = 64) or 2
+  static constexpr int kPasses = kBM / kRowsPerPass;       // 1 or 2
   static constexpr int kJ = kWaveK / 32;            // MFMA blocks along k per wave
   // Per-group constants of a step (min, scale, width, word offset: 16 bytes per group) go
   // through a ring in LDS: at most BK / 32 groups per row of the tile (groups have >= 32 elements).
   static constexpr int kGroupsPerRow = BK / 32;
   static constexpr int kMetaEntries = kBM * kGroupsPerRow;          // per step
   static constexpr int kMetaRing = BK > 64 ? 8 : 5;                 // steps in the ring (5 is the minimum)
+  static_assert(kPasses >= 1 && kGyRows >= 2, "tile shape");
 };
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -67,6 +75,11 @@ __device__ __forceinline__ f32x16 mfma_32x32x16(const uint4& a, const uint4& b, 
     return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0,
                                                   0);
   }
+}
+
+// binary32: one element of each operand per lane, two values of m per instruction
+__device__ __forceinline__ f32x16 mfma_32x32x2(float a, float b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
 }
 
 typedef short i16x4 __attribute__((ext_vector_type(4)));
@@ -139,13 +152,15 @@ __device__ __forceinline__ uint32_t narrow16_pair(float lo, float hi) {
 }
 
 template <int DT, bool MIXED, int BK>
-__global__ __launch_bounds__(TileB<BK>::kThreads, BK > 128 ? 1 : 2) void k_unpack_matmul(
+__global__ __launch_bounds__((TileB<BK, (DT == kF32 ? 4 : 2)>::kThreads), (BK > 128 ? 1 : 2)) void k_unpack_matmul(
     const uint32_t* __restrict__ words, const float* __restrict__ mn, const float* __restrict__ scale,
     const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, uint32_t uniform_bits, int32_t gs,
     const void* __restrict__ grad_y, int64_t M, int64_t N, int64_t K, int32_t tiles_n, int32_t tiles_k,
     uint32_t whole, int32_t slices, float* __restrict__ out, float* __restrict__ partial) {
-  using TB = TileB<BK>;
-  constexpr int kRowB = TB::kRow, kBufBytes = TB::kBufBytes, kP = TB::kPasses, kJ = TB::kJ, kR = TB::kGyRows;
+  constexpr int ES = DT == kF32 ? 4 : 2;
+  using TB = TileB<BK, ES>;
+  constexpr int kBM = TB::kBM, kRowA = TB::kRowA, kRowB = TB::kRow, kBufBytes = TB::kBufBytes, kP = TB::kPasses,
+                kJ = TB::kJ, kR = TB::kGyRows;
   // Two copies of: the grad_y tile (kBM rows of kRowA bytes), then the xhat tile (kBM rows of
   // kRowB bytes).  While the products read one copy, the next step's tiles are written into the other.
   __shared__ __attribute__((aligned(16))) char lds[2][kBufBytes];
@@ -180,18 +195,18 @@ __global__ __launch_bounds__(TileB<BK>::kThreads, BK > 128 ? 1 : 2) void k_unpac
   const int steps = (int)(m_per_slice / kBM);
 
   // Loader roles.  grad_y: thread (cg, rq) owns rows kR*rq .. kR*rq+kR-1 of the step and columns
-  // 8*cg .. 8*cg+7 of the 256.  x: thread (co, xr) owns columns 8*co .. 8*co+7 of the BK in row
+  // 16 bytes of the 256 columns.  x: thread (co, xr) owns columns 8*co .. 8*co+7 of the BK in row
   // xr (and, for BK = 128, row xr + 16).  Addresses are a block-uniform 64-bit base that
   // advances by a constant per step, plus 32-bit per-thread byte offsets.
-  const uint32_t cg = t & 31u, rq = t >> 5;
+  const uint32_t cg = t % (uint32_t)TB::kGyChunks, rq = t / (uint32_t)TB::kGyChunks;
   const uint32_t co = t % (uint32_t)TB::kSegs, xr = t / (uint32_t)TB::kSegs;
-  const uint32_t row_bytes = (uint32_t)N * 2u;                          // bytes per grad_y row
+  const uint32_t row_bytes = (uint32_t)N * (uint32_t)ES;                // bytes per grad_y row
   const uint32_t gpr = (uint32_t)(K / gs);                              // groups per row of x
   const uint32_t k_col = (uint32_t)k0 + 8u * co;
   const uint32_t gk = k_col / (uint32_t)gs;
   const uint32_t in_group = k_col - gk * (uint32_t)gs;                  // multiple of 8
   const uint32_t wpgb = (uint32_t)gs >> 5;                              // words per group and bit of width
-  const char* gy_base = reinterpret_cast<const char*>(grad_y) + (m_begin * (int64_t)row_bytes + n0 * 2);
+  const char* gy_base = reinterpret_cast<const char*>(grad_y) + (m_begin * (int64_t)row_bytes + n0 * ES);
   const uint32_t gy_voff = ((uint32_t)kR * rq) * row_bytes + 16u * cg;
   const int64_t g_step0 = m_begin * (int64_t)gpr;                        // uniform; + 32*gpr per step
 
@@ -271,20 +286,25 @@ __global__ __launch_bounds__(TileB<BK>::kThreads, BK > 128 ? 1 : 2) void k_unpac
 
   const uint32_t wn = wave & 3u, wk = wave >> 2;    // (wk = 0 except for the 256-column tile)
   const uint32_t li = lane & 31u, lg = lane >> 5;
-  // Operand reads: lane l of 16-lane group G = l / 16 addresses row 8*(l/32) + (l%16)/4 (plus 16 per
-  // sub-step, plus 4 for the second half of the operand) and the 4 columns 16*(G%2) + 4*(l%4) ..
-  // of its 32-column block; it receives column 16*(G%2) + l%16 = l%32 of the block.
+  // Operand reads, 16-bit formats: lane l of 16-lane group G = l / 16 addresses row
+  // 8*(l/32) + (l%16)/4 (plus 16 per sub-step, plus 4 for the second half of the operand) and
+  // the 4 columns 16*(G%2) + 4*(l%4) .. of its 32-column block; it receives column
+  // 16*(G%2) + l%16 = l%32 of the block.  In odd rows of the xhat tile the two 8-byte halves of
+  // every 16 bytes are exchanged: the writes of two neighbouring rows (one instruction) then
+  // fall on different banks.  binary32: lane l reads the element in row l/32 (plus 2 per pair of
+  // m), column l%32 of its block: no transposition is needed with one element per lane.
   const uint32_t tr_row = 8u * lg + ((lane & 15u) >> 2), tr_col = 16u * ((lane >> 4) & 1u) + 4u * (lane & 3u);
-  const uint32_t a_read = tr_row * (uint32_t)kRowA + (64u * wn + tr_col) * 2u;
-  // In odd rows of the xhat tile the two 8-byte halves of every 16 bytes are exchanged: the
-  // writes of two neighbouring rows (one instruction) then fall on different banks.
-  const uint32_t b_read = (uint32_t)(kBM * kRowA) + tr_row * (uint32_t)kRowB + wk * (uint32_t)(TB::kWaveK * 2) +
-                          ((tr_col * 2u) ^ (8u * (tr_row & 1u)));
+  const uint32_t a_read = ES == 2 ? tr_row * (uint32_t)kRowA + (64u * wn + tr_col) * 2u
+                                  : lg * (uint32_t)kRowA + (64u * wn + li) * 4u;
+  const uint32_t b_read = (uint32_t)(kBM * kRowA) + wk * (uint32_t)(TB::kWaveK * ES) +
+                          (ES == 2 ? tr_row * (uint32_t)kRowB + ((tr_col * 2u) ^ (8u * (tr_row & 1u)))
+                                   : lg * (uint32_t)kRowB + li * 4u);
 
-  // Half of the work of turning a stage into LDS tiles: two of the thread's four grad_y rows
+  // Half of the work of turning a stage into LDS tiles: half of the thread's grad_y rows
   // (copied as loaded) and half of each of its rows of x.
   const uint32_t a_store = ((uint32_t)kR * rq) * (uint32_t)kRowA + 16u * cg;
-  const uint32_t b_store = (uint32_t)(kBM * kRowA) + xr * (uint32_t)kRowB + 16u * co + 8u * (xr & 1u);
+  const uint32_t b_store = (uint32_t)(kBM * kRowA) + xr * (uint32_t)kRowB +
+                           (ES == 2 ? 16u * co + 8u * (xr & 1u) : 32u * co);
   auto build_half = [&](const Stage<kP, kR>& cur, char* buf, int hs, uint32_t slot) __attribute__((always_inline)) {
 #pragma unroll
     for (int rr = 0; rr < kR / 2; ++rr) {
@@ -311,8 +331,13 @@ __global__ __launch_bounds__(TileB<BK>::kThreads, BK > 128 ? 1 : 2) void k_unpac
         sh -= b;
         v[cc] = __builtin_fmaf((float)code, ms.y, ms.x);
       }
-      *reinterpret_cast<uint2*>(buf + ((b_store + (uint32_t)(p * TB::kRowsPerPass * kRowB)) ^ (8u * (uint32_t)hs))) =
-          make_uint2(narrow16_pair<DT>(v[0], v[1]), narrow16_pair<DT>(v[2], v[3]));
+      if constexpr (ES == 2) {
+        *reinterpret_cast<uint2*>(buf + ((b_store + (uint32_t)(p * TB::kRowsPerPass * kRowB)) ^ (8u * (uint32_t)hs))) =
+            make_uint2(narrow16_pair<DT>(v[0], v[1]), narrow16_pair<DT>(v[2], v[3]));
+      } else {
+        *reinterpret_cast<float4*>(buf + b_store + (uint32_t)(p * TB::kRowsPerPass * kRowB) + 16u * (uint32_t)hs) =
+            make_float4(v[0], v[1], v[2], v[3]);
+      }
     }
   };
 
@@ -344,17 +369,34 @@ __global__ __launch_bounds__(TileB<BK>::kThreads, BK > 128 ? 1 : 2) void k_unpac
     const char* a_lds = lds[buf] + a_read;
     const char* b_lds = lds[buf] + b_read;
 #pragma unroll
-    for (int ss = 0; ss < kBM / 16; ++ss) {
-      uint4 a[2], b[kJ];
+    for (int ss = 0; ss < 2; ++ss) {                // two halves of the step, a half of the next tiles built in each
+      if constexpr (ES == 2) {
+        uint4 a[2], b[kJ];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) a[i] = operand_tr(a_lds + ss * 16 * kRowA + i * 64, kRowA);
+        for (int i = 0; i < 2; ++i) a[i] = operand_tr(a_lds + ss * 16 * kRowA + i * 64, kRowA);
 #pragma unroll
-      for (int j = 0; j < kJ; ++j) b[j] = operand_tr(b_lds + ss * 16 * kRowB + j * 64, kRowB);
-      build_half(next, lds[buf ^ 1], ss, ring(at, 1));
+        for (int j = 0; j < kJ; ++j) b[j] = operand_tr(b_lds + ss * 16 * kRowB + j * 64, kRowB);
+        build_half(next, lds[buf ^ 1], ss, ring(at, 1));
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < kJ; ++j) acc[i][j] = mfma_32x32x16<DT>(a[i], b[j], acc[i][j]);
+          for (int j = 0; j < kJ; ++j) acc[i][j] = mfma_32x32x16<DT>(a[i], b[j], acc[i][j]);
+      } else {
+        build_half(next, lds[buf ^ 1], ss, ring(at, 1));
+#pragma unroll
+        for (int kk = 0; kk < kBM / 4; ++kk) {        // pairs of m in this half
+          const int row = ss * (kBM / 2) + 2 * kk;
+          float a[2], b[kJ];
+#pragma unroll
+          for (int i = 0; i < 2; ++i) a[i] = *reinterpret_cast<const float*>(a_lds + row * kRowA + i * 128);
+#pragma unroll
+          for (int j = 0; j < kJ; ++j) b[j] = *reinterpret_cast<const float*>(b_lds + row * kRowB + j * 128);
+#pragma unroll
+          for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < kJ; ++j) acc[i][j] = mfma_32x32x2(a[i], b[j], acc[i][j]);
+        }
+      }
     }
     // Requested unconditionally (past the end the last step is requested again and never
     // used), so that the number of loads in flight is the same in every iteration.
@@ -446,6 +488,11 @@ __global__ __launch_bounds__(256) void k_sum_slices(const float4* __restrict__ p
 
 }  // namespace
 
+// M is a multiple of 32 for every element format (the 16-bit kernels take 32 values of m per
+// step, the binary32 kernel 16), and the slicing below does not depend on the format, so that
+// the workspace size is a function of the shape alone.
+constexpr int kStepM = 32;
+
 // Width of the tile along k.  Each doubling halves the number of times a row of grad_y is
 // fetched; the 256-column tile (8 waves, one work-group per CU) is used when the output has
 // enough of them to fill the chip without slicing m, else the 128-column one (measured: LLM
@@ -474,7 +521,7 @@ Schedule schedule(int64_t M, int64_t N, int64_t K) {
   sc.bk = tile_bk(N, K);
   sc.tiles = (N / kBN) * (K / sc.bk);
   const int64_t slots = 256 * (sc.bk == 256 ? 1 : sc.bk == 128 ? 2 : 3);
-  const int64_t steps = M / kBM;
+  const int64_t steps = M / kStepM;
   const double t_all_m = (double)steps * (sc.bk == 256 ? 1.1e-6 : 1.25e-6);   // one work-group over all of m
   const double tile_bytes = (double)kBN * sc.bk * 4.0;
   sc.whole = sc.tiles;
@@ -503,7 +550,7 @@ int64_t daf_unpack_matmul_workspace_size(int64_t M, int64_t N, int64_t K) {
 
 bool daf_unpack_matmul_shape_ok(int64_t M, int64_t N, int64_t K, int32_t gs) {
   // N and K below 2^24: the per-thread parts of the addresses are 32-bit byte offsets.
-  return M > 0 && N > 0 && K > 0 && M % kBM == 0 && N % kBN == 0 && K % 64 == 0 && K % gs == 0 &&
+  return M > 0 && N > 0 && K > 0 && M % kStepM == 0 && N % kBN == 0 && K % 64 == 0 && K % gs == 0 &&
          N < (1 << 24) && K < (1 << 24) && (N / kBN) * (K / 64) * 16 < (int64_t)1 << 31;
 }
 
@@ -520,7 +567,8 @@ hipError_t daf_launch_unpack_matmul(const daf_plan_t* p, const uint32_t* words, 
   const int32_t slices = sc.slices;
   const void* gy = grad_y;
 #define DAF_LAUNCH(DT, MIXED, BK)                                                                                 \
-  hipLaunchKernelGGL((k_unpack_matmul<DT, MIXED, BK>), dim3(blocks), dim3(TileB<BK>::kThreads), 0, stream, words,    \
+  hipLaunchKernelGGL((k_unpack_matmul<DT, MIXED, BK>), dim3(blocks),                                              \
+                     dim3(TileB<BK, DT == daf::kF32 ? 4 : 2>::kThreads), 0, stream, words,                        \
                      mn, scale,                                                                                   \
                      d_bits, p->d_off, (uint32_t)p->uniform_bits, p->group_size, gy, M, N, K, tiles_n, tiles_k,   \
                      whole, slices, out, workspace)
@@ -534,6 +582,12 @@ hipError_t daf_launch_unpack_matmul(const daf_plan_t* p, const uint32_t* words, 
     if (p->uniform_bits) DAF_LAUNCH_BK(daf::kBF16, false); else DAF_LAUNCH_BK(daf::kBF16, true);
   } else if (dtype == daf::kF16) {
     if (p->uniform_bits) DAF_LAUNCH_BK(daf::kF16, false); else DAF_LAUNCH_BK(daf::kF16, true);
+  } else if (dtype == daf::kF32 && bk >= 128) {       // (no 64-column tile for binary32)
+    if (bk == 256) {
+      if (p->uniform_bits) DAF_LAUNCH(daf::kF32, false, 256); else DAF_LAUNCH(daf::kF32, true, 256);
+    } else {
+      if (p->uniform_bits) DAF_LAUNCH(daf::kF32, false, 128); else DAF_LAUNCH(daf::kF32, true, 128);
+    }
   } else {
     return hipErrorInvalidValue;
   }

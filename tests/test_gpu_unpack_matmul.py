@@ -49,7 +49,7 @@ def _case(daf, orc, M, N, K, gs, bits, dtype, seed):
     return ws_bytes
 
 
-@pytest.mark.parametrize("dtype", [BF16, F16])
+@pytest.mark.parametrize("dtype", [BF16, F16, F32])
 @pytest.mark.parametrize("bits", [1, 2, 4, 8, "mixed"])
 @pytest.mark.parametrize("gs", [32, 128])
 def test_grad_weight_small(env, dtype, bits, gs):
@@ -80,7 +80,8 @@ def test_grad_weight_without_split_needs_no_workspace(env):
 # 256 or more 256 x 256 tiles: the 256-column tile (8 waves per work-group)
 @pytest.mark.parametrize("case", [(32, 4096, 4096, 64, "mixed", BF16), (96, 4096, 4096, 128, "mixed", F16),
                                   (64, 8192, 2048, 32, "mixed", BF16), (64, 2048, 8192, 256, 8, F16),
-                                  (32, 4096, 4096, 64, 1, BF16)])
+                                  (32, 4096, 4096, 64, 1, BF16), (64, 4096, 4096, 64, "mixed", F32),
+                                  (32, 2048, 8192, 128, 2, F32)])
 def test_grad_weight_wide_tile(env, case):
     daf, orc = env
     M, N, K, gs, bits, dtype = case
@@ -92,7 +93,8 @@ def test_grad_weight_wide_tile(env, case):
 # One tile more than whole rounds of work-groups (256, 512 or 768 per round for the 256-, 128- and
 # 64-column tile): the tiles of the last round are cut into slices of m, the others are not.
 @pytest.mark.timeout(300)
-@pytest.mark.parametrize("K,bk,bits,dtype", [(4352, 256, "mixed", BF16), (4224, 128, "mixed", F16), (3136, 64, 4, BF16)])
+@pytest.mark.parametrize("K,bk,bits,dtype", [(4352, 256, "mixed", BF16), (4224, 128, "mixed", F16), (3136, 64, 4, BF16),
+                                             (4352, 256, "mixed", F32), (4224, 128, 2, F32)])
 def test_grad_weight_sliced_last_round(env, K, bk, bits, dtype):
     daf, orc = env
     M, N = 4096, 4096
@@ -115,8 +117,10 @@ def test_grad_weight_argument_errors(env):
     with pytest.raises(daf.DafError) as e:                                    # split, but no workspace
         daf.daf_unpack_matmul_grad_weight(plan, words, mn, mn, gy, out, None)
     assert e.value.status == -1
-    with pytest.raises(daf.DafError) as e:                                    # binary32 is not offered
-        daf.daf_unpack_matmul_grad_weight(plan, words, mn, mn, gy.float(), out, torch.empty(1 << 22, dtype=torch.uint8, device="cuda:0"))
+    plan3 = daf.daf_plan((128, 192), 64, 2)                                   # binary32 needs K % 128 == 0
+    with pytest.raises(daf.DafError) as e:
+        daf.daf_unpack_matmul_grad_weight(plan3, words, mn, mn, gy.float(), torch.zeros(256, 192, device="cuda:0"),
+                                          torch.empty(1 << 22, dtype=torch.uint8, device="cuda:0"))
     assert e.value.status == -2
     plan2 = daf.daf_plan((80, 256), 64, 2)                                    # M not a multiple of 32
     with pytest.raises(daf.DafError) as e:
@@ -124,14 +128,16 @@ def test_grad_weight_argument_errors(env):
     assert e.value.status == -2
 
 
-@pytest.mark.parametrize("dtype", [BF16, F16])
+@pytest.mark.parametrize("dtype", [BF16, F16, F32])
 @pytest.mark.parametrize("bits", [1, 2, 4, 8, "mixed"])
 @pytest.mark.parametrize("K", [384, 192])                                      # 128- and 64-column tiles
 def test_identity_gradient_returns_xhat_bit_for_bit(env, dtype, bits, K):
+    if dtype == F32 and K % 128:
+        pytest.skip("binary32 has no 64-column tile")
     _identity_case(env, dtype, bits, 256, K)
 
 
-@pytest.mark.parametrize("dtype,bits", [(BF16, "mixed"), (F16, "mixed"), (BF16, 8), (F16, 2)])
+@pytest.mark.parametrize("dtype,bits", [(BF16, "mixed"), (F16, "mixed"), (BF16, 8), (F16, 2), (F32, "mixed"), (F32, 4)])
 def test_identity_gradient_wide_tile(env, dtype, bits):
     _identity_case(env, dtype, bits, 4096, 4096)                               # 256 tiles of 256 x 256
 
