@@ -190,9 +190,11 @@ __global__ __launch_bounds__((TileB<BK, (DT == kF32 ? 4 : 2)>::kThreads), (BK > 
   const uint32_t tile = sliced ? whole + ti : ti;
   const uint32_t tn = tile / (uint32_t)tiles_k, tk = tile - tn * (uint32_t)tiles_k;
   const int64_t n0 = (int64_t)tn * kBN, k0 = (int64_t)tk * BK;
-  const int64_t m_per_slice = sliced ? M / slices : M;
-  const int64_t m_begin = (int64_t)slice * m_per_slice;
-  const int steps = (int)(m_per_slice / kBM);
+  // The steps of m are dealt out to the slices as evenly as whole steps allow.
+  const int all_steps = (int)(M / kBM);
+  const int per = sliced ? all_steps / slices : all_steps, extra = sliced ? all_steps % slices : 0;
+  const int steps = per + ((int)slice < extra ? 1 : 0);
+  const int64_t m_begin = ((int64_t)slice * per + ((int)slice < extra ? (int)slice : extra)) * kBM;
 
   // Loader roles.  grad_y: thread (cg, rq) owns rows kR*rq .. kR*rq+kR-1 of the step and columns
   // 16 bytes of the 256 columns.  x: thread (co, xr) owns columns 8*co .. 8*co+7 of the BK in row
@@ -505,8 +507,8 @@ static int tile_bk(int64_t N, int64_t K) {
 // How the tiles are run.  Work-groups run in rounds of as many as fit on the chip (slots: 1 per
 // CU with the 256-column tile, 2 with the 128-column one, 3 with the 64-column one; 256 CUs).
 // The tiles of the whole rounds run over all of m; the tiles of a last, partly filled round
-// (all tiles, when there is less than one round) may be cut into `slices` slices of m (a power
-// of two, at most 16, that divides the number of steps) that run as work-groups of their own
+// (all tiles, when there is less than one round) may be cut into `slices` slices of m (2 to 16,
+// of as equal a number of steps as possible) that run as work-groups of their own
 // and leave partial sums: a round of those takes 1/slices of the time, and the partial sums
 // (kept below 256 MiB) are written once and read once more at about 4 TB/s.  The cheapest
 // choice by that estimate; the per-step times are measured ones.
@@ -529,9 +531,10 @@ Schedule schedule(int64_t M, int64_t N, int64_t K) {
   double best_cost = (double)((sc.tiles + slots - 1) / slots) * t_all_m;
   const int64_t whole = sc.tiles / slots * slots, rest = sc.tiles - whole;
   if (rest == 0) return sc;
-  for (int32_t s = 2; s <= 16 && steps % s == 0; s *= 2) {
+  for (int32_t s = 2; s <= 16 && steps >= 4 * s; ++s) {
     if ((double)s * rest * tile_bytes > 256.0 * 1048576.0) break;
-    const double cost = (double)(whole / slots) * t_all_m + (double)((rest * s + slots - 1) / slots) * t_all_m / s +
+    const double longest = (double)((steps + s - 1) / s) / (double)steps;      // share of m of the longest slice
+    const double cost = (double)(whole / slots) * t_all_m + (double)((rest * s + slots - 1) / slots) * t_all_m * longest +
                         (2 * s + 1) * rest * tile_bytes / 4.0e12;
     if (cost < best_cost * 0.98) {                   // (a clear gain only)
       best_cost = cost;

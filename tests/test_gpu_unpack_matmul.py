@@ -61,7 +61,7 @@ def test_grad_weight_small(env, dtype, bits, gs):
 # K a multiple of 128 runs the 128-column tile, any other multiple of 64 the 64-column one.
 @pytest.mark.parametrize("shape", [(32, 256, 128), (64, 256, 128), (96, 256, 256), (192, 512, 384), (1024, 256, 128),
                                    (2048, 512, 1024), (32, 256, 64), (96, 256, 192), (160, 512, 320),
-                                   (1024, 256, 448)])
+                                   (1024, 256, 448), (1088, 256, 128)])         # the last: 34 steps in 7 slices
 @pytest.mark.parametrize("bits", [2, "mixed"])
 def test_grad_weight_shapes(env, shape, bits):
     daf, orc = env
@@ -106,10 +106,10 @@ def test_grad_weight_sliced_last_round(env, K, bk, bits, dtype):
 
 def test_grad_weight_argument_errors(env):
     daf, _ = env
-    plan = daf.daf_plan((128, 256), 64, 2)
+    plan = daf.daf_plan((512, 256), 64, 2)
     words = torch.zeros(plan.packed_words, dtype=torch.int32, device="cuda:0")
     mn = torch.zeros(plan.num_groups, device="cuda:0")
-    gy = torch.zeros(128, 256, dtype=torch.bfloat16, device="cuda:0")
+    gy = torch.zeros(512, 256, dtype=torch.bfloat16, device="cuda:0")
     out = torch.zeros(256, 256, device="cuda:0")
     assert daf.daf_unpack_matmul_workspace_bytes(plan, 256, 256) > 0
     assert daf.daf_unpack_matmul_workspace_bytes(plan, 100, 256) == -1       # N not a multiple of 256
