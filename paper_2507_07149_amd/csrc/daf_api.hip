@@ -289,7 +289,6 @@ int daf_unpack_matmul_grad_weight(const daf_plan_t* plan, const uint32_t* words,
     return DAF_EINVAL;
   if (plan->uniform_bits && bits != nullptr) return DAF_EINVAL;
   if (dtype != DAF_F16 && dtype != DAF_BF16 && dtype != DAF_F32) return DAF_EUNSUPPORTED;
-  if (dtype == DAF_F32 && K % 128 != 0) return DAF_EUNSUPPORTED;
   const int64_t M = plan->n / K;
   if (!daf_unpack_matmul_shape_ok(M, N, K, plan->group_size)) return DAF_EUNSUPPORTED;
   if (plan->total_words >= (int64_t)1 << 30) return DAF_EUNSUPPORTED;   // 32-bit byte offsets into the words

@@ -52,14 +52,17 @@ struct TileB {
   static constexpr int kGyRows = kBM / (kThreads / kGyChunks);   // rows of the grad_y tile per thread: 4 or 2
   static constexpr int kSegs = BK / 8;              // 8-column segments per row
   static constexpr int kRowsPerPass = kThreads / kSegs;    // rows of x the threads cover at once
-  static constexpr int kPasses = kBM / kRowsPerPass;       // 1 or 2
+  static constexpr int kPasses = kBM >= kRowsPerPass ? kBM / kRowsPerPass : 1;   // 1 or 2
+  // (binary32 with 64 columns: the threads cover 32 rows at once but a step has 16; the upper
+  // half of the threads, whole waves, then has no part in the x tile)
+  static constexpr bool kAllThreadsOnX = kBM >= kRowsPerPass;
   static constexpr int kJ = kWaveK / 32;            // MFMA blocks along k per wave
   // Per-group constants of a step (min, scale, width, word offset: 16 bytes per group) go
   // through a ring in LDS: at most BK / 32 groups per row of the tile (groups have >= 32 elements).
   static constexpr int kGroupsPerRow = BK / 32;
   static constexpr int kMetaEntries = kBM * kGroupsPerRow;          // per step
   static constexpr int kMetaRing = BK > 64 ? 8 : 5;                 // steps in the ring (5 is the minimum)
-  static_assert(kPasses >= 1 && kGyRows >= 2, "tile shape");
+  static_assert(kGyRows >= 2, "tile shape");
 };
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -202,6 +205,7 @@ __global__ __launch_bounds__((TileB<BK, (DT == kF32 ? 4 : 2)>::kThreads), (BK > 
   // advances by a constant per step, plus 32-bit per-thread byte offsets.
   const uint32_t cg = t % (uint32_t)TB::kGyChunks, rq = t / (uint32_t)TB::kGyChunks;
   const uint32_t co = t % (uint32_t)TB::kSegs, xr = t / (uint32_t)TB::kSegs;
+  const bool on_x = TB::kAllThreadsOnX || xr < (uint32_t)kBM;          // (uniform per wave)
   const uint32_t row_bytes = (uint32_t)N * (uint32_t)ES;                // bytes per grad_y row
   const uint32_t gpr = (uint32_t)(K / gs);                              // groups per row of x
   const uint32_t k_col = (uint32_t)k0 + 8u * co;
@@ -246,6 +250,7 @@ __global__ __launch_bounds__((TileB<BK, (DT == kF32 ? 4 : 2)>::kThreads), (BK > 
   };
   const uint32_t g_voff = xr * gpr + gk;                                 // the thread's group, relative to the step's first
   auto fetch_addr = [&](Addr<kP>& ad, uint32_t slot, int step) __attribute__((always_inline)) {
+    if (!on_x) return;
 #pragma unroll
     for (int p = 0; p < kP; ++p) {
       if (MIXED) {
@@ -268,6 +273,7 @@ __global__ __launch_bounds__((TileB<BK, (DT == kF32 ? 4 : 2)>::kThreads), (BK > 
       const u32x4 v = load_at<u32x4>(gp + (int64_t)r * row_bytes, opaque(gy_voff));   // (per load: else rows 1..3 get vector addresses)
       f.gy[r] = make_uint4(v.x, v.y, v.z, v.w);
     }
+    if (!on_x) return;
 #pragma unroll
     for (int p = 0; p < kP; ++p) {
       // The 8 codes lie in one word, or (8 bits) in two: codes 0..3 in the first, 4..7 in the next.
@@ -313,7 +319,8 @@ __global__ __launch_bounds__((TileB<BK, (DT == kF32 ? 4 : 2)>::kThreads), (BK > 
       const int r = (kR / 2) * hs + rr;
       *reinterpret_cast<uint4*>(buf + a_store + (uint32_t)r * kRowA) = cur.gy[r];
     }
-    // ---- xhat: unpack, dequantize, round to the element format; 4 columns = 8 bytes of the row ----
+    if (!on_x) return;
+    // ---- xhat: unpack, dequantize, round to the element format; 4 columns of the row ----
     // Element j of a group has its lowest bit at bit -(j + 1) * b (mod 32) of its word; the
     // bit-field extract takes its offset mod 32, which also covers the second word of 8-bit codes.
 #pragma unroll
@@ -585,12 +592,8 @@ hipError_t daf_launch_unpack_matmul(const daf_plan_t* p, const uint32_t* words, 
     if (p->uniform_bits) DAF_LAUNCH_BK(daf::kBF16, false); else DAF_LAUNCH_BK(daf::kBF16, true);
   } else if (dtype == daf::kF16) {
     if (p->uniform_bits) DAF_LAUNCH_BK(daf::kF16, false); else DAF_LAUNCH_BK(daf::kF16, true);
-  } else if (dtype == daf::kF32 && bk >= 128) {       // (no 64-column tile for binary32)
-    if (bk == 256) {
-      if (p->uniform_bits) DAF_LAUNCH(daf::kF32, false, 256); else DAF_LAUNCH(daf::kF32, true, 256);
-    } else {
-      if (p->uniform_bits) DAF_LAUNCH(daf::kF32, false, 128); else DAF_LAUNCH(daf::kF32, true, 128);
-    }
+  } else if (dtype == daf::kF32) {
+    if (p->uniform_bits) DAF_LAUNCH_BK(daf::kF32, false); else DAF_LAUNCH_BK(daf::kF32, true);
   } else {
     return hipErrorInvalidValue;
   }
