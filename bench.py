@@ -59,7 +59,7 @@ def parse():
     ap.add_argument("--fused-matmul", action="store_true",
                     help="time daf_unpack_matmul_grad_weight (unpack+dequantize inside the weight-gradient "
                          "product) against daf_unpack_dequantize followed by the library matrix product; "
-                         "--config 5 (LLM MLP, bf16) or 3 (ViT MLP, fp16)")
+                         "--config 5 (LLM MLP, bf16), 3 (ViT MLP, fp16) or 2 (conv activation as [N*H*W, C], fp32)")
     ap.add_argument("--f32", action="store_true",
                     help="with --fused-matmul: the same shape with binary32 tensors (32x32x2 MFMA, 157.3 TFLOP/s peak)")
     ap.add_argument("--uniform-bits", type=int, default=None, choices=[1, 2, 4, 8],
@@ -240,9 +240,12 @@ def main():
 
     if args.fused_matmul:
         (w,) = make_config(args.config)
-        K = w.x.shape[-1]
+        # configurations 5 and 3: the linear layer after the activation; configuration 2: the conv
+        # activation read as [N*H*W, C] (a pointwise convolution in a channels-last view): a long
+        # reduction into a 256 x 256 output
+        K = 256 if args.config == 2 else w.x.shape[-1]
         M = w.numel // K
-        N = {5: 4096, 3: 3072}.get(args.config, 1024)
+        N = {5: 4096, 3: 3072, 2: 256}.get(args.config, 1024)
         dt = torch.float32 if args.f32 else w.x.dtype
         x = w.x.reshape(-1).to(dev).to(dt)
         bits = int(w.bits[0]) if w.bits.size == 1 else torch.from_numpy(w.bits).to(dev)
@@ -284,11 +287,11 @@ def main():
         t_mm = timed(lambda: torch.mm(gy.t(), xh, out=out_lib), reps)
         rel = ((out - out_lib.float()).abs().max() / out.abs().max()).item()
         flops = 2.0 * M * N * K
-        peak = 157.3 if args.f32 else 2500.0           # dense MFMA, binary32 / 16-bit formats
+        peak = 157.3 if x.dtype == torch.float32 else 2500.0   # dense MFMA, binary32 / 16-bit formats
         ach = flops / (t_fused * 1e-3) / 1e12
         print(json.dumps({"metric": "weight gradient from the packed activation, TFLOP/s", "value": round(ach, 1),
                           "unit": "TFLOP/s", "n_gpus": 1, "steps": reps, "data": "synthetic", "higher_is_better": True,
-                          "dtype": "f32" if args.f32 else {1: "f16", 2: "bf16"}[w.dtype],
+                          "dtype": "f32" if args.f32 else {0: "f32", 1: "f16", 2: "bf16"}[w.dtype],
                           "config": {"workload": CONFIG_NAMES[args.config] + f"_grad_weight_N{N}", "M": M, "N": N, "K": K,
                                      "splits_workspace_bytes": ws_bytes},
                           "fused_ms": round(t_fused, 4), "unfused_dequantize_plus_library_mm_ms": round(t_unfused, 4),

@@ -475,31 +475,41 @@ __global__ __launch_bounds__((TileB<BK, (DT == kF32 ? 4 : 2)>::kThreads), (BK > 
 }
 
 // The sliced tiles: out[tile] = sum over the slices of partial[slice][tile - whole]; one
-// work-group per 256 x 16 strip (bk4 = BK / 4 float4 per row).
-__global__ __launch_bounds__(256) void k_sum_slices(const float4* __restrict__ partial, uint32_t whole, uint32_t count,
-                                                    int32_t slices, int32_t tiles_k, int32_t bk4, int64_t K,
-                                                    float* __restrict__ out) {
+// work-group per 256 x 16 strip of a tile (bk4 = BK / 4 float4 per row).  A launch adds n
+// slices that lie `stride` slices apart, starting at slice blockIdx.y * n * stride, and writes
+// the sum over the first of them (TO_OUT = false) or into the output (TO_OUT = true, one group):
+// more than 16 slices are added in two levels, 16 at a time and then the 16th ones, so that
+// the additions of one output are spread over several work-groups.
+template <bool TO_OUT>
+__global__ __launch_bounds__(256) void k_sum_slices(float4* __restrict__ partial, uint32_t whole, uint32_t count,
+                                                    int32_t slices, int32_t n, int32_t stride, int32_t tiles_k,
+                                                    int32_t bk4, int64_t K, float* __restrict__ out) {
   const uint32_t strips = (uint32_t)(kBN * bk4) / 256u;           // work-groups per tile
   const uint32_t ti = blockIdx.x / strips;
   const uint32_t e = (blockIdx.x - ti * strips) * 256u + threadIdx.x;   // float4 index inside the tile
-  const uint32_t tile = whole + ti;
-  const uint32_t tn = tile / (uint32_t)tiles_k, tk = tile - tn * (uint32_t)tiles_k;
-  const uint32_t row = e / (uint32_t)bk4, col4 = e - row * (uint32_t)bk4;
   const int64_t tile4 = (int64_t)kBN * bk4;
-  float4 s = partial[(int64_t)ti * tile4 + e];
-  for (int32_t p = 1; p < slices; ++p) {
-    const float4 v = partial[((int64_t)p * count + ti) * tile4 + e];
+  const int32_t first = (int32_t)blockIdx.y * n * stride;
+  float4* p0 = partial + ((int64_t)first * count + ti) * tile4 + e;
+  float4 s = *p0;
+  for (int32_t j = 1; j < n && first + j * stride < slices; ++j) {
+    const float4 v = p0[(int64_t)j * stride * count * tile4];
     s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
   }
-  float* dst = out + ((int64_t)tn * kBN + row) * K + (int64_t)tk * (bk4 * 4) + 4 * col4;
-  *reinterpret_cast<float4*>(dst) = s;
+  if (TO_OUT) {
+    const uint32_t tile = whole + ti;
+    const uint32_t tn = tile / (uint32_t)tiles_k, tk = tile - tn * (uint32_t)tiles_k;
+    const uint32_t row = e / (uint32_t)bk4, col4 = e - row * (uint32_t)bk4;
+    float* dst = out + ((int64_t)tn * kBN + row) * K + (int64_t)tk * (bk4 * 4) + 4 * col4;
+    *reinterpret_cast<float4*>(dst) = s;
+  } else {
+    *p0 = s;
+  }
 }
 
 }  // namespace
 
 // M is a multiple of 32 for every element format (the 16-bit kernels take 32 values of m per
-// step, the binary32 kernel 16), and the slicing below does not depend on the format, so that
-// the workspace size is a function of the shape alone.
+// step, the binary32 kernel 16); the slicing below counts m in units of 32.
 constexpr int kStepM = 32;
 
 // Width of the tile along k.  Each doubling halves the number of times a row of grad_y is
@@ -515,7 +525,7 @@ static int tile_bk(int64_t N, int64_t K) {
 // CU with the 256-column tile, 2 with the 128-column one, 3 with the 64-column one; 256 CUs).
 // The tiles of the whole rounds run over all of m; the tiles of a last, partly filled round
 // (all tiles, when there is less than one round) may be cut into `slices` slices of m (2 to 16,
-// of as equal a number of steps as possible) that run as work-groups of their own
+// more for outputs of a few tiles; of as equal a number of steps as possible) that run as work-groups of their own
 // and leave partial sums: a round of those takes 1/slices of the time, and the partial sums
 // (kept below 256 MiB) are written once and read once more at about 4 TB/s.  The cheapest
 // choice by that estimate; the per-step times are measured ones.
@@ -525,20 +535,24 @@ struct Schedule {
   int64_t tiles, whole;    // tiles in all; tiles that run over all of m
   int32_t slices;          // of each other tile (1: there is none)
 };
-Schedule schedule(int64_t M, int64_t N, int64_t K) {
+Schedule schedule(int64_t M, int64_t N, int64_t K, int es) {   // es: bytes per element (2 or 4)
   Schedule sc;
   sc.bk = tile_bk(N, K);
   sc.tiles = (N / kBN) * (K / sc.bk);
   const int64_t slots = 256 * (sc.bk == 256 ? 1 : sc.bk == 128 ? 2 : 3);
   const int64_t steps = M / kStepM;
-  const double t_all_m = (double)steps * (sc.bk == 256 ? 1.1e-6 : 1.25e-6);   // one work-group over all of m
+  // one work-group over all of m, per 32 values of m: the 16-bit kernels are bound by instruction
+  // issue, the binary32 kernel by its MFMAs (128 per wave of 64 cycles each)
+  const double t_all_m = (double)steps * (es == 4 ? 8.0e-6 : sc.bk == 256 ? 1.1e-6 : 1.25e-6);
   const double tile_bytes = (double)kBN * sc.bk * 4.0;
   sc.whole = sc.tiles;
   sc.slices = 1;
   double best_cost = (double)((sc.tiles + slots - 1) / slots) * t_all_m;
   const int64_t whole = sc.tiles / slots * slots, rest = sc.tiles - whole;
   if (rest == 0) return sc;
-  for (int32_t s = 2; s <= 16 && steps >= 4 * s; ++s) {
+  // (at most 16 slices, or, for outputs of a few tiles only, as many as fill the chip once)
+  const int64_t max_slices = rest * 16 >= slots ? 16 : (slots / rest < 256 ? slots / rest : 256);
+  for (int32_t s = 2; s <= max_slices && steps >= 4 * s; ++s) {
     if ((double)s * rest * tile_bytes > 256.0 * 1048576.0) break;
     const double longest = (double)((steps + s - 1) / s) / (double)steps;      // share of m of the longest slice
     const double cost = (double)(whole / slots) * t_all_m + (double)((rest * s + slots - 1) / slots) * t_all_m * longest +
@@ -553,9 +567,16 @@ Schedule schedule(int64_t M, int64_t N, int64_t K) {
 }
 }  // namespace
 
+// The number of slices depends on the element format (the binary32 kernel is slower per step,
+// so more slices pay off); the workspace is sized for the larger of the two.
 int64_t daf_unpack_matmul_workspace_size(int64_t M, int64_t N, int64_t K) {
-  const Schedule sc = schedule(M, N, K);
-  return sc.slices > 1 ? (int64_t)sc.slices * (sc.tiles - sc.whole) * kBN * sc.bk * 4 : 0;
+  int64_t bytes = 0;
+  for (int es = 2; es <= 4; es += 2) {
+    const Schedule sc = schedule(M, N, K, es);
+    const int64_t b = sc.slices > 1 ? (int64_t)sc.slices * (sc.tiles - sc.whole) * kBN * sc.bk * 4 : 0;
+    bytes = b > bytes ? b : bytes;
+  }
+  return bytes;
 }
 
 bool daf_unpack_matmul_shape_ok(int64_t M, int64_t N, int64_t K, int32_t gs) {
@@ -568,7 +589,7 @@ hipError_t daf_launch_unpack_matmul(const daf_plan_t* p, const uint32_t* words, 
                                     const uint8_t* d_bits, const void* grad_y, int64_t N, int64_t K, int dtype,
                                     float* out, float* workspace, hipStream_t stream) {
   const int64_t M = p->n / K;
-  const Schedule sc = schedule(M, N, K);
+  const Schedule sc = schedule(M, N, K, dtype == daf::kF32 ? 4 : 2);
   const int bk = sc.bk;
   const int32_t tiles_n = (int32_t)(N / kBN), tiles_k = (int32_t)(K / bk);
   const int64_t rest = sc.tiles - sc.whole;
@@ -603,7 +624,16 @@ hipError_t daf_launch_unpack_matmul(const daf_plan_t* p, const uint32_t* words, 
   if (e != hipSuccess || rest == 0) return e;
   const int32_t bk4 = bk / 4;
   const unsigned rblocks = (unsigned)(rest * (kBN * bk4 / 256));
-  hipLaunchKernelGGL(k_sum_slices, dim3(rblocks), dim3(256), 0, stream, reinterpret_cast<const float4*>(workspace),
-                     whole, (uint32_t)rest, slices, tiles_k, bk4, K, out);
+  float4* part = reinterpret_cast<float4*>(workspace);
+  int32_t n = slices, stride = 1;
+  if (slices > 16) {                                  // first level: every 16 slices into the first of them
+    const unsigned chunks = (unsigned)((slices + 15) / 16);
+    hipLaunchKernelGGL(k_sum_slices<false>, dim3(rblocks, chunks), dim3(256), 0, stream, part, whole, (uint32_t)rest,
+                       slices, 16, 1, tiles_k, bk4, K, out);
+    n = (int32_t)chunks;
+    stride = 16;
+  }
+  hipLaunchKernelGGL(k_sum_slices<true>, dim3(rblocks, 1), dim3(256), 0, stream, part, whole, (uint32_t)rest, slices, n,
+                     stride, tiles_k, bk4, K, out);
   return hipGetLastError();
 }
