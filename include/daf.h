@@ -318,7 +318,7 @@ int daf_unpack_relu_backward(const daf_plan_t* plan, const uint32_t* words, cons
  *                (partial sums when m is split over several work-groups; may be NULL if 0).
  *
  * Errors: DAF_EINVAL (null or misaligned pointer, K not dividing the element count, missing
- * workspace); DAF_EUNSUPPORTED (M % 32, N % 256, K % 64 or K % group_size
+ * workspace); DAF_EUNSUPPORTED (M % 32, N % 64, K % 64 or K % group_size
  * non-zero; N or K of 2^24 or more; 2^30 or more packed words); DAF_EDEVICE.  daf_unpack_matmul_workspace_bytes returns -1 for such shapes.
  */
 int64_t daf_unpack_matmul_workspace_bytes(const daf_plan_t* plan, int64_t N, int64_t K);

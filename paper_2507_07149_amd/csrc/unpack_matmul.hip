@@ -154,7 +154,8 @@ __device__ __forceinline__ uint32_t narrow16_pair(float lo, float hi) {
   }
 }
 
-template <int DT, bool MIXED, int BK>
+// PARTIAL_N: N is not a multiple of 256 (see n_valid below); otherwise those checks are compiled out.
+template <int DT, bool MIXED, int BK, bool PARTIAL_N>
 __global__ __launch_bounds__((TileB<BK, (DT == kF32 ? 4 : 2)>::kThreads), (BK > 128 ? 1 : 2)) void k_unpack_matmul(
     const uint32_t* __restrict__ words, const float* __restrict__ mn, const float* __restrict__ scale,
     const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, uint32_t uniform_bits, int32_t gs,
@@ -193,6 +194,10 @@ __global__ __launch_bounds__((TileB<BK, (DT == kF32 ? 4 : 2)>::kThreads), (BK > 
   const uint32_t tile = sliced ? whole + ti : ti;
   const uint32_t tn = tile / (uint32_t)tiles_k, tk = tile - tn * (uint32_t)tiles_k;
   const int64_t n0 = (int64_t)tn * kBN, k0 = (int64_t)tk * BK;
+  // The last tile of n may reach past the output (N is a multiple of 64, not of 256): the waves
+  // whose 64 columns lie outside take part in the loads and the tile construction but run no
+  // products and store nothing; the chunks of grad_y outside are read from column 0 instead.
+  const uint32_t n_valid = PARTIAL_N ? (uint32_t)((N - n0) < kBN ? (N - n0) : kBN) : (uint32_t)kBN;
   // The steps of m are dealt out to the slices as evenly as whole steps allow.
   const int all_steps = (int)(M / kBM);
   const int per = sliced ? all_steps / slices : all_steps, extra = sliced ? all_steps % slices : 0;
@@ -213,7 +218,7 @@ __global__ __launch_bounds__((TileB<BK, (DT == kF32 ? 4 : 2)>::kThreads), (BK > 
   const uint32_t in_group = k_col - gk * (uint32_t)gs;                  // multiple of 8
   const uint32_t wpgb = (uint32_t)gs >> 5;                              // words per group and bit of width
   const char* gy_base = reinterpret_cast<const char*>(grad_y) + (m_begin * (int64_t)row_bytes + n0 * ES);
-  const uint32_t gy_voff = ((uint32_t)kR * rq) * row_bytes + 16u * cg;
+  const uint32_t gy_voff = ((uint32_t)kR * rq) * row_bytes + (cg * (16u / ES) < n_valid ? 16u * cg : 0u);
   const int64_t g_step0 = m_begin * (int64_t)gpr;                        // uniform; + 32*gpr per step
 
   // The per-group constants are fetched once per work-group and step, one group per thread
@@ -293,6 +298,7 @@ __global__ __launch_bounds__((TileB<BK, (DT == kF32 ? 4 : 2)>::kThreads), (BK > 
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
   const uint32_t wn = wave & 3u, wk = wave >> 2;    // (wk = 0 except for the 256-column tile)
+  const bool wave_valid = !PARTIAL_N || 64u * wn < n_valid;   // (uniform per wave)
   const uint32_t li = lane & 31u, lg = lane >> 5;
   // Operand reads, 16-bit formats: lane l of 16-lane group G = l / 16 addresses row
   // 8*(l/32) + (l%16)/4 (plus 16 per sub-step, plus 4 for the second half of the operand) and
@@ -379,7 +385,9 @@ __global__ __launch_bounds__((TileB<BK, (DT == kF32 ? 4 : 2)>::kThreads), (BK > 
     const char* b_lds = lds[buf] + b_read;
 #pragma unroll
     for (int ss = 0; ss < 2; ++ss) {                // two halves of the step, a half of the next tiles built in each
-      if constexpr (ES == 2) {
+      if (!wave_valid) {                            // (a wave outside the output only helps to build the tiles)
+        build_half(next, lds[buf ^ 1], ss, ring(at, 1));
+      } else if constexpr (ES == 2) {
         uint4 a[2], b[kJ];
 #pragma unroll
         for (int i = 0; i < 2; ++i) a[i] = operand_tr(a_lds + ss * 16 * kRowA + i * 64, kRowA);
@@ -462,6 +470,7 @@ __global__ __launch_bounds__((TileB<BK, (DT == kF32 ? 4 : 2)>::kThreads), (BK > 
   // ---- epilogue: register r of a 32 x 32 block is row 8*(r/4) + 4*(lane/32) + r%4, column lane%32 ----
   float* dst = sliced ? partial + ((int64_t)slice * count + ti) * (int64_t)(kBN * BK) : out + n0 * K + k0;
   const int64_t ld = sliced ? BK : K;
+  if (!wave_valid) return;
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -483,11 +492,15 @@ __global__ __launch_bounds__((TileB<BK, (DT == kF32 ? 4 : 2)>::kThreads), (BK > 
 template <bool TO_OUT>
 __global__ __launch_bounds__(256) void k_sum_slices(float4* __restrict__ partial, uint32_t whole, uint32_t count,
                                                     int32_t slices, int32_t n, int32_t stride, int32_t tiles_k,
-                                                    int32_t bk4, int64_t K, float* __restrict__ out) {
+                                                    int32_t bk4, int64_t N, int64_t K, float* __restrict__ out) {
   const uint32_t strips = (uint32_t)(kBN * bk4) / 256u;           // work-groups per tile
   const uint32_t ti = blockIdx.x / strips;
   const uint32_t e = (blockIdx.x - ti * strips) * 256u + threadIdx.x;   // float4 index inside the tile
   const int64_t tile4 = (int64_t)kBN * bk4;
+  const uint32_t tile = whole + ti;
+  const uint32_t tn = tile / (uint32_t)tiles_k, tk = tile - tn * (uint32_t)tiles_k;
+  const uint32_t row = e / (uint32_t)bk4, col4 = e - row * (uint32_t)bk4;
+  if ((int64_t)tn * kBN + row >= N) return;          // rows of the last tile of n past the output
   const int32_t first = (int32_t)blockIdx.y * n * stride;
   float4* p0 = partial + ((int64_t)first * count + ti) * tile4 + e;
   float4 s = *p0;
@@ -496,9 +509,6 @@ __global__ __launch_bounds__(256) void k_sum_slices(float4* __restrict__ partial
     s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
   }
   if (TO_OUT) {
-    const uint32_t tile = whole + ti;
-    const uint32_t tn = tile / (uint32_t)tiles_k, tk = tile - tn * (uint32_t)tiles_k;
-    const uint32_t row = e / (uint32_t)bk4, col4 = e - row * (uint32_t)bk4;
     float* dst = out + ((int64_t)tn * kBN + row) * K + (int64_t)tk * (bk4 * 4) + 4 * col4;
     *reinterpret_cast<float4*>(dst) = s;
   } else {
@@ -517,7 +527,7 @@ constexpr int kStepM = 32;
 // enough of them to fill the chip without slicing m, else the 128-column one (measured: LLM
 // shape 780 -> 860 TFLOP/s with 256 columns, ViT shape 0.30 against 0.29 ms).
 static int tile_bk(int64_t N, int64_t K) {
-  if (K % 256 == 0 && (N / kBN) * (K / 256) >= 256) return 256;
+  if (K % 256 == 0 && ((N + kBN - 1) / kBN) * (K / 256) >= 256) return 256;
   return K % 128 == 0 ? 128 : 64;
 }
 
@@ -538,7 +548,7 @@ struct Schedule {
 Schedule schedule(int64_t M, int64_t N, int64_t K, int es) {   // es: bytes per element (2 or 4)
   Schedule sc;
   sc.bk = tile_bk(N, K);
-  sc.tiles = (N / kBN) * (K / sc.bk);
+  sc.tiles = ((N + kBN - 1) / kBN) * (K / sc.bk);
   const int64_t slots = 256 * (sc.bk == 256 ? 1 : sc.bk == 128 ? 2 : 3);
   const int64_t steps = M / kStepM;
   // one work-group over all of m, per 32 values of m: the 16-bit kernels are bound by instruction
@@ -581,8 +591,9 @@ int64_t daf_unpack_matmul_workspace_size(int64_t M, int64_t N, int64_t K) {
 
 bool daf_unpack_matmul_shape_ok(int64_t M, int64_t N, int64_t K, int32_t gs) {
   // N and K below 2^24: the per-thread parts of the addresses are 32-bit byte offsets.
-  return M > 0 && N > 0 && K > 0 && M % kStepM == 0 && N % kBN == 0 && K % 64 == 0 && K % gs == 0 &&
-         N < (1 << 24) && K < (1 << 24) && (N / kBN) * (K / 64) * 16 < (int64_t)1 << 31;
+  // (N a multiple of 64: a wave's 64 columns of n are inside the output or outside it as a whole)
+  return M > 0 && N > 0 && K > 0 && M % kStepM == 0 && N % 64 == 0 && K % 64 == 0 && K % gs == 0 &&
+         N < (1 << 24) && K < (1 << 24) && ((N + kBN - 1) / kBN) * (K / 64) * 16 < (int64_t)1 << 31;
 }
 
 hipError_t daf_launch_unpack_matmul(const daf_plan_t* p, const uint32_t* words, const float* mn, const float* scale,
@@ -591,18 +602,22 @@ hipError_t daf_launch_unpack_matmul(const daf_plan_t* p, const uint32_t* words, 
   const int64_t M = p->n / K;
   const Schedule sc = schedule(M, N, K, dtype == daf::kF32 ? 4 : 2);
   const int bk = sc.bk;
-  const int32_t tiles_n = (int32_t)(N / kBN), tiles_k = (int32_t)(K / bk);
+  const int32_t tiles_n = (int32_t)((N + kBN - 1) / kBN), tiles_k = (int32_t)(K / bk);
   const int64_t rest = sc.tiles - sc.whole;
   const unsigned blocks = (unsigned)(sc.whole + rest * sc.slices);
   const uint32_t whole = (uint32_t)sc.whole;
   const int32_t slices = sc.slices;
   const void* gy = grad_y;
-#define DAF_LAUNCH(DT, MIXED, BK)                                                                                 \
-  hipLaunchKernelGGL((k_unpack_matmul<DT, MIXED, BK>), dim3(blocks),                                              \
+#define DAF_LAUNCH_P(DT, MIXED, BK, PARTIAL)                                                                               \
+  hipLaunchKernelGGL((k_unpack_matmul<DT, MIXED, BK, PARTIAL>), dim3(blocks),                                     \
                      dim3(TileB<BK, DT == daf::kF32 ? 4 : 2>::kThreads), 0, stream, words,                        \
                      mn, scale,                                                                                   \
                      d_bits, p->d_off, (uint32_t)p->uniform_bits, p->group_size, gy, M, N, K, tiles_n, tiles_k,   \
                      whole, slices, out, workspace)
+#define DAF_LAUNCH(DT, MIXED, BK)                                                                                 \
+  do {                                                                                                            \
+    if (N % kBN == 0) DAF_LAUNCH_P(DT, MIXED, BK, false); else DAF_LAUNCH_P(DT, MIXED, BK, true);                 \
+  } while (0)
 #define DAF_LAUNCH_BK(DT, MIXED)                                                                                  \
   do {                                                                                                            \
     if (bk == 256) DAF_LAUNCH(DT, MIXED, 256);                                                                    \
@@ -620,6 +635,7 @@ hipError_t daf_launch_unpack_matmul(const daf_plan_t* p, const uint32_t* words, 
   }
 #undef DAF_LAUNCH_BK
 #undef DAF_LAUNCH
+#undef DAF_LAUNCH_P
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || rest == 0) return e;
   const int32_t bk4 = bk / 4;
@@ -629,11 +645,11 @@ hipError_t daf_launch_unpack_matmul(const daf_plan_t* p, const uint32_t* words, 
   if (slices > 16) {                                  // first level: every 16 slices into the first of them
     const unsigned chunks = (unsigned)((slices + 15) / 16);
     hipLaunchKernelGGL(k_sum_slices<false>, dim3(rblocks, chunks), dim3(256), 0, stream, part, whole, (uint32_t)rest,
-                       slices, 16, 1, tiles_k, bk4, K, out);
+                       slices, 16, 1, tiles_k, bk4, N, K, out);
     n = (int32_t)chunks;
     stride = 16;
   }
   hipLaunchKernelGGL(k_sum_slices<true>, dim3(rblocks, 1), dim3(256), 0, stream, part, whole, (uint32_t)rest, slices, n,
-                     stride, tiles_k, bk4, K, out);
+                     stride, tiles_k, bk4, N, K, out);
   return hipGetLastError();
 }

@@ -70,6 +70,17 @@ def test_grad_weight_shapes(env, shape, bits):
     _case(daf, orc, M, N, K, 64, bits, BF16, 11)
 
 
+# N a multiple of 64 but not of 256: the last tile of n has waves outside the output
+@pytest.mark.parametrize("case", [(256, 64, 256, 64, "mixed", BF16), (128, 320, 384, 32, 2, F16), (512, 192, 128, 128, "mixed", F32),
+                                  (8192, 64, 256, 64, 4, F32), (2048, 448, 192, 64, "mixed", BF16),
+                                  (32, 4160, 4096, 64, "mixed", BF16)])       # the last: 256-column tile, 17 tiles of n
+def test_grad_weight_n_not_a_multiple_of_256(env, case):
+    daf, orc = env
+    M, N, K, gs, bits, dtype = case
+    print("case n % 256 != 0", case, flush=True)
+    _case(daf, orc, M, N, K, gs, bits, dtype, 29)
+
+
 def test_grad_weight_tall_and_skinny(env):
     """A long reduction into one or two tiles: m is cut into far more than 16 slices."""
     daf, orc = env
@@ -121,7 +132,7 @@ def test_grad_weight_argument_errors(env):
     gy = torch.zeros(512, 256, dtype=torch.bfloat16, device="cuda:0")
     out = torch.zeros(256, 256, device="cuda:0")
     assert daf.daf_unpack_matmul_workspace_bytes(plan, 256, 256) > 0
-    assert daf.daf_unpack_matmul_workspace_bytes(plan, 100, 256) == -1       # N not a multiple of 256
+    assert daf.daf_unpack_matmul_workspace_bytes(plan, 100, 256) == -1       # N not a multiple of 64
     assert daf.daf_unpack_matmul_workspace_bytes(plan, 256, 96) == -1        # K does not divide the tensor
     with pytest.raises(daf.DafError) as e:                                    # split, but no workspace
         daf.daf_unpack_matmul_grad_weight(plan, words, mn, mn, gy, out, None)
