@@ -430,13 +430,15 @@ __global__ __launch_bounds__((TileB<BK, (DT == kF32 ? 4 : 2)>::kThreads), (BK > 
   Stage<kP, kR> st[2];
   Addr<kP> ad[2];
   if (meta_wave) {
+    uint4 m0[5];                                    // all requested before the first is stored: one load latency
 #pragma unroll
     for (int q = 0; q < 5; ++q) {
-      uint4 m0 = make_uint4(0u, 0u, 0u, 0u);
-      meta_load(m0, g_step0 + (int64_t)min(q, steps - 1) * g_stride);
-      meta_store(m0, (uint32_t)q);
+      m0[q] = make_uint4(0u, 0u, 0u, 0u);
+      meta_load(m0[q], g_step0 + (int64_t)min(q, steps - 1) * g_stride);
     }
     meta_load(mv, g_step0 + (int64_t)min(5, steps - 1) * g_stride);
+#pragma unroll
+    for (int q = 0; q < 5; ++q) meta_store(m0[q], (uint32_t)q);
   }
   gu_meta = g_step0 + (int64_t)min(6, steps - 1) * g_stride;
   __syncthreads();
