@@ -307,19 +307,23 @@ int daf_unpack_relu_backward(const daf_plan_t* plan, const uint32_t* words, cons
  *     out_grad_w[n, k] = sum_m grad_y[m, n] * xhat[m, k]        (binary32, [N, K] row-major)
  * where xhat[m, k] is exactly the value daf_unpack_dequantize would write in `dtype`.  The words
  * are unpacked and dequantized tile by tile inside the product (matrix cores: 16-bit formats
- * with binary32 accumulation, binary32 tensors with binary32 products) and xhat is never written to memory (Sec. 3.3 / Sec. 4.3.1: unpack next to the
- * consumer).  The order of the additions differs from a plain loop, so the result agrees with a
- * double-precision evaluation to about M * 2^-24 relative to sum_m |grad_y| * |xhat|.
+ * with binary32 accumulation, binary32 tensors with binary32 products) and xhat is never
+ * written to memory (Sec. 3.3 / Sec. 4.3.1: unpack next to the consumer).  The order of the
+ * additions differs from a plain loop, so the result agrees with a double-precision evaluation
+ * to about M * 2^-24 relative to sum_m |grad_y| * |xhat|.  The result is deterministic: the
+ * same call gives the same bits.
  *
  *   grad_y       DEVICE, M*N elements of dtype, 16-byte aligned.
  *   N, K         columns of grad_y; columns of x (must divide the plan's element count).
  *   out_grad_w   DEVICE, N*K floats, 16-byte aligned.
  *   workspace    DEVICE, daf_unpack_matmul_workspace_bytes(plan, N, K) bytes, 16-byte aligned
- *                (partial sums when m is split over several work-groups; may be NULL if 0).
+ *                (partial sums when m is split over several work-groups; may be NULL if 0; the
+ *                size is the same for every element format).
  *
  * Errors: DAF_EINVAL (null or misaligned pointer, K not dividing the element count, missing
- * workspace); DAF_EUNSUPPORTED (M % 32, N % 64, K % 64 or K % group_size
- * non-zero; N or K of 2^24 or more; 2^30 or more packed words); DAF_EDEVICE.  daf_unpack_matmul_workspace_bytes returns -1 for such shapes.
+ * workspace); DAF_EUNSUPPORTED (M % 32, N % 64, K % 64 or K % group_size non-zero; N or K of
+ * 2^24 or more; 2^30 or more packed words); DAF_EDEVICE.  daf_unpack_matmul_workspace_bytes
+ * returns -1 for such shapes.
  */
 int64_t daf_unpack_matmul_workspace_bytes(const daf_plan_t* plan, int64_t N, int64_t K);
 int daf_unpack_matmul_grad_weight(const daf_plan_t* plan, const uint32_t* words, const float* min, const float* scale,
