@@ -1,0 +1,50 @@
+"""Seeded random sweeps over the argument space of the main entry points, each case against
+the oracle: sizes with ragged tails, group sizes that are not powers of two, every element
+format and width; and, for the fused weight gradient, groups that straddle the tiles of k."""
+import numpy as np
+import pytest
+import torch
+
+from daf_inputs import BF16, F16, F32, Workload, to_numpy_bits, torch_dtype
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def H():
+    from tests import hip_harness
+    assert torch.cuda.is_available()
+    return hip_harness
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_quantize_dequantize_random_cases(H, seed):
+    rng = np.random.default_rng(1000 + seed)
+    for case in range(12):
+        dtype = int(rng.choice([F32, F16, BF16]))
+        gs = int(rng.choice([32, 64, 96, 128, 160, 256, 288, 512, 1024, 4096, 4128, 8192]))
+        n = int(rng.integers(1, 9)) * gs * int(rng.integers(1, 40)) + int(rng.integers(0, gs))
+        n = max(n, 1)
+        G = (n + gs - 1) // gs
+        kind = int(rng.integers(0, 5))
+        bits = (rng.choice([1, 2, 4, 8], G).astype(np.uint8) if kind == 4 else np.array([[1, 2, 4, 8][kind]], np.uint8))
+        g = torch.Generator().manual_seed(int(rng.integers(0, 1 << 30)))
+        x = (torch.randn(n, generator=g) * float(np.exp(rng.normal(0, 3)))).to(torch_dtype(dtype))
+        x[torch.isinf(x.float())] = 0
+        w = Workload(f"sweep{seed}_{case}_dt{dtype}_gs{gs}_n{n}_k{kind}", x, dtype, gs, bits, int(rng.integers(0, 1 << 40)))
+        print("case", w.name, flush=True)
+        H.assert_full_parity(w, H.run_hip(w))
+
+
+@pytest.mark.parametrize("case", [(64, 256, 960, 96, "mixed", BF16), (96, 256, 960, 160, 4, F16), (64, 320, 960, 192, "mixed", F32),
+                                  (128, 256, 384, 96, "mixed", BF16), (64, 256, 1152, 288, 2, F32), (32, 4096, 4608, 96, "mixed", BF16),
+                                  (160, 256, 768, 384, "mixed", F16), (64, 256, 2048, 1024, 8, BF16)])
+def test_grad_weight_groups_that_straddle_tiles(case):
+    """Group sizes that are not powers of two (and groups wider than a tile of k): a tile row then
+    reads two to four groups, or a part of one."""
+    import paper_2507_07149_amd as daf
+    from oracle import daf_oracle as orc
+    from tests.test_gpu_unpack_matmul import _case
+    M, N, K, gs, bits, dtype = case
+    print("case straddle", case, flush=True)
+    _case(daf, orc, M, N, K, gs, bits, dtype, 31)
