@@ -48,3 +48,43 @@ def test_grad_weight_groups_that_straddle_tiles(case):
     M, N, K, gs, bits, dtype = case
     print("case straddle", case, flush=True)
     _case(daf, orc, M, N, K, gs, bits, dtype, 31)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_list_calls_random_lists(seed):
+    """Random lists of up to 40 tensors (more than one launch's 32 descriptors) of one format:
+    sizes from one element to a few tiles, any group size and width kind in any order."""
+    import paper_2507_07149_amd as daf
+    from oracle import daf_oracle as orc
+    from tests.test_gpu_batch import _roundtrip
+    rng = np.random.default_rng(2000 + seed)
+    dtype = [F32, F16, BF16, F32][seed]
+    specs = []
+    for _ in range(int(rng.integers(3, 41))):
+        gs = int(rng.choice([32, 64, 96, 128, 256, 1024, 4096, 8192]))
+        n = int(rng.integers(1, 4)) * gs * int(rng.integers(1, 12)) + int(rng.integers(0, gs))
+        specs.append((n, gs, [1, 2, 4, 8, "mixed"][int(rng.integers(0, 5))]))
+    _roundtrip(daf, orc, dtype, specs)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_fused_relu_random_cases(seed):
+    import paper_2507_07149_amd as daf
+    from oracle import daf_oracle as orc
+    from tests.test_gpu_fused_relu import _check, _run
+    rng = np.random.default_rng(3000 + seed)
+    for case in range(8):
+        dtype = int(rng.choice([F32, F16, BF16]))
+        gs = int(rng.choice([32, 64, 96, 128, 256, 1024, 4096]))
+        n = int(rng.integers(1, 6)) * gs * int(rng.integers(1, 30)) + int(rng.integers(0, gs))
+        G = (n + gs - 1) // gs
+        kind = int(rng.integers(0, 5))
+        b = rng.choice([1, 2, 4, 8], G).astype(np.uint8) if kind == 4 else np.array([[1, 2, 4, 8][kind]], np.uint8)
+        g = torch.Generator().manual_seed(int(rng.integers(0, 1 << 30)))
+        z = torch.randn(n, generator=g).to(torch_dtype(dtype))
+        plan = daf.daf_plan((n,), gs, torch.from_numpy(b).cuda() if b.size > 1 else int(b[0]))
+        sd = int(rng.integers(0, 1 << 40))
+        in_place = bool(rng.integers(0, 2))
+        print("case relu sweep", seed, case, dtype, gs, n, kind, in_place, flush=True)
+        _check(orc, z, dtype, gs, b, sd, _run(daf, plan, z.clone(), sd, in_place))
+        plan.destroy()
