@@ -67,6 +67,10 @@ def parse():
     ap.add_argument("--fused-relu", action="store_true",
                     help="time daf_relu_quantize_pack (activation function fused into the quantize pass) "
                          "against a separate relu kernel followed by daf_quantize_pack")
+    ap.add_argument("--output-policy", action="store_true",
+                    help="time daf_unpack_dequantize alone and followed by a kernel that reads its output "
+                         "(daf_group_minmax), with streaming and with cached output stores "
+                         "(daf_plan_set_output_cached)")
     ap.add_argument("--page-store", action="store_true",
                     help="time the host-side paged activation store (red-black trees against re-sorting, and the "
                          "plain model) on synthetic iterations; uses no GPU")
@@ -301,6 +305,61 @@ def main():
                           "max_rel_diff_vs_library_output": round(rel, 5),
                           "roofline": {"bound": "mfma", "achieved": round(ach, 1), "peak": peak, "unit": "TFLOP/s",
                                        "frac": round(ach / peak, 4), "traffic": None, "kernel": "k_unpack_matmul"}}))
+        return
+
+    if args.output_policy:
+        workloads = make_config(args.config)
+        in_bytes = sum(w.numel * w.x.element_size() for w in workloads)
+        n_sets = 1 if in_bytes >= ROTATE_BYTES else -(-ROTATE_BYTES // in_bytes)
+        plans, sets = [], []
+        for w in workloads:
+            plans.append(daf.daf_plan(tuple(w.x.shape), w.group_size,
+                                      int(w.bits[0]) if w.bits.size == 1 else torch.from_numpy(w.bits).to(dev)))
+        for _ in range(n_sets):
+            bufs = []
+            for w, p in zip(workloads, plans):
+                b = dict(x=w.x.reshape(-1).to(dev), words=torch.empty(p.packed_words, dtype=torch.int32, device=dev),
+                         mn=torch.empty(p.num_groups, device=dev), sc=torch.empty(p.num_groups, device=dev),
+                         lo=torch.empty(p.num_groups, device=dev), hi=torch.empty(p.num_groups, device=dev))
+                daf.daf_quantize_pack(p, b["x"], w.seed, b["words"], b["mn"], b["sc"])
+                bufs.append(b)
+            sets.append(bufs)
+
+        def unpack(k):
+            for (p, b) in zip(plans, sets[k]):
+                daf.daf_unpack_dequantize(p, b["words"], b["mn"], b["sc"], b["x"])
+
+        def reader(k):
+            for (p, b) in zip(plans, sets[k]):
+                daf.daf_group_minmax(p, b["x"], b["lo"], b["hi"])
+
+        def pair(k):
+            for (p, b) in zip(plans, sets[k]):
+                daf.daf_unpack_dequantize(p, b["words"], b["mn"], b["sc"], b["x"])
+                daf.daf_group_minmax(p, b["x"], b["lo"], b["hi"])
+
+        def timed(fn):
+            for i in range(args.warmup):
+                fn(i % n_sets)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for i in range(args.steps):
+                fn(i % n_sets)
+            e1.record()
+            torch.cuda.synchronize()
+            return round(e0.elapsed_time(e1) / args.steps, 4)
+
+        res = {"reader_alone_ms": timed(reader)}
+        for cached in (False, True):
+            for p in plans:
+                p.set_output_cached(cached)
+            key = "cached" if cached else "streaming"
+            res[key] = {"unpack_alone_ms": timed(unpack), "unpack_then_reader_ms": timed(pair)}
+        print(json.dumps({"metric": "unpack+dequantize output store policy", "unit": "ms", "n_gpus": 1,
+                          "steps": args.steps, "warmup": args.warmup, "data": "synthetic",
+                          "config": {"workload": CONFIG_NAMES[args.config], "tensors": len(workloads),
+                                     "buffer_sets": n_sets, "activation_bytes": in_bytes}, **res}))
         return
 
     if args.fused_relu:

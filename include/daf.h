@@ -93,6 +93,21 @@ int32_t daf_plan_uniform_bits(const daf_plan_t* plan);   /* the shared width, or
  * Works for uniform plans too (offsets are then computed, not stored). */
 int daf_plan_copy_offsets(const daf_plan_t* plan, uint32_t* out_off);
 
+/* How daf_unpack_dequantize, daf_unpack_dequantize_batch and daf_unpack_relu_backward write
+ * their output for this plan (unpacking next to the consumer, Sec. 3.3): the values are the
+ * same either way, only the store instruction differs.
+ *   cached = 0 (default)  streaming stores: the call alone is fastest (up to 16 % faster than
+ *                         with cached stores); right when the consumer is compute-bound (a
+ *                         matrix product), runs later, or the output is small or very large.
+ *   cached = 1            ordinary stores: the call alone is slower, but a memory-bound kernel
+ *                         that reads the output immediately afterwards finds part of it in
+ *                         the caches.  Measured to pay only for outputs of roughly 80-200 MB
+ *                         (the two kernels together 4-12 % faster); at 50 MB and at 700 MB and
+ *                         more it is equal or slower than the default.
+ * A plain host write: not to be changed while a call on the plan is being enqueued from
+ * another thread.  Errors: DAF_EINVAL (NULL plan, cached not 0 or 1). */
+int daf_plan_set_output_cached(daf_plan_t* plan, int cached);
+
 /* Frees the plan and the device memory it owns.  NULL is allowed. */
 void daf_plan_destroy(daf_plan_t* plan);
 

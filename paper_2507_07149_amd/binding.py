@@ -47,6 +47,8 @@ def load_library():
         getattr(L, name).restype = res
     L.daf_plan_copy_offsets.argtypes = [vp, vp]
     L.daf_plan_copy_offsets.restype = c.c_int
+    L.daf_plan_set_output_cached.argtypes = [vp, c.c_int]
+    L.daf_plan_set_output_cached.restype = c.c_int
     L.daf_plan_destroy.argtypes = [vp]
     L.daf_plan_destroy.restype = None
     L.daf_quantize_pack.argtypes = [vp, vp, c.c_int, u64, vp, vp, vp, vp]
@@ -114,6 +116,11 @@ class Plan:
     packed_words = property(lambda s: int(load_library().daf_plan_packed_words(s.handle)))
     group_size = property(lambda s: int(load_library().daf_plan_group_size(s.handle)))
     uniform_bits = property(lambda s: int(load_library().daf_plan_uniform_bits(s.handle)))
+
+    def set_output_cached(self, cached: bool) -> None:
+        rc = load_library().daf_plan_set_output_cached(self.handle, 1 if cached else 0)
+        if rc != 0:
+            raise DafError(rc, "daf_plan_set_output_cached")
 
     def offsets(self) -> torch.Tensor:
         out = torch.empty(self.num_groups, dtype=torch.int32)

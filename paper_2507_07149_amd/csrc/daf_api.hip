@@ -76,6 +76,7 @@ int daf_plan(const int64_t* shape, int ndim, int32_t group_size, const uint8_t* 
   p->d_off = nullptr;
   p->d_big_scratch = nullptr;
   p->device = -1;
+  p->output_cached = 0;
   int64_t big_bytes = 0;
   const bool big = daf_plan_needs_big_scratch(n, group_size, G, &big_bytes);
 
@@ -134,6 +135,12 @@ int64_t daf_plan_num_groups(const daf_plan_t* plan) { return plan ? plan->num_gr
 int64_t daf_plan_packed_words(const daf_plan_t* plan) { return plan ? plan->total_words : -1; }
 int32_t daf_plan_group_size(const daf_plan_t* plan) { return plan ? plan->group_size : -1; }
 int32_t daf_plan_uniform_bits(const daf_plan_t* plan) { return plan ? plan->uniform_bits : -1; }
+
+int daf_plan_set_output_cached(daf_plan_t* plan, int cached) {
+  if (plan == nullptr || (cached != 0 && cached != 1)) return DAF_EINVAL;
+  plan->output_cached = cached;
+  return DAF_OK;
+}
 
 int daf_plan_copy_offsets(const daf_plan_t* plan, uint32_t* out_off) {
   if (plan == nullptr || out_off == nullptr) return DAF_EINVAL;

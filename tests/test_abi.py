@@ -64,6 +64,9 @@ def test_uniform_plan_needs_no_device(lib):
     assert rc == 0 and lib.daf_plan_packed_words(p) == 5
     off = (ctypes.c_uint32 * 2)()
     assert lib.daf_plan_copy_offsets(p, off) == 0 and list(off) == [0, 4]
+    assert lib.daf_plan_set_output_cached(p, 1) == 0 and lib.daf_plan_set_output_cached(p, 0) == 0
+    assert lib.daf_plan_set_output_cached(p, 2) == -1 and lib.daf_plan_set_output_cached(p, -1) == -1
+    assert lib.daf_plan_set_output_cached(None, 1) == -1
     lib.daf_plan_destroy(p)
     lib.daf_plan_destroy(None)
 
