@@ -566,10 +566,17 @@ def main():
     dk = kernel_pass("d", batch, n_batches)
     qk_ms, dk_ms = qk["median"], dk["median"]
     alg = sum(algorithmic_bytes(w, p.packed_words) for w, p in zip(workloads, plans))
-    # groups longer than a 4096-element tile need their statistics before any element can be
-    # quantized: the quantize direction then reads the activation twice
-    alg_q = alg + sum(w.numel * w.x.element_size() for w in workloads if w.group_size > 4096)
+    # groups longer than 32768 elements (or fewer than 256 groups of a whole number of 4096-element
+    # tiles) need their statistics before any element can be quantized: the quantize direction
+    # then reads the activation twice; shorter groups are kept in registers by one workgroup
+    def two_reads(w):
+        gs = w.group_size
+        return gs > 32768 or (gs > 4096 and gs % 4096 == 0 and w.numel // gs < 256)
+    alg_q = alg + sum(w.numel * w.x.element_size() for w in workloads if two_reads(w))
     value = 2 * in_bytes / (ms_per_step * 1e-3) / 1e9
+    gs0 = workloads[0].group_size
+    q_kernel_name = ("k_quantize_pack_tile" if gs0 & (gs0 - 1) == 0 and gs0 <= 4096 or two_reads(workloads[0])
+                     else "k_quantize_pack_units" if gs0 <= 4096 else "k_quantize_pack_long")
 
     traffic = MEASURED_TRAFFIC.get(args.config, (None, None)) if args.group_size is None else (None, None)
 
@@ -595,7 +602,7 @@ def main():
                               "kernel_ms_mean": round(dk["mean"], 4),
                               "output_GBps": round(in_bytes / dk_ms / 1e6, 1), "algorithmic_bytes": alg,
                               "launches": 1 if batched else len(workloads)},
-        "roofline": dict(roof(qk_ms, traffic[0], alg_q), kernel="k_quantize_pack_tile"),
+        "roofline": dict(roof(qk_ms, traffic[0], alg_q), kernel=q_kernel_name),
         "roofline_unpack_dequantize": dict(roof(dk_ms, traffic[1], alg), kernel="k_unpack_dequantize_chunk"),
     }
 

@@ -123,11 +123,20 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_group(
     const uint32_t woff = uniform_bits ? (uint32_t)(g * (((int64_t)gs * uniform_bits) >> 5)) : off[g];
 
     float mn = load_elem<DT, RELU>(x, lo), mx = mn;        // element 0 exists in every group
-    for (int32_t j = lane; j < len; j += kWave) {
-      const float v = load_elem<DT, RELU>(x, lo + j);
-      if (RELU) store_elem<DT>(out_y, lo + j, v);          // every element passes here exactly once
-      mn = fminf(mn, v);
-      mx = fmaxf(mx, v);
+    for (int32_t j0 = lane; j0 < len; j0 += 8 * kWave) {    // eight loads in flight per lane
+      float v[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const int32_t j = j0 + q * kWave;
+        v[q] = load_elem<DT, RELU>(x, lo + (j < len ? j : j0));
+      }
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const int32_t j = j0 + q * kWave;
+        if (RELU && j < len) store_elem<DT>(out_y, lo + j, v[q]);   // every element passes here exactly once
+        mn = fminf(mn, v[q]);
+        mx = fmaxf(mx, v[q]);
+      }
     }
     for (int o = 32; o > 0; o >>= 1) {
       mn = fminf(mn, __shfl_xor(mn, o));
@@ -142,31 +151,38 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_group(
     const int32_t n_words = (int32_t)(((int64_t)len * b + 31) >> 5);
     float err = 0.0f, mag = 0.0f;
     uint32_t var_i = 0u;
+    // A word's codes are taken 16 elements at a time (one Philox block; a word of 1-bit codes
+    // takes two rounds): all loads of a round are issued before any is used, so a lone long
+    // group costs one memory latency per round and not one per element.
+    const int32_t per_round = (int32_t)(cpw < 16u ? cpw : 16u);
     for (int32_t t = lane; t < n_words; t += kWave) {
       uint32_t word = 0;
-      uint64_t cur_blk = ~0ull;
-      uint4 rnd = make_uint4(0, 0, 0, 0);
-      for (uint32_t c = 0; c < cpw; ++c) {
-        const int32_t j = (int32_t)(t * cpw + c);
-        if (j >= len) break;
-        const uint64_t i = (uint64_t)(lo + j);
-        const uint64_t blk = i / kElemsPerPhilox;
-        if (blk != cur_blk) {
-          rnd = philox_block(blk, seed_lo, seed_hi);
-          cur_blk = blk;
-        }
-        const uint32_t slot = (uint32_t)(i % kElemsPerPhilox);
-        const uint32_t rw = (slot < 4) ? rnd.x : (slot < 8) ? rnd.y : (slot < 12) ? rnd.z : rnd.w;
-        const uint32_t r = (rw >> (8u * (slot & 3u))) & 0xFFu;
-        const float xv = load_elem<DT, RELU>(x, lo + j);     // z or y: max(., +0) gives y either way
-        int rt;
-        const int nc = neg_code<true>(xv, s.mn, s.inv, r, &rt);
-        word |= (uint32_t)(-nc) << (32u - b - c * b);
-        if (METRICS) {
-          const float d = xv - __builtin_fmaf((float)(-nc), s.scale, s.mn);
-          err = __builtin_fmaf(d, d, err);
-          mag = __builtin_fmaf(xv, xv, mag);
-          var_i += sr_variance_term(rt);
+      for (int32_t c0 = 0; c0 < (int32_t)cpw; c0 += 16) {
+        const int32_t j0 = t * (int32_t)cpw + c0;            // a multiple of per_round
+        if (j0 >= len) break;
+        const uint64_t i0 = (uint64_t)(lo + j0);
+        const uint4 rnd = philox_block(i0 / kElemsPerPhilox, seed_lo, seed_hi);
+        const uint32_t slot0 = (uint32_t)(i0 % kElemsPerPhilox);
+        float xv[16];
+#pragma unroll
+        for (int c = 0; c < 16; ++c)
+          xv[c] = (c < per_round && j0 + c < len) ? load_elem<DT, RELU>(x, lo + j0 + c) : 0.0f;   // z or y: max(., +0) gives y either way
+#pragma unroll
+        for (int c = 0; c < 16; ++c) {
+          if (c < per_round && j0 + c < len) {
+            const uint32_t slot = slot0 + (uint32_t)c;
+            const uint32_t rw = (slot < 4) ? rnd.x : (slot < 8) ? rnd.y : (slot < 12) ? rnd.z : rnd.w;
+            const uint32_t r = (rw >> (8u * (slot & 3u))) & 0xFFu;
+            int rt;
+            const int nc = neg_code<true>(xv[c], s.mn, s.inv, r, &rt);
+            word |= (uint32_t)(-nc) << (32u - b - (uint32_t)(c0 + c) * b);
+            if (METRICS) {
+              const float d = xv[c] - __builtin_fmaf((float)(-nc), s.scale, s.mn);
+              err = __builtin_fmaf(d, d, err);
+              mag = __builtin_fmaf(xv[c], xv[c], mag);
+              var_i += sr_variance_term(rt);
+            }
+          }
         }
       }
       words[woff + t] = word;
@@ -840,6 +856,444 @@ hipError_t launch_big(const daf_plan_t* p, const void* x, uint32_t seed_lo, uint
   return hipGetLastError();
 }
 
+// Drops the codes of one chunk (negated accumulators n0, n1 as quantize_chunk returns them) at
+// byte address `addr` of the staged word run: a nibble pair, a byte, a halfword or whole words.
+template <int EPL>
+__device__ __forceinline__ void stage_chunk(uint8_t* stage8, uint32_t addr, uint32_t b, uint32_t n0, uint32_t n1,
+                                            int lane) {
+  if (EPL == 4) {
+    const uint32_t acc = 0u - n0;
+    if (b == 1u) {           // 4 bits per lane: the even lane takes its odd neighbour's nibble
+      const uint32_t nb = dpp<kDppXor1>(acc, acc);
+      if ((lane & 1) == 0) stage8[addr] = (uint8_t)((acc << 4) | nb);
+    } else if (b == 2u) {
+      stage8[addr] = (uint8_t)acc;
+    } else if (b == 4u) {
+      *reinterpret_cast<uint16_t*>(stage8 + addr) = (uint16_t)acc;
+    } else {
+      *reinterpret_cast<uint32_t*>(stage8 + addr) = acc;
+    }
+  } else {
+    if (b == 8u) {
+      *reinterpret_cast<uint2*>(stage8 + addr) = make_uint2(0u - n0, 0u - n1);
+    } else {
+      const uint32_t both = 0u - ((n0 << (4u * b)) + n1);
+      if (b == 4u) {
+        *reinterpret_cast<uint32_t*>(stage8 + addr) = both;
+      } else if (b == 2u) {
+        *reinterpret_cast<uint16_t*>(stage8 + addr) = (uint16_t)both;
+      } else {
+        stage8[addr] = (uint8_t)both;
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Unit path: one wave per run of whole groups, for group sizes that are a multiple of 32
+// elements but not a power of two (a row of a transformer activation: 768, 3072, ...).
+// ------------------------------------------------------------------------------------------
+// A unit is 32 consecutive elements: an aligned run of 8 lanes (binary32) or 4 lanes (16-bit
+// formats) of one load.  A group is m units (3 <= m <= 128), a tile is k = 128 / m whole groups
+// (fewer in the tensor's last tile), at most 4096 elements as on the fast path; lane l of load u holds chunk u*64 + l of the tile
+// as far as the tile reaches (lanes past its end hold a copy of its last chunk and store
+// nothing).  Min and max are reduced to units with DPP, the units of a group are then combined
+// by 64 / k lanes (rounded down to a power of two) reading them from LDS.  Everything after
+// that is the fast path's: lane g finishes group g, every chunk is quantized against its
+// group's entry and staged, the tile's words leave as one run.
+template <int DT>
+struct UnitShape {
+  static constexpr int kEpl = ElemTraits<DT>::kPerLoad;
+  static constexpr int kLoads = 4096 / (kWave * kEpl);             // 16 (binary32) or 8 (16-bit)
+  static constexpr int kLanesLog2 = (DT == kF32) ? 3 : 2;          // log2 lanes (chunks) per unit
+  static constexpr int kUnitsPerLoad = kWave >> kLanesLog2;
+  static constexpr int kUnits = kLoads * kUnitsPerLoad;            // 128
+  static constexpr int kPhilox = 4096 / kElemsPerPhilox / kWave;   // Philox calls per lane
+  static_assert(kUnits == 128 && kLoads % 2 == 0, "unit tile");
+};
+
+template <int DT>
+struct alignas(16) UnitLds {
+  union {
+    uint8_t rand_bytes[4096];        // byte e serves tile element e; later the staged words
+    uint32_t stage[1024];
+  };
+  GroupInfo info[kWave];
+  float2 ustat[UnitShape<DT>::kUnits];   // (min, max) per unit
+};
+
+template <int DT, int B>
+__global__ __launch_bounds__(kThreads) void k_quantize_pack_units(
+    const u32x4* __restrict__ x, int64_t n_tiles, int32_t m, int32_t k_full, int32_t k_last, uint32_t magic,
+    int32_t part_log2,
+    const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, uint32_t seed_lo, uint32_t seed_hi,
+    uint32_t* __restrict__ words, float* __restrict__ out_min, float* __restrict__ out_scale) {
+  using S = UnitShape<DT>;
+  constexpr int kEpl = S::kEpl;
+  constexpr bool kMixed = (B == 0);
+  __shared__ UnitLds<DT> lds_all[kWavesPerBlock];
+
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t tile = (int64_t)blockIdx.x * kWavesPerBlock + wave_in_block;
+  if (tile >= n_tiles) return;
+  UnitLds<DT>& lds = lds_all[wave_in_block];
+  uint8_t* stage8 = reinterpret_cast<uint8_t*>(lds.stage);
+
+  const int k = (tile == n_tiles - 1) ? k_last : k_full;     // the last tile may hold fewer groups
+  const uint32_t units = (uint32_t)(k * m);                  // units of the tile, <= 128
+  const uint32_t n_chunks = units << S::kLanesLog2;          // chunks of the tile
+  const uint32_t group_chunks = (uint32_t)m << S::kLanesLog2;
+  const uint32_t group_words32 = (uint32_t)m;                // words per group and bit of width
+  const int64_t g0 = tile * k_full;
+  const int64_t chunk0 = tile * (int64_t)(((uint32_t)(k_full * m)) << S::kLanesLog2);
+
+  // 1. all global loads of the tile, issued up front
+  uint4 raw[S::kLoads];
+#pragma unroll
+  for (int u = 0; u < S::kLoads; ++u) {
+    const uint32_t c = (uint32_t)(u * kWave + lane);
+    const uint32_t cc = c < n_chunks ? c : n_chunks - 1u;
+    const u32x4 v = __builtin_nontemporal_load(&x[chunk0 + cc]);
+    raw[u] = make_uint4(v.x, v.y, v.z, v.w);
+  }
+
+  uint32_t my_b = (uint32_t)B;
+  uint32_t tile_base;
+  if (kMixed) {
+    my_b = (lane < k) ? (uint32_t)bits[g0 + lane] : 1u;
+    tile_base = off[g0];
+  } else {
+    tile_base = (uint32_t)tile * ((uint32_t)(k_full * m) * (uint32_t)B);
+  }
+
+  // 2. random bytes of the tile (two Philox blocks per unit)
+  {
+    const uint64_t blk0 = (uint64_t)tile * (uint64_t)((uint32_t)(k_full * m) * 2u);
+    uint4* dst = reinterpret_cast<uint4*>(lds.rand_bytes);
+#pragma unroll
+    for (int q = 0; q < S::kPhilox; ++q) {
+      const uint32_t i = (uint32_t)(q * kWave + lane);
+      if (i < units * 2u) dst[i] = philox_block(blk0 + i, seed_lo, seed_hi);
+    }
+  }
+
+  // 3. min/max per unit: in-lane over the chunk, then across the unit's lanes
+  float xf[S::kLoads][kEpl];
+#pragma unroll
+  for (int u = 0; u < S::kLoads; u += 2) {
+    float mn[2], mx[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+#pragma unroll
+      for (int e = 0; e < kEpl; ++e) xf[u + h][e] = chunk_elem<DT>(raw[u + h], e);
+      const float(&v)[kEpl] = xf[u + h];
+      if (kEpl == 4) {
+        mn[h] = vmin(vmin3(v[0], v[1], v[2]), v[3]);
+        mx[h] = vmax(vmax3(v[0], v[1], v[2]), v[3]);
+      } else {
+        mn[h] = vmin(vmin3(vmin3(vmin3(v[0], v[1], v[2]), v[3], v[4 % kEpl]), v[5 % kEpl], v[6 % kEpl]), v[7 % kEpl]);
+        mx[h] = vmax(vmax3(vmax3(vmax3(v[0], v[1], v[2]), v[3], v[4 % kEpl]), v[5 % kEpl], v[6 % kEpl]), v[7 % kEpl]);
+      }
+    }
+    seg_minmax_x2<S::kLanesLog2>(mn[0], mx[0], mn[1], mx[1]);
+    if ((lane & ((1 << S::kLanesLog2) - 1)) == (1 << S::kLanesLog2) - 1) {
+      lds.ustat[u * S::kUnitsPerLoad + (lane >> S::kLanesLog2)] = make_float2(mn[0], mx[0]);
+      lds.ustat[(u + 1) * S::kUnitsPerLoad + (lane >> S::kLanesLog2)] = make_float2(mn[1], mx[1]);
+    }
+  }
+  wave_lds_sync();
+
+  // 4a. units -> groups: 2^part_log2 lanes share a group's m units, then combine
+  float2 st;
+  {
+    const int part = 1 << part_log2;
+    int j = lane >> part_log2;
+    j = j < k ? j : k - 1;                                   // idle lanes repeat the last group
+    const int p0 = lane & (part - 1);                        // < m: part <= 64 / k <= m
+    const float2* us = lds.ustat + j * m;
+    st = us[p0];
+    for (int i = p0 + part; i < m; i += part) {
+      const float2 t = us[i];
+      st.x = vmin(st.x, t.x);
+      st.y = vmax(st.y, t.y);
+    }
+    for (int d = 1; d < part; d <<= 1) {
+      st.x = vmin(st.x, __shfl_xor(st.x, d));
+      st.y = vmax(st.y, __shfl_xor(st.y, d));
+    }
+    const int src = (lane < k ? lane : k - 1) << part_log2;  // lane g takes group g's pair
+    st.x = __shfl(st.x, src);
+    st.y = __shfl(st.y, src);
+  }
+
+  // 4b. lane g of the wave finishes group g of the tile: scale, reciprocal, place in the run
+  bool need_exact2;
+  uint32_t tile_words;
+  {
+    const GroupScale s = group_scale(st.x, st.y, my_b);
+    const float invs = s.inv * kScale;
+    need_exact2 = __builtin_amdgcn_ballot_w64(!(invs <= 3.402823466e+38f) && lane < k) != 0ull;
+    uint32_t woff;
+    if (kMixed) {
+      const uint32_t w = (lane < k) ? group_words32 * my_b : 0u;
+      const uint32_t incl = wave_inclusive_sum(w);
+      tile_words = (uint32_t)__builtin_amdgcn_readlane((int)incl, kWave - 1);
+      woff = incl - w;
+    } else {
+      tile_words = units * (uint32_t)B;
+      woff = (uint32_t)lane * (group_words32 * (uint32_t)B);
+    }
+    if (lane < k) {
+      out_min[g0 + lane] = s.mn;
+      out_scale[g0 + lane] = s.scale;
+      GroupInfo gi;
+      gi.mn = s.mn;
+      gi.invs = need_exact2 ? s.inv : invs;
+      const uint32_t lane_bits = (uint32_t)kEpl * my_b;
+      const uint32_t swz = (lane_bits <= 8u) ? 3u : (lane_bits == 16u) ? 2u : 0u;
+      gi.b = my_b | (swz << 8);
+      gi.byte_off = woff * 4u;
+      lds.info[lane] = gi;
+    }
+  }
+
+  // the lane's random bytes, one dword per four elements, out of LDS before it is reused
+  uint32_t rnd[S::kLoads][kEpl / 4];
+#pragma unroll
+  for (int u = 0; u < S::kLoads; ++u) {
+    if (kEpl == 4) {
+      rnd[u][0] = reinterpret_cast<const uint32_t*>(lds.rand_bytes)[u * kWave + lane];
+    } else {
+      const uint2 r2 = reinterpret_cast<const uint2*>(lds.rand_bytes)[u * kWave + lane];
+      rnd[u][0] = r2.x;
+      rnd[u][kEpl / 4 - 1] = r2.y;
+    }
+  }
+  wave_lds_sync();
+
+  // 5. quantize every chunk of the tile and drop its bits at their place in the staged run
+#pragma unroll
+  for (int u = 0; u < S::kLoads; ++u) {
+    const uint32_t c = (uint32_t)(u * kWave + lane);
+    if (c < n_chunks) {
+      const uint32_t grp = ((c >> S::kLanesLog2) * magic) >> 16;      // unit / m
+      const uint32_t lig = c - grp * group_chunks;                    // chunk inside its group
+      const GroupInfo gi = lds.info[grp];
+      const uint32_t b = kMixed ? (gi.b & 0xFFu) : (uint32_t)B;
+      const uint32_t addr = (gi.byte_off + ((lig * b * (uint32_t)kEpl) >> 3)) ^ (gi.b >> 8);
+      uint32_t n0, n1;
+      if (need_exact2) quantize_chunk<DT, true>(xf[u], gi.mn, gi.invs, b, rnd[u], n0, n1);
+      else             quantize_chunk<DT, false>(xf[u], gi.mn, gi.invs, b, rnd[u], n0, n1);
+      stage_chunk<kEpl>(stage8, addr, b, n0, n1, lane);
+    }
+  }
+  wave_lds_sync();
+
+  // 6. the tile's words are one contiguous run in the packed buffer
+  uint32_t* dst = words + tile_base;
+  for (uint32_t i = lane; i < tile_words; i += kWave) dst[i] = lds.stage[i];
+}
+
+// Long groups, 128 < m <= 1024 units (4096 < group size <= 32768 elements, e.g. a row of
+// 11008): one workgroup per group, one wave per slice of at most 128 units.  Every wave keeps
+// its slice in registers, the waves exchange their (min, max) through LDS, and each then
+// quantizes and writes its part of the group's words: the activation is read once.
+struct LongWaveLds {
+  union {
+    uint8_t rand_bytes[4096];
+    uint32_t stage[1024];
+  };
+};
+constexpr int kLongMaxWaves = 8;
+
+template <int DT, int B>
+__global__ __launch_bounds__(kWave * kLongMaxWaves) void k_quantize_pack_long(
+    const u32x4* __restrict__ x, int32_t m, int32_t units_per_wave, const uint8_t* __restrict__ bits,
+    const uint32_t* __restrict__ off, uint32_t seed_lo, uint32_t seed_hi, uint32_t* __restrict__ words,
+    float* __restrict__ out_min, float* __restrict__ out_scale) {
+  using S = UnitShape<DT>;
+  constexpr int kEpl = S::kEpl;
+  constexpr bool kMixed = (B == 0);
+  extern __shared__ __align__(16) uint8_t dyn_lds[];         // n_waves slices, then n_waves (min, max) pairs
+
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int n_waves = (int)(blockDim.x >> 6);
+  const int64_t g = blockIdx.x;
+  LongWaveLds& lds = reinterpret_cast<LongWaveLds*>(dyn_lds)[wave];
+  float2* wstat = reinterpret_cast<float2*>(dyn_lds + (size_t)n_waves * sizeof(LongWaveLds));
+  uint8_t* stage8 = reinterpret_cast<uint8_t*>(lds.stage);
+
+  const int32_t unit0 = wave * units_per_wave;               // first unit of this wave's slice
+  const uint32_t units = (uint32_t)((m - unit0 < units_per_wave) ? m - unit0 : units_per_wave);   // >= 1
+  const uint32_t n_chunks = units << S::kLanesLog2;
+  const int64_t first_unit = g * m + unit0;                  // in the tensor
+  const int64_t chunk0 = first_unit << S::kLanesLog2;
+
+  // 1. all global loads of the slice, issued up front
+  uint4 raw[S::kLoads];
+#pragma unroll
+  for (int u = 0; u < S::kLoads; ++u) {
+    const uint32_t c = (uint32_t)(u * kWave + lane);
+    const uint32_t cc = c < n_chunks ? c : n_chunks - 1u;    // lanes past the end repeat the last chunk
+    const u32x4 v = __builtin_nontemporal_load(&x[chunk0 + cc]);
+    raw[u] = make_uint4(v.x, v.y, v.z, v.w);
+  }
+  const uint32_t b = kMixed ? (uint32_t)bits[g] : (uint32_t)B;
+  const uint32_t group_base = kMixed ? off[g] : (uint32_t)g * ((uint32_t)m * (uint32_t)B);
+
+  // 2. random bytes of the slice (two Philox blocks per unit)
+  {
+    const uint64_t blk0 = (uint64_t)first_unit * 2u;
+    uint4* dst = reinterpret_cast<uint4*>(lds.rand_bytes);
+#pragma unroll
+    for (int q = 0; q < S::kPhilox; ++q) {
+      const uint32_t i = (uint32_t)(q * kWave + lane);
+      if (i < units * 2u) dst[i] = philox_block(blk0 + i, seed_lo, seed_hi);
+    }
+  }
+
+  // 3. min/max of the slice, then of the group
+  float xf[S::kLoads][kEpl];
+  {
+    float a[2], c2[2];
+#pragma unroll
+    for (int u = 0; u < S::kLoads; ++u) {
+#pragma unroll
+      for (int e = 0; e < kEpl; ++e) xf[u][e] = chunk_elem<DT>(raw[u], e);
+      const float(&v)[kEpl] = xf[u];
+      float lo = vmin(vmin3(v[0], v[1], v[2]), v[3]), hi = vmax(vmax3(v[0], v[1], v[2]), v[3]);
+      if (kEpl == 8) {
+        lo = vmin3(lo, vmin3(v[4 % kEpl], v[5 % kEpl], v[6 % kEpl]), v[7 % kEpl]);
+        hi = vmax3(hi, vmax3(v[4 % kEpl], v[5 % kEpl], v[6 % kEpl]), v[7 % kEpl]);
+      }
+      a[u & 1] = (u < 2) ? lo : vmin(a[u & 1], lo);
+      c2[u & 1] = (u < 2) ? hi : vmax(c2[u & 1], hi);
+    }
+    seg_minmax_x2<6>(a[0], c2[0], a[1], c2[1]);
+    if (lane == kWave - 1) wstat[wave] = make_float2(vmin(a[0], a[1]), vmax(c2[0], c2[1]));
+  }
+  __syncthreads();
+  float2 st = wstat[0];
+  for (int w = 1; w < n_waves; ++w) {
+    const float2 t = wstat[w];
+    st.x = vmin(st.x, t.x);
+    st.y = vmax(st.y, t.y);
+  }
+  const GroupScale s = group_scale(st.x, st.y, b);
+  float invs = s.inv * kScale;
+  const bool need_exact2 = !(invs <= 3.402823466e+38f);
+  if (need_exact2) invs = s.inv;
+  if (threadIdx.x == 0) {
+    out_min[g] = s.mn;
+    out_scale[g] = s.scale;
+  }
+
+  // the lane's random bytes, one dword per four elements, out of LDS before it is reused
+  uint32_t rnd[S::kLoads][kEpl / 4];
+#pragma unroll
+  for (int u = 0; u < S::kLoads; ++u) {
+    if (kEpl == 4) {
+      rnd[u][0] = reinterpret_cast<const uint32_t*>(lds.rand_bytes)[u * kWave + lane];
+    } else {
+      const uint2 r2 = reinterpret_cast<const uint2*>(lds.rand_bytes)[u * kWave + lane];
+      rnd[u][0] = r2.x;
+      rnd[u][kEpl / 4 - 1] = r2.y;
+    }
+  }
+  wave_lds_sync();
+
+  // 5. quantize every chunk of the slice and drop its bits at their place in the staged run
+  const uint32_t lane_bits = (uint32_t)kEpl * b;
+  const uint32_t swz = (lane_bits <= 8u) ? 3u : (lane_bits == 16u) ? 2u : 0u;
+#pragma unroll
+  for (int u = 0; u < S::kLoads; ++u) {
+    const uint32_t c = (uint32_t)(u * kWave + lane);
+    if (c < n_chunks) {
+      const uint32_t addr = ((c * lane_bits) >> 3) ^ swz;
+      uint32_t n0, n1;
+      if (need_exact2) quantize_chunk<DT, true>(xf[u], s.mn, invs, b, rnd[u], n0, n1);
+      else             quantize_chunk<DT, false>(xf[u], s.mn, invs, b, rnd[u], n0, n1);
+      stage_chunk<kEpl>(stage8, addr, b, n0, n1, lane);
+    }
+  }
+  wave_lds_sync();
+
+  // 6. the slice's words are one contiguous run inside the group's
+  uint32_t* dst = words + group_base + (uint32_t)unit0 * b;
+  const uint32_t slice_words = units * b;
+  for (uint32_t i = lane; i < slice_words; i += kWave) dst[i] = lds.stage[i];
+}
+
+// Takes plans whose groups are 32 * m elements, 128 < m <= 1024, when there are enough groups to
+// fill the device with one workgroup each, or when the two-pass route does not apply (groups
+// not a whole number of tiles).  Returns the groups it covered (all whole groups, or none).
+template <int DT>
+hipError_t launch_long(const daf_plan_t* p, const void* x, uint32_t seed_lo, uint32_t seed_hi, uint32_t* out_words,
+                       float* out_min, float* out_scale, int64_t* covered, hipStream_t stream) {
+  *covered = 0;
+  const int32_t gs = p->group_size;
+  const int32_t m = gs / 32;
+  if (gs % 32 != 0 || m <= 128 || m > 128 * kLongMaxWaves) return hipSuccess;
+  const int64_t full_groups = p->n / gs;
+  if (full_groups == 0 || full_groups > 0x7fffffff) return hipSuccess;
+  if (p->d_big_scratch != nullptr && full_groups < 256) return hipSuccess;     // the two-pass route fills the device better
+  const int32_t n_waves = (m + 127) / 128;
+  const int32_t units_per_wave = (m + n_waves - 1) / n_waves;
+  const unsigned lds_bytes = (unsigned)(n_waves * (sizeof(LongWaveLds) + sizeof(float2)));
+#define DAF_LAUNCH(BITS)                                                                                          \
+  hipLaunchKernelGGL((k_quantize_pack_long<DT, BITS>), dim3((unsigned)full_groups), dim3(kWave * n_waves),        \
+                     lds_bytes, stream, static_cast<const u32x4*>(x), m, units_per_wave, p->d_bits, p->d_off,     \
+                     seed_lo, seed_hi, out_words, out_min, out_scale)
+  switch (p->uniform_bits) {
+    case 0: DAF_LAUNCH(0); break;
+    case 1: DAF_LAUNCH(1); break;
+    case 2: DAF_LAUNCH(2); break;
+    case 4: DAF_LAUNCH(4); break;
+    case 8: DAF_LAUNCH(8); break;
+    default: return hipErrorInvalidValue;
+  }
+#undef DAF_LAUNCH
+  *covered = full_groups;
+  return hipGetLastError();
+}
+
+// Group sizes the unit path takes: 32 * m elements with 3 <= m <= 128 and m not a power of two
+// (those are the fast path's).  Returns the groups it covered.
+template <int DT>
+hipError_t launch_units(const daf_plan_t* p, const void* x, uint32_t seed_lo, uint32_t seed_hi, uint32_t* out_words,
+                        float* out_min, float* out_scale, int64_t* covered, hipStream_t stream) {
+  *covered = 0;
+  const int32_t gs = p->group_size;
+  const int32_t m = gs / 32;
+  if (gs % 32 != 0 || m < 3 || m > 128 || (m & (m - 1)) == 0) return hipSuccess;
+  const int32_t k = 128 / m;
+  const int64_t full_groups = p->n / gs;
+  const int64_t n_tiles = (full_groups + k - 1) / k;                  // the last one may hold fewer groups
+  if (n_tiles == 0) return hipSuccess;
+  const int32_t k_last = (int32_t)(full_groups - (n_tiles - 1) * k);
+  const uint32_t magic = (65536u + (uint32_t)m - 1u) / (uint32_t)m;   // floor(u / m) = (u * magic) >> 16 for u < 128
+  int32_t part_log2 = 0;
+  while ((2 << part_log2) * k <= kWave) ++part_log2;                  // largest power of two <= 64 / k
+  const unsigned blocks = (unsigned)((n_tiles + kWavesPerBlock - 1) / kWavesPerBlock);
+#define DAF_LAUNCH(BITS)                                                                                       \
+  hipLaunchKernelGGL((k_quantize_pack_units<DT, BITS>), dim3(blocks), dim3(kThreads), 0, stream,               \
+                     static_cast<const u32x4*>(x), n_tiles, m, k, k_last, magic, part_log2, p->d_bits, p->d_off, \
+                     seed_lo, seed_hi, out_words, out_min, out_scale)
+  switch (p->uniform_bits) {
+    case 0: DAF_LAUNCH(0); break;
+    case 1: DAF_LAUNCH(1); break;
+    case 2: DAF_LAUNCH(2); break;
+    case 4: DAF_LAUNCH(4); break;
+    case 8: DAF_LAUNCH(8); break;
+    default: return hipErrorInvalidValue;
+  }
+#undef DAF_LAUNCH
+  *covered = full_groups;
+  return hipGetLastError();
+}
+
 // ------------------------------------------------------------------------------------------
 // Statistics only: per-group min and max, for a controller that chooses the widths.
 // ------------------------------------------------------------------------------------------
@@ -970,14 +1424,18 @@ hipError_t launch_dtype(const daf_plan_t* p, const void* x, uint64_t seed, uint3
   constexpr int kEpl = ElemTraits<DT>::kPerLoad;
   const int64_t full_groups = p->n / p->group_size;
   int64_t fast_groups = 0;
-  if (p->d_big_scratch != nullptr) {    // groups longer than a tile (set up by daf_plan)
+  if (!METRICS && !RELU) {              // groups of 4128 .. 32768 elements, one workgroup each
+    const hipError_t e = launch_long<DT>(p, x, seed_lo, seed_hi, out_words, out_min, out_scale, &fast_groups, stream);
+    if (e != hipSuccess) return e;
+  }
+  if (fast_groups == 0 && p->d_big_scratch != nullptr) {    // groups longer than a tile (set up by daf_plan)
     if (METRICS || RELU) return hipErrorNotSupported;
     return launch_big<DT>(p, x, seed_lo, seed_hi, out_words, out_min, out_scale, stream);
   }
 
   // fast path: groups of 4 .. 1024 chunks (a power of two, at most one tile), whole tiles only
   const int32_t lpg = p->group_size / kEpl;
-  if (p->group_size % kEpl == 0 && lpg >= 4 && (lpg & (lpg - 1)) == 0) {
+  if (fast_groups == 0 && p->group_size % kEpl == 0 && lpg >= 4 && (lpg & (lpg - 1)) == 0) {
     int64_t n_tiles = 0;
     hipError_t e = hipSuccess;
 #define DAF_CASE(LOG2)                                                                                   \
@@ -996,6 +1454,11 @@ hipError_t launch_dtype(const daf_plan_t* p, const void* x, uint64_t seed, uint3
       default: break;
     }
 #undef DAF_CASE
+    if (e != hipSuccess) return e;
+  }
+
+  if (fast_groups == 0 && !METRICS && !RELU) {
+    const hipError_t e = launch_units<DT>(p, x, seed_lo, seed_hi, out_words, out_min, out_scale, &fast_groups, stream);
     if (e != hipSuccess) return e;
   }
 
