@@ -131,6 +131,11 @@ void daf_plan_destroy(daf_plan_t* plan);
  *   out_min    DEVICE, G floats; out_scale: DEVICE, G floats.  Always binary32.
  *   stream     the call only enqueues work on this stream; it does not synchronize.
  *
+ * x is read once for every group size up to 32768 elements (any multiple of 32: a row of 768,
+ * 3072 or 11008 elements is as good a group as a power of two); longer groups, fewer than 256
+ * groups of 8192, 16384 or 32768 elements, and one group for the whole tensor need the group's
+ * statistics before any element can be quantized and read x twice.
+ *
  * Errors: DAF_EINVAL (null or misaligned pointer), DAF_EUNSUPPORTED (dtype), DAF_EDEVICE.
  */
 int daf_quantize_pack(const daf_plan_t* plan, const void* x, daf_dtype_t dtype, uint64_t seed,
