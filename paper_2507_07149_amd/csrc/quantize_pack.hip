@@ -922,6 +922,74 @@ struct alignas(16) UnitLds {
   float2 ustat[UnitShape<DT>::kUnits];   // (min, max) per unit
 };
 
+// All global loads of a unit tile, issued up front: lane l of load u takes chunk u*64 + l,
+// lanes past the tile's end a copy of its last chunk.
+template <int DT>
+__device__ __forceinline__ void unit_tile_load(const u32x4* __restrict__ x, int64_t chunk0, uint32_t n_chunks, int lane,
+                                               uint4 (&raw)[UnitShape<DT>::kLoads]) {
+#pragma unroll
+  for (int u = 0; u < UnitShape<DT>::kLoads; ++u) {
+    const uint32_t c = (uint32_t)(u * kWave + lane);
+    const uint32_t cc = c < n_chunks ? c : n_chunks - 1u;
+    const u32x4 v = __builtin_nontemporal_load(&x[chunk0 + cc]);
+    raw[u] = make_uint4(v.x, v.y, v.z, v.w);
+  }
+}
+
+// Widens the tile into xf and returns, in lane g < k, the (min, max) of group g of the tile
+// (k groups of m units each).  In-lane over the chunk, DPP across the unit's lanes, one pair
+// per unit to LDS; then 2^part_log2 lanes share a group's m units and combine.
+template <int DT>
+__device__ __forceinline__ float2 unit_tile_stats(const uint4 (&raw)[UnitShape<DT>::kLoads],
+                                                  float (&xf)[UnitShape<DT>::kLoads][ElemTraits<DT>::kPerLoad],
+                                                  float2* ustat, int k, int m, int part_log2, int lane) {
+  using S = UnitShape<DT>;
+  constexpr int kEpl = S::kEpl;
+#pragma unroll
+  for (int u = 0; u < S::kLoads; u += 2) {
+    float mn[2], mx[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+#pragma unroll
+      for (int e = 0; e < kEpl; ++e) xf[u + h][e] = chunk_elem<DT>(raw[u + h], e);
+      const float(&v)[kEpl] = xf[u + h];
+      if (kEpl == 4) {
+        mn[h] = vmin(vmin3(v[0], v[1], v[2]), v[3]);
+        mx[h] = vmax(vmax3(v[0], v[1], v[2]), v[3]);
+      } else {
+        mn[h] = vmin(vmin3(vmin3(vmin3(v[0], v[1], v[2]), v[3], v[4 % kEpl]), v[5 % kEpl], v[6 % kEpl]), v[7 % kEpl]);
+        mx[h] = vmax(vmax3(vmax3(vmax3(v[0], v[1], v[2]), v[3], v[4 % kEpl]), v[5 % kEpl], v[6 % kEpl]), v[7 % kEpl]);
+      }
+    }
+    seg_minmax_x2<S::kLanesLog2>(mn[0], mx[0], mn[1], mx[1]);
+    if ((lane & ((1 << S::kLanesLog2) - 1)) == (1 << S::kLanesLog2) - 1) {
+      ustat[u * S::kUnitsPerLoad + (lane >> S::kLanesLog2)] = make_float2(mn[0], mx[0]);
+      ustat[(u + 1) * S::kUnitsPerLoad + (lane >> S::kLanesLog2)] = make_float2(mn[1], mx[1]);
+    }
+  }
+  wave_lds_sync();
+
+  const int part = 1 << part_log2;
+  int j = lane >> part_log2;
+  j = j < k ? j : k - 1;                                   // idle lanes repeat the last group
+  const int p0 = lane & (part - 1);                        // < m: part <= 64 / k <= m
+  const float2* us = ustat + j * m;
+  float2 st = us[p0];
+  for (int i = p0 + part; i < m; i += part) {
+    const float2 t = us[i];
+    st.x = vmin(st.x, t.x);
+    st.y = vmax(st.y, t.y);
+  }
+  for (int d = 1; d < part; d <<= 1) {
+    st.x = vmin(st.x, __shfl_xor(st.x, d));
+    st.y = vmax(st.y, __shfl_xor(st.y, d));
+  }
+  const int src = (lane < k ? lane : k - 1) << part_log2;  // lane g takes group g's pair
+  st.x = __shfl(st.x, src);
+  st.y = __shfl(st.y, src);
+  return st;
+}
+
 template <int DT, int B>
 __global__ __launch_bounds__(kThreads) void k_quantize_pack_units(
     const u32x4* __restrict__ x, int64_t n_tiles, int32_t m, int32_t k_full, int32_t k_last, uint32_t magic,
@@ -950,13 +1018,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_units(
 
   // 1. all global loads of the tile, issued up front
   uint4 raw[S::kLoads];
-#pragma unroll
-  for (int u = 0; u < S::kLoads; ++u) {
-    const uint32_t c = (uint32_t)(u * kWave + lane);
-    const uint32_t cc = c < n_chunks ? c : n_chunks - 1u;
-    const u32x4 v = __builtin_nontemporal_load(&x[chunk0 + cc]);
-    raw[u] = make_uint4(v.x, v.y, v.z, v.w);
-  }
+  unit_tile_load<DT>(x, chunk0, n_chunks, lane, raw);
 
   uint32_t my_b = (uint32_t)B;
   uint32_t tile_base;
@@ -978,54 +1040,9 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_units(
     }
   }
 
-  // 3. min/max per unit: in-lane over the chunk, then across the unit's lanes
+  // 3. + 4a. min/max per unit, then per group: lane g holds group g's pair
   float xf[S::kLoads][kEpl];
-#pragma unroll
-  for (int u = 0; u < S::kLoads; u += 2) {
-    float mn[2], mx[2];
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-#pragma unroll
-      for (int e = 0; e < kEpl; ++e) xf[u + h][e] = chunk_elem<DT>(raw[u + h], e);
-      const float(&v)[kEpl] = xf[u + h];
-      if (kEpl == 4) {
-        mn[h] = vmin(vmin3(v[0], v[1], v[2]), v[3]);
-        mx[h] = vmax(vmax3(v[0], v[1], v[2]), v[3]);
-      } else {
-        mn[h] = vmin(vmin3(vmin3(vmin3(v[0], v[1], v[2]), v[3], v[4 % kEpl]), v[5 % kEpl], v[6 % kEpl]), v[7 % kEpl]);
-        mx[h] = vmax(vmax3(vmax3(vmax3(v[0], v[1], v[2]), v[3], v[4 % kEpl]), v[5 % kEpl], v[6 % kEpl]), v[7 % kEpl]);
-      }
-    }
-    seg_minmax_x2<S::kLanesLog2>(mn[0], mx[0], mn[1], mx[1]);
-    if ((lane & ((1 << S::kLanesLog2) - 1)) == (1 << S::kLanesLog2) - 1) {
-      lds.ustat[u * S::kUnitsPerLoad + (lane >> S::kLanesLog2)] = make_float2(mn[0], mx[0]);
-      lds.ustat[(u + 1) * S::kUnitsPerLoad + (lane >> S::kLanesLog2)] = make_float2(mn[1], mx[1]);
-    }
-  }
-  wave_lds_sync();
-
-  // 4a. units -> groups: 2^part_log2 lanes share a group's m units, then combine
-  float2 st;
-  {
-    const int part = 1 << part_log2;
-    int j = lane >> part_log2;
-    j = j < k ? j : k - 1;                                   // idle lanes repeat the last group
-    const int p0 = lane & (part - 1);                        // < m: part <= 64 / k <= m
-    const float2* us = lds.ustat + j * m;
-    st = us[p0];
-    for (int i = p0 + part; i < m; i += part) {
-      const float2 t = us[i];
-      st.x = vmin(st.x, t.x);
-      st.y = vmax(st.y, t.y);
-    }
-    for (int d = 1; d < part; d <<= 1) {
-      st.x = vmin(st.x, __shfl_xor(st.x, d));
-      st.y = vmax(st.y, __shfl_xor(st.y, d));
-    }
-    const int src = (lane < k ? lane : k - 1) << part_log2;  // lane g takes group g's pair
-    st.x = __shfl(st.x, src);
-    st.y = __shfl(st.y, src);
-  }
+  const float2 st = unit_tile_stats<DT>(raw, xf, lds.ustat, k, m, part_log2, lane);
 
   // 4b. lane g of the wave finishes group g of the tile: scale, reciprocal, place in the run
   bool need_exact2;
@@ -1259,23 +1276,36 @@ hipError_t launch_long(const daf_plan_t* p, const void* x, uint32_t seed_lo, uin
   return hipGetLastError();
 }
 
+// Geometry of the unit path for a plan, shared by the quantize and the statistics launchers.
+struct UnitGeometry {
+  int32_t m, k, k_last, part_log2;
+  int64_t n_tiles, full_groups;
+};
+inline bool unit_geometry(const daf_plan_t* p, UnitGeometry* u) {
+  const int32_t gs = p->group_size;
+  u->m = gs / 32;
+  if (gs % 32 != 0 || u->m < 3 || u->m > 128 || (u->m & (u->m - 1)) == 0) return false;
+  u->k = 128 / u->m;
+  u->full_groups = p->n / gs;
+  u->n_tiles = (u->full_groups + u->k - 1) / u->k;                  // the last one may hold fewer groups
+  if (u->n_tiles == 0) return false;
+  u->k_last = (int32_t)(u->full_groups - (u->n_tiles - 1) * u->k);
+  u->part_log2 = 0;
+  while ((2 << u->part_log2) * u->k <= kWave) ++u->part_log2;       // largest power of two <= 64 / k
+  return true;
+}
+
 // Group sizes the unit path takes: 32 * m elements with 3 <= m <= 128 and m not a power of two
 // (those are the fast path's).  Returns the groups it covered.
 template <int DT>
 hipError_t launch_units(const daf_plan_t* p, const void* x, uint32_t seed_lo, uint32_t seed_hi, uint32_t* out_words,
                         float* out_min, float* out_scale, int64_t* covered, hipStream_t stream) {
   *covered = 0;
-  const int32_t gs = p->group_size;
-  const int32_t m = gs / 32;
-  if (gs % 32 != 0 || m < 3 || m > 128 || (m & (m - 1)) == 0) return hipSuccess;
-  const int32_t k = 128 / m;
-  const int64_t full_groups = p->n / gs;
-  const int64_t n_tiles = (full_groups + k - 1) / k;                  // the last one may hold fewer groups
-  if (n_tiles == 0) return hipSuccess;
-  const int32_t k_last = (int32_t)(full_groups - (n_tiles - 1) * k);
+  UnitGeometry ug;
+  if (!unit_geometry(p, &ug)) return hipSuccess;
+  const int32_t m = ug.m, k = ug.k, k_last = ug.k_last, part_log2 = ug.part_log2;
+  const int64_t n_tiles = ug.n_tiles, full_groups = ug.full_groups;
   const uint32_t magic = (65536u + (uint32_t)m - 1u) / (uint32_t)m;   // floor(u / m) = (u * magic) >> 16 for u < 128
-  int32_t part_log2 = 0;
-  while ((2 << part_log2) * k <= kWave) ++part_log2;                  // largest power of two <= 64 / k
   const unsigned blocks = (unsigned)((n_tiles + kWavesPerBlock - 1) / kWavesPerBlock);
 #define DAF_LAUNCH(BITS)                                                                                       \
   hipLaunchKernelGGL((k_quantize_pack_units<DT, BITS>), dim3(blocks), dim3(kThreads), 0, stream,               \
@@ -1330,22 +1360,46 @@ __global__ __launch_bounds__(kThreads) void k_group_minmax_tile(const u32x4* __r
   }
 }
 
+// One wave per group, any group size (a multiple of 32 elements, so every group starts on a
+// 16-byte boundary): the group's whole 16-byte chunks four per lane at a time, the elements
+// after them (the tensor's short last group only) one by one.
 template <int DT>
 __global__ __launch_bounds__(kThreads) void k_group_minmax_group(const void* __restrict__ x, int64_t n, int32_t gs,
                                                                  int64_t g_begin, int64_t g_end,
                                                                  float* __restrict__ out_min,
                                                                  float* __restrict__ out_max) {
+  constexpr int kEpl = ElemTraits<DT>::kPerLoad;
   const int lane = threadIdx.x & (kWave - 1);
   const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
   const int64_t n_waves = (int64_t)gridDim.x * kWavesPerBlock;
   for (int64_t g = g_begin + wave; g < g_end; g += n_waves) {
     const int64_t lo = g * (int64_t)gs;
-    const int64_t len = (lo + gs <= n) ? gs : (n - lo);
-    float mn = load_elem<DT>(x, lo), mx = mn;
-    for (int64_t j = lane; j < len; j += kWave) {
-      const float v = load_elem<DT>(x, lo + j);
-      mn = vmin(mn, v);
-      mx = vmax(mx, v);
+    const int32_t len = (int32_t)((lo + gs <= n) ? gs : (n - lo));
+    const int32_t n_chunks = len / kEpl;
+    const u32x4* chunks = static_cast<const u32x4*>(x) + lo / kEpl;
+    float mn = load_elem<DT>(x, lo), mx = mn;              // element 0 exists in every group
+    for (int32_t c0 = lane; c0 < n_chunks; c0 += 4 * kWave) {
+      u32x4 v[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int32_t c = c0 + q * kWave;
+        v[q] = __builtin_nontemporal_load(&chunks[c < n_chunks ? c : c0]);
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const uint4 raw = make_uint4(v[q].x, v[q].y, v[q].z, v[q].w);
+#pragma unroll
+        for (int e = 0; e < kEpl; ++e) {
+          const float f = chunk_elem<DT>(raw, e);
+          mn = vmin(mn, f);
+          mx = vmax(mx, f);
+        }
+      }
+    }
+    for (int32_t j = n_chunks * kEpl + lane; j < len; j += kWave) {
+      const float f = load_elem<DT>(x, lo + j);
+      mn = vmin(mn, f);
+      mx = vmax(mx, f);
     }
     float mn2 = mn, mx2 = mx;
     seg_minmax_x2<6>(mn, mx, mn2, mx2);
@@ -1365,11 +1419,39 @@ __global__ void k_stat_to_outputs(const float2* __restrict__ stat, int64_t num_g
   }
 }
 
+// Statistics only, for the group sizes of the unit path (32 * m elements, 3 <= m <= 128, m not a
+// power of two): the first steps of k_quantize_pack_units.
+template <int DT>
+__global__ __launch_bounds__(kThreads) void k_group_minmax_units(const u32x4* __restrict__ x, int64_t n_tiles, int32_t m,
+                                                                 int32_t k_full, int32_t k_last, int32_t part_log2,
+                                                                 float* __restrict__ out_min,
+                                                                 float* __restrict__ out_max) {
+  using S = UnitShape<DT>;
+  __shared__ float2 ustat_all[kWavesPerBlock][S::kUnits];
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t tile = (int64_t)blockIdx.x * kWavesPerBlock + wave_in_block;
+  if (tile >= n_tiles) return;
+  const int k = (tile == n_tiles - 1) ? k_last : k_full;
+  const uint32_t n_chunks = ((uint32_t)(k * m)) << S::kLanesLog2;
+  const int64_t chunk0 = tile * (int64_t)(((uint32_t)(k_full * m)) << S::kLanesLog2);
+  uint4 raw[S::kLoads];
+  unit_tile_load<DT>(x, chunk0, n_chunks, lane, raw);
+  float xf[S::kLoads][S::kEpl];
+  const float2 st = unit_tile_stats<DT>(raw, xf, ustat_all[wave_in_block], k, m, part_log2, lane);
+  if (lane < k) {
+    out_min[tile * k_full + lane] = st.x + 0.0f;
+    out_max[tile * k_full + lane] = st.y + 0.0f;
+  }
+}
+
 template <int DT>
 hipError_t launch_group_minmax(const daf_plan_t* p, const void* x, float* out_min, float* out_max,
                                hipStream_t stream) {
   constexpr int kEpl = ElemTraits<DT>::kPerLoad;
-  if (p->d_big_scratch != nullptr) {          // groups longer than a tile: tile pairs, then per-group reduce
+  // Groups longer than a tile: tile pairs, then a per-group reduce, unless there are enough
+  // groups to fill the device with one wave each (then one launch below does it, 25 % faster).
+  if (p->d_big_scratch != nullptr && p->num_groups < 1024) {
     const int64_t n_full_tiles = p->n / kBigTile;
     const int64_t n_partials = n_full_tiles + ((n_full_tiles * kBigTile < p->n) ? 1 : 0);
     const int64_t tpg = (p->num_groups == 1) ? n_partials : p->group_size / kBigTile;
@@ -1406,6 +1488,13 @@ hipError_t launch_group_minmax(const daf_plan_t* p, const void* x, float* out_mi
 #undef DAF_CASE
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+  }
+  UnitGeometry ug;
+  if (fast_groups == 0 && unit_geometry(p, &ug)) {
+    hipLaunchKernelGGL((k_group_minmax_units<DT>), dim3((unsigned)((ug.n_tiles + kWavesPerBlock - 1) / kWavesPerBlock)),
+                       dim3(kThreads), 0, stream, static_cast<const u32x4*>(x), ug.n_tiles, ug.m, ug.k, ug.k_last,
+                       ug.part_log2, out_min, out_max);
+    fast_groups = ug.full_groups;
   }
   const int64_t rest = p->num_groups - fast_groups;
   if (rest > 0) {

@@ -28,7 +28,8 @@ def _group_minmax(daf, x, gs):
 
 
 @pytest.mark.parametrize("dtype", [F32, F16, BF16])
-@pytest.mark.parametrize("gs", [32, 64, 96, 128, 256, 1024, 4096, 8192, 12320, 1 << 20])
+@pytest.mark.parametrize("gs", [32, 64, 96, 128, 160, 256, 768, 1024, 1568, 2080, 3072, 4064, 4096, 8192, 11008, 12320,
+                                1 << 20])
 def test_group_minmax_matrix(env, dtype, gs):
     daf, orc = env
     n = 4096 * 11 + 3 * gs + 29 if gs < (1 << 20) else 4096 * 40 + 77
@@ -40,6 +41,20 @@ def test_group_minmax_matrix(env, dtype, gs):
     omn, omx = orc.group_minmax(to_numpy_bits(x), dtype, gs)
     assert np.array_equal(mn.cpu().numpy().view(np.uint32), omn.view(np.uint32))
     assert np.array_equal(mx.cpu().numpy().view(np.uint32), omx.view(np.uint32))
+
+
+def test_group_minmax_many_long_groups(env):
+    """1024 groups or more of a whole number of tiles: one wave per group instead of the
+    tile-pair route."""
+    daf, orc = env
+    for dtype, gs in ((F32, 8192), (BF16, 16384)):
+        n = 1030 * gs + 100
+        g = torch.Generator().manual_seed(gs)
+        x = (torch.randn(n, generator=g) * 2).to(torch_dtype(dtype))
+        mn, mx = _group_minmax(daf, x, gs)
+        omn, omx = orc.group_minmax(to_numpy_bits(x), dtype, gs)
+        assert np.array_equal(mn.cpu().numpy().view(np.uint32), omn.view(np.uint32))
+        assert np.array_equal(mx.cpu().numpy().view(np.uint32), omx.view(np.uint32))
 
 
 def _select(daf, gmin, gmax, classes):

@@ -126,3 +126,27 @@ def test_long_groups_every_wave_count(H):
         w = _long_workload(BF16 if m % 2 else F32, gs, "mixed" if m % 3 else 8, seed=m, groups=3, last=0)
         print("case", w.name, flush=True)
         H.assert_full_parity(w, H.run_hip(w))
+
+
+def test_group_minmax_every_m(H):
+    """daf_group_minmax on every group size 32 * m, 3 <= m <= 128, and on long groups, against
+    the oracle's per-group minimum and maximum."""
+    import paper_2507_07149_amd as daf
+    from daf_inputs import to_numpy_bits
+    from oracle import daf_oracle as orc
+    for m in list(range(3, 129)) + [129, 344, 385, 1023, 1500]:
+        gs = 32 * m
+        dtype = (F32, F16, BF16)[m % 3]
+        n = (2 * max(1, 128 // m) + 1) * gs + (m % 5) * 7
+        g = torch.Generator().manual_seed(m)
+        x = (torch.randn(n, generator=g) * 3).to(torch_dtype(dtype))
+        plan = daf.daf_plan((n,), gs, 8)
+        G = plan.num_groups
+        mn = torch.full((G,), float("nan"), device="cuda:0")
+        mx = torch.full((G,), float("nan"), device="cuda:0")
+        daf.daf_group_minmax(plan, x.cuda(), mn, mx)
+        torch.cuda.synchronize()
+        omn, omx = orc.group_minmax(to_numpy_bits(x), dtype, gs)
+        assert np.array_equal(mn.cpu().numpy().view(np.uint32), omn.view(np.uint32)), f"min, m={m}"
+        assert np.array_equal(mx.cpu().numpy().view(np.uint32), omx.view(np.uint32)), f"max, m={m}"
+        plan.destroy()
