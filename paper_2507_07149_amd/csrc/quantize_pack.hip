@@ -925,7 +925,7 @@ struct alignas(16) UnitLds {
 // All global loads of a unit tile, issued up front: lane l of load u takes chunk u*64 + l,
 // lanes past the tile's end a copy of its last chunk.
 template <int DT>
-__device__ __forceinline__ void unit_tile_load(const u32x4* __restrict__ x, int64_t chunk0, uint32_t n_chunks, int lane,
+__device__ __forceinline__ void unit_tile_load(const u32x4* x, int64_t chunk0, uint32_t n_chunks, int lane,
                                                uint4 (&raw)[UnitShape<DT>::kLoads]) {
 #pragma unroll
   for (int u = 0; u < UnitShape<DT>::kLoads; ++u) {
@@ -933,6 +933,22 @@ __device__ __forceinline__ void unit_tile_load(const u32x4* __restrict__ x, int6
     const uint32_t cc = c < n_chunks ? c : n_chunks - 1u;
     const u32x4 v = __builtin_nontemporal_load(&x[chunk0 + cc]);
     raw[u] = make_uint4(v.x, v.y, v.z, v.w);
+  }
+}
+
+// RELU variants: every loaded element becomes max(z, +0) and the tile's chunks are written to
+// out_y in the layout they were read in (out_y may be the input: a lane overwrites only chunks
+// it has loaded, and max(., +0) of an already written chunk is the chunk itself).
+template <int DT>
+__device__ __forceinline__ void unit_tile_relu(uint4 (&raw)[UnitShape<DT>::kLoads], u32x4* out_y, int64_t chunk0,
+                                               uint32_t n_chunks, int lane) {
+#pragma unroll
+  for (int u = 0; u < UnitShape<DT>::kLoads; ++u) {
+    raw[u] = make_uint4(relu_bits<DT>(raw[u].x), relu_bits<DT>(raw[u].y), relu_bits<DT>(raw[u].z),
+                        relu_bits<DT>(raw[u].w));
+    const uint32_t c = (uint32_t)(u * kWave + lane);
+    const u32x4 y = {raw[u].x, raw[u].y, raw[u].z, raw[u].w};
+    if (c < n_chunks) out_y[chunk0 + c] = y;
   }
 }
 
@@ -990,12 +1006,12 @@ __device__ __forceinline__ float2 unit_tile_stats(const uint4 (&raw)[UnitShape<D
   return st;
 }
 
-template <int DT, int B>
+template <int DT, int B, bool RELU = false>
 __global__ __launch_bounds__(kThreads) void k_quantize_pack_units(
-    const u32x4* __restrict__ x, int64_t n_tiles, int32_t m, int32_t k_full, int32_t k_last, uint32_t magic,
-    int32_t part_log2,
+    typename std::conditional<RELU, const u32x4*, const u32x4* __restrict__>::type x, int64_t n_tiles, int32_t m,
+    int32_t k_full, int32_t k_last, uint32_t magic, int32_t part_log2,
     const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, uint32_t seed_lo, uint32_t seed_hi,
-    uint32_t* __restrict__ words, float* __restrict__ out_min, float* __restrict__ out_scale) {
+    uint32_t* __restrict__ words, float* __restrict__ out_min, float* __restrict__ out_scale, u32x4* out_y) {
   using S = UnitShape<DT>;
   constexpr int kEpl = S::kEpl;
   constexpr bool kMixed = (B == 0);
@@ -1019,6 +1035,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_units(
   // 1. all global loads of the tile, issued up front
   uint4 raw[S::kLoads];
   unit_tile_load<DT>(x, chunk0, n_chunks, lane, raw);
+  if constexpr (RELU) unit_tile_relu<DT>(raw, out_y, chunk0, n_chunks, lane);
 
   uint32_t my_b = (uint32_t)B;
   uint32_t tile_base;
@@ -1124,11 +1141,12 @@ struct LongWaveLds {
 };
 constexpr int kLongMaxWaves = 8;
 
-template <int DT, int B>
+template <int DT, int B, bool RELU = false>
 __global__ __launch_bounds__(kWave * kLongMaxWaves) void k_quantize_pack_long(
-    const u32x4* __restrict__ x, int32_t m, int32_t units_per_wave, const uint8_t* __restrict__ bits,
+    typename std::conditional<RELU, const u32x4*, const u32x4* __restrict__>::type x, int32_t m,
+    int32_t units_per_wave, const uint8_t* __restrict__ bits,
     const uint32_t* __restrict__ off, uint32_t seed_lo, uint32_t seed_hi, uint32_t* __restrict__ words,
-    float* __restrict__ out_min, float* __restrict__ out_scale) {
+    float* __restrict__ out_min, float* __restrict__ out_scale, u32x4* out_y) {
   using S = UnitShape<DT>;
   constexpr int kEpl = S::kEpl;
   constexpr bool kMixed = (B == 0);
@@ -1150,13 +1168,8 @@ __global__ __launch_bounds__(kWave * kLongMaxWaves) void k_quantize_pack_long(
 
   // 1. all global loads of the slice, issued up front
   uint4 raw[S::kLoads];
-#pragma unroll
-  for (int u = 0; u < S::kLoads; ++u) {
-    const uint32_t c = (uint32_t)(u * kWave + lane);
-    const uint32_t cc = c < n_chunks ? c : n_chunks - 1u;    // lanes past the end repeat the last chunk
-    const u32x4 v = __builtin_nontemporal_load(&x[chunk0 + cc]);
-    raw[u] = make_uint4(v.x, v.y, v.z, v.w);
-  }
+  unit_tile_load<DT>(x, chunk0, n_chunks, lane, raw);
+  if constexpr (RELU) unit_tile_relu<DT>(raw, out_y, chunk0, n_chunks, lane);
   const uint32_t b = kMixed ? (uint32_t)bits[g] : (uint32_t)B;
   const uint32_t group_base = kMixed ? off[g] : (uint32_t)g * ((uint32_t)m * (uint32_t)B);
 
@@ -1246,9 +1259,9 @@ __global__ __launch_bounds__(kWave * kLongMaxWaves) void k_quantize_pack_long(
 // Takes plans whose groups are 32 * m elements, 128 < m <= 1024, when there are enough groups to
 // fill the device with one workgroup each, or when the two-pass route does not apply (groups
 // not a whole number of tiles).  Returns the groups it covered (all whole groups, or none).
-template <int DT>
+template <int DT, bool RELU>
 hipError_t launch_long(const daf_plan_t* p, const void* x, uint32_t seed_lo, uint32_t seed_hi, uint32_t* out_words,
-                       float* out_min, float* out_scale, int64_t* covered, hipStream_t stream) {
+                       float* out_min, float* out_scale, void* out_y, int64_t* covered, hipStream_t stream) {
   *covered = 0;
   const int32_t gs = p->group_size;
   const int32_t m = gs / 32;
@@ -1260,9 +1273,9 @@ hipError_t launch_long(const daf_plan_t* p, const void* x, uint32_t seed_lo, uin
   const int32_t units_per_wave = (m + n_waves - 1) / n_waves;
   const unsigned lds_bytes = (unsigned)(n_waves * (sizeof(LongWaveLds) + sizeof(float2)));
 #define DAF_LAUNCH(BITS)                                                                                          \
-  hipLaunchKernelGGL((k_quantize_pack_long<DT, BITS>), dim3((unsigned)full_groups), dim3(kWave * n_waves),        \
+  hipLaunchKernelGGL((k_quantize_pack_long<DT, BITS, RELU>), dim3((unsigned)full_groups), dim3(kWave * n_waves),  \
                      lds_bytes, stream, static_cast<const u32x4*>(x), m, units_per_wave, p->d_bits, p->d_off,     \
-                     seed_lo, seed_hi, out_words, out_min, out_scale)
+                     seed_lo, seed_hi, out_words, out_min, out_scale, static_cast<u32x4*>(out_y))
   switch (p->uniform_bits) {
     case 0: DAF_LAUNCH(0); break;
     case 1: DAF_LAUNCH(1); break;
@@ -1297,9 +1310,9 @@ inline bool unit_geometry(const daf_plan_t* p, UnitGeometry* u) {
 
 // Group sizes the unit path takes: 32 * m elements with 3 <= m <= 128 and m not a power of two
 // (those are the fast path's).  Returns the groups it covered.
-template <int DT>
+template <int DT, bool RELU>
 hipError_t launch_units(const daf_plan_t* p, const void* x, uint32_t seed_lo, uint32_t seed_hi, uint32_t* out_words,
-                        float* out_min, float* out_scale, int64_t* covered, hipStream_t stream) {
+                        float* out_min, float* out_scale, void* out_y, int64_t* covered, hipStream_t stream) {
   *covered = 0;
   UnitGeometry ug;
   if (!unit_geometry(p, &ug)) return hipSuccess;
@@ -1308,9 +1321,9 @@ hipError_t launch_units(const daf_plan_t* p, const void* x, uint32_t seed_lo, ui
   const uint32_t magic = (65536u + (uint32_t)m - 1u) / (uint32_t)m;   // floor(u / m) = (u * magic) >> 16 for u < 128
   const unsigned blocks = (unsigned)((n_tiles + kWavesPerBlock - 1) / kWavesPerBlock);
 #define DAF_LAUNCH(BITS)                                                                                       \
-  hipLaunchKernelGGL((k_quantize_pack_units<DT, BITS>), dim3(blocks), dim3(kThreads), 0, stream,               \
+  hipLaunchKernelGGL((k_quantize_pack_units<DT, BITS, RELU>), dim3(blocks), dim3(kThreads), 0, stream,         \
                      static_cast<const u32x4*>(x), n_tiles, m, k, k_last, magic, part_log2, p->d_bits, p->d_off, \
-                     seed_lo, seed_hi, out_words, out_min, out_scale)
+                     seed_lo, seed_hi, out_words, out_min, out_scale, static_cast<u32x4*>(out_y))
   switch (p->uniform_bits) {
     case 0: DAF_LAUNCH(0); break;
     case 1: DAF_LAUNCH(1); break;
@@ -1513,8 +1526,9 @@ hipError_t launch_dtype(const daf_plan_t* p, const void* x, uint64_t seed, uint3
   constexpr int kEpl = ElemTraits<DT>::kPerLoad;
   const int64_t full_groups = p->n / p->group_size;
   int64_t fast_groups = 0;
-  if (!METRICS && !RELU) {              // groups of 4128 .. 32768 elements, one workgroup each
-    const hipError_t e = launch_long<DT>(p, x, seed_lo, seed_hi, out_words, out_min, out_scale, &fast_groups, stream);
+  if (!METRICS) {                       // groups of 4128 .. 32768 elements, one workgroup each
+    const hipError_t e = launch_long<DT, RELU>(p, x, seed_lo, seed_hi, out_words, out_min, out_scale, out_y,
+                                               &fast_groups, stream);
     if (e != hipSuccess) return e;
   }
   if (fast_groups == 0 && p->d_big_scratch != nullptr) {    // groups longer than a tile (set up by daf_plan)
@@ -1546,8 +1560,9 @@ hipError_t launch_dtype(const daf_plan_t* p, const void* x, uint64_t seed, uint3
     if (e != hipSuccess) return e;
   }
 
-  if (fast_groups == 0 && !METRICS && !RELU) {
-    const hipError_t e = launch_units<DT>(p, x, seed_lo, seed_hi, out_words, out_min, out_scale, &fast_groups, stream);
+  if (fast_groups == 0 && !METRICS) {
+    const hipError_t e = launch_units<DT, RELU>(p, x, seed_lo, seed_hi, out_words, out_min, out_scale, out_y,
+                                                &fast_groups, stream);
     if (e != hipSuccess) return e;
   }
 

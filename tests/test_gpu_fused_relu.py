@@ -44,7 +44,7 @@ def _check(orc, z, dtype, gs, b, seed, got):
 
 
 @pytest.mark.parametrize("dtype", [F32, F16, BF16])
-@pytest.mark.parametrize("gs", [32, 64, 96, 128, 256, 1024, 4096])
+@pytest.mark.parametrize("gs", [32, 64, 96, 128, 160, 256, 768, 1024, 2080, 3072, 4096, 4128, 11008])
 @pytest.mark.parametrize("bits", [1, 2, 8, "mixed"])
 @pytest.mark.parametrize("in_place", [False, True])
 def test_fused_relu_matrix(env, dtype, gs, bits, in_place):
