@@ -107,15 +107,22 @@ __device__ __forceinline__ void store_elem(void* y, int64_t i, float v) {   // v
 
 // RELU = true: the input is z, every element is replaced by max(z, +0) before anything else, and
 // the result is also written to out_y (which may be the input buffer itself).
-template <int DT, bool METRICS = false, bool RELU = false>
+//
+// COOP = true: the four waves of a workgroup share one group (long groups, of which a call
+// usually has one: the tensor's short last group); the loops below then stride by the
+// workgroup and the waves exchange their (min, max) through LDS.
+template <int DT, bool METRICS = false, bool RELU = false, bool COOP = false>
 __global__ __launch_bounds__(kThreads) void k_quantize_pack_group(
     const void* x, int64_t n, int32_t gs, int64_t g_begin, int64_t g_end,
     const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, int32_t uniform_bits,
     uint32_t seed_lo, uint32_t seed_hi, uint32_t* __restrict__ words, float* __restrict__ out_min,
     float* __restrict__ out_scale, float* __restrict__ out_metrics, void* out_y) {
-  const int lane = threadIdx.x & (kWave - 1);
-  const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
-  const int64_t n_waves = (int64_t)gridDim.x * kWavesPerBlock;
+  static_assert(!(COOP && METRICS), "the metrics sums are reduced inside one wave");
+  constexpr int kStride = COOP ? kThreads : kWave;           // threads that share a group
+  __shared__ float2 coop_stat[kWavesPerBlock];
+  const int lane = COOP ? (int)threadIdx.x : (int)(threadIdx.x & (kWave - 1));   // index among them
+  const int64_t wave = COOP ? (int64_t)blockIdx.x : (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+  const int64_t n_waves = COOP ? (int64_t)gridDim.x : (int64_t)gridDim.x * kWavesPerBlock;
   for (int64_t g = g_begin + wave; g < g_end; g += n_waves) {
     const int64_t lo = g * (int64_t)gs;
     const int32_t len = (int32_t)((lo + gs <= n) ? gs : (n - lo));
@@ -123,16 +130,16 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_group(
     const uint32_t woff = uniform_bits ? (uint32_t)(g * (((int64_t)gs * uniform_bits) >> 5)) : off[g];
 
     float mn = load_elem<DT, RELU>(x, lo), mx = mn;        // element 0 exists in every group
-    for (int32_t j0 = lane; j0 < len; j0 += 8 * kWave) {    // eight loads in flight per lane
+    for (int32_t j0 = lane; j0 < len; j0 += 8 * kStride) {  // eight loads in flight per lane
       float v[8];
 #pragma unroll
       for (int q = 0; q < 8; ++q) {
-        const int32_t j = j0 + q * kWave;
+        const int32_t j = j0 + q * kStride;
         v[q] = load_elem<DT, RELU>(x, lo + (j < len ? j : j0));
       }
 #pragma unroll
       for (int q = 0; q < 8; ++q) {
-        const int32_t j = j0 + q * kWave;
+        const int32_t j = j0 + q * kStride;
         if (RELU && j < len) store_elem<DT>(out_y, lo + j, v[q]);   // every element passes here exactly once
         mn = fminf(mn, v[q]);
         mx = fmaxf(mx, v[q]);
@@ -141,6 +148,18 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_group(
     for (int o = 32; o > 0; o >>= 1) {
       mn = fminf(mn, __shfl_xor(mn, o));
       mx = fmaxf(mx, __shfl_xor(mx, o));
+    }
+    if (COOP) {
+      // (the barrier also orders the y written above before the reads below: in place, a thread
+      // re-reads elements that another wave has replaced by max(z, +0))
+      if ((threadIdx.x & (kWave - 1)) == 0) coop_stat[threadIdx.x >> 6] = make_float2(mn, mx);
+      __syncthreads();
+#pragma unroll
+      for (int w = 0; w < kWavesPerBlock; ++w) {
+        mn = fminf(mn, coop_stat[w].x);
+        mx = fmaxf(mx, coop_stat[w].y);
+      }
+      __syncthreads();                                     // before the next group overwrites the pairs
     }
     const GroupScale s = group_scale(mn, mx, b);
     if (lane == 0) {
@@ -155,7 +174,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_group(
     // takes two rounds): all loads of a round are issued before any is used, so a lone long
     // group costs one memory latency per round and not one per element.
     const int32_t per_round = (int32_t)(cpw < 16u ? cpw : 16u);
-    for (int32_t t = lane; t < n_words; t += kWave) {
+    for (int32_t t = lane; t < n_words; t += kStride) {
       uint32_t word = 0;
       for (int32_t c0 = 0; c0 < (int32_t)cpw; c0 += 16) {
         const int32_t j0 = t * (int32_t)cpw + c0;            // a multiple of per_round
@@ -1111,11 +1130,13 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_units(
   for (int u = 0; u < S::kLoads; ++u) {
     const uint32_t c = (uint32_t)(u * kWave + lane);
     if (c < n_chunks) {
-      const uint32_t grp = ((c >> S::kLanesLog2) * magic) >> 16;      // unit / m
-      const uint32_t lig = c - grp * group_chunks;                    // chunk inside its group
+      // (24-bit multiplications: every product here is far below 2^24, and the full 32-bit
+      // multiplication runs at a quarter of the rate)
+      const uint32_t grp = __umul24(c >> S::kLanesLog2, magic) >> 16;   // unit / m
+      const uint32_t lig = c - __umul24(grp, group_chunks);            // chunk inside its group
       const GroupInfo gi = lds.info[grp];
       const uint32_t b = kMixed ? (gi.b & 0xFFu) : (uint32_t)B;
-      const uint32_t addr = (gi.byte_off + ((lig * b * (uint32_t)kEpl) >> 3)) ^ (gi.b >> 8);
+      const uint32_t addr = (gi.byte_off + (__umul24(lig, b * (uint32_t)kEpl) >> 3)) ^ (gi.b >> 8);
       uint32_t n0, n1;
       if (need_exact2) quantize_chunk<DT, true>(xf[u], gi.mn, gi.invs, b, rnd[u], n0, n1);
       else             quantize_chunk<DT, false>(xf[u], gi.mn, gi.invs, b, rnd[u], n0, n1);
@@ -1241,7 +1262,7 @@ __global__ __launch_bounds__(kWave * kLongMaxWaves) void k_quantize_pack_long(
   for (int u = 0; u < S::kLoads; ++u) {
     const uint32_t c = (uint32_t)(u * kWave + lane);
     if (c < n_chunks) {
-      const uint32_t addr = ((c * lane_bits) >> 3) ^ swz;
+      const uint32_t addr = (__umul24(c, lane_bits) >> 3) ^ swz;
       uint32_t n0, n1;
       if (need_exact2) quantize_chunk<DT, true>(xf[u], s.mn, invs, b, rnd[u], n0, n1);
       else             quantize_chunk<DT, false>(xf[u], s.mn, invs, b, rnd[u], n0, n1);
@@ -1569,6 +1590,15 @@ hipError_t launch_dtype(const daf_plan_t* p, const void* x, uint64_t seed, uint3
   // general path for everything the tiles did not cover
   const int64_t rest = p->num_groups - fast_groups;
   if (rest > 0) {
+    if constexpr (!METRICS) {
+      if (p->group_size >= 1024) {         // long groups: a workgroup each
+        const int64_t blocks = rest < 65536 ? rest : 65536;
+        hipLaunchKernelGGL((k_quantize_pack_group<DT, false, RELU, true>), dim3((unsigned)blocks), dim3(kThreads), 0,
+                           stream, x, p->n, p->group_size, fast_groups, p->num_groups, p->d_bits, p->d_off,
+                           p->uniform_bits, seed_lo, seed_hi, out_words, out_min, out_scale, out_metrics, out_y);
+        return hipGetLastError();
+      }
+    }
     int64_t blocks = (rest + kWavesPerBlock - 1) / kWavesPerBlock;
     if (blocks > 65536) blocks = 65536;
     hipLaunchKernelGGL((k_quantize_pack_group<DT, METRICS, RELU>), dim3((unsigned)blocks), dim3(kThreads), 0, stream,
