@@ -1025,22 +1025,48 @@ __device__ __forceinline__ float2 unit_tile_stats(const uint4 (&raw)[UnitShape<D
   return st;
 }
 
-template <int DT, int B, bool RELU = false>
+// METRICS variant of the unit kernel: per-unit partial sums (error, magnitude, rounding variance;
+// one writer per entry), combined per group in a fixed order, so the sums do not depend on timing.
+struct UnitMetricsLds {
+  float gscale[kWave];
+  float usum[3][128];
+};
+struct UnitNoMetricsLds {};
+
+// Sum of a group's m per-unit values, returned in lane g < k for group g (same sharing of the
+// units among 2^part_log2 lanes as unit_tile_stats).
+__device__ __forceinline__ float unit_group_sum(const float* usum, int k, int m, int part_log2, int lane) {
+  const int part = 1 << part_log2;
+  int j = lane >> part_log2;
+  j = j < k ? j : k - 1;
+  const int p0 = lane & (part - 1);
+  const float* us = usum + j * m;
+  float acc = us[p0];
+  for (int i = p0 + part; i < m; i += part) acc += us[i];
+  for (int d = 1; d < part; d <<= 1) acc += __shfl_xor(acc, d);
+  return __shfl(acc, (lane < k ? lane : k - 1) << part_log2);
+}
+
+template <int DT, int B, bool RELU = false, bool METRICS = false>
 __global__ __launch_bounds__(kThreads) void k_quantize_pack_units(
     typename std::conditional<RELU, const u32x4*, const u32x4* __restrict__>::type x, int64_t n_tiles, int32_t m,
     int32_t k_full, int32_t k_last, uint32_t magic, int32_t part_log2,
     const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, uint32_t seed_lo, uint32_t seed_hi,
-    uint32_t* __restrict__ words, float* __restrict__ out_min, float* __restrict__ out_scale, u32x4* out_y) {
+    uint32_t* __restrict__ words, float* __restrict__ out_min, float* __restrict__ out_scale, u32x4* out_y,
+    float* __restrict__ out_metrics) {
   using S = UnitShape<DT>;
+  static_assert(!(RELU && METRICS), "the fused max(z, 0) and the fused metrics are separate variants");
   constexpr int kEpl = S::kEpl;
   constexpr bool kMixed = (B == 0);
   __shared__ UnitLds<DT> lds_all[kWavesPerBlock];
+  __shared__ typename std::conditional<METRICS, UnitMetricsLds, UnitNoMetricsLds>::type mlds_all[kWavesPerBlock];
 
   const int lane = threadIdx.x & (kWave - 1);
   const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int64_t tile = (int64_t)blockIdx.x * kWavesPerBlock + wave_in_block;
   if (tile >= n_tiles) return;
   UnitLds<DT>& lds = lds_all[wave_in_block];
+  auto& mlds = mlds_all[wave_in_block];
   uint8_t* stage8 = reinterpret_cast<uint8_t*>(lds.stage);
 
   const int k = (tile == n_tiles - 1) ? k_last : k_full;     // the last tile may hold fewer groups
@@ -1108,6 +1134,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_units(
       gi.b = my_b | (swz << 8);
       gi.byte_off = woff * 4u;
       lds.info[lane] = gi;
+      if constexpr (METRICS) mlds.gscale[lane] = s.scale;
     }
   }
 
@@ -1138,8 +1165,24 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_units(
       const uint32_t b = kMixed ? (gi.b & 0xFFu) : (uint32_t)B;
       const uint32_t addr = (gi.byte_off + (__umul24(lig, b * (uint32_t)kEpl) >> 3)) ^ (gi.b >> 8);
       uint32_t n0, n1;
-      if (need_exact2) quantize_chunk<DT, true>(xf[u], gi.mn, gi.invs, b, rnd[u], n0, n1);
-      else             quantize_chunk<DT, false>(xf[u], gi.mn, gi.invs, b, rnd[u], n0, n1);
+      if constexpr (METRICS) {
+        const float g_scale = mlds.gscale[grp];
+        float err, mag, var, unused = 0.0f;
+        if (need_exact2)
+          quantize_chunk<DT, true, true>(xf[u], gi.mn, gi.invs, b, rnd[u], n0, n1, g_scale, &err, &mag, &var);
+        else
+          quantize_chunk<DT, false, true>(xf[u], gi.mn, gi.invs, b, rnd[u], n0, n1, g_scale, &err, &mag, &var);
+        seg_sum2<S::kLanesLog2>(err, mag);       // over the unit's lanes (all valid, or none)
+        seg_sum2<S::kLanesLog2>(var, unused);
+        if ((lane & ((1 << S::kLanesLog2) - 1)) == (1 << S::kLanesLog2) - 1) {
+          mlds.usum[0][c >> S::kLanesLog2] = err;
+          mlds.usum[1][c >> S::kLanesLog2] = mag;
+          mlds.usum[2][c >> S::kLanesLog2] = var;
+        }
+      } else {
+        if (need_exact2) quantize_chunk<DT, true>(xf[u], gi.mn, gi.invs, b, rnd[u], n0, n1);
+        else             quantize_chunk<DT, false>(xf[u], gi.mn, gi.invs, b, rnd[u], n0, n1);
+      }
       stage_chunk<kEpl>(stage8, addr, b, n0, n1, lane);
     }
   }
@@ -1148,6 +1191,18 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_units(
   // 6. the tile's words are one contiguous run in the packed buffer
   uint32_t* dst = words + tile_base;
   for (uint32_t i = lane; i < tile_words; i += kWave) dst[i] = lds.stage[i];
+  if constexpr (METRICS) {
+    const float err = unit_group_sum(mlds.usum[0], k, m, part_log2, lane);
+    const float mag = unit_group_sum(mlds.usum[1], k, m, part_log2, lane);
+    const float var = unit_group_sum(mlds.usum[2], k, m, part_log2, lane);
+    if (lane < k) {
+      const float sc = mlds.gscale[lane];
+      float* o = out_metrics + 3 * (g0 + lane);
+      o[0] = err;
+      o[1] = mag;
+      o[2] = (var * 1.52587890625e-05f) * (sc * sc);
+    }
+  }
 }
 
 // Long groups, 128 < m <= 1024 units (4096 < group size <= 32768 elements, e.g. a row of
@@ -1331,9 +1386,10 @@ inline bool unit_geometry(const daf_plan_t* p, UnitGeometry* u) {
 
 // Group sizes the unit path takes: 32 * m elements with 3 <= m <= 128 and m not a power of two
 // (those are the fast path's).  Returns the groups it covered.
-template <int DT, bool RELU>
+template <int DT, bool RELU, bool METRICS>
 hipError_t launch_units(const daf_plan_t* p, const void* x, uint32_t seed_lo, uint32_t seed_hi, uint32_t* out_words,
-                        float* out_min, float* out_scale, void* out_y, int64_t* covered, hipStream_t stream) {
+                        float* out_min, float* out_scale, void* out_y, float* out_metrics, int64_t* covered,
+                        hipStream_t stream) {
   *covered = 0;
   UnitGeometry ug;
   if (!unit_geometry(p, &ug)) return hipSuccess;
@@ -1342,9 +1398,9 @@ hipError_t launch_units(const daf_plan_t* p, const void* x, uint32_t seed_lo, ui
   const uint32_t magic = (65536u + (uint32_t)m - 1u) / (uint32_t)m;   // floor(u / m) = (u * magic) >> 16 for u < 128
   const unsigned blocks = (unsigned)((n_tiles + kWavesPerBlock - 1) / kWavesPerBlock);
 #define DAF_LAUNCH(BITS)                                                                                       \
-  hipLaunchKernelGGL((k_quantize_pack_units<DT, BITS, RELU>), dim3(blocks), dim3(kThreads), 0, stream,         \
+  hipLaunchKernelGGL((k_quantize_pack_units<DT, BITS, RELU, METRICS>), dim3(blocks), dim3(kThreads), 0, stream, \
                      static_cast<const u32x4*>(x), n_tiles, m, k, k_last, magic, part_log2, p->d_bits, p->d_off, \
-                     seed_lo, seed_hi, out_words, out_min, out_scale, static_cast<u32x4*>(out_y))
+                     seed_lo, seed_hi, out_words, out_min, out_scale, static_cast<u32x4*>(out_y), out_metrics)
   switch (p->uniform_bits) {
     case 0: DAF_LAUNCH(0); break;
     case 1: DAF_LAUNCH(1); break;
@@ -1581,9 +1637,9 @@ hipError_t launch_dtype(const daf_plan_t* p, const void* x, uint64_t seed, uint3
     if (e != hipSuccess) return e;
   }
 
-  if (fast_groups == 0 && !METRICS) {
-    const hipError_t e = launch_units<DT, RELU>(p, x, seed_lo, seed_hi, out_words, out_min, out_scale, out_y,
-                                                &fast_groups, stream);
+  if (fast_groups == 0) {
+    const hipError_t e = launch_units<DT, RELU, METRICS>(p, x, seed_lo, seed_hi, out_words, out_min, out_scale, out_y,
+                                                         out_metrics, &fast_groups, stream);
     if (e != hipSuccess) return e;
   }
 
