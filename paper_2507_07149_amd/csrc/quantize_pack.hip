@@ -1048,9 +1048,9 @@ __device__ __forceinline__ float unit_group_sum(const float* usum, int k, int m,
 }
 
 template <int DT, int B, bool RELU = false, bool METRICS = false>
-__global__ __launch_bounds__(kThreads) void k_quantize_pack_units(
-    typename std::conditional<RELU, const u32x4*, const u32x4* __restrict__>::type x, int64_t n_tiles, int32_t m,
-    int32_t k_full, int32_t k_last, uint32_t magic, int32_t part_log2,
+__device__ __forceinline__ void quantize_pack_units_body(
+    typename std::conditional<RELU, const u32x4*, const u32x4* __restrict__>::type x, int64_t tile, int wave_in_block,
+    int64_t n_tiles, int32_t m, int32_t k_full, int32_t k_last, uint32_t magic, int32_t part_log2,
     const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, uint32_t seed_lo, uint32_t seed_hi,
     uint32_t* __restrict__ words, float* __restrict__ out_min, float* __restrict__ out_scale, u32x4* out_y,
     float* __restrict__ out_metrics) {
@@ -1062,9 +1062,6 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_units(
   __shared__ typename std::conditional<METRICS, UnitMetricsLds, UnitNoMetricsLds>::type mlds_all[kWavesPerBlock];
 
   const int lane = threadIdx.x & (kWave - 1);
-  const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int64_t tile = (int64_t)blockIdx.x * kWavesPerBlock + wave_in_block;
-  if (tile >= n_tiles) return;
   UnitLds<DT>& lds = lds_all[wave_in_block];
   auto& mlds = mlds_all[wave_in_block];
   uint8_t* stage8 = reinterpret_cast<uint8_t*>(lds.stage);
@@ -1363,6 +1360,54 @@ hipError_t launch_long(const daf_plan_t* p, const void* x, uint32_t seed_lo, uin
 #undef DAF_LAUNCH
   *covered = full_groups;
   return hipGetLastError();
+}
+
+template <int DT, int B, bool RELU = false, bool METRICS = false>
+__global__ __launch_bounds__(kThreads) void k_quantize_pack_units(
+    typename std::conditional<RELU, const u32x4*, const u32x4* __restrict__>::type x, int64_t n_tiles, int32_t m,
+    int32_t k_full, int32_t k_last, uint32_t magic, int32_t part_log2,
+    const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, uint32_t seed_lo, uint32_t seed_hi,
+    uint32_t* __restrict__ words, float* __restrict__ out_min, float* __restrict__ out_scale, u32x4* out_y,
+    float* __restrict__ out_metrics) {
+  const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t tile = (int64_t)blockIdx.x * kWavesPerBlock + wave_in_block;
+  if (tile >= n_tiles) return;
+  quantize_pack_units_body<DT, B, RELU, METRICS>(x, tile, wave_in_block, n_tiles, m, k_full, k_last, magic, part_log2,
+                                                 bits, off, seed_lo, seed_hi, words, out_min, out_scale, out_y,
+                                                 out_metrics);
+}
+
+// Several tensors in one launch, as k_quantize_pack_tile_batch; the entries may have different
+// group sizes (the tile geometry travels with each entry).
+struct UnitBatchEntry {
+  const void* x;
+  const uint8_t* bits;
+  const uint32_t* off;
+  uint32_t* words;
+  float* mn;
+  float* sc;
+  int64_t tile_end;                                 // tiles of this and all earlier entries
+  uint32_t seed_lo, seed_hi;
+  int32_t m, k, k_last, part_log2;
+  uint32_t magic;
+};
+struct UnitBatch {
+  UnitBatchEntry e[kMaxBatch];
+  int32_t n;
+};
+
+template <int DT, int B>
+__global__ __launch_bounds__(kThreads) void k_quantize_pack_units_batch(const UnitBatch batch) {
+  const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t gtile = (int64_t)blockIdx.x * kWavesPerBlock + wave_in_block;
+  if (gtile >= batch.e[batch.n - 1].tile_end) return;
+  int t = 0;
+  while (gtile >= batch.e[t].tile_end) ++t;         // uniform over the wave; t < batch.n by the check above
+  const UnitBatchEntry& e = batch.e[t];
+  const int64_t first = t ? batch.e[t - 1].tile_end : 0;
+  quantize_pack_units_body<DT, B>(static_cast<const u32x4*>(e.x), gtile - first, wave_in_block, e.tile_end - first, e.m,
+                                  e.k, e.k_last, e.magic, e.part_log2, e.bits, e.off, e.seed_lo, e.seed_hi, e.words,
+                                  e.mn, e.sc, nullptr, nullptr);
 }
 
 // Geometry of the unit path for a plan, shared by the quantize and the statistics launchers.
@@ -1735,17 +1780,72 @@ template <int DT>
 hipError_t launch_items(const daf_quantize_item_t* items, int32_t n_items, hipStream_t stream) {
   Batch batch;
   batch.n = 0;
-  int cur_log2 = -1, cur_gs = -1, cur_bits = -1;
+  UnitBatch ubatch;                    // items of the unit path (group sizes that are not a power of two)
+  ubatch.n = 0;
+  int cur_log2 = -1, cur_gs = -1, cur_bits = -1, ucur_bits = -1;
   hipError_t err = hipSuccess;
   auto flush = [&]() {
     if (batch.n > 0 && err == hipSuccess) err = launch_batch<DT>(batch, cur_log2, cur_bits, stream);
     batch.n = 0;
+  };
+  auto uflush = [&]() {
+    if (ubatch.n > 0 && err == hipSuccess) {
+      const unsigned blocks = (unsigned)((ubatch.e[ubatch.n - 1].tile_end + kWavesPerBlock - 1) / kWavesPerBlock);
+#define DAF_LAUNCH(BITS) \
+  hipLaunchKernelGGL((k_quantize_pack_units_batch<DT, BITS>), dim3(blocks), dim3(kThreads), 0, stream, ubatch)
+      switch (ucur_bits) {
+        case 0: DAF_LAUNCH(0); break;
+        case 1: DAF_LAUNCH(1); break;
+        case 2: DAF_LAUNCH(2); break;
+        case 4: DAF_LAUNCH(4); break;
+        case 8: DAF_LAUNCH(8); break;
+        default: err = hipErrorInvalidValue; break;
+      }
+#undef DAF_LAUNCH
+      if (err == hipSuccess) err = hipGetLastError();
+    }
+    ubatch.n = 0;
   };
   for (int32_t i = 0; i < n_items && err == hipSuccess; ++i) {
     const daf_quantize_item_t& it = items[i];
     const daf_plan_t* p = it.plan;
     int log2 = 0;
     int64_t n_tiles = 0, fast_groups = 0;
+    UnitGeometry ug;
+    if (p->d_big_scratch == nullptr && unit_geometry(p, &ug)) {
+      if (ubatch.n == kMaxBatch || (ubatch.n > 0 && p->uniform_bits != ucur_bits) ||
+          (ubatch.n > 0 && ubatch.e[ubatch.n - 1].tile_end + ug.n_tiles > 0x7fffffff))
+        uflush();
+      ucur_bits = p->uniform_bits;
+      UnitBatchEntry& e = ubatch.e[ubatch.n];
+      e.x = it.x;
+      e.bits = p->d_bits;
+      e.off = p->d_off;
+      e.words = it.out_words;
+      e.mn = it.out_min;
+      e.sc = it.out_scale;
+      e.tile_end = (ubatch.n ? ubatch.e[ubatch.n - 1].tile_end : 0) + ug.n_tiles;
+      e.seed_lo = (uint32_t)it.seed;
+      e.seed_hi = (uint32_t)(it.seed >> 32);
+      e.m = ug.m;
+      e.k = ug.k;
+      e.k_last = ug.k_last;
+      e.part_log2 = ug.part_log2;
+      e.magic = (65536u + (uint32_t)ug.m - 1u) / (uint32_t)ug.m;
+      ++ubatch.n;
+      if (p->num_groups > ug.full_groups && err == hipSuccess) {        // the short last group
+        if (p->group_size >= 1024)
+          hipLaunchKernelGGL((k_quantize_pack_group<DT, false, false, true>), dim3(1), dim3(kThreads), 0, stream, it.x,
+                             p->n, p->group_size, ug.full_groups, p->num_groups, p->d_bits, p->d_off, p->uniform_bits,
+                             e.seed_lo, e.seed_hi, it.out_words, it.out_min, it.out_scale, nullptr, nullptr);
+        else
+          hipLaunchKernelGGL((k_quantize_pack_group<DT, false, false>), dim3(1), dim3(kThreads), 0, stream, it.x,
+                             p->n, p->group_size, ug.full_groups, p->num_groups, p->d_bits, p->d_off, p->uniform_bits,
+                             e.seed_lo, e.seed_hi, it.out_words, it.out_min, it.out_scale, nullptr, nullptr);
+        err = hipGetLastError();
+      }
+      continue;
+    }
     if (!tile_geometry<DT>(p, &log2, &n_tiles, &fast_groups)) {
       flush();
       if (err == hipSuccess)
@@ -1778,6 +1878,7 @@ hipError_t launch_items(const daf_quantize_item_t* items, int32_t n_items, hipSt
     }
   }
   flush();
+  uflush();
   return err;
 }
 

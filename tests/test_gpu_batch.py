@@ -66,6 +66,21 @@ def test_batch_of_unlike_tensors(env, dtype):
                                  (1000, 96, 2), (20000, 8192, 1), (4096 * 2, 128, 4), (33, 32, "mixed")])
 
 
+@pytest.mark.parametrize("dtype", [F32, F16, BF16])
+def test_batch_of_tensors_with_row_sized_groups(env, dtype):
+    """Group sizes that are not a power of two share one launch whatever their size, as long as
+    the width kind is the same; power-of-two items in between keep their own batches."""
+    daf, orc = env
+    _roundtrip(daf, orc, dtype, [(768 * 40, 768, 2), (3072 * 9 + 5, 3072, 2), (96 * 100 + 96 * 3, 96, 2), (4096 * 3, 256, 2),
+                                 (160 * 77 + 33, 160, 2), (768 * 11, 768, "mixed"), (4064 * 3 + 1500, 4064, "mixed"),
+                                 (4096 * 2, 64, "mixed"), (2080 * 7, 2080, 8), (11008 * 3 + 100, 11008, 8)])
+
+
+def test_batch_of_many_row_sized_tensors(env):
+    daf, orc = env
+    _roundtrip(daf, orc, BF16, [(768 * (5 + i % 4), 768 if i % 3 else 3072, 4) for i in range(40)])
+
+
 def test_batch_longer_than_one_launch(env):
     daf, orc = env
     _roundtrip(daf, orc, F32, [(4096 * (1 + i % 3), 256, 2) for i in range(70)])
