@@ -71,6 +71,17 @@ def test_grad_weight_shapes(env, shape, bits):
 
 
 # N a multiple of 64 but not of 256: the last tile of n has waves outside the output
+@pytest.mark.parametrize("case", [(64, 256, 768, 768, "mixed", BF16), (96, 256, 768, 384, 4, F16), (64, 64, 704, 704, "mixed", F32),
+                                  (128, 512, 3072, 3072, "mixed", BF16), (64, 256, 1536, 96, "mixed", F16),
+                                  (32, 256, 2816, 1408, 2, BF16)])
+def test_grad_weight_groups_that_are_rows_or_not_a_power_of_two(env, case):
+    """One group per row of the activation (768, 3072), half rows, and small odd multiples of 32."""
+    daf, orc = env
+    M, N, K, gs, bits, dtype = case
+    print("case", case, flush=True)
+    _case(daf, orc, M, N, K, gs, bits, dtype, 19)
+
+
 @pytest.mark.parametrize("case", [(256, 64, 256, 64, "mixed", BF16), (128, 320, 384, 32, 2, F16), (512, 192, 128, 128, "mixed", F32),
                                   (8192, 64, 256, 64, 4, F32), (2048, 448, 192, 64, "mixed", BF16),
                                   (32, 4160, 4096, 64, "mixed", BF16)])       # the last: 256-column tile, 17 tiles of n
