@@ -88,3 +88,37 @@ def test_fused_relu_random_cases(seed):
         print("case relu sweep", seed, case, dtype, gs, n, kind, in_place, flush=True)
         _check(orc, z, dtype, gs, b, sd, _run(daf, plan, z.clone(), sd, in_place))
         plan.destroy()
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_any_group_size_random_cases(H, seed):
+    """Group sizes drawn from every regime of the dispatch (32 * m for m around 1 ... 1100, with
+    extra weight on the borders between the kernels), random lengths with and without whole
+    last groups: quantize + dequantize against the oracle, and the statistics-only call."""
+    import paper_2507_07149_amd as daf
+    from oracle import daf_oracle as orc
+    rng = np.random.default_rng(3000 + seed)
+    borders = [1, 2, 3, 4, 5, 63, 64, 65, 127, 128, 129, 130, 255, 256, 257, 384, 511, 512, 513, 1023, 1024, 1025, 1030]
+    for case in range(14):
+        m = int(rng.choice(borders)) if rng.random() < 0.5 else int(rng.integers(1, 1100))
+        gs = 32 * m
+        groups = int(rng.integers(1, max(2, 300000 // gs)))
+        n = groups * gs + (int(rng.integers(1, gs)) if rng.random() < 0.6 else 0)
+        dtype = int(rng.choice([F32, F16, BF16]))
+        G = (n + gs - 1) // gs
+        kind = int(rng.integers(0, 5))
+        bits = (rng.choice([1, 2, 4, 8], G).astype(np.uint8) if kind == 4 else np.array([[1, 2, 4, 8][kind]], np.uint8))
+        g = torch.Generator().manual_seed(int(rng.integers(0, 1 << 30)))
+        x = (torch.randn(n, generator=g) * float(np.exp(rng.normal(0, 2)))).to(torch_dtype(dtype))
+        x[torch.isinf(x.float())] = 0
+        w = Workload(f"anygs{seed}_{case}_dt{dtype}_m{m}_n{n}_k{kind}", x, dtype, gs, bits, int(rng.integers(0, 1 << 40)))
+        print("case", w.name, flush=True)
+        res = H.run_hip(w)
+        H.assert_full_parity(w, res)
+        mn = torch.full((G,), float("nan"), device="cuda:0")
+        mx = torch.full((G,), float("nan"), device="cuda:0")
+        daf.daf_group_minmax(res.plan, x.cuda(), mn, mx)
+        torch.cuda.synchronize()
+        omn, omx = orc.group_minmax(to_numpy_bits(x), dtype, gs)
+        assert np.array_equal(mn.cpu().numpy().view(np.uint32), omn.view(np.uint32)), w.name
+        assert np.array_equal(mx.cpu().numpy().view(np.uint32), omx.view(np.uint32)), w.name
