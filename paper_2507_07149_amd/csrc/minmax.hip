@@ -23,8 +23,14 @@ namespace {
 using namespace daf;
 
 constexpr int kThreads = 256;
-constexpr int kUnroll = 4;                      // 16-byte chunks in flight per thread and iteration
-constexpr int kMaxBlocks = 2048;
+// 16-byte chunks in flight per thread and iteration, and the largest grid, per method (measured
+// on a 51 M-element tensor: two-pass 39.6 us with 4 chunks and 2048 workgroups, 34.7 us with 8
+// and 1024; the atomic form serialises on its one result, so it takes one workgroup per compute
+// unit with more loads in flight each: 166 us with 4 and 2048, 42.6 us with 16 and 256).
+constexpr int kUnroll = 8;
+constexpr int kMaxBlocks = 1024;
+constexpr int kUnrollAtomic = 16;
+constexpr int kMaxBlocksAtomic = 256;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 struct MinMaxWorkspace {          // layout of the caller's workspace
@@ -91,6 +97,7 @@ __global__ __launch_bounds__(kThreads) void k_minmax(const void* __restrict__ x,
                                                      MinMaxWorkspace* __restrict__ ws,
                                                      float* __restrict__ out_minmax) {
   constexpr int kEpl = ElemTraits<DT>::kPerLoad;
+  constexpr int kU = ATOMIC ? kUnrollAtomic : kUnroll;
   __shared__ float2 lds[kThreads / kWave];
   const u32x4* chunks = static_cast<const u32x4*>(x);
   const int64_t n_chunks = n / kEpl;
@@ -100,12 +107,12 @@ __global__ __launch_bounds__(kThreads) void k_minmax(const void* __restrict__ x,
 
   const int64_t stride = (int64_t)gridDim.x * kThreads;
   int64_t c = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-  for (; c + (kUnroll - 1) * stride < n_chunks; c += kUnroll * stride) {
-    u32x4 v[kUnroll];
+  for (; c + (kU - 1) * stride < n_chunks; c += kU * stride) {
+    u32x4 v[kU];
 #pragma unroll
-    for (int k = 0; k < kUnroll; ++k) v[k] = __builtin_nontemporal_load(&chunks[c + k * stride]);
+    for (int k = 0; k < kU; ++k) v[k] = __builtin_nontemporal_load(&chunks[c + k * stride]);
 #pragma unroll
-    for (int k = 0; k < kUnroll; k += 2) {
+    for (int k = 0; k < kU; k += 2) {
       chunk_minmax<DT>(v[k], mn, mx);
       chunk_minmax<DT>(v[k + 1], mn2, mx2);
     }
@@ -172,9 +179,11 @@ template <int DT>
 hipError_t launch(const void* x, int64_t n, int method, MinMaxWorkspace* ws, float* out, hipStream_t stream) {
   constexpr int kEpl = ElemTraits<DT>::kPerLoad;
   const int64_t n_chunks = n / kEpl;
-  int64_t blocks = (n_chunks + (int64_t)kThreads * kUnroll - 1) / ((int64_t)kThreads * kUnroll);
+  const int unroll = method == DAF_REDUCE_ATOMIC ? kUnrollAtomic : kUnroll;
+  const int cap = method == DAF_REDUCE_ATOMIC ? kMaxBlocksAtomic : kMaxBlocks;
+  int64_t blocks = (n_chunks + (int64_t)kThreads * unroll - 1) / ((int64_t)kThreads * unroll);
   if (blocks < 1) blocks = 1;
-  if (blocks > kMaxBlocks) blocks = kMaxBlocks;
+  if (blocks > cap) blocks = cap;
   if (method == DAF_REDUCE_ATOMIC) {
     hipLaunchKernelGGL((k_minmax<DT, true>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, x, n, ws, out);
     return hipGetLastError();
