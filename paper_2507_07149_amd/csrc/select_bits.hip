@@ -24,11 +24,15 @@ constexpr int kThreads = 256;
 constexpr int kItems = 8;                        // consecutive groups per thread in the ordered passes
 constexpr int kBlockGroups = kThreads * kItems;  // 2048
 constexpr int kMaxThresholds = 3;                // C <= 4
+constexpr int kHistCopies = 16;
 
 struct SelectState {
   uint32_t prefix[kMaxThresholds];      // digits of T_k decided so far
   uint32_t rank[kMaxThresholds];        // rank still to be located inside the prefix bucket; E_k at the end
-  uint32_t hist[kMaxThresholds][256];
+  // kHistCopies copies of the histograms, a workgroup adds to copy (its index mod kHistCopies):
+  // atomics to one address are served one after the other at the memory side (about 8 ns each),
+  // and with few distinct digits every workgroup hits the same few counters.
+  uint32_t hist[kHistCopies][kMaxThresholds][256];
 };
 
 __global__ __launch_bounds__(kThreads) void k_select_keys(const float* __restrict__ gmin, const float* __restrict__ gmax,
@@ -44,11 +48,30 @@ __global__ __launch_bounds__(kThreads) void k_select_keys(const float* __restric
     st->rank[2] = r2;
   }
   if (blockIdx.x == 0) {
-    for (int i = threadIdx.x; i < kMaxThresholds * 256; i += kThreads) (&st->hist[0][0])[i] = 0u;
+    for (int i = threadIdx.x; i < kHistCopies * kMaxThresholds * 256; i += kThreads) (&st->hist[0][0][0])[i] = 0u;
   }
 }
 
-// Histogram of the digit at `shift` among the keys whose higher digits equal the prefix.
+// Adds one count per active lane to h[digit].  The digits of a wave are often few (the leading
+// digit of a range is its sign and most of its exponent), and LDS atomics of one instruction to
+// one address are served one after the other: the three most frequent leaders' digits are
+// counted with a ballot and added once, whatever is left goes one lane at a time.
+__device__ __forceinline__ void wave_hist_add(uint32_t* h, uint32_t digit, bool active) {
+  const int lane = threadIdx.x & (kWave - 1);
+  uint64_t todo = __builtin_amdgcn_ballot_w64(active);
+  for (int round = 0; round < 3 && todo != 0ull; ++round) {
+    const int leader = __builtin_ctzll(todo);
+    const uint32_t d = (uint32_t)__builtin_amdgcn_readlane((int)digit, leader);
+    const uint64_t same = __builtin_amdgcn_ballot_w64(active && digit == d) & todo;
+    if (__builtin_popcountll(same) < 4) break;           // spread-out digits: plain atomics are cheaper
+    if (lane == leader) atomicAdd(&h[d], (uint32_t)__builtin_popcountll(same));
+    todo &= ~same;
+  }
+  if ((todo >> lane) & 1ull) atomicAdd(&h[digit], 1u);
+}
+
+// Histogram of the digit at `shift` among the keys whose higher digits equal the prefix.  In
+// the first pass (shift 24) every key counts for every threshold: one histogram serves all.
 __global__ __launch_bounds__(kThreads) void k_select_hist(const uint32_t* __restrict__ keys, int64_t G,
                                                           SelectState* __restrict__ st, int n_thresholds, int shift) {
   __shared__ uint32_t lh[kMaxThresholds][256];
@@ -57,18 +80,45 @@ __global__ __launch_bounds__(kThreads) void k_select_hist(const uint32_t* __rest
   uint32_t prefix[kMaxThresholds];
   for (int k = 0; k < kMaxThresholds; ++k) prefix[k] = st->prefix[k];
   const int64_t stride = (int64_t)gridDim.x * kThreads;
-  for (int64_t g = (int64_t)blockIdx.x * kThreads + threadIdx.x; g < G; g += stride) {
-    const uint32_t key = keys[g];
-    const uint32_t digit = (key >> shift) & 0xFFu;
-    for (int k = 0; k < n_thresholds; ++k) {
-      const bool match = (shift == 24) || (((key ^ prefix[k]) >> (shift + 8)) == 0u);
-      if (match) atomicAdd(&lh[k][digit], 1u);
+  // every lane of a wave makes the same number of trips (the ballots need whole waves); lanes
+  // past the end take part with nothing to add
+  // Sixteen keys per lane and trip: four 16-byte loads issued together (the key array is padded
+  // to whole chunks), so that enough bytes are in flight; a wave takes 256 consecutive chunks.
+  constexpr int kLoads = 4;
+  const int64_t n_chunks = (G + 3) >> 2;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t wave_stride = stride / kWave * (kWave * kLoads);
+  const int64_t first = ((int64_t)blockIdx.x * (kThreads / kWave) + (threadIdx.x >> 6)) * (kWave * kLoads);
+  for (int64_t c0 = first; c0 < n_chunks; c0 += wave_stride) {
+    uint4 v[kLoads];
+#pragma unroll
+    for (int j = 0; j < kLoads; ++j) {
+      const int64_t c = c0 + j * kWave + lane;
+      v[j] = make_uint4(0u, 0u, 0u, 0u);
+      if (c < n_chunks) v[j] = reinterpret_cast<const uint4*>(keys)[c];
+    }
+#pragma unroll
+    for (int j = 0; j < kLoads; ++j) {
+      const int64_t c = c0 + j * kWave + lane;
+      const uint32_t key4[4] = {v[j].x, v[j].y, v[j].z, v[j].w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const bool in = c * 4 + e < G;
+        const uint32_t key = key4[e];
+        const uint32_t digit = (key >> shift) & 0xFFu;
+        if (shift == 24) {
+          wave_hist_add(lh[0], digit, in);
+        } else {
+          for (int k = 0; k < n_thresholds; ++k)
+            wave_hist_add(lh[k], digit, in && (((key ^ prefix[k]) >> (shift + 8)) == 0u));
+        }
+      }
     }
   }
   __syncthreads();
   for (int i = threadIdx.x; i < n_thresholds * 256; i += kThreads) {
-    const uint32_t c = (&lh[0][0])[i];
-    if (c) atomicAdd(&(&st->hist[0][0])[i], c);
+    const uint32_t c = (shift == 24) ? lh[0][i & 255] : (&lh[0][0])[i];
+    if (c) atomicAdd(&(&st->hist[blockIdx.x % kHistCopies][0][0])[i], c);
   }
 }
 
@@ -76,7 +126,11 @@ __global__ __launch_bounds__(kThreads) void k_select_hist(const uint32_t* __rest
 __global__ __launch_bounds__(256) void k_select_pick(SelectState* __restrict__ st, int n_thresholds, int shift) {
   __shared__ uint32_t cum[256];
   for (int k = 0; k < n_thresholds; ++k) {
-    const uint32_t h = st->hist[k][threadIdx.x];
+    uint32_t h = 0u;
+    for (int r = 0; r < kHistCopies; ++r) {
+      h += st->hist[r][k][threadIdx.x];
+      st->hist[r][k][threadIdx.x] = 0u;                  // ready for the next pass
+    }
     cum[threadIdx.x] = h;
     __syncthreads();
     uint32_t acc = h;                                    // inclusive scan over the 256 bins
@@ -94,9 +148,45 @@ __global__ __launch_bounds__(256) void k_select_pick(SelectState* __restrict__ s
       st->prefix[k] |= (uint32_t)threadIdx.x << shift;
       st->rank[k] = rank - before;
     }
-    st->hist[k][threadIdx.x] = 0u;                       // ready for the next pass
     __syncthreads();
   }
+}
+
+// A thread's kItems consecutive keys: two 16-byte loads (the key array is padded to a multiple
+// of four entries and 16-byte aligned, and a thread's first index is a multiple of eight);
+// entries at or past G read as 0xFFFFFFFF.
+__device__ __forceinline__ void load_keys(const uint32_t* __restrict__ keys, int64_t base, int64_t G,
+                                          uint32_t (&key)[kItems]) {
+  static_assert(kItems == 8, "two uint4 loads");
+  const int64_t padded = (G + 3) & ~(int64_t)3;
+  uint4 a = make_uint4(~0u, ~0u, ~0u, ~0u), b = a;
+  if (base < padded) a = *reinterpret_cast<const uint4*>(keys + base);
+  if (base + 4 < padded) b = *reinterpret_cast<const uint4*>(keys + base + 4);
+  key[0] = a.x; key[1] = a.y; key[2] = a.z; key[3] = a.w;
+  key[4] = b.x; key[5] = b.y; key[6] = b.z; key[7] = b.w;
+#pragma unroll
+  for (int i = 0; i < kItems; ++i)
+    if (base + i >= G) key[i] = 0xFFFFFFFFu;
+}
+
+// Exclusive prefix sum of one value per thread over the kThreads threads of a workgroup, and the
+// workgroup's total: a DPP scan inside each wave, the wave totals through LDS (two barriers).
+__device__ __forceinline__ uint32_t block_exclusive_sum(uint32_t v, uint32_t* wave_tot, uint32_t* total) {
+  constexpr int kWaves = kThreads / kWave;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+  const uint32_t incl = wave_inclusive_sum(v);
+  __syncthreads();                                       // wave_tot may still be read from an earlier call
+  if (lane == kWave - 1) wave_tot[wave] = incl;
+  __syncthreads();
+  uint32_t before = 0u, all = 0u;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) {
+    const uint32_t t = wave_tot[w];
+    before += (w < wave) ? t : 0u;
+    all += t;
+  }
+  *total = all;
+  return before + incl - v;
 }
 
 // Per block of 2048 consecutive groups: how many keys equal each threshold.
@@ -108,11 +198,14 @@ __global__ __launch_bounds__(kThreads) void k_select_tie_count(const uint32_t* _
   __syncthreads();
   const int64_t base = (int64_t)blockIdx.x * kBlockGroups + (int64_t)threadIdx.x * kItems;
   uint32_t c[kMaxThresholds] = {0u, 0u, 0u};
+  uint32_t key[kItems];
+  load_keys(keys, base, G, key);
+  uint32_t T[kMaxThresholds];
+  for (int k = 0; k < kMaxThresholds; ++k) T[k] = st->prefix[k];
+#pragma unroll
   for (int i = 0; i < kItems; ++i) {
-    const int64_t g = base + i;
-    if (g < G) {
-      const uint32_t key = keys[g];
-      for (int k = 0; k < n_thresholds; ++k) c[k] += (key == st->prefix[k]) ? 1u : 0u;
+    if (base + i < G) {
+      for (int k = 0; k < n_thresholds; ++k) c[k] += (key[i] == T[k]) ? 1u : 0u;
     }
   }
   for (int k = 0; k < n_thresholds; ++k)
@@ -121,29 +214,24 @@ __global__ __launch_bounds__(kThreads) void k_select_tie_count(const uint32_t* _
   if (threadIdx.x < (unsigned)n_thresholds) block_ties[(int64_t)threadIdx.x * gridDim.x + blockIdx.x] = cnt[threadIdx.x];
 }
 
-// One workgroup: exclusive scan of the per-block tie counts, per threshold, in place.
+// One workgroup: exclusive scan of the per-block tie counts, per threshold, in place.  A thread
+// takes a run of consecutive entries, the runs' sums are scanned across the workgroup.
 __global__ __launch_bounds__(kThreads) void k_select_tie_scan(uint32_t* __restrict__ block_ties, int64_t n_blocks,
                                                               int n_thresholds) {
-  __shared__ uint32_t lds[kThreads];
+  __shared__ uint32_t wave_tot[kThreads / kWave];
+  const int64_t per = (n_blocks + kThreads - 1) / kThreads;
+  const int64_t lo = (int64_t)threadIdx.x * per;
+  const int64_t hi = lo + per < n_blocks ? lo + per : n_blocks;
   for (int k = 0; k < n_thresholds; ++k) {
     uint32_t* t = block_ties + (int64_t)k * n_blocks;
-    uint32_t carry = 0;
-    for (int64_t c = 0; c < n_blocks; c += kThreads) {
-      const int64_t i = c + threadIdx.x;
-      const uint32_t v = (i < n_blocks) ? t[i] : 0u;
-      lds[threadIdx.x] = v;
-      __syncthreads();
-      uint32_t acc = v;
-      for (int o = 1; o < kThreads; o <<= 1) {
-        const uint32_t add = (threadIdx.x >= (unsigned)o) ? lds[threadIdx.x - o] : 0u;
-        __syncthreads();
-        acc += add;
-        lds[threadIdx.x] = acc;
-        __syncthreads();
-      }
-      if (i < n_blocks) t[i] = carry + acc - v;
-      carry += lds[kThreads - 1];
-      __syncthreads();
+    uint32_t sum = 0u;
+    for (int64_t i = lo; i < hi; ++i) sum += t[i];
+    uint32_t total;
+    uint32_t run = block_exclusive_sum(sum, wave_tot, &total);
+    for (int64_t i = lo; i < hi; ++i) {
+      const uint32_t v = t[i];
+      t[i] = run;
+      run += v;
     }
   }
 }
@@ -152,7 +240,7 @@ __global__ __launch_bounds__(kThreads) void k_select_classify(const uint32_t* __
                                                               const SelectState* __restrict__ st, int n_thresholds,
                                                               const uint32_t* __restrict__ block_ties,
                                                               uint32_t classes_packed, uint8_t* __restrict__ out_bits) {
-  __shared__ uint32_t lds[kMaxThresholds][kThreads];
+  __shared__ uint32_t wave_tot[kThreads / kWave];
   const int64_t base = (int64_t)blockIdx.x * kBlockGroups + (int64_t)threadIdx.x * kItems;
   uint32_t T[kMaxThresholds], E[kMaxThresholds];
   for (int k = 0; k < kMaxThresholds; ++k) {
@@ -161,36 +249,37 @@ __global__ __launch_bounds__(kThreads) void k_select_classify(const uint32_t* __
   }
   uint32_t key[kItems];
   uint32_t mine[kMaxThresholds] = {0u, 0u, 0u};          // equal keys among this thread's groups
+  load_keys(keys, base, G, key);
+#pragma unroll
   for (int i = 0; i < kItems; ++i) {
     const int64_t g = base + i;
-    key[i] = (g < G) ? keys[g] : 0xFFFFFFFFu;
     for (int k = 0; k < n_thresholds; ++k) mine[k] += (g < G && key[i] == T[k]) ? 1u : 0u;
   }
   // exclusive prefix of `mine` over the threads of the block, per threshold
   uint32_t before[kMaxThresholds];
-  for (int k = 0; k < n_thresholds; ++k) lds[k][threadIdx.x] = mine[k];
-  __syncthreads();
   for (int k = 0; k < n_thresholds; ++k) {
-    uint32_t acc = mine[k];
-    for (int o = 1; o < kThreads; o <<= 1) {
-      const uint32_t add = (threadIdx.x >= (unsigned)o) ? lds[k][threadIdx.x - o] : 0u;
-      __syncthreads();
-      acc += add;
-      lds[k][threadIdx.x] = acc;
-      __syncthreads();
-    }
-    before[k] = block_ties[(int64_t)k * gridDim.x + blockIdx.x] + acc - mine[k];
+    uint32_t total;
+    before[k] = block_ties[(int64_t)k * gridDim.x + blockIdx.x] + block_exclusive_sum(mine[k], wave_tot, &total);
   }
+  uint8_t w[kItems];
+#pragma unroll
   for (int i = 0; i < kItems; ++i) {
-    const int64_t g = base + i;
-    if (g >= G) break;
     uint32_t cls = 0;
     for (int k = 0; k < n_thresholds; ++k) {
       const bool eq = key[i] == T[k];
       if (key[i] > T[k] || (eq && before[k] >= E[k])) ++cls;
       before[k] += eq ? 1u : 0u;
     }
-    out_bits[g] = (uint8_t)(classes_packed >> (8u * cls));
+    w[i] = (uint8_t)(classes_packed >> (8u * cls));
+  }
+  if (base + kItems <= G && (reinterpret_cast<uintptr_t>(out_bits) & 7u) == 0u) {
+    const uint2 v = make_uint2((uint32_t)w[0] | ((uint32_t)w[1] << 8) | ((uint32_t)w[2] << 16) | ((uint32_t)w[3] << 24),
+                               (uint32_t)w[4] | ((uint32_t)w[5] << 8) | ((uint32_t)w[6] << 16) | ((uint32_t)w[7] << 24));
+    *reinterpret_cast<uint2*>(out_bits + base) = v;       // eight widths in one store
+  } else {
+#pragma unroll
+    for (int i = 0; i < kItems; ++i)
+      if (base + i < G) out_bits[base + i] = w[i];
   }
 }
 
@@ -223,7 +312,8 @@ hipError_t daf_launch_select_bits(const float* gmin, const float* gmax, int64_t 
   const unsigned gblocks = (unsigned)((G + kThreads - 1) / kThreads);
   hipLaunchKernelGGL(k_select_keys, dim3(gblocks), dim3(kThreads), 0, stream, gmin, gmax, G, keys, st, R[0], R[1], R[2]);
   if (n_thr > 0) {
-    unsigned hblocks = gblocks < 1024u ? gblocks : 1024u;
+    const unsigned cblocks = (unsigned)((((G + 3) >> 2) + 4 * kThreads - 1) / (4 * kThreads));   // sixteen keys per thread and trip
+    const unsigned hblocks = cblocks < 1024u ? cblocks : 1024u;
     for (int shift = 24; shift >= 0; shift -= 8) {
       hipLaunchKernelGGL(k_select_hist, dim3(hblocks), dim3(kThreads), 0, stream, keys, G, st, n_thr, shift);
       hipLaunchKernelGGL(k_select_pick, dim3(1), dim3(256), 0, stream, st, n_thr, shift);
