@@ -101,27 +101,41 @@ int daf_plan(const int64_t* shape, int ndim, int32_t group_size, const uint8_t* 
   p->uniform_bits = 0;
   hipStream_t st = static_cast<hipStream_t>(stream);
   int rc = DAF_OK;
-  unsigned long long* d_sums = nullptr;   // block sums + [n_blocks] total + bad flag
   const int64_t n_blocks = daf_plan_scan_blocks(G);
-  struct { unsigned long long total; int bad; int pad; } h = {0, 0, 0};
+  struct ScanResult { unsigned long long total; int bad; int pad; };
+  // One device allocation holds the offsets, the scan's block sums (+ total and error flag) and
+  // the plan's copy of the widths; the scan's result comes back through pinned host memory
+  // (allocated once per thread): allocations, frees and a copy into pageable memory each cost
+  // tens of microseconds, several times the three scan kernels together.
+  static thread_local ScanResult* h_pinned = nullptr;
+  ScanResult h = {0, 0, 0};
   do {
     if (hipGetDevice(&p->device) != hipSuccess) { rc = DAF_EDEVICE; break; }
-    if (hipMalloc(&p->d_bits, (size_t)G) != hipSuccess) { rc = DAF_ENOMEM; break; }
-    if (hipMalloc(&p->d_off, (size_t)G * sizeof(uint32_t)) != hipSuccess) { rc = DAF_ENOMEM; break; }
+    if (h_pinned == nullptr && hipHostMalloc(reinterpret_cast<void**>(&h_pinned), sizeof(ScanResult), hipHostMallocDefault) != hipSuccess) {
+      h_pinned = nullptr;
+      rc = DAF_ENOMEM;
+      break;
+    }
+    const size_t off_bytes = (((size_t)G * sizeof(uint32_t)) + 15) & ~(size_t)15;
+    const size_t sums_bytes = (((size_t)(n_blocks + 2) * sizeof(unsigned long long)) + 15) & ~(size_t)15;
+    char* base = nullptr;
+    if (hipMalloc(reinterpret_cast<void**>(&base), off_bytes + sums_bytes + (size_t)G) != hipSuccess) { rc = DAF_ENOMEM; break; }
+    p->d_off = reinterpret_cast<uint32_t*>(base);          // the allocation's address: freed through d_off
+    unsigned long long* d_sums = reinterpret_cast<unsigned long long*>(base + off_bytes);
+    p->d_bits = reinterpret_cast<uint8_t*>(base + off_bytes + sums_bytes);
     if (big && hipMalloc(&p->d_big_scratch, (size_t)big_bytes) != hipSuccess) { rc = DAF_ENOMEM; break; }
-    if (hipMalloc(&d_sums, (size_t)(n_blocks + 2) * sizeof(unsigned long long)) != hipSuccess) { rc = DAF_ENOMEM; break; }
     unsigned long long* d_total = d_sums + n_blocks;
     int* d_bad = reinterpret_cast<int*>(d_sums + n_blocks + 1);
     if (hipMemcpyAsync(p->d_bits, bits, (size_t)G, hipMemcpyDeviceToDevice, st) != hipSuccess) { rc = DAF_EDEVICE; break; }
     if (hipMemsetAsync(d_total, 0, 2 * sizeof(unsigned long long), st) != hipSuccess) { rc = DAF_EDEVICE; break; }
     if (daf_launch_plan_scan(p->d_bits, G, n, group_size, p->d_off, d_sums, n_blocks, d_total, d_bad, st) != hipSuccess) { rc = DAF_EDEVICE; break; }
-    if (hipMemcpyAsync(&h, d_total, sizeof(h), hipMemcpyDeviceToHost, st) != hipSuccess) { rc = DAF_EDEVICE; break; }
+    if (hipMemcpyAsync(h_pinned, d_total, sizeof(ScanResult), hipMemcpyDeviceToHost, st) != hipSuccess) { rc = DAF_EDEVICE; break; }
     if (hipStreamSynchronize(st) != hipSuccess) { rc = DAF_EDEVICE; break; }
+    h = *h_pinned;
     if (h.bad) { rc = DAF_EINVAL; break; }
     if (h.total >= 1ull << 32) { rc = DAF_EUNSUPPORTED; break; }
     p->total_words = (int64_t)h.total;
   } while (false);
-  if (d_sums) (void)hipFree(d_sums);
   if (rc != DAF_OK) {
     daf_plan_destroy(p);
     return rc;
@@ -158,8 +172,7 @@ int daf_plan_copy_offsets(const daf_plan_t* plan, uint32_t* out_off) {
 
 void daf_plan_destroy(daf_plan_t* plan) {
   if (plan == nullptr) return;
-  if (plan->d_bits) (void)hipFree(plan->d_bits);
-  if (plan->d_off) (void)hipFree(plan->d_off);
+  if (plan->d_off) (void)hipFree(plan->d_off);            // one allocation: offsets, scan scratch, widths
   if (plan->d_big_scratch) (void)hipFree(plan->d_big_scratch);
   delete plan;
 }

@@ -13,8 +13,8 @@ struct daf_plan_s {
   int32_t uniform_bits;  // shared width, or 0 when widths are per group
   int device;            // HIP device the plan's memory lives on
   int32_t output_cached; // unpack+dequantize output: 0 streaming stores (default), 1 cached stores
-  uint8_t* d_bits;       // G widths (device), mixed plans only
-  uint32_t* d_off;       // G word offsets (device), mixed plans only
+  uint8_t* d_bits;       // G widths (device), mixed plans only; lives inside d_off's allocation
+  uint32_t* d_off;       // G word offsets (device), mixed plans only; the address that is freed
   void* d_big_scratch;   // groups longer than a 4096-element tile: one (min, max) pair per tile and
                          // per group, written by the quantize call's first pass (else null)
 };

@@ -21,6 +21,25 @@ __device__ __forceinline__ uint32_t group_words(uint32_t b, int64_t g, int64_t n
   return (uint32_t)((len * b + 31) >> 5);
 }
 
+// A thread's kItems consecutive widths: one 8-byte load when all of them exist and the array
+// is 8-byte aligned (a thread's first index is a multiple of eight), else byte by byte; entries
+// at or past num_groups read as 0.
+__device__ __forceinline__ void load_widths(const uint8_t* __restrict__ bits, int64_t base, int64_t num_groups,
+                                            uint32_t (&b)[kItems]) {
+  static_assert(kItems == 8, "one 8-byte load");
+  if (base + kItems <= num_groups && (reinterpret_cast<uintptr_t>(bits) & 7u) == 0u) {
+    const uint2 v = *reinterpret_cast<const uint2*>(bits + base);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      b[i] = (v.x >> (8 * i)) & 0xFFu;
+      b[4 + i] = (v.y >> (8 * i)) & 0xFFu;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < kItems; ++i) b[i] = (base + i < num_groups) ? (uint32_t)bits[base + i] : 0u;
+  }
+}
+
 // Sum over a block; result valid in thread 0.
 __device__ __forceinline__ unsigned long long block_sum(unsigned long long v, unsigned long long* lds) {
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
@@ -38,61 +57,33 @@ __global__ __launch_bounds__(kThreads) void k_plan_block_sums(const uint8_t* __r
   const int64_t base = (int64_t)blockIdx.x * kBlockGroups + (int64_t)threadIdx.x * kItems;
   unsigned long long s = 0;
   int bad = 0;
+  uint32_t b[kItems];
+  load_widths(bits, base, num_groups, b);
 #pragma unroll
   for (int i = 0; i < kItems; ++i) {
     const int64_t g = base + i;
-    if (g < num_groups) s += group_words(bits[g], g, num_groups, n, gs, &bad);
+    if (g < num_groups) s += group_words(b[i], g, num_groups, n, gs, &bad);
   }
   if (bad) atomicOr(bad_flag, 1);
   const unsigned long long tot = block_sum(s, lds);
   if (threadIdx.x == 0) block_sums[blockIdx.x] = tot;
 }
 
-// One block turns block_sums[] into exclusive offsets in place and writes the grand total.
+// One block turns block_sums[] into exclusive offsets in place and writes the grand total: a
+// thread sums a run of consecutive entries, the 256 run sums are scanned once, the run is
+// rewritten.
 __global__ __launch_bounds__(kThreads) void k_plan_scan_block_sums(unsigned long long* __restrict__ block_sums,
                                                                    int64_t n_blocks,
                                                                    unsigned long long* __restrict__ total) {
   __shared__ unsigned long long lds[kThreads];
-  unsigned long long carry = 0;
-  for (int64_t c = 0; c < n_blocks; c += kThreads) {
-    const int64_t i = c + threadIdx.x;
-    const unsigned long long v = (i < n_blocks) ? block_sums[i] : 0ull;
-    lds[threadIdx.x] = v;
-    __syncthreads();
-    // Hillis-Steele inclusive scan over the 256 entries
-    unsigned long long acc = v;
-    for (int o = 1; o < kThreads; o <<= 1) {
-      const unsigned long long add = (threadIdx.x >= (unsigned)o) ? lds[threadIdx.x - o] : 0ull;
-      __syncthreads();
-      acc += add;
-      lds[threadIdx.x] = acc;
-      __syncthreads();
-    }
-    if (i < n_blocks) block_sums[i] = carry + acc - v;
-    carry += lds[kThreads - 1];
-    __syncthreads();
-  }
-  if (threadIdx.x == 0) *total = carry;
-}
-
-__global__ __launch_bounds__(kThreads) void k_plan_write_offsets(const uint8_t* __restrict__ bits,
-                                                                 int64_t num_groups, int64_t n, int32_t gs,
-                                                                 const unsigned long long* __restrict__ block_off,
-                                                                 uint32_t* __restrict__ off) {
-  __shared__ unsigned long long lds[kThreads];
-  const int64_t base = (int64_t)blockIdx.x * kBlockGroups + (int64_t)threadIdx.x * kItems;
-  uint32_t w[kItems];
-  unsigned long long s = 0;
-  int bad = 0;
-#pragma unroll
-  for (int i = 0; i < kItems; ++i) {
-    const int64_t g = base + i;
-    w[i] = (g < num_groups) ? group_words(bits[g], g, num_groups, n, gs, &bad) : 0u;
-    s += w[i];
-  }
-  lds[threadIdx.x] = s;
+  const int64_t per = (n_blocks + kThreads - 1) / kThreads;
+  const int64_t lo = (int64_t)threadIdx.x * per;
+  const int64_t hi = lo + per < n_blocks ? lo + per : n_blocks;
+  unsigned long long sum = 0;
+  for (int64_t i = lo; i < hi; ++i) sum += block_sums[i];
+  lds[threadIdx.x] = sum;
   __syncthreads();
-  unsigned long long acc = s;
+  unsigned long long acc = sum;                          // Hillis-Steele inclusive scan over the 256 run sums
   for (int o = 1; o < kThreads; o <<= 1) {
     const unsigned long long add = (threadIdx.x >= (unsigned)o) ? lds[threadIdx.x - o] : 0ull;
     __syncthreads();
@@ -100,12 +91,55 @@ __global__ __launch_bounds__(kThreads) void k_plan_write_offsets(const uint8_t* 
     lds[threadIdx.x] = acc;
     __syncthreads();
   }
-  unsigned long long run = block_off[blockIdx.x] + acc - s;   // exclusive offset of this thread's first group
+  unsigned long long run = acc - sum;
+  for (int64_t i = lo; i < hi; ++i) {
+    const unsigned long long v = block_sums[i];
+    block_sums[i] = run;
+    run += v;
+  }
+  if (threadIdx.x == kThreads - 1) *total = acc;
+}
+
+// Offsets are kept modulo 2^32 (a plan whose total reaches 2^32 words is rejected from the 64-bit
+// total, and its offsets are never used), so the scan inside a block runs on 32-bit values: a
+// DPP scan inside each wave, the wave totals through LDS.
+__global__ __launch_bounds__(kThreads) void k_plan_write_offsets(const uint8_t* __restrict__ bits,
+                                                                 int64_t num_groups, int64_t n, int32_t gs,
+                                                                 const unsigned long long* __restrict__ block_off,
+                                                                 uint32_t* __restrict__ off) {
+  __shared__ uint32_t wave_tot[kThreads / daf::kWave];
+  const int64_t base = (int64_t)blockIdx.x * kBlockGroups + (int64_t)threadIdx.x * kItems;
+  uint32_t b[kItems], w[kItems];
+  load_widths(bits, base, num_groups, b);
+  uint32_t s = 0;
+  int bad = 0;
 #pragma unroll
   for (int i = 0; i < kItems; ++i) {
     const int64_t g = base + i;
-    if (g < num_groups) off[g] = (uint32_t)run;
+    w[i] = (g < num_groups) ? group_words(b[i], g, num_groups, n, gs, &bad) : 0u;
+    s += w[i];
+  }
+  const int lane = threadIdx.x & (daf::kWave - 1), wave = threadIdx.x >> 6;
+  const uint32_t incl = daf::wave_inclusive_sum(s);
+  if (lane == daf::kWave - 1) wave_tot[wave] = incl;
+  __syncthreads();
+  uint32_t before = 0u;
+#pragma unroll
+  for (int v = 0; v < kThreads / daf::kWave; ++v) before += (v < wave) ? wave_tot[v] : 0u;
+  uint32_t run = (uint32_t)block_off[blockIdx.x] + before + incl - s;   // offset of this thread's first group
+  uint32_t o[kItems];
+#pragma unroll
+  for (int i = 0; i < kItems; ++i) {
+    o[i] = run;
     run += w[i];
+  }
+  if (base + kItems <= num_groups) {                     // two 16-byte stores
+    *reinterpret_cast<uint4*>(off + base) = make_uint4(o[0], o[1], o[2], o[3]);
+    *reinterpret_cast<uint4*>(off + base + 4) = make_uint4(o[4], o[5], o[6], o[7]);
+  } else {
+#pragma unroll
+    for (int i = 0; i < kItems; ++i)
+      if (base + i < num_groups) off[base + i] = o[i];
   }
 }
 
