@@ -111,7 +111,7 @@ int daf_plan(const int64_t* shape, int ndim, int32_t group_size, const uint8_t* 
   ScanResult h = {0, 0, 0};
   do {
     if (hipGetDevice(&p->device) != hipSuccess) { rc = DAF_EDEVICE; break; }
-    if (h_pinned == nullptr && hipHostMalloc(reinterpret_cast<void**>(&h_pinned), sizeof(ScanResult), hipHostMallocDefault) != hipSuccess) {
+    if (h_pinned == nullptr && hipHostMalloc(reinterpret_cast<void**>(&h_pinned), sizeof(ScanResult), hipHostMallocPortable) != hipSuccess) {
       h_pinned = nullptr;
       rc = DAF_ENOMEM;
       break;

@@ -1,15 +1,22 @@
 // Forward-pass side: per-group min/max -> scale -> stochastic-rounding quantization ->
 // bit packing, in one pass over the activation (paper Sec. 2.2, Eq. 1; Sec. 3.3; order of
-// codes in a word from Algorithm 2).  Two kernels:
+// codes in a word from Algorithm 2).  The kernels, by group size (always a multiple of 32):
 //
-//   k_quantize_pack_tile   the fast path.  One wave owns a tile of 2048 or 4096 consecutive
-//                          elements (a whole number of groups).  x is read from HBM once with
-//                          16-byte loads and stays in registers between the reduction and the
-//                          quantization; random bytes, group statistics and the packed words
-//                          are staged in wave-private LDS; the words leave as contiguous runs.
-//   k_quantize_pack_group  the general path, one wave per group: any group size that is a
-//                          multiple of 32, the groups after the last full tile, and the short
-//                          last group.
+//   k_quantize_pack_tile   powers of two up to 4096.  One wave owns a tile of 2048 or 4096
+//                          consecutive elements (a whole number of groups).  x is read from HBM
+//                          once with 16-byte loads and stays in registers between the reduction
+//                          and the quantization; random bytes, group statistics and the packed
+//                          words are staged in wave-private LDS; the words leave as contiguous
+//                          runs.
+//   k_quantize_pack_units  other sizes up to 4096: the same, with a tile of as many whole groups
+//                          as fit into 128 units of 32 elements.
+//   k_quantize_pack_long   4128 ... 32768: one workgroup per group, a slice per wave, (min, max)
+//                          exchanged through LDS; x is still read once.
+//   two passes             longer groups and per-tensor statistics (k_tile_minmax,
+//                          k_group_reduce, then k_quantize_pack_tile with the group's pair).
+//   k_quantize_pack_group  one wave (or workgroup) per group, element loads: whatever the others
+//                          leave, i.e. the groups after the last full tile and the short last
+//                          group.
 //
 // Rounding arithmetic.  With mn, L = 2^b-1 and inv = L/range of the group, an element maps to
 // v = (x-mn)*inv and is rounded up iff r + 1/2 < frac(v)*256 for its random byte r, i.e. iff
