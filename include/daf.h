@@ -295,7 +295,8 @@ int daf_unpack_dequantize_batch(const daf_dequantize_item_t* items, int32_t n_it
  *   others   as daf_quantize_pack.
  *
  * Errors: as daf_quantize_pack; DAF_EINVAL also for out_y partially overlapping z;
- * DAF_EUNSUPPORTED also for plans whose groups are longer than 4096 elements.
+ * DAF_EUNSUPPORTED also for plans for which daf_quantize_pack reads x twice (groups longer than
+ * 32768 elements, fewer than 256 groups of 8192, 16384 or 32768 elements, one group for the tensor).
  */
 int daf_relu_quantize_pack(const daf_plan_t* plan, const void* z, daf_dtype_t dtype, uint64_t seed, void* out_y,
                            uint32_t* out_words, float* out_min, float* out_scale, void* stream);

@@ -227,7 +227,7 @@ int daf_relu_quantize_pack(const daf_plan_t* plan, const void* z, daf_dtype_t dt
       !aligned(out_scale, 4))
     return DAF_EINVAL;
   if (dtype != DAF_F32 && dtype != DAF_F16 && dtype != DAF_BF16) return DAF_EUNSUPPORTED;
-  if (plan->d_big_scratch != nullptr) return DAF_EUNSUPPORTED;     // groups longer than 4096 elements
+  if (!daf_quantize_reads_once(plan)) return DAF_EUNSUPPORTED;     // the group's statistics need a pass of their own
   if (out_y != z) {                                                // in place, or not overlapping at all
     const int64_t bytes = plan->n * (dtype == DAF_F32 ? 4 : 2);
     const char* a = static_cast<const char*>(z);

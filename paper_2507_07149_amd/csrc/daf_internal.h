@@ -23,6 +23,10 @@ struct daf_plan_s {
 // i.e. when daf_quantize_pack takes the two-pass route; bytes of scratch it then needs.
 bool daf_plan_needs_big_scratch(int64_t n, int32_t group_size, int64_t num_groups, int64_t* bytes);
 
+// True when daf_quantize_pack reads the activation once for this plan (no statistics pass first):
+// the fused variants that write a second output in the same pass exist for such plans only.
+bool daf_quantize_reads_once(const daf_plan_t* plan);
+
 // Launchers.  Each returns hipSuccess or the first HIP error.
 hipError_t daf_launch_plan_scan(const uint8_t* d_bits, int64_t num_groups, int64_t n, int32_t group_size,
                                 uint32_t* d_off, unsigned long long* d_block_sums, int64_t n_blocks,

@@ -1339,16 +1339,24 @@ __global__ __launch_bounds__(kWave * kLongMaxWaves) void k_quantize_pack_long(
 // Takes plans whose groups are 32 * m elements, 128 < m <= 1024, when there are enough groups to
 // fill the device with one workgroup each, or when the two-pass route does not apply (groups
 // not a whole number of tiles).  Returns the groups it covered (all whole groups, or none).
+inline bool long_applies(const daf_plan_t* p) {
+  const int32_t gs = p->group_size;
+  const int32_t m = gs / 32;
+  if (gs % 32 != 0 || m <= 128 || m > 128 * kLongMaxWaves) return false;
+  const int64_t full_groups = p->n / gs;
+  if (full_groups == 0 || full_groups > 0x7fffffff) return false;
+  if (p->d_big_scratch != nullptr && full_groups < 256) return false;          // the two-pass route fills the device better
+  return true;
+}
+
 template <int DT, bool RELU>
 hipError_t launch_long(const daf_plan_t* p, const void* x, uint32_t seed_lo, uint32_t seed_hi, uint32_t* out_words,
                        float* out_min, float* out_scale, void* out_y, int64_t* covered, hipStream_t stream) {
   *covered = 0;
+  if (!long_applies(p)) return hipSuccess;
   const int32_t gs = p->group_size;
   const int32_t m = gs / 32;
-  if (gs % 32 != 0 || m <= 128 || m > 128 * kLongMaxWaves) return hipSuccess;
   const int64_t full_groups = p->n / gs;
-  if (full_groups == 0 || full_groups > 0x7fffffff) return hipSuccess;
-  if (p->d_big_scratch != nullptr && full_groups < 256) return hipSuccess;     // the two-pass route fills the device better
   const int32_t n_waves = (m + 127) / 128;
   const int32_t units_per_wave = (m + n_waves - 1) / n_waves;
   const unsigned lds_bytes = (unsigned)(n_waves * (sizeof(LongWaveLds) + sizeof(float2)));
@@ -1899,6 +1907,10 @@ hipError_t launch_items(const daf_quantize_item_t* items, int32_t n_items, hipSt
 #endif
 #define DAF_DT_NAME_(name, dt) name##_dt##dt
 #define DAF_DT_NAME(name, dt) DAF_DT_NAME_(name, dt)
+
+#if DAF_DT == 0
+bool daf_quantize_reads_once(const daf_plan_t* plan) { return plan->d_big_scratch == nullptr || long_applies(plan); }
+#endif
 
 hipError_t DAF_DT_NAME(daf_launch_quantize_pack_batch, DAF_DT)(const daf_quantize_item_t* items, int32_t n_items,
                                                                hipStream_t stream) {

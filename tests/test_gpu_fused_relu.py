@@ -179,3 +179,27 @@ def test_unpack_relu_backward_argument_errors(env):
     assert e.value.status == -1
     with pytest.raises(ValueError):
         daf.daf_unpack_relu_backward(plan, words, mn, mn, big[:8192], torch.zeros(8192, dtype=torch.float16, device="cuda:0"))
+
+
+@pytest.mark.parametrize("dtype,gs,bits", [(F32, 8192, 2), (BF16, 16384, "mixed"), (F16, 32768, 8)])
+def test_fused_relu_long_groups_of_whole_tiles(env, dtype, gs, bits):
+    """256 groups or more of 8192 ... 32768 elements are read once (one workgroup per group), so
+    the fused max(z, 0) exists for them; fewer such groups go through two passes and are refused."""
+    daf, orc = env
+    n = 257 * gs + 321
+    G = (n + gs - 1) // gs
+    g = torch.Generator().manual_seed(gs + dtype)
+    z = (torch.randn(n, generator=g) * 2.0).to(torch_dtype(dtype))
+    b = (np.random.default_rng(gs).choice([1, 2, 4, 8], G).astype(np.uint8) if bits == "mixed"
+         else np.array([bits], np.uint8))
+    plan = daf.daf_plan((n,), gs, torch.from_numpy(b).cuda() if b.size > 1 else int(b[0]))
+    for in_place in (False, True):
+        _check(orc, z, dtype, gs, b, 17, _run(daf, plan, z, 17, in_place))
+    plan.destroy()
+    few = daf.daf_plan((gs * 3,), gs, 2)
+    zz = torch.zeros(gs * 3, dtype=torch_dtype(dtype), device="cuda:0")
+    with pytest.raises(daf.DafError) as e:
+        daf.daf_relu_quantize_pack(few, zz, 0, zz, torch.empty(few.packed_words, dtype=torch.int32, device="cuda:0"),
+                                   torch.empty(3, device="cuda:0"), torch.empty(3, device="cuda:0"))
+    assert e.value.status == -2
+    few.destroy()
