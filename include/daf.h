@@ -237,8 +237,9 @@ int daf_group_minmax(const daf_plan_t* plan, const void* x, daf_dtype_t dtype,
  *
  *   out_metrics   DEVICE, 3*G floats, 4-byte aligned.
  *
- * Errors: as daf_quantize_pack; DAF_EUNSUPPORTED also for plans whose groups are longer than
- * 4096 elements.
+ * Errors: as daf_quantize_pack; DAF_EUNSUPPORTED also for plans for which daf_quantize_pack reads
+ * x twice (groups longer than 32768 elements, fewer than 256 groups of 8192, 16384 or 32768
+ * elements, one group for the tensor).
  */
 int daf_quantize_pack_metrics(const daf_plan_t* plan, const void* x, daf_dtype_t dtype, uint64_t seed,
                               uint32_t* out_words, float* out_min, float* out_scale,

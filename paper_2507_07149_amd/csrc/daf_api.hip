@@ -249,7 +249,7 @@ int daf_quantize_pack_metrics(const daf_plan_t* plan, const void* x, daf_dtype_t
       !aligned(out_metrics, 4))
     return DAF_EINVAL;
   if (dtype != DAF_F32 && dtype != DAF_F16 && dtype != DAF_BF16) return DAF_EUNSUPPORTED;
-  if (plan->d_big_scratch != nullptr) return DAF_EUNSUPPORTED;     // groups longer than 4096 elements
+  if (!daf_quantize_reads_once(plan)) return DAF_EUNSUPPORTED;     // the group's statistics need a pass of their own
   const hipError_t e = daf_launch_quantize_pack(plan, x, (int)dtype, seed, out_words, out_min, out_scale,
                                                 out_metrics, nullptr, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? DAF_OK : DAF_EDEVICE;

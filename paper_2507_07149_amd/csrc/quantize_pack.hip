@@ -1221,16 +1221,18 @@ struct LongWaveLds {
 };
 constexpr int kLongMaxWaves = 8;
 
-template <int DT, int B, bool RELU = false>
+template <int DT, int B, bool RELU = false, bool METRICS = false>
 __global__ __launch_bounds__(kWave * kLongMaxWaves) void k_quantize_pack_long(
     typename std::conditional<RELU, const u32x4*, const u32x4* __restrict__>::type x, int32_t m,
     int32_t units_per_wave, const uint8_t* __restrict__ bits,
     const uint32_t* __restrict__ off, uint32_t seed_lo, uint32_t seed_hi, uint32_t* __restrict__ words,
-    float* __restrict__ out_min, float* __restrict__ out_scale, u32x4* out_y) {
+    float* __restrict__ out_min, float* __restrict__ out_scale, u32x4* out_y, float* __restrict__ out_metrics) {
   using S = UnitShape<DT>;
+  static_assert(!(RELU && METRICS), "the fused max(z, 0) and the fused metrics are separate variants");
   constexpr int kEpl = S::kEpl;
   constexpr bool kMixed = (B == 0);
-  extern __shared__ __align__(16) uint8_t dyn_lds[];         // n_waves slices, then n_waves (min, max) pairs
+  // n_waves slices, then n_waves (min, max) pairs, then (METRICS) n_waves partial sums
+  extern __shared__ __align__(16) uint8_t dyn_lds[];
 
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -1315,6 +1317,7 @@ __global__ __launch_bounds__(kWave * kLongMaxWaves) void k_quantize_pack_long(
   wave_lds_sync();
 
   // 5. quantize every chunk of the slice and drop its bits at their place in the staged run
+  float m_err = 0.0f, m_mag = 0.0f, m_var = 0.0f;            // METRICS: this lane's share of the group's sums
   const uint32_t lane_bits = (uint32_t)kEpl * b;
   const uint32_t swz = (lane_bits <= 8u) ? 3u : (lane_bits == 16u) ? 2u : 0u;
 #pragma unroll
@@ -1323,8 +1326,17 @@ __global__ __launch_bounds__(kWave * kLongMaxWaves) void k_quantize_pack_long(
     if (c < n_chunks) {
       const uint32_t addr = (__umul24(c, lane_bits) >> 3) ^ swz;
       uint32_t n0, n1;
-      if (need_exact2) quantize_chunk<DT, true>(xf[u], s.mn, invs, b, rnd[u], n0, n1);
-      else             quantize_chunk<DT, false>(xf[u], s.mn, invs, b, rnd[u], n0, n1);
+      if constexpr (METRICS) {
+        float err, mag, var;
+        if (need_exact2) quantize_chunk<DT, true, true>(xf[u], s.mn, invs, b, rnd[u], n0, n1, s.scale, &err, &mag, &var);
+        else             quantize_chunk<DT, false, true>(xf[u], s.mn, invs, b, rnd[u], n0, n1, s.scale, &err, &mag, &var);
+        m_err += err;
+        m_mag += mag;
+        m_var += var;
+      } else {
+        if (need_exact2) quantize_chunk<DT, true>(xf[u], s.mn, invs, b, rnd[u], n0, n1);
+        else             quantize_chunk<DT, false>(xf[u], s.mn, invs, b, rnd[u], n0, n1);
+      }
       stage_chunk<kEpl>(stage8, addr, b, n0, n1, lane);
     }
   }
@@ -1334,6 +1346,27 @@ __global__ __launch_bounds__(kWave * kLongMaxWaves) void k_quantize_pack_long(
   uint32_t* dst = words + group_base + (uint32_t)unit0 * b;
   const uint32_t slice_words = units * b;
   for (uint32_t i = lane; i < slice_words; i += kWave) dst[i] = lds.stage[i];
+
+  if constexpr (METRICS) {
+    // per lane over its chunks, across the wave, then across the waves in a fixed order
+    float unused = 0.0f;
+    seg_sum2<6>(m_err, m_mag);
+    seg_sum2<6>(m_var, unused);
+    float4* wsum = reinterpret_cast<float4*>(dyn_lds + (size_t)n_waves * (sizeof(LongWaveLds) + sizeof(float2)));
+    if (lane == kWave - 1) wsum[wave] = make_float4(m_err, m_mag, m_var, 0.0f);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      float e = 0.0f, q = 0.0f, v = 0.0f;
+      for (int w = 0; w < n_waves; ++w) {
+        e += wsum[w].x;
+        q += wsum[w].y;
+        v += wsum[w].z;
+      }
+      out_metrics[3 * g] = e;
+      out_metrics[3 * g + 1] = q;
+      out_metrics[3 * g + 2] = (v * 1.52587890625e-05f) * (s.scale * s.scale);
+    }
+  }
 }
 
 // Takes plans whose groups are 32 * m elements, 128 < m <= 1024, when there are enough groups to
@@ -1349,9 +1382,10 @@ inline bool long_applies(const daf_plan_t* p) {
   return true;
 }
 
-template <int DT, bool RELU>
+template <int DT, bool RELU, bool METRICS>
 hipError_t launch_long(const daf_plan_t* p, const void* x, uint32_t seed_lo, uint32_t seed_hi, uint32_t* out_words,
-                       float* out_min, float* out_scale, void* out_y, int64_t* covered, hipStream_t stream) {
+                       float* out_min, float* out_scale, void* out_y, float* out_metrics, int64_t* covered,
+                       hipStream_t stream) {
   *covered = 0;
   if (!long_applies(p)) return hipSuccess;
   const int32_t gs = p->group_size;
@@ -1359,11 +1393,12 @@ hipError_t launch_long(const daf_plan_t* p, const void* x, uint32_t seed_lo, uin
   const int64_t full_groups = p->n / gs;
   const int32_t n_waves = (m + 127) / 128;
   const int32_t units_per_wave = (m + n_waves - 1) / n_waves;
-  const unsigned lds_bytes = (unsigned)(n_waves * (sizeof(LongWaveLds) + sizeof(float2)));
+  const unsigned lds_bytes = (unsigned)(n_waves * (sizeof(LongWaveLds) + sizeof(float2) + (METRICS ? sizeof(float4) : 0)));
 #define DAF_LAUNCH(BITS)                                                                                          \
-  hipLaunchKernelGGL((k_quantize_pack_long<DT, BITS, RELU>), dim3((unsigned)full_groups), dim3(kWave * n_waves),  \
-                     lds_bytes, stream, static_cast<const u32x4*>(x), m, units_per_wave, p->d_bits, p->d_off,     \
-                     seed_lo, seed_hi, out_words, out_min, out_scale, static_cast<u32x4*>(out_y))
+  hipLaunchKernelGGL((k_quantize_pack_long<DT, BITS, RELU, METRICS>), dim3((unsigned)full_groups),                \
+                     dim3(kWave * n_waves), lds_bytes, stream, static_cast<const u32x4*>(x), m, units_per_wave,   \
+                     p->d_bits, p->d_off, seed_lo, seed_hi, out_words, out_min, out_scale,                        \
+                     static_cast<u32x4*>(out_y), out_metrics)
   switch (p->uniform_bits) {
     case 0: DAF_LAUNCH(0); break;
     case 1: DAF_LAUNCH(1); break;
@@ -1663,9 +1698,9 @@ hipError_t launch_dtype(const daf_plan_t* p, const void* x, uint64_t seed, uint3
   constexpr int kEpl = ElemTraits<DT>::kPerLoad;
   const int64_t full_groups = p->n / p->group_size;
   int64_t fast_groups = 0;
-  if (!METRICS) {                       // groups of 4128 .. 32768 elements, one workgroup each
-    const hipError_t e = launch_long<DT, RELU>(p, x, seed_lo, seed_hi, out_words, out_min, out_scale, out_y,
-                                               &fast_groups, stream);
+  {                                     // groups of 4128 .. 32768 elements, one workgroup each
+    const hipError_t e = launch_long<DT, RELU, METRICS>(p, x, seed_lo, seed_hi, out_words, out_min, out_scale, out_y,
+                                                        out_metrics, &fast_groups, stream);
     if (e != hipSuccess) return e;
   }
   if (fast_groups == 0 && p->d_big_scratch != nullptr) {    // groups longer than a tile (set up by daf_plan)

@@ -137,7 +137,7 @@ def test_argument_errors(env):
 
 
 @pytest.mark.parametrize("dtype", [F32, F16, BF16])
-@pytest.mark.parametrize("gs", [32, 64, 96, 128, 160, 256, 768, 1024, 2080, 3072, 4064, 4096])
+@pytest.mark.parametrize("gs", [32, 64, 96, 128, 160, 256, 768, 1024, 2080, 3072, 4064, 4096, 4128, 11008, 32736])
 @pytest.mark.parametrize("bits", [2, 8, "mixed"])
 def test_fused_metrics(env, dtype, gs, bits):
     """daf_quantize_pack_metrics: words/min/scale identical to daf_quantize_pack (bit-exact
