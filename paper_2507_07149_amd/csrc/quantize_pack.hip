@@ -1222,8 +1222,8 @@ struct LongWaveLds {
 constexpr int kLongMaxWaves = 8;
 
 template <int DT, int B, bool RELU = false, bool METRICS = false>
-__global__ __launch_bounds__(kWave * kLongMaxWaves) void k_quantize_pack_long(
-    typename std::conditional<RELU, const u32x4*, const u32x4* __restrict__>::type x, int32_t m,
+__device__ __forceinline__ void quantize_pack_long_body(
+    typename std::conditional<RELU, const u32x4*, const u32x4* __restrict__>::type x, int64_t g, int32_t m,
     int32_t units_per_wave, const uint8_t* __restrict__ bits,
     const uint32_t* __restrict__ off, uint32_t seed_lo, uint32_t seed_hi, uint32_t* __restrict__ words,
     float* __restrict__ out_min, float* __restrict__ out_scale, u32x4* out_y, float* __restrict__ out_metrics) {
@@ -1231,15 +1231,14 @@ __global__ __launch_bounds__(kWave * kLongMaxWaves) void k_quantize_pack_long(
   static_assert(!(RELU && METRICS), "the fused max(z, 0) and the fused metrics are separate variants");
   constexpr int kEpl = S::kEpl;
   constexpr bool kMixed = (B == 0);
-  // n_waves slices, then n_waves (min, max) pairs, then (METRICS) n_waves partial sums
+  // n_waves slices, then 16 bytes per wave for its (min, max), then (METRICS) 16 per wave for its sums
   extern __shared__ __align__(16) uint8_t dyn_lds[];
 
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n_waves = (int)(blockDim.x >> 6);
-  const int64_t g = blockIdx.x;
   LongWaveLds& lds = reinterpret_cast<LongWaveLds*>(dyn_lds)[wave];
-  float2* wstat = reinterpret_cast<float2*>(dyn_lds + (size_t)n_waves * sizeof(LongWaveLds));
+  float4* wstat = reinterpret_cast<float4*>(dyn_lds + (size_t)n_waves * sizeof(LongWaveLds));   // 16 bytes per wave
   uint8_t* stage8 = reinterpret_cast<uint8_t*>(lds.stage);
 
   const int32_t unit0 = wave * units_per_wave;               // first unit of this wave's slice
@@ -1284,12 +1283,12 @@ __global__ __launch_bounds__(kWave * kLongMaxWaves) void k_quantize_pack_long(
       c2[u & 1] = (u < 2) ? hi : vmax(c2[u & 1], hi);
     }
     seg_minmax_x2<6>(a[0], c2[0], a[1], c2[1]);
-    if (lane == kWave - 1) wstat[wave] = make_float2(vmin(a[0], a[1]), vmax(c2[0], c2[1]));
+    if (lane == kWave - 1) wstat[wave] = make_float4(vmin(a[0], a[1]), vmax(c2[0], c2[1]), 0.0f, 0.0f);
   }
   __syncthreads();
-  float2 st = wstat[0];
+  float2 st = make_float2(wstat[0].x, wstat[0].y);
   for (int w = 1; w < n_waves; ++w) {
-    const float2 t = wstat[w];
+    const float4 t = wstat[w];
     st.x = vmin(st.x, t.x);
     st.y = vmax(st.y, t.y);
   }
@@ -1352,7 +1351,7 @@ __global__ __launch_bounds__(kWave * kLongMaxWaves) void k_quantize_pack_long(
     float unused = 0.0f;
     seg_sum2<6>(m_err, m_mag);
     seg_sum2<6>(m_var, unused);
-    float4* wsum = reinterpret_cast<float4*>(dyn_lds + (size_t)n_waves * (sizeof(LongWaveLds) + sizeof(float2)));
+    float4* wsum = wstat + n_waves;
     if (lane == kWave - 1) wsum[wave] = make_float4(m_err, m_mag, m_var, 0.0f);
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -1372,6 +1371,45 @@ __global__ __launch_bounds__(kWave * kLongMaxWaves) void k_quantize_pack_long(
 // Takes plans whose groups are 32 * m elements, 128 < m <= 1024, when there are enough groups to
 // fill the device with one workgroup each, or when the two-pass route does not apply (groups
 // not a whole number of tiles).  Returns the groups it covered (all whole groups, or none).
+template <int DT, int B, bool RELU = false, bool METRICS = false>
+__global__ __launch_bounds__(kWave * kLongMaxWaves) void k_quantize_pack_long(
+    typename std::conditional<RELU, const u32x4*, const u32x4* __restrict__>::type x, int32_t m,
+    int32_t units_per_wave, const uint8_t* __restrict__ bits,
+    const uint32_t* __restrict__ off, uint32_t seed_lo, uint32_t seed_hi, uint32_t* __restrict__ words,
+    float* __restrict__ out_min, float* __restrict__ out_scale, u32x4* out_y, float* __restrict__ out_metrics) {
+  quantize_pack_long_body<DT, B, RELU, METRICS>(x, (int64_t)blockIdx.x, m, units_per_wave, bits, off, seed_lo, seed_hi,
+                                                words, out_min, out_scale, out_y, out_metrics);
+}
+
+// Several tensors in one launch: the groups of all entries form one sequence of workgroups.  The
+// entries of a launch have the same number of waves per group (the workgroup size).
+struct LongBatchEntry {
+  const void* x;
+  const uint8_t* bits;
+  const uint32_t* off;
+  uint32_t* words;
+  float* mn;
+  float* sc;
+  int64_t group_end;                                // whole groups of this and all earlier entries
+  uint32_t seed_lo, seed_hi;
+  int32_t m, units_per_wave;
+};
+struct LongBatch {
+  LongBatchEntry e[kMaxBatch];
+  int32_t n;
+};
+
+template <int DT, int B>
+__global__ __launch_bounds__(kWave * kLongMaxWaves) void k_quantize_pack_long_batch(const LongBatch batch) {
+  const int64_t gg = blockIdx.x;                    // < batch.e[batch.n - 1].group_end: the grid is exactly that
+  int t = 0;
+  while (gg >= batch.e[t].group_end) ++t;           // uniform over the workgroup
+  const LongBatchEntry& e = batch.e[t];
+  quantize_pack_long_body<DT, B>(static_cast<const u32x4*>(e.x), gg - (t ? batch.e[t - 1].group_end : 0), e.m,
+                                 e.units_per_wave, e.bits, e.off, e.seed_lo, e.seed_hi, e.words, e.mn, e.sc, nullptr,
+                                 nullptr);
+}
+
 inline bool long_applies(const daf_plan_t* p) {
   const int32_t gs = p->group_size;
   const int32_t m = gs / 32;
@@ -1393,7 +1431,7 @@ hipError_t launch_long(const daf_plan_t* p, const void* x, uint32_t seed_lo, uin
   const int64_t full_groups = p->n / gs;
   const int32_t n_waves = (m + 127) / 128;
   const int32_t units_per_wave = (m + n_waves - 1) / n_waves;
-  const unsigned lds_bytes = (unsigned)(n_waves * (sizeof(LongWaveLds) + sizeof(float2) + (METRICS ? sizeof(float4) : 0)));
+  const unsigned lds_bytes = (unsigned)(n_waves * (sizeof(LongWaveLds) + sizeof(float4) + (METRICS ? sizeof(float4) : 0)));
 #define DAF_LAUNCH(BITS)                                                                                          \
   hipLaunchKernelGGL((k_quantize_pack_long<DT, BITS, RELU, METRICS>), dim3((unsigned)full_groups),                \
                      dim3(kWave * n_waves), lds_bytes, stream, static_cast<const u32x4*>(x), m, units_per_wave,   \
@@ -1838,6 +1876,29 @@ hipError_t launch_items(const daf_quantize_item_t* items, int32_t n_items, hipSt
     if (batch.n > 0 && err == hipSuccess) err = launch_batch<DT>(batch, cur_log2, cur_bits, stream);
     batch.n = 0;
   };
+  LongBatch lbatch;                    // items of the one-workgroup-per-group kernel
+  lbatch.n = 0;
+  int lcur_bits = -1, lcur_waves = -1;
+  auto lflush = [&]() {
+    if (lbatch.n > 0 && err == hipSuccess) {
+      const unsigned blocks = (unsigned)lbatch.e[lbatch.n - 1].group_end;
+      const unsigned lds_bytes = (unsigned)(lcur_waves * (sizeof(LongWaveLds) + sizeof(float4)));
+#define DAF_LAUNCH(BITS)                                                                                    \
+  hipLaunchKernelGGL((k_quantize_pack_long_batch<DT, BITS>), dim3(blocks), dim3(kWave * lcur_waves), lds_bytes, \
+                     stream, lbatch)
+      switch (lcur_bits) {
+        case 0: DAF_LAUNCH(0); break;
+        case 1: DAF_LAUNCH(1); break;
+        case 2: DAF_LAUNCH(2); break;
+        case 4: DAF_LAUNCH(4); break;
+        case 8: DAF_LAUNCH(8); break;
+        default: err = hipErrorInvalidValue; break;
+      }
+#undef DAF_LAUNCH
+      if (err == hipSuccess) err = hipGetLastError();
+    }
+    lbatch.n = 0;
+  };
   auto uflush = [&]() {
     if (ubatch.n > 0 && err == hipSuccess) {
       const unsigned blocks = (unsigned)((ubatch.e[ubatch.n - 1].tile_end + kWavesPerBlock - 1) / kWavesPerBlock);
@@ -1861,6 +1922,36 @@ hipError_t launch_items(const daf_quantize_item_t* items, int32_t n_items, hipSt
     const daf_plan_t* p = it.plan;
     int log2 = 0;
     int64_t n_tiles = 0, fast_groups = 0;
+    if (long_applies(p)) {
+      const int32_t m = p->group_size / 32;
+      const int32_t n_waves = (m + 127) / 128;
+      const int64_t full_groups = p->n / p->group_size;
+      if (lbatch.n == kMaxBatch || (lbatch.n > 0 && (p->uniform_bits != lcur_bits || n_waves != lcur_waves)) ||
+          (lbatch.n > 0 && lbatch.e[lbatch.n - 1].group_end + full_groups > 0x7fffffff))
+        lflush();
+      lcur_bits = p->uniform_bits;
+      lcur_waves = n_waves;
+      LongBatchEntry& e = lbatch.e[lbatch.n];
+      e.x = it.x;
+      e.bits = p->d_bits;
+      e.off = p->d_off;
+      e.words = it.out_words;
+      e.mn = it.out_min;
+      e.sc = it.out_scale;
+      e.group_end = (lbatch.n ? lbatch.e[lbatch.n - 1].group_end : 0) + full_groups;
+      e.seed_lo = (uint32_t)it.seed;
+      e.seed_hi = (uint32_t)(it.seed >> 32);
+      e.m = m;
+      e.units_per_wave = (m + n_waves - 1) / n_waves;
+      ++lbatch.n;
+      if (p->num_groups > full_groups && err == hipSuccess) {           // the short last group
+        hipLaunchKernelGGL((k_quantize_pack_group<DT, false, false, true>), dim3(1), dim3(kThreads), 0, stream, it.x,
+                           p->n, p->group_size, full_groups, p->num_groups, p->d_bits, p->d_off, p->uniform_bits,
+                           e.seed_lo, e.seed_hi, it.out_words, it.out_min, it.out_scale, nullptr, nullptr);
+        err = hipGetLastError();
+      }
+      continue;
+    }
     UnitGeometry ug;
     if (p->d_big_scratch == nullptr && unit_geometry(p, &ug)) {
       if (ubatch.n == kMaxBatch || (ubatch.n > 0 && p->uniform_bits != ucur_bits) ||
@@ -1929,6 +2020,7 @@ hipError_t launch_items(const daf_quantize_item_t* items, int32_t n_items, hipSt
   }
   flush();
   uflush();
+  lflush();
   return err;
 }
 
