@@ -71,6 +71,15 @@ def parse():
                     help="time daf_unpack_dequantize alone and followed by a kernel that reads its output "
                          "(daf_group_minmax), with streaming and with cached output stores "
                          "(daf_plan_set_output_cached)")
+    ap.add_argument("--sweep", action="store_true",
+                    help="kernel-time map over element formats, group sizes (--sweep-group-sizes) and widths on one "
+                         "tensor of 2^27 normal random elements: one line of JSON per case, fraction of 8 TB/s on "
+                         "algorithmic bytes for quantize+pack and unpack+dequantize")
+    ap.add_argument("--sweep-group-sizes", type=str, default="32,64,96,256,768,3072,4096,11008,16384",
+                    help="comma-separated group sizes for --sweep")
+    ap.add_argument("--list-rows", action="store_true",
+                    help="16 fp16 tensors with per-group widths and one group per row: one quantize call per tensor "
+                         "against one list call, for three tensor shapes")
     ap.add_argument("--page-store", action="store_true",
                     help="time the host-side paged activation store (red-black trees against re-sorting, and the "
                          "plain model) on synthetic iterations; uses no GPU")
@@ -305,6 +314,89 @@ def main():
                           "max_rel_diff_vs_library_output": round(rel, 5),
                           "roofline": {"bound": "mfma", "achieved": round(ach, 1), "peak": peak, "unit": "TFLOP/s",
                                        "frac": round(ach / peak, 4), "traffic": None, "kernel": "k_unpack_matmul"}}))
+        return
+
+    if args.sweep:
+        n = 1 << 27
+
+        def timeit(f, reps=20):
+            for _ in range(25):                          # the clocks take tens of milliseconds of load to settle
+                f()
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(reps):
+                f()
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / reps
+
+        for dt in (torch.float32, torch.float16, torch.bfloat16):
+            xs = [torch.randn(n, device=dev, dtype=torch.float32).to(dt) for _ in range(2)]
+            xh = torch.empty_like(xs[0])
+            for gs in [int(v) for v in args.sweep_group_sizes.split(",")]:
+                G = (n + gs - 1) // gs
+                for bits in (1, 2, 4, 8, "mixed"):
+                    if bits == "mixed":
+                        b = torch.from_numpy(np.random.default_rng(0).choice([1, 2, 4, 8], G).astype(np.uint8)).to(dev)
+                        plan = daf.daf_plan((n,), gs, b)
+                    else:
+                        plan = daf.daf_plan((n,), gs, bits)
+                    words = torch.empty(plan.packed_words, dtype=torch.int32, device=dev)
+                    mn, sc = torch.empty(G, device=dev), torch.empty(G, device=dev)
+                    it = [0]
+
+                    def q():
+                        daf.daf_quantize_pack(plan, xs[it[0] & 1], 3, words, mn, sc)
+                        it[0] += 1
+                    tq = timeit(q)
+                    td = timeit(lambda: daf.daf_unpack_dequantize(plan, words, mn, sc, xh))
+                    alg = n * xs[0].element_size() + plan.packed_words * 4 + G * 8 + (G * 5 if bits == "mixed" else 0)
+                    print(json.dumps({"dtype": str(dt)[6:], "group_size": gs, "bits": bits,
+                                      "quantize_us": round(tq * 1e3, 1), "quantize_frac": round(alg / (tq * 1e-3) / 8e12, 3),
+                                      "dequantize_us": round(td * 1e3, 1),
+                                      "dequantize_frac": round(alg / (td * 1e-3) / 8e12, 3)}), flush=True)
+                    plan.destroy()
+        return
+
+    if args.list_rows:
+        res = []
+        for shape, gs in (((32, 1024, 768), 768), ((8, 197, 3072), 3072), ((8, 197, 768), 768)):
+            n, T = int(np.prod(shape)), 16
+            items, keep = [], []
+            for i in range(T):
+                x = torch.randn(n, device=dev).to(torch.float16)
+                G = n // gs
+                b = torch.from_numpy(np.random.default_rng(i).choice([1, 2, 4, 8], G).astype(np.uint8)).to(dev)
+                p = daf.daf_plan((n,), gs, b)
+                items.append((p, x, i, torch.empty(p.packed_words, dtype=torch.int32, device=dev),
+                              torch.empty(G, device=dev), torch.empty(G, device=dev)))
+                keep.append(b)
+            marshalled = daf.quantize_items(items)
+
+            def one_by_one():
+                for it in items:
+                    daf.daf_quantize_pack(*it)
+
+            def as_list():
+                daf.daf_quantize_pack_batch(marshalled)
+            row = {"shape": list(shape), "group_size": gs, "tensors": T}
+            for name, f in (("one_call_per_tensor_us", one_by_one), ("list_call_us", as_list)):
+                for _ in range(10):
+                    f()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                torch.cuda.synchronize()
+                e0.record()
+                for _ in range(30):
+                    f()
+                e1.record()
+                torch.cuda.synchronize()
+                row[name] = round(e0.elapsed_time(e1) / 30 * 1e3, 1)
+            res.append(row)
+            for it in items:
+                it[0].destroy()
+        print(json.dumps({"metric": "quantize+pack of 16 tensors with one group per row", "unit": "us", "n_gpus": 1,
+                          "data": "synthetic", "dtype": "f16", "results": res}))
         return
 
     if args.output_policy:
