@@ -89,6 +89,25 @@ int64_t daf_plan_packed_words(const daf_plan_t* plan);   /* words the caller mus
 int32_t daf_plan_group_size(const daf_plan_t* plan);
 int32_t daf_plan_uniform_bits(const daf_plan_t* plan);   /* the shared width, or 0 for per-group widths */
 
+/* Which kernels daf_quantize_pack (and its fused variants) use for the whole groups of this plan
+ * when the tensor has the given element format; the groups after the last whole tile and the
+ * tensor's short last group always go one by one.  A host computation, for tuning and tests.
+ *   DAF_ROUTE_TILE      group size a power of two up to 4096: one wave per 4096-element tile
+ *   DAF_ROUTE_UNITS     other group sizes up to 4096: one wave per run of whole groups
+ *   DAF_ROUTE_LONG      4128 ... 32768 elements: one workgroup per group
+ *   DAF_ROUTE_TWO_PASS  longer groups of whole tiles, fewer than 256 groups of 8192 ... 32768, one
+ *                       group for the tensor: statistics first, the activation is read twice
+ *   DAF_ROUTE_GROUP     everything else: one wave or workgroup per group, element loads
+ * Returns the route (>= 0), DAF_EINVAL for a NULL plan, DAF_EUNSUPPORTED for an unknown dtype. */
+typedef enum {
+  DAF_ROUTE_TILE = 0,
+  DAF_ROUTE_UNITS = 1,
+  DAF_ROUTE_LONG = 2,
+  DAF_ROUTE_TWO_PASS = 3,
+  DAF_ROUTE_GROUP = 4
+} daf_route_t;
+int daf_plan_quantize_route(const daf_plan_t* plan, daf_dtype_t dtype);
+
 /* Copies the G group word offsets to HOST memory (synchronous; for inspection and tests).
  * Works for uniform plans too (offsets are then computed, not stored). */
 int daf_plan_copy_offsets(const daf_plan_t* plan, uint32_t* out_off);

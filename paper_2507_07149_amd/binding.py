@@ -47,6 +47,8 @@ def load_library():
         getattr(L, name).restype = res
     L.daf_plan_copy_offsets.argtypes = [vp, vp]
     L.daf_plan_copy_offsets.restype = c.c_int
+    L.daf_plan_quantize_route.argtypes = [vp, c.c_int]
+    L.daf_plan_quantize_route.restype = c.c_int
     L.daf_plan_set_output_cached.argtypes = [vp, c.c_int]
     L.daf_plan_set_output_cached.restype = c.c_int
     L.daf_plan_destroy.argtypes = [vp]
@@ -116,6 +118,14 @@ class Plan:
     packed_words = property(lambda s: int(load_library().daf_plan_packed_words(s.handle)))
     group_size = property(lambda s: int(load_library().daf_plan_group_size(s.handle)))
     uniform_bits = property(lambda s: int(load_library().daf_plan_uniform_bits(s.handle)))
+
+    ROUTES = ("tile", "units", "long", "two_pass", "group")
+
+    def quantize_route(self, dtype: torch.dtype) -> str:
+        rc = load_library().daf_plan_quantize_route(self.handle, _DTYPE_ID[dtype])
+        if rc < 0:
+            raise DafError(rc, "daf_plan_quantize_route")
+        return Plan.ROUTES[rc]
 
     def set_output_cached(self, cached: bool) -> None:
         rc = load_library().daf_plan_set_output_cached(self.handle, 1 if cached else 0)

@@ -156,6 +156,12 @@ int daf_plan_set_output_cached(daf_plan_t* plan, int cached) {
   return DAF_OK;
 }
 
+int daf_plan_quantize_route(const daf_plan_t* plan, daf_dtype_t dtype) {
+  if (plan == nullptr) return DAF_EINVAL;
+  if (dtype != DAF_F32 && dtype != DAF_F16 && dtype != DAF_BF16) return DAF_EUNSUPPORTED;
+  return daf_quantize_route(plan, (int)dtype);
+}
+
 int daf_plan_copy_offsets(const daf_plan_t* plan, uint32_t* out_off) {
   if (plan == nullptr || out_off == nullptr) return DAF_EINVAL;
   if (plan->uniform_bits) {

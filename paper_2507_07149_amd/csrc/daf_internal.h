@@ -27,6 +27,10 @@ bool daf_plan_needs_big_scratch(int64_t n, int32_t group_size, int64_t num_group
 // the fused variants that write a second output in the same pass exist for such plans only.
 bool daf_quantize_reads_once(const daf_plan_t* plan);
 
+// The kernels daf_quantize_pack uses for the plan's whole groups: a value of daf_route_t, -1 for an
+// unknown dtype.  A host computation.
+int daf_quantize_route(const daf_plan_t* plan, int dtype);
+
 // Launchers.  Each returns hipSuccess or the first HIP error.
 hipError_t daf_launch_plan_scan(const uint8_t* d_bits, int64_t num_groups, int64_t n, int32_t group_size,
                                 uint32_t* d_off, unsigned long long* d_block_sums, int64_t n_blocks,

@@ -10,6 +10,18 @@ DAF_DECLARE(0)
 DAF_DECLARE(1)
 DAF_DECLARE(2)
 #undef DAF_DECLARE
+int daf_quantize_route_dt0(const daf_plan_t*);
+int daf_quantize_route_dt1(const daf_plan_t*);
+int daf_quantize_route_dt2(const daf_plan_t*);
+
+int daf_quantize_route(const daf_plan_t* plan, int dtype) {
+  switch (dtype) {
+    case 0: return daf_quantize_route_dt0(plan);
+    case 1: return daf_quantize_route_dt1(plan);
+    case 2: return daf_quantize_route_dt2(plan);
+    default: return -1;
+  }
+}
 
 hipError_t daf_launch_quantize_pack_batch(const daf_quantize_item_t* items, int32_t n_items, int dtype,
                                           hipStream_t stream) {

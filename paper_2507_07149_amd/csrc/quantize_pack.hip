@@ -1729,75 +1729,6 @@ hipError_t launch_group_minmax(const daf_plan_t* p, const void* x, float* out_mi
   return hipGetLastError();
 }
 
-template <int DT, bool METRICS, bool RELU = false>
-hipError_t launch_dtype(const daf_plan_t* p, const void* x, uint64_t seed, uint32_t* out_words, float* out_min,
-                        float* out_scale, float* out_metrics, void* out_y, hipStream_t stream) {
-  const uint32_t seed_lo = (uint32_t)seed, seed_hi = (uint32_t)(seed >> 32);
-  constexpr int kEpl = ElemTraits<DT>::kPerLoad;
-  const int64_t full_groups = p->n / p->group_size;
-  int64_t fast_groups = 0;
-  {                                     // groups of 4128 .. 32768 elements, one workgroup each
-    const hipError_t e = launch_long<DT, RELU, METRICS>(p, x, seed_lo, seed_hi, out_words, out_min, out_scale, out_y,
-                                                        out_metrics, &fast_groups, stream);
-    if (e != hipSuccess) return e;
-  }
-  if (fast_groups == 0 && p->d_big_scratch != nullptr) {    // groups longer than a tile (set up by daf_plan)
-    if (METRICS || RELU) return hipErrorNotSupported;
-    return launch_big<DT>(p, x, seed_lo, seed_hi, out_words, out_min, out_scale, stream);
-  }
-
-  // fast path: groups of 4 .. 1024 chunks (a power of two, at most one tile), whole tiles only
-  const int32_t lpg = p->group_size / kEpl;
-  if (fast_groups == 0 && p->group_size % kEpl == 0 && lpg >= 4 && (lpg & (lpg - 1)) == 0) {
-    int64_t n_tiles = 0;
-    hipError_t e = hipSuccess;
-#define DAF_CASE(LOG2)                                                                                   \
-  case (1 << LOG2):                                                                                      \
-    if constexpr (TileShape<DT, LOG2>::kValid) {                                                         \
-      n_tiles = full_groups / TileShape<DT, LOG2>::kGroups;                                              \
-      fast_groups = n_tiles * TileShape<DT, LOG2>::kGroups;                                              \
-      if (n_tiles > 0) e = launch_tile<DT, LOG2, METRICS, RELU>(p, x, n_tiles, seed_lo, seed_hi, out_words, \
-                                                                out_min, out_scale, out_metrics, out_y,  \
-                                                                stream);                                 \
-    }                                                                                                    \
-    break;
-    switch (lpg) {
-      DAF_CASE(2) DAF_CASE(3) DAF_CASE(4) DAF_CASE(5) DAF_CASE(6)
-      DAF_CASE(7) DAF_CASE(8) DAF_CASE(9) DAF_CASE(10)
-      default: break;
-    }
-#undef DAF_CASE
-    if (e != hipSuccess) return e;
-  }
-
-  if (fast_groups == 0) {
-    const hipError_t e = launch_units<DT, RELU, METRICS>(p, x, seed_lo, seed_hi, out_words, out_min, out_scale, out_y,
-                                                         out_metrics, &fast_groups, stream);
-    if (e != hipSuccess) return e;
-  }
-
-  // general path for everything the tiles did not cover
-  const int64_t rest = p->num_groups - fast_groups;
-  if (rest > 0) {
-    if constexpr (!METRICS) {
-      if (p->group_size >= 1024) {         // long groups: a workgroup each
-        const int64_t blocks = rest < 65536 ? rest : 65536;
-        hipLaunchKernelGGL((k_quantize_pack_group<DT, false, RELU, true>), dim3((unsigned)blocks), dim3(kThreads), 0,
-                           stream, x, p->n, p->group_size, fast_groups, p->num_groups, p->d_bits, p->d_off,
-                           p->uniform_bits, seed_lo, seed_hi, out_words, out_min, out_scale, out_metrics, out_y);
-        return hipGetLastError();
-      }
-    }
-    int64_t blocks = (rest + kWavesPerBlock - 1) / kWavesPerBlock;
-    if (blocks > 65536) blocks = 65536;
-    hipLaunchKernelGGL((k_quantize_pack_group<DT, METRICS, RELU>), dim3((unsigned)blocks), dim3(kThreads), 0, stream,
-                       x, p->n, p->group_size, fast_groups, p->num_groups, p->d_bits, p->d_off, p->uniform_bits,
-                       seed_lo, seed_hi, out_words, out_min, out_scale, out_metrics, out_y);
-    return hipGetLastError();
-  }
-  return hipSuccess;
-}
-
 // Tiles per tensor on the fast path (0 if the plan is not eligible) and the groups they cover.
 template <int DT>
 bool tile_geometry(const daf_plan_t* p, int* lpg_log2, int64_t* n_tiles, int64_t* fast_groups) {
@@ -1825,6 +1756,89 @@ bool tile_geometry(const daf_plan_t* p, int* lpg_log2, int64_t* n_tiles, int64_t
   }
 #undef DAF_CASE
   return ok;
+}
+
+// Which kernels a plan's quantize call uses for its whole groups (the values of daf_route_t).
+template <int DT>
+int quantize_route(const daf_plan_t* p) {
+  int log2 = 0;
+  int64_t n_tiles = 0, fast_groups = 0;
+  UnitGeometry ug;
+  if (long_applies(p)) return 2;
+  if (p->d_big_scratch != nullptr) return 3;
+  if (tile_geometry<DT>(p, &log2, &n_tiles, &fast_groups)) return 0;
+  if (unit_geometry(p, &ug)) return 1;
+  return 4;
+}
+
+template <int DT, bool METRICS, bool RELU = false>
+hipError_t launch_dtype(const daf_plan_t* p, const void* x, uint64_t seed, uint32_t* out_words, float* out_min,
+                        float* out_scale, float* out_metrics, void* out_y, hipStream_t stream) {
+  const uint32_t seed_lo = (uint32_t)seed, seed_hi = (uint32_t)(seed >> 32);
+  constexpr int kEpl = ElemTraits<DT>::kPerLoad;
+  const int64_t full_groups = p->n / p->group_size;
+  int64_t fast_groups = 0;
+  const int route = quantize_route<DT>(p);                  // 0 tile, 1 units, 2 long, 3 two passes, 4 group by group
+  if (route == 2) {                     // groups of 4128 .. 32768 elements, one workgroup each
+    const hipError_t e = launch_long<DT, RELU, METRICS>(p, x, seed_lo, seed_hi, out_words, out_min, out_scale, out_y,
+                                                        out_metrics, &fast_groups, stream);
+    if (e != hipSuccess) return e;
+  }
+  if (route == 3) {                     // statistics first (scratch set up by daf_plan)
+    if (METRICS || RELU) return hipErrorNotSupported;
+    return launch_big<DT>(p, x, seed_lo, seed_hi, out_words, out_min, out_scale, stream);
+  }
+
+  // fast path: groups of 4 .. 1024 chunks (a power of two, at most one tile), whole tiles only
+  const int32_t lpg = p->group_size / kEpl;
+  if (route == 0) {
+    int64_t n_tiles = 0;
+    hipError_t e = hipSuccess;
+#define DAF_CASE(LOG2)                                                                                   \
+  case (1 << LOG2):                                                                                      \
+    if constexpr (TileShape<DT, LOG2>::kValid) {                                                         \
+      n_tiles = full_groups / TileShape<DT, LOG2>::kGroups;                                              \
+      fast_groups = n_tiles * TileShape<DT, LOG2>::kGroups;                                              \
+      if (n_tiles > 0) e = launch_tile<DT, LOG2, METRICS, RELU>(p, x, n_tiles, seed_lo, seed_hi, out_words, \
+                                                                out_min, out_scale, out_metrics, out_y,  \
+                                                                stream);                                 \
+    }                                                                                                    \
+    break;
+    switch (lpg) {
+      DAF_CASE(2) DAF_CASE(3) DAF_CASE(4) DAF_CASE(5) DAF_CASE(6)
+      DAF_CASE(7) DAF_CASE(8) DAF_CASE(9) DAF_CASE(10)
+      default: break;
+    }
+#undef DAF_CASE
+    if (e != hipSuccess) return e;
+  }
+
+  if (route == 1) {
+    const hipError_t e = launch_units<DT, RELU, METRICS>(p, x, seed_lo, seed_hi, out_words, out_min, out_scale, out_y,
+                                                         out_metrics, &fast_groups, stream);
+    if (e != hipSuccess) return e;
+  }
+
+  // general path for everything the tiles did not cover
+  const int64_t rest = p->num_groups - fast_groups;
+  if (rest > 0) {
+    if constexpr (!METRICS) {
+      if (p->group_size >= 1024) {         // long groups: a workgroup each
+        const int64_t blocks = rest < 65536 ? rest : 65536;
+        hipLaunchKernelGGL((k_quantize_pack_group<DT, false, RELU, true>), dim3((unsigned)blocks), dim3(kThreads), 0,
+                           stream, x, p->n, p->group_size, fast_groups, p->num_groups, p->d_bits, p->d_off,
+                           p->uniform_bits, seed_lo, seed_hi, out_words, out_min, out_scale, out_metrics, out_y);
+        return hipGetLastError();
+      }
+    }
+    int64_t blocks = (rest + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL((k_quantize_pack_group<DT, METRICS, RELU>), dim3((unsigned)blocks), dim3(kThreads), 0, stream,
+                       x, p->n, p->group_size, fast_groups, p->num_groups, p->d_bits, p->d_off, p->uniform_bits,
+                       seed_lo, seed_hi, out_words, out_min, out_scale, out_metrics, out_y);
+    return hipGetLastError();
+  }
+  return hipSuccess;
 }
 
 template <int DT, int LPG_LOG2>
@@ -2038,6 +2052,8 @@ hipError_t launch_items(const daf_quantize_item_t* items, int32_t n_items, hipSt
 #if DAF_DT == 0
 bool daf_quantize_reads_once(const daf_plan_t* plan) { return plan->d_big_scratch == nullptr || long_applies(plan); }
 #endif
+
+int DAF_DT_NAME(daf_quantize_route, DAF_DT)(const daf_plan_t* plan) { return quantize_route<DAF_DT>(plan); }
 
 hipError_t DAF_DT_NAME(daf_launch_quantize_pack_batch, DAF_DT)(const daf_quantize_item_t* items, int32_t n_items,
                                                                hipStream_t stream) {

@@ -105,3 +105,20 @@ def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_LIB_PATH", str(tmp_path / "libdaf.so"))
     with pytest.raises(ImportError):
         binding.load_library()
+
+
+@pytest.mark.parametrize("n,gs,dtype,want", [
+    (4096 * 10, 256, 0, 0), (4096 * 10, 4096, 2, 0), (4096 * 10, 32, 1, 0),         # tile
+    (768 * 100, 768, 0, 1), (96 * 1000, 96, 1, 1), (4064 * 9, 4064, 2, 1),          # units
+    (11008 * 7, 11008, 0, 2), (4128 * 3, 4128, 2, 2), (32736 * 2 + 5, 32736, 1, 2),  # long (not whole tiles)
+    (40000 * 3, 40000, 0, 4), (32800 * 2, 32800, 2, 4),                              # group by group
+    (100, 256, 0, 4), (700, 768, 1, 4),                                              # no whole group
+])
+def test_quantize_route_of_uniform_plans(lib, n, gs, dtype, want):
+    """The route a plan's quantize call takes, for plans that need no device (one width, no
+    statistics pass): tile, units, long, group by group."""
+    rc, p = _plan(lib, (n,), gs, [2])
+    assert rc == 0
+    assert lib.daf_plan_quantize_route(p, dtype) == want
+    assert lib.daf_plan_quantize_route(p, 7) == -2 and lib.daf_plan_quantize_route(None, 0) == -1
+    lib.daf_plan_destroy(p)

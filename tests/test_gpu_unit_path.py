@@ -150,3 +150,21 @@ def test_group_minmax_every_m(H):
         assert np.array_equal(mn.cpu().numpy().view(np.uint32), omn.view(np.uint32)), f"min, m={m}"
         assert np.array_equal(mx.cpu().numpy().view(np.uint32), omx.view(np.uint32)), f"max, m={m}"
         plan.destroy()
+
+
+def test_quantize_routes(H):
+    """daf_plan_quantize_route names the kernels the parity tests above exercise."""
+    import paper_2507_07149_amd as daf
+    cases = [((4096 * 8,), 256, 2, torch.float32, "tile"), ((768 * 50,), 768, 2, torch.bfloat16, "units"),
+             ((11008 * 5,), 11008, 2, torch.float16, "long"), ((8192 * 300,), 8192, 2, torch.float32, "long"),
+             ((8192 * 5,), 8192, 2, torch.float32, "two_pass"), ((65536 * 300,), 65536, 2, torch.float32, "two_pass"),
+             ((100000,), 100000 // 32 * 32 + 32, 2, torch.float32, "two_pass"),          # one group for the tensor
+             ((40000 * 4,), 40000, 2, torch.float32, "group")]
+    for shape, gs, bits, dt, want in cases:
+        p = daf.daf_plan(shape, gs, bits)
+        assert p.quantize_route(dt) == want, (shape, gs, want)
+        p.destroy()
+    b = torch.from_numpy(np.random.default_rng(0).choice([1, 2, 4, 8], 50).astype(np.uint8)).cuda()
+    p = daf.daf_plan((768 * 50,), 768, b)
+    assert p.quantize_route(torch.float32) == "units"
+    p.destroy()
