@@ -118,18 +118,18 @@ __device__ __forceinline__ void store_elem(void* y, int64_t i, float v) {   // v
 // COOP = true: the four waves of a workgroup share one group (long groups, of which a call
 // usually has one: the tensor's short last group); the loops below then stride by the
 // workgroup and the waves exchange their (min, max) through LDS.
+// `wave` of `n_waves`: this wave's (COOP: this workgroup's) place among those that share the
+// groups g_begin .. g_end - 1.
 template <int DT, bool METRICS = false, bool RELU = false, bool COOP = false>
-__global__ __launch_bounds__(kThreads) void k_quantize_pack_group(
+__device__ __forceinline__ void quantize_pack_group_body(
     const void* x, int64_t n, int32_t gs, int64_t g_begin, int64_t g_end,
     const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, int32_t uniform_bits,
     uint32_t seed_lo, uint32_t seed_hi, uint32_t* __restrict__ words, float* __restrict__ out_min,
-    float* __restrict__ out_scale, float* __restrict__ out_metrics, void* out_y) {
+    float* __restrict__ out_scale, float* __restrict__ out_metrics, void* out_y, int64_t wave, int64_t n_waves) {
   static_assert(!(COOP && METRICS), "the metrics sums are reduced inside one wave");
   constexpr int kStride = COOP ? kThreads : kWave;           // threads that share a group
   __shared__ float2 coop_stat[kWavesPerBlock];
   const int lane = COOP ? (int)threadIdx.x : (int)(threadIdx.x & (kWave - 1));   // index among them
-  const int64_t wave = COOP ? (int64_t)blockIdx.x : (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
-  const int64_t n_waves = COOP ? (int64_t)gridDim.x : (int64_t)gridDim.x * kWavesPerBlock;
   for (int64_t g = g_begin + wave; g < g_end; g += n_waves) {
     const int64_t lo = g * (int64_t)gs;
     const int32_t len = (int32_t)((lo + gs <= n) ? gs : (n - lo));
@@ -224,6 +224,45 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_group(
       }
     }
   }
+}
+
+template <int DT, bool METRICS = false, bool RELU = false, bool COOP = false>
+__global__ __launch_bounds__(kThreads) void k_quantize_pack_group(
+    const void* x, int64_t n, int32_t gs, int64_t g_begin, int64_t g_end,
+    const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, int32_t uniform_bits,
+    uint32_t seed_lo, uint32_t seed_hi, uint32_t* __restrict__ words, float* __restrict__ out_min,
+    float* __restrict__ out_scale, float* __restrict__ out_metrics, void* out_y) {
+  const int64_t wave = COOP ? (int64_t)blockIdx.x : (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+  const int64_t n_waves = COOP ? (int64_t)gridDim.x : (int64_t)gridDim.x * kWavesPerBlock;
+  quantize_pack_group_body<DT, METRICS, RELU, COOP>(x, n, gs, g_begin, g_end, bits, off, uniform_bits, seed_lo, seed_hi,
+                                                    words, out_min, out_scale, out_metrics, out_y, wave, n_waves);
+}
+
+// The leftovers of several tensors in one launch (list calls): one workgroup per entry takes the
+// entry's groups g_begin .. g_end - 1, its four waves a group each or (COOP) all four together.
+struct GroupBatchEntry {
+  const void* x;
+  const uint8_t* bits;
+  const uint32_t* off;
+  uint32_t* words;
+  float* mn;
+  float* sc;
+  int64_t n, g_begin, g_end;
+  int32_t gs, uniform_bits;
+  uint32_t seed_lo, seed_hi;
+};
+struct GroupBatch {
+  GroupBatchEntry e[32];
+  int32_t n;
+};
+
+template <int DT, bool COOP>
+__global__ __launch_bounds__(kThreads) void k_quantize_pack_group_batch(const GroupBatch batch) {
+  const GroupBatchEntry& e = batch.e[blockIdx.x];
+  quantize_pack_group_body<DT, false, false, COOP>(e.x, e.n, e.gs, e.g_begin, e.g_end, e.bits, e.off, e.uniform_bits,
+                                                   e.seed_lo, e.seed_hi, e.words, e.mn, e.sc, nullptr, nullptr,
+                                                   COOP ? (int64_t)0 : (int64_t)(threadIdx.x >> 6),
+                                                   COOP ? (int64_t)1 : (int64_t)kWavesPerBlock);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1890,6 +1929,41 @@ hipError_t launch_items(const daf_quantize_item_t* items, int32_t n_items, hipSt
     if (batch.n > 0 && err == hipSuccess) err = launch_batch<DT>(batch, cur_log2, cur_bits, stream);
     batch.n = 0;
   };
+  GroupBatch gbatch[2];                // leftovers: [0] a wave per group, [1] a workgroup per group
+  gbatch[0].n = gbatch[1].n = 0;
+  auto gflush = [&](int coop) {
+    GroupBatch& gb = gbatch[coop];
+    if (gb.n > 0 && err == hipSuccess) {
+      if (coop)
+        hipLaunchKernelGGL((k_quantize_pack_group_batch<DT, true>), dim3((unsigned)gb.n), dim3(kThreads), 0, stream, gb);
+      else
+        hipLaunchKernelGGL((k_quantize_pack_group_batch<DT, false>), dim3((unsigned)gb.n), dim3(kThreads), 0, stream, gb);
+      err = hipGetLastError();
+    }
+    gb.n = 0;
+  };
+  // the groups [g_begin, num_groups) of an item, to be quantized group by group
+  auto leftovers = [&](const daf_quantize_item_t& it, int64_t g_begin) {
+    const daf_plan_t* p = it.plan;
+    if (g_begin >= p->num_groups || err != hipSuccess) return;
+    const int coop = p->group_size >= 1024 ? 1 : 0;
+    GroupBatch& gb = gbatch[coop];
+    if (gb.n == 32) gflush(coop);
+    GroupBatchEntry& e = gb.e[gb.n++];
+    e.x = it.x;
+    e.bits = p->d_bits;
+    e.off = p->d_off;
+    e.words = it.out_words;
+    e.mn = it.out_min;
+    e.sc = it.out_scale;
+    e.n = p->n;
+    e.g_begin = g_begin;
+    e.g_end = p->num_groups;
+    e.gs = p->group_size;
+    e.uniform_bits = p->uniform_bits;
+    e.seed_lo = (uint32_t)it.seed;
+    e.seed_hi = (uint32_t)(it.seed >> 32);
+  };
   LongBatch lbatch;                    // items of the one-workgroup-per-group kernel
   lbatch.n = 0;
   int lcur_bits = -1, lcur_waves = -1;
@@ -1958,12 +2032,7 @@ hipError_t launch_items(const daf_quantize_item_t* items, int32_t n_items, hipSt
       e.m = m;
       e.units_per_wave = (m + n_waves - 1) / n_waves;
       ++lbatch.n;
-      if (p->num_groups > full_groups && err == hipSuccess) {           // the short last group
-        hipLaunchKernelGGL((k_quantize_pack_group<DT, false, false, true>), dim3(1), dim3(kThreads), 0, stream, it.x,
-                           p->n, p->group_size, full_groups, p->num_groups, p->d_bits, p->d_off, p->uniform_bits,
-                           e.seed_lo, e.seed_hi, it.out_words, it.out_min, it.out_scale, nullptr, nullptr);
-        err = hipGetLastError();
-      }
+      leftovers(it, full_groups);                                       // the short last group
       continue;
     }
     UnitGeometry ug;
@@ -1988,17 +2057,7 @@ hipError_t launch_items(const daf_quantize_item_t* items, int32_t n_items, hipSt
       e.part_log2 = ug.part_log2;
       e.magic = (65536u + (uint32_t)ug.m - 1u) / (uint32_t)ug.m;
       ++ubatch.n;
-      if (p->num_groups > ug.full_groups && err == hipSuccess) {        // the short last group
-        if (p->group_size >= 1024)
-          hipLaunchKernelGGL((k_quantize_pack_group<DT, false, false, true>), dim3(1), dim3(kThreads), 0, stream, it.x,
-                             p->n, p->group_size, ug.full_groups, p->num_groups, p->d_bits, p->d_off, p->uniform_bits,
-                             e.seed_lo, e.seed_hi, it.out_words, it.out_min, it.out_scale, nullptr, nullptr);
-        else
-          hipLaunchKernelGGL((k_quantize_pack_group<DT, false, false>), dim3(1), dim3(kThreads), 0, stream, it.x,
-                             p->n, p->group_size, ug.full_groups, p->num_groups, p->d_bits, p->d_off, p->uniform_bits,
-                             e.seed_lo, e.seed_hi, it.out_words, it.out_min, it.out_scale, nullptr, nullptr);
-        err = hipGetLastError();
-      }
+      leftovers(it, ug.full_groups);                                    // the short last group
       continue;
     }
     if (!tile_geometry<DT>(p, &log2, &n_tiles, &fast_groups)) {
@@ -2022,19 +2081,13 @@ hipError_t launch_items(const daf_quantize_item_t* items, int32_t n_items, hipSt
     e.seed_lo = (uint32_t)it.seed;
     e.seed_hi = (uint32_t)(it.seed >> 32);
     ++batch.n;
-    const int64_t rest = p->num_groups - fast_groups;
-    if (rest > 0 && err == hipSuccess) {
-      int64_t blocks = (rest + kWavesPerBlock - 1) / kWavesPerBlock;
-      if (blocks > 65536) blocks = 65536;
-      hipLaunchKernelGGL((k_quantize_pack_group<DT, false, false>), dim3((unsigned)blocks), dim3(kThreads), 0, stream,
-                         it.x, p->n, p->group_size, fast_groups, p->num_groups, p->d_bits, p->d_off, p->uniform_bits,
-                         e.seed_lo, e.seed_hi, it.out_words, it.out_min, it.out_scale, nullptr, nullptr);
-      err = hipGetLastError();
-    }
+    leftovers(it, fast_groups);                                         // groups after the last whole tile
   }
   flush();
   uflush();
   lflush();
+  gflush(0);
+  gflush(1);
   return err;
 }
 
