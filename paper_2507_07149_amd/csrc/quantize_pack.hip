@@ -127,8 +127,8 @@ __device__ __forceinline__ void quantize_pack_group_body(
     uint32_t seed_lo, uint32_t seed_hi, uint32_t* __restrict__ words, float* __restrict__ out_min,
     float* __restrict__ out_scale, float* __restrict__ out_metrics, void* out_y, int64_t wave, int64_t n_waves) {
   static_assert(!(COOP && METRICS), "the metrics sums are reduced inside one wave");
-  constexpr int kStride = COOP ? kThreads : kWave;           // threads that share a group
-  __shared__ float2 coop_stat[kWavesPerBlock];
+  const int kStride = COOP ? (int)blockDim.x : kWave;        // threads that share a group (COOP: any workgroup size)
+  __shared__ float2 coop_stat[16];
   const int lane = COOP ? (int)threadIdx.x : (int)(threadIdx.x & (kWave - 1));   // index among them
   for (int64_t g = g_begin + wave; g < g_end; g += n_waves) {
     const int64_t lo = g * (int64_t)gs;
@@ -161,8 +161,7 @@ __device__ __forceinline__ void quantize_pack_group_body(
       // re-reads elements that another wave has replaced by max(z, +0))
       if ((threadIdx.x & (kWave - 1)) == 0) coop_stat[threadIdx.x >> 6] = make_float2(mn, mx);
       __syncthreads();
-#pragma unroll
-      for (int w = 0; w < kWavesPerBlock; ++w) {
+      for (int w = 0; w < (int)(blockDim.x >> 6); ++w) {
         mn = fminf(mn, coop_stat[w].x);
         mx = fmaxf(mx, coop_stat[w].y);
       }
@@ -1415,9 +1414,21 @@ __global__ __launch_bounds__(kWave * kLongMaxWaves) void k_quantize_pack_long(
     typename std::conditional<RELU, const u32x4*, const u32x4* __restrict__>::type x, int32_t m,
     int32_t units_per_wave, const uint8_t* __restrict__ bits,
     const uint32_t* __restrict__ off, uint32_t seed_lo, uint32_t seed_hi, uint32_t* __restrict__ words,
-    float* __restrict__ out_min, float* __restrict__ out_scale, u32x4* out_y, float* __restrict__ out_metrics) {
-  quantize_pack_long_body<DT, B, RELU, METRICS>(x, (int64_t)blockIdx.x, m, units_per_wave, bits, off, seed_lo, seed_hi,
-                                                words, out_min, out_scale, out_y, out_metrics);
+    float* __restrict__ out_min, float* __restrict__ out_scale, u32x4* out_y, float* __restrict__ out_metrics,
+    int64_t n_elems, int64_t full_groups) {
+  // When the tensor has a short last group the grid has one more workgroup, the first, which
+  // quantizes that group the general way: no launch of its own, and its chain of dependent loads
+  // runs while the whole groups stream.
+  const unsigned first_group_block = gridDim.x > (unsigned)full_groups ? 1u : 0u;
+  if (blockIdx.x < first_group_block) {
+    quantize_pack_group_body<DT, METRICS, RELU, !METRICS>(x, n_elems, m * 32, full_groups, full_groups + 1, bits, off, B,
+                                                          seed_lo, seed_hi, words, out_min, out_scale, out_metrics, out_y,
+                                                          METRICS ? (int64_t)(threadIdx.x >> 6) : (int64_t)0,
+                                                          METRICS ? (int64_t)(blockDim.x >> 6) : (int64_t)1);
+    return;
+  }
+  quantize_pack_long_body<DT, B, RELU, METRICS>(x, (int64_t)(blockIdx.x - first_group_block), m, units_per_wave, bits,
+                                                off, seed_lo, seed_hi, words, out_min, out_scale, out_y, out_metrics);
 }
 
 // Several tensors in one launch: the groups of all entries form one sequence of workgroups.  The
@@ -1454,7 +1465,7 @@ inline bool long_applies(const daf_plan_t* p) {
   const int32_t m = gs / 32;
   if (gs % 32 != 0 || m <= 128 || m > 128 * kLongMaxWaves) return false;
   const int64_t full_groups = p->n / gs;
-  if (full_groups == 0 || full_groups > 0x7fffffff) return false;
+  if (full_groups == 0 || full_groups >= 0x7fffffff) return false;
   if (p->d_big_scratch != nullptr && full_groups < 256) return false;          // the two-pass route fills the device better
   return true;
 }
@@ -1471,11 +1482,12 @@ hipError_t launch_long(const daf_plan_t* p, const void* x, uint32_t seed_lo, uin
   const int32_t n_waves = (m + 127) / 128;
   const int32_t units_per_wave = (m + n_waves - 1) / n_waves;
   const unsigned lds_bytes = (unsigned)(n_waves * (sizeof(LongWaveLds) + sizeof(float4) + (METRICS ? sizeof(float4) : 0)));
+  const unsigned blocks = (unsigned)full_groups + (p->num_groups > full_groups ? 1u : 0u);   // + the short last group
 #define DAF_LAUNCH(BITS)                                                                                          \
-  hipLaunchKernelGGL((k_quantize_pack_long<DT, BITS, RELU, METRICS>), dim3((unsigned)full_groups),                \
+  hipLaunchKernelGGL((k_quantize_pack_long<DT, BITS, RELU, METRICS>), dim3(blocks),                               \
                      dim3(kWave * n_waves), lds_bytes, stream, static_cast<const u32x4*>(x), m, units_per_wave,   \
                      p->d_bits, p->d_off, seed_lo, seed_hi, out_words, out_min, out_scale,                        \
-                     static_cast<u32x4*>(out_y), out_metrics)
+                     static_cast<u32x4*>(out_y), out_metrics, p->n, full_groups)
   switch (p->uniform_bits) {
     case 0: DAF_LAUNCH(0); break;
     case 1: DAF_LAUNCH(1); break;
@@ -1485,7 +1497,7 @@ hipError_t launch_long(const daf_plan_t* p, const void* x, uint32_t seed_lo, uin
     default: return hipErrorInvalidValue;
   }
 #undef DAF_LAUNCH
-  *covered = full_groups;
+  *covered = p->num_groups;                                 // the short last group included
   return hipGetLastError();
 }
 
@@ -1495,9 +1507,20 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_units(
     int32_t k_full, int32_t k_last, uint32_t magic, int32_t part_log2,
     const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, uint32_t seed_lo, uint32_t seed_hi,
     uint32_t* __restrict__ words, float* __restrict__ out_min, float* __restrict__ out_scale, u32x4* out_y,
-    float* __restrict__ out_metrics) {
+    float* __restrict__ out_metrics, int64_t n_elems, int64_t left_begin, int64_t left_end) {
   const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int64_t tile = (int64_t)blockIdx.x * kWavesPerBlock + wave_in_block;
+  // When the tensor has a short last group the grid has one more workgroup, the first, which
+  // quantizes the groups left_begin .. left_end - 1 the general way: no launch of their own, and
+  // their chain of dependent loads runs while the tiles stream.
+  const unsigned first_tile_block = left_end > left_begin ? 1u : 0u;
+  const int64_t tile = (int64_t)(blockIdx.x - first_tile_block) * kWavesPerBlock + wave_in_block;
+  if (blockIdx.x < first_tile_block) {
+    quantize_pack_group_body<DT, METRICS, RELU, !METRICS>(x, n_elems, m * 32, left_begin, left_end, bits, off, B, seed_lo,
+                                                          seed_hi, words, out_min, out_scale, out_metrics, out_y,
+                                                          METRICS ? (int64_t)wave_in_block : (int64_t)0,
+                                                          METRICS ? (int64_t)kWavesPerBlock : (int64_t)1);
+    return;
+  }
   if (tile >= n_tiles) return;
   quantize_pack_units_body<DT, B, RELU, METRICS>(x, tile, wave_in_block, n_tiles, m, k_full, k_last, magic, part_log2,
                                                  bits, off, seed_lo, seed_hi, words, out_min, out_scale, out_y,
@@ -1568,11 +1591,13 @@ hipError_t launch_units(const daf_plan_t* p, const void* x, uint32_t seed_lo, ui
   const int32_t m = ug.m, k = ug.k, k_last = ug.k_last, part_log2 = ug.part_log2;
   const int64_t n_tiles = ug.n_tiles, full_groups = ug.full_groups;
   const uint32_t magic = (65536u + (uint32_t)m - 1u) / (uint32_t)m;   // floor(u / m) = (u * magic) >> 16 for u < 128
-  const unsigned blocks = (unsigned)((n_tiles + kWavesPerBlock - 1) / kWavesPerBlock);
+  // one more workgroup for the tensor's short last group, if it has one
+  const unsigned blocks = (unsigned)((n_tiles + kWavesPerBlock - 1) / kWavesPerBlock) + (p->num_groups > full_groups ? 1u : 0u);
 #define DAF_LAUNCH(BITS)                                                                                       \
   hipLaunchKernelGGL((k_quantize_pack_units<DT, BITS, RELU, METRICS>), dim3(blocks), dim3(kThreads), 0, stream, \
                      static_cast<const u32x4*>(x), n_tiles, m, k, k_last, magic, part_log2, p->d_bits, p->d_off, \
-                     seed_lo, seed_hi, out_words, out_min, out_scale, static_cast<u32x4*>(out_y), out_metrics)
+                     seed_lo, seed_hi, out_words, out_min, out_scale, static_cast<u32x4*>(out_y), out_metrics,  \
+                     p->n, full_groups, p->num_groups)
   switch (p->uniform_bits) {
     case 0: DAF_LAUNCH(0); break;
     case 1: DAF_LAUNCH(1); break;
@@ -1582,7 +1607,7 @@ hipError_t launch_units(const daf_plan_t* p, const void* x, uint32_t seed_lo, ui
     default: return hipErrorInvalidValue;
   }
 #undef DAF_LAUNCH
-  *covered = full_groups;
+  *covered = p->num_groups;                                 // the short last group included
   return hipGetLastError();
 }
 
