@@ -670,9 +670,24 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_tile(
     const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, uint32_t seed_lo, uint32_t seed_hi,
     uint32_t* __restrict__ words, float* __restrict__ out_min, float* __restrict__ out_scale,
     const float2* __restrict__ ext_stat, int64_t tiles_per_group, float* __restrict__ out_metrics,
-    u32x4* out_y) {
+    u32x4* out_y, int64_t n_elems, int64_t left_begin, int64_t left_end) {
   const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int64_t tile = (int64_t)blockIdx.x * kWavesPerBlock + wave_in_block;
+  // When groups are left over after the last whole tile (left_begin .. left_end - 1, the tensor's
+  // short last group among them) the grid has one more workgroup, the first, which quantizes
+  // them the general way: no launch of their own, and they run while the tiles stream.
+  const unsigned first_tile_block = (!EXT && left_end > left_begin) ? 1u : 0u;
+  if constexpr (!EXT) {
+    if (blockIdx.x < first_tile_block) {
+      constexpr bool kCoop = !METRICS && TileShape<DT, LPG_LOG2>::kGroupSize >= 1024;
+      quantize_pack_group_body<DT, METRICS, RELU, kCoop>(x, n_elems, TileShape<DT, LPG_LOG2>::kGroupSize, left_begin,
+                                                         left_end, bits, off, B, seed_lo, seed_hi, words, out_min,
+                                                         out_scale, out_metrics, out_y,
+                                                         kCoop ? (int64_t)0 : (int64_t)wave_in_block,
+                                                         kCoop ? (int64_t)1 : (int64_t)kWavesPerBlock);
+      return;
+    }
+  }
+  const int64_t tile = (int64_t)(blockIdx.x - first_tile_block) * kWavesPerBlock + wave_in_block;
   if (tile >= n_tiles) return;
   quantize_pack_tile_body<DT, LPG_LOG2, B, EXT, METRICS, RELU>(x, tile, wave_in_block, bits, off, seed_lo, seed_hi, words,
                                                                out_min, out_scale, ext_stat, tiles_per_group,
@@ -716,13 +731,15 @@ template <int DT, int LPG_LOG2, bool METRICS, bool RELU>
 hipError_t launch_tile(const daf_plan_t* p, const void* x, int64_t n_tiles, uint32_t seed_lo, uint32_t seed_hi,
                        uint32_t* out_words, float* out_min, float* out_scale, float* out_metrics, void* out_y,
                        hipStream_t stream) {
+  const int64_t left = n_tiles * TileShape<DT, LPG_LOG2>::kGroups;   // first group after the whole tiles
 #define DAF_LAUNCH(BITS)                                                                                   \
   do {                                                                                                     \
     auto kernel = k_quantize_pack_tile<DT, LPG_LOG2, BITS, false, METRICS, RELU>;                          \
-    const unsigned blocks = (unsigned)((n_tiles + kWavesPerBlock - 1) / kWavesPerBlock);                   \
+    const unsigned blocks = (unsigned)((n_tiles + kWavesPerBlock - 1) / kWavesPerBlock) + (left < p->num_groups ? 1u : 0u); \
     hipLaunchKernelGGL(kernel, dim3(blocks), dim3(kThreads), 0, stream, static_cast<const u32x4*>(x),      \
                        n_tiles, p->d_bits, p->d_off, seed_lo, seed_hi, out_words, out_min, out_scale,      \
-                       nullptr, (int64_t)1, out_metrics, static_cast<u32x4*>(out_y));                      \
+                       nullptr, (int64_t)1, out_metrics, static_cast<u32x4*>(out_y), p->n, left,           \
+                       p->num_groups);                                                                     \
   } while (0)
   switch (p->uniform_bits) {
     case 0: DAF_LAUNCH(0); break;
@@ -900,7 +917,7 @@ hipError_t launch_big(const daf_plan_t* p, const void* x, uint32_t seed_lo, uint
 #define DAF_LAUNCH(BITS)                                                                                      \
   hipLaunchKernelGGL((k_quantize_pack_tile<DT, kMaxLog2, BITS, true>), dim3(blocks), dim3(kThreads), 0, stream, \
                      static_cast<const u32x4*>(x), n_full_tiles, p->d_bits, p->d_off, seed_lo, seed_hi,       \
-                     out_words, out_min, out_scale, stat, tpg, nullptr, nullptr)
+                     out_words, out_min, out_scale, stat, tpg, nullptr, nullptr, (int64_t)0, (int64_t)0, (int64_t)0)
     switch (p->uniform_bits) {
       case 0: DAF_LAUNCH(0); break;
       case 1: DAF_LAUNCH(1); break;
@@ -1862,7 +1879,7 @@ hipError_t launch_dtype(const daf_plan_t* p, const void* x, uint64_t seed, uint3
   case (1 << LOG2):                                                                                      \
     if constexpr (TileShape<DT, LOG2>::kValid) {                                                         \
       n_tiles = full_groups / TileShape<DT, LOG2>::kGroups;                                              \
-      fast_groups = n_tiles * TileShape<DT, LOG2>::kGroups;                                              \
+      fast_groups = p->num_groups;          /* the leftover groups ride in the same launch */            \
       if (n_tiles > 0) e = launch_tile<DT, LOG2, METRICS, RELU>(p, x, n_tiles, seed_lo, seed_hi, out_words, \
                                                                 out_min, out_scale, out_metrics, out_y,  \
                                                                 stream);                                 \
