@@ -35,21 +35,16 @@ struct SelectState {
   uint32_t hist[kHistCopies][kMaxThresholds][256];
 };
 
-__global__ __launch_bounds__(kThreads) void k_select_keys(const float* __restrict__ gmin, const float* __restrict__ gmax,
-                                                          int64_t G, uint32_t* __restrict__ keys,
-                                                          SelectState* __restrict__ st, uint32_t r0, uint32_t r1,
+// One workgroup: ranks to locate, empty prefixes, zeroed counters.
+__global__ __launch_bounds__(kThreads) void k_select_init(SelectState* __restrict__ st, uint32_t r0, uint32_t r1,
                                                           uint32_t r2) {
-  const int64_t g = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-  if (g < G) keys[g] = f2u(gmax[g] - gmin[g]);
-  if (g == 0) {
+  if (threadIdx.x == 0) {
     st->prefix[0] = st->prefix[1] = st->prefix[2] = 0u;
     st->rank[0] = r0;
     st->rank[1] = r1;
     st->rank[2] = r2;
   }
-  if (blockIdx.x == 0) {
-    for (int i = threadIdx.x; i < kHistCopies * kMaxThresholds * 256; i += kThreads) (&st->hist[0][0][0])[i] = 0u;
-  }
+  for (int i = threadIdx.x; i < kHistCopies * kMaxThresholds * 256; i += kThreads) (&st->hist[0][0][0])[i] = 0u;
 }
 
 // Adds one count per active lane to h[digit].  The digits of a wave are often few (the leading
@@ -68,6 +63,43 @@ __device__ __forceinline__ void wave_hist_add(uint32_t* h, uint32_t digit, bool 
     todo &= ~same;
   }
   if ((todo >> lane) & 1ull) atomicAdd(&h[digit], 1u);
+}
+
+// keys[g] = bit pattern of the group's range, and in the same pass the histogram of the keys'
+// leading digit (the first of the four passes: every key counts for every threshold, so one
+// histogram is added to the counters of all of them).  A wave takes 512 consecutive groups per trip,
+// eight loads of each array in flight per lane.
+__global__ __launch_bounds__(kThreads) void k_select_keys(const float* __restrict__ gmin, const float* __restrict__ gmax,
+                                                          int64_t G, uint32_t* __restrict__ keys,
+                                                          SelectState* __restrict__ st, int n_thresholds) {
+  constexpr int kLoads = 8;
+  __shared__ uint32_t lh[256];
+  for (int i = threadIdx.x; i < 256; i += kThreads) lh[i] = 0u;
+  __syncthreads();
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t wave_stride = (int64_t)gridDim.x * (kThreads / kWave) * (kWave * kLoads);
+  const int64_t first = ((int64_t)blockIdx.x * (kThreads / kWave) + (threadIdx.x >> 6)) * (kWave * kLoads);
+  for (int64_t g0 = first; g0 < G; g0 += wave_stride) {
+    float lo[kLoads], hi[kLoads];
+#pragma unroll
+    for (int j = 0; j < kLoads; ++j) {
+      const int64_t g = g0 + j * kWave + lane;
+      lo[j] = (g < G) ? gmin[g] : 0.0f;
+      hi[j] = (g < G) ? gmax[g] : 0.0f;
+    }
+#pragma unroll
+    for (int j = 0; j < kLoads; ++j) {
+      const int64_t g = g0 + j * kWave + lane;
+      const uint32_t key = f2u(hi[j] - lo[j]);
+      if (g < G) keys[g] = key;
+      wave_hist_add(lh, key >> 24, g < G);
+    }
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < n_thresholds * 256; i += kThreads) {
+    const uint32_t c = lh[i & 255];
+    if (c) atomicAdd(&(&st->hist[blockIdx.x % kHistCopies][0][0])[i], c);
+  }
 }
 
 // Histogram of the digit at `shift` among the keys whose higher digits equal the prefix.  In
@@ -309,13 +341,16 @@ hipError_t daf_launch_select_bits(const float* gmin, const float* gmax, int64_t 
   // thresholds skipped because R_k >= G sit at the end (R_k grows with k), so class = number of
   // satisfied thresholds still indexes `classes` correctly.
 
-  const unsigned gblocks = (unsigned)((G + kThreads - 1) / kThreads);
-  hipLaunchKernelGGL(k_select_keys, dim3(gblocks), dim3(kThreads), 0, stream, gmin, gmax, G, keys, st, R[0], R[1], R[2]);
+  hipLaunchKernelGGL(k_select_init, dim3(1), dim3(kThreads), 0, stream, st, R[0], R[1], R[2]);
+  const unsigned kblocks = (unsigned)((G + 8 * kThreads - 1) / (8 * kThreads));                  // eight keys per thread and trip
+  hipLaunchKernelGGL(k_select_keys, dim3(kblocks < 1024u ? kblocks : 1024u), dim3(kThreads), 0, stream, gmin, gmax, G,
+                     keys, st, n_thr);
   if (n_thr > 0) {
     const unsigned cblocks = (unsigned)((((G + 3) >> 2) + 4 * kThreads - 1) / (4 * kThreads));   // sixteen keys per thread and trip
     const unsigned hblocks = cblocks < 1024u ? cblocks : 1024u;
     for (int shift = 24; shift >= 0; shift -= 8) {
-      hipLaunchKernelGGL(k_select_hist, dim3(hblocks), dim3(kThreads), 0, stream, keys, G, st, n_thr, shift);
+      if (shift != 24)                 // the leading digit was counted while the keys were written
+        hipLaunchKernelGGL(k_select_hist, dim3(hblocks), dim3(kThreads), 0, stream, keys, G, st, n_thr, shift);
       hipLaunchKernelGGL(k_select_pick, dim3(1), dim3(256), 0, stream, st, n_thr, shift);
     }
     hipLaunchKernelGGL(k_select_tie_count, dim3((unsigned)n_blocks), dim3(kThreads), 0, stream, keys, G, st, n_thr,
