@@ -1631,51 +1631,15 @@ hipError_t launch_units(const daf_plan_t* p, const void* x, uint32_t seed_lo, ui
 // ------------------------------------------------------------------------------------------
 // Statistics only: per-group min and max, for a controller that chooses the widths.
 // ------------------------------------------------------------------------------------------
-template <int DT, int LPG_LOG2>
-__global__ __launch_bounds__(kThreads) void k_group_minmax_tile(const u32x4* __restrict__ x, int64_t n_tiles,
-                                                                float* __restrict__ out_min,
-                                                                float* __restrict__ out_max) {
-  using S = TileShape<DT, LPG_LOG2>;
-  __shared__ float2 stat_all[kWavesPerBlock][kWave];
-  const int lane = threadIdx.x & (kWave - 1);
-  const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int64_t tile = (int64_t)blockIdx.x * kWavesPerBlock + wave_in_block;
-  if (tile >= n_tiles) return;
-  float2* stat = stat_all[wave_in_block];
-  uint4 raw[S::kLoads];
-#pragma unroll
-  for (int u = 0; u < S::kLoads; ++u) {
-    const u32x4 v = __builtin_nontemporal_load(&x[tile * (S::kLoads * kWave) + u * kWave + lane]);
-    raw[u] = make_uint4(v.x, v.y, v.z, v.w);
-  }
-  float xf[S::kLoads][S::kEpl];
-  tile_minmax<DT, LPG_LOG2>(raw, xf, stat, lane);
-  wave_lds_sync();
-  if (lane < S::kGroups) {
-    float2 st = stat[lane * S::kLoadsPerGroup];
-#pragma unroll
-    for (int j = 1; j < S::kLoadsPerGroup; ++j) {
-      const float2 t = stat[lane * S::kLoadsPerGroup + j];
-      st.x = vmin(st.x, t.x);
-      st.y = vmax(st.y, t.y);
-    }
-    out_min[tile * S::kGroups + lane] = st.x + 0.0f;
-    out_max[tile * S::kGroups + lane] = st.y + 0.0f;
-  }
-}
-
 // One wave per group, any group size (a multiple of 32 elements, so every group starts on a
 // 16-byte boundary): the group's whole 16-byte chunks four per lane at a time, the elements
 // after them (the tensor's short last group only) one by one.
 template <int DT>
-__global__ __launch_bounds__(kThreads) void k_group_minmax_group(const void* __restrict__ x, int64_t n, int32_t gs,
-                                                                 int64_t g_begin, int64_t g_end,
-                                                                 float* __restrict__ out_min,
-                                                                 float* __restrict__ out_max) {
+__device__ __forceinline__ void group_minmax_group_body(const void* __restrict__ x, int64_t n, int32_t gs,
+                                                        int64_t g_begin, int64_t g_end, float* __restrict__ out_min,
+                                                        float* __restrict__ out_max, int64_t wave, int64_t n_waves) {
   constexpr int kEpl = ElemTraits<DT>::kPerLoad;
   const int lane = threadIdx.x & (kWave - 1);
-  const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
-  const int64_t n_waves = (int64_t)gridDim.x * kWavesPerBlock;
   for (int64_t g = g_begin + wave; g < g_end; g += n_waves) {
     const int64_t lo = g * (int64_t)gs;
     const int32_t len = (int32_t)((lo + gs <= n) ? gs : (n - lo));
@@ -1714,6 +1678,57 @@ __global__ __launch_bounds__(kThreads) void k_group_minmax_group(const void* __r
   }
 }
 
+template <int DT>
+__global__ __launch_bounds__(kThreads) void k_group_minmax_group(const void* __restrict__ x, int64_t n, int32_t gs,
+                                                                 int64_t g_begin, int64_t g_end,
+                                                                 float* __restrict__ out_min,
+                                                                 float* __restrict__ out_max) {
+  group_minmax_group_body<DT>(x, n, gs, g_begin, g_end, out_min, out_max,
+                              (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6),
+                              (int64_t)gridDim.x * kWavesPerBlock);
+}
+
+template <int DT, int LPG_LOG2>
+__global__ __launch_bounds__(kThreads) void k_group_minmax_tile(const u32x4* __restrict__ x, int64_t n_tiles,
+                                                                float* __restrict__ out_min,
+                                                                float* __restrict__ out_max, int64_t n_elems,
+                                                                int64_t left_begin, int64_t left_end) {
+  using S = TileShape<DT, LPG_LOG2>;
+  __shared__ float2 stat_all[kWavesPerBlock][kWave];
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  // groups left over after the last whole tile: one more workgroup, the first of the grid
+  const unsigned first_tile_block = left_end > left_begin ? 1u : 0u;
+  if (blockIdx.x < first_tile_block) {
+    group_minmax_group_body<DT>(x, n_elems, S::kGroupSize, left_begin, left_end, out_min, out_max, wave_in_block,
+                                kWavesPerBlock);
+    return;
+  }
+  const int64_t tile = (int64_t)(blockIdx.x - first_tile_block) * kWavesPerBlock + wave_in_block;
+  if (tile >= n_tiles) return;
+  float2* stat = stat_all[wave_in_block];
+  uint4 raw[S::kLoads];
+#pragma unroll
+  for (int u = 0; u < S::kLoads; ++u) {
+    const u32x4 v = __builtin_nontemporal_load(&x[tile * (S::kLoads * kWave) + u * kWave + lane]);
+    raw[u] = make_uint4(v.x, v.y, v.z, v.w);
+  }
+  float xf[S::kLoads][S::kEpl];
+  tile_minmax<DT, LPG_LOG2>(raw, xf, stat, lane);
+  wave_lds_sync();
+  if (lane < S::kGroups) {
+    float2 st = stat[lane * S::kLoadsPerGroup];
+#pragma unroll
+    for (int j = 1; j < S::kLoadsPerGroup; ++j) {
+      const float2 t = stat[lane * S::kLoadsPerGroup + j];
+      st.x = vmin(st.x, t.x);
+      st.y = vmax(st.y, t.y);
+    }
+    out_min[tile * S::kGroups + lane] = st.x + 0.0f;
+    out_max[tile * S::kGroups + lane] = st.y + 0.0f;
+  }
+}
+
 __global__ void k_stat_to_outputs(const float2* __restrict__ stat, int64_t num_groups, float* __restrict__ out_min,
                                   float* __restrict__ out_max) {
   const int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -1729,12 +1744,20 @@ template <int DT>
 __global__ __launch_bounds__(kThreads) void k_group_minmax_units(const u32x4* __restrict__ x, int64_t n_tiles, int32_t m,
                                                                  int32_t k_full, int32_t k_last, int32_t part_log2,
                                                                  float* __restrict__ out_min,
-                                                                 float* __restrict__ out_max) {
+                                                                 float* __restrict__ out_max, int64_t n_elems,
+                                                                 int64_t left_begin, int64_t left_end) {
   using S = UnitShape<DT>;
   __shared__ float2 ustat_all[kWavesPerBlock][S::kUnits];
   const int lane = threadIdx.x & (kWave - 1);
   const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int64_t tile = (int64_t)blockIdx.x * kWavesPerBlock + wave_in_block;
+  // the tensor's short last group: one more workgroup, the first of the grid
+  const unsigned first_tile_block = left_end > left_begin ? 1u : 0u;
+  if (blockIdx.x < first_tile_block) {
+    group_minmax_group_body<DT>(x, n_elems, m * 32, left_begin, left_end, out_min, out_max, wave_in_block,
+                                kWavesPerBlock);
+    return;
+  }
+  const int64_t tile = (int64_t)(blockIdx.x - first_tile_block) * kWavesPerBlock + wave_in_block;
   if (tile >= n_tiles) return;
   const int k = (tile == n_tiles - 1) ? k_last : k_full;
   const uint32_t n_chunks = ((uint32_t)(k * m)) << S::kLanesLog2;
@@ -1777,11 +1800,13 @@ hipError_t launch_group_minmax(const daf_plan_t* p, const void* x, float* out_mi
   case (1 << LOG2):                                                                                             \
     if constexpr (TileShape<DT, LOG2>::kValid) {                                                                \
       const int64_t n_tiles = full_groups / TileShape<DT, LOG2>::kGroups;                                       \
-      fast_groups = n_tiles * TileShape<DT, LOG2>::kGroups;                                                     \
-      if (n_tiles > 0)                                                                                          \
+      const int64_t left = n_tiles * TileShape<DT, LOG2>::kGroups;                                              \
+      if (n_tiles > 0) {                                                                                        \
         hipLaunchKernelGGL((k_group_minmax_tile<DT, LOG2>), dim3((unsigned)((n_tiles + kWavesPerBlock - 1) /    \
-                           kWavesPerBlock)), dim3(kThreads), 0, stream, static_cast<const u32x4*>(x), n_tiles,  \
-                           out_min, out_max);                                                                   \
+                           kWavesPerBlock) + (left < p->num_groups ? 1u : 0u)), dim3(kThreads), 0, stream,      \
+                           static_cast<const u32x4*>(x), n_tiles, out_min, out_max, p->n, left, p->num_groups); \
+        fast_groups = p->num_groups;        /* the leftover groups ride in the same launch */                   \
+      }                                                                                                         \
     }                                                                                                           \
     break;
     switch (lpg) {
@@ -1795,10 +1820,11 @@ hipError_t launch_group_minmax(const daf_plan_t* p, const void* x, float* out_mi
   }
   UnitGeometry ug;
   if (fast_groups == 0 && unit_geometry(p, &ug)) {
-    hipLaunchKernelGGL((k_group_minmax_units<DT>), dim3((unsigned)((ug.n_tiles + kWavesPerBlock - 1) / kWavesPerBlock)),
-                       dim3(kThreads), 0, stream, static_cast<const u32x4*>(x), ug.n_tiles, ug.m, ug.k, ug.k_last,
-                       ug.part_log2, out_min, out_max);
-    fast_groups = ug.full_groups;
+    hipLaunchKernelGGL((k_group_minmax_units<DT>), dim3((unsigned)((ug.n_tiles + kWavesPerBlock - 1) / kWavesPerBlock) +
+                       (ug.full_groups < p->num_groups ? 1u : 0u)), dim3(kThreads), 0, stream,
+                       static_cast<const u32x4*>(x), ug.n_tiles, ug.m, ug.k, ug.k_last, ug.part_log2, out_min, out_max,
+                       p->n, ug.full_groups, p->num_groups);
+    fast_groups = p->num_groups;            // the short last group rides in the same launch
   }
   const int64_t rest = p->num_groups - fast_groups;
   if (rest > 0) {
