@@ -7,7 +7,8 @@
 //                              group and its bits never straddle a word pair, so it needs one
 //                              (or, at 8 bits and 16-bit output, two) packed words.  Covers every
 //                              whole chunk of the tensor, for any group size.
-//   k_unpack_dequantize_tail   the fewer than 8 elements after the last whole chunk.
+//   k_unpack_dequantize_tail   the fewer than 8 elements after the last whole chunk (list calls; a
+//                              single-tensor call gives them to one more workgroup of the main launch).
 //
 // RELU_BWD = true turns both into the backward of y = max(z, 0) whose output y was the saved
 // activation: instead of xhat the kernels write grad_z = (xhat > 0) ? grad_y : +0, with xhat
@@ -41,7 +42,7 @@ __device__ __forceinline__ uint32_t keep_where_positive(uint32_t xhat_word, uint
 
 // The last elements of the tensor, [e_begin, n) with n - e_begin < 8: all in the last group.
 template <int DT, bool RELU_BWD>
-__global__ __launch_bounds__(kWave) void k_unpack_dequantize_tail(
+__device__ __forceinline__ void unpack_dequantize_tail_body(
     const uint32_t* __restrict__ words, const float* __restrict__ mn, const float* __restrict__ scale,
     const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, int32_t uniform_bits, int64_t e_begin,
     int64_t n, int32_t gs, void* out, const void* grad) {
@@ -66,6 +67,14 @@ __global__ __launch_bounds__(kWave) void k_unpack_dequantize_tail(
   } else {
     store_elem<DT>(out, i, v);
   }
+}
+
+template <int DT, bool RELU_BWD>
+__global__ __launch_bounds__(kWave) void k_unpack_dequantize_tail(
+    const uint32_t* __restrict__ words, const float* __restrict__ mn, const float* __restrict__ scale,
+    const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, int32_t uniform_bits, int64_t e_begin,
+    int64_t n, int32_t gs, void* out, const void* grad) {
+  unpack_dequantize_tail_body<DT, RELU_BWD>(words, mn, scale, bits, off, uniform_bits, e_begin, n, gs, out, grad);
 }
 
 // The loop over a thread's chunks is split into phases (metadata loads, word loads,
@@ -171,9 +180,18 @@ template <int DT, bool MIXED, bool RELU_BWD>
 __global__ __launch_bounds__(kThreads) void k_unpack_dequantize_chunk(
     const uint32_t* __restrict__ words, const float* __restrict__ mn, const float* __restrict__ scale,
     const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, int32_t uniform_bits,
-    int64_t n_chunks, int32_t gs, int32_t gs_shift, u32x4* out, const u32x4* grad, int cached) {
-  unpack_dequantize_block<DT, MIXED, RELU_BWD>((int64_t)blockIdx.x, words, mn, scale, bits, off, uniform_bits, n_chunks,
-                                               gs, gs_shift, out, grad, cached != 0);
+    int64_t n_chunks, int32_t gs, int32_t gs_shift, u32x4* out, const u32x4* grad, int cached, int64_t n) {
+  // When elements are left after the last whole chunk (fewer than 8) the grid has one more
+  // workgroup, the first, whose first wave takes them: no launch of their own.
+  const unsigned first_chunk_block = n > n_chunks * ElemTraits<DT>::kPerLoad ? 1u : 0u;
+  if (blockIdx.x < first_chunk_block) {
+    if (threadIdx.x < kWave)
+      unpack_dequantize_tail_body<DT, RELU_BWD>(words, mn, scale, bits, off, uniform_bits,
+                                                n_chunks * ElemTraits<DT>::kPerLoad, n, gs, out, grad);
+    return;
+  }
+  unpack_dequantize_block<DT, MIXED, RELU_BWD>((int64_t)(blockIdx.x - first_chunk_block), words, mn, scale, bits, off,
+                                               uniform_bits, n_chunks, gs, gs_shift, out, grad, cached != 0);
 }
 
 // Several tensors in one launch: the blocks of all of them form one sequence and a block finds
@@ -216,17 +234,16 @@ hipError_t launch_dtype(const daf_plan_t* p, const uint32_t* words, const float*
   if ((p->group_size & (p->group_size - 1)) == 0) gs_shift = __builtin_ctz((unsigned)p->group_size);
   if (n_chunks > 0) {
     const int64_t per_block = (int64_t)kThreads * kChunksPerThread;
-    const unsigned blocks = (unsigned)((n_chunks + per_block - 1) / per_block);
+    const unsigned blocks = (unsigned)((n_chunks + per_block - 1) / per_block) + (n_chunks * kEpl < p->n ? 1u : 0u);
     if (p->uniform_bits)
       hipLaunchKernelGGL((k_unpack_dequantize_chunk<DT, false, RELU_BWD>), dim3(blocks), dim3(kThreads), 0, stream,
                          words, mn, scale, nullptr, nullptr, p->uniform_bits, n_chunks, p->group_size, gs_shift,
-                         static_cast<u32x4*>(out_x), static_cast<const u32x4*>(grad), p->output_cached);
+                         static_cast<u32x4*>(out_x), static_cast<const u32x4*>(grad), p->output_cached, p->n);
     else
       hipLaunchKernelGGL((k_unpack_dequantize_chunk<DT, true, RELU_BWD>), dim3(blocks), dim3(kThreads), 0, stream,
                          words, mn, scale, d_bits, p->d_off, 0, n_chunks, p->group_size, gs_shift,
-                         static_cast<u32x4*>(out_x), static_cast<const u32x4*>(grad), p->output_cached);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+                         static_cast<u32x4*>(out_x), static_cast<const u32x4*>(grad), p->output_cached, p->n);
+    return hipGetLastError();                            // the elements after the last chunk rode along
   }
   if (n_chunks * kEpl < p->n) {
     hipLaunchKernelGGL((k_unpack_dequantize_tail<DT, RELU_BWD>), dim3(1), dim3(kWave), 0, stream, words, mn, scale,
