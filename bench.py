@@ -658,12 +658,12 @@ def main():
     dk = kernel_pass("d", batch, n_batches)
     qk_ms, dk_ms = qk["median"], dk["median"]
     alg = sum(algorithmic_bytes(w, p.packed_words) for w, p in zip(workloads, plans))
-    # groups longer than 32768 elements (or fewer than 256 groups of a whole number of 4096-element
+    # groups longer than 65536 elements (or fewer than 256 groups of a whole number of 4096-element
     # tiles) need their statistics before any element can be quantized: the quantize direction
     # then reads the activation twice; shorter groups are kept in registers by one workgroup
     def two_reads(w):
         gs = w.group_size
-        return gs > 32768 or (gs > 4096 and gs % 4096 == 0 and w.numel // gs < 256)
+        return gs > 65536 or (gs > 4096 and gs % 4096 == 0 and w.numel // gs < 256)
     alg_q = alg + sum(w.numel * w.x.element_size() for w in workloads if two_reads(w))
     value = 2 * in_bytes / (ms_per_step * 1e-3) / 1e9
     gs0 = workloads[0].group_size

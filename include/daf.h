@@ -94,8 +94,8 @@ int32_t daf_plan_uniform_bits(const daf_plan_t* plan);   /* the shared width, or
  * tensor's short last group always go one by one.  A host computation, for tuning and tests.
  *   DAF_ROUTE_TILE      group size a power of two up to 4096: one wave per 4096-element tile
  *   DAF_ROUTE_UNITS     other group sizes up to 4096: one wave per run of whole groups
- *   DAF_ROUTE_LONG      4128 ... 32768 elements: one workgroup per group
- *   DAF_ROUTE_TWO_PASS  longer groups of whole tiles, fewer than 256 groups of 8192 ... 32768, one
+ *   DAF_ROUTE_LONG      4128 ... 65536 elements: one workgroup per group
+ *   DAF_ROUTE_TWO_PASS  longer groups of whole tiles, fewer than 256 groups of 8192 ... 65536, one
  *                       group for the tensor: statistics first, the activation is read twice
  *   DAF_ROUTE_GROUP     everything else: one wave or workgroup per group, element loads
  * Returns the route (>= 0), DAF_EINVAL for a NULL plan, DAF_EUNSUPPORTED for an unknown dtype. */
@@ -150,9 +150,9 @@ void daf_plan_destroy(daf_plan_t* plan);
  *   out_min    DEVICE, G floats; out_scale: DEVICE, G floats.  Always binary32.
  *   stream     the call only enqueues work on this stream; it does not synchronize.
  *
- * x is read once for every group size up to 32768 elements (any multiple of 32: a row of 768,
+ * x is read once for every group size up to 65536 elements (any multiple of 32: a row of 768,
  * 3072 or 11008 elements is as good a group as a power of two); longer groups, fewer than 256
- * groups of 8192, 16384 or 32768 elements, and one group for the whole tensor need the group's
+ * groups of 8192 ... 65536 elements (whole tiles), and one group for the whole tensor need the group's
  * statistics before any element can be quantized and read x twice.
  *
  * Errors: DAF_EINVAL (null or misaligned pointer), DAF_EUNSUPPORTED (dtype), DAF_EDEVICE.
@@ -257,7 +257,7 @@ int daf_group_minmax(const daf_plan_t* plan, const void* x, daf_dtype_t dtype,
  *   out_metrics   DEVICE, 3*G floats, 4-byte aligned.
  *
  * Errors: as daf_quantize_pack; DAF_EUNSUPPORTED also for plans for which daf_quantize_pack reads
- * x twice (groups longer than 32768 elements, fewer than 256 groups of 8192, 16384 or 32768
+ * x twice (groups longer than 65536 elements, fewer than 256 groups of 8192 ... 65536
  * elements, one group for the tensor).
  */
 int daf_quantize_pack_metrics(const daf_plan_t* plan, const void* x, daf_dtype_t dtype, uint64_t seed,
@@ -316,7 +316,7 @@ int daf_unpack_dequantize_batch(const daf_dequantize_item_t* items, int32_t n_it
  *
  * Errors: as daf_quantize_pack; DAF_EINVAL also for out_y partially overlapping z;
  * DAF_EUNSUPPORTED also for plans for which daf_quantize_pack reads x twice (groups longer than
- * 32768 elements, fewer than 256 groups of 8192, 16384 or 32768 elements, one group for the tensor).
+ * 65536 elements, fewer than 256 groups of 8192 ... 65536 elements, one group for the tensor).
  */
 int daf_relu_quantize_pack(const daf_plan_t* plan, const void* z, daf_dtype_t dtype, uint64_t seed, void* out_y,
                            uint32_t* out_words, float* out_min, float* out_scale, void* stream);

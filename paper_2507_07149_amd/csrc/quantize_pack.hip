@@ -10,7 +10,7 @@
 //                          runs.
 //   k_quantize_pack_units  other sizes up to 4096: the same, with a tile of as many whole groups
 //                          as fit into 128 units of 32 elements.
-//   k_quantize_pack_long   4128 ... 32768: one workgroup per group, a slice per wave, (min, max)
+//   k_quantize_pack_long   4128 ... 65536: one workgroup per group, a slice per wave, (min, max)
 //                          exchanged through LDS; x is still read once.
 //   two passes             longer groups and per-tensor statistics (k_tile_minmax,
 //                          k_group_reduce, then k_quantize_pack_tile with the group's pair).
@@ -1264,7 +1264,7 @@ __device__ __forceinline__ void quantize_pack_units_body(
   }
 }
 
-// Long groups, 128 < m <= 1024 units (4096 < group size <= 32768 elements, e.g. a row of
+// Long groups, 128 < m <= 2048 units (4096 < group size <= 65536 elements, e.g. a row of
 // 11008): one workgroup per group, one wave per slice of at most 128 units.  Every wave keeps
 // its slice in registers, the waves exchange their (min, max) through LDS, and each then
 // quantizes and writes its part of the group's words: the activation is read once.
@@ -1274,7 +1274,7 @@ struct LongWaveLds {
     uint32_t stage[1024];
   };
 };
-constexpr int kLongMaxWaves = 8;
+constexpr int kLongMaxWaves = 16;
 
 template <int DT, int B, bool RELU = false, bool METRICS = false>
 __device__ __forceinline__ void quantize_pack_long_body(
@@ -1423,7 +1423,7 @@ __device__ __forceinline__ void quantize_pack_long_body(
   }
 }
 
-// Takes plans whose groups are 32 * m elements, 128 < m <= 1024, when there are enough groups to
+// Takes plans whose groups are 32 * m elements, 128 < m <= 2048, when there are enough groups to
 // fill the device with one workgroup each, or when the two-pass route does not apply (groups
 // not a whole number of tiles).  Returns the groups it covered (all whole groups, or none).
 template <int DT, int B, bool RELU = false, bool METRICS = false>
@@ -1886,7 +1886,7 @@ hipError_t launch_dtype(const daf_plan_t* p, const void* x, uint64_t seed, uint3
   const int64_t full_groups = p->n / p->group_size;
   int64_t fast_groups = 0;
   const int route = quantize_route<DT>(p);                  // 0 tile, 1 units, 2 long, 3 two passes, 4 group by group
-  if (route == 2) {                     // groups of 4128 .. 32768 elements, one workgroup each
+  if (route == 2) {                     // groups of 4128 .. 65536 elements, one workgroup each
     const hipError_t e = launch_long<DT, RELU, METRICS>(p, x, seed_lo, seed_hi, out_words, out_min, out_scale, out_y,
                                                         out_metrics, &fast_groups, stream);
     if (e != hipSuccess) return e;

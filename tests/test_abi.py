@@ -111,7 +111,8 @@ def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     (4096 * 10, 256, 0, 0), (4096 * 10, 4096, 2, 0), (4096 * 10, 32, 1, 0),         # tile
     (768 * 100, 768, 0, 1), (96 * 1000, 96, 1, 1), (4064 * 9, 4064, 2, 1),          # units
     (11008 * 7, 11008, 0, 2), (4128 * 3, 4128, 2, 2), (32736 * 2 + 5, 32736, 1, 2),  # long (not whole tiles)
-    (40000 * 3, 40000, 0, 4), (32800 * 2, 32800, 2, 4),                              # group by group
+    (40000 * 3, 40000, 0, 2), (65504 * 2, 65504, 2, 2),                              # long, up to 65536
+    (69984 * 3, 69984, 0, 4), (65568 * 2, 65568, 2, 4),                              # group by group
     (100, 256, 0, 4), (700, 768, 1, 4),                                              # no whole group
 ])
 def test_quantize_route_of_uniform_plans(lib, n, gs, dtype, want):

@@ -78,12 +78,13 @@ def test_batch_of_tensors_with_row_sized_groups(env, dtype):
 
 @pytest.mark.parametrize("dtype", [F32, BF16])
 def test_batch_of_tensors_with_long_groups(env, dtype):
-    """Groups of 4128 ... 32768 elements: items with the same number of waves per group and the same
+    """Groups of 4128 ... 65536 elements: items with the same number of waves per group and the same
     width kind share a launch; others, and the short last groups, get their own."""
     daf, orc = env
     _roundtrip(daf, orc, dtype, [(11008 * 5, 11008, 2), (11008 * 3 + 700, 11008, 2), (12288 * 2 + 5, 12288, 2), (4128 * 7, 4128, 2),
                                  (8192 * 300, 8192, 2), (4096 * 3, 256, 2), (11008 * 4, 11008, "mixed"), (9600 * 6 + 9000, 9600, "mixed"),
-                                 (32736 * 2 + 1, 32736, 8), (768 * 9, 768, 8), (32768 * 3, 32768, 8)])
+                                 (32736 * 2 + 1, 32736, 8), (768 * 9, 768, 8), (32768 * 3, 32768, 8), (65504 * 2 + 9, 65504, 8),
+                                 (40000 * 3, 40000, 2)])
 
 
 def test_batch_of_many_row_sized_tensors(env):

@@ -181,9 +181,9 @@ def test_unpack_relu_backward_argument_errors(env):
         daf.daf_unpack_relu_backward(plan, words, mn, mn, big[:8192], torch.zeros(8192, dtype=torch.float16, device="cuda:0"))
 
 
-@pytest.mark.parametrize("dtype,gs,bits", [(F32, 8192, 2), (BF16, 16384, "mixed"), (F16, 32768, 8)])
+@pytest.mark.parametrize("dtype,gs,bits", [(F32, 8192, 2), (BF16, 16384, "mixed"), (F16, 32768, 8), (BF16, 65536, 4)])
 def test_fused_relu_long_groups_of_whole_tiles(env, dtype, gs, bits):
-    """256 groups or more of 8192 ... 32768 elements are read once (one workgroup per group), so
+    """256 groups or more of 8192 ... 65536 elements are read once (one workgroup per group), so
     the fused max(z, 0) exists for them; fewer such groups go through two passes and are refused."""
     daf, orc = env
     n = 257 * gs + 321

@@ -92,15 +92,16 @@ def test_fused_relu_random_cases(seed):
 
 @pytest.mark.parametrize("seed", range(6))
 def test_any_group_size_random_cases(H, seed):
-    """Group sizes drawn from every regime of the dispatch (32 * m for m around 1 ... 1100, with
+    """Group sizes drawn from every regime of the dispatch (32 * m for m around 1 ... 2200, with
     extra weight on the borders between the kernels), random lengths with and without whole
     last groups: quantize + dequantize against the oracle, and the statistics-only call."""
     import paper_2507_07149_amd as daf
     from oracle import daf_oracle as orc
     rng = np.random.default_rng(3000 + seed)
-    borders = [1, 2, 3, 4, 5, 63, 64, 65, 127, 128, 129, 130, 255, 256, 257, 384, 511, 512, 513, 1023, 1024, 1025, 1030]
+    borders = [1, 2, 3, 4, 5, 63, 64, 65, 127, 128, 129, 130, 255, 256, 257, 384, 511, 512, 513, 1023, 1024, 1025, 1030, 2047,
+               2048, 2049]
     for case in range(14):
-        m = int(rng.choice(borders)) if rng.random() < 0.5 else int(rng.integers(1, 1100))
+        m = int(rng.choice(borders)) if rng.random() < 0.5 else int(rng.integers(1, 2200))
         gs = 32 * m
         groups = int(rng.integers(1, max(2, 300000 // gs)))
         n = groups * gs + (int(rng.integers(1, gs)) if rng.random() < 0.6 else 0)

@@ -84,7 +84,7 @@ def test_unit_path_extreme_values(H):
         H.assert_full_parity(w, H.run_hip(w))
 
 
-# ---- groups of 4128 .. 32768 elements: one workgroup per group ---------------------------------
+# ---- groups of 4128 .. 65536 elements: one workgroup per group ---------------------------------
 
 def _long_workload(dtype, gs, bits, seed, groups, last):
     n = groups * gs + last
@@ -100,7 +100,7 @@ def _long_workload(dtype, gs, bits, seed, groups, last):
 
 
 @pytest.mark.parametrize("dtype", [F32, F16, BF16])
-@pytest.mark.parametrize("gs", [4128, 5120, 11008, 12320, 32736])      # 129, 160, 344, 385, 1023 units: 2, 2, 3, 4, 8 waves
+@pytest.mark.parametrize("gs", [4128, 5120, 11008, 12320, 32736, 40000, 65504])   # 129 ... 2047 units: 2, 2, 3, 4, 8, 10, 16 waves
 @pytest.mark.parametrize("bits", [1, 2, 4, 8, "mixed"])
 def test_long_groups_not_a_multiple_of_the_tile(H, dtype, gs, bits):
     w = _long_workload(dtype, gs, bits, seed=gs % 1000 + dtype, groups=5, last=gs // 3 + 1)
@@ -108,7 +108,8 @@ def test_long_groups_not_a_multiple_of_the_tile(H, dtype, gs, bits):
     H.assert_full_parity(w, H.run_hip(w))
 
 
-@pytest.mark.parametrize("dtype,gs,bits", [(F32, 8192, 2), (BF16, 8192, "mixed"), (F16, 16384, 4), (F32, 32768, "mixed")])
+@pytest.mark.parametrize("dtype,gs,bits", [(F32, 8192, 2), (BF16, 8192, "mixed"), (F16, 16384, 4), (F32, 32768, "mixed"),
+                                           (BF16, 65536, 2), (F16, 49152, "mixed")])
 def test_long_groups_of_whole_tiles(H, dtype, gs, bits):
     """256 groups or more: the one-workgroup-per-group kernel also takes groups that are a whole
     number of tiles (fewer groups go through the two-pass route, tested elsewhere)."""
@@ -119,7 +120,7 @@ def test_long_groups_of_whole_tiles(H, dtype, gs, bits):
 
 def test_long_groups_every_wave_count(H):
     """Group sizes around every change of the number of waves and of the slice length."""
-    for m in (129, 130, 255, 256 + 1, 383, 384, 385, 511, 513, 640, 767, 769, 896, 897, 1000, 1024):
+    for m in (129, 130, 255, 256 + 1, 383, 384, 385, 511, 513, 640, 767, 769, 896, 897, 1000, 1024, 1025, 1153, 1536, 1921, 2047):
         gs = 32 * m
         if m == 1024:
             continue                                     # a power of two: whole tiles, covered above
@@ -157,9 +158,10 @@ def test_quantize_routes(H):
     import paper_2507_07149_amd as daf
     cases = [((4096 * 8,), 256, 2, torch.float32, "tile"), ((768 * 50,), 768, 2, torch.bfloat16, "units"),
              ((11008 * 5,), 11008, 2, torch.float16, "long"), ((8192 * 300,), 8192, 2, torch.float32, "long"),
-             ((8192 * 5,), 8192, 2, torch.float32, "two_pass"), ((65536 * 300,), 65536, 2, torch.float32, "two_pass"),
+             ((8192 * 5,), 8192, 2, torch.float32, "two_pass"), ((65536 * 300,), 65536, 2, torch.float32, "long"),
+             ((131072 * 300,), 131072, 2, torch.float32, "two_pass"),
              ((100000,), 100000 // 32 * 32 + 32, 2, torch.float32, "two_pass"),          # one group for the tensor
-             ((40000 * 4,), 40000, 2, torch.float32, "group")]
+             ((40000 * 4,), 40000, 2, torch.float32, "long"), ((69984 * 4,), 69984, 2, torch.float32, "group")]
     for shape, gs, bits, dt, want in cases:
         p = daf.daf_plan(shape, gs, bits)
         assert p.quantize_route(dt) == want, (shape, gs, want)
