@@ -100,24 +100,72 @@ def _stream_handle(stream) -> Optional[int]:
     return stream.cuda_stream or None
 
 
+# The C ABI takes bare pointers and cannot see sizes, so a tensor that is too small, on the host,
+# strided or of the wrong dtype would make a kernel read or write out of bounds.  These checks are
+# the only place where that can be caught; they raise ValueError before anything is launched.
+_ELEM_DTYPES = (torch.float32, torch.float16, torch.bfloat16)
+
+
+class _Args:
+    """Checks the tensors of one call: type, dtype, layout and size as each is named, and that
+    all of them live on the device once every size has passed (`on_device`)."""
+
+    def __init__(self, plan=None):
+        self.plan = plan
+        self.seen = []
+
+    def tensor(self, name: str, t, dtype, numel: int, exact: bool = False) -> None:
+        if not isinstance(t, torch.Tensor):
+            raise ValueError(f"{name}: expected a torch.Tensor, got {type(t).__name__}")
+        if not t.is_contiguous():
+            raise ValueError(f"{name}: must be contiguous")
+        if isinstance(dtype, tuple):
+            if t.dtype not in dtype:
+                raise ValueError(f"{name}: dtype {t.dtype} not in {dtype}")
+        elif t.dtype != dtype:
+            raise ValueError(f"{name}: dtype {t.dtype}, expected {dtype}")
+        if (t.numel() != numel) if exact else (t.numel() < numel):
+            raise ValueError(f"{name}: {t.numel()} elements, expected {'' if exact else 'at least '}{numel}")
+        self.seen.append((name, t))
+
+    def activation(self, name: str, t) -> None:
+        self.tensor(name, t, _ELEM_DTYPES, self.plan.num_elements, exact=True)
+
+    def packed(self, words, mn, scale, prefix: str = "") -> None:
+        self.tensor(prefix + "words", words, torch.int32, self.plan.packed_words)
+        self.tensor(prefix + "min", mn, torch.float32, self.plan.num_groups)
+        self.tensor(prefix + "scale", scale, torch.float32, self.plan.num_groups)
+
+    def bits(self, bits) -> None:
+        if bits is not None:
+            self.tensor("bits", bits, torch.uint8, self.plan.num_groups)
+
+    def on_device(self) -> None:
+        for name, t in self.seen:
+            if not t.is_cuda:
+                raise ValueError(f"{name}: must be a device (cuda) tensor")
+
+
 class Plan:
     """Owns a daf_plan_t*.  `bits` (a device uint8 tensor for per-group widths) is kept alive."""
 
     def __init__(self, handle: int, bits_keepalive=None):
         self._h = handle
         self._keep = bits_keepalive
+        # the plan's sizes never change: read them once, so that the argument checks of every
+        # call cost no foreign-function calls
+        L = load_library()
+        self.num_elements = int(L.daf_plan_num_elements(handle))
+        self.num_groups = int(L.daf_plan_num_groups(handle))
+        self.packed_words = int(L.daf_plan_packed_words(handle))
+        self.group_size = int(L.daf_plan_group_size(handle))
+        self.uniform_bits = int(L.daf_plan_uniform_bits(handle))
 
     @property
     def handle(self) -> int:
         if not self._h:
             raise ValueError("plan already destroyed")
         return self._h
-
-    num_elements = property(lambda s: int(load_library().daf_plan_num_elements(s.handle)))
-    num_groups = property(lambda s: int(load_library().daf_plan_num_groups(s.handle)))
-    packed_words = property(lambda s: int(load_library().daf_plan_packed_words(s.handle)))
-    group_size = property(lambda s: int(load_library().daf_plan_group_size(s.handle)))
-    uniform_bits = property(lambda s: int(load_library().daf_plan_uniform_bits(s.handle)))
 
     ROUTES = ("tile", "units", "long", "two_pass", "group")
 
@@ -173,6 +221,10 @@ def daf_plan(shape: Sequence[int], group_size: int, bits, stream=None) -> Plan:
 
 def daf_quantize_pack(plan: Plan, x: torch.Tensor, seed: int, out_words: torch.Tensor, out_min: torch.Tensor,
                       out_scale: torch.Tensor, stream=None) -> None:
+    a = _Args(plan)
+    a.activation("x", x)
+    a.packed(out_words, out_min, out_scale, "out_")
+    a.on_device()
     rc = load_library().daf_quantize_pack(plan.handle, x.data_ptr(), _DTYPE_ID[x.dtype], seed,
                                           out_words.data_ptr(), out_min.data_ptr(), out_scale.data_ptr(),
                                           _stream_handle(stream))
@@ -182,6 +234,11 @@ def daf_quantize_pack(plan: Plan, x: torch.Tensor, seed: int, out_words: torch.T
 
 def daf_unpack_dequantize(plan: Plan, words: torch.Tensor, mn: torch.Tensor, scale: torch.Tensor,
                           out_x: torch.Tensor, bits: Optional[torch.Tensor] = None, stream=None) -> None:
+    a = _Args(plan)
+    a.packed(words, mn, scale)
+    a.bits(bits)
+    a.activation("out_x", out_x)
+    a.on_device()
     rc = load_library().daf_unpack_dequantize(plan.handle, words.data_ptr(), mn.data_ptr(), scale.data_ptr(),
                                               bits.data_ptr() if bits is not None else None,
                                               out_x.data_ptr(), _DTYPE_ID[out_x.dtype], _stream_handle(stream))
@@ -203,9 +260,16 @@ def quantize_items(items):
     """Marshals [(plan, x, seed, out_words, out_min, out_scale), ...] once; the result can be passed to
     daf_quantize_pack_batch any number of times while the tensors stay alive."""
     arr = (_QuantizeItem * len(items))()
-    for a, (plan, x, seed, words, mn, sc) in zip(arr, items):
-        a.plan, a.x, a.seed = plan.handle, x.data_ptr(), seed
-        a.out_words, a.out_min, a.out_scale = words.data_ptr(), mn.data_ptr(), sc.data_ptr()
+    chk = _Args()
+    for it, (plan, x, seed, words, mn, sc) in zip(arr, items):
+        chk.plan = plan
+        chk.activation("x", x)
+        chk.packed(words, mn, sc, "out_")
+        if x.dtype != items[0][1].dtype:
+            raise ValueError("all tensors of a list call must have one dtype")
+        it.plan, it.x, it.seed = plan.handle, x.data_ptr(), seed
+        it.out_words, it.out_min, it.out_scale = words.data_ptr(), mn.data_ptr(), sc.data_ptr()
+    chk.on_device()
     arr.dtype_id = _DTYPE_ID[items[0][1].dtype]
     return arr
 
@@ -213,10 +277,18 @@ def quantize_items(items):
 def dequantize_items(items):
     """Marshals [(plan, words, min, scale, out_x, bits or None), ...] for daf_unpack_dequantize_batch."""
     arr = (_DequantizeItem * len(items))()
-    for a, (plan, words, mn, sc, out_x, bits) in zip(arr, items):
-        a.plan, a.words, a.min, a.scale = plan.handle, words.data_ptr(), mn.data_ptr(), sc.data_ptr()
-        a.bits = bits.data_ptr() if bits is not None else None
-        a.out_x = out_x.data_ptr()
+    chk = _Args()
+    for it, (plan, words, mn, sc, out_x, bits) in zip(arr, items):
+        chk.plan = plan
+        chk.packed(words, mn, sc)
+        chk.bits(bits)
+        chk.activation("out_x", out_x)
+        if out_x.dtype != items[0][4].dtype:
+            raise ValueError("all tensors of a list call must have one dtype")
+        it.plan, it.words, it.min, it.scale = plan.handle, words.data_ptr(), mn.data_ptr(), sc.data_ptr()
+        it.bits = bits.data_ptr() if bits is not None else None
+        it.out_x = out_x.data_ptr()
+    chk.on_device()
     arr.dtype_id = _DTYPE_ID[items[0][4].dtype]
     return arr
 
@@ -242,8 +314,14 @@ def daf_unpack_dequantize_batch(items, stream=None) -> None:
 def daf_unpack_relu_backward(plan: Plan, words: torch.Tensor, mn: torch.Tensor, scale: torch.Tensor,
                              grad_y: torch.Tensor, out_grad_z: torch.Tensor, bits: Optional[torch.Tensor] = None,
                              stream=None) -> None:
-    if out_grad_z.dtype != grad_y.dtype or out_grad_z.numel() != grad_y.numel():
-        raise ValueError("out_grad_z must have the dtype and the number of elements of grad_y")
+    a = _Args(plan)
+    a.packed(words, mn, scale)
+    a.bits(bits)
+    a.activation("grad_y", grad_y)
+    a.activation("out_grad_z", out_grad_z)
+    if out_grad_z.dtype != grad_y.dtype:
+        raise ValueError("out_grad_z must have the dtype of grad_y")
+    a.on_device()
     rc = load_library().daf_unpack_relu_backward(plan.handle, words.data_ptr(), mn.data_ptr(), scale.data_ptr(),
                                                  bits.data_ptr() if bits is not None else None, grad_y.data_ptr(),
                                                  out_grad_z.data_ptr(), _DTYPE_ID[grad_y.dtype],
@@ -261,9 +339,24 @@ def daf_unpack_matmul_grad_weight(plan: Plan, words: torch.Tensor, mn: torch.Ten
                                   workspace: Optional[torch.Tensor] = None, bits: Optional[torch.Tensor] = None,
                                   stream=None) -> None:
     """grad_y is [M, N]; out_grad_w is float32 [N, K]; the plan's tensor is read as [M, K]."""
+    a = _Args(plan)
+    a.packed(words, mn, scale)
+    a.bits(bits)
+    if out_grad_w.dim() != 2 or grad_y.dim() != 2:
+        raise ValueError("grad_y must be [M, N] and out_grad_w [N, K]")
+    if plan.num_elements % out_grad_w.shape[1] != 0:
+        raise ValueError("K = out_grad_w.shape[1] must divide the plan's element count")
+    a.tensor("grad_y", grad_y, _ELEM_DTYPES, (plan.num_elements // out_grad_w.shape[1]) * out_grad_w.shape[0], exact=True)
+    a.tensor("out_grad_w", out_grad_w, torch.float32, out_grad_w.numel())
+    need = daf_unpack_matmul_workspace_bytes(plan, out_grad_w.shape[0], out_grad_w.shape[1])
+    if need > 0:
+        if workspace is None:
+            raise ValueError(f"workspace of {need} bytes required")
+        a.tensor("workspace", workspace, workspace.dtype, -(-need // workspace.element_size()))
     N, K = out_grad_w.shape
-    if out_grad_w.dtype != torch.float32 or grad_y.shape[-1] != N:
+    if grad_y.shape[-1] != N:
         raise ValueError("out_grad_w must be float32 [N, K] with N = grad_y.shape[-1]")
+    a.on_device()
     rc = load_library().daf_unpack_matmul_grad_weight(
         plan.handle, words.data_ptr(), mn.data_ptr(), scale.data_ptr(), bits.data_ptr() if bits is not None else None,
         grad_y.data_ptr(), N, K, _DTYPE_ID[grad_y.dtype], out_grad_w.data_ptr(),
@@ -286,6 +379,11 @@ def daf_minmax_workspace(device="cuda:0", stream=None) -> torch.Tensor:
 
 
 def daf_minmax(x: torch.Tensor, method: int, workspace: torch.Tensor, out_minmax: torch.Tensor, stream=None) -> None:
+    a = _Args()
+    a.tensor("x", x, _ELEM_DTYPES, 1)
+    a.tensor("workspace", workspace, torch.uint8, int(load_library().daf_minmax_workspace_bytes()))
+    a.tensor("out_minmax", out_minmax, torch.float32, 2)
+    a.on_device()
     rc = load_library().daf_minmax(x.data_ptr(), _DTYPE_ID[x.dtype], x.numel(), method, workspace.data_ptr(),
                                    out_minmax.data_ptr(), _stream_handle(stream))
     if rc != 0:
@@ -293,6 +391,11 @@ def daf_minmax(x: torch.Tensor, method: int, workspace: torch.Tensor, out_minmax
 
 
 def daf_group_minmax(plan: Plan, x: torch.Tensor, out_min: torch.Tensor, out_max: torch.Tensor, stream=None) -> None:
+    a = _Args(plan)
+    a.activation("x", x)
+    a.tensor("out_min", out_min, torch.float32, plan.num_groups)
+    a.tensor("out_max", out_max, torch.float32, plan.num_groups)
+    a.on_device()
     rc = load_library().daf_group_minmax(plan.handle, x.data_ptr(), _DTYPE_ID[x.dtype], out_min.data_ptr(),
                                          out_max.data_ptr(), _stream_handle(stream))
     if rc != 0:
@@ -306,6 +409,13 @@ def daf_select_bits_workspace(num_groups: int, device="cuda:0") -> torch.Tensor:
 
 def daf_select_bits(group_min: torch.Tensor, group_max: torch.Tensor, classes: Sequence[int], out_bits: torch.Tensor,
                     workspace: torch.Tensor, stream=None) -> None:
+    G = group_min.numel() if isinstance(group_min, torch.Tensor) else 0
+    a = _Args()
+    a.tensor("group_min", group_min, torch.float32, max(G, 1))
+    a.tensor("group_max", group_max, torch.float32, G, exact=True)
+    a.tensor("out_bits", out_bits, torch.uint8, G)
+    a.tensor("workspace", workspace, torch.uint8, int(load_library().daf_select_bits_workspace_bytes(G)))
+    a.on_device()
     cl = (ctypes.c_uint8 * len(classes))(*[int(c) for c in classes])
     rc = load_library().daf_select_bits(group_min.data_ptr(), group_max.data_ptr(), group_min.numel(),
                                         ctypes.cast(cl, ctypes.c_void_p), len(classes), out_bits.data_ptr(),
@@ -316,8 +426,13 @@ def daf_select_bits(group_min: torch.Tensor, group_max: torch.Tensor, classes: S
 
 def daf_relu_quantize_pack(plan: Plan, z: torch.Tensor, seed: int, out_y: torch.Tensor, out_words: torch.Tensor,
                            out_min: torch.Tensor, out_scale: torch.Tensor, stream=None) -> None:
-    if out_y.dtype != z.dtype or out_y.numel() != z.numel():
-        raise ValueError("out_y must have the dtype and the number of elements of z")
+    a = _Args(plan)
+    a.activation("z", z)
+    a.activation("out_y", out_y)
+    a.packed(out_words, out_min, out_scale, "out_")
+    if out_y.dtype != z.dtype:
+        raise ValueError("out_y must have the dtype of z")
+    a.on_device()
     rc = load_library().daf_relu_quantize_pack(plan.handle, z.data_ptr(), _DTYPE_ID[z.dtype], seed, out_y.data_ptr(),
                                                out_words.data_ptr(), out_min.data_ptr(), out_scale.data_ptr(),
                                                _stream_handle(stream))
@@ -327,6 +442,11 @@ def daf_relu_quantize_pack(plan: Plan, z: torch.Tensor, seed: int, out_y: torch.
 
 def daf_quantize_pack_metrics(plan: Plan, x: torch.Tensor, seed: int, out_words: torch.Tensor, out_min: torch.Tensor,
                               out_scale: torch.Tensor, out_metrics: torch.Tensor, stream=None) -> None:
+    a = _Args(plan)
+    a.activation("x", x)
+    a.packed(out_words, out_min, out_scale, "out_")
+    a.tensor("out_metrics", out_metrics, torch.float32, 3 * plan.num_groups)
+    a.on_device()
     rc = load_library().daf_quantize_pack_metrics(plan.handle, x.data_ptr(), _DTYPE_ID[x.dtype], seed,
                                                   out_words.data_ptr(), out_min.data_ptr(), out_scale.data_ptr(),
                                                   out_metrics.data_ptr(), _stream_handle(stream))

@@ -79,6 +79,57 @@ def assert_full_parity(w: Workload, res: HipResult):
         assert d is None, f"dequantized element {d} not bit-identical: hip {gx[d]!r} oracle {oxh[d]!r}"
 
 
+def oracle_whole(w: Workload, threads: int = 16):
+    """The oracle's words, min, scale and dequantized values for a whole full-size tensor.  The
+    oracle's own range functions are called on disjoint group ranges from several host threads
+    (groups are independent once the offsets are known), so that a 0.2-2.4 GB tensor takes seconds."""
+    import concurrent.futures as cf
+    xb = to_numpy_bits(w.x)
+    n, gs = w.numel, w.group_size
+    off, total = orc.plan(n, gs, w.bits)
+    G = off.size
+    ow = np.empty(total, dtype=np.uint32)
+    omn = np.empty(G, dtype=np.float32)
+    osc = np.empty(G, dtype=np.float32)
+    oxh = np.empty(n, dtype=xb.dtype)
+    cuts = [G * i // threads for i in range(threads + 1)]
+
+    def one(i):
+        g0, g1 = cuts[i], cuts[i + 1]
+        if g1 > g0:
+            orc.quantize_pack_range(xb, w.dtype, gs, w.bits, off, w.seed, g0, g1, ow, omn, osc)
+            orc.unpack_dequantize_range(ow, omn, osc, w.bits, off, n, gs, g0, g1, oxh, w.dtype)
+
+    with cf.ThreadPoolExecutor(max_workers=threads) as ex:
+        list(ex.map(one, range(threads)))
+    return off, total, ow, omn, osc, oxh
+
+
+def assert_whole_parity(w: Workload, res: HipResult, threads: int = 16):
+    """Full-size workloads: every packed word, every min, every scale and every dequantized
+    element against the oracle, bit for bit; the first difference is reported."""
+    off, total, ow, omn, osc, oxh = oracle_whole(w, threads)
+    assert res.plan.packed_words == total and res.plan.num_groups == off.size
+    assert np.array_equal(res.plan.offsets().numpy().view(np.uint32), off)
+    d = first_diff(u32(res.mn), omn.view(np.uint32))
+    assert d is None, f"min differs first at group {d}: hip {res.mn[d].item()!r} oracle {omn[d]!r}"
+    d = first_diff(u32(res.scale), osc.view(np.uint32))
+    assert d is None, f"scale differs first at group {d}: hip {res.scale[d].item()!r} oracle {osc[d]!r}"
+    gw = u32(res.words)
+    d = first_diff(gw, ow)
+    if d is not None:
+        g = int(np.searchsorted(off, d, side="right") - 1)
+        raise AssertionError(f"packed word {d} differs (group {g}, bits "
+                             f"{int(w.bits[0] if w.bits.size == 1 else w.bits[g])}): hip {gw[d]:08x} oracle {ow[d]:08x}")
+    del gw
+    if res.xhat is not None:
+        gx = to_numpy_bits(res.xhat.cpu())
+        d = first_diff(gx.view(np.uint32 if w.dtype == orc.F32 else np.uint16),
+                       oxh.view(np.uint32 if w.dtype == orc.F32 else np.uint16))
+        assert d is None, (f"dequantized element {d} (group {d // w.group_size}) not bit-identical: "
+                           f"hip {gx[d]!r} oracle {oxh[d]!r}")
+
+
 def assert_sampled_parity(w: Workload, res: HipResult, n_samples: int = 1500, seed: int = 0):
     """Full-size workloads: compare sampled groups (plus the first and last ones) with the
     oracle computed group by group, and check global properties on the GPU."""

@@ -90,22 +90,22 @@ def test_degenerate_groups(H, dtype):
         H.assert_full_parity(w, H.run_hip(w))
 
 
-# full-size configurations, in the launch configuration bench.py times: sampled groups against
-# the oracle (which computes them one by one), plus properties evaluated over every element
+# full-size configurations: every word, min, scale and dequantized element against the oracle
 @pytest.mark.timeout(400)
 @pytest.mark.parametrize("cfg", [2, 3, 5])
-def test_full_size_configs_sampled(H, cfg):
+def test_full_size_configs_whole_tensor(H, cfg):
     (w,) = make_config(cfg)
     print("case", w.name, tuple(w.x.shape), flush=True)
     res = H.run_hip(w)
-    print("ran; checking", flush=True)
-    H.assert_sampled_parity(w, res, n_samples=1200, seed=cfg)
+    print("ran; oracle on the whole tensor", flush=True)
+    H.assert_whole_parity(w, res)
 
 
-@pytest.mark.timeout(400)
-def test_full_size_resnet18_step_sampled(H):
-    """All 17 saved activations of the batch-256 step: quantize in forward order, dequantize in
-    reverse order with every packed result alive, then sampled comparison per tensor."""
+@pytest.mark.timeout(600)
+def test_full_size_resnet18_step_whole_tensors(H):
+    """All 17 saved activations of the batch-256 step through the list entry points, as bench.py
+    times them: quantize in forward order in one call, dequantize in reverse order in one call
+    with every packed result alive, then every tensor compared in full with the oracle."""
     import paper_2507_07149_amd as daf
     ws = make_config(4)
     assert len(ws) == 17 and sum(w.numel for w in ws) == 590_872_576
@@ -114,20 +114,20 @@ def test_full_size_resnet18_step_sampled(H):
     for w in ws:
         x = w.x.reshape(-1).to(dev)
         plan = daf.daf_plan(tuple(w.x.shape), w.group_size, int(w.bits[0]))
-        words = torch.empty(plan.packed_words, dtype=torch.int32, device=dev)
-        mn = torch.empty(plan.num_groups, device=dev)
-        sc = torch.empty(plan.num_groups, device=dev)
-        daf.daf_quantize_pack(plan, x, w.seed, words, mn, sc)
-        state.append((plan, x, words, mn, sc))
+        words = torch.full((plan.packed_words,), -1, dtype=torch.int32, device=dev)
+        mn = torch.full((plan.num_groups,), float("nan"), device=dev)
+        sc = torch.full((plan.num_groups,), float("nan"), device=dev)
+        xh = torch.full_like(x, float("nan"))
+        state.append((plan, x, words, mn, sc, xh))
+    daf.daf_quantize_pack_batch([(p, x, w.seed, words, mn, sc) for w, (p, x, words, mn, sc, xh) in zip(ws, state)])
+    daf.daf_unpack_dequantize_batch([(p, words, mn, sc, xh, None) for (p, x, words, mn, sc, xh) in reversed(state)])
+    torch.cuda.synchronize()
     for t in reversed(range(17)):
-        plan, x, words, mn, sc = state[t]
-        xh = torch.empty_like(x)
-        daf.daf_unpack_dequantize(plan, words, mn, sc, xh)
-        torch.cuda.synchronize()
-        print("tensor", t, flush=True)
-        H.assert_sampled_parity(ws[t], H.HipResult(plan, words, mn, sc, xh, None), n_samples=150, seed=t)
+        plan, x, words, mn, sc, xh = state[t]
+        print("tensor", t, tuple(ws[t].x.shape), flush=True)
+        H.assert_whole_parity(ws[t], H.HipResult(plan, words, mn, sc, xh, None))
         state[t] = None
-        del x, xh
+        del x, xh, words
 
 
 @pytest.mark.timeout(400)
