@@ -210,6 +210,9 @@ def test_abi_errors_on_device(H):
         daf.daf_quantize_pack(plan, x[1:1025], 0, words, mn, sc)
     assert e.value.status == -1
     with pytest.raises(daf.DafError):                           # bits given for a uniform plan
+        daf.daf_unpack_dequantize(plan, words, mn, sc, x[:1024],
+                                  bits=torch.full((plan.num_groups,), 2, dtype=torch.uint8, device=dev))
+    with pytest.raises(ValueError):                             # too few widths: caught by the binding
         daf.daf_unpack_dequantize(plan, words, mn, sc, x[:1024], bits=bad_bits)
     daf.daf_quantize_pack(plan, x[:1024], 0, words, mn, sc)     # and the good call still works
     torch.cuda.synchronize()
