@@ -49,7 +49,8 @@ typedef enum {
   DAF_EINVAL = -1,        /* null pointer, bad shape, bad bits value, misaligned pointer, wrong count */
   DAF_EUNSUPPORTED = -2,  /* group_size not a multiple of 32, unknown dtype, packed size >= 2^32 words */
   DAF_ENOMEM = -3,        /* host or device allocation for the plan failed */
-  DAF_EDEVICE = -4        /* a HIP call or kernel launch failed */
+  DAF_EDEVICE = -4,       /* a HIP call or kernel launch failed */
+  DAF_ETOOLARGE = -5      /* daf_quantize_pack_static: the tensor needs more scratch than the static buffer holds */
 } daf_status_t;
 
 /* Number of random bits spent per element by stochastic rounding (8). */
@@ -155,10 +156,41 @@ void daf_plan_destroy(daf_plan_t* plan);
  * groups of 8192 ... 65536 elements (whole tiles), and one group for the whole tensor need the group's
  * statistics before any element can be quantized and read x twice.
  *
+ * Concurrency.  Calls on different plans, or on a plan whose daf_plan_quantize_route is not
+ * DAF_ROUTE_TWO_PASS, may overlap freely (different streams, several host threads): the plan is
+ * only read.  A DAF_ROUTE_TWO_PASS plan owns scratch memory (the per-tile and per-group
+ * statistics between its passes) that every call on it writes: calls on ONE such plan, from this
+ * entry point, daf_quantize_pack_batch or daf_group_minmax, must not overlap in time -- keep them
+ * on one stream, or create one plan per stream (plans are cheap: 8 bytes per 4096 elements).
+ *
  * Errors: DAF_EINVAL (null or misaligned pointer), DAF_EUNSUPPORTED (dtype), DAF_EDEVICE.
  */
 int daf_quantize_pack(const daf_plan_t* plan, const void* x, daf_dtype_t dtype, uint64_t seed,
                       uint32_t* out_words, float* out_min, float* out_scale, void* stream);
+
+/* daf_quantize_pack_static -- daf_quantize_pack for callers that cannot allocate device memory
+ * or hold allocations made for them: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same results, bit for bit.  The difference:
+ * where daf_quantize_pack keeps the per-tile and per-group (min, max) pairs of its two-pass route
+ * (groups longer than 65536 elements, fewer than 256 groups of 8192 ... 65536 elements, one group
+ * for the whole tensor) in memory that daf_plan allocated for the plan, this call keeps them in
+ * a buffer of DAF_STATIC_SCRATCH_BYTES that is part of the library's device image (one copy per
+ * GPU, held until the process ends).  The call allocates and frees nothing and does not
+ * synchronize; the first call on a device looks the buffer's address up once.
+ *
+ *   limit   the two-pass route needs 8 * (ceil(N / 4096) + G) bytes: at most
+ *           DAF_STATIC_SCRATCH_BYTES, i.e. about 1.07e9 elements with one group per tensor;
+ *           beyond that the call returns DAF_ETOOLARGE and launches nothing.  Plans on any other
+ *           route use no scratch memory and have no limit.
+ *   races   all calls on one GPU share the one buffer: two such calls for two-pass plans must not
+ *           overlap in time (different streams, or graphs that replay concurrently).  The buffer
+ *           keeps the previous call's contents; every entry a call reads it has written first.
+ *
+ * Errors: as daf_quantize_pack, plus DAF_ETOOLARGE.
+ */
+#define DAF_STATIC_SCRATCH_BYTES (2 << 20)
+int daf_quantize_pack_static(const daf_plan_t* plan, const void* x, daf_dtype_t dtype, uint64_t seed,
+                             uint32_t* out_words, float* out_min, float* out_scale, void* stream);
 
 /* daf_unpack_dequantize -- backward-pass side: extract every code (Algorithm 2's rule,
  * for the group's width) and restore xhat = fma(code, scale, min) in binary32, then round

@@ -55,6 +55,8 @@ def load_library():
     L.daf_plan_destroy.restype = None
     L.daf_quantize_pack.argtypes = [vp, vp, c.c_int, u64, vp, vp, vp, vp]
     L.daf_quantize_pack.restype = c.c_int
+    L.daf_quantize_pack_static.argtypes = [vp, vp, c.c_int, u64, vp, vp, vp, vp]
+    L.daf_quantize_pack_static.restype = c.c_int
     L.daf_unpack_dequantize.argtypes = [vp, vp, vp, vp, vp, vp, c.c_int, vp]
     L.daf_unpack_dequantize.restype = c.c_int
     L.daf_quantize_pack_metrics.argtypes = [vp, vp, c.c_int, u64, vp, vp, vp, vp, vp]
@@ -230,6 +232,23 @@ def daf_quantize_pack(plan: Plan, x: torch.Tensor, seed: int, out_words: torch.T
                                           _stream_handle(stream))
     if rc != 0:
         raise DafError(rc, "daf_quantize_pack")
+
+
+STATIC_SCRATCH_BYTES = 2 << 20      # DAF_STATIC_SCRATCH_BYTES of daf.h
+
+
+def daf_quantize_pack_static(plan: Plan, x: torch.Tensor, seed: int, out_words: torch.Tensor, out_min: torch.Tensor,
+                             out_scale: torch.Tensor, stream=None) -> None:
+    """daf_quantize_pack that allocates nothing: the two-pass route's scratch is the library's static buffer."""
+    a = _Args(plan)
+    a.activation("x", x)
+    a.packed(out_words, out_min, out_scale, "out_")
+    a.on_device()
+    rc = load_library().daf_quantize_pack_static(plan.handle, x.data_ptr(), _DTYPE_ID[x.dtype], seed,
+                                                 out_words.data_ptr(), out_min.data_ptr(), out_scale.data_ptr(),
+                                                 _stream_handle(stream))
+    if rc != 0:
+        raise DafError(rc, "daf_quantize_pack_static")
 
 
 def daf_unpack_dequantize(plan: Plan, words: torch.Tensor, mn: torch.Tensor, scale: torch.Tensor,

@@ -1,5 +1,6 @@
 // C ABI of libdaf: argument checks, plan construction, dispatch to the kernel launchers.
 // Every check that does not need the GPU comes before the first HIP call.
+#include <mutex>
 #include <new>
 
 #include "daf_internal.h"
@@ -28,6 +29,38 @@ struct DeviceGuard {      // make the plan's device current for the duration of 
 
 }  // namespace
 
+// Scratch memory of daf_quantize_pack_static: the per-tile and per-group (min, max) pairs of the
+// two-pass route, for callers that cannot allocate.  One copy per GPU, held until the process
+// ends.  In host code `scratch` is only a handle for hipGetSymbolAddress; the device address
+// it yields (one per device) is what the kernels receive.
+static __device__ __align__(256) unsigned char scratch[DAF_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};      // device address of `scratch` on each device, once looked up
+
+// The address of `scratch` on the current device (looked up on the first call there).
+hipError_t static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (ptr == nullptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+
+}  // namespace
+
 bool daf_plan_needs_big_scratch(int64_t n, int32_t group_size, int64_t num_groups, int64_t* bytes) {
   constexpr int64_t kTile = 4096;
   if (group_size <= kTile) return false;
@@ -48,6 +81,7 @@ const char* daf_status_string(int status) {
     case DAF_EUNSUPPORTED: return "DAF_EUNSUPPORTED: unsupported group size, dtype or packed size";
     case DAF_ENOMEM: return "DAF_ENOMEM: allocation failed";
     case DAF_EDEVICE: return "DAF_EDEVICE: HIP call or kernel launch failed";
+    case DAF_ETOOLARGE: return "DAF_ETOOLARGE: the tensor needs more scratch memory than the library's static buffer holds";
     default: return "unknown daf status";
   }
 }
@@ -190,7 +224,25 @@ int daf_quantize_pack(const daf_plan_t* plan, const void* x, daf_dtype_t dtype, 
   if (!aligned(x, 16) || !aligned(out_words, 4) || !aligned(out_min, 4) || !aligned(out_scale, 4)) return DAF_EINVAL;
   if (dtype != DAF_F32 && dtype != DAF_F16 && dtype != DAF_BF16) return DAF_EUNSUPPORTED;
   const hipError_t e = daf_launch_quantize_pack(plan, x, (int)dtype, seed, out_words, out_min, out_scale, nullptr,
-                                                nullptr, static_cast<hipStream_t>(stream));
+                                                nullptr, nullptr, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? DAF_OK : DAF_EDEVICE;
+}
+
+int daf_quantize_pack_static(const daf_plan_t* plan, const void* x, daf_dtype_t dtype, uint64_t seed,
+                             uint32_t* out_words, float* out_min, float* out_scale, void* stream) {
+  if (plan == nullptr || x == nullptr || out_words == nullptr || out_min == nullptr || out_scale == nullptr)
+    return DAF_EINVAL;
+  if (!aligned(x, 16) || !aligned(out_words, 4) || !aligned(out_min, 4) || !aligned(out_scale, 4)) return DAF_EINVAL;
+  if (dtype != DAF_F32 && dtype != DAF_F16 && dtype != DAF_BF16) return DAF_EUNSUPPORTED;
+  void* ptr = nullptr;
+  if (daf_quantize_route(plan, (int)dtype) == DAF_ROUTE_TWO_PASS) {     // the only route with scratch memory
+    int64_t bytes = 0;
+    (void)daf_plan_needs_big_scratch(plan->n, plan->group_size, plan->num_groups, &bytes);
+    if (bytes > (int64_t)DAF_STATIC_SCRATCH_BYTES) return DAF_ETOOLARGE;
+    if (static_scratch(&ptr) != hipSuccess) return DAF_EDEVICE;
+  }
+  const hipError_t e = daf_launch_quantize_pack(plan, x, (int)dtype, seed, out_words, out_min, out_scale, nullptr,
+                                                nullptr, ptr, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? DAF_OK : DAF_EDEVICE;
 }
 
@@ -241,7 +293,7 @@ int daf_relu_quantize_pack(const daf_plan_t* plan, const void* z, daf_dtype_t dt
     if (a < b + bytes && b < a + bytes) return DAF_EINVAL;
   }
   const hipError_t e = daf_launch_quantize_pack(plan, z, (int)dtype, seed, out_words, out_min, out_scale, nullptr,
-                                                out_y, static_cast<hipStream_t>(stream));
+                                                out_y, nullptr, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? DAF_OK : DAF_EDEVICE;
 }
 
@@ -257,7 +309,7 @@ int daf_quantize_pack_metrics(const daf_plan_t* plan, const void* x, daf_dtype_t
   if (dtype != DAF_F32 && dtype != DAF_F16 && dtype != DAF_BF16) return DAF_EUNSUPPORTED;
   if (!daf_quantize_reads_once(plan)) return DAF_EUNSUPPORTED;     // the group's statistics need a pass of their own
   const hipError_t e = daf_launch_quantize_pack(plan, x, (int)dtype, seed, out_words, out_min, out_scale,
-                                                out_metrics, nullptr, static_cast<hipStream_t>(stream));
+                                                out_metrics, nullptr, nullptr, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? DAF_OK : DAF_EDEVICE;
 }
 

@@ -40,9 +40,11 @@ int64_t daf_plan_scan_blocks(int64_t num_groups);
 // out_metrics: null, or 3 floats per group (sum (x-xhat)^2, sum x^2, rounding variance); not with groups longer than a tile.
 // out_relu_y: null, or the buffer that receives max(x, +0), which is then what gets quantized (may be x
 // itself); not together with out_metrics, not with groups longer than a tile.
+// big_scratch: null = the plan's own scratch; else device memory of at least the size
+// daf_plan_needs_big_scratch reports, used by the two-pass route in its place.
 hipError_t daf_launch_quantize_pack(const daf_plan_t* plan, const void* x, int dtype, uint64_t seed,
                                     uint32_t* out_words, float* out_min, float* out_scale, float* out_metrics,
-                                    void* out_relu_y, hipStream_t stream);
+                                    void* out_relu_y, void* big_scratch, hipStream_t stream);
 
 // Weight gradient straight from the packed activation (unpack_matmul.hip).  The plan's tensor is
 // read as [n / K, K]; out is [N, K] binary32; workspace holds daf_unpack_matmul_workspace_size bytes.

@@ -5,7 +5,7 @@
   hipError_t daf_launch_quantize_pack_batch_dt##dt(const daf_quantize_item_t*, int32_t, hipStream_t);               \
   hipError_t daf_launch_group_minmax_dt##dt(const daf_plan_t*, const void*, float*, float*, hipStream_t);            \
   hipError_t daf_launch_quantize_pack_dt##dt(const daf_plan_t*, const void*, uint64_t, uint32_t*, float*, float*,    \
-                                             float*, void*, hipStream_t);
+                                             float*, void*, void*, hipStream_t);
 DAF_DECLARE(0)
 DAF_DECLARE(1)
 DAF_DECLARE(2)
@@ -45,11 +45,11 @@ hipError_t daf_launch_group_minmax(const daf_plan_t* plan, const void* x, int dt
 
 hipError_t daf_launch_quantize_pack(const daf_plan_t* plan, const void* x, int dtype, uint64_t seed,
                                     uint32_t* out_words, float* out_min, float* out_scale, float* out_metrics,
-                                    void* out_relu_y, hipStream_t stream) {
+                                    void* out_relu_y, void* big_scratch, hipStream_t stream) {
   switch (dtype) {
-    case 0: return daf_launch_quantize_pack_dt0(plan, x, seed, out_words, out_min, out_scale, out_metrics, out_relu_y, stream);
-    case 1: return daf_launch_quantize_pack_dt1(plan, x, seed, out_words, out_min, out_scale, out_metrics, out_relu_y, stream);
-    case 2: return daf_launch_quantize_pack_dt2(plan, x, seed, out_words, out_min, out_scale, out_metrics, out_relu_y, stream);
+    case 0: return daf_launch_quantize_pack_dt0(plan, x, seed, out_words, out_min, out_scale, out_metrics, out_relu_y, big_scratch, stream);
+    case 1: return daf_launch_quantize_pack_dt1(plan, x, seed, out_words, out_min, out_scale, out_metrics, out_relu_y, big_scratch, stream);
+    case 2: return daf_launch_quantize_pack_dt2(plan, x, seed, out_words, out_min, out_scale, out_metrics, out_relu_y, big_scratch, stream);
     default: return hipErrorInvalidValue;
   }
 }

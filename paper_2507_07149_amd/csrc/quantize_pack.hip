@@ -898,14 +898,14 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_tail_ext(
 
 template <int DT>
 hipError_t launch_big(const daf_plan_t* p, const void* x, uint32_t seed_lo, uint32_t seed_hi, uint32_t* out_words,
-                      float* out_min, float* out_scale, hipStream_t stream) {
+                      float* out_min, float* out_scale, void* scratch, hipStream_t stream) {
   constexpr int kMaxLog2 = (DT == kF32) ? 10 : 9;                // the shape whose tile is one group
   static_assert(TileShape<DT, kMaxLog2>::kElems == kBigTile && TileShape<DT, kMaxLog2>::kGroups == 1, "shape");
   const int64_t n_full_tiles = p->n / kBigTile;
   const bool tail = n_full_tiles * kBigTile < p->n;
   const int64_t n_partials = n_full_tiles + (tail ? 1 : 0);
   const int64_t tpg = (p->num_groups == 1) ? n_partials : p->group_size / kBigTile;
-  float2* partial = reinterpret_cast<float2*>(p->d_big_scratch);
+  float2* partial = reinterpret_cast<float2*>(scratch);        // every entry read below is written first
   float2* stat = partial + n_partials;
 
   const unsigned blocks1 = (unsigned)((n_partials + kWavesPerBlock - 1) / kWavesPerBlock);
@@ -1880,7 +1880,8 @@ int quantize_route(const daf_plan_t* p) {
 
 template <int DT, bool METRICS, bool RELU = false>
 hipError_t launch_dtype(const daf_plan_t* p, const void* x, uint64_t seed, uint32_t* out_words, float* out_min,
-                        float* out_scale, float* out_metrics, void* out_y, hipStream_t stream) {
+                        float* out_scale, float* out_metrics, void* out_y, hipStream_t stream,
+                        void* big_scratch = nullptr) {
   const uint32_t seed_lo = (uint32_t)seed, seed_hi = (uint32_t)(seed >> 32);
   constexpr int kEpl = ElemTraits<DT>::kPerLoad;
   const int64_t full_groups = p->n / p->group_size;
@@ -1893,7 +1894,8 @@ hipError_t launch_dtype(const daf_plan_t* p, const void* x, uint64_t seed, uint3
   }
   if (route == 3) {                     // statistics first (scratch set up by daf_plan)
     if (METRICS || RELU) return hipErrorNotSupported;
-    return launch_big<DT>(p, x, seed_lo, seed_hi, out_words, out_min, out_scale, stream);
+    return launch_big<DT>(p, x, seed_lo, seed_hi, out_words, out_min, out_scale,
+                          big_scratch ? big_scratch : p->d_big_scratch, stream);
   }
 
   // fast path: groups of 4 .. 1024 chunks (a power of two, at most one tile), whole tiles only
@@ -2188,10 +2190,12 @@ hipError_t DAF_DT_NAME(daf_launch_group_minmax, DAF_DT)(const daf_plan_t* plan, 
 
 hipError_t DAF_DT_NAME(daf_launch_quantize_pack, DAF_DT)(const daf_plan_t* plan, const void* x, uint64_t seed,
                                                          uint32_t* out_words, float* out_min, float* out_scale,
-                                                         float* out_metrics, void* out_relu_y, hipStream_t stream) {
+                                                         float* out_metrics, void* out_relu_y, void* big_scratch,
+                                                         hipStream_t stream) {
   if (out_metrics && out_relu_y) return hipErrorNotSupported;
   if (out_relu_y)
     return launch_dtype<DAF_DT, false, true>(plan, x, seed, out_words, out_min, out_scale, nullptr, out_relu_y, stream);
   return out_metrics ? launch_dtype<DAF_DT, true>(plan, x, seed, out_words, out_min, out_scale, out_metrics, nullptr, stream)
-                     : launch_dtype<DAF_DT, false>(plan, x, seed, out_words, out_min, out_scale, nullptr, nullptr, stream);
+                     : launch_dtype<DAF_DT, false>(plan, x, seed, out_words, out_min, out_scale, nullptr, nullptr, stream,
+                                                   big_scratch);
 }
