@@ -270,22 +270,25 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_group_batch(const Gr
 // Lane l of load u holds the 16-byte chunk u*64 + l of the tile.  A group spans
 // 2^LPG_LOG2 consecutive chunks: up to 64 neighbouring lanes of one load (LPG_LOG2 <= 6), or
 // the whole wave over 2, 4, 8 or 16 consecutive loads (LPG_LOG2 = 7..10).
-template <int DT, int LPG_LOG2>
+// DIV = 2: a tile of half the size (2048 elements of a 16-bit format): twice as many, shorter
+// waves, for tensors so small that whole-size tiles would leave the last round of waves half
+// empty.
+template <int DT, int LPG_LOG2, int DIV = 1>
 struct TileShape {
   static constexpr int kEpl = ElemTraits<DT>::kPerLoad;            // elements per lane per load
   static constexpr int kLaneLog2 = LPG_LOG2 < 6 ? LPG_LOG2 : 6;    // log2 lanes of a group in one load
   static constexpr int kLpg = 1 << kLaneLog2;                      // lanes per group (in one load)
   static constexpr int kGpl = kWave / kLpg;                        // group segments per load
   static constexpr int kLoadsPerGroup = 1 << (LPG_LOG2 - kLaneLog2);
-  static constexpr int kMaxLoads = 4096 / (kWave * kEpl);          // 16 (fp32) or 8 (16-bit)
+  static constexpr int kMaxLoads = 4096 / (kWave * kEpl) / DIV;    // 16 (fp32) or 8 (16-bit), over DIV
   static constexpr int kLoads = (kMaxLoads * kGpl <= kWave) ? kMaxLoads : kWave / kGpl;
   static constexpr int kSegments = kLoads * kGpl;                  // (load, lane run) pairs, <= 64
   static constexpr int kGroups = kSegments / kLoadsPerGroup;       // groups per tile
   static constexpr int kElems = kLoads * kWave * kEpl;             // 2048 or 4096
   static constexpr int kGroupSize = (1 << LPG_LOG2) * kEpl;
   static constexpr int kPhilox = kElems / kElemsPerPhilox / kWave; // Philox calls per lane
-  static constexpr bool kValid = kLoadsPerGroup <= kLoads;
-  static_assert(kSegments <= kWave && kPhilox >= 1, "tile shape");
+  static constexpr bool kValid = kLoadsPerGroup <= kLoads && kElems >= kElemsPerPhilox * kWave;
+  static_assert(kSegments <= kWave, "tile shape");
 };
 
 struct alignas(16) GroupInfo {   // what every lane of a group needs for the element map
@@ -295,9 +298,9 @@ struct alignas(16) GroupInfo {   // what every lane of a group needs for the ele
   uint32_t byte_off;             // byte offset of the group inside the tile's packed run
 };
 
-template <int DT, int LPG_LOG2>
+template <int DT, int LPG_LOG2, int DIV = 1>
 struct alignas(16) WaveLds {
-  using S = TileShape<DT, LPG_LOG2>;
+  using S = TileShape<DT, LPG_LOG2, DIV>;
   // First the random bytes of the tile (byte e serves tile element e); once every lane has
   // taken its bytes into registers the same memory stages the tile's packed words (at most
   // 8 bits per element, so the run always fits).
@@ -356,11 +359,11 @@ __device__ __forceinline__ void quantize_chunk(const float (&xf)[ElemTraits<DT>:
 
 // Widens the tile's chunks into xf and leaves one (min, max) pair per (load, lane run) segment
 // in stat[load * runs_per_load + run]; a group's segments are consecutive entries.
-template <int DT, int LPG_LOG2>
-__device__ __forceinline__ void tile_minmax(const uint4 (&raw)[TileShape<DT, LPG_LOG2>::kLoads],
-                                            float (&xf)[TileShape<DT, LPG_LOG2>::kLoads][ElemTraits<DT>::kPerLoad],
+template <int DT, int LPG_LOG2, int DIV = 1>
+__device__ __forceinline__ void tile_minmax(const uint4 (&raw)[TileShape<DT, LPG_LOG2, DIV>::kLoads],
+                                            float (&xf)[TileShape<DT, LPG_LOG2, DIV>::kLoads][ElemTraits<DT>::kPerLoad],
                                             float2* stat, int lane) {
-  using S = TileShape<DT, LPG_LOG2>;
+  using S = TileShape<DT, LPG_LOG2, DIV>;
   constexpr int kEpl = S::kEpl;
   static_assert(S::kLoads % 2 == 0, "loads are reduced in pairs");
   if constexpr (DT == kF32 && LPG_LOG2 >= 5) {
@@ -430,24 +433,24 @@ __device__ __forceinline__ void tile_minmax(const uint4 (&raw)[TileShape<DT, LPG
 // RELU = true: x holds z; every element becomes max(z, +0) right after the load, the result is
 // written to out_y in the same layout (out_y may be x itself: a lane only overwrites chunks it
 // has already loaded), and everything else sees y.
-template <int DT, int LPG_LOG2, int B, bool EXT = false, bool METRICS = false, bool RELU = false>
+template <int DT, int LPG_LOG2, int B, bool EXT = false, bool METRICS = false, bool RELU = false, int DIV = 1>
 __device__ __forceinline__ void quantize_pack_tile_body(
     typename std::conditional<RELU, const u32x4*, const u32x4* __restrict__>::type x, int64_t tile, int wave_in_block,
     const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, uint32_t seed_lo, uint32_t seed_hi,
     uint32_t* __restrict__ words, float* __restrict__ out_min, float* __restrict__ out_scale,
     const float2* __restrict__ ext_stat, int64_t tiles_per_group, float* __restrict__ out_metrics,
     u32x4* out_y) {
-  using S = TileShape<DT, LPG_LOG2>;
+  using S = TileShape<DT, LPG_LOG2, DIV>;
   static_assert(!EXT || S::kGroups == 1, "external statistics: the tile is part of one group");
   static_assert(!(EXT && METRICS), "metrics are not computed for groups longer than a tile");
   static_assert(!(RELU && (EXT || METRICS)), "the fused max(z, 0) exists for the plain tile kernel only");
   constexpr int kEpl = S::kEpl;
   constexpr bool kMixed = (B == 0);
   constexpr uint32_t kGroupWords32 = S::kGroupSize / 32;      // words per group and bit of width
-  __shared__ WaveLds<DT, LPG_LOG2> lds_all[kWavesPerBlock];
+  __shared__ WaveLds<DT, LPG_LOG2, DIV> lds_all[kWavesPerBlock];
 
   const int lane = threadIdx.x & (kWave - 1);
-  WaveLds<DT, LPG_LOG2>& lds = lds_all[wave_in_block];
+  WaveLds<DT, LPG_LOG2, DIV>& lds = lds_all[wave_in_block];
   const uint32_t lane_in_run = (uint32_t)(lane & (S::kLpg - 1));
   uint8_t* stage8 = reinterpret_cast<uint8_t*>(lds.stage);
 
@@ -501,7 +504,7 @@ __device__ __forceinline__ void quantize_pack_tile_body(
         for (int e = 0; e < kEpl; ++e) xf[u][e] = chunk_elem<DT>(raw[u], e);
       }
     } else {
-      tile_minmax<DT, LPG_LOG2>(raw, xf, lds.stat, lane);
+      tile_minmax<DT, LPG_LOG2, DIV>(raw, xf, lds.stat, lane);
     }
     wave_lds_sync();
 
@@ -653,7 +656,9 @@ __device__ __forceinline__ void quantize_pack_tile_body(
 
     // 6. the tile's words are one contiguous run in the packed buffer
     uint32_t* dst = words + tile_base;
-    for (uint32_t i = lane; i < tile_words; i += kWave) dst[i] = lds.stage[i];
+    // (streaming stores: the words are read back by the backward pass, long after they have left
+    // the caches; with ordinary stores the mixed-width kernels ran a tenth slower)
+    for (uint32_t i = lane; i < tile_words; i += kWave) __builtin_nontemporal_store(lds.stage[i], &dst[i]);
     if (METRICS && lane < S::kGroups) {
       const float sc = lds.gscale[lane];
       float* m = out_metrics + 3 * (g0 + lane);
@@ -664,7 +669,7 @@ __device__ __forceinline__ void quantize_pack_tile_body(
   }
 }
 
-template <int DT, int LPG_LOG2, int B, bool EXT = false, bool METRICS = false, bool RELU = false>
+template <int DT, int LPG_LOG2, int B, bool EXT = false, bool METRICS = false, bool RELU = false, int DIV = 1>
 __global__ __launch_bounds__(kThreads) void k_quantize_pack_tile(
     typename std::conditional<RELU, const u32x4*, const u32x4* __restrict__>::type x, int64_t n_tiles,
     const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, uint32_t seed_lo, uint32_t seed_hi,
@@ -689,9 +694,9 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_tile(
   }
   const int64_t tile = (int64_t)(blockIdx.x - first_tile_block) * kWavesPerBlock + wave_in_block;
   if (tile >= n_tiles) return;
-  quantize_pack_tile_body<DT, LPG_LOG2, B, EXT, METRICS, RELU>(x, tile, wave_in_block, bits, off, seed_lo, seed_hi, words,
-                                                               out_min, out_scale, ext_stat, tiles_per_group,
-                                                               out_metrics, out_y);
+  quantize_pack_tile_body<DT, LPG_LOG2, B, EXT, METRICS, RELU, DIV>(x, tile, wave_in_block, bits, off, seed_lo, seed_hi,
+                                                                    words, out_min, out_scale, ext_stat,
+                                                                    tiles_per_group, out_metrics, out_y);
 }
 
 // Several tensors in one launch (the activations a training step saves, Sec. 3.1): the tiles
@@ -727,19 +732,37 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_tile_batch(const Bat
                                            e.seed_hi, e.words, e.mn, e.sc, nullptr, (int64_t)1, nullptr, nullptr);
 }
 
+// Tensors of a 16-bit format with fewer whole tiles than this take half-size tiles.  The 16-bit
+// kernels are bound by vector instructions, not by memory, so their waves run in rounds of equal
+// length (4 waves per SIMD, 4096 at a time on 256 compute units): 6144 tiles are one and a half
+// rounds and cost two; as 12288 half-size tiles they cost three rounds of half the length.
+constexpr int64_t kHalfTilesBelow = 4 * 4096;
+
 template <int DT, int LPG_LOG2, bool METRICS, bool RELU>
 hipError_t launch_tile(const daf_plan_t* p, const void* x, int64_t n_tiles, uint32_t seed_lo, uint32_t seed_hi,
                        uint32_t* out_words, float* out_min, float* out_scale, float* out_metrics, void* out_y,
                        hipStream_t stream) {
-  const int64_t left = n_tiles * TileShape<DT, LPG_LOG2>::kGroups;   // first group after the whole tiles
-#define DAF_LAUNCH(BITS)                                                                                   \
+  constexpr bool kHalfOk = DT != kF32 && !METRICS && !RELU && TileShape<DT, LPG_LOG2, 2>::kValid &&
+                           TileShape<DT, LPG_LOG2, 2>::kElems < TileShape<DT, LPG_LOG2, 1>::kElems;
+  const bool half = kHalfOk && n_tiles < kHalfTilesBelow;
+#define DAF_LAUNCH_DIV(BITS, DIV)                                                                          \
   do {                                                                                                     \
-    auto kernel = k_quantize_pack_tile<DT, LPG_LOG2, BITS, false, METRICS, RELU>;                          \
-    const unsigned blocks = (unsigned)((n_tiles + kWavesPerBlock - 1) / kWavesPerBlock) + (left < p->num_groups ? 1u : 0u); \
+    using S = TileShape<DT, LPG_LOG2, DIV>;                                                                \
+    const int64_t tiles = (p->n / p->group_size) / S::kGroups;     /* whole tiles of this size */           \
+    const int64_t left = tiles * S::kGroups;                       /* first group after them */             \
+    auto kernel = k_quantize_pack_tile<DT, LPG_LOG2, BITS, false, METRICS, RELU, DIV>;                     \
+    const unsigned blocks = (unsigned)((tiles + kWavesPerBlock - 1) / kWavesPerBlock) + (left < p->num_groups ? 1u : 0u); \
     hipLaunchKernelGGL(kernel, dim3(blocks), dim3(kThreads), 0, stream, static_cast<const u32x4*>(x),      \
-                       n_tiles, p->d_bits, p->d_off, seed_lo, seed_hi, out_words, out_min, out_scale,      \
+                       tiles, p->d_bits, p->d_off, seed_lo, seed_hi, out_words, out_min, out_scale,        \
                        nullptr, (int64_t)1, out_metrics, static_cast<u32x4*>(out_y), p->n, left,           \
                        p->num_groups);                                                                     \
+  } while (0)
+#define DAF_LAUNCH(BITS)                                        \
+  do {                                                          \
+    if constexpr (kHalfOk) {                                    \
+      if (half) { DAF_LAUNCH_DIV(BITS, 2); break; }             \
+    }                                                           \
+    DAF_LAUNCH_DIV(BITS, 1);                                    \
   } while (0)
   switch (p->uniform_bits) {
     case 0: DAF_LAUNCH(0); break;
@@ -750,6 +773,7 @@ hipError_t launch_tile(const daf_plan_t* p, const void* x, int64_t n_tiles, uint
     default: return hipErrorInvalidValue;
   }
 #undef DAF_LAUNCH
+#undef DAF_LAUNCH_DIV
   return hipGetLastError();
 }
 
@@ -1249,7 +1273,7 @@ __device__ __forceinline__ void quantize_pack_units_body(
 
   // 6. the tile's words are one contiguous run in the packed buffer
   uint32_t* dst = words + tile_base;
-  for (uint32_t i = lane; i < tile_words; i += kWave) dst[i] = lds.stage[i];
+  for (uint32_t i = lane; i < tile_words; i += kWave) __builtin_nontemporal_store(lds.stage[i], &dst[i]);
   if constexpr (METRICS) {
     const float err = unit_group_sum(mlds.usum[0], k, m, part_log2, lane);
     const float mag = unit_group_sum(mlds.usum[1], k, m, part_log2, lane);
@@ -1399,7 +1423,7 @@ __device__ __forceinline__ void quantize_pack_long_body(
   // 6. the slice's words are one contiguous run inside the group's
   uint32_t* dst = words + group_base + (uint32_t)unit0 * b;
   const uint32_t slice_words = units * b;
-  for (uint32_t i = lane; i < slice_words; i += kWave) dst[i] = lds.stage[i];
+  for (uint32_t i = lane; i < slice_words; i += kWave) __builtin_nontemporal_store(lds.stage[i], &dst[i]);
 
   if constexpr (METRICS) {
     // per lane over its chunks, across the wave, then across the waves in a fixed order
