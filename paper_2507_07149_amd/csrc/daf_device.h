@@ -205,6 +205,93 @@ __device__ __forceinline__ void transposed_minmax16(const float (&mn_in)[16], co
   }
 }
 
+// ---- binary16 pairs: two elements per dword, no widening --------------------------------------
+// Minimum / maximum of both halves of three or two dwords (finite inputs; a zero may come out
+// with either sign, which the callers' "+ 0.0f" settles).
+__device__ __forceinline__ uint32_t pk_min3_f16(uint32_t a, uint32_t b, uint32_t c) {
+  uint32_t r;
+  asm("v_pk_minimum3_f16 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+__device__ __forceinline__ uint32_t pk_max3_f16(uint32_t a, uint32_t b, uint32_t c) {
+  uint32_t r;
+  asm("v_pk_maximum3_f16 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+__device__ __forceinline__ uint32_t pk_min_f16(uint32_t a, uint32_t b) {
+  uint32_t r;
+  asm("v_pk_min_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+__device__ __forceinline__ uint32_t pk_max_f16(uint32_t a, uint32_t b) {
+  uint32_t r;
+  asm("v_pk_max_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+
+// The statistics of the eight binary16 values of a chunk as one dword [-max : min] (two
+// binary16 halves), so that a single packed minimum per step reduces both across lanes.
+__device__ __forceinline__ uint32_t chunk_stat_f16(const uint4& raw) {
+  const uint32_t mn = pk_min_f16(pk_min3_f16(raw.x, raw.y, raw.z), raw.w);
+  const uint32_t mx = pk_max_f16(pk_max3_f16(raw.x, raw.y, raw.z), raw.w);
+  uint32_t q, r;
+  // both halves of q: min of the two halves of mn; both halves of r: -(max of the two halves of mx)
+  asm("v_pk_min_f16 %0, %1, %1 op_sel:[0,1] op_sel_hi:[1,0]" : "=v"(q) : "v"(mn));
+  asm("v_pk_min_f16 %0, %1, %1 op_sel:[0,1] op_sel_hi:[1,0] neg_lo:[1,1] neg_hi:[1,1]" : "=v"(r) : "v"(mx));
+  return __builtin_amdgcn_perm(r, q, 0x07060100u);       // high half from r, low half from q
+}
+__device__ __forceinline__ float stat_f16_min(uint32_t p) { return (float)__builtin_bit_cast(_Float16, (uint16_t)p); }
+__device__ __forceinline__ float stat_f16_max(uint32_t p) {
+  return -(float)__builtin_bit_cast(_Float16, (uint16_t)(p >> 16));
+}
+
+// Packed minimum of four [-max : min] dwords over aligned runs of 2^LPG_LOG2 lanes; the complete
+// result is guaranteed in the LAST lane of each run.  A step moves the partner lane's value with
+// a DPP move and merges it with a packed minimum (packed instructions take no DPP operand).
+// Four chains are interleaved, so every DPP read of a register comes at least three instructions
+// after the write (two wait states are needed); the leading and trailing s_nop cover what the
+// compiler puts around the block.  In the row-broadcast steps the lanes outside the row mask keep
+// the previous step's partner value in the temporary: a value of their own run, so merging it
+// again changes nothing.
+#define DAF_PK4(CTRL)                                                                              \
+  "v_mov_b32_dpp %4, %0 " CTRL "\n" "v_mov_b32_dpp %5, %1 " CTRL "\n"                              \
+  "v_mov_b32_dpp %6, %2 " CTRL "\n" "v_mov_b32_dpp %7, %3 " CTRL "\n"                              \
+  "v_pk_min_f16 %0, %0, %4\n" "v_pk_min_f16 %1, %1, %5\n"                                          \
+  "v_pk_min_f16 %2, %2, %6\n" "v_pk_min_f16 %3, %3, %7\n"
+#define DAF_PK4_ASM(BODY)                                                                          \
+  asm("s_nop 4\n" BODY "s_nop 1\n"                                                                 \
+      : "+v"(a), "+v"(b), "+v"(c), "+v"(d), "=&v"(t0), "=&v"(t1), "=&v"(t2), "=&v"(t3))
+template <int LPG_LOG2>
+__device__ __forceinline__ void seg_pk_min_x4(uint32_t& a, uint32_t& b, uint32_t& c, uint32_t& d) {
+  static_assert(LPG_LOG2 >= 2 && LPG_LOG2 <= 6, "run length 4..64 lanes");
+  uint32_t t0, t1, t2, t3;
+  if constexpr (LPG_LOG2 == 2) {
+    DAF_PK4_ASM(DAF_PK4(DAF_DPP_X1) DAF_PK4(DAF_DPP_X2));
+  } else if constexpr (LPG_LOG2 == 3) {
+    DAF_PK4_ASM(DAF_PK4(DAF_DPP_X1) DAF_PK4(DAF_DPP_X2) DAF_PK4(DAF_DPP_HM));
+  } else if constexpr (LPG_LOG2 == 4) {
+    DAF_PK4_ASM(DAF_PK4(DAF_DPP_X1) DAF_PK4(DAF_DPP_X2) DAF_PK4(DAF_DPP_HM) DAF_PK4(DAF_DPP_M));
+  } else if constexpr (LPG_LOG2 == 5) {
+    DAF_PK4_ASM(DAF_PK4(DAF_DPP_X1) DAF_PK4(DAF_DPP_X2) DAF_PK4(DAF_DPP_HM) DAF_PK4(DAF_DPP_M)
+                DAF_PK4(DAF_DPP_B15));
+  } else {
+    DAF_PK4_ASM(DAF_PK4(DAF_DPP_X1) DAF_PK4(DAF_DPP_X2) DAF_PK4(DAF_DPP_HM) DAF_PK4(DAF_DPP_M)
+                DAF_PK4(DAF_DPP_B15) DAF_PK4(DAF_DPP_B31));
+  }
+}
+#undef DAF_PK4_ASM
+#undef DAF_PK4
+
+// min - x for the low (HI = 0) or high (HI = 1) binary16 half of `pair`, in binary32 with one
+// rounding: a mixed-precision fma x * (-1) + min, which is the widened subtraction exactly.
+template <int HI>
+__device__ __forceinline__ float min_minus_half(uint32_t pair, float mn) {
+  float d;
+  if (HI) asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(pair), "v"(mn));
+  else    asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(pair), "v"(mn));
+  return d;
+}
+
 // Sums of two values over aligned runs of 2^LPG_LOG2 lanes (complete in the LAST lane of each
 // run).  Two chains: an instruction reads the register written two instructions earlier, so one
 // s_nop between steps completes the two wait states a DPP read needs.

@@ -65,6 +65,13 @@ __device__ __forceinline__ GroupScale group_scale(float mn, float mx, uint32_t b
 // Negated code of one element.  EXACT2 = false: invs = inv*256 (finite).  EXACT2 = true:
 // invs = inv, and the factor 256 is applied to the rounded product.
 template <bool EXACT2>
+__device__ __forceinline__ int neg_code_of_difference(float d, float invs, uint32_t r) {   // d = mn - x
+  float w = d * invs;
+  if (EXACT2) w = w * kScale;
+  return (round_half_up_to_int(w) + (int)r) >> 8;
+}
+
+template <bool EXACT2>
 __device__ __forceinline__ int neg_code(float x, float mn, float invs, uint32_t r, int* t_out = nullptr) {
   float w = (mn - x) * invs;
   if (EXACT2) w = w * kScale;
@@ -304,9 +311,11 @@ struct alignas(16) WaveLds {
   // First the random bytes of the tile (byte e serves tile element e); once every lane has
   // taken its bytes into registers the same memory stages the tile's packed words (at most
   // 8 bits per element, so the run always fits).
+  // The staged run starts up to three words in, so that 16-byte pieces of it line up with
+  // 16-byte pieces of the packed buffer.
   union {
     uint8_t rand_bytes[S::kElems];
-    uint32_t stage[S::kElems / 4];
+    uint32_t stage[S::kElems / 4 + 4];
   };
   GroupInfo info[kWave];
   float2 stat[kWave];                   // (min, max) per group, written by the group's last lane;
@@ -354,6 +363,47 @@ __device__ __forceinline__ void quantize_chunk(const float (&xf)[ElemTraits<DT>:
     *err = e2;
     *mag = m2;
     *var = (float)v2;
+  }
+}
+
+// The same for a chunk of eight binary16 values taken straight from the loaded dwords: min - x is
+// one mixed-precision fma per element (the widening conversion disappears into it).
+template <bool EXACT2>
+__device__ __forceinline__ void quantize_chunk_f16(const uint4& raw, float mn, float invs, uint32_t b,
+                                                   const uint32_t* rnd, uint32_t& nacc0, uint32_t& nacc1) {
+  const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+  uint32_t nacc[2] = {0u, 0u};
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    const uint32_t rw = rnd[q];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const uint32_t pair = w[q * 2 + (e >> 1)];
+      const float d = (e & 1) ? min_minus_half<1>(pair, mn) : min_minus_half<0>(pair, mn);
+      nacc[q] = (nacc[q] << b) + (uint32_t)neg_code_of_difference<EXACT2>(d, invs, (rw >> (8 * e)) & 0xFFu);
+    }
+  }
+  nacc0 = nacc[0];
+  nacc1 = nacc[1];
+}
+
+// binary16 tiles: one [-max : min] dword (two binary16 halves, daf_device.h) per (load, lane run)
+// segment in stat[segment].x; nothing is widened.
+template <int LPG_LOG2, int DIV>
+__device__ __forceinline__ void tile_minmax_f16(const uint4 (&raw)[TileShape<kF16, LPG_LOG2, DIV>::kLoads], float2* stat,
+                                                int lane) {
+  using S = TileShape<kF16, LPG_LOG2, DIV>;
+  static_assert(S::kLoads % 4 == 0, "loads are reduced four at a time");
+#pragma unroll
+  for (int u = 0; u < S::kLoads; u += 4) {
+    uint32_t p[4];
+#pragma unroll
+    for (int h = 0; h < 4; ++h) p[h] = chunk_stat_f16(raw[u + h]);
+    seg_pk_min_x4<S::kLaneLog2>(p[0], p[1], p[2], p[3]);
+    if ((lane & (S::kLpg - 1)) == S::kLpg - 1) {
+#pragma unroll
+      for (int h = 0; h < 4; ++h) stat[(u + h) * S::kGpl + (lane >> S::kLaneLog2)].x = u2f(p[h]);
+    }
   }
 }
 
@@ -415,6 +465,51 @@ __device__ __forceinline__ void tile_minmax(const uint4 (&raw)[TileShape<DT, LPG
   }
 }
 
+// Drops the codes of one chunk (negated accumulators n0, n1 as quantize_chunk returns them) at
+// byte address `addr` of the staged word run: a nibble pair, a byte, a halfword or whole words.
+template <int EPL>
+__device__ __forceinline__ void stage_chunk(uint8_t* stage8, uint32_t addr, uint32_t b, uint32_t n0, uint32_t n1,
+                                            int lane);
+
+// The same with `addr` an absolute LDS byte address (the staging area's own address already
+// added in, once per group instead of once per store).
+template <int EPL>
+__device__ __forceinline__ void stage_chunk_at(uint32_t addr, uint32_t b, uint32_t n0, uint32_t n1, int lane) {
+  typedef __attribute__((address_space(3))) uint8_t lds_u8;
+  stage_chunk<EPL>((uint8_t*)(lds_u8*)(uintptr_t)addr, 0u, b, n0, n1, lane);
+}
+
+template <int EPL>
+__device__ __forceinline__ void stage_chunk(uint8_t* stage8, uint32_t addr, uint32_t b, uint32_t n0, uint32_t n1,
+                                            int lane) {
+  if (EPL == 4) {
+    const uint32_t acc = 0u - n0;
+    if (b == 1u) {           // 4 bits per lane: the even lane takes its odd neighbour's nibble
+      const uint32_t nb = dpp<kDppXor1>(acc, acc);
+      if ((lane & 1) == 0) stage8[addr] = (uint8_t)((acc << 4) | nb);
+    } else if (b == 2u) {
+      stage8[addr] = (uint8_t)acc;
+    } else if (b == 4u) {
+      *reinterpret_cast<uint16_t*>(stage8 + addr) = (uint16_t)acc;
+    } else {
+      *reinterpret_cast<uint32_t*>(stage8 + addr) = acc;
+    }
+  } else {
+    if (b == 8u) {
+      *reinterpret_cast<uint2*>(stage8 + addr) = make_uint2(0u - n0, 0u - n1);
+    } else {
+      const uint32_t both = 0u - ((n0 << (4u * b)) + n1);
+      if (b == 4u) {
+        *reinterpret_cast<uint32_t*>(stage8 + addr) = both;
+      } else if (b == 2u) {
+        *reinterpret_cast<uint16_t*>(stage8 + addr) = (uint16_t)both;
+      } else {
+        stage8[addr] = (uint8_t)both;
+      }
+    }
+  }
+}
+
 // B = 1, 2, 4, 8: every group has that width (offsets are computed).  B = 0: per-group widths
 // from `bits`, offsets from `off`.
 // One tile per wave; the hardware schedules the waves.  (A looping variant in which a wave
@@ -452,7 +547,8 @@ __device__ __forceinline__ void quantize_pack_tile_body(
   const int lane = threadIdx.x & (kWave - 1);
   WaveLds<DT, LPG_LOG2, DIV>& lds = lds_all[wave_in_block];
   const uint32_t lane_in_run = (uint32_t)(lane & (S::kLpg - 1));
-  uint8_t* stage8 = reinterpret_cast<uint8_t*>(lds.stage);
+  // LDS byte address of the staging area (16-byte aligned, so the byte swizzles commute with it)
+  const uint32_t stage_base = (uint32_t)reinterpret_cast<uintptr_t>(lds.stage);
 
   // 1. all global loads of the tile, issued up front
   uint4 raw[S::kLoads];
@@ -486,6 +582,10 @@ __device__ __forceinline__ void quantize_pack_tile_body(
       tile_base = (uint32_t)tile * (uint32_t)(S::kGroups * kGroupWords32 * B);
     }
 
+    // The run is staged `head` words into the staging area, head = the word index of its first
+    // word in the packed buffer modulo 4: 16-byte pieces of the two then coincide.
+    const uint32_t head = ((uint32_t)(reinterpret_cast<uintptr_t>(words) >> 2) + tile_base) & 3u;
+
     // 2. random bytes of the tile (independent of the data; overlaps the loads' latency)
     {
       const uint64_t blk0 = (uint64_t)tile * (S::kElems / kElemsPerPhilox);
@@ -495,9 +595,14 @@ __device__ __forceinline__ void quantize_pack_tile_body(
         dst[m * kWave + lane] = philox_block(blk0 + (uint64_t)(m * kWave + lane), seed_lo, seed_hi);
     }
 
-    // 3. per-group min/max: in-lane over the chunk, then across the group's lanes
-    float xf[S::kLoads][kEpl];
-    if constexpr (EXT) {
+    // 3. per-group min/max: in-lane over the chunk, then across the group's lanes.
+    //    binary16 tiles stay in their loaded form: packed minimum / maximum on the pairs here, and
+    //    the subtraction of step 5 widens on the fly (the metrics variant needs the widened values).
+    constexpr bool kPairs16 = (DT == kF16) && !METRICS;
+    float xf[kPairs16 ? 1 : S::kLoads][kEpl];
+    if constexpr (kPairs16) {
+      if constexpr (!EXT) tile_minmax_f16<LPG_LOG2, DIV>(raw, lds.stat, lane);
+    } else if constexpr (EXT) {
 #pragma unroll
       for (int u = 0; u < S::kLoads; ++u) {
 #pragma unroll
@@ -515,6 +620,12 @@ __device__ __forceinline__ void quantize_pack_tile_body(
       float2 st;
       if constexpr (EXT) {
         st = ext_stat[g0];
+      } else if constexpr (kPairs16) {
+        uint32_t pk = f2u(lds.stat[(lane & (S::kGroups - 1)) * S::kLoadsPerGroup].x);
+#pragma unroll
+        for (int j = 1; j < S::kLoadsPerGroup; ++j)
+          pk = pk_min_f16(pk, f2u(lds.stat[(lane & (S::kGroups - 1)) * S::kLoadsPerGroup + j].x));
+        st = make_float2(stat_f16_min(pk), stat_f16_max(pk));
       } else {
         // the group's (load, lane run) segments are consecutive entries of stat
         st = lds.stat[(lane & (S::kGroups - 1)) * S::kLoadsPerGroup];
@@ -558,7 +669,7 @@ __device__ __forceinline__ void quantize_pack_tile_body(
         const uint32_t lane_bits = (uint32_t)kEpl * my_b;
         const uint32_t swz = (lane_bits <= 8u) ? 3u : (lane_bits == 16u) ? 2u : 0u;
         gi.b = my_b | (swz << 8);
-        gi.byte_off = woff * 4u;
+        gi.byte_off = stage_base + (woff + head) * 4u;
         lds.info[lane] = gi;
         if (METRICS) lds.gscale[lane] = s.scale;
       }
@@ -586,79 +697,68 @@ __device__ __forceinline__ void quantize_pack_tile_body(
     // 5. quantize every chunk and drop its bits at their place in the staged word run.
     //    The staged run is a big-endian bit string per word: byte k of the string lives at
     //    byte address k^3, halfword k at byte address 2k^2.
+    //    (One copy of the loop per multiplication variant, chosen once per tile: the variant for
+    //    groups whose reciprocal times 256 overflows is rare.)
+    auto quantize_tile = [&](auto exact2) {
+      constexpr bool kExact2 = decltype(exact2)::value;
 #pragma unroll
-    for (int u = 0; u < S::kLoads; ++u) {
-      const int grp = (u * S::kGpl + (lane >> S::kLaneLog2)) / S::kLoadsPerGroup;
-      // position of this lane's chunk among the chunks of its group
-      const uint32_t lig = lane_in_run + (uint32_t)(u % S::kLoadsPerGroup) * kWave;
-      float g_mn, g_invs;
-      uint32_t b, addr;
-      if (kMixed) {
-        const GroupInfo gi = lds.info[grp];
-        g_mn = gi.mn; g_invs = gi.invs; b = gi.b & 0xFFu;
-        // byte address of this lane's bits: lig * (kEpl*b) bits = lig*b*kEpl/8 bytes
-        addr = (gi.byte_off + ((lig * b * (uint32_t)kEpl) >> 3)) ^ (gi.b >> 8);
-      } else {
-        const float2 mi = *reinterpret_cast<const float2*>(&lds.info[grp]);
-        g_mn = mi.x; g_invs = mi.y; b = B;
-        constexpr uint32_t kLaneBits = (uint32_t)kEpl * B;
-        constexpr uint32_t kSwz = (kLaneBits <= 8u) ? 3u : (kLaneBits == 16u) ? 2u : 0u;
-        addr = ((uint32_t)grp * (kGroupWords32 * B * 4u) + ((lig * kLaneBits) >> 3)) ^ kSwz;
-      }
-      uint32_t n0, n1;
-      if constexpr (METRICS) {
-        const float g_scale = lds.gscale[grp];
-        float err, mag, var, unused = 0.0f;
-        if (need_exact2)
-          quantize_chunk<DT, true, true>(xf[u], g_mn, g_invs, b, rnd[u], n0, n1, g_scale, &err, &mag, &var);
-        else
-          quantize_chunk<DT, false, true>(xf[u], g_mn, g_invs, b, rnd[u], n0, n1, g_scale, &err, &mag, &var);
-        seg_sum2<S::kLaneLog2>(err, mag);      // over the group's lanes of this load
-        seg_sum2<S::kLaneLog2>(var, unused);
-        if (lane_in_run == (uint32_t)S::kLpg - 1u) {
-          const float2 acc = lds.stat[grp];    // the group's earlier loads (same lane, in order)
-          lds.stat[grp] = make_float2(acc.x + err, acc.y + mag);
-          lds.gvar[grp] += var;
-        }
-      } else {
-        if (need_exact2) quantize_chunk<DT, true>(xf[u], g_mn, g_invs, b, rnd[u], n0, n1);
-        else             quantize_chunk<DT, false>(xf[u], g_mn, g_invs, b, rnd[u], n0, n1);
-      }
-
-      if (kEpl == 4) {
-        const uint32_t acc = 0u - n0;
-        if (b == 1u) {           // 4 bits per lane: the even lane takes its odd neighbour's nibble
-          const uint32_t nb = dpp<kDppXor1>(acc, acc);
-          if ((lane & 1) == 0) stage8[addr] = (uint8_t)((acc << 4) | nb);
-        } else if (b == 2u) {
-          stage8[addr] = (uint8_t)acc;
-        } else if (b == 4u) {
-          *reinterpret_cast<uint16_t*>(stage8 + addr) = (uint16_t)acc;
+      for (int u = 0; u < S::kLoads; ++u) {
+        const int grp = (u * S::kGpl + (lane >> S::kLaneLog2)) / S::kLoadsPerGroup;
+        // position of this lane's chunk among the chunks of its group
+        const uint32_t lig = lane_in_run + (uint32_t)(u % S::kLoadsPerGroup) * kWave;
+        float g_mn, g_invs;
+        uint32_t b, addr;
+        if (kMixed) {
+          const GroupInfo gi = lds.info[grp];
+          g_mn = gi.mn; g_invs = gi.invs; b = gi.b & 0xFFu;
+          // byte address of this lane's bits: lig * (kEpl*b) bits = lig*b*kEpl/8 bytes
+          addr = (gi.byte_off + ((lig * b * (uint32_t)kEpl) >> 3)) ^ (gi.b >> 8);
         } else {
-          *reinterpret_cast<uint32_t*>(stage8 + addr) = acc;
+          const float2 mi = *reinterpret_cast<const float2*>(&lds.info[grp]);
+          g_mn = mi.x; g_invs = mi.y; b = B;
+          constexpr uint32_t kLaneBits = (uint32_t)kEpl * B;
+          constexpr uint32_t kSwz = (kLaneBits <= 8u) ? 3u : (kLaneBits == 16u) ? 2u : 0u;
+          addr = (stage_base + head * 4u + (uint32_t)grp * (kGroupWords32 * B * 4u) + ((lig * kLaneBits) >> 3)) ^ kSwz;
         }
-      } else {
-        if (b == 8u) {
-          *reinterpret_cast<uint2*>(stage8 + addr) = make_uint2(0u - n0, 0u - n1);
-        } else {
-          const uint32_t both = 0u - ((n0 << (4u * b)) + n1);
-          if (b == 4u) {
-            *reinterpret_cast<uint32_t*>(stage8 + addr) = both;
-          } else if (b == 2u) {
-            *reinterpret_cast<uint16_t*>(stage8 + addr) = (uint16_t)both;
-          } else {
-            stage8[addr] = (uint8_t)both;
+        uint32_t n0, n1;
+        if constexpr (METRICS) {
+          const float g_scale = lds.gscale[grp];
+          float err, mag, var, unused = 0.0f;
+          quantize_chunk<DT, kExact2, true>(xf[u], g_mn, g_invs, b, rnd[u], n0, n1, g_scale, &err, &mag, &var);
+          seg_sum2<S::kLaneLog2>(err, mag);      // over the group's lanes of this load
+          seg_sum2<S::kLaneLog2>(var, unused);
+          if (lane_in_run == (uint32_t)S::kLpg - 1u) {
+            const float2 acc = lds.stat[grp];    // the group's earlier loads (same lane, in order)
+            lds.stat[grp] = make_float2(acc.x + err, acc.y + mag);
+            lds.gvar[grp] += var;
           }
+        } else if constexpr (kPairs16) {
+          quantize_chunk_f16<kExact2>(raw[u], g_mn, g_invs, b, rnd[u], n0, n1);
+        } else {
+          quantize_chunk<DT, kExact2>(xf[u], g_mn, g_invs, b, rnd[u], n0, n1);
         }
+        stage_chunk_at<kEpl>(addr, b, n0, n1, lane);
       }
-    }
+    };
+    if (need_exact2) quantize_tile(std::true_type{});
+    else             quantize_tile(std::false_type{});
     wave_lds_sync();
 
-    // 6. the tile's words are one contiguous run in the packed buffer
-    uint32_t* dst = words + tile_base;
-    // (streaming stores: the words are read back by the backward pass, long after they have left
-    // the caches; with ordinary stores the mixed-width kernels ran a tenth slower)
-    for (uint32_t i = lane; i < tile_words; i += kWave) __builtin_nontemporal_store(lds.stage[i], &dst[i]);
+    // 6. the tile's words are one contiguous run of the packed buffer; they leave in 16-byte
+    //    pieces (single words at a ragged start or end) with streaming stores: the words are read
+    //    back by the backward pass, long after they have left the caches (with ordinary stores
+    //    the mixed-width kernels ran a tenth slower).
+    {
+      const uint32_t span = head + tile_words;
+      uint32_t* dst = words + tile_base - head;                 // 16-byte aligned
+      const uint32_t full_begin = (head + 3u) & ~3u, full_end = span & ~3u;
+      for (uint32_t w0 = full_begin + (uint32_t)lane * 4u; w0 < full_end; w0 += kWave * 4u)
+        __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(&lds.stage[w0]), reinterpret_cast<u32x4*>(dst + w0));
+      // the up to three words before the first and after the last whole piece: lanes 0..3 and 4..7
+      const uint32_t w = (lane < 4) ? (uint32_t)lane : full_end + (uint32_t)lane - 4u;
+      if (lane < 8 && ((lane < 4) ? (w >= head && w < full_begin) : (w < span)))
+        __builtin_nontemporal_store(lds.stage[w], dst + w);
+    }
     if (METRICS && lane < S::kGroups) {
       const float sc = lds.gscale[lane];
       float* m = out_metrics + 3 * (g0 + lane);
@@ -959,39 +1059,6 @@ hipError_t launch_big(const daf_plan_t* p, const void* x, uint32_t seed_lo, uint
                        p->uniform_bits, stat, seed_lo, seed_hi, out_words, out_min, out_scale);
   }
   return hipGetLastError();
-}
-
-// Drops the codes of one chunk (negated accumulators n0, n1 as quantize_chunk returns them) at
-// byte address `addr` of the staged word run: a nibble pair, a byte, a halfword or whole words.
-template <int EPL>
-__device__ __forceinline__ void stage_chunk(uint8_t* stage8, uint32_t addr, uint32_t b, uint32_t n0, uint32_t n1,
-                                            int lane) {
-  if (EPL == 4) {
-    const uint32_t acc = 0u - n0;
-    if (b == 1u) {           // 4 bits per lane: the even lane takes its odd neighbour's nibble
-      const uint32_t nb = dpp<kDppXor1>(acc, acc);
-      if ((lane & 1) == 0) stage8[addr] = (uint8_t)((acc << 4) | nb);
-    } else if (b == 2u) {
-      stage8[addr] = (uint8_t)acc;
-    } else if (b == 4u) {
-      *reinterpret_cast<uint16_t*>(stage8 + addr) = (uint16_t)acc;
-    } else {
-      *reinterpret_cast<uint32_t*>(stage8 + addr) = acc;
-    }
-  } else {
-    if (b == 8u) {
-      *reinterpret_cast<uint2*>(stage8 + addr) = make_uint2(0u - n0, 0u - n1);
-    } else {
-      const uint32_t both = 0u - ((n0 << (4u * b)) + n1);
-      if (b == 4u) {
-        *reinterpret_cast<uint32_t*>(stage8 + addr) = both;
-      } else if (b == 2u) {
-        *reinterpret_cast<uint16_t*>(stage8 + addr) = (uint16_t)both;
-      } else {
-        stage8[addr] = (uint8_t)both;
-      }
-    }
-  }
 }
 
 // ------------------------------------------------------------------------------------------
