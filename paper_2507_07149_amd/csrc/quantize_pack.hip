@@ -298,6 +298,23 @@ struct TileShape {
   static_assert(kSegments <= kWave, "tile shape");
 };
 
+// The tile the quantize kernels use for a group shape.  binary32 tiles are a quarter of the
+// largest size (1024 elements, 4 loads per lane; a half where a group needs more loads): the
+// binary32 kernel is bound by memory, and with a third of the registers per wave more waves keep
+// loads in flight.  Measured, whole / half / quarter tiles: 40.6 / 37.0 / 35.2 us on a
+// 51 M-element tensor, 150 / 141 / 131 us on 205 M elements.  The 16-bit kernels are bound by
+// vector instructions and lose to the per-tile overhead of smaller tiles (measured), so they keep
+// the whole size.
+template <int DT, int LPG_LOG2>
+constexpr int tile_div() {
+  if (DT != kF32) return 1;
+  if (TileShape<DT, LPG_LOG2, 4>::kValid && TileShape<DT, LPG_LOG2, 4>::kElems < TileShape<DT, LPG_LOG2, 2>::kElems) return 4;
+  if (TileShape<DT, LPG_LOG2, 2>::kValid && TileShape<DT, LPG_LOG2, 2>::kElems < TileShape<DT, LPG_LOG2, 1>::kElems) return 2;
+  return 1;
+}
+template <int DT, int LPG_LOG2>
+using QTile = TileShape<DT, LPG_LOG2, tile_div<DT, LPG_LOG2>()>;
+
 struct alignas(16) GroupInfo {   // what every lane of a group needs for the element map
   float mn;
   float invs;                    // inv*256, or inv on the two-multiplication path
@@ -416,9 +433,8 @@ __device__ __forceinline__ void tile_minmax(const uint4 (&raw)[TileShape<DT, LPG
   using S = TileShape<DT, LPG_LOG2, DIV>;
   constexpr int kEpl = S::kEpl;
   static_assert(S::kLoads % 2 == 0, "loads are reduced in pairs");
-  if constexpr (DT == kF32 && LPG_LOG2 >= 5) {
+  if constexpr (DT == kF32 && LPG_LOG2 >= 5 && S::kLoads == 16) {
     // groups of 32 or 64 lanes: all 16 loads are reduced together (transposed reduction)
-    static_assert(S::kLoads == 16, "transposed reduction takes 16 values");
     float lmn[16], lmx[16];
 #pragma unroll
     for (int u = 0; u < 16; ++u) {
@@ -828,41 +844,25 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_tile_batch(const Bat
   while (gtile >= batch.e[t].tile_end) ++t;         // uniform over the wave; t < batch.n by the check above
   const BatchEntry& e = batch.e[t];
   const int64_t tile = gtile - (t ? batch.e[t - 1].tile_end : 0);
-  quantize_pack_tile_body<DT, LPG_LOG2, B>(static_cast<const u32x4*>(e.x), tile, wave_in_block, e.bits, e.off, e.seed_lo,
-                                           e.seed_hi, e.words, e.mn, e.sc, nullptr, (int64_t)1, nullptr, nullptr);
+  quantize_pack_tile_body<DT, LPG_LOG2, B, false, false, false, tile_div<DT, LPG_LOG2>()>(
+      static_cast<const u32x4*>(e.x), tile, wave_in_block, e.bits, e.off, e.seed_lo, e.seed_hi, e.words, e.mn, e.sc,
+      nullptr, (int64_t)1, nullptr, nullptr);
 }
-
-// Tensors of a 16-bit format with fewer whole tiles than this take half-size tiles.  The 16-bit
-// kernels are bound by vector instructions, not by memory, so their waves run in rounds of equal
-// length (4 waves per SIMD, 4096 at a time on 256 compute units): 6144 tiles are one and a half
-// rounds and cost two; as 12288 half-size tiles they cost three rounds of half the length.
-constexpr int64_t kHalfTilesBelow = 4 * 4096;
 
 template <int DT, int LPG_LOG2, bool METRICS, bool RELU>
 hipError_t launch_tile(const daf_plan_t* p, const void* x, int64_t n_tiles, uint32_t seed_lo, uint32_t seed_hi,
                        uint32_t* out_words, float* out_min, float* out_scale, float* out_metrics, void* out_y,
                        hipStream_t stream) {
-  constexpr bool kHalfOk = DT != kF32 && !METRICS && !RELU && TileShape<DT, LPG_LOG2, 2>::kValid &&
-                           TileShape<DT, LPG_LOG2, 2>::kElems < TileShape<DT, LPG_LOG2, 1>::kElems;
-  const bool half = kHalfOk && n_tiles < kHalfTilesBelow;
-#define DAF_LAUNCH_DIV(BITS, DIV)                                                                          \
+  using S = QTile<DT, LPG_LOG2>;
+  const int64_t left = n_tiles * S::kGroups;                         // first group after the whole tiles
+#define DAF_LAUNCH(BITS)                                                                                   \
   do {                                                                                                     \
-    using S = TileShape<DT, LPG_LOG2, DIV>;                                                                \
-    const int64_t tiles = (p->n / p->group_size) / S::kGroups;     /* whole tiles of this size */           \
-    const int64_t left = tiles * S::kGroups;                       /* first group after them */             \
-    auto kernel = k_quantize_pack_tile<DT, LPG_LOG2, BITS, false, METRICS, RELU, DIV>;                     \
-    const unsigned blocks = (unsigned)((tiles + kWavesPerBlock - 1) / kWavesPerBlock) + (left < p->num_groups ? 1u : 0u); \
+    auto kernel = k_quantize_pack_tile<DT, LPG_LOG2, BITS, false, METRICS, RELU, tile_div<DT, LPG_LOG2>()>; \
+    const unsigned blocks = (unsigned)((n_tiles + kWavesPerBlock - 1) / kWavesPerBlock) + (left < p->num_groups ? 1u : 0u); \
     hipLaunchKernelGGL(kernel, dim3(blocks), dim3(kThreads), 0, stream, static_cast<const u32x4*>(x),      \
-                       tiles, p->d_bits, p->d_off, seed_lo, seed_hi, out_words, out_min, out_scale,        \
+                       n_tiles, p->d_bits, p->d_off, seed_lo, seed_hi, out_words, out_min, out_scale,      \
                        nullptr, (int64_t)1, out_metrics, static_cast<u32x4*>(out_y), p->n, left,           \
                        p->num_groups);                                                                     \
-  } while (0)
-#define DAF_LAUNCH(BITS)                                        \
-  do {                                                          \
-    if constexpr (kHalfOk) {                                    \
-      if (half) { DAF_LAUNCH_DIV(BITS, 2); break; }             \
-    }                                                           \
-    DAF_LAUNCH_DIV(BITS, 1);                                    \
   } while (0)
   switch (p->uniform_bits) {
     case 0: DAF_LAUNCH(0); break;
@@ -873,7 +873,6 @@ hipError_t launch_tile(const daf_plan_t* p, const void* x, int64_t n_tiles, uint
     default: return hipErrorInvalidValue;
   }
 #undef DAF_LAUNCH
-#undef DAF_LAUNCH_DIV
   return hipGetLastError();
 }
 
@@ -1940,10 +1939,10 @@ bool tile_geometry(const daf_plan_t* p, int* lpg_log2, int64_t* n_tiles, int64_t
   bool ok = false;
 #define DAF_CASE(LOG2)                                                   \
   case (1 << LOG2):                                                      \
-    if constexpr (TileShape<DT, LOG2>::kValid) {                         \
+    if constexpr (QTile<DT, LOG2>::kValid) {                             \
       *lpg_log2 = LOG2;                                                  \
-      *n_tiles = full_groups / TileShape<DT, LOG2>::kGroups;             \
-      *fast_groups = *n_tiles * TileShape<DT, LOG2>::kGroups;            \
+      *n_tiles = full_groups / QTile<DT, LOG2>::kGroups;                 \
+      *fast_groups = *n_tiles * QTile<DT, LOG2>::kGroups;                \
       ok = *n_tiles > 0;                                                 \
     }                                                                    \
     break;
@@ -1996,8 +1995,8 @@ hipError_t launch_dtype(const daf_plan_t* p, const void* x, uint64_t seed, uint3
     hipError_t e = hipSuccess;
 #define DAF_CASE(LOG2)                                                                                   \
   case (1 << LOG2):                                                                                      \
-    if constexpr (TileShape<DT, LOG2>::kValid) {                                                         \
-      n_tiles = full_groups / TileShape<DT, LOG2>::kGroups;                                              \
+    if constexpr (QTile<DT, LOG2>::kValid) {                                                             \
+      n_tiles = full_groups / QTile<DT, LOG2>::kGroups;                                                  \
       fast_groups = p->num_groups;          /* the leftover groups ride in the same launch */            \
       if (n_tiles > 0) e = launch_tile<DT, LOG2, METRICS, RELU>(p, x, n_tiles, seed_lo, seed_hi, out_words, \
                                                                 out_min, out_scale, out_metrics, out_y,  \
@@ -2064,7 +2063,7 @@ hipError_t launch_batch(const Batch& batch, int lpg_log2, int32_t uniform_bits, 
   switch (lpg_log2) {
 #define DAF_CASE(LOG2)                                                                      \
   case LOG2:                                                                                \
-    if constexpr (TileShape<DT, LOG2>::kValid) return launch_batch_bits<DT, LOG2>(batch, uniform_bits, stream); \
+    if constexpr (QTile<DT, LOG2>::kValid) return launch_batch_bits<DT, LOG2>(batch, uniform_bits, stream);  \
     break;
     DAF_CASE(2) DAF_CASE(3) DAF_CASE(4) DAF_CASE(5) DAF_CASE(6)
     DAF_CASE(7) DAF_CASE(8) DAF_CASE(9) DAF_CASE(10)
