@@ -38,6 +38,7 @@ QUOTED_TRAFFIC = {
     5: (994368003, 1007779370, "profiles/quantize_dequantize_llm_mlp_bf16_16x2048x11008_g64_b248.md"),
 }
 ROTATE_BYTES = 768 << 20          # buffer sets rotate over at least this much input
+ROTATE_PACKED_BYTES = 512 << 20   # ... and over at least this much packed output (words, min, scale)
 
 
 def parse():
@@ -583,14 +584,25 @@ def measure(cfg, args, daf, torch, np, dev, headline):
         plans_by_set.append([daf.daf_plan(tuple(w.x.shape), w.group_size, int(w.bits[0]) if b is None else b)
                              for w, b in zip(workloads, dbits)])
     plans = plans_by_set[0]
+    # The backward pass reads packed words, min and scale that the forward pass wrote long before:
+    # they must come from HBM in the timed launches too, so the buffer sets also rotate over more
+    # packed bytes than the 256 MB memory-side cache holds (a 14 MB packed tensor would
+    # otherwise be served from it and unpack+dequantize would read a quarter faster).
+    packed_bytes = sum(4 * p.packed_words + 8 * p.num_groups for p in plans)
+    n_sets = max(n_sets, -(-ROTATE_PACKED_BYTES // packed_bytes))
+    if plan_sets > 1:
+        for _ in range(n_sets - plan_sets):
+            plans_by_set.append([daf.daf_plan(tuple(w.x.shape), w.group_size, int(w.bits[0]) if b is None else b)
+                                 for w, b in zip(workloads, dbits)])
+        plan_sets = n_sets
 
     def plan_of(k, t):
         return plans_by_set[k % plan_sets][t]
     sets = []
     for s in range(n_sets):
         bufs = []
-        for w, p in zip(workloads, plans):
-            x = w.x.reshape(-1).to(dev)
+        for t, (w, p) in enumerate(zip(workloads, plans)):
+            x = w.x.reshape(-1).to(dev) if s == 0 else sets[0][t]["x"].clone()
             bufs.append(dict(x=x, words=torch.empty(p.packed_words, dtype=torch.int32, device=dev),
                              mn=torch.empty(p.num_groups, dtype=torch.float32, device=dev),
                              sc=torch.empty(p.num_groups, dtype=torch.float32, device=dev),

@@ -840,8 +840,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_tile_batch(const Bat
   const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int64_t gtile = (int64_t)blockIdx.x * kWavesPerBlock + wave_in_block;
   if (gtile >= batch.e[batch.n - 1].tile_end) return;
-  int t = 0;
-  while (gtile >= batch.e[t].tile_end) ++t;         // uniform over the wave; t < batch.n by the check above
+  const int t = batch_entry_of(batch.e, batch.n, gtile, [](const BatchEntry& b) { return b.tile_end; });   // < batch.n by the check above
   const BatchEntry& e = batch.e[t];
   const int64_t tile = gtile - (t ? batch.e[t - 1].tile_end : 0);
   quantize_pack_tile_body<DT, LPG_LOG2, B, false, false, false, tile_div<DT, LPG_LOG2>()>(
@@ -1658,8 +1657,7 @@ __global__ __launch_bounds__(kThreads) void k_quantize_pack_units_batch(const Un
   const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int64_t gtile = (int64_t)blockIdx.x * kWavesPerBlock + wave_in_block;
   if (gtile >= batch.e[batch.n - 1].tile_end) return;
-  int t = 0;
-  while (gtile >= batch.e[t].tile_end) ++t;         // uniform over the wave; t < batch.n by the check above
+  const int t = batch_entry_of(batch.e, batch.n, gtile, [](const UnitBatchEntry& b) { return b.tile_end; });   // < batch.n
   const UnitBatchEntry& e = batch.e[t];
   const int64_t first = t ? batch.e[t - 1].tile_end : 0;
   quantize_pack_units_body<DT, B>(static_cast<const u32x4*>(e.x), gtile - first, wave_in_block, e.tile_end - first, e.m,

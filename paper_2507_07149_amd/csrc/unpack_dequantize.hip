@@ -22,7 +22,19 @@ namespace {
 using namespace daf;
 
 constexpr int kThreads = 256;
-constexpr int kChunksPerThread = 8;
+// 16-byte chunks per thread: 8, so that the small dependent loads of eight chunks (widths and
+// offsets first, then the words) are in flight together.  Measured with the packed inputs coming
+// from HBM, as they do in a backward pass (tensors rotating over more than the memory-side
+// cache holds): 1 / 2 / 4 / 8 chunks with one width for all groups take 46.7 / 45.3 / 41.7 /
+// 41.9 us on a 51 M-element binary32 tensor.  (With the 14 MB of packed input left in that cache
+// by the previous launch, one chunk per thread looks best, 32.5 us: a measurement artefact.)
+#ifndef DAF_DEQ_CHUNKS_UNIFORM
+#define DAF_DEQ_CHUNKS_UNIFORM 8
+#endif
+#ifndef DAF_DEQ_CHUNKS_MIXED
+#define DAF_DEQ_CHUNKS_MIXED 8
+#endif
+constexpr int chunks_per_thread(bool mixed) { return mixed ? DAF_DEQ_CHUNKS_MIXED : DAF_DEQ_CHUNKS_UNIFORM; }
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 template <int DT>
@@ -87,7 +99,7 @@ __device__ __forceinline__ void unpack_dequantize_block(
     const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, int32_t uniform_bits,
     int64_t n_chunks, int32_t gs, int32_t gs_shift, u32x4* out, const u32x4* grad, bool cached) {
   constexpr int kEpl = ElemTraits<DT>::kPerLoad;
-  constexpr int K = kChunksPerThread;
+  constexpr int K = chunks_per_thread(MIXED);
   const int64_t base = block * (kThreads * K) + threadIdx.x;
 
   int64_t g[K];
@@ -217,8 +229,8 @@ struct Batch {
 template <int DT, bool MIXED>
 __global__ __launch_bounds__(kThreads) void k_unpack_dequantize_chunk_batch(const Batch batch) {
   const int64_t gblock = blockIdx.x;
-  int t = 0;
-  while (t + 1 < batch.n && gblock >= batch.e[t].block_end) ++t;
+  // (gblock < the last entry's block_end by the grid size, so t < batch.n)
+  const int t = batch_entry_of(batch.e, batch.n, gblock, [](const BatchEntry& b) { return b.block_end; });
   const BatchEntry& e = batch.e[t];
   unpack_dequantize_block<DT, MIXED, false>(gblock - (t ? batch.e[t - 1].block_end : 0), e.words, e.mn, e.scale, e.bits,
                                             e.off, e.uniform_bits, e.n_chunks, e.gs, e.gs_shift, e.out, nullptr,
@@ -233,7 +245,7 @@ hipError_t launch_dtype(const daf_plan_t* p, const uint32_t* words, const float*
   int32_t gs_shift = -1;
   if ((p->group_size & (p->group_size - 1)) == 0) gs_shift = __builtin_ctz((unsigned)p->group_size);
   if (n_chunks > 0) {
-    const int64_t per_block = (int64_t)kThreads * kChunksPerThread;
+    const int64_t per_block = (int64_t)kThreads * chunks_per_thread(p->uniform_bits == 0);
     const unsigned blocks = (unsigned)((n_chunks + per_block - 1) / per_block) + (n_chunks * kEpl < p->n ? 1u : 0u);
     if (p->uniform_bits)
       hipLaunchKernelGGL((k_unpack_dequantize_chunk<DT, false, RELU_BWD>), dim3(blocks), dim3(kThreads), 0, stream,
@@ -260,7 +272,6 @@ hipError_t launch_dtype(const daf_plan_t* p, const uint32_t* words, const float*
 template <int DT>
 hipError_t launch_items(const daf_dequantize_item_t* items, int32_t n_items, hipStream_t stream) {
   constexpr int kEpl = ElemTraits<DT>::kPerLoad;
-  const int64_t per_block = (int64_t)kThreads * kChunksPerThread;
   Batch batch;
   batch.n = 0;
   bool cur_mixed = false;
@@ -283,6 +294,7 @@ hipError_t launch_items(const daf_dequantize_item_t* items, int32_t n_items, hip
     const int64_t n_chunks = p->n / kEpl;
     const bool mixed = p->uniform_bits == 0;
     if (n_chunks > 0) {
+      const int64_t per_block = (int64_t)kThreads * chunks_per_thread(mixed);
       const int64_t blocks = (n_chunks + per_block - 1) / per_block;
       if (batch.n == kMaxBatch || (batch.n > 0 && mixed != cur_mixed) ||
           (batch.n > 0 && batch.e[batch.n - 1].block_end + blocks > 0x7fffffff))
