@@ -332,16 +332,19 @@ __device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v) {
   return v;
 }
 
-// List calls: the units (tiles, blocks) of all tensors of a launch form one sequence, and entry t
-// of the descriptor array holds the number of units of entries 0..t.  The entry that owns unit
-// `pos` is the number of entries whose cumulative count is <= pos: lane l looks at entry l and a
-// ballot counts them (a walk over the entries would cost one dependent scalar load per entry,
-// which is most of the time of a small workgroup).  n <= 64 entries; the result is wave-uniform.
-template <typename Entry, typename Get>
-__device__ __forceinline__ int batch_entry_of(const Entry* entries, int n, int64_t pos, Get cumulative) {
-  const int lane = threadIdx.x & (kWave - 1);
-  const bool below = lane < n && cumulative(entries[lane < n ? lane : 0]) <= pos;
-  return __builtin_amdgcn_readfirstlane(__builtin_popcountll(__builtin_amdgcn_ballot_w64(below)));
+// List calls: the units (tiles, blocks) of all tensors of a launch form one sequence, and
+// ends[t] holds the number of units of entries 0..t (0xFFFFFFFF in the unused entries).  The
+// entry that owns unit `pos` is the number of entries whose cumulative count is <= pos.  The 32
+// counts are kernel arguments: they arrive with the wave's first scalar loads, and 32 scalar
+// compares find the entry without a trip to memory (a walk over the descriptors costs one
+// dependent load per entry; a per-lane load and a ballot one vector round trip, which made a
+// short-lived dequantize wave a tenth slower).  `pos` must be wave-uniform.
+constexpr int kBatchSlots = 32;
+__device__ __forceinline__ int batch_entry_of(const uint32_t (&ends)[kBatchSlots], uint32_t pos) {
+  int t = 0;
+#pragma unroll
+  for (int i = 0; i < kBatchSlots; ++i) t += (ends[i] <= pos) ? 1 : 0;
+  return t;
 }
 
 // Philox4x32-10 (Salmon et al., SC'11): ten rounds of two 32x32->64 multiplies and two

@@ -831,16 +831,22 @@ struct BatchEntry {
   uint32_t seed_lo, seed_hi;
 };
 struct Batch {
+  uint32_t ends[kBatchSlots];                       // e[t].tile_end, 0xFFFFFFFF beyond n
   BatchEntry e[kMaxBatch];
   int32_t n;
+  void clear() {
+    n = 0;
+    for (int i = 0; i < kBatchSlots; ++i) ends[i] = 0xFFFFFFFFu;
+  }
 };
+static_assert(kMaxBatch <= kBatchSlots, "one cumulative count per entry");
 
 template <int DT, int LPG_LOG2, int B>
 __global__ __launch_bounds__(kThreads) void k_quantize_pack_tile_batch(const Batch batch) {
   const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int64_t gtile = (int64_t)blockIdx.x * kWavesPerBlock + wave_in_block;
-  if (gtile >= batch.e[batch.n - 1].tile_end) return;
-  const int t = batch_entry_of(batch.e, batch.n, gtile, [](const BatchEntry& b) { return b.tile_end; });   // < batch.n by the check above
+  const int t = batch_entry_of(batch.ends, (uint32_t)gtile);
+  if (t >= batch.n) return;                          // past the last tile (the grid is whole workgroups)
   const BatchEntry& e = batch.e[t];
   const int64_t tile = gtile - (t ? batch.e[t - 1].tile_end : 0);
   quantize_pack_tile_body<DT, LPG_LOG2, B, false, false, false, tile_div<DT, LPG_LOG2>()>(
@@ -1648,16 +1654,21 @@ struct UnitBatchEntry {
   uint32_t magic;
 };
 struct UnitBatch {
+  uint32_t ends[kBatchSlots];                       // e[t].tile_end, 0xFFFFFFFF beyond n
   UnitBatchEntry e[kMaxBatch];
   int32_t n;
+  void clear() {
+    n = 0;
+    for (int i = 0; i < kBatchSlots; ++i) ends[i] = 0xFFFFFFFFu;
+  }
 };
 
 template <int DT, int B>
 __global__ __launch_bounds__(kThreads) void k_quantize_pack_units_batch(const UnitBatch batch) {
   const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int64_t gtile = (int64_t)blockIdx.x * kWavesPerBlock + wave_in_block;
-  if (gtile >= batch.e[batch.n - 1].tile_end) return;
-  const int t = batch_entry_of(batch.e, batch.n, gtile, [](const UnitBatchEntry& b) { return b.tile_end; });   // < batch.n
+  const int t = batch_entry_of(batch.ends, (uint32_t)gtile);
+  if (t >= batch.n) return;
   const UnitBatchEntry& e = batch.e[t];
   const int64_t first = t ? batch.e[t - 1].tile_end : 0;
   quantize_pack_units_body<DT, B>(static_cast<const u32x4*>(e.x), gtile - first, wave_in_block, e.tile_end - first, e.m,
@@ -2078,14 +2089,14 @@ hipError_t launch_batch(const Batch& batch, int lpg_log2, int32_t uniform_bits, 
 template <int DT>
 hipError_t launch_items(const daf_quantize_item_t* items, int32_t n_items, hipStream_t stream) {
   Batch batch;
-  batch.n = 0;
+  batch.clear();
   UnitBatch ubatch;                    // items of the unit path (group sizes that are not a power of two)
-  ubatch.n = 0;
+  ubatch.clear();
   int cur_log2 = -1, cur_gs = -1, cur_bits = -1, ucur_bits = -1;
   hipError_t err = hipSuccess;
   auto flush = [&]() {
     if (batch.n > 0 && err == hipSuccess) err = launch_batch<DT>(batch, cur_log2, cur_bits, stream);
-    batch.n = 0;
+    batch.clear();
   };
   GroupBatch gbatch[2];                // leftovers: [0] a wave per group, [1] a workgroup per group
   gbatch[0].n = gbatch[1].n = 0;
@@ -2161,7 +2172,7 @@ hipError_t launch_items(const daf_quantize_item_t* items, int32_t n_items, hipSt
 #undef DAF_LAUNCH
       if (err == hipSuccess) err = hipGetLastError();
     }
-    ubatch.n = 0;
+    ubatch.clear();
   };
   for (int32_t i = 0; i < n_items && err == hipSuccess; ++i) {
     const daf_quantize_item_t& it = items[i];
@@ -2207,6 +2218,7 @@ hipError_t launch_items(const daf_quantize_item_t* items, int32_t n_items, hipSt
       e.mn = it.out_min;
       e.sc = it.out_scale;
       e.tile_end = (ubatch.n ? ubatch.e[ubatch.n - 1].tile_end : 0) + ug.n_tiles;
+      ubatch.ends[ubatch.n] = (uint32_t)e.tile_end;
       e.seed_lo = (uint32_t)it.seed;
       e.seed_hi = (uint32_t)(it.seed >> 32);
       e.m = ug.m;
@@ -2224,7 +2236,9 @@ hipError_t launch_items(const daf_quantize_item_t* items, int32_t n_items, hipSt
         err = launch_dtype<DT, false>(p, it.x, it.seed, it.out_words, it.out_min, it.out_scale, nullptr, nullptr, stream);
       continue;
     }
-    if (batch.n == kMaxBatch || (batch.n > 0 && (p->group_size != cur_gs || p->uniform_bits != cur_bits))) flush();
+    if (batch.n == kMaxBatch || (batch.n > 0 && (p->group_size != cur_gs || p->uniform_bits != cur_bits)) ||
+        (batch.n > 0 && batch.e[batch.n - 1].tile_end + n_tiles > 0x7fffffff))
+      flush();
     cur_log2 = log2;
     cur_gs = p->group_size;
     cur_bits = p->uniform_bits;
@@ -2236,6 +2250,7 @@ hipError_t launch_items(const daf_quantize_item_t* items, int32_t n_items, hipSt
     e.mn = it.out_min;
     e.sc = it.out_scale;
     e.tile_end = (batch.n ? batch.e[batch.n - 1].tile_end : 0) + n_tiles;
+    batch.ends[batch.n] = (uint32_t)e.tile_end;
     e.seed_lo = (uint32_t)it.seed;
     e.seed_hi = (uint32_t)(it.seed >> 32);
     ++batch.n;
