@@ -247,26 +247,27 @@ struct alignas(16) TileGroup {   // what a chunk needs to know about its group
 };
 
 // B = 1, 2, 4, 8: every group has that width.  B = 0: per-group widths and offsets.
-template <int DT, int B>
+template <int DT, int B, int U>
 struct alignas(16) TileLds {
-  static constexpr int kWords = kTileChunks * ElemTraits<DT>::kPerLoad * (B ? B : 8) / 32;   // the run, at most
+  static constexpr int kWords = kWave * U * ElemTraits<DT>::kPerLoad * (B ? B : 8) / 32;     // the run, at most
   uint32_t stage[kWords + 4];
   TileGroup group[kWave];
 };
 
-template <int DT, int B, bool RELU_BWD>
+// U = 16-byte chunks per lane: 8; 16 for small tensors with per-group widths (see launch_dtype).
+template <int DT, int B, bool RELU_BWD, int U = kTileChunksPerLane>
 __device__ __forceinline__ void unpack_dequantize_tile_body(
     int64_t tile, int wave_in_block, const uint32_t* __restrict__ words, const float* __restrict__ mn,
     const float* __restrict__ scale, const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off,
     int32_t gs_log2, u32x4* out, const u32x4* grad, bool cached) {
   constexpr int kEpl = ElemTraits<DT>::kPerLoad;
-  constexpr int U = kTileChunksPerLane;
+  constexpr int kTileChunks = kWave * U;
   constexpr int kElems = kTileChunks * kEpl;
   constexpr bool kMixed = (B == 0);
-  constexpr int kMaxWords = TileLds<DT, B>::kWords;
+  constexpr int kMaxWords = TileLds<DT, B, U>::kWords;
   constexpr int kWordLoads = (kMaxWords + kWave - 1) / kWave;     // per lane
-  __shared__ TileLds<DT, B> lds_all[kWavesPerBlock];
-  TileLds<DT, B>& lds = lds_all[wave_in_block];
+  __shared__ TileLds<DT, B, U> lds_all[kWavesPerBlock];
+  TileLds<DT, B, U>& lds = lds_all[wave_in_block];
   const int lane = threadIdx.x & (kWave - 1);
   const int groups = kElems >> gs_log2;                          // 1 .. 64 whole groups per tile
   const int64_t g0 = tile * groups;
@@ -351,12 +352,14 @@ __device__ __forceinline__ void unpack_dequantize_tile_body(
 #define DAF_DEQ_TILE_WAVES 6
 #endif
 #define DAF_TILE_WAVES __attribute__((amdgpu_waves_per_eu(1, DAF_DEQ_TILE_WAVES)))
-template <int DT, int B, bool RELU_BWD>
+template <int DT, int B, bool RELU_BWD, int U = kTileChunksPerLane>
 __global__ __launch_bounds__(kThreads) DAF_TILE_WAVES void k_unpack_dequantize_tile(
     const uint32_t* __restrict__ words, const float* __restrict__ mn, const float* __restrict__ scale,
     const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, int64_t n_tiles, int32_t gs, int32_t gs_log2,
     u32x4* out, const u32x4* grad, int cached, int64_t n_chunks, int64_t n) {
   constexpr int kEpl = ElemTraits<DT>::kPerLoad;
+  constexpr int kTileChunks = kWave * U;
+  static_assert(kTileChunks <= kThreads * chunks_per_thread(B == 0), "the left-over chunks fit one workgroup");
   const bool left = n_tiles * kTileChunks * kEpl < n;
   if (left && blockIdx.x == 0) {
     if (n_tiles * kTileChunks < n_chunks)
@@ -369,8 +372,8 @@ __global__ __launch_bounds__(kThreads) DAF_TILE_WAVES void k_unpack_dequantize_t
   const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int64_t tile = (int64_t)(blockIdx.x - (left ? 1u : 0u)) * kWavesPerBlock + wave_in_block;
   if (tile >= n_tiles) return;
-  unpack_dequantize_tile_body<DT, B, RELU_BWD>(tile, wave_in_block, words, mn, scale, bits, off, gs_log2, out, grad,
-                                               cached != 0);
+  unpack_dequantize_tile_body<DT, B, RELU_BWD, U>(tile, wave_in_block, words, mn, scale, bits, off, gs_log2, out, grad,
+                                                  cached != 0);
 }
 
 // Several tensors in one launch: the tiles of all of them form one sequence.
@@ -405,8 +408,8 @@ __global__ __launch_bounds__(kThreads) DAF_TILE_WAVES void k_unpack_dequantize_t
 
 // Whole tiles of a plan on the tile path (0: the plan's group size does not fit it).
 template <int DT>
-int64_t tile_path_tiles(const daf_plan_t* p, int32_t* gs_log2) {
-  constexpr int kElems = kTileChunks * ElemTraits<DT>::kPerLoad;
+int64_t tile_path_tiles(const daf_plan_t* p, int32_t* gs_log2, int chunks_per_lane = kTileChunksPerLane) {
+  const int kElems = kWave * chunks_per_lane * ElemTraits<DT>::kPerLoad;
   const int32_t gs = p->group_size;
   if ((gs & (gs - 1)) != 0 || gs > kElems || kElems / gs > kWave) return 0;
   *gs_log2 = __builtin_ctz((unsigned)gs);
@@ -480,6 +483,24 @@ hipError_t launch_dtype(const daf_plan_t* p, const uint32_t* words, const float*
   int32_t gs_log2 = 0;
   const int64_t n_tiles = tile_path_tiles<DT>(p, &gs_log2);
   if (n_tiles == 0) return launch_chunks<DT, RELU_BWD>(p, words, mn, scale, d_bits, out_x, grad, 0, stream);
+  // A small tensor with per-group widths takes tiles of twice the size: every wave pays two
+  // round trips to memory (widths, then words) before it can store anything, and with few
+  // waves per SIMD to overlap them fewer, longer waves come out ahead (a 50 MB binary16 tensor:
+  // 14.5 -> 12.5 us; the 721 MB bfloat16 one prefers the smaller tile, 157 against 164 us).
+  if (p->uniform_bits == 0 && n_tiles <= 8192) {
+    int32_t log2_big = 0;
+    const int64_t big_tiles = tile_path_tiles<DT>(p, &log2_big, 2 * kTileChunksPerLane);
+    if (big_tiles > 0) {
+      constexpr int kBig = 2 * kTileChunks;
+      const bool left = big_tiles * kBig * kEpl < p->n;
+      const unsigned blocks = (unsigned)((big_tiles + kWavesPerBlock - 1) / kWavesPerBlock) + (left ? 1u : 0u);
+      hipLaunchKernelGGL((k_unpack_dequantize_tile<DT, 0, RELU_BWD, 2 * kTileChunksPerLane>), dim3(blocks), dim3(kThreads),
+                         0, stream, words, mn, scale, d_bits, p->d_off, big_tiles, p->group_size, log2_big,
+                         static_cast<u32x4*>(out_x), static_cast<const u32x4*>(grad), p->output_cached, p->n / kEpl,
+                         p->n);
+      return hipGetLastError();
+    }
+  }
   const bool left = n_tiles * kTileChunks * kEpl < p->n;
   const unsigned blocks = (unsigned)((n_tiles + kWavesPerBlock - 1) / kWavesPerBlock) + (left ? 1u : 0u);
 #define DAF_LAUNCH(BITS)                                                                                      \
