@@ -33,9 +33,10 @@ HBM_PEAK_GBPS = 8000.0
 # this program, each scaled by what the same counter reads for a 1 GiB device copy; QUOTED from the named
 # summary, not measured in the run that prints them (the JSON says so next to the figure).
 QUOTED_TRAFFIC = {
-    2: (220116407, 220276367, "profiles/quantize_dequantize_resnet50_conv_f32_64x256x56x56_g256_b2.md"),
-    3: (64895828, 65096579, "profiles/quantize_dequantize_vit_bert_f16_32x1024x768_g128_b1248.md"),
-    5: (994368003, 1007779370, "profiles/quantize_dequantize_llm_mlp_bf16_16x2048x11008_g64_b248.md"),
+    2: (220055818, 220159672, "profiles/quantize_dequantize_resnet50_conv_f32_64x256x56x56_g256_b2.md"),
+    3: (65503175, 64721348, "profiles/quantize_dequantize_vit_bert_f16_32x1024x768_g128_b1248.md"),
+    4: (2529705172, 2530220191, "profiles/quantize_dequantize_resnet18_step_f32_bs256_g256_b2.md"),
+    5: (1000922059, 1002183800, "profiles/quantize_dequantize_llm_mlp_bf16_16x2048x11008_g64_b248.md"),
 }
 ROTATE_BYTES = 768 << 20          # buffer sets rotate over at least this much input
 ROTATE_PACKED_BYTES = 512 << 20   # ... and over at least this much packed output (words, min, scale)
