@@ -144,7 +144,9 @@ void daf_plan_destroy(daf_plan_t* plan);
  * codes and scale = range/(2^b-1).
  *
  *   plan       from daf_plan, for this tensor's shape, group size and widths.
- *   x          DEVICE, N elements of `dtype`, 16-byte aligned.  Finite values only.
+ *   x          DEVICE, N elements of `dtype`, 16-byte aligned.  Finite values only, and every
+ *              group's range max - min must be finite in binary32 as well (a group that spans
+ *              more than 3.4e38, e.g. -3e38 and 3e38, has scale = inf and dequantizes to NaN).
  *   dtype      element type of x.  16-bit inputs are widened exactly to binary32 first.
  *   seed       key of the random stream.
  *   out_words  DEVICE, daf_plan_packed_words(plan) uint32, 4-byte aligned; fully overwritten.

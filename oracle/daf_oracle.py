@@ -1,8 +1,11 @@
 """ctypes + numpy face of the C++ oracle (oracle/daf_oracle.cpp).
 
-TEST INFRASTRUCTURE.  Arrays in, arrays out; every function is a thin call into the C++
-code, which is where the method is written down.  16-bit inputs travel as uint16 bit
-patterns (numpy has no bfloat16).
+TEST INFRASTRUCTURE.  Arrays in, arrays out.  The quantize / pack / unpack / dequantize path, the
+plan, the random numbers, the reductions and the width rule are thin calls into the C++ code,
+which is where the method is written down.  Three plain definitions that the fused GPU calls
+are checked against are written out here in numpy instead: `relu` (max(z, +0) on the element
+format), `relu_backward` (grad where xhat > 0) and `grad_weight` (the matrix product in double
+precision).  16-bit inputs travel as uint16 bit patterns (numpy has no bfloat16).
 """
 import ctypes
 import os

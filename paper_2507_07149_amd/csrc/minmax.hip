@@ -40,23 +40,17 @@ struct MinMaxWorkspace {          // layout of the caller's workspace
   float2 partial[kMaxBlocks];     // two-pass method: one pair per workgroup
 };
 
-// Algorithm 1: float atomic minimum from compare-and-swap on the bit pattern.
-__device__ __forceinline__ void atomic_min_float(float* address, float val) {
-  unsigned* address_as_uint = reinterpret_cast<unsigned*>(address);
-  unsigned old = __atomic_load_n(address_as_uint, __ATOMIC_RELAXED);
-  while (val < u2f(old)) {
-    const unsigned assumed = old;
-    old = atomicCAS(address_as_uint, assumed, f2u(fminf(u2f(assumed), val)));
-    if (old == assumed) break;
-  }
-}
-__device__ __forceinline__ void atomic_max_float(float* address, float val) {
-  unsigned* address_as_uint = reinterpret_cast<unsigned*>(address);
-  unsigned old = __atomic_load_n(address_as_uint, __ATOMIC_RELAXED);
-  while (val > u2f(old)) {
-    const unsigned assumed = old;
-    old = atomicCAS(address_as_uint, assumed, f2u(fmaxf(u2f(assumed), val)));
-    if (old == assumed) break;
+// Float atomic minimum / maximum in the manner of Algorithm 1: the value lives in memory as its
+// bit pattern and is replaced with an integer compare-and-swap, retried while another workgroup
+// got in between.  The loop is left as soon as the stored value is already at least as good as the
+// candidate, so no swap is issued for a value that cannot change the result.
+template <bool IS_MIN>
+__device__ __forceinline__ void atomic_extremum(float* target, float candidate) {
+  unsigned* bits = reinterpret_cast<unsigned*>(target);
+  unsigned seen = __atomic_load_n(bits, __ATOMIC_RELAXED);
+  while (IS_MIN ? candidate < u2f(seen) : candidate > u2f(seen)) {
+    // on failure `seen` receives the value found, and the test above runs again on it
+    if (__atomic_compare_exchange_n(bits, &seen, f2u(candidate), false, __ATOMIC_RELAXED, __ATOMIC_RELAXED)) break;
   }
 }
 
@@ -139,8 +133,8 @@ __global__ __launch_bounds__(kThreads) void k_minmax(const void* __restrict__ x,
   // below covers the path that only loaded.  No plain load or store is shared, so no cache
   // write-back/invalidate (which a full fence would add, per workgroup) is needed; measured,
   // such fences made this kernel 5x slower on 2048 workgroups.
-  atomic_min_float(&ws->cur_min, mn);
-  atomic_max_float(&ws->cur_max, mx);
+  atomic_extremum<true>(&ws->cur_min, mn);
+  atomic_extremum<false>(&ws->cur_max, mx);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   const unsigned ticket = atomicAdd(&ws->ticket, 1u);
   if (ticket == gridDim.x - 1) {                                // every workgroup has merged its pair
