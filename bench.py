@@ -251,6 +251,24 @@ def main():
             daf.daf_plan(tuple(w.x.shape), w.group_size, bits).destroy()
         t_plan = (time.perf_counter() - t) * 1e6 / 10
         ok = bool((bits.cpu().numpy() == w.bits).all())
+        # the same without a host round trip: one plan kept across iterations, its widths replaced
+        # on the stream (daf_plan_update), the quantize launch right behind it
+        plan = daf.daf_plan(tuple(w.x.shape), w.group_size, bits)
+        words = torch.empty(plan.packed_words_bound, dtype=torch.int32, device=dev)
+        qmn, qsc = torch.empty(G, device=dev), torch.empty(G, device=dev)
+        t_update = timed(lambda: plan.update(bits), args.steps)
+
+        def controller():
+            daf.daf_group_minmax(stats_plan, x, mn, mx)
+            daf.daf_select_bits(mn, mx, classes, bits, ws)
+            plan.update(bits)
+
+        def iteration():
+            controller()
+            daf.daf_quantize_pack(plan, x, w.seed, words, qmn, qsc)
+        t_ctrl = timed(controller, args.steps)
+        t_iter = timed(iteration, args.steps)
+        plan.finish()
         stats_bytes = w.numel * w.x.element_size() + 8 * G
         print(json.dumps({"metric": "device-side width selection", "unit": "us", "n_gpus": 1, "data": "synthetic",
                           "config": {"workload": CONFIG_NAMES[args.config], "groups": G},
@@ -258,6 +276,10 @@ def main():
                           "group_minmax_GBps": round(stats_bytes / t_stats / 1e3, 1),
                           "group_minmax_frac_of_8TBps": round(stats_bytes / t_stats / 1e3 / HBM_PEAK_GBPS, 4),
                           "select_bits_us": round(t_select, 2), "plan_us_with_sync": round(t_plan, 1),
+                          "plan_update_us_no_sync": round(t_update, 2),
+                          "statistics_widths_plan_us_no_sync": round(t_ctrl, 2),
+                          "statistics_widths_plan_quantize_us_no_sync": round(t_iter, 2),
+                          "packed_words_after_finish": plan.packed_words,
                           "widths_match_generator": ok}))
         return
 

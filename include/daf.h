@@ -83,6 +83,32 @@ const char* daf_status_string(int status);
 int daf_plan(const int64_t* shape, int ndim, int32_t group_size,
              const uint8_t* bits, int64_t n_bits, void* stream, daf_plan_t** out_plan);
 
+/* daf_plan_update / daf_plan_finish -- new widths for an existing per-group-width plan without
+ * stopping the stream.  A controller that re-chooses the widths in every iteration (Sec. 3.2: the
+ * importance of an activation is re-estimated while training runs; Sec. 3.4.1: the widths follow)
+ * keeps one plan per saved tensor and runs
+ *     statistics -> widths (e.g. daf_group_minmax, daf_select_bits) -> daf_plan_update -> daf_quantize_pack
+ * on one stream, with no host round trip: daf_plan_update only enqueues the scan that rewrites
+ * the plan's copy of the widths and its offset array.
+ *
+ *   plan     a plan created by daf_plan with n_bits == G (per-group widths).
+ *   bits     DEVICE, G widths; read by the enqueued scan (keep it alive until the scan has run).
+ *            A width outside {1,2,4,8} is replaced by 8 in the plan's copy, so every later call
+ *            on the plan stays inside its buffers, and daf_plan_finish reports it.
+ *   stream   the scan is enqueued here; calls that use the plan must be ordered after it (same
+ *            stream, or an event).
+ *
+ * After daf_plan_update the exact packed size is not known to the host: daf_plan_packed_words
+ * returns daf_plan_packed_words_bound (the size with 8 bits for every group; allocate out_words
+ * for that) until daf_plan_finish, which synchronizes `stream` once, fetches the exact size and
+ * returns DAF_EINVAL if the last update contained an invalid width.  Calling it is optional.
+ *
+ * Errors: DAF_EINVAL (null pointer, a one-width plan), DAF_EUNSUPPORTED (the bound reaches 2^32
+ * words), DAF_EDEVICE. */
+int daf_plan_update(daf_plan_t* plan, const uint8_t* bits, void* stream);
+int daf_plan_finish(daf_plan_t* plan, void* stream);
+int64_t daf_plan_packed_words_bound(const daf_plan_t* plan);
+
 /* Plan queries (plain host reads, no HIP call). */
 int64_t daf_plan_num_elements(const daf_plan_t* plan);   /* N */
 int64_t daf_plan_num_groups(const daf_plan_t* plan);     /* G */

@@ -45,6 +45,12 @@ def load_library():
                       ("daf_plan_uniform_bits", i32)):
         getattr(L, name).argtypes = [vp]
         getattr(L, name).restype = res
+    L.daf_plan_update.argtypes = [vp, vp, vp]
+    L.daf_plan_update.restype = c.c_int
+    L.daf_plan_finish.argtypes = [vp, vp]
+    L.daf_plan_finish.restype = c.c_int
+    L.daf_plan_packed_words_bound.argtypes = [vp]
+    L.daf_plan_packed_words_bound.restype = i64
     L.daf_plan_copy_offsets.argtypes = [vp, vp]
     L.daf_plan_copy_offsets.restype = c.c_int
     L.daf_plan_quantize_route.argtypes = [vp, c.c_int]
@@ -168,6 +174,30 @@ class Plan:
         if not self._h:
             raise ValueError("plan already destroyed")
         return self._h
+
+    def update(self, bits: torch.Tensor, stream=None) -> None:
+        """daf_plan_update: new per-group widths (device uint8[G]) for this plan, enqueued on `stream`
+        without synchronizing; `packed_words` reads as the 8-bit bound until `finish()`."""
+        a = _Args(self)
+        a.tensor("bits", bits, torch.uint8, self.num_groups, exact=True)
+        a.on_device()
+        rc = load_library().daf_plan_update(self.handle, bits.data_ptr(), _stream_handle(stream))
+        if rc != 0:
+            raise DafError(rc, "daf_plan_update")
+        self._keep = bits
+        self.packed_words = int(load_library().daf_plan_packed_words(self.handle))
+
+    def finish(self, stream=None) -> None:
+        """daf_plan_finish: one synchronization; the exact packed size, and DafError if the last
+        update contained a width outside {1,2,4,8}."""
+        rc = load_library().daf_plan_finish(self.handle, _stream_handle(stream))
+        self.packed_words = int(load_library().daf_plan_packed_words(self.handle))
+        if rc != 0:
+            raise DafError(rc, "daf_plan_finish")
+
+    @property
+    def packed_words_bound(self) -> int:
+        return int(load_library().daf_plan_packed_words_bound(self.handle))
 
     ROUTES = ("tile", "units", "long", "two_pass", "group")
 

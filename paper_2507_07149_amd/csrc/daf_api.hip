@@ -109,6 +109,13 @@ int daf_plan(const int64_t* shape, int ndim, int32_t group_size, const uint8_t* 
   p->d_bits = nullptr;
   p->d_off = nullptr;
   p->d_big_scratch = nullptr;
+  p->d_scan = nullptr;
+  p->scan_blocks = 0;
+  p->pending = 0;
+  {
+    const int64_t full = n / group_size, tail = n - full * group_size;
+    p->bound_words = full * ((int64_t)group_size * 8 / 32) + (tail * 8 + 31) / 32;
+  }
   p->device = -1;
   p->output_cached = 0;
   int64_t big_bytes = 0;
@@ -136,7 +143,7 @@ int daf_plan(const int64_t* shape, int ndim, int32_t group_size, const uint8_t* 
   hipStream_t st = static_cast<hipStream_t>(stream);
   int rc = DAF_OK;
   const int64_t n_blocks = daf_plan_scan_blocks(G);
-  struct ScanResult { unsigned long long total; int bad; int pad; };
+  struct ScanResult { unsigned long long total; int bad; int pad; };   // (as in daf_plan_finish)
   // One device allocation holds the offsets, the scan's block sums (+ total and error flag) and
   // the plan's copy of the widths; the scan's result comes back through pinned host memory
   // (allocated once per thread): allocations, frees and a copy into pageable memory each cost
@@ -158,11 +165,11 @@ int daf_plan(const int64_t* shape, int ndim, int32_t group_size, const uint8_t* 
     unsigned long long* d_sums = reinterpret_cast<unsigned long long*>(base + off_bytes);
     p->d_bits = reinterpret_cast<uint8_t*>(base + off_bytes + sums_bytes);
     if (big && hipMalloc(&p->d_big_scratch, (size_t)big_bytes) != hipSuccess) { rc = DAF_ENOMEM; break; }
+    p->d_scan = d_sums;
+    p->scan_blocks = n_blocks;
     unsigned long long* d_total = d_sums + n_blocks;
     int* d_bad = reinterpret_cast<int*>(d_sums + n_blocks + 1);
-    if (hipMemcpyAsync(p->d_bits, bits, (size_t)G, hipMemcpyDeviceToDevice, st) != hipSuccess) { rc = DAF_EDEVICE; break; }
-    if (hipMemsetAsync(d_total, 0, 2 * sizeof(unsigned long long), st) != hipSuccess) { rc = DAF_EDEVICE; break; }
-    if (daf_launch_plan_scan(p->d_bits, G, n, group_size, p->d_off, d_sums, n_blocks, d_total, d_bad, st) != hipSuccess) { rc = DAF_EDEVICE; break; }
+    if (daf_launch_plan_scan(bits, p->d_bits, G, n, group_size, p->d_off, d_sums, n_blocks, d_total, d_bad, st) != hipSuccess) { rc = DAF_EDEVICE; break; }
     if (hipMemcpyAsync(h_pinned, d_total, sizeof(ScanResult), hipMemcpyDeviceToHost, st) != hipSuccess) { rc = DAF_EDEVICE; break; }
     if (hipStreamSynchronize(st) != hipSuccess) { rc = DAF_EDEVICE; break; }
     h = *h_pinned;
@@ -177,6 +184,39 @@ int daf_plan(const int64_t* shape, int ndim, int32_t group_size, const uint8_t* 
   *out_plan = p;
   return DAF_OK;
 }
+
+namespace {
+struct ScanResult { unsigned long long total; int bad; int pad; };
+}
+
+int daf_plan_update(daf_plan_t* plan, const uint8_t* bits, void* stream) {
+  if (plan == nullptr || bits == nullptr) return DAF_EINVAL;
+  if (plan->uniform_bits != 0 || plan->d_scan == nullptr) return DAF_EINVAL;   // per-group-width plans only
+  if (plan->bound_words >= (int64_t)1 << 32) return DAF_EUNSUPPORTED;          // offsets are 32-bit words
+  unsigned long long* d_total = plan->d_scan + plan->scan_blocks;
+  int* d_bad = reinterpret_cast<int*>(plan->d_scan + plan->scan_blocks + 1);
+  if (daf_launch_plan_scan(bits, plan->d_bits, plan->num_groups, plan->n, plan->group_size, plan->d_off, plan->d_scan,
+                           plan->scan_blocks, d_total, d_bad, static_cast<hipStream_t>(stream)) != hipSuccess)
+    return DAF_EDEVICE;
+  plan->pending = 1;
+  plan->total_words = plan->bound_words;
+  return DAF_OK;
+}
+
+int daf_plan_finish(daf_plan_t* plan, void* stream) {
+  if (plan == nullptr) return DAF_EINVAL;
+  if (!plan->pending) return DAF_OK;
+  ScanResult h = {0, 0, 0};
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (hipMemcpyAsync(&h, plan->d_scan + plan->scan_blocks, sizeof(ScanResult), hipMemcpyDeviceToHost, st) != hipSuccess)
+    return DAF_EDEVICE;
+  if (hipStreamSynchronize(st) != hipSuccess) return DAF_EDEVICE;
+  plan->pending = 0;
+  plan->total_words = (int64_t)h.total;      // with invalid widths counted as 8 bits: the layout the kernels used
+  return h.bad ? DAF_EINVAL : DAF_OK;
+}
+
+int64_t daf_plan_packed_words_bound(const daf_plan_t* plan) { return plan ? plan->bound_words : -1; }
 
 int64_t daf_plan_num_elements(const daf_plan_t* plan) { return plan ? plan->n : -1; }
 int64_t daf_plan_num_groups(const daf_plan_t* plan) { return plan ? plan->num_groups : -1; }

@@ -17,6 +17,11 @@ struct daf_plan_s {
   uint32_t* d_off;       // G word offsets (device), mixed plans only; the address that is freed
   void* d_big_scratch;   // groups longer than a 4096-element tile: one (min, max) pair per tile and
                          // per group, written by the quantize call's first pass (else null)
+  unsigned long long* d_scan;  // mixed plans: the scan's block sums, then the total and the invalid-width flag
+  int64_t scan_blocks;
+  int64_t bound_words;   // packed size if every group had 8 bits: what total_words reads while an
+                         // update's exact size has not been fetched (pending != 0)
+  int32_t pending;
 };
 
 // True when the plan's groups are longer than a tile and tile-aligned (or there is one group),
@@ -32,8 +37,10 @@ bool daf_quantize_reads_once(const daf_plan_t* plan);
 int daf_quantize_route(const daf_plan_t* plan, int dtype);
 
 // Launchers.  Each returns hipSuccess or the first HIP error.
-hipError_t daf_launch_plan_scan(const uint8_t* d_bits, int64_t num_groups, int64_t n, int32_t group_size,
-                                uint32_t* d_off, unsigned long long* d_block_sums, int64_t n_blocks,
+// src_bits: the caller's widths; plan_bits: the plan's copy, written by the scan with every width
+// outside {1,2,4,8} replaced by 8 (and *d_bad set).  No value needs clearing beforehand.
+hipError_t daf_launch_plan_scan(const uint8_t* src_bits, uint8_t* plan_bits, int64_t num_groups, int64_t n,
+                                int32_t group_size, uint32_t* d_off, unsigned long long* d_block_sums, int64_t n_blocks,
                                 unsigned long long* d_total, int* d_bad, hipStream_t stream);
 int64_t daf_plan_scan_blocks(int64_t num_groups);
 

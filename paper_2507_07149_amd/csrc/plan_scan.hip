@@ -49,24 +49,44 @@ __device__ __forceinline__ unsigned long long block_sum(unsigned long long v, un
   return lds[0] + lds[1] + lds[2] + lds[3];
 }
 
-__global__ __launch_bounds__(kThreads) void k_plan_block_sums(const uint8_t* __restrict__ bits,
+// Widths outside {1,2,4,8} are replaced by 8 in the plan's copy (so that every kernel that reads
+// the copy stays inside its buffers whatever the caller passed) and reported: bit 63 of the
+// block's sum carries "this block saw an invalid width".
+constexpr unsigned long long kBadBit = 1ull << 63;
+
+__global__ __launch_bounds__(kThreads) void k_plan_block_sums(const uint8_t* __restrict__ src_bits,
+                                                              uint8_t* __restrict__ plan_bits,
                                                               int64_t num_groups, int64_t n, int32_t gs,
-                                                              unsigned long long* __restrict__ block_sums,
-                                                              int* __restrict__ bad_flag) {
+                                                              unsigned long long* __restrict__ block_sums) {
   __shared__ unsigned long long lds[4];
   const int64_t base = (int64_t)blockIdx.x * kBlockGroups + (int64_t)threadIdx.x * kItems;
   unsigned long long s = 0;
   int bad = 0;
   uint32_t b[kItems];
-  load_widths(bits, base, num_groups, b);
+  load_widths(src_bits, base, num_groups, b);
 #pragma unroll
   for (int i = 0; i < kItems; ++i) {
     const int64_t g = base + i;
-    if (g < num_groups) s += group_words(b[i], g, num_groups, n, gs, &bad);
+    if (g < num_groups) {
+      int bad_here = 0;
+      (void)group_words(b[i], g, num_groups, n, gs, &bad_here);
+      if (bad_here) { b[i] = 8u; bad = 1; }
+      s += group_words(b[i], g, num_groups, n, gs, &bad_here);
+    }
   }
-  if (bad) atomicOr(bad_flag, 1);
-  const unsigned long long tot = block_sum(s, lds);
-  if (threadIdx.x == 0) block_sums[blockIdx.x] = tot;
+  if (base + kItems <= num_groups && (reinterpret_cast<uintptr_t>(plan_bits) & 7u) == 0u) {
+    uint2 v;
+    v.x = b[0] | (b[1] << 8) | (b[2] << 16) | (b[3] << 24);
+    v.y = b[4] | (b[5] << 8) | (b[6] << 16) | (b[7] << 24);
+    *reinterpret_cast<uint2*>(plan_bits + base) = v;
+  } else {
+#pragma unroll
+    for (int i = 0; i < kItems; ++i)
+      if (base + i < num_groups) plan_bits[base + i] = (uint8_t)b[i];
+  }
+  const int any_bad = __syncthreads_or(bad);
+  const unsigned long long tot = block_sum(s, lds);      // far below 2^63
+  if (threadIdx.x == 0) block_sums[blockIdx.x] = tot | (any_bad ? kBadBit : 0ull);
 }
 
 // One block turns block_sums[] into exclusive offsets in place and writes the grand total: a
@@ -74,13 +94,22 @@ __global__ __launch_bounds__(kThreads) void k_plan_block_sums(const uint8_t* __r
 // rewritten.
 __global__ __launch_bounds__(kThreads) void k_plan_scan_block_sums(unsigned long long* __restrict__ block_sums,
                                                                    int64_t n_blocks,
-                                                                   unsigned long long* __restrict__ total) {
+                                                                   unsigned long long* __restrict__ total,
+                                                                   int* __restrict__ bad_flag) {
   __shared__ unsigned long long lds[kThreads];
   const int64_t per = (n_blocks + kThreads - 1) / kThreads;
   const int64_t lo = (int64_t)threadIdx.x * per;
   const int64_t hi = lo + per < n_blocks ? lo + per : n_blocks;
   unsigned long long sum = 0;
-  for (int64_t i = lo; i < hi; ++i) sum += block_sums[i];
+  int bad = 0;
+  for (int64_t i = lo; i < hi; ++i) {
+    const unsigned long long v = block_sums[i];
+    bad |= (v & kBadBit) ? 1 : 0;
+    block_sums[i] = v & ~kBadBit;
+    sum += v & ~kBadBit;
+  }
+  const int any_bad = __syncthreads_or(bad);
+  if (threadIdx.x == 0) *bad_flag = any_bad;
   lds[threadIdx.x] = sum;
   __syncthreads();
   unsigned long long acc = sum;                          // Hillis-Steele inclusive scan over the 256 run sums
@@ -147,14 +176,14 @@ __global__ __launch_bounds__(kThreads) void k_plan_write_offsets(const uint8_t* 
 
 int64_t daf_plan_scan_blocks(int64_t num_groups) { return (num_groups + kBlockGroups - 1) / kBlockGroups; }
 
-hipError_t daf_launch_plan_scan(const uint8_t* d_bits, int64_t num_groups, int64_t n, int32_t group_size,
-                                uint32_t* d_off, unsigned long long* d_block_sums, int64_t n_blocks,
+hipError_t daf_launch_plan_scan(const uint8_t* src_bits, uint8_t* plan_bits, int64_t num_groups, int64_t n,
+                                int32_t group_size, uint32_t* d_off, unsigned long long* d_block_sums, int64_t n_blocks,
                                 unsigned long long* d_total, int* d_bad, hipStream_t stream) {
-  hipLaunchKernelGGL(k_plan_block_sums, dim3((unsigned)n_blocks), dim3(kThreads), 0, stream, d_bits,
-                     num_groups, n, group_size, d_block_sums, d_bad);
+  hipLaunchKernelGGL(k_plan_block_sums, dim3((unsigned)n_blocks), dim3(kThreads), 0, stream, src_bits, plan_bits,
+                     num_groups, n, group_size, d_block_sums);
   hipLaunchKernelGGL(k_plan_scan_block_sums, dim3(1), dim3(kThreads), 0, stream, d_block_sums, n_blocks,
-                     d_total);
-  hipLaunchKernelGGL(k_plan_write_offsets, dim3((unsigned)n_blocks), dim3(kThreads), 0, stream, d_bits,
+                     d_total, d_bad);
+  hipLaunchKernelGGL(k_plan_write_offsets, dim3((unsigned)n_blocks), dim3(kThreads), 0, stream, plan_bits,
                      num_groups, n, group_size, d_block_sums, d_off);
   return hipGetLastError();
 }
