@@ -374,15 +374,25 @@ def main():
                         plan = daf.daf_plan((n,), gs, b)
                     else:
                         plan = daf.daf_plan((n,), gs, bits)
-                    words = torch.empty(plan.packed_words, dtype=torch.int32, device=dev)
-                    mn, sc = torch.empty(G, device=dev), torch.empty(G, device=dev)
+                    # packed outputs rotate over more than the memory-side cache holds, so that the
+                    # dequantize direction reads them from HBM as a backward pass does
+                    packed = plan.packed_words * 4 + 8 * G
+                    n_out = max(2, min(40, -(-ROTATE_PACKED_BYTES // packed)))
+                    outs = [(torch.empty(plan.packed_words, dtype=torch.int32, device=dev), torch.empty(G, device=dev),
+                             torch.empty(G, device=dev)) for _ in range(n_out)]
                     it = [0]
 
                     def q():
-                        daf.daf_quantize_pack(plan, xs[it[0] & 1], 3, words, mn, sc)
+                        daf.daf_quantize_pack(plan, xs[it[0] & 1], 3, *outs[it[0] % n_out])
+                        it[0] += 1
+                    for _ in range(n_out):
+                        q()
+
+                    def d():
+                        daf.daf_unpack_dequantize(plan, *outs[it[0] % n_out], xh)
                         it[0] += 1
                     tq = timeit(q)
-                    td = timeit(lambda: daf.daf_unpack_dequantize(plan, words, mn, sc, xh))
+                    td = timeit(d)
                     alg = n * xs[0].element_size() + plan.packed_words * 4 + G * 8 + (G * 5 if bits == "mixed" else 0)
                     print(json.dumps({"dtype": str(dt)[6:], "group_size": gs, "bits": bits,
                                       "quantize_us": round(tq * 1e3, 1), "quantize_frac": round(alg / (tq * 1e-3) / 8e12, 3),
@@ -439,6 +449,7 @@ def main():
         for w in workloads:
             plans.append(daf.daf_plan(tuple(w.x.shape), w.group_size,
                                       int(w.bits[0]) if w.bits.size == 1 else torch.from_numpy(w.bits).to(dev)))
+        n_sets = max(n_sets, -(-ROTATE_PACKED_BYTES // sum(4 * p.packed_words + 8 * p.num_groups for p in plans)))
         for _ in range(n_sets):
             bufs = []
             for w, p in zip(workloads, plans):
@@ -496,6 +507,9 @@ def main():
         for w in workloads:
             plans.append(daf.daf_plan(tuple(w.x.shape), w.group_size,
                                       int(w.bits[0]) if w.bits.size == 1 else torch.from_numpy(w.bits).to(dev)))
+        # (the packed outputs rotate through more than the memory-side cache holds as well, so that
+        # the backward kernels read them from HBM)
+        n_sets = max(n_sets, -(-ROTATE_PACKED_BYTES // sum(4 * p.packed_words + 8 * p.num_groups for p in plans)))
         for _ in range(n_sets):
             bufs = []
             for w, p in zip(workloads, plans):
@@ -554,7 +568,7 @@ def main():
                           "backward_speedup": round(t_bsep / t_bfused, 3),
                           "roofline_backward": {"bound": "hbm", "achieved": round(ach_b, 1), "peak": HBM_PEAK_GBPS,
                                                 "unit": "GB/s", "frac": round(ach_b / HBM_PEAK_GBPS, 4),
-                                                "kernel": "k_unpack_dequantize_chunk<..., RELU_BWD>",
+                                                "kernel": "k_unpack_dequantize_tile<..., RELU_BWD>",
                                                 "algorithmic_bytes": alg},
                           "roofline": {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                                        "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None,
