@@ -289,7 +289,8 @@ int daf_minmax(const void* x, daf_dtype_t dtype, int64_t n, int method, void* wo
  *   classes, n_classes     HOST, 1..4 widths, each in {1,2,4,8}.
  *   out_bits               DEVICE, G bytes.
  *   workspace              DEVICE, daf_select_bits_workspace_bytes(G) bytes, 16-byte aligned;
- *                          contents need no preparation and are garbage afterwards.
+ *                          contents need no preparation and are garbage afterwards; calls that
+ *                          share a workspace must not overlap in time.
  *
  * Both calls only enqueue work on `stream`.
  * Errors: DAF_EINVAL (null/misaligned pointer, G < 1, bad class count or width),

@@ -89,6 +89,24 @@ def test_select_bits_ties(env, classes):
         assert np.array_equal(got.cpu().numpy(), orc.select_bits(gmin, gmax, classes)), (G, choices)
 
 
+def test_select_bits_workspace_reuse(env):
+    """One workspace, filled with ones beforehand, serves calls of different sizes one after the
+    other: every call leaves its counters and tickets as the next one needs them.  Many equal
+    ranges spread over many blocks put the thresholds in the middle of runs of ties."""
+    daf, orc = env
+    rng = np.random.default_rng(11)
+    G_max = 700_001
+    ws = daf.daf_select_bits_workspace(G_max)
+    ws.fill_(1)
+    for G in (G_max, 4099, 250_000, 1, G_max):
+        gmin = np.zeros(G, dtype=np.float32)
+        gmax = rng.choice([0.25, 0.5, 0.5, 0.5, 1.0, 1.0, 1.0, 1.0, 3.0], G).astype(np.float32)
+        out = torch.full((G,), 255, dtype=torch.uint8, device="cuda:0")
+        daf.daf_select_bits(torch.from_numpy(gmin).cuda(), torch.from_numpy(gmax).cuda(), (1, 2, 4, 8), out, ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), orc.select_bits(gmin, gmax, (1, 2, 4, 8))), G
+
+
 @pytest.mark.timeout(400)
 @pytest.mark.parametrize("cfg,scale,classes", [(3, 1 / 8, (1, 2, 4, 8)), (5, 1 / 16, (2, 4, 8)),
                                                (3, 1.0, (1, 2, 4, 8)), (5, 1.0, (2, 4, 8))])
