@@ -382,6 +382,36 @@ int daf_unpack_dequantize_batch(const daf_dequantize_item_t* items, int32_t n_it
 int daf_relu_quantize_pack(const daf_plan_t* plan, const void* z, daf_dtype_t dtype, uint64_t seed, void* out_y,
                            uint32_t* out_words, float* out_min, float* out_scale, void* stream);
 
+/* ---- producer fusion into a matrix product ---------------------------------------------------
+ *
+ * daf_linear_quantize_pack -- the forward pass of a linear layer, y = x W^T, with the
+ * quantization of y as the epilogue of the product's output tile: the kernel that produces the
+ * activation also reduces it (per-group min/max), quantizes and packs it (Sec. 3.2.3: fuse the
+ * reduction into the producing operator; Sec. 2.2 Eq. 1 and Sec. 3.3 for what is computed).
+ * y is written once (the next layer needs it) and never read back for the quantization.
+ *
+ *   y[m, n] = round_to_dtype( sum_k x[m, k] * W[n, k] ), the products accumulated in binary32 on
+ *   the matrix cores (the order of the additions is the kernel's own), rounded to nearest even;
+ *   out_words / out_min / out_scale are exactly what daf_quantize_pack(plan, y, ...) gives for
+ *   that y, bit for bit (same element map, same Philox bytes, same word layout).
+ *
+ *   plan     describes y: M * N elements, group size 32, 64 or 128 (a group is a run of
+ *            consecutive elements of a row of y), one width or per-group widths.
+ *   x        DEVICE, [M, K] row-major, dtype, 16-byte aligned.       M = elements / N.
+ *   weight   DEVICE, [N, K] row-major, dtype, 16-byte aligned.
+ *   N, K     N and M multiples of 256, K a multiple of 64.
+ *   dtype    DAF_F16 or DAF_BF16.
+ *   out_y    DEVICE, [M, N] row-major, dtype, 16-byte aligned.
+ *   others   as daf_quantize_pack.
+ *
+ * Asynchronous on `stream`.  Errors: DAF_EINVAL (null or misaligned pointer, N or K < 1, N does
+ * not divide the plan's element count), DAF_EUNSUPPORTED (binary32, another group size, shapes
+ * that are not whole tiles), DAF_EDEVICE.
+ */
+int daf_linear_quantize_pack(const daf_plan_t* plan, const void* x, const void* weight, int64_t N, int64_t K,
+                             daf_dtype_t dtype, uint64_t seed, void* out_y, uint32_t* out_words, float* out_min,
+                             float* out_scale, void* stream);
+
 /* ---- consumer fusion for an element-wise consumer -------------------------------------------
  *
  * daf_unpack_relu_backward -- backward of y = max(z, 0) when y is the saved, quantized

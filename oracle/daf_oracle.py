@@ -124,6 +124,21 @@ def grad_weight(xhat: np.ndarray, grad_y: np.ndarray, m: int, k: int, n: int, dt
     return gy.T @ xh
 
 
+def linear_forward(x: np.ndarray, w: np.ndarray, m: int, k: int, n: int, dtype: int) -> np.ndarray:
+    """Forward pass of a linear layer, y = x W^T: y[i, j] = sum_c x[i, c] * w[j, c], x [m, k] and
+    w [n, k] in the element format (float32, or uint16 bit patterns).  Products and sum are
+    evaluated in double precision (each product of two 16-bit-format values is exact in it), the
+    sum is rounded to binary32 and then to the element format with `narrow` (nearest even).
+    Returned flat, [m * n], in the element format.  Where the double-precision sum is itself a
+    binary32 value (small-integer inputs, as the bit-exact GPU tests use) the result is the
+    correctly rounded product; in general the two roundings can differ from a single one in the
+    last place, and from a binary32 accumulation by its rounding errors: tests on general
+    inputs compare with a tolerance."""
+    xd = widen(x, dtype).astype(np.float64).reshape(m, k)
+    wd = widen(w, dtype).astype(np.float64).reshape(n, k)
+    return narrow((xd @ wd.T).astype(np.float32).reshape(-1), dtype)
+
+
 def minmax(x: np.ndarray, dtype: int) -> np.ndarray:
     """Whole-tensor (min, max) as float32[2]."""
     x = np.ascontiguousarray(x.reshape(-1), dtype=_NP[dtype])

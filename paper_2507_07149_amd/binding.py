@@ -73,6 +73,8 @@ def load_library():
     L.daf_unpack_dequantize_batch.restype = c.c_int
     L.daf_relu_quantize_pack.argtypes = [vp, vp, c.c_int, u64, vp, vp, vp, vp, vp]
     L.daf_relu_quantize_pack.restype = c.c_int
+    L.daf_linear_quantize_pack.argtypes = [vp, vp, vp, i64, i64, c.c_int, u64, vp, vp, vp, vp, vp]
+    L.daf_linear_quantize_pack.restype = c.c_int
     L.daf_unpack_relu_backward.argtypes = [vp, vp, vp, vp, vp, vp, vp, c.c_int, vp]
     L.daf_unpack_relu_backward.restype = c.c_int
     L.daf_unpack_matmul_workspace_bytes.argtypes = [vp, i64, i64]
@@ -485,6 +487,30 @@ def daf_relu_quantize_pack(plan: Plan, z: torch.Tensor, seed: int, out_y: torch.
                                                _stream_handle(stream))
     if rc != 0:
         raise DafError(rc, "daf_relu_quantize_pack")
+
+
+def daf_linear_quantize_pack(plan: Plan, x: torch.Tensor, weight: torch.Tensor, seed: int, out_y: torch.Tensor,
+                             out_words: torch.Tensor, out_min: torch.Tensor, out_scale: torch.Tensor, stream=None) -> None:
+    """y = x @ weight.T with the quantize+pack of y in the product's epilogue; `plan` describes y."""
+    if x.dim() != 2 or weight.dim() != 2 or x.shape[1] != weight.shape[1]:
+        raise ValueError("x must be [M, K] and weight [N, K]")
+    M, K = x.shape
+    N = weight.shape[0]
+    if M * N != plan.num_elements:
+        raise ValueError(f"the plan describes {plan.num_elements} elements, y has {M * N}")
+    a = _Args(plan)
+    a.tensor("x", x, x.dtype, M * K, exact=True)
+    a.tensor("weight", weight, x.dtype, N * K, exact=True)
+    a.activation("out_y", out_y)
+    a.packed(out_words, out_min, out_scale, "out_")
+    if out_y.dtype != x.dtype:
+        raise ValueError("out_y must have the dtype of x")
+    a.on_device()
+    rc = load_library().daf_linear_quantize_pack(plan.handle, x.data_ptr(), weight.data_ptr(), N, K, _DTYPE_ID[x.dtype],
+                                                 seed, out_y.data_ptr(), out_words.data_ptr(), out_min.data_ptr(),
+                                                 out_scale.data_ptr(), _stream_handle(stream))
+    if rc != 0:
+        raise DafError(rc, "daf_linear_quantize_pack")
 
 
 def daf_quantize_pack_metrics(plan: Plan, x: torch.Tensor, seed: int, out_words: torch.Tensor, out_min: torch.Tensor,

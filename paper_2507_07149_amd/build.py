@@ -24,7 +24,8 @@ SOURCES = [("quantize_pack.hip", "quantize_pack_f32", ["-DDAF_DT=0"]),
            ("daf_api.hip", "daf_api", []), ("quantize_dispatch.hip", "quantize_dispatch", []),
            ("plan_scan.hip", "plan_scan", []), ("unpack_dequantize.hip", "unpack_dequantize", []),
            ("minmax.hip", "minmax", []), ("select_bits.hip", "select_bits", []),
-           ("unpack_matmul.hip", "unpack_matmul", []), ("page_store.cpp", "page_store", [])]
+           ("unpack_matmul.hip", "unpack_matmul", []), ("linear_quantize.hip", "linear_quantize", []),
+           ("page_store.cpp", "page_store", [])]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-ffp-contract=off", "-fno-strict-aliasing",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall",

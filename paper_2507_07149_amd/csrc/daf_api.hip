@@ -337,6 +337,22 @@ int daf_relu_quantize_pack(const daf_plan_t* plan, const void* z, daf_dtype_t dt
   return e == hipSuccess ? DAF_OK : DAF_EDEVICE;
 }
 
+int daf_linear_quantize_pack(const daf_plan_t* plan, const void* x, const void* weight, int64_t N, int64_t K,
+                             daf_dtype_t dtype, uint64_t seed, void* out_y, uint32_t* out_words, float* out_min,
+                             float* out_scale, void* stream) {
+  if (plan == nullptr || x == nullptr || weight == nullptr || out_y == nullptr || out_words == nullptr ||
+      out_min == nullptr || out_scale == nullptr || N < 1 || K < 1)
+    return DAF_EINVAL;
+  if (!aligned(x, 16) || !aligned(weight, 16) || !aligned(out_y, 16) || !aligned(out_words, 4) ||
+      !aligned(out_min, 4) || !aligned(out_scale, 4))
+    return DAF_EINVAL;
+  if (plan->n % N != 0) return DAF_EINVAL;
+  if (!daf_linear_quantize_supported(plan, N, K, (int)dtype)) return DAF_EUNSUPPORTED;
+  const hipError_t e = daf_launch_linear_quantize_pack(plan, x, weight, N, K, (int)dtype, seed, out_y, out_words,
+                                                       out_min, out_scale, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? DAF_OK : DAF_EDEVICE;
+}
+
 int daf_quantize_pack_metrics(const daf_plan_t* plan, const void* x, daf_dtype_t dtype, uint64_t seed,
                               uint32_t* out_words, float* out_min, float* out_scale, float* out_metrics,
                               void* stream) {

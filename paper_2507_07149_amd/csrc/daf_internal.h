@@ -80,5 +80,12 @@ hipError_t daf_launch_minmax(const void* x, int dtype, int64_t n, int method, vo
 hipError_t daf_launch_group_minmax(const daf_plan_t* plan, const void* x, int dtype, float* out_min, float* out_max,
                                    hipStream_t stream);
 int64_t daf_select_bits_workspace_size(int64_t num_groups);
+// y = x W^T with quantize+pack of y in the tile epilogue (linear_quantize.hip).  `supported` is a host
+// check of shapes, group size and dtype; the launcher assumes it holds.
+bool daf_linear_quantize_supported(const daf_plan_t* plan, int64_t N, int64_t K, int dtype);
+hipError_t daf_launch_linear_quantize_pack(const daf_plan_t* plan, const void* x, const void* w, int64_t N, int64_t K,
+                                           int dtype, uint64_t seed, void* y, uint32_t* words, float* mn, float* sc,
+                                           hipStream_t stream);
+
 hipError_t daf_launch_select_bits(const float* gmin, const float* gmax, int64_t num_groups, const uint8_t* classes,
                                   int n_classes, uint8_t* out_bits, void* workspace, hipStream_t stream);

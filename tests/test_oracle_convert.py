@@ -123,3 +123,39 @@ def test_grad_weight_against_explicit_loops_and_fractions():
     xh[3, 7] = 2.0; gy[3, 4] = 5.0
     got = orc.grad_weight(xh, gy, m, k, n, orc.F32)
     assert got[4, 7] == 10.0 and np.count_nonzero(got) == 1
+
+
+def test_linear_forward_against_exact_rationals_loops_and_a_single_entry():
+    # y = x W^T: exact rational arithmetic on a tiny bfloat16 case (the result must be the bfloat16
+    # value nearest to the exact sum whenever that sum is not within 2^-24 of a tie), plain Python
+    # loops on small-integer inputs (every sum exact, so the result is the rounded exact value), and
+    # one non-zero entry per operand to pin which index is which
+    from fractions import Fraction
+    import torch
+    rng = np.random.default_rng(5)
+    m, k, n = 4, 6, 3
+    x = torch.from_numpy(rng.standard_normal((m, k)).astype(np.float32)).to(torch.bfloat16)
+    w = torch.from_numpy(rng.standard_normal((n, k)).astype(np.float32)).to(torch.bfloat16)
+    bits = lambda t: t.contiguous().view(torch.int16).numpy().view(np.uint16)
+    got = orc.widen(orc.linear_forward(bits(x), bits(w), m, k, n, orc.BF16), orc.BF16).reshape(m, n)
+    for i in range(m):
+        for j in range(n):
+            exact = sum(Fraction(float(x[i, c])) * Fraction(float(w[j, c])) for c in range(k))
+            ulp = Fraction(2) ** (int(np.frexp(float(abs(exact)))[1]) - 8) if exact != 0 else Fraction(0)
+            assert abs(Fraction(float(got[i, j])) - exact) <= ulp / 2 + abs(exact) * Fraction(1, 2 ** 23)
+    m, k, n = 7, 40, 5
+    xi = rng.integers(-3, 4, (m, k)).astype(np.float32)
+    wi = rng.integers(-3, 4, (n, k)).astype(np.float32) / 4
+    for dtype, tdt in ((orc.F16, torch.float16), (orc.BF16, torch.bfloat16)):
+        got = orc.widen(orc.linear_forward(bits(torch.from_numpy(xi).to(tdt)), bits(torch.from_numpy(wi).to(tdt)),
+                                           m, k, n, dtype), dtype).reshape(m, n)
+        for i in range(m):
+            for j in range(n):
+                want = 0.0
+                for c in range(k):
+                    want += float(xi[i, c]) * float(wi[j, c])           # exact: multiples of 1/4 below 2^10
+                assert got[i, j] == float(torch.tensor(want, dtype=torch.float64).to(tdt))
+    xo = np.zeros((m, k), np.float32); wo = np.zeros((n, k), np.float32)
+    xo[2, 11] = 3.0; wo[4, 11] = 0.5
+    got = orc.linear_forward(xo, wo, m, k, n, orc.F32).reshape(m, n)
+    assert got[2, 4] == 1.5 and np.count_nonzero(got) == 1
