@@ -68,6 +68,11 @@ def parse():
                     help="time daf_unpack_matmul_grad_weight (unpack+dequantize inside the weight-gradient "
                          "product) against daf_unpack_dequantize followed by the library matrix product; "
                          "--config 5 (LLM MLP, bf16), 3 (ViT MLP, fp16) or 2 (conv activation as [N*H*W, C], fp32)")
+    ap.add_argument("--fused-linear", action="store_true",
+                    help="time daf_linear_quantize_pack (y = x W^T with the quantize+pack of y in the product's "
+                         "epilogue) against the library matrix product followed by daf_quantize_pack; "
+                         "--config 5 (LLM MLP up-projection, bf16, K = 4096) or 3 (ViT MLP down-projection, fp16, K = 3072: "
+                         "the configuration's shape read as [M, 768] with groups of 128)")
     ap.add_argument("--f32", action="store_true",
                     help="with --fused-matmul: the same shape with binary32 tensors (32x32x2 MFMA, 157.3 TFLOP/s peak)")
     ap.add_argument("--uniform-bits", type=int, default=None, choices=[1, 2, 4, 8],
@@ -171,6 +176,8 @@ def main():
     if args.page_store:
         bench_page_store(args, np)
         return
+    if args.config is None and args.fused_linear:
+        args.config = 5
     if args.config is None and (args.device_widths or args.fused_matmul or args.output_policy or args.fused_relu):
         args.config = 2
 
@@ -281,6 +288,100 @@ def main():
                           "statistics_widths_plan_quantize_us_no_sync": round(t_iter, 2),
                           "packed_words_after_finish": plan.packed_words,
                           "widths_match_generator": ok}))
+        return
+
+    if args.fused_linear:
+        (w,) = make_config(args.config)
+        # The configuration's tensor is the OUTPUT y [M, N] of the layer (its shape, group size and
+        # per-group widths); x and W are normal random operands scaled so that y has unit variance.
+        N = w.x.shape[-1]
+        M = w.numel // N
+        K = {5: 4096, 3: 3072}.get(args.config, 1024)
+        dt = w.x.dtype
+        g = torch.Generator(device=dev).manual_seed(w.seed)
+        x = torch.randn(M, K, device=dev, generator=g).to(dt)
+        W = (torch.randn(N, K, device=dev, generator=g) / K ** 0.5).to(dt)
+        bits = int(w.bits[0]) if w.bits.size == 1 else torch.from_numpy(w.bits).to(dev)
+        if args.uniform_bits:
+            bits = args.uniform_bits
+        plan = daf.daf_plan((M, N), w.group_size, bits)
+        G = plan.num_groups
+        n_sets = 3
+        outs = [(torch.empty(M, N, dtype=dt, device=dev), torch.empty(plan.packed_words, dtype=torch.int32, device=dev),
+                 torch.empty(G, device=dev), torch.empty(G, device=dev)) for _ in range(n_sets)]
+        it = [0]
+
+        def timed(fn, reps):
+            for _ in range(max(2, args.warmup // 4)):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps
+
+        def fused():
+            y, words, mn, sc = outs[it[0] % n_sets]
+            it[0] += 1
+            daf.daf_linear_quantize_pack(plan, x, W, w.seed, y, words, mn, sc)
+
+        def library_mm():
+            torch.mm(x, W.t(), out=outs[it[0] % n_sets][0])
+
+        def unfused():
+            y, words, mn, sc = outs[it[0] % n_sets]
+            it[0] += 1
+            torch.mm(x, W.t(), out=y)
+            daf.daf_quantize_pack(plan, y.view(-1), w.seed, words, mn, sc)
+
+        def product_only():
+            daf.daf_linear_quantize_pack(plan, x, W, w.seed, outs[it[0] % n_sets][0], None, None, None)
+
+        def own_mm_then_quantize():
+            y, words, mn, sc = outs[it[0] % n_sets]
+            it[0] += 1
+            daf.daf_linear_quantize_pack(plan, x, W, w.seed, y, None, None, None)
+            daf.daf_quantize_pack(plan, y.view(-1), w.seed, words, mn, sc)
+
+        reps = max(3, min(args.steps, 20))
+        t_fused = timed(fused, reps)
+        t_unfused = timed(unfused, reps)
+        t_mm = timed(library_mm, reps)
+        t_own = timed(product_only, reps)
+        t_own_unfused = timed(own_mm_then_quantize, reps)
+        # the two products differ in the order of their binary32 additions: compare y, and the packed
+        # output of the fused call with daf_quantize_pack applied to the y it wrote
+        fused()
+        yf, wf, mnf, scf = outs[(it[0] - 1) % n_sets]
+        y_lib = torch.mm(x, W.t())
+        rel = ((yf.float() - y_lib.float()).abs().max() / y_lib.float().abs().max()).item()
+        w2, mn2, sc2 = torch.empty_like(wf), torch.empty_like(mnf), torch.empty_like(scf)
+        daf.daf_quantize_pack(plan, yf.view(-1), w.seed, w2, mn2, sc2)
+        torch.cuda.synchronize()
+        same = bool(torch.equal(wf, w2) and torch.equal(mnf, mn2) and torch.equal(scf, sc2))
+        flops = 2.0 * M * N * K
+        ach = flops / (t_fused * 1e-3) / 1e12
+        print(json.dumps({"metric": "linear layer forward with quantize+pack in the epilogue, TFLOP/s", "value": round(ach, 1),
+                          "unit": "TFLOP/s", "n_gpus": 1, "steps": reps, "data": "synthetic", "higher_is_better": True,
+                          "dtype": {0: "f32", 1: "f16", 2: "bf16"}[w.dtype],
+                          "config": {"workload": CONFIG_NAMES[args.config] + f"_linear_forward_K{K}", "M": M, "N": N, "K": K,
+                                     "buffer_sets": n_sets},
+                          "fused_ms": round(t_fused, 4), "library_mm_then_quantize_ms": round(t_unfused, 4),
+                          "library_mm_alone_ms": round(t_mm, 4),
+                          "library_mm_TFLOPs": round(flops / (t_mm * 1e-3) / 1e12, 1),
+                          "same_kernel_without_quantization_ms": round(t_own, 4),
+                          "same_kernel_without_quantization_then_quantize_ms": round(t_own_unfused, 4),
+                          "epilogue_cost_ms": round(t_fused - t_own, 4),
+                          "separate_quantize_pass_ms": round(t_own_unfused - t_own, 4),
+                          "y_bytes_not_read_back": M * N * x.element_size(),
+                          "max_rel_diff_of_y_vs_library": round(rel, 5),
+                          "packed_output_equals_quantize_pack_of_own_y": same,
+                          "roofline": {"bound": "mfma", "achieved": round(ach, 1), "peak": 2500.0, "unit": "TFLOP/s",
+                                       "frac": round(ach / 2500.0, 4), "traffic": None,
+                                       "kernel": "k_linear_quantize_pack"}}))
         return
 
     if args.fused_matmul:

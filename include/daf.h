@@ -402,7 +402,8 @@ int daf_relu_quantize_pack(const daf_plan_t* plan, const void* z, daf_dtype_t dt
  *   N, K     N and M multiples of 256, K a multiple of 64.
  *   dtype    DAF_F16 or DAF_BF16.
  *   out_y    DEVICE, [M, N] row-major, dtype, 16-byte aligned.
- *   others   as daf_quantize_pack.
+ *   others   as daf_quantize_pack; or all three of out_words, out_min, out_scale null: the
+ *            product alone (the same kernel without the quantization in its epilogue).
  *
  * Asynchronous on `stream`.  Errors: DAF_EINVAL (null or misaligned pointer, N or K < 1, N does
  * not divide the plan's element count), DAF_EUNSUPPORTED (binary32, another group size, shapes
@@ -411,6 +412,11 @@ int daf_relu_quantize_pack(const daf_plan_t* plan, const void* z, daf_dtype_t dt
 int daf_linear_quantize_pack(const daf_plan_t* plan, const void* x, const void* weight, int64_t N, int64_t K,
                              daf_dtype_t dtype, uint64_t seed, void* out_y, uint32_t* out_words, float* out_min,
                              float* out_scale, void* stream);
+/* The 256 x 256 output tile (row and column, in tiles) that workgroup `id` of a
+ * daf_linear_quantize_pack launch over tiles_m x tiles_n tiles computes: the host copy of the map
+ * the kernel uses, so that tests without a GPU can check that it visits every tile once.
+ * Returns DAF_EINVAL for an id outside [0, tiles_m * tiles_n) or a null pointer. */
+int daf_linear_tile_of_workgroup(int32_t id, int32_t tiles_m, int32_t tiles_n, int32_t* tile_m, int32_t* tile_n);
 
 /* ---- consumer fusion for an element-wise consumer -------------------------------------------
  *

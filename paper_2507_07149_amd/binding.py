@@ -75,6 +75,8 @@ def load_library():
     L.daf_relu_quantize_pack.restype = c.c_int
     L.daf_linear_quantize_pack.argtypes = [vp, vp, vp, i64, i64, c.c_int, u64, vp, vp, vp, vp, vp]
     L.daf_linear_quantize_pack.restype = c.c_int
+    L.daf_linear_tile_of_workgroup.argtypes = [i32, i32, i32, vp, vp]
+    L.daf_linear_tile_of_workgroup.restype = c.c_int
     L.daf_unpack_relu_backward.argtypes = [vp, vp, vp, vp, vp, vp, vp, c.c_int, vp]
     L.daf_unpack_relu_backward.restype = c.c_int
     L.daf_unpack_matmul_workspace_bytes.argtypes = [vp, i64, i64]
@@ -491,7 +493,8 @@ def daf_relu_quantize_pack(plan: Plan, z: torch.Tensor, seed: int, out_y: torch.
 
 def daf_linear_quantize_pack(plan: Plan, x: torch.Tensor, weight: torch.Tensor, seed: int, out_y: torch.Tensor,
                              out_words: torch.Tensor, out_min: torch.Tensor, out_scale: torch.Tensor, stream=None) -> None:
-    """y = x @ weight.T with the quantize+pack of y in the product's epilogue; `plan` describes y."""
+    """y = x @ weight.T with the quantize+pack of y in the product's epilogue; `plan` describes y.
+    With out_words, out_min and out_scale all None: the product alone."""
     if x.dim() != 2 or weight.dim() != 2 or x.shape[1] != weight.shape[1]:
         raise ValueError("x must be [M, K] and weight [N, K]")
     M, K = x.shape
@@ -502,13 +505,16 @@ def daf_linear_quantize_pack(plan: Plan, x: torch.Tensor, weight: torch.Tensor, 
     a.tensor("x", x, x.dtype, M * K, exact=True)
     a.tensor("weight", weight, x.dtype, N * K, exact=True)
     a.activation("out_y", out_y)
-    a.packed(out_words, out_min, out_scale, "out_")
+    product_only = out_words is None and out_min is None and out_scale is None
+    if not product_only:
+        a.packed(out_words, out_min, out_scale, "out_")
     if out_y.dtype != x.dtype:
         raise ValueError("out_y must have the dtype of x")
     a.on_device()
+    ptr = (lambda t: None) if product_only else (lambda t: t.data_ptr())
     rc = load_library().daf_linear_quantize_pack(plan.handle, x.data_ptr(), weight.data_ptr(), N, K, _DTYPE_ID[x.dtype],
-                                                 seed, out_y.data_ptr(), out_words.data_ptr(), out_min.data_ptr(),
-                                                 out_scale.data_ptr(), _stream_handle(stream))
+                                                 seed, out_y.data_ptr(), ptr(out_words), ptr(out_min),
+                                                 ptr(out_scale), _stream_handle(stream))
     if rc != 0:
         raise DafError(rc, "daf_linear_quantize_pack")
 

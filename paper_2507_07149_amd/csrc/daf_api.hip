@@ -340,9 +340,10 @@ int daf_relu_quantize_pack(const daf_plan_t* plan, const void* z, daf_dtype_t dt
 int daf_linear_quantize_pack(const daf_plan_t* plan, const void* x, const void* weight, int64_t N, int64_t K,
                              daf_dtype_t dtype, uint64_t seed, void* out_y, uint32_t* out_words, float* out_min,
                              float* out_scale, void* stream) {
-  if (plan == nullptr || x == nullptr || weight == nullptr || out_y == nullptr || out_words == nullptr ||
-      out_min == nullptr || out_scale == nullptr || N < 1 || K < 1)
-    return DAF_EINVAL;
+  if (plan == nullptr || x == nullptr || weight == nullptr || out_y == nullptr || N < 1 || K < 1) return DAF_EINVAL;
+  // all three packed outputs, or none of them (the product alone)
+  const bool product_only = out_words == nullptr && out_min == nullptr && out_scale == nullptr;
+  if (!product_only && (out_words == nullptr || out_min == nullptr || out_scale == nullptr)) return DAF_EINVAL;
   if (!aligned(x, 16) || !aligned(weight, 16) || !aligned(out_y, 16) || !aligned(out_words, 4) ||
       !aligned(out_min, 4) || !aligned(out_scale, 4))
     return DAF_EINVAL;
@@ -351,6 +352,17 @@ int daf_linear_quantize_pack(const daf_plan_t* plan, const void* x, const void* 
   const hipError_t e = daf_launch_linear_quantize_pack(plan, x, weight, N, K, (int)dtype, seed, out_y, out_words,
                                                        out_min, out_scale, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? DAF_OK : DAF_EDEVICE;
+}
+
+int daf_linear_tile_of_workgroup(int32_t id, int32_t tiles_m, int32_t tiles_n, int32_t* tile_m, int32_t* tile_n) {
+  if (tile_m == nullptr || tile_n == nullptr || tiles_m < 1 || tiles_n < 1 || id < 0 ||
+      (int64_t)id >= (int64_t)tiles_m * tiles_n)
+    return DAF_EINVAL;
+  int m, n;
+  daf_linear_tile_map(id, tiles_m, tiles_n, &m, &n);
+  *tile_m = m;
+  *tile_n = n;
+  return DAF_OK;
 }
 
 int daf_quantize_pack_metrics(const daf_plan_t* plan, const void* x, daf_dtype_t dtype, uint64_t seed,

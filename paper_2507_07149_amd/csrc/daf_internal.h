@@ -83,6 +83,8 @@ int64_t daf_select_bits_workspace_size(int64_t num_groups);
 // y = x W^T with quantize+pack of y in the tile epilogue (linear_quantize.hip).  `supported` is a host
 // check of shapes, group size and dtype; the launcher assumes it holds.
 bool daf_linear_quantize_supported(const daf_plan_t* plan, int64_t N, int64_t K, int dtype);
+// The output tile (256 x 256) that workgroup `id` of the launch computes; a host copy of the kernel's own map.
+void daf_linear_tile_map(int id, int tiles_m, int tiles_n, int* tm, int* tn);
 hipError_t daf_launch_linear_quantize_pack(const daf_plan_t* plan, const void* x, const void* w, int64_t N, int64_t K,
                                            int dtype, uint64_t seed, void* y, uint32_t* words, float* mn, float* sc,
                                            hipStream_t stream);

@@ -65,6 +65,34 @@ __device__ __forceinline__ uint32_t other_half(uint32_t v) {
 __device__ __forceinline__ float both_halves_min(float v) { return vmin(v, u2f(other_half(f2u(v)))); }
 __device__ __forceinline__ float both_halves_max(float v) { return vmax(v, u2f(other_half(f2u(v)))); }
 
+// blockIdx -> tile.  Whole rounds of 256 workgroups: the s-th workgroup of die d in round r takes
+// position 256 r + 32 d + s; the rest keep their index.  Position -> tile: panels of kPanel tile
+// rows, column by column inside a panel (the last panel may be lower).  Both maps are bijections.
+struct TileIndex {
+  int m, n;
+};
+__host__ __device__ inline TileIndex tile_of_workgroup(int id, int tiles_m, int tiles_n) {
+  constexpr int kDies = 8, kPerDie = 32, kPanel = 4;
+  const int total = tiles_m * tiles_n;
+  int pos = id;
+  if (id < total / (kDies * kPerDie) * (kDies * kPerDie)) {
+    const int die = id % kDies, seq = id / kDies;
+    pos = (seq / kPerDie) * (kDies * kPerDie) + die * kPerDie + seq % kPerDie;
+  }
+  const int full = tiles_m / kPanel * kPanel;            // tile rows in whole panels
+  TileIndex t;
+  if (pos < full * tiles_n) {
+    const int panel = pos / (kPanel * tiles_n), in = pos % (kPanel * tiles_n);
+    t.m = panel * kPanel + in % kPanel;
+    t.n = in / kPanel;
+  } else {
+    const int rows = tiles_m - full, in = pos - full * tiles_n;
+    t.m = full + in % rows;
+    t.n = in / rows;
+  }
+  return t;
+}
+
 // A thread's share of one step's tiles: four 16-byte pieces of W and four of x (rows 64 apart).
 struct Staged {
   u32x4 w0, w1, w2, w3, x0, x1, x2, x3;
@@ -91,7 +119,7 @@ __device__ __forceinline__ void stash(const Staged& st, char* base) {
   *reinterpret_cast<u32x4*>(base + kOperandBytes + 192 * kPitch) = st.x3;
 }
 
-template <int DT, int GS_LOG2, bool MIXED>
+template <int DT, int GS_LOG2, bool MIXED, bool QUANT>
 __global__ __launch_bounds__(kLinThreads, 2) void k_linear_quantize_pack(
     const char* __restrict__ x, const char* __restrict__ w, int M, int N, int K, uint32_t seed_lo, uint32_t seed_hi,
     uint32_t uniform_b, const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, char* __restrict__ y,
@@ -101,12 +129,15 @@ __global__ __launch_bounds__(kLinThreads, 2) void k_linear_quantize_pack(
   const int wm = wave & 3, wn = wave >> 2;
   const int li = lane & 31, lg = lane >> 5;
 
-  // Workgroups are handed to the eight dies in turn: each die gets a run of consecutive tiles
-  // (n fastest), whose workgroups share rows of x and find W in the die's cache.
-  const int tiles_n = N / kBN, total = tiles_n * (M / kBM);
-  int tile = blockIdx.x;
-  if (total % 8 == 0) tile = (tile % 8) * (total / 8) + tile / 8;
-  const int64_t m0 = (int64_t)(tile / tiles_n) * kBM, n0 = (int64_t)(tile % tiles_n) * kBN;
+  // Workgroups are handed to the eight dies in turn, so the 32 workgroups that run together on one
+  // die (32 compute units, one cache) are every eighth one.  They get 32 consecutive positions
+  // of an order that walks panels of four tile rows column by column: a patch of about 4 x 8
+  // tiles, whose workgroups, moving through k in step, share four slabs of x and eight of W in
+  // that cache instead of one and thirty-two.
+  const int tiles_n = N / kBN, tiles_m = M / kBM;
+  const TileIndex ti = tile_of_workgroup((int)blockIdx.x, tiles_m, tiles_n);
+  const int tm = ti.m, tn = ti.n;
+  const int64_t m0 = (int64_t)tm * kBM, n0 = (int64_t)tn * kBN;
 
   // Staging: 2048 16-byte pieces per operand and step of 64 k, four per thread: rows crow + 64 j.
   const int crow = t >> 3, ccol = t & 7;
@@ -196,6 +227,7 @@ __global__ __launch_bounds__(kLinThreads, 2) void k_linear_quantize_pack(
       bmn[nb] = mn;
       bmx[nb] = mx;
     }
+    if (!QUANT) continue;                                        // the product alone
 #pragma unroll
     for (int gi = 0; gi < kGroups; ++gi) {
       float mn = bmn[gi * kBlocksPerGroup], mx = bmx[gi * kBlocksPerGroup];
@@ -261,12 +293,15 @@ hipError_t launch_gs(const daf_plan_t* p, const void* x, const void* w, int M, i
                      uint32_t* words, float* mn, float* sc, hipStream_t stream) {
   const unsigned grid = (unsigned)((M / kBM) * (N / kBN));
   const uint32_t lo = (uint32_t)seed, hi = (uint32_t)(seed >> 32);
-  if (p->uniform_bits)
-    hipLaunchKernelGGL((k_linear_quantize_pack<DT, GS_LOG2, false>), dim3(grid), dim3(kLinThreads), 0, stream,
+  if (words == nullptr)
+    hipLaunchKernelGGL((k_linear_quantize_pack<DT, GS_LOG2, false, false>), dim3(grid), dim3(kLinThreads), 0, stream,
+                       (const char*)x, (const char*)w, M, N, K, lo, hi, 8u, nullptr, nullptr, (char*)y, words, mn, sc);
+  else if (p->uniform_bits)
+    hipLaunchKernelGGL((k_linear_quantize_pack<DT, GS_LOG2, false, true>), dim3(grid), dim3(kLinThreads), 0, stream,
                        (const char*)x, (const char*)w, M, N, K, lo, hi, (uint32_t)p->uniform_bits, nullptr, nullptr,
                        (char*)y, words, mn, sc);
   else
-    hipLaunchKernelGGL((k_linear_quantize_pack<DT, GS_LOG2, true>), dim3(grid), dim3(kLinThreads), 0, stream,
+    hipLaunchKernelGGL((k_linear_quantize_pack<DT, GS_LOG2, true, true>), dim3(grid), dim3(kLinThreads), 0, stream,
                        (const char*)x, (const char*)w, M, N, K, lo, hi, 0u, p->d_bits, p->d_off, (char*)y, words, mn, sc);
   return hipGetLastError();
 }
@@ -282,6 +317,12 @@ hipError_t launch_dt(const daf_plan_t* p, const void* x, const void* w, int M, i
 }
 
 }  // namespace
+
+void daf_linear_tile_map(int id, int tiles_m, int tiles_n, int* tm, int* tn) {
+  const TileIndex t = tile_of_workgroup(id, tiles_m, tiles_n);
+  *tm = t.m;
+  *tn = t.n;
+}
 
 bool daf_linear_quantize_supported(const daf_plan_t* p, int64_t N, int64_t K, int dtype) {
   if (dtype != DAF_F16 && dtype != DAF_BF16) return false;

@@ -82,3 +82,29 @@ def test_list_calls_and_fused_calls_reject(plan):
         daf.daf_select_bits(mn, sc, (2, 4), torch.zeros(3, dtype=torch.uint8), torch.zeros(1 << 20, dtype=torch.uint8))
     with pytest.raises(ValueError, match="out_minmax"):
         daf.daf_minmax(x, daf.REDUCE_TWO_PASS, torch.zeros(1 << 16, dtype=torch.uint8), torch.zeros(1))
+
+
+def test_linear_tile_map_visits_every_tile_once():
+    """The workgroup -> output tile map of daf_linear_quantize_pack (a host copy of the kernel's)
+    is a bijection for tile grids with and without whole rounds of 256 workgroups, whole panels
+    of four tile rows, and for a single tile; and 32 consecutive workgroups of one die (every
+    eighth index) stay inside a compact patch when the grid is large."""
+    import ctypes
+    from paper_2507_07149_amd.binding import load_library
+    L = load_library()
+    for tiles_m, tiles_n in ((1, 1), (2, 3), (4, 8), (8, 32), (128, 43), (7, 5), (3, 100), (9, 64), (128, 3)):
+        seen = set()
+        tm, tn = ctypes.c_int32(), ctypes.c_int32()
+        for i in range(tiles_m * tiles_n):
+            assert L.daf_linear_tile_of_workgroup(i, tiles_m, tiles_n, ctypes.byref(tm), ctypes.byref(tn)) == 0
+            assert 0 <= tm.value < tiles_m and 0 <= tn.value < tiles_n
+            seen.add((tm.value, tn.value))
+        assert len(seen) == tiles_m * tiles_n, (tiles_m, tiles_n)
+        assert L.daf_linear_tile_of_workgroup(tiles_m * tiles_n, tiles_m, tiles_n, ctypes.byref(tm), ctypes.byref(tn)) != 0
+    tiles_m, tiles_n = 128, 43
+    rows, cols = set(), set()
+    tm, tn = ctypes.c_int32(), ctypes.c_int32()
+    for s in range(32):                                   # die 3, first round
+        L.daf_linear_tile_of_workgroup(8 * s + 3, tiles_m, tiles_n, ctypes.byref(tm), ctypes.byref(tn))
+        rows.add(tm.value); cols.add(tn.value)
+    assert len(rows) <= 4 and len(cols) <= 9
