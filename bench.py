@@ -275,6 +275,18 @@ def main():
             daf.daf_quantize_pack(plan, x, w.seed, words, qmn, qsc)
         t_ctrl = timed(controller, args.steps)
         t_iter = timed(iteration, args.steps)
+        # the same iteration captured once into a HIP graph and replayed (no call in it allocates,
+        # synchronizes or copies through the host)
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            side.wait_stream(torch.cuda.current_stream())
+            iteration()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            iteration()
+        t_graph = timed(graph.replay, args.steps)
+        bits_graph_ok = bool((bits.cpu().numpy() == w.bits).all())
         plan.finish()
         stats_bytes = w.numel * w.x.element_size() + 8 * G
         print(json.dumps({"metric": "device-side width selection", "unit": "us", "n_gpus": 1, "data": "synthetic",
@@ -284,6 +296,8 @@ def main():
                           "group_minmax_frac_of_8TBps": round(stats_bytes / t_stats / 1e3 / HBM_PEAK_GBPS, 4),
                           "select_bits_us": round(t_select, 2), "plan_us_with_sync": round(t_plan, 1),
                           "plan_update_us_no_sync": round(t_update, 2),
+                          "statistics_widths_plan_quantize_us_graph_replay": round(t_graph, 2),
+                          "widths_match_generator_after_graph_replay": bits_graph_ok,
                           "statistics_widths_plan_us_no_sync": round(t_ctrl, 2),
                           "statistics_widths_plan_quantize_us_no_sync": round(t_iter, 2),
                           "packed_words_after_finish": plan.packed_words,

@@ -102,3 +102,70 @@ def test_statistics_widths_plan_quantize_on_the_device():
     plan.finish()
     assert plan.packed_words == ow.size
     plan.destroy()
+
+
+def test_statistics_widths_plan_quantize_replayed_from_a_hip_graph():
+    """The sequence a training loop runs every iteration (per-group statistics -> widths -> new
+    offsets -> quantize) is captured once into a HIP graph and replayed on fresh activations:
+    none of the four calls allocates, copies through the host, clears memory with a memset node or
+    synchronizes.  Every replay is checked against the oracle, with the program's own eager work
+    and synchronizations between the replays."""
+    dtype, gs, classes = BF16, 64, (2, 4, 8)
+    n = 4096 * 37 + 64 * 5
+    G = (n + gs - 1) // gs
+    dev = "cuda:0"
+    gen = torch.Generator().manual_seed(123)
+    x_dev = torch.zeros(n, dtype=torch_dtype(dtype), device=dev)
+    stats_plan = daf.daf_plan((n,), gs, 8)
+    plan = daf.daf_plan((n,), gs, torch.full((G,), 8, dtype=torch.uint8, device=dev))
+    mn_s, mx_s = torch.empty(G, device=dev), torch.empty(G, device=dev)
+    bits = torch.empty(G, dtype=torch.uint8, device=dev)
+    ws = daf.daf_select_bits_workspace(G)
+    words = torch.zeros(plan.packed_words_bound, dtype=torch.int32, device=dev)
+    mn, sc = torch.empty(G, device=dev), torch.empty(G, device=dev)
+
+    def sequence():
+        daf.daf_group_minmax(stats_plan, x_dev, mn_s, mx_s)
+        daf.daf_select_bits(mn_s, mx_s, classes, bits, ws)
+        plan.update(bits)
+        daf.daf_quantize_pack(plan, x_dev, 9, words, mn, sc)
+
+    def check(x_cpu):
+        xb = to_numpy_bits(x_cpu)
+        gmin, gmax = orc.group_minmax(xb, dtype, gs)
+        want_bits = orc.select_bits(gmin, gmax, classes)
+        ow, omn, osc, _ = orc.quantize_pack(xb, dtype, gs, want_bits, 9)
+        assert np.array_equal(bits.cpu().numpy(), want_bits)
+        assert np.array_equal(words[: ow.size].cpu().numpy().view(np.uint32), ow)
+        assert np.array_equal(mn.cpu().numpy().view(np.uint32), omn.view(np.uint32))
+        assert np.array_equal(sc.cpu().numpy().view(np.uint32), osc.view(np.uint32))
+        return ow.size
+
+    side = torch.cuda.Stream()
+    x0 = (torch.randn(n, generator=gen) * 3).to(torch_dtype(dtype))
+    x_dev.copy_(x0)
+    with torch.cuda.stream(side):                       # once eagerly on the capture stream
+        side.wait_stream(torch.cuda.current_stream())
+        sequence()
+    torch.cuda.synchronize()
+    check(x0)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        sequence()
+    for trial in range(4):
+        xt = (torch.randn(n, generator=gen) * (0.5 + trial)).to(torch_dtype(dtype))
+        if trial == 2:
+            xt[: n // 2] = 1.5                          # many equal ranges: ties across blocks
+        x_dev.copy_(xt)
+        words.fill_(-1)
+        eager = torch.randn(1 << 16, device=dev).sum()  # unrelated eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        total = check(xt)
+        plan.finish()
+        assert plan.packed_words == total
+        assert torch.isfinite(eager)
+    del graph
+    plan.destroy()
+    stats_plan.destroy()
