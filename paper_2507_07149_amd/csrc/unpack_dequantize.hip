@@ -376,6 +376,149 @@ __global__ __launch_bounds__(kThreads) DAF_TILE_WAVES void k_unpack_dequantize_t
                                                   cached != 0);
 }
 
+// ---- tiles for group sizes that are not a power of two -------------------------------------
+// The same tile, but groups start anywhere in it (the first and the last may continue in the
+// neighbouring tiles): lane l holds the constants of group g_first + l, a chunk finds its group
+// by dividing its element index by the group size (a multiply-high with a rounded-up
+// reciprocal, exact for the few thousand values that occur), and with one width for all groups
+// the packed words do not depend on the group size at all: element e sits at bit e * B of the
+// stream.  With per-group widths the run starts at the word of the tile's first element inside
+// its group and may be one word longer than the tile's bits.
+template <int DT, int B>
+struct alignas(16) TileLdsAny {
+  static constexpr int kWords = TileLds<DT, B, kTileChunksPerLane>::kWords + (B ? 0 : kWave);
+  uint32_t stage[kWords + 4];
+  TileGroup group[kWave];
+};
+
+template <int DT, int B, bool RELU_BWD>
+__device__ __forceinline__ void unpack_dequantize_tile_any_body(
+    int64_t tile, int wave_in_block, const uint32_t* __restrict__ words, const float* __restrict__ mn,
+    const float* __restrict__ scale, const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, int32_t gs,
+    uint32_t gs_magic, int64_t G, u32x4* out, const u32x4* grad, bool cached) {
+  constexpr int U = kTileChunksPerLane;
+  constexpr int kEpl = ElemTraits<DT>::kPerLoad;
+  constexpr int kElems = kTileChunks * kEpl;
+  constexpr bool kMixed = (B == 0);
+  constexpr int kMaxWords = TileLdsAny<DT, B>::kWords;
+  constexpr int kWordLoads = kMaxWords / kWave;
+  static_assert(kMaxWords % kWave == 0, "every lane loads whole rounds of the run");
+  __shared__ TileLdsAny<DT, B> lds_all[kWavesPerBlock];
+  TileLdsAny<DT, B>& lds = lds_all[wave_in_block];
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t e_tile0 = tile * kElems;
+  const int64_t g_first = e_tile0 / gs;                          // once per wave
+  const uint32_t rem0 = (uint32_t)(e_tile0 - g_first * gs);      // the tile starts this far into its first group
+  const int groups = (int)((rem0 + (uint32_t)kElems - 1u) / (uint32_t)gs) + 1;   // at most 64: checked by the launcher
+
+  TileGroup mine;
+  mine.mn = 0.0f; mine.scale = 0.0f; mine.b = B ? (uint32_t)B : 1u; mine.woff = 0u;
+  uint32_t my_off = 0u;
+  if (lane < groups && g_first + lane < G) {
+    mine.mn = mn[g_first + lane];
+    mine.scale = scale[g_first + lane];
+    if (kMixed) {
+      mine.b = bits[g_first + lane];
+      my_off = off[g_first + lane];
+    }
+  }
+  u32x4 gq[RELU_BWD ? U : 1];
+  if (RELU_BWD) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) gq[u] = __builtin_nontemporal_load(&grad[tile * kTileChunks + u * kWave + lane]);
+  }
+  uint32_t wv[kWordLoads];
+  if (!kMixed) {
+    const uint32_t tile_base = (uint32_t)tile * (uint32_t)(kElems / 32 * B);
+#pragma unroll
+    for (int j = 0; j < kWordLoads; ++j) wv[j] = __builtin_nontemporal_load(&words[tile_base + j * kWave + lane]);
+  } else {
+    const uint32_t b_first = (uint32_t)__builtin_amdgcn_readlane((int)mine.b, 0);
+    const uint32_t off_first = (uint32_t)__builtin_amdgcn_readlane((int)my_off, 0);
+    const uint32_t first_word = off_first + ((rem0 * b_first) >> 5);
+    const uint32_t e_last = rem0 + (uint32_t)(kElems - kEpl);                     // the tile's last chunk
+    const int gl_last = __builtin_amdgcn_readfirstlane((int)__umulhi(e_last, gs_magic));
+    const uint32_t b_last = (uint32_t)__builtin_amdgcn_readlane((int)mine.b, gl_last);
+    const uint32_t off_last = (uint32_t)__builtin_amdgcn_readlane((int)my_off, gl_last);
+    const uint32_t bit_end = (e_last - (uint32_t)gl_last * (uint32_t)gs + (uint32_t)kEpl) * b_last;
+    const uint32_t tile_words = off_last + ((bit_end + 31u) >> 5) - first_word;   // <= kMaxWords
+    mine.woff = my_off - first_word;                    // modulo 2^32: the first group may start before the run
+#pragma unroll
+    for (int j = 0; j < kWordLoads; ++j) {
+      const uint32_t i = (uint32_t)(j * kWave + lane);
+      wv[j] = (i < tile_words) ? __builtin_nontemporal_load(&words[first_word + i]) : 0u;
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < kWordLoads; ++j) lds.stage[j * kWave + lane] = wv[j];
+  lds.group[lane] = mine;
+  wave_lds_sync();
+
+  TileGroup g[U];
+  uint32_t w0[U], w1[U], bit[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const uint32_t e0 = (uint32_t)(u * kWave + lane) * kEpl;     // first element of chunk u*64 + lane of the tile
+    const uint32_t gl = __umulhi(rem0 + e0, gs_magic);           // = (rem0 + e0) / gs
+    g[u] = lds.group[gl];
+    const uint32_t b = kMixed ? g[u].b : (uint32_t)B;
+    uint32_t widx;
+    if (kMixed) {
+      bit[u] = (rem0 + e0 - gl * (uint32_t)gs) * b;              // bit position inside the group
+      widx = g[u].woff + (bit[u] >> 5);
+    } else {
+      bit[u] = e0 * b;                                           // bit position inside the tile's run
+      widx = bit[u] >> 5;
+    }
+    w0[u] = lds.stage[widx];
+    w1[u] = (kEpl == 8 && b == 8u) ? lds.stage[widx + 1] : 0u;
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const uint32_t b = kMixed ? g[u].b : (uint32_t)B;
+    u32x4 o = dequantize_chunk<DT>(w0[u], w1[u], bit[u] & 31u, b, g[u].mn, g[u].scale);
+    if (RELU_BWD) {
+      o = (u32x4){keep_where_positive<DT>(o.x, gq[u].x), keep_where_positive<DT>(o.y, gq[u].y),
+                  keep_where_positive<DT>(o.z, gq[u].z), keep_where_positive<DT>(o.w, gq[u].w)};
+    }
+    store_chunk(out, tile * kTileChunks + (int64_t)(u * kWave + lane), o, cached);
+  }
+}
+
+template <int DT, int B, bool RELU_BWD>
+__global__ __launch_bounds__(kThreads) DAF_TILE_WAVES void k_unpack_dequantize_tile_any(
+    const uint32_t* __restrict__ words, const float* __restrict__ mn, const float* __restrict__ scale,
+    const uint8_t* __restrict__ bits, const uint32_t* __restrict__ off, int64_t n_tiles, int32_t gs, uint32_t gs_magic,
+    int64_t G, u32x4* out, const u32x4* grad, int cached, int64_t n_chunks, int64_t n) {
+  constexpr int kEpl = ElemTraits<DT>::kPerLoad;
+  const bool left = n_tiles * kTileChunks * kEpl < n;
+  if (left && blockIdx.x == 0) {                       // what the tiles leave over, the chunk kernel's way
+    if (n_tiles * kTileChunks < n_chunks)
+      unpack_dequantize_block<DT, B == 0, RELU_BWD>(0, words, mn, scale, bits, off, B, n_chunks, gs, -1, out, grad,
+                                                    cached != 0, n_tiles * kTileChunks);
+    if (n_chunks * kEpl < n && threadIdx.x < kWave)
+      unpack_dequantize_tail_body<DT, RELU_BWD>(words, mn, scale, bits, off, B, n_chunks * kEpl, n, gs, out, grad);
+    return;
+  }
+  const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t tile = (int64_t)(blockIdx.x - (left ? 1u : 0u)) * kWavesPerBlock + wave_in_block;
+  if (tile >= n_tiles) return;
+  unpack_dequantize_tile_any_body<DT, B, RELU_BWD>(tile, wave_in_block, words, mn, scale, bits, off, gs, gs_magic, G, out,
+                                                   grad, cached != 0);
+}
+
+// Whole tiles of a plan whose group size is not a power of two on that path (0: does not fit).
+template <int DT>
+int64_t any_tile_path_tiles(const daf_plan_t* p, uint32_t* magic) {
+  constexpr int kElems = kTileChunks * ElemTraits<DT>::kPerLoad;
+  const int64_t gs = p->group_size;
+  if ((gs & (gs - 1)) == 0 || gs < 64 || gs > 32768 || gs % 32 != 0) return 0;
+  if ((gs - 1 + kElems - 1) / gs + 1 > kWave) return 0;           // groups that touch one tile
+  if (p->num_groups >= ((int64_t)1 << 31)) return 0;
+  *magic = (uint32_t)((((uint64_t)1 << 32) + (uint64_t)gs - 1) / (uint64_t)gs);
+  return p->n / kElems;
+}
+
 // Several tensors in one launch: the tiles of all of them form one sequence.
 struct TileBatchEntry {
   const uint32_t* words;
@@ -482,6 +625,30 @@ hipError_t launch_dtype(const daf_plan_t* p, const uint32_t* words, const float*
   constexpr int kEpl = ElemTraits<DT>::kPerLoad;
   int32_t gs_log2 = 0;
   const int64_t n_tiles = tile_path_tiles<DT>(p, &gs_log2);
+  uint32_t magic = 0;
+  // (binary32 with 8 bits for every group stays with the chunk kernel: 0.76-0.78 of the memory rate
+  // there against 0.70-0.74 through tiles, measured on 2^27 elements with groups of 96 ... 11008)
+  const int64_t any_tiles =
+      (n_tiles == 0 && !(DT == kF32 && p->uniform_bits == 8)) ? any_tile_path_tiles<DT>(p, &magic) : 0;
+  if (any_tiles > 0) {
+    const bool left = any_tiles * kTileChunks * kEpl < p->n;
+    const unsigned blocks = (unsigned)((any_tiles + kWavesPerBlock - 1) / kWavesPerBlock) + (left ? 1u : 0u);
+#define DAF_LAUNCH(BITS)                                                                                          \
+  hipLaunchKernelGGL((k_unpack_dequantize_tile_any<DT, BITS, RELU_BWD>), dim3(blocks), dim3(kThreads), 0, stream,  \
+                     words, mn, scale, d_bits, p->d_off, any_tiles, p->group_size, magic, p->num_groups,          \
+                     static_cast<u32x4*>(out_x), static_cast<const u32x4*>(grad), p->output_cached, p->n / kEpl,  \
+                     p->n)
+    switch (p->uniform_bits) {
+      case 0: DAF_LAUNCH(0); break;
+      case 1: DAF_LAUNCH(1); break;
+      case 2: DAF_LAUNCH(2); break;
+      case 4: DAF_LAUNCH(4); break;
+      case 8: DAF_LAUNCH(8); break;
+      default: return hipErrorInvalidValue;
+    }
+#undef DAF_LAUNCH
+    return hipGetLastError();
+  }
   if (n_tiles == 0) return launch_chunks<DT, RELU_BWD>(p, words, mn, scale, d_bits, out_x, grad, 0, stream);
   // A small tensor with per-group widths takes tiles of twice the size: every wave pays two
   // round trips to memory (widths, then words) before it can store anything, and with few
