@@ -867,6 +867,14 @@ def measure(cfg, args, daf, torch, np, dev, headline):
                      else "k_quantize_pack_units" if gs0 <= 4096 else "k_quantize_pack_long")
     if batched:
         q_kernel_name += "_batch"
+    pow2 = gs0 > 0 and gs0 & (gs0 - 1) == 0
+    fp32_8bit = workloads[0].x.dtype == torch.float32 and workloads[0].bits.size == 1 and int(workloads[0].bits[0]) == 8
+    if pow2 and gs0 <= 4096:
+        d_kernel_name = "k_unpack_dequantize_tile" + ("_batch" if batched else "")
+    elif not pow2 and 64 <= gs0 <= 32768 and not batched and not fp32_8bit:
+        d_kernel_name = "k_unpack_dequantize_tile_any"
+    else:
+        d_kernel_name = "k_unpack_dequantize_chunk" + ("_batch" if batched else "")
 
     traffic = QUOTED_TRAFFIC.get(cfg) if args.group_size is None else None
 
@@ -891,7 +899,7 @@ def measure(cfg, args, daf, torch, np, dev, headline):
                               "output_GBps": round(in_bytes / dk_ms / 1e6, 1), "algorithmic_bytes": alg,
                               "launches": 1 if batched else len(workloads)},
         "roofline": dict(roof(qk_ms, 0, alg_q), kernel=q_kernel_name),
-        "roofline_unpack_dequantize": dict(roof(dk_ms, 1, alg), kernel="k_unpack_dequantize_chunk" + ("_batch" if batched else "")),
+        "roofline_unpack_dequantize": dict(roof(dk_ms, 1, alg), kernel=d_kernel_name),
     }
     if not headline:
         for ps in plans_by_set:
