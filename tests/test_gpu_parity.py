@@ -168,6 +168,73 @@ def test_per_tensor_quantization_of_the_resnet50_activation(H):
     assert res.mn.cpu().numpy()[0] == mm[0]
 
 
+@pytest.mark.timeout(900)
+def test_more_than_two_to_the_32_elements(H):
+    """Element indices beyond 32 bits: a bfloat16 tensor of 2^32 + 12,488 elements (8.6 GB), 2-bit
+    groups of 64, quantized and dequantized in one call each.  The oracle runs group by group on
+    sampled groups: the first and the last ones (the last group has 8 elements), the groups on
+    both sides of element 2^31 and of element 2^32 (where a 32-bit index would wrap: the Philox
+    counter, the tile index and the word offset all pass through there), and random ones.  The
+    activation is generated on the device in pieces; the host holds only the sampled groups, in
+    arrays whose untouched pages are never committed."""
+    import paper_2507_07149_amd as daf
+    from oracle import daf_oracle as orc
+    from daf_inputs import to_numpy_bits
+    dev = "cuda:0"
+    n, gs, b, seed = (1 << 32) + 3 * 4096 + 200, 64, 2, 0x1234_5678_9ABC
+    free, _ = torch.cuda.mem_get_info()
+    if free < 24 << 30:
+        pytest.skip("needs 24 GB of free device memory")
+    x = torch.empty(n, dtype=torch.bfloat16, device=dev)
+    gen = torch.Generator(device=dev).manual_seed(99)
+    piece = 1 << 28
+    for lo in range(0, n, piece):
+        hi = min(n, lo + piece)
+        x[lo:hi] = (torch.randn(hi - lo, device=dev, generator=gen) * 3).to(torch.bfloat16)
+    plan = daf.daf_plan((n,), gs, b)
+    G = plan.num_groups
+    off, total = orc.plan(n, gs, np.array([b], np.uint8))
+    assert G == (n + gs - 1) // gs == off.size and plan.packed_words == total
+    words = torch.empty(total, dtype=torch.int32, device=dev)
+    mn, sc = torch.empty(G, device=dev), torch.empty(G, device=dev)
+    daf.daf_quantize_pack(plan, x, seed, words, mn, sc)
+    xh = torch.empty_like(x)
+    daf.daf_unpack_dequantize(plan, words, mn, sc, xh)
+    torch.cuda.synchronize()
+
+    rng = np.random.default_rng(5)
+    near = lambda e: np.arange(e // gs - 40, e // gs + 40)
+    picks = np.unique(np.concatenate([np.arange(70), np.arange(G - 70, G), near(1 << 31), near(1 << 32),
+                                      near((1 << 32) + 4096), rng.integers(0, G, 300)]))
+    xb = np.zeros(n, dtype=np.uint16)                      # lazily committed: only the sampled groups are written
+    ow = np.zeros(total, dtype=np.uint32)
+    omn, osc = np.zeros(G, dtype=np.float32), np.zeros(G, dtype=np.float32)
+    oxh = np.zeros(n, dtype=np.uint16)
+    bits1 = np.array([b], np.uint8)
+    for g in picks:
+        g = int(g)
+        lo, hi = g * gs, min((g + 1) * gs, n)
+        xb[lo:hi] = to_numpy_bits(x[lo:hi].cpu())
+        orc.quantize_pack_range(xb, BF16, gs, bits1, off, seed, g, g + 1, ow, omn, osc)
+        nw = ((hi - lo) * b + 31) // 32
+        o0 = int(off[g])
+        assert mn[g].item() == omn[g] and sc[g].item() == osc[g], f"min/scale of group {g}"
+        assert np.array_equal(words[o0:o0 + nw].cpu().numpy().view(np.uint32), ow[o0:o0 + nw]), f"words of group {g}"
+        orc.unpack_dequantize_range(ow, omn, osc, bits1, off, n, gs, g, g + 1, oxh, BF16)
+        assert np.array_equal(to_numpy_bits(xh[lo:hi].cpu()), oxh[lo:hi]), f"dequantized values of group {g}"
+    # a property over every element, on the device in pieces: min is the group minimum, |x - xhat| <= scale + rounding
+    full = (n // gs) * gs
+    for lo in range(0, full, piece):
+        hi = min(full, lo + piece)
+        xs = x[lo:hi].float().reshape(-1, gs)
+        g0, g1 = lo // gs, hi // gs
+        assert torch.equal(mn[g0:g1], xs.amin(dim=1) + 0.0)
+        err = (xs - xh[lo:hi].float().reshape(-1, gs)).abs()
+        bound = sc[g0:g1, None] * (1 + 2.0 ** -20) + (xs.abs() + sc[g0:g1, None]) * 2.0 ** -8
+        assert bool((err <= bound).all())
+    plan.destroy()
+
+
 def test_seed_changes_codes_and_is_reproducible(H):
     w = _workload(F32, 4096 * 4, 256, 2, seed=1)
     a = H.u32(H.run_hip(w).words)
