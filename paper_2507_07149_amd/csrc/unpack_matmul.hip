@@ -155,6 +155,26 @@ __device__ __forceinline__ uint32_t narrow16_pair(float lo, float hi) {
 }
 
 // PARTIAL_N: N is not a multiple of 256 (see n_valid below); otherwise those checks are compiled out.
+// Position in the tile sequence -> tile.  The sequence walks panels of four tile rows (n) column
+// by column (k): 32 consecutive positions, which is what runs on one XCD at a time, are a patch of
+// about 4 x 8 tiles that shares four panels of grad_y and eight of the packed x in that XCD's
+// L2, where a row-major sequence shares one or two and thirty-two.  A bijection on
+// [0, tiles_n * tiles_k); the last panel may be lower.
+__device__ __forceinline__ void tile_of_position(uint32_t pos, uint32_t tiles_n, uint32_t tiles_k, uint32_t& tn,
+                                                 uint32_t& tk) {
+  constexpr uint32_t kPanel = 4;
+  const uint32_t full = tiles_n / kPanel * kPanel;
+  if (pos < full * tiles_k) {
+    const uint32_t panel = pos / (kPanel * tiles_k), in = pos - panel * (kPanel * tiles_k);
+    tn = panel * kPanel + in % kPanel;
+    tk = in / kPanel;
+  } else {
+    const uint32_t rows = tiles_n - full, in = pos - full * tiles_k;
+    tn = full + in % rows;
+    tk = in / rows;
+  }
+}
+
 template <int DT, bool MIXED, int BK, bool PARTIAL_N>
 __global__ __launch_bounds__((TileB<BK, (DT == kF32 ? 4 : 2)>::kThreads), (BK > 128 ? 1 : 2)) void k_unpack_matmul(
     const uint32_t* __restrict__ words, const float* __restrict__ mn, const float* __restrict__ scale,
@@ -177,8 +197,8 @@ __global__ __launch_bounds__((TileB<BK, (DT == kF32 ? 4 : 2)>::kThreads), (BK > 
   // tiles after those are each taken by `slices` work-groups, one slice of m each, which write
   // their partial sums to `partial` as compact tiles [slice][tile - whole][256][BK].
   // Consecutive block ids go to different XCDs (each with its own L2).  Give every XCD a
-  // contiguous range of the tile sequence, k running fastest: the tiles resident on an XCD at
-  // one time then share one or two panels of grad_y (the large operand) in its L2.
+  // contiguous range of the tile sequence (tile_of_position): the tiles resident on an XCD at
+  // one time are then a compact patch.
   const uint32_t n_tiles = (uint32_t)tiles_n * (uint32_t)tiles_k;
   const uint32_t bid = blockIdx.x;
   const bool sliced = bid >= whole;
@@ -192,7 +212,8 @@ __global__ __launch_bounds__((TileB<BK, (DT == kF32 ? 4 : 2)>::kThreads), (BK > 
     ti = xcd * base + (xcd < rem ? xcd : rem) + idx;
   }
   const uint32_t tile = sliced ? whole + ti : ti;
-  const uint32_t tn = tile / (uint32_t)tiles_k, tk = tile - tn * (uint32_t)tiles_k;
+  uint32_t tn, tk;
+  tile_of_position(tile, (uint32_t)tiles_n, (uint32_t)tiles_k, tn, tk);
   const int64_t n0 = (int64_t)tn * kBN, k0 = (int64_t)tk * BK;
   // The last tile of n may reach past the output (N is a multiple of 64, not of 256): the waves
   // whose 64 columns lie outside take part in the loads and the tile construction but run no
@@ -493,14 +514,16 @@ __global__ __launch_bounds__((TileB<BK, (DT == kF32 ? 4 : 2)>::kThreads), (BK > 
 // the additions of one output are spread over several work-groups.
 template <bool TO_OUT>
 __global__ __launch_bounds__(256) void k_sum_slices(float4* __restrict__ partial, uint32_t whole, uint32_t count,
-                                                    int32_t slices, int32_t n, int32_t stride, int32_t tiles_k,
+                                                    int32_t slices, int32_t n, int32_t stride, uint32_t tiles_n,
+                                                    int32_t tiles_k,
                                                     int32_t bk4, int64_t N, int64_t K, float* __restrict__ out) {
   const uint32_t strips = (uint32_t)(kBN * bk4) / 256u;           // work-groups per tile
   const uint32_t ti = blockIdx.x / strips;
   const uint32_t e = (blockIdx.x - ti * strips) * 256u + threadIdx.x;   // float4 index inside the tile
   const int64_t tile4 = (int64_t)kBN * bk4;
   const uint32_t tile = whole + ti;
-  const uint32_t tn = tile / (uint32_t)tiles_k, tk = tile - tn * (uint32_t)tiles_k;
+  uint32_t tn, tk;
+  tile_of_position(tile, tiles_n, (uint32_t)tiles_k, tn, tk);
   const uint32_t row = e / (uint32_t)bk4, col4 = e - row * (uint32_t)bk4;
   if ((int64_t)tn * kBN + row >= N) return;          // rows of the last tile of n past the output
   const int32_t first = (int32_t)blockIdx.y * n * stride;
@@ -647,11 +670,11 @@ hipError_t daf_launch_unpack_matmul(const daf_plan_t* p, const uint32_t* words, 
   if (slices > 16) {                                  // first level: every 16 slices into the first of them
     const unsigned chunks = (unsigned)((slices + 15) / 16);
     hipLaunchKernelGGL(k_sum_slices<false>, dim3(rblocks, chunks), dim3(256), 0, stream, part, whole, (uint32_t)rest,
-                       slices, 16, 1, tiles_k, bk4, N, K, out);
+                       slices, 16, 1, (uint32_t)tiles_n, tiles_k, bk4, N, K, out);
     n = (int32_t)chunks;
     stride = 16;
   }
   hipLaunchKernelGGL(k_sum_slices<true>, dim3(rblocks, 1), dim3(256), 0, stream, part, whole, (uint32_t)rest, slices, n,
-                     stride, tiles_k, bk4, N, K, out);
+                     stride, (uint32_t)tiles_n, tiles_k, bk4, N, K, out);
   return hipGetLastError();
 }
