@@ -273,7 +273,7 @@ __device__ __forceinline__ void unpack_dequantize_tile_body(
   const int64_t g0 = tile * groups;
   const uint32_t group_words32 = (1u << gs_log2) >> 5;           // words per group and bit of width
 
-  // round 1: the groups' constants (lane g takes group g), the gradient chunks, and with one
+  // first trip to memory: the groups' constants (lane g takes group g), the gradient chunks, and with one
   // width for all groups the words as well
   TileGroup mine;
   mine.mn = 0.0f; mine.scale = 0.0f; mine.b = B ? (uint32_t)B : 1u;
@@ -303,7 +303,7 @@ __device__ __forceinline__ void unpack_dequantize_tile_body(
     const uint32_t incl = wave_inclusive_sum(gw);
     tile_words = (uint32_t)__builtin_amdgcn_readlane((int)incl, kWave - 1);
     mine.woff = incl - gw;
-    // round 2: the run's words (its length is known only now)
+    // second trip: the run's words (its length is known only now)
 #pragma unroll
     for (int j = 0; j < kWordLoads; ++j) {
       const uint32_t i = (uint32_t)(j * kWave + lane);                 // < kWordLoads * 64 = kMaxWords: inside stage
