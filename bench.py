@@ -275,6 +275,22 @@ def main():
             daf.daf_quantize_pack(plan, x, w.seed, words, qmn, qsc)
         t_ctrl = timed(controller, args.steps)
         t_iter = timed(iteration, args.steps)
+
+        # ... and with no pass over the activation for the widths at all: the next iteration's widths
+        # come from the scales (and widths) the quantize call of this iteration left behind
+        bits_next = bits.clone()
+
+        def lagged_controller():
+            daf.daf_select_bits_from_scale(qsc, bits_next, classes, bits_next, ws)
+            plan.update(bits_next)
+
+        def lagged_iteration():
+            daf.daf_quantize_pack(plan, x, w.seed, words, qmn, qsc)
+            lagged_controller()
+        iteration()
+        t_lag_ctrl = timed(lagged_controller, args.steps)
+        t_lag_iter = timed(lagged_iteration, args.steps)
+        plan.update(bits)
         # the same iteration captured once into a HIP graph and replayed (no call in it allocates,
         # synchronizes or copies through the host)
         side = torch.cuda.Stream()
@@ -296,6 +312,8 @@ def main():
                           "group_minmax_frac_of_8TBps": round(stats_bytes / t_stats / 1e3 / HBM_PEAK_GBPS, 4),
                           "select_bits_us": round(t_select, 2), "plan_us_with_sync": round(t_plan, 1),
                           "plan_update_us_no_sync": round(t_update, 2),
+                          "widths_from_previous_scales_plan_us_no_sync": round(t_lag_ctrl, 2),
+                          "quantize_then_widths_from_its_scales_plan_us_no_sync": round(t_lag_iter, 2),
                           "statistics_widths_plan_quantize_us_graph_replay": round(t_graph, 2),
                           "widths_match_generator_after_graph_replay": bits_graph_ok,
                           "statistics_widths_plan_us_no_sync": round(t_ctrl, 2),

@@ -473,6 +473,24 @@ int daf_select_bits(const float* group_min, const float* group_max, int64_t num_
                     const uint8_t* classes, int32_t n_classes, uint8_t* out_bits,
                     void* workspace, void* stream);
 
+/* daf_select_bits_from_scale -- the same rule with the ranges taken from what an earlier
+ * daf_quantize_pack of the tensor left behind, so that choosing the next iteration's widths
+ * needs no pass over the activation at all (Sec. 3.4.1: the controller works from statistics
+ * gathered while training runs): range_g = scale_g * (2^b_g - 1) in binary32, Eq. 1 (left)
+ * turned round, where scale_g is that call's out_scale and b_g the width it used.  Groups are
+ * ranked by (range_g, g) and classified exactly as in daf_select_bits.
+ *
+ *   group_scale    DEVICE, G floats (out_scale of the earlier call).
+ *   group_bits     DEVICE, G widths the earlier call used, or NULL: then uniform_bits (1, 2, 4, 8)
+ *                  is the width of every group.  May be out_bits itself (the widths are read
+ *                  before any is written).
+ *   others         as daf_select_bits.
+ * Errors: as daf_select_bits; DAF_EINVAL also for group_bits NULL with an invalid uniform_bits.
+ */
+int daf_select_bits_from_scale(const float* group_scale, const uint8_t* group_bits, int32_t uniform_bits,
+                               int64_t num_groups, const uint8_t* classes, int32_t n_classes,
+                               uint8_t* out_bits, void* workspace, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -89,6 +89,8 @@ def load_library():
     L.daf_select_bits_workspace_bytes.restype = i64
     L.daf_select_bits.argtypes = [vp, vp, i64, vp, i32, vp, vp, vp]
     L.daf_select_bits.restype = c.c_int
+    L.daf_select_bits_from_scale.argtypes = [vp, vp, i32, i64, vp, i32, vp, vp, vp]
+    L.daf_select_bits_from_scale.restype = c.c_int
     L.daf_minmax_workspace_bytes.restype = i64
     L.daf_minmax_workspace_init.argtypes = [vp, vp]
     L.daf_minmax_workspace_init.restype = c.c_int
@@ -473,6 +475,29 @@ def daf_select_bits(group_min: torch.Tensor, group_max: torch.Tensor, classes: S
                                         workspace.data_ptr(), _stream_handle(stream))
     if rc != 0:
         raise DafError(rc, "daf_select_bits")
+
+
+def daf_select_bits_from_scale(group_scale: torch.Tensor, prev_bits, classes: Sequence[int], out_bits: torch.Tensor,
+                               workspace: torch.Tensor, stream=None) -> None:
+    """Widths for the next iteration from the scales (and widths: a uint8 tensor, or one int for
+    all groups) of an earlier daf_quantize_pack: no pass over the activation."""
+    G = group_scale.numel() if isinstance(group_scale, torch.Tensor) else 0
+    a = _Args()
+    a.tensor("group_scale", group_scale, torch.float32, max(G, 1))
+    uniform = 0
+    if isinstance(prev_bits, torch.Tensor):
+        a.tensor("prev_bits", prev_bits, torch.uint8, G, exact=True)
+    else:
+        uniform = int(prev_bits)
+    a.tensor("out_bits", out_bits, torch.uint8, G)
+    a.tensor("workspace", workspace, torch.uint8, int(load_library().daf_select_bits_workspace_bytes(G)))
+    a.on_device()
+    cl = (ctypes.c_uint8 * len(classes))(*[int(c) for c in classes])
+    rc = load_library().daf_select_bits_from_scale(
+        group_scale.data_ptr(), prev_bits.data_ptr() if isinstance(prev_bits, torch.Tensor) else None, uniform, G,
+        ctypes.cast(cl, ctypes.c_void_p), len(classes), out_bits.data_ptr(), workspace.data_ptr(), _stream_handle(stream))
+    if rc != 0:
+        raise DafError(rc, "daf_select_bits_from_scale")
 
 
 def daf_relu_quantize_pack(plan: Plan, z: torch.Tensor, seed: int, out_y: torch.Tensor, out_words: torch.Tensor,

@@ -486,8 +486,24 @@ int daf_select_bits(const float* group_min, const float* group_max, int64_t num_
   for (int c = 0; c < n_classes; ++c)
     if (!valid_width(classes[c])) return DAF_EINVAL;
   if (num_groups >= (int64_t)1 << 32) return DAF_EUNSUPPORTED;
-  const hipError_t e = daf_launch_select_bits(group_min, group_max, num_groups, classes, n_classes, out_bits,
+  const hipError_t e = daf_launch_select_bits(group_min, group_max, nullptr, 0, num_groups, classes, n_classes, out_bits,
                                               workspace, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? DAF_OK : DAF_EDEVICE;
+}
+
+int daf_select_bits_from_scale(const float* group_scale, const uint8_t* group_bits, int32_t uniform_bits,
+                               int64_t num_groups, const uint8_t* classes, int32_t n_classes, uint8_t* out_bits,
+                               void* workspace, void* stream) {
+  if (group_scale == nullptr || classes == nullptr || out_bits == nullptr || workspace == nullptr || num_groups < 1 ||
+      n_classes < 1 || n_classes > 4)
+    return DAF_EINVAL;
+  if (group_bits == nullptr && !valid_width((uint8_t)uniform_bits)) return DAF_EINVAL;
+  if (!aligned(group_scale, 4) || !aligned(workspace, 16)) return DAF_EINVAL;
+  for (int c = 0; c < n_classes; ++c)
+    if (!valid_width(classes[c])) return DAF_EINVAL;
+  if (num_groups >= (int64_t)1 << 32) return DAF_EUNSUPPORTED;
+  const hipError_t e = daf_launch_select_bits(group_scale, nullptr, group_bits, uniform_bits, num_groups, classes,
+                                              n_classes, out_bits, workspace, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? DAF_OK : DAF_EDEVICE;
 }
 

@@ -89,5 +89,8 @@ hipError_t daf_launch_linear_quantize_pack(const daf_plan_t* plan, const void* x
                                            int dtype, uint64_t seed, void* y, uint32_t* words, float* mn, float* sc,
                                            hipStream_t stream);
 
-hipError_t daf_launch_select_bits(const float* gmin, const float* gmax, int64_t num_groups, const uint8_t* classes,
-                                  int n_classes, uint8_t* out_bits, void* workspace, hipStream_t stream);
+// gmax != null: ranges are gmax - gmin.  gmax == null: gmin holds scales, ranges are scale * (2^b - 1)
+// with b = prev_bits[g] (device) or prev_uniform when prev_bits is null.
+hipError_t daf_launch_select_bits(const float* gmin, const float* gmax, const uint8_t* prev_bits, int32_t prev_uniform,
+                                  int64_t num_groups, const uint8_t* classes, int n_classes, uint8_t* out_bits,
+                                  void* workspace, hipStream_t stream);

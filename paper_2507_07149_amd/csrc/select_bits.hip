@@ -235,7 +235,12 @@ __device__ __forceinline__ void finish_pass(SelectState* __restrict__ st, int n_
 // keys[g] = bit pattern of the group's range, and in the same pass the histogram of the keys'
 // leading digit (every key counts for every threshold, so one histogram serves all).  A wave
 // takes 512 consecutive groups per trip, eight loads of each array in flight per lane.
+// FROM_SCALE = false: the range is gmax - gmin.  FROM_SCALE = true: gmin holds the groups' scales of
+// an earlier quantize call and prev_bits (or, when null, prev_uniform) the widths it ran with; the
+// range is scale * (2^b - 1), Eq. 1 (left) turned round, in binary32.
+template <bool FROM_SCALE>
 __global__ __launch_bounds__(kThreads) void k_select_keys(const float* __restrict__ gmin, const float* __restrict__ gmax,
+                                                          const uint8_t* __restrict__ prev_bits, uint32_t prev_uniform,
                                                           int64_t G, uint32_t* __restrict__ keys,
                                                           SelectState* __restrict__ st, int n_thresholds) {
   constexpr int kLoads = 8;
@@ -253,12 +258,17 @@ __global__ __launch_bounds__(kThreads) void k_select_keys(const float* __restric
     for (int j = 0; j < kLoads; ++j) {
       const int64_t g = g0 + j * kWave + lane;
       lo[j] = (g < G) ? gmin[g] : 0.0f;
-      hi[j] = (g < G) ? gmax[g] : 0.0f;
+      if (FROM_SCALE) {
+        const uint32_t b = (prev_bits != nullptr && g < G) ? (uint32_t)prev_bits[g] : prev_uniform;
+        hi[j] = (float)((1u << (b & 15u)) - 1u);          // L of the earlier call
+      } else {
+        hi[j] = (g < G) ? gmax[g] : 0.0f;
+      }
     }
 #pragma unroll
     for (int j = 0; j < kLoads; ++j) {
       const int64_t g = g0 + j * kWave + lane;
-      const uint32_t key = f2u(hi[j] - lo[j]);
+      const uint32_t key = f2u(FROM_SCALE ? lo[j] * hi[j] : hi[j] - lo[j]);
       if (g < G) keys[g] = key;
       hist_add<kLdsCopies0>(lh, key >> pass_shift(0), g < G);
     }
@@ -501,8 +511,9 @@ int64_t daf_select_bits_workspace_size(int64_t G) {
   return (int64_t)sizeof(SelectState) + ((G + 3) / 4) * 16 + kMaxThresholds * ((n_blocks + 3) / 4) * 16 + 64;
 }
 
-hipError_t daf_launch_select_bits(const float* gmin, const float* gmax, int64_t G, const uint8_t* classes,
-                                  int n_classes, uint8_t* out_bits, void* workspace, hipStream_t stream) {
+hipError_t daf_launch_select_bits(const float* gmin, const float* gmax, const uint8_t* prev_bits, int32_t prev_uniform,
+                                  int64_t G, const uint8_t* classes, int n_classes, uint8_t* out_bits, void* workspace,
+                                  hipStream_t stream) {
   SelectState* st = static_cast<SelectState*>(workspace);
   uint32_t* keys = reinterpret_cast<uint32_t*>(static_cast<char*>(workspace) + ((sizeof(SelectState) + 15) / 16) * 16);
   uint32_t* block_ties = keys + ((G + 3) / 4) * 4;
@@ -527,8 +538,12 @@ hipError_t daf_launch_select_bits(const float* gmin, const float* gmax, int64_t 
   const unsigned cap = kMaxWorkgroups;
   hipLaunchKernelGGL(k_select_init, dim3(24), dim3(kThreads), 0, stream, st, R[0], R[1], R[2]);
   const unsigned kblocks = (unsigned)((G + 8 * kThreads - 1) / (8 * kThreads));                  // eight keys per thread and trip
-  hipLaunchKernelGGL(k_select_keys, dim3(kblocks < cap ? kblocks : cap), dim3(kThreads), 0, stream, gmin, gmax, G,
-                     keys, st, n_thr);
+  if (gmax != nullptr)
+    hipLaunchKernelGGL(k_select_keys<false>, dim3(kblocks < cap ? kblocks : cap), dim3(kThreads), 0, stream, gmin, gmax,
+                       nullptr, 0u, G, keys, st, n_thr);
+  else
+    hipLaunchKernelGGL(k_select_keys<true>, dim3(kblocks < cap ? kblocks : cap), dim3(kThreads), 0, stream, gmin, nullptr,
+                       prev_bits, (uint32_t)prev_uniform, G, keys, st, n_thr);
   if (n_thr > 0) {
     const unsigned cblocks = (unsigned)((((G + 3) >> 2) + 4 * kThreads - 1) / (4 * kThreads));   // sixteen keys per thread and trip
     const unsigned hblocks = cblocks < cap ? cblocks : cap;

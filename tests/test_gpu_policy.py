@@ -107,6 +107,39 @@ def test_select_bits_workspace_reuse(env):
         assert np.array_equal(out.cpu().numpy(), orc.select_bits(gmin, gmax, (1, 2, 4, 8))), G
 
 
+@pytest.mark.parametrize("prev", ["per-group", 4])
+def test_select_bits_from_the_scales_of_an_earlier_quantize_call(env, prev):
+    """The next iteration's widths from what daf_quantize_pack left behind: range = scale * (2^b - 1)
+    in binary32, then the rule of daf_select_bits; in place over the previous widths as well."""
+    daf, orc = env
+    n, gs, classes = 4096 * 53 + 64 * 7, 64, (1, 2, 4, 8)
+    G = n // gs
+    g = torch.Generator().manual_seed(77)
+    x = (torch.randn(n, generator=g) * torch.rand(n, generator=g) * 4).to(torch.bfloat16)
+    x[: n // 3] = x[: n // 3].round()                      # coarse values: many equal ranges
+    rng = np.random.default_rng(8)
+    b_prev = rng.choice([1, 2, 4, 8], G).astype(np.uint8) if prev == "per-group" else np.array([prev], np.uint8)
+    plan = daf.daf_plan((n,), gs, torch.from_numpy(b_prev).cuda() if b_prev.size > 1 else int(b_prev[0]))
+    words = torch.empty(plan.packed_words, dtype=torch.int32, device="cuda:0")
+    mn, sc = torch.empty(G, device="cuda:0"), torch.empty(G, device="cuda:0")
+    daf.daf_quantize_pack(plan, x.cuda(), 5, words, mn, sc)
+    out = torch.full((G,), 255, dtype=torch.uint8, device="cuda:0")
+    ws = daf.daf_select_bits_workspace(G)
+    prev_arg = torch.from_numpy(b_prev).cuda() if b_prev.size > 1 else int(b_prev[0])
+    daf.daf_select_bits_from_scale(sc, prev_arg, classes, out, ws)
+    torch.cuda.synchronize()
+    from daf_inputs import to_numpy_bits
+    _, _, osc, _ = orc.quantize_pack(to_numpy_bits(x), orc.BF16, gs, b_prev, 5)
+    L = ((1 << np.broadcast_to(b_prev, (G,)).astype(np.int64)) - 1).astype(np.float32)
+    want = orc.select_bits(np.zeros(G, np.float32), (osc * L).astype(np.float32), classes)
+    assert np.array_equal(out.cpu().numpy(), want)
+    if b_prev.size > 1:                                    # in place: the new widths replace the old ones
+        daf.daf_select_bits_from_scale(sc, prev_arg, classes, prev_arg, ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(prev_arg.cpu().numpy(), want)
+    plan.destroy()
+
+
 @pytest.mark.timeout(400)
 @pytest.mark.parametrize("cfg,scale,classes", [(3, 1 / 8, (1, 2, 4, 8)), (5, 1 / 16, (2, 4, 8)),
                                                (3, 1.0, (1, 2, 4, 8)), (5, 1.0, (2, 4, 8))])
